@@ -1,0 +1,141 @@
+/*
+ * ff.h - C ABI of libff: Evoformer gated axial attention with pair bias on one MI355X.
+ *
+ * The library implements, as hand-written HIP kernels for gfx950, the attention module
+ * that FastFold (arXiv 2203.00854) optimises inside AlphaFold's Evoformer:
+ *
+ *   LayerNorm -> Q/K/V/gate projections -> softmax(Q K^T / sqrt(d) + mask + pair bias) V
+ *             -> sigmoid gate -> output projection
+ *
+ * in the four axial variants the Evoformer uses (Section 2.3: row-wise and column-wise
+ * attention on the MSA representation, the attention bias that carries the pair
+ * representation into the MSA row attention, and the "similar blocks" of the pair stack,
+ * i.e. AlphaFold's triangle attention around the starting and the ending node), plus the
+ * fixed row chunking used for long-sequence inference (Sections 3.2, 5.3, 6.2).
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller.  The library never
+ *     allocates or frees device memory and keeps no state between calls (scratch memory
+ *     is the caller's workspace argument).
+ *   - Tensors are dense, row-major, in the dtype named by the call (float32 or bfloat16).
+ *     Weights have the tensor dtype.  The mask is always float32.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = the default
+ *     stream) and the call returns without synchronising.
+ *   - Errors are returned as ff_status; nothing is launched and nothing is written to the
+ *     output when an argument is rejected.  ff_last_error() gives a message (thread-local).
+ *   - Arithmetic: LayerNorm statistics, softmax maxima and sums and all accumulations are
+ *     float32.  In FF_BF16 the projected q/k/v/gate, the softmax weights and the gated
+ *     context are rounded to bfloat16 as matrix-core operands; FF_F32 uses no bfloat16.
+ */
+#ifndef FF_H
+#define FF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { FF_OK = 0, FF_EINVAL = 1, FF_EUNSUPPORTED = 2, FF_EWORKSPACE = 3, FF_EHIP = 4 } ff_status;
+typedef enum { FF_F32 = 0, FF_BF16 = 1 } ff_dtype;
+
+/* Which axis is attended and where the bias comes from (Section 2.3).
+ * x is [n_a, n_b, c].  "batch row" = an index of the axis that is NOT attended; batch rows
+ * are independent given the bias (Section 4.2).
+ *   FF_MSA_ROW    x = MSA rep [N_seq, N_res, c_m]; batch row s, attention over residues j;
+ *                 bias[h,i,j] = LayerNorm_z(z[i,j,:]) . w_b[h,:] from the pair rep z.
+ *   FF_MSA_COL    x = MSA rep; batch row i (a residue), attention over sequences t; no bias.
+ *   FF_TRI_START  x = pair rep [N_res, N_res, c_z]; batch row i, attention over k;
+ *                 logits of (i; j,k) get bias[h,j,k] = LayerNorm(x[j,k,:]) . w_b[h,:].
+ *   FF_TRI_END    x = pair rep; batch row j, attention over k; logits of (j; i,k) get
+ *                 bias[h,k,i].  Equals FF_TRI_START applied to x with its first two axes
+ *                 swapped, swapped back. */
+typedef enum { FF_MSA_ROW = 0, FF_MSA_COL = 1, FF_TRI_START = 2, FF_TRI_END = 3 } ff_mode;
+
+/* Shape of one attention module. */
+typedef struct {
+    int32_t mode;      /* ff_mode */
+    int32_t dtype;     /* ff_dtype of x, z, out and all weights */
+    int32_t n_a, n_b;  /* x and out are [n_a, n_b, c]; triangle modes need n_a == n_b */
+    int32_t c;         /* channels of x (c_m for the MSA rep, c_z for the pair rep) */
+    int32_t c_z;       /* channels of z; FF_MSA_ROW only, otherwise ignored */
+    int32_t heads;     /* H */
+    int32_t head_dim;  /* d; channel h*d + e of a projection belongs to head h */
+    float   ln_eps;    /* LayerNorm epsilon, inside the square root */
+} ff_attn_desc;
+
+/* Weights, all [out, in] row-major (y = x W^T + b), dtype = desc.dtype.
+ * q, k, v and the bias projection have no additive bias; the gate and the output
+ * projection have one (Section 5.2 names the gate as bias + sigmoid + product). */
+typedef struct {
+    const void *ln_g, *ln_b;    /* [c]      LayerNorm of x                                  */
+    const void *lnz_g, *lnz_b;  /* [c_z]    LayerNorm of z, FF_MSA_ROW only, else NULL      */
+    const void *w_q, *w_k, *w_v;/* [H*d, c]                                                 */
+    const void *w_b;            /* [H, c_z] FF_MSA_ROW; [H, c] triangle modes; NULL for COL */
+    const void *w_g, *b_g;      /* [H*d, c], [H*d]  gate                                    */
+    const void *w_o, *b_o;      /* [c, H*d], [c]    output projection                       */
+} ff_attn_weights;
+
+/* LayerNorm over the last axis of x [rows, c] (Section 5.2: the batch-reduction kernel the
+ * paper rewrites for small hidden sizes):
+ *   y = (x - mean) / sqrt(var + eps) * gamma + beta, biased variance, float32 statistics.
+ * x, gamma, beta, y: device pointers of dtype dt; y may alias x.  rows >= 0, 1 <= c <= 8192.
+ * Returns FF_EINVAL for bad sizes/NULL pointers, FF_EHIP if the launch fails. */
+ff_status ff_layernorm(const void* x, const void* gamma, const void* beta, void* y,
+                       int64_t rows, int32_t c, float eps, int32_t dt, void* hip_stream);
+
+/* Bytes of device workspace ff_gated_attention (chunk_rows = 0) or ff_attention_chunked
+ * (chunk_rows >= 1) needs for this shape: projected q,k,v,gate and the gated context of one
+ * chunk of batch rows plus the bias tensor [H, L, L] in float32 - never the score tensor
+ * (Section 3.2 gives its size, N_r^3 * N_head * 2 bytes, as the memory bottleneck).
+ * Returns 0 if desc is invalid (ff_last_error says why). */
+size_t ff_attention_workspace_bytes(const ff_attn_desc* desc, int32_t chunk_rows);
+
+/* One gated attention module (Sections 2.1, 2.3, 5.2), all batch rows at once.
+ *   x    [n_a, n_b, c]   input representation
+ *   z    [n_b, n_b, c_z] pair representation, FF_MSA_ROW only; must be NULL otherwise
+ *   mask [n_a, n_b] float32 of 0/1 or NULL (= all ones).  mask[a,b] == 0 removes token
+ *        (a,b) as a KEY: it gets softmax weight exactly 0 (the paper's "mask" addend of
+ *        the softmax input, read as minus infinity).  Queries are never masked.  A query
+ *        whose keys are all masked gets zero context, so its output is b_o.
+ *   out  [n_a, n_b, c]   out = (gate * context) W_o^T + b_o; no residual add, no dropout.
+ *        Must not overlap x, z or ws.
+ *   ws, ws_bytes  device scratch of at least ff_attention_workspace_bytes(desc, 0) bytes,
+ *        256-byte aligned.
+ * Returns FF_EINVAL (bad enum, non-positive size, NULL required pointer, non-NULL z outside
+ * FF_MSA_ROW, n_a != n_b in a triangle mode, misaligned ws), FF_EWORKSPACE (ws too small),
+ * FF_EUNSUPPORTED (a size beyond the kernels' limits: head_dim > 128, c or c_z > 8192),
+ * FF_EHIP (launch failure). */
+ff_status ff_gated_attention(const ff_attn_desc* desc, const ff_attn_weights* w,
+                             const void* x, const void* z, const float* mask,
+                             void* out, void* ws, size_t ws_bytes, void* hip_stream);
+
+/* The same module evaluated chunk_rows batch rows at a time (Section 5.3: a chunk
+ * partitions a dimension that takes no part in the computation, Y_i = F(X_i^chunk,
+ * X^nonchunk); Section 6.2/6.4 use chunk size 64).  The chunked input is the batch-row
+ * axis of x (and of out and mask); the non-chunked input is the bias tensor, computed once
+ * before the loop.  The last chunk may be short; chunk_rows larger than the number of
+ * batch rows is one chunk.  The result is bit-identical to ff_gated_attention.
+ * ws must hold ff_attention_workspace_bytes(desc, chunk_rows) bytes.
+ * Extra error: chunk_rows < 1 -> FF_EINVAL. */
+ff_status ff_attention_chunked(const ff_attn_desc* desc, const ff_attn_weights* w,
+                               const void* x, const void* z, const float* mask,
+                               void* out, void* ws, size_t ws_bytes, void* hip_stream,
+                               int32_t chunk_rows);
+
+/* Name of the kernel family that ff_gated_attention would pick for this shape:
+ * "mfma_bf16" (matrix-core path) or "generic" (float32 vector path).  For tests and the
+ * benchmark report.  NULL if desc is invalid. */
+const char* ff_attention_path(const ff_attn_desc* desc);
+
+/* Message for the last non-OK status returned on this thread ("" if none). */
+const char* ff_last_error(void);
+
+/* Library version string. */
+const char* ff_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FF_H */

@@ -1,0 +1,11 @@
+"""MI355X-native Evoformer gated axial attention with pair bias (FastFold, arXiv 2203.00854).
+
+The product is the HIP library libff.so behind the C ABI of include/ff.h; this package
+holds its sources (csrc/), the build step, a thin ctypes binding and the seeded input
+generators used by the tests and the benchmark.
+"""
+from .binding import (  # noqa: F401
+    FF_BF16, FF_F32, FF_MSA_COL, FF_MSA_ROW, FF_TRI_END, FF_TRI_START, AttnDesc, AttnWeights, FFError,
+    ff_attention_chunked, ff_attention_path, ff_attention_workspace_bytes, ff_gated_attention, ff_layernorm,
+    last_error, lib, make_desc, make_weights, to_device,
+)

@@ -1,0 +1,193 @@
+"""Thin Python binding of libff's C ABI (include/ff.h): argument marshalling only.
+
+Every step of the attention path runs inside the HIP library; torch is used here for
+device memory and the current stream.  If the library has not been built the import of
+any entry point fails loudly - there is no CPU or PyTorch fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional
+
+PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(PKG, "libff.so")
+
+FF_OK, FF_EINVAL, FF_EUNSUPPORTED, FF_EWORKSPACE, FF_EHIP = range(5)
+FF_F32, FF_BF16 = 0, 1
+FF_MSA_ROW, FF_MSA_COL, FF_TRI_START, FF_TRI_END = range(4)
+
+WEIGHT_FIELDS = ("ln_g", "ln_b", "lnz_g", "lnz_b", "w_q", "w_k", "w_v", "w_b", "w_g", "b_g", "w_o", "b_o")
+
+
+class AttnDesc(C.Structure):
+    _fields_ = [("mode", C.c_int32), ("dtype", C.c_int32), ("n_a", C.c_int32), ("n_b", C.c_int32),
+                ("c", C.c_int32), ("c_z", C.c_int32), ("heads", C.c_int32), ("head_dim", C.c_int32),
+                ("ln_eps", C.c_float)]
+
+
+class AttnWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in WEIGHT_FIELDS]
+
+
+class FFError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"libff status {status}: {message}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2203_00854_amd.build` "
+                "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        L.ff_layernorm.restype = C.c_int
+        L.ff_layernorm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
+                                   C.c_float, C.c_int32, C.c_void_p]
+        L.ff_attention_workspace_bytes.restype = C.c_size_t
+        L.ff_attention_workspace_bytes.argtypes = [C.POINTER(AttnDesc), C.c_int32]
+        common = [C.POINTER(AttnDesc), C.POINTER(AttnWeights), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                  C.c_void_p, C.c_size_t, C.c_void_p]
+        L.ff_gated_attention.restype = C.c_int
+        L.ff_gated_attention.argtypes = common
+        L.ff_attention_chunked.restype = C.c_int
+        L.ff_attention_chunked.argtypes = common + [C.c_int32]
+        L.ff_attention_path.restype = C.c_char_p
+        L.ff_attention_path.argtypes = [C.POINTER(AttnDesc)]
+        L.ff_last_error.restype = C.c_char_p
+        L.ff_version.restype = C.c_char_p
+        _lib = L
+    return _lib
+
+
+def last_error() -> str:
+    return lib().ff_last_error().decode()
+
+
+def _check(status: int):
+    if status != FF_OK:
+        raise FFError(status, last_error())
+
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.float32:
+        return FF_F32
+    if t.dtype == torch.bfloat16:
+        return FF_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def make_desc(mode: int, x, heads: int, head_dim: int, c_z: int = 0, ln_eps: float = 1e-5) -> AttnDesc:
+    n_a, n_b, c = x.shape
+    return AttnDesc(mode, _dtype_code(x), n_a, n_b, c, c_z, heads, head_dim, ln_eps)
+
+
+def make_weights(w: Dict[str, "object"]) -> AttnWeights:
+    s = AttnWeights()
+    for n in WEIGHT_FIELDS:
+        t = w.get(n)
+        if t is not None:
+            assert t.is_contiguous() and t.is_cuda
+        setattr(s, n, _ptr(t))
+    return s
+
+
+def ff_layernorm(x, gamma, beta, eps: float = 1e-5, out=None):
+    """LayerNorm over the last axis of a contiguous CUDA tensor."""
+    import torch
+    assert x.is_cuda and x.is_contiguous()
+    if out is None:
+        out = torch.empty_like(x)
+    c = x.shape[-1]
+    rows = x.numel() // c if c else 0
+    _check(lib().ff_layernorm(_ptr(x), _ptr(gamma), _ptr(beta), _ptr(out), rows, c, eps, _dtype_code(x), _stream()))
+    return out
+
+
+def ff_attention_workspace_bytes(desc: AttnDesc, chunk_rows: int = 0) -> int:
+    n = lib().ff_attention_workspace_bytes(C.byref(desc), chunk_rows)
+    if n == 0:
+        raise FFError(FF_EINVAL, last_error())
+    return n
+
+
+def ff_attention_path(desc: AttnDesc) -> str:
+    p = lib().ff_attention_path(C.byref(desc))
+    if p is None:
+        raise FFError(FF_EINVAL, last_error())
+    return p.decode()
+
+
+def _alloc_ws(nbytes: int, device):
+    import torch
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)
+
+
+def ff_gated_attention(desc: AttnDesc, w: Dict[str, "object"], x, z=None, mask=None, out=None, ws=None):
+    """One gated attention module; returns out [n_a, n_b, c]."""
+    import torch
+    assert x.is_cuda and x.is_contiguous()
+    if out is None:
+        out = torch.empty_like(x)
+    if ws is None:
+        ws = _alloc_ws(ff_attention_workspace_bytes(desc, 0), x.device)
+    wts = make_weights(w)
+    _check(lib().ff_gated_attention(C.byref(desc), C.byref(wts), _ptr(x), _ptr(z), _ptr(mask), _ptr(out), _ptr(ws),
+                                    ws.numel(), _stream()))
+    return out
+
+
+def ff_attention_chunked(desc: AttnDesc, w: Dict[str, "object"], x, z=None, mask=None, chunk_rows: int = 64,
+                         out=None, ws=None):
+    """The same module, chunk_rows batch rows at a time."""
+    import torch
+    assert x.is_cuda and x.is_contiguous()
+    if out is None:
+        out = torch.empty_like(x)
+    if ws is None:
+        ws = _alloc_ws(ff_attention_workspace_bytes(desc, max(chunk_rows, 1)), x.device)
+    wts = make_weights(w)
+    _check(lib().ff_attention_chunked(C.byref(desc), C.byref(wts), _ptr(x), _ptr(z), _ptr(mask), _ptr(out), _ptr(ws),
+                                      ws.numel(), _stream(), chunk_rows))
+    return out
+
+
+# ------------------------------------------------------------------------- test/bench glue
+def to_device(case, device="cuda:0"):
+    """Upload a seeded case (paper_2203_00854_amd.inputs.Case) as torch tensors.
+    Returns (desc, weights, x, z, mask)."""
+    import numpy as np
+    import torch
+
+    def up(a):
+        if a is None:
+            return None
+        if a.dtype == np.uint16:
+            return torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
+        return torch.from_numpy(a).to(device)
+
+    sp = case.spec
+    x = up(case.x)
+    z = up(case.z)
+    mask = up(case.mask)
+    w = {k: up(v) for k, v in case.weights.items()}
+    desc = AttnDesc(sp.mode, FF_F32 if sp.dtype == "f32" else FF_BF16, sp.n_a, sp.n_b, sp.c, sp.c_z, sp.heads,
+                    sp.head_dim, sp.ln_eps)
+    return desc, w, x, z, mask

@@ -1,0 +1,155 @@
+// C ABI entry points of libff: argument checking, workspace carving, the chunk loop.
+// All arithmetic of the path runs in the kernels of the other translation units.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "ff_common.h"
+
+namespace ff {
+
+static thread_local char g_err[512] = "";
+
+ff_status fail(ff_status st, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+ff_status check_launch(const char* what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(FF_EHIP, "%s: %s", what, hipGetErrorString(e));
+    return FF_OK;
+}
+
+static ff_status make_problem(const ff_attn_desc* d, Problem* p) {
+    if (!d) return fail(FF_EINVAL, "desc is NULL");
+    if (d->mode < FF_MSA_ROW || d->mode > FF_TRI_END) return fail(FF_EINVAL, "bad mode %d", d->mode);
+    if (d->dtype != FF_F32 && d->dtype != FF_BF16) return fail(FF_EINVAL, "bad dtype %d", d->dtype);
+    if (d->n_a < 1 || d->n_b < 1 || d->c < 1 || d->heads < 1 || d->head_dim < 1)
+        return fail(FF_EINVAL, "non-positive size (n_a=%d n_b=%d c=%d heads=%d head_dim=%d)", d->n_a, d->n_b,
+                    d->c, d->heads, d->head_dim);
+    if (d->mode == FF_MSA_ROW && d->c_z < 1) return fail(FF_EINVAL, "row mode needs c_z >= 1 (got %d)", d->c_z);
+    if ((d->mode == FF_TRI_START || d->mode == FF_TRI_END) && d->n_a != d->n_b)
+        return fail(FF_EINVAL, "triangle modes need n_a == n_b (got %d, %d)", d->n_a, d->n_b);
+    if (!(d->ln_eps >= 0.f)) return fail(FF_EINVAL, "ln_eps must be >= 0");
+    if (d->head_dim > 128) return fail(FF_EUNSUPPORTED, "head_dim %d > 128", d->head_dim);
+    if (d->c > 8192 || (d->mode == FF_MSA_ROW && d->c_z > 8192))
+        return fail(FF_EUNSUPPORTED, "c or c_z > 8192");
+    if ((int64_t)d->heads * d->head_dim > 16384) return fail(FF_EUNSUPPORTED, "heads*head_dim > 16384");
+    p->mode = d->mode;
+    p->dtype = d->dtype;
+    p->n_a = d->n_a;
+    p->n_b = d->n_b;
+    p->c = d->c;
+    p->c_z = d->mode == FF_MSA_ROW ? d->c_z : 0;
+    p->H = d->heads;
+    p->d = d->head_dim;
+    p->Hd = d->heads * d->head_dim;
+    p->eps = d->ln_eps;
+    const bool along_b = (d->mode == FF_MSA_ROW || d->mode == FF_TRI_START);
+    p->R = along_b ? d->n_a : d->n_b;
+    p->L = along_b ? d->n_b : d->n_a;
+    p->sr = along_b ? d->n_b : 1;
+    p->sl = along_b ? 1 : d->n_b;
+    p->has_bias = d->mode != FF_MSA_COL;
+    return FF_OK;
+}
+
+static size_t carve(const Problem& p, int chunk, Workspace* ws, void* base) {
+    return mfma_supported(p) ? mfma_workspace(p, chunk, ws, base) : generic_workspace(p, chunk, ws, base);
+}
+
+static ff_status run(const ff_attn_desc* desc, const ff_attn_weights* w, const void* x, const void* z,
+                     const float* mask, void* out, void* wsp, size_t ws_bytes, void* stream_, int chunk_rows,
+                     bool chunked) {
+    Problem p;
+    ff_status st = make_problem(desc, &p);
+    if (st != FF_OK) return st;
+    if (chunked && chunk_rows < 1) return fail(FF_EINVAL, "chunk_rows must be >= 1 (got %d)", chunk_rows);
+    if (!w) return fail(FF_EINVAL, "weights is NULL");
+    if (!x || !out) return fail(FF_EINVAL, "x or out is NULL");
+    if (!w->ln_g || !w->ln_b || !w->w_q || !w->w_k || !w->w_v || !w->w_g || !w->b_g || !w->w_o || !w->b_o)
+        return fail(FF_EINVAL, "a required weight pointer is NULL");
+    if (p.mode == FF_MSA_ROW) {
+        if (!z) return fail(FF_EINVAL, "row mode needs z");
+        if (!w->lnz_g || !w->lnz_b || !w->w_b) return fail(FF_EINVAL, "row mode needs lnz_g, lnz_b and w_b");
+    } else {
+        if (z) return fail(FF_EINVAL, "z must be NULL outside row mode");
+        if (p.has_bias && !w->w_b) return fail(FF_EINVAL, "triangle modes need w_b");
+    }
+    if (out == x || (z && out == z)) return fail(FF_EINVAL, "out must not alias x or z");
+    int chunk = chunked ? (chunk_rows < p.R ? chunk_rows : p.R) : p.R;
+    Workspace ws;
+    size_t need = carve(p, chunk, &ws, wsp);
+    if (!wsp) return fail(FF_EINVAL, "workspace is NULL (%zu bytes needed)", need);
+    if (((uintptr_t)wsp & 255u) != 0) return fail(FF_EINVAL, "workspace must be 256-byte aligned");
+    if (ws_bytes < need) return fail(FF_EWORKSPACE, "workspace too small: %zu bytes given, %zu needed", ws_bytes, need);
+
+    hipStream_t stream = (hipStream_t)stream_;
+    const bool fast = mfma_supported(p);
+    if (p.has_bias) {
+        st = fast ? mfma_bias(p, *w, x, z, ws, stream) : generic_bias(p, *w, x, z, ws, stream);
+        if (st != FF_OK) return st;
+    }
+    for (int r0 = 0; r0 < p.R; r0 += chunk) {
+        int rows = p.R - r0 < chunk ? p.R - r0 : chunk;
+        st = fast ? mfma_chunk(p, *w, x, mask, out, ws, r0, rows, stream)
+                  : generic_chunk(p, *w, x, mask, out, ws, r0, rows, stream);
+        if (st != FF_OK) return st;
+    }
+    return FF_OK;
+}
+
+}  // namespace ff
+
+using namespace ff;
+
+extern "C" {
+
+ff_status ff_layernorm(const void* x, const void* gamma, const void* beta, void* y, int64_t rows, int32_t c,
+                       float eps, int32_t dt, void* hip_stream) {
+    if (dt != FF_F32 && dt != FF_BF16) return fail(FF_EINVAL, "bad dtype %d", dt);
+    if (rows < 0 || c < 1 || c > 8192) return fail(FF_EINVAL, "bad size rows=%lld c=%d", (long long)rows, c);
+    if (!(eps >= 0.f)) return fail(FF_EINVAL, "eps must be >= 0");
+    if (rows == 0) return FF_OK;
+    if (!x || !gamma || !beta || !y) return fail(FF_EINVAL, "NULL pointer");
+    return layernorm_launch(x, gamma, beta, y, rows, c, eps, dt, (hipStream_t)hip_stream);
+}
+
+size_t ff_attention_workspace_bytes(const ff_attn_desc* desc, int32_t chunk_rows) {
+    Problem p;
+    if (make_problem(desc, &p) != FF_OK) return 0;
+    if (chunk_rows < 0) {
+        fail(FF_EINVAL, "chunk_rows must be >= 0");
+        return 0;
+    }
+    int chunk = (chunk_rows == 0 || chunk_rows > p.R) ? p.R : chunk_rows;
+    Workspace ws;
+    return carve(p, chunk, &ws, nullptr);
+}
+
+ff_status ff_gated_attention(const ff_attn_desc* desc, const ff_attn_weights* w, const void* x, const void* z,
+                             const float* mask, void* out, void* ws, size_t ws_bytes, void* hip_stream) {
+    return run(desc, w, x, z, mask, out, ws, ws_bytes, hip_stream, 0, false);
+}
+
+ff_status ff_attention_chunked(const ff_attn_desc* desc, const ff_attn_weights* w, const void* x, const void* z,
+                               const float* mask, void* out, void* ws, size_t ws_bytes, void* hip_stream,
+                               int32_t chunk_rows) {
+    return run(desc, w, x, z, mask, out, ws, ws_bytes, hip_stream, chunk_rows, true);
+}
+
+const char* ff_attention_path(const ff_attn_desc* desc) {
+    Problem p;
+    if (make_problem(desc, &p) != FF_OK) return nullptr;
+    return mfma_supported(p) ? "mfma_bf16" : "generic";
+}
+
+const char* ff_last_error(void) { return g_err; }
+
+const char* ff_version(void) { return "libff 0.1 (gfx950)"; }
+
+}  // extern "C"

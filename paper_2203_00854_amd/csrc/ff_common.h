@@ -1,0 +1,92 @@
+// Internal declarations shared by the libff translation units (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "ff.h"
+
+namespace ff {
+
+typedef uint16_t bf16_t;  // bfloat16 bit pattern
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+// ---- scalar conversions -------------------------------------------------------------
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+
+// round to nearest even; NaN stays NaN
+__device__ __forceinline__ bf16_t f32_to_bf16(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+
+template <typename T> __device__ __forceinline__ float to_f32(T v);
+template <> __device__ __forceinline__ float to_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f32<bf16_t>(bf16_t v) { return bf16_to_f32(v); }
+
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return f32_to_bf16(v); }
+
+// ---- wave64 reductions --------------------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// ---- the problem as the kernels see it ------------------------------------------------
+// Every mode is "R independent batch rows, each a sequence of L tokens".  Token (r, l)
+// of the mode lives at x + (r*sr + l*sl) * c; the mask entry of key (r, l) at mask[r*sr + l*sl].
+struct Problem {
+    int mode, dtype;
+    int n_a, n_b, c, c_z, H, d;
+    float eps;
+    int R, L;          // batch rows, attended length
+    int64_t sr, sl;    // token strides
+    int Hd;            // H*d
+    bool has_bias;
+};
+
+struct Workspace {
+    float* bias;       // [H, L, L] float32, already multiplied by log2(e); NULL in column mode
+    void* qkvg;        // layout is private to each kernel family
+    void* o;           // gated context of one chunk
+    float* stats;      // generic family: mean, rstd per token of one chunk
+    size_t total;      // bytes
+};
+
+// error plumbing (ff_api.hip)
+ff_status fail(ff_status st, const char* fmt, ...);
+ff_status check_launch(const char* what);
+
+// ---- kernel families (each returns after enqueueing on `stream`) ---------------------
+// generic float32 vector path (ff_generic.hip); T selected by p.dtype
+size_t generic_workspace(const Problem& p, int chunk, Workspace* ws, void* base);
+ff_status generic_bias(const Problem& p, const ff_attn_weights& w, const void* x, const void* z,
+                       const Workspace& ws, hipStream_t stream);
+ff_status generic_chunk(const Problem& p, const ff_attn_weights& w, const void* x, const float* mask,
+                        void* out, const Workspace& ws, int r0, int rows, hipStream_t stream);
+
+// bf16 matrix-core path (ff_mfma_*.hip)
+bool mfma_supported(const Problem& p);
+size_t mfma_workspace(const Problem& p, int chunk, Workspace* ws, void* base);
+ff_status mfma_bias(const Problem& p, const ff_attn_weights& w, const void* x, const void* z,
+                    const Workspace& ws, hipStream_t stream);
+ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, const float* mask,
+                     void* out, const Workspace& ws, int r0, int rows, hipStream_t stream);
+
+// LayerNorm (ff_layernorm.hip)
+ff_status layernorm_launch(const void* x, const void* g, const void* b, void* y, int64_t rows, int c,
+                           float eps, int dt, hipStream_t stream);
+
+}  // namespace ff

@@ -1,0 +1,124 @@
+"""The C-ABI library loads, exports what include/ff.h declares, and rejects bad arguments
+with status codes before anything reaches the GPU.  No compute calls here."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2203_00854_amd as P
+from paper_2203_00854_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "ff.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ff_[a-z_]+)\s*\(", text)))
+
+
+def test_header_declares_the_boundary():
+    names = header_functions()
+    for n in ("ff_layernorm", "ff_gated_attention", "ff_attention_chunked", "ff_attention_workspace_bytes",
+              "ff_last_error"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol():
+    lib = P.lib()
+    for n in header_functions():
+        assert hasattr(lib, n), n
+
+
+def test_struct_layout_matches_header():
+    assert C.sizeof(B.AttnDesc) == 9 * 4
+    assert C.sizeof(B.AttnWeights) == 12 * C.sizeof(C.c_void_p)
+
+
+def good_desc(**kw):
+    d = dict(mode=P.FF_MSA_ROW, dtype=P.FF_BF16, n_a=8, n_b=32, c=32, c_z=16, heads=4, head_dim=8, ln_eps=1e-5)
+    d.update(kw)
+    return P.AttnDesc(**d)
+
+
+def test_workspace_size_is_positive_and_grows_with_chunk():
+    d = good_desc()
+    full = P.ff_attention_workspace_bytes(d, 0)
+    one = P.ff_attention_workspace_bytes(d, 1)
+    assert 0 < one < full
+    assert P.ff_attention_workspace_bytes(d, 10 ** 6) == full
+    assert full % 256 == 0
+
+
+def test_workspace_never_holds_the_score_tensor():
+    """Section 3.2: the score tensor N_r^3 * N_head * 2 bytes is the memory problem.  The
+    workspace for N_res=2048, H=4 chunked by 64 rows must be far below 4*2048^3*2 = 68.7 GB
+    and even below one chunk of scores (64*4*2048^2*2 = 2.1 GB)."""
+    d = good_desc(mode=P.FF_TRI_START, n_a=2048, n_b=2048, c=128, c_z=0, heads=4, head_dim=32)
+    ws = P.ff_attention_workspace_bytes(d, 64)
+    assert ws < 64 * 4 * 2048 ** 2 * 2
+    assert ws < 1 << 30
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(mode=9), B.FF_EINVAL), (dict(dtype=5), B.FF_EINVAL), (dict(n_a=0), B.FF_EINVAL),
+    (dict(heads=-1), B.FF_EINVAL), (dict(c_z=0), B.FF_EINVAL), (dict(head_dim=256), B.FF_EUNSUPPORTED),
+    (dict(mode=P.FF_TRI_START, n_a=5, n_b=6), B.FF_EINVAL), (dict(c=10000), B.FF_EUNSUPPORTED),
+])
+def test_bad_descriptors(kw, status):
+    d = good_desc(**kw)
+    assert P.lib().ff_attention_workspace_bytes(C.byref(d), 0) == 0
+    assert P.last_error() != ""
+    w = B.AttnWeights()
+    st = P.lib().ff_gated_attention(C.byref(d), C.byref(w), 0x1000, 0x2000, None, 0x3000, 0x100000, 1 << 40, None)
+    assert st == status
+
+
+def _fake_weights(row=True):
+    w = B.AttnWeights()
+    for i, n in enumerate(B.WEIGHT_FIELDS):
+        setattr(w, n, 0x10000 * (i + 1))
+    if not row:
+        w.lnz_g = None
+        w.lnz_b = None
+    return w
+
+
+def test_argument_errors_before_any_launch():
+    lib = P.lib()
+    d = good_desc()
+    w = _fake_weights()
+    need = P.ff_attention_workspace_bytes(d, 0)
+    X, Z, OUT, WS = 0x100000, 0x200000, 0x300000, 0x400000
+    call = lambda *a: lib.ff_gated_attention(C.byref(d), *a)
+    assert call(C.byref(w), None, Z, None, OUT, WS, need, None) == B.FF_EINVAL          # x NULL
+    assert call(C.byref(w), X, None, None, OUT, WS, need, None) == B.FF_EINVAL          # z missing in row mode
+    assert call(C.byref(w), X, Z, None, X, WS, need, None) == B.FF_EINVAL               # out aliases x
+    assert call(C.byref(w), X, Z, None, OUT, None, need, None) == B.FF_EINVAL           # no workspace
+    assert call(C.byref(w), X, Z, None, OUT, WS + 8, need, None) == B.FF_EINVAL         # misaligned workspace
+    assert call(C.byref(w), X, Z, None, OUT, WS, need - 1, None) == B.FF_EWORKSPACE
+    assert "workspace too small" in P.last_error()
+    assert call(None, X, Z, None, OUT, WS, need, None) == B.FF_EINVAL                   # weights NULL
+    w2 = _fake_weights()
+    w2.w_b = None
+    assert call(C.byref(w2), X, Z, None, OUT, WS, need, None) == B.FF_EINVAL
+    dc = good_desc(mode=P.FF_MSA_COL)
+    wc = _fake_weights(row=False)
+    assert lib.ff_gated_attention(C.byref(dc), C.byref(wc), X, Z, None, OUT, WS, 1 << 40, None) == B.FF_EINVAL  # z given
+    assert lib.ff_attention_chunked(C.byref(d), C.byref(w), X, Z, None, OUT, WS, need, None, 0) == B.FF_EINVAL
+    assert "chunk_rows" in P.last_error()
+
+
+def test_layernorm_argument_errors():
+    lib = P.lib()
+    assert lib.ff_layernorm(0x1000, 0x2000, 0x3000, 0x4000, 4, 0, 1e-5, 0, None) == B.FF_EINVAL
+    assert lib.ff_layernorm(0x1000, 0x2000, 0x3000, 0x4000, -1, 8, 1e-5, 0, None) == B.FF_EINVAL
+    assert lib.ff_layernorm(0x1000, 0x2000, 0x3000, 0x4000, 4, 8, 1e-5, 3, None) == B.FF_EINVAL
+    assert lib.ff_layernorm(None, 0x2000, 0x3000, 0x4000, 4, 8, 1e-5, 0, None) == B.FF_EINVAL
+    assert lib.ff_layernorm(None, None, None, None, 0, 8, 1e-5, 0, None) == B.FF_OK     # empty input: nothing to do
+
+
+def test_path_selection_reports_a_family():
+    assert P.ff_attention_path(good_desc(dtype=P.FF_F32)) == "generic"
+    assert P.ff_attention_path(good_desc(n_a=128, n_b=256, c=256, c_z=128, heads=8, head_dim=32)) in ("mfma_bf16", "generic")
