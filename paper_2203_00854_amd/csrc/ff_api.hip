@@ -58,8 +58,24 @@ static ff_status make_problem(const ff_attn_desc* d, Problem* p) {
     return FF_OK;
 }
 
-static size_t carve(const Problem& p, int chunk, Workspace* ws, void* base) {
-    return mfma_supported(p) ? mfma_workspace(p, chunk, ws, base) : generic_workspace(p, chunk, ws, base);
+// Both families need at most max(mfma, generic) bytes; the size reported to the caller is that
+// maximum so that the family can still be chosen per call (the matrix-core kernels use 16-byte
+// accesses and are only taken when every pointer is 16-byte aligned).
+static size_t carve(const Problem& p, int chunk, Workspace* ws, void* base, bool fast) {
+    return fast ? mfma_workspace(p, chunk, ws, base) : generic_workspace(p, chunk, ws, base);
+}
+static size_t workspace_need(const Problem& p, int chunk) {
+    Workspace tmp;
+    size_t a = generic_workspace(p, chunk, &tmp, nullptr);
+    if (mfma_supported(p)) {
+        size_t b = mfma_workspace(p, chunk, &tmp, nullptr);
+        if (b > a) a = b;
+    }
+    return a;
+}
+static bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+static bool overlaps(const void* a, size_t an, const void* b, size_t bn) {
+    return (uintptr_t)a < (uintptr_t)b + bn && (uintptr_t)b < (uintptr_t)a + an;
 }
 
 static ff_status run(const ff_attn_desc* desc, const ff_attn_weights* w, const void* x, const void* z,
@@ -80,16 +96,24 @@ static ff_status run(const ff_attn_desc* desc, const ff_attn_weights* w, const v
         if (z) return fail(FF_EINVAL, "z must be NULL outside row mode");
         if (p.has_bias && !w->w_b) return fail(FF_EINVAL, "triangle modes need w_b");
     }
-    if (out == x || (z && out == z)) return fail(FF_EINVAL, "out must not alias x or z");
+    const size_t esz = p.dtype == FF_F32 ? 4 : 2;
+    const size_t x_bytes = (size_t)p.n_a * p.n_b * p.c * esz;
+    const size_t z_bytes = (size_t)p.n_b * p.n_b * p.c_z * esz;
+    if (overlaps(out, x_bytes, x, x_bytes) || (z && overlaps(out, x_bytes, z, z_bytes)))
+        return fail(FF_EINVAL, "out must not overlap x or z");
     int chunk = chunked ? (chunk_rows < p.R ? chunk_rows : p.R) : p.R;
-    Workspace ws;
-    size_t need = carve(p, chunk, &ws, wsp);
+    const size_t need = workspace_need(p, chunk);
     if (!wsp) return fail(FF_EINVAL, "workspace is NULL (%zu bytes needed)", need);
     if (((uintptr_t)wsp & 255u) != 0) return fail(FF_EINVAL, "workspace must be 256-byte aligned");
     if (ws_bytes < need) return fail(FF_EWORKSPACE, "workspace too small: %zu bytes given, %zu needed", ws_bytes, need);
+    if (overlaps(out, x_bytes, wsp, need)) return fail(FF_EINVAL, "out must not overlap the workspace");
 
     hipStream_t stream = (hipStream_t)stream_;
-    const bool fast = mfma_supported(p);
+    bool fast = mfma_supported(p) && aligned16(x) && aligned16(out) && aligned16(z);
+    const void* wp[] = {w->ln_g, w->ln_b, w->lnz_g, w->lnz_b, w->w_q, w->w_k, w->w_v, w->w_b, w->w_g, w->b_g, w->w_o, w->b_o};
+    for (const void* q : wp) fast = fast && aligned16(q);
+    Workspace ws;
+    carve(p, chunk, &ws, wsp, fast);
     if (p.has_bias) {
         st = fast ? mfma_bias(p, *w, x, z, ws, stream) : generic_bias(p, *w, x, z, ws, stream);
         if (st != FF_OK) return st;
@@ -127,8 +151,7 @@ size_t ff_attention_workspace_bytes(const ff_attn_desc* desc, int32_t chunk_rows
         return 0;
     }
     int chunk = (chunk_rows == 0 || chunk_rows > p.R) ? p.R : chunk_rows;
-    Workspace ws;
-    return carve(p, chunk, &ws, nullptr);
+    return workspace_need(p, chunk);
 }
 
 ff_status ff_gated_attention(const ff_attn_desc* desc, const ff_attn_weights* w, const void* x, const void* z,

@@ -63,6 +63,7 @@ struct Workspace {
     void* o;           // gated context of one chunk
     float* stats;      // generic family: mean, rstd per token of one chunk
     size_t total;      // bytes
+    int chunk;         // batch rows per chunk the tensors above are sized for
 };
 
 // error plumbing (ff_api.hip)
@@ -74,6 +75,9 @@ ff_status check_launch(const char* what);
 size_t generic_workspace(const Problem& p, int chunk, Workspace* ws, void* base);
 ff_status generic_bias(const Problem& p, const ff_attn_weights& w, const void* x, const void* z,
                        const Workspace& ws, hipStream_t stream);
+// the generic bias kernel writing into a [H][Lq][Lp] tensor (both families use it)
+ff_status generic_bias_into(const Problem& p, const ff_attn_weights& w, const void* x, const void* z, float* bias,
+                            int Lq, int Lp, hipStream_t stream);
 ff_status generic_chunk(const Problem& p, const ff_attn_weights& w, const void* x, const float* mask,
                         void* out, const Workspace& ws, int r0, int rows, hipStream_t stream);
 

@@ -33,6 +33,7 @@ size_t generic_workspace(const Problem& p, int chunk, Workspace* ws, void* base)
     ws->o = b + off;
     off += align256(tokens * p.Hd * esz);
     ws->total = off;
+    ws->chunk = chunk;
     return off;
 }
 
@@ -42,7 +43,7 @@ size_t generic_workspace(const Problem& p, int chunk, Workspace* ws, void* base)
 template <typename T>
 __global__ __launch_bounds__(256) void k_bias_generic(const T* __restrict__ src, int64_t sq, int64_t sk, int c,
                                                        const T* __restrict__ g, const T* __restrict__ b,
-                                                       const T* __restrict__ wb, int H, int L, float eps,
+                                                       const T* __restrict__ wb, int H, int L, int Lq, int Lp, float eps,
                                                        float* __restrict__ bias) {
     const int lane = threadIdx.x & 63;
     const int64_t pair = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -65,7 +66,7 @@ __global__ __launch_bounds__(256) void k_bias_generic(const T* __restrict__ src,
             acc += xh * to_f32<T>(wb[(size_t)h * c + i]);
         }
         acc = wave_sum(acc);
-        if (lane == 0) bias[((size_t)h * L + q) * L + k] = acc * kLog2e;
+        if (lane == 0) bias[((size_t)h * Lq + q) * Lp + k] = acc * kLog2e;
     }
 }
 
@@ -99,7 +100,7 @@ __global__ __launch_bounds__(256) void k_stats_generic(const T* __restrict__ x, 
 //   PROJ = true : A = LayerNorm(x) on the fly (stats, gamma, beta), B rows from w_q|w_k|w_v|w_g,
 //                 epilogue: q scaled, gate = sigmoid(acc + b_g); C -> qkvg[t][4Hd]
 //   PROJ = false: A = o[t][Hd], B = w_o, epilogue + b_o, C -> out at the token's address.
-struct GemmArgs {
+struct GenericGemmArgs {
     const void* a;         // x (PROJ) or o
     int64_t sr, sl;        // token strides of x / out
     int L, r0, tokens;     // chunk geometry
@@ -114,7 +115,7 @@ struct GemmArgs {
 };
 
 template <typename T, bool PROJ>
-__global__ __launch_bounds__(256) void k_gemm_generic(GemmArgs g) {
+__global__ __launch_bounds__(256) void k_gemm_generic(GenericGemmArgs g) {
     __shared__ float As[16][64 + 1];
     __shared__ float Bs[16][64 + 1];
     const int tid = threadIdx.x;
@@ -258,16 +259,16 @@ __global__ __launch_bounds__(256) void k_attn_generic(const T* __restrict__ qkvg
 
 // ---------------------------------------------------------------------------------------
 template <typename T>
-static ff_status bias_t(const Problem& p, const ff_attn_weights& w, const void* x, const void* z,
-                        const Workspace& ws, hipStream_t st) {
+static ff_status bias_t(const Problem& p, const ff_attn_weights& w, const void* x, const void* z, float* bias, int Lq,
+                        int Lp, hipStream_t st) {
     const int64_t pairs = (int64_t)p.L * p.L;
     const unsigned blocks = (unsigned)((pairs + 3) / 4);
     if (p.mode == FF_MSA_ROW)
         hipLaunchKernelGGL((k_bias_generic<T>), dim3(blocks), dim3(256), 0, st, (const T*)z, (int64_t)p.L, (int64_t)1,
-                           p.c_z, (const T*)w.lnz_g, (const T*)w.lnz_b, (const T*)w.w_b, p.H, p.L, p.eps, ws.bias);
+                           p.c_z, (const T*)w.lnz_g, (const T*)w.lnz_b, (const T*)w.w_b, p.H, p.L, Lq, Lp, p.eps, bias);
     else
         hipLaunchKernelGGL((k_bias_generic<T>), dim3(blocks), dim3(256), 0, st, (const T*)x, p.sr, p.sl, p.c,
-                           (const T*)w.ln_g, (const T*)w.ln_b, (const T*)w.w_b, p.H, p.L, p.eps, ws.bias);
+                           (const T*)w.ln_g, (const T*)w.ln_b, (const T*)w.w_b, p.H, p.L, Lq, Lp, p.eps, bias);
     return check_launch("bias (generic)");
 }
 
@@ -277,7 +278,7 @@ static ff_status chunk_t(const Problem& p, const ff_attn_weights& w, const void*
     const int tokens = rows * p.L;
     hipLaunchKernelGGL((k_stats_generic<T>), dim3((tokens + 3) / 4), dim3(256), 0, st, (const T*)x, p.sr, p.sl, p.c,
                        p.L, r0, tokens, p.eps, ws.stats);
-    GemmArgs g{};
+    GenericGemmArgs g{};
     g.a = x; g.sr = p.sr; g.sl = p.sl; g.L = p.L; g.r0 = r0; g.tokens = tokens;
     g.K = p.c; g.N = 4 * p.Hd; g.stats = ws.stats; g.ln_g = w.ln_g; g.ln_b = w.ln_b;
     g.w[0] = w.w_q; g.w[1] = w.w_k; g.w[2] = w.w_v; g.w[3] = w.w_g; g.bvec = w.b_g; g.Hd = p.Hd;
@@ -297,7 +298,7 @@ static ff_status chunk_t(const Problem& p, const ff_attn_weights& w, const void*
     else FF_ATTN(128);
 #undef FF_ATTN
 
-    GemmArgs o{};
+    GenericGemmArgs o{};
     o.a = ws.o; o.sr = p.sr; o.sl = p.sl; o.L = p.L; o.r0 = r0; o.tokens = tokens;
     o.K = p.Hd; o.N = p.c; o.w[0] = w.w_o; o.bvec = w.b_o; o.Hd = p.Hd; o.cdst = out;
     hipLaunchKernelGGL((k_gemm_generic<T, false>), dim3((tokens + 63) / 64, (o.N + 63) / 64), dim3(256), 0, st, o);
@@ -306,7 +307,13 @@ static ff_status chunk_t(const Problem& p, const ff_attn_weights& w, const void*
 
 ff_status generic_bias(const Problem& p, const ff_attn_weights& w, const void* x, const void* z, const Workspace& ws,
                        hipStream_t stream) {
-    return p.dtype == FF_F32 ? bias_t<float>(p, w, x, z, ws, stream) : bias_t<bf16_t>(p, w, x, z, ws, stream);
+    return generic_bias_into(p, w, x, z, ws.bias, p.L, p.L, stream);
+}
+
+ff_status generic_bias_into(const Problem& p, const ff_attn_weights& w, const void* x, const void* z, float* bias,
+                            int Lq, int Lp, hipStream_t stream) {
+    return p.dtype == FF_F32 ? bias_t<float>(p, w, x, z, bias, Lq, Lp, stream)
+                             : bias_t<bf16_t>(p, w, x, z, bias, Lq, Lp, stream);
 }
 
 ff_status generic_chunk(const Problem& p, const ff_attn_weights& w, const void* x, const float* mask, void* out,
