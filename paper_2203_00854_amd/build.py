@@ -25,6 +25,9 @@ FLAGS = [
     "-Wall", "-Wno-unused-function",
     # packed-FP32 VALU forms are switched off for all device code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # matrix-core accumulators live in ordinary VGPRs: the softmax works on them directly,
+    # so the AGPR form would cost a register move per element and tile
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
 

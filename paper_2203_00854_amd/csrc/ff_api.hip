@@ -114,10 +114,8 @@ static ff_status run(const ff_attn_desc* desc, const ff_attn_weights* w, const v
     for (const void* q : wp) fast = fast && aligned16(q);
     Workspace ws;
     carve(p, chunk, &ws, wsp, fast);
-    if (p.has_bias) {
-        st = fast ? mfma_bias(p, *w, x, z, ws, stream) : generic_bias(p, *w, x, z, ws, stream);
-        if (st != FF_OK) return st;
-    }
+    st = fast ? mfma_prepare(p, *w, x, z, ws, stream) : generic_prepare(p, *w, x, z, ws, stream);
+    if (st != FF_OK) return st;
     for (int r0 = 0; r0 < p.R; r0 += chunk) {
         int rows = p.R - r0 < chunk ? p.R - r0 : chunk;
         st = fast ? mfma_chunk(p, *w, x, mask, out, ws, r0, rows, stream)

@@ -62,6 +62,7 @@ struct Workspace {
     void* qkvg;        // layout is private to each kernel family
     void* o;           // gated context of one chunk
     float* stats;      // generic family: mean, rstd per token of one chunk
+    void* prep;        // matrix-core family: prepared weights
     size_t total;      // bytes
     int chunk;         // batch rows per chunk the tensors above are sized for
 };
@@ -73,8 +74,10 @@ ff_status check_launch(const char* what);
 // ---- kernel families (each returns after enqueueing on `stream`) ---------------------
 // generic float32 vector path (ff_generic.hip); T selected by p.dtype
 size_t generic_workspace(const Problem& p, int chunk, Workspace* ws, void* base);
-ff_status generic_bias(const Problem& p, const ff_attn_weights& w, const void* x, const void* z,
-                       const Workspace& ws, hipStream_t stream);
+// once per call, before the chunks: the pair-bias tensor (and, for the matrix-core family, the
+// prepared weights)
+ff_status generic_prepare(const Problem& p, const ff_attn_weights& w, const void* x, const void* z,
+                          const Workspace& ws, hipStream_t stream);
 // the generic bias kernel writing into a [H][Lq][Lp] tensor (both families use it)
 ff_status generic_bias_into(const Problem& p, const ff_attn_weights& w, const void* x, const void* z, float* bias,
                             int Lq, int Lp, hipStream_t stream);
@@ -84,8 +87,8 @@ ff_status generic_chunk(const Problem& p, const ff_attn_weights& w, const void* 
 // bf16 matrix-core path (ff_mfma_*.hip)
 bool mfma_supported(const Problem& p);
 size_t mfma_workspace(const Problem& p, int chunk, Workspace* ws, void* base);
-ff_status mfma_bias(const Problem& p, const ff_attn_weights& w, const void* x, const void* z,
-                    const Workspace& ws, hipStream_t stream);
+ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x, const void* z,
+                       const Workspace& ws, hipStream_t stream);
 ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, const float* mask,
                      void* out, const Workspace& ws, int r0, int rows, hipStream_t stream);
 

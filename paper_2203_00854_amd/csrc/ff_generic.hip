@@ -26,6 +26,7 @@ size_t generic_workspace(const Problem& p, int chunk, Workspace* ws, void* base)
         ws->bias = (float*)(b + off);
         off += align256((size_t)p.H * p.L * p.L * 4);
     }
+    ws->prep = nullptr;
     ws->stats = (float*)(b + off);
     off += align256(tokens * 2 * 4);
     ws->qkvg = b + off;
@@ -305,8 +306,9 @@ static ff_status chunk_t(const Problem& p, const ff_attn_weights& w, const void*
     return check_launch("attention chunk (generic)");
 }
 
-ff_status generic_bias(const Problem& p, const ff_attn_weights& w, const void* x, const void* z, const Workspace& ws,
-                       hipStream_t stream) {
+ff_status generic_prepare(const Problem& p, const ff_attn_weights& w, const void* x, const void* z,
+                          const Workspace& ws, hipStream_t stream) {
+    if (!p.has_bias) return FF_OK;
     return generic_bias_into(p, w, x, z, ws.bias, p.L, p.L, stream);
 }
 

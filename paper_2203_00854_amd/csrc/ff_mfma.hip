@@ -1,30 +1,38 @@
 // bfloat16 matrix-core kernel family for gfx950 (wave64, v_mfma_f32_32x32x16_bf16).
 //
-// Pipeline per chunk of batch rows (FastFold Sections 2.1, 2.3, 5.2):
-//   k_pair_bias   LayerNorm + H dot products per pair, float32 bias tensor     (HBM bound)
-//   k_gemm<PROJ>  LayerNorm fused as the prologue of the merged q|k|v|gate GEMM
-//                 (Section 5.2 "merge GEMM"); epilogue scales q, applies bias+sigmoid
-//                 to the gate, writes q,k,gate token-major and v transposed
-//   k_attn        flash-style attention: S^T = K Q^T on the matrix cores with the
-//                 bias tile as accumulator input, mask, online softmax in registers
-//                 (the paper's fused scale+mask+bias softmax, Section 5.2, never
-//                 materialising the score tensor of Section 3.2), O^T = V^T P^T,
-//                 gate product in the epilogue
-//   k_gemm<OUT>   output projection + b_o, scattered to the caller's layout
+// Pipeline per call (FastFold Sections 2.1, 2.3, 5.2):
+//   k_prep      once per call: folds the LayerNorm gain into the merged q|k|v|gate(|bias)
+//               weight matrix (Section 5.2 "merge GEMM"), with per-feature sums so that the
+//               LayerNorm can be finished in the GEMM epilogue
+//   k_gemm<PROJ> merged projection straight from the raw input: with W' = W*gamma,
+//               LN(x) W^T = rstd * (x W'^T - mean * rowsum(W')) + W beta, so the matrix cores
+//               read x as it lies in HBM and the statistics (float32, two passes over the
+//               register-resident row) only meet the result in the epilogue.  Epilogue:
+//               q scaled, gate = sigmoid(. + b_g), q,k,gate token-major, v transposed,
+//               pair-bias columns as float32 [H][Lq][Lp]
+//   k_attn      flash-style attention: S^T = K Q^T on the matrix cores with the bias tile as
+//               accumulator input; the key mask and the running reference maximum ride in
+//               two spare slots of the contraction, so the matrix core already returns
+//               s - m (+ -inf for masked keys) and the vector unit only exponentiates
+//               (the paper's fused scale + mask + bias softmax, Section 5.2, without ever
+//               materialising the score tensor of Section 3.2); O^T = V^T P^T; gate product
+//   k_gemm<OUT> output projection + b_o, scattered to the caller's layout
 //
-// Matrix-core operand layouts used throughout (wave64, 32x32x16, bf16 in, f32 out):
+// Matrix-core operand layouts (wave64, 32x32x16, bf16 in, f32 out):
 //   A (32 x 16): lane l holds row l%32, columns 8*(l/32) .. +7
 //   B (16 x 32): lane l holds column l%32, rows 8*(l/32) .. +7
 //   C/D (32 x 32): lane l holds column l%32, register v holds row 8*(v/4) + 4*(l/32) + v%4
-// Computing S^T (keys x queries) instead of S puts one query in one lane, so the softmax
-// statistics are lane-local except for one exchange between the two half-waves, and the
-// exponentiated tile already has the B-operand layout of the second contraction once the
-// key order inside a 32-key tile is permuted; the same permutation is applied when the K
-// rows and the V^T columns are fetched, so no data is moved between the two contractions.
+// Computing S^T (keys x queries) puts one query in one lane, so softmax statistics are
+// lane-local except for one exchange between the two half-waves, and the exponentiated tile
+// already has the B-operand layout of the second contraction once the key order inside a
+// 32-key tile is permuted; the same permutation is applied when K rows and V^T columns are
+// fetched, so nothing moves between the two contractions.
 //
 // Workspace layout of this family (Lp = L rounded up to 32, token p = rl*Lp + l):
 //   bias [H][Lq][Lp] float32 (times log2 e), Lq = L rounded up to 64
-//   q, k, g, o  [rows*Lp][Hd] bf16;  vt [rows][H][D][Lp] bf16 (pad keys hold zeros)
+//   q, k, g, o  [rows*Lp][Hd] bf16;  vt [rows][H][D][Lp] bf16
+//   prepared weights [(4*Hd + 32)][c] (+ [32][c_z] in row mode) bf16, their sums and offsets
+// Pad tokens (l in [L, Lp)) hold finite values everywhere; they are masked as keys.
 #include "ff_common.h"
 
 namespace ff {
@@ -39,7 +47,7 @@ union Frag {
     uint32_t w[4];
 };
 
-__device__ __forceinline__ uint32_t pack2(float a, float b) {
+__device__ __forceinline__ uint32_t pack2(float a, float b) {   // a -> low half (first element)
     bf16x2 t;
     t[0] = (__bf16)a;
     t[1] = (__bf16)b;
@@ -47,9 +55,16 @@ __device__ __forceinline__ uint32_t pack2(float a, float b) {
 }
 __device__ __forceinline__ float lo_f32(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float hi_f32(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+__device__ __forceinline__ float bf16_round(float f) { return lo_f32(pack2(f, 0.f)); }
 
 __device__ __forceinline__ uint4 ldg16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
 __device__ __forceinline__ uint2 ldg8(const void* p) { return *reinterpret_cast<const uint2*>(p); }
+
+// sum of the two bf16 halves of w, added to acc (v_dot2c_f32_bf16)
+__device__ __forceinline__ float add_pair(uint32_t w, float acc) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), __builtin_bit_cast(bf16x2, 0x3f803f80u), acc,
+                                           false);
+}
 
 // value of the other half-wave's lane (l ^ 32)
 __device__ __forceinline__ float other_half(float v) {
@@ -72,6 +87,8 @@ static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 // ------------------------------------------------------------------------------------
 struct MfmaWs {
     bf16_t *q, *k, *g, *vt, *o;
+    bf16_t *wp, *zwp;      // prepared weights: main [(4Hd+32)][c], row-mode bias [32][c_z]
+    float *sn, *cn;        // [(4Hd+32) + 32] row sums of wp / zwp, and output offsets
 };
 
 static MfmaWs split_ws(const Problem& p, int chunk, const Workspace& ws) {
@@ -83,6 +100,15 @@ static MfmaWs split_ws(const Problem& p, int chunk, const Workspace& ws) {
     m.g = m.k + n;
     m.vt = m.g + n;
     m.o = (bf16_t*)ws.o;
+    char* pr = (char*)ws.prep;
+    const size_t rows_main = 4 * (size_t)p.Hd + 32;
+    m.wp = (bf16_t*)pr;
+    pr += align256(rows_main * p.c * 2);
+    m.zwp = (bf16_t*)pr;
+    pr += align256((size_t)32 * (p.c_z > 0 ? p.c_z : 1) * 2);
+    m.sn = (float*)pr;
+    pr += align256((rows_main + 32) * 4);
+    m.cn = (float*)pr;
     return m;
 }
 
@@ -92,7 +118,8 @@ bool mfma_supported(const Problem& p) {
     if (p.Hd % 32 != 0 || p.Hd > 256) return false;
     if (p.d % 8 != 0 || p.d > 32) return false;
     if (p.L > 16384) return false;
-    if (p.mode == FF_MSA_ROW && (p.c_z % 8 != 0)) return false;
+    if (p.H > 32) return false;
+    if (p.mode == FF_MSA_ROW && (p.c_z % 16 != 0 || p.c_z > 256)) return false;
     return true;
 }
 
@@ -111,152 +138,120 @@ size_t mfma_workspace(const Problem& p, int chunk, Workspace* ws, void* base) {
     off += align256(4 * n);
     ws->o = b + off;
     off += align256(n);
+    ws->prep = b + off;
+    const size_t rows_main = 4 * (size_t)p.Hd + 32;
+    off += align256(rows_main * p.c * 2) + align256((size_t)32 * (p.c_z > 0 ? p.c_z : 1) * 2) +
+           2 * align256((rows_main + 32) * 4);
     ws->total = off;
     ws->chunk = chunk;
     return off;
 }
 
 // ====================================================================================
-// Pair bias.  A group of G lanes owns one pair (q, k): 16 bytes per lane, LayerNorm
-// statistics and the H dot products by xor-shuffles inside the group.
-//   bias[h][q][k] = log2(e) * sum_c LN(src[q,k,:])_c * w_b[h][c]
-template <int HMAX>
-__global__ __launch_bounds__(256) void k_pair_bias(const bf16_t* __restrict__ src, int64_t sq, int64_t sk, int c,
-                                                    const bf16_t* __restrict__ gam, const bf16_t* __restrict__ bet,
-                                                    const bf16_t* __restrict__ wb, int H, int L, int Lq, int Lp,
-                                                    int G, float eps, float* __restrict__ bias) {
-    const int lig = threadIdx.x & (G - 1);
-    const int chunks = c >> 3;
-    const bool has = lig < chunks;
-    float wg[HMAX][8];      // w_b * gamma for this lane's 8 channels
-    float cst[HMAX];        // sum_c beta_c * w_b[h][c]
-#pragma unroll
-    for (int h = 0; h < HMAX; ++h) {
-        cst[h] = 0.f;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) wg[h][j] = 0.f;
-    }
-    if (has) {
-        const uint4 gr = ldg16(gam + lig * 8), br = ldg16(bet + lig * 8);
-        const uint32_t gw[4] = {gr.x, gr.y, gr.z, gr.w}, bw[4] = {br.x, br.y, br.z, br.w};
-#pragma unroll
-        for (int h = 0; h < HMAX; ++h) {
-            if (h < H) {
-                const uint4 wr = ldg16(wb + (size_t)h * c + lig * 8);
-                const uint32_t ww[4] = {wr.x, wr.y, wr.z, wr.w};
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    wg[h][2 * i] = lo_f32(ww[i]) * lo_f32(gw[i]);
-                    wg[h][2 * i + 1] = hi_f32(ww[i]) * hi_f32(gw[i]);
-                    cst[h] += lo_f32(ww[i]) * lo_f32(bw[i]) + hi_f32(ww[i]) * hi_f32(bw[i]);
-                }
-            }
-        }
-    }
-#pragma unroll
-    for (int h = 0; h < HMAX; ++h)
-        for (int o = G >> 1; o > 0; o >>= 1) cst[h] += __shfl_xor(cst[h], o, 64);
+// Weight preparation: one wavefront per output row n of the merged matrix.
+//   wp[n][k] = bf16(scale * W[n][k] * gamma[k]);  sn[n] = sum_k wp[n][k];
+//   cn[n] = scale * sum_k W[n][k] * beta[k] (+ extra[n])
+struct PrepSeg {
+    const bf16_t* w;        // [rows][K]
+    const bf16_t* extra;    // [rows] added to cn, or NULL
+    int rows, rows_pad;     // rows_pad - rows zero rows follow
+    float scale;
+};
+struct PrepArgs {
+    PrepSeg seg[5];
+    int nseg, K;
+    const bf16_t *gamma, *beta;
+    bf16_t* wp;
+    float *sn, *cn;
+};
 
-    const int groups = 256 / G;
-    const int64_t pairs = (int64_t)L * L;
-    const float inv_c = 1.f / (float)c;
-    for (int64_t pr = (int64_t)blockIdx.x * groups + threadIdx.x / G; pr < pairs; pr += (int64_t)gridDim.x * groups) {
-        const int q = (int)(pr / L), k = (int)(pr - (int64_t)q * L);
-        float v[8];
-        float s = 0.f;
-        if (has) {
-            const uint4 r = ldg16(src + ((int64_t)q * sq + (int64_t)k * sk) * c + lig * 8);
-            const uint32_t rw[4] = {r.x, r.y, r.z, r.w};
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                v[2 * i] = lo_f32(rw[i]);
-                v[2 * i + 1] = hi_f32(rw[i]);
-            }
-#pragma unroll
-            for (int j = 0; j < 8; ++j) s += v[j];
-        } else {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) v[j] = 0.f;
+__global__ __launch_bounds__(256) void k_prep(PrepArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+    int base = 0, sg = -1, local = 0;
+    for (int i = 0; i < a.nseg; ++i) {
+        if (sg < 0 && n < base + a.seg[i].rows_pad) {
+            sg = i;
+            local = n - base;
         }
-        for (int o = G >> 1; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-        const float mean = s * inv_c;
-        float qq = 0.f;
-        if (has) {
+        base += a.seg[i].rows_pad;
+    }
+    if (sg < 0) return;
+    const bf16_t* wsrc = nullptr;
+    const bf16_t* extra = nullptr;
+    int rows = 0;
+    float scale = 0.f;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                v[j] -= mean;
-                qq += v[j] * v[j];
-            }
+    for (int i = 0; i < 5; ++i)
+        if (i == sg) {
+            wsrc = a.seg[i].w;
+            extra = a.seg[i].extra;
+            rows = a.seg[i].rows;
+            scale = a.seg[i].scale;
         }
-        for (int o = G >> 1; o > 0; o >>= 1) qq += __shfl_xor(qq, o, 64);
-        const float rstd = rsqrtf(qq * inv_c + eps);
-        float mine = 0.f;
-#pragma unroll
-        for (int h = 0; h < HMAX; ++h) {
-            if (h < H) {
-                float a = 0.f;
-#pragma unroll
-                for (int j = 0; j < 8; ++j) a += v[j] * wg[h][j];
-                for (int o = G >> 1; o > 0; o >>= 1) a += __shfl_xor(a, o, 64);
-                if (lig == (h & (G - 1))) mine = (a * rstd + cst[h]) * kLog2e;
-                if (G < HMAX && lig == (h & (G - 1)))   // fewer lanes than heads: write at once
-                    bias[((size_t)h * Lq + q) * Lp + k] = mine;
-            }
+    const bool real = local < rows;
+    float sum = 0.f, cst = 0.f;
+    for (int k = lane; k < a.K; k += 64) {
+        float r = 0.f;
+        if (real) {
+            const float wv = bf16_to_f32(wsrc[(size_t)local * a.K + k]) * scale;
+            r = bf16_round(wv * bf16_to_f32(a.gamma[k]));
+            cst += wv * bf16_to_f32(a.beta[k]);
         }
-        if (G >= HMAX && lig < H) bias[((size_t)lig * Lq + q) * Lp + k] = mine;
+        a.wp[(size_t)n * a.K + k] = f32_to_bf16(r);
+        sum += r;
+    }
+    sum = wave_sum(sum);
+    cst = wave_sum(cst);
+    if (lane == 0) {
+        a.sn[n] = sum;
+        a.cn[n] = cst + ((real && extra) ? bf16_to_f32(extra[local]) : 0.f);
     }
 }
 
 // ====================================================================================
-// GEMM with the whole contraction length (<= 256) resident: a wavefront owns 64 tokens
-// (two 32-token tiles) as register-resident operand fragments and sweeps over 32-feature
-// tiles of the weight matrix, which the block streams through LDS (double buffered).
+// GEMM with the whole contraction length (<= 256) resident: a wavefront owns 64 tokens (two
+// 32-token tiles) as register-resident operand fragments and sweeps over 32-feature tiles
+// of the weight matrix, which the block streams through LDS (double buffered).
 struct GemmArgs {
-    const bf16_t* src;     // PROJ: x (strided tokens); OUT: o [rows*Lp][K]
-    int64_t sr, sl;        // token strides of x / out
-    int r0, rows, L, Lp;
-    int K;                 // contraction length (c for PROJ, Hd for OUT)
-    const bf16_t *ln_g, *ln_b;
+    const bf16_t* src;     // PROJ: x or z (strided tokens); OUT: o [rows*Lp][K]
+    int64_t sr, sl;        // token strides of src (PROJ) / out (OUT)
+    int r0, rows, L, Lp, Lq;
+    int K;                 // contraction length
     float eps;
-    const bf16_t* w[4];    // PROJ: w_q, w_k, w_v, w_g, each [Hd][K]; OUT: w[0] = w_o [N][K]
-    const bf16_t* bvec;    // PROJ: b_g [Hd]; OUT: b_o [N]
+    const bf16_t* w;       // PROJ: prepared weights [tiles*32][K]; OUT: w_o [N][K]
+    const float *sn, *cn;  // PROJ: per-feature sums / offsets
+    const bf16_t* bvec;    // OUT: b_o [N]
     int Hd, H, D;
-    float qscale;
+    int nt_main;           // PROJ: 32-feature tiles of q|k|v|gate; tile nt_main is the pair-bias tile
     bf16_t *q, *k, *g, *vt;  // PROJ outputs
-    bf16_t* out;             // OUT output [n_a][n_b][N], token (r,l) at (r*sr + l*sl)*N
-    int N;                   // features in total (4*Hd or c)
-    int tiles_per_split;     // 32-feature tiles per blockIdx.y
+    float* bias;             // PROJ pair-bias output [H][Lq][Lp]
+    bf16_t* out;             // OUT output, token (r,l) at (r*sr + l*sl)*N
+    int N;                   // OUT: features
+    int ft_first, ft_count;  // range of feature tiles of this launch
+    int tiles_per_split;     // tiles per blockIdx.y
 };
 
-template <int KC, bool PROJ, int WAVES>
-__global__ __launch_bounds__(WAVES * 64) void k_gemm(GemmArgs a) {
-    constexpr int NT = WAVES * 64;
+template <int KC, bool PROJ>
+__global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
+    constexpr int NT = 256;
     constexpr int PITCH = KC * 32 + 16;                 // bytes per weight row in LDS (padded)
     __shared__ __attribute__((aligned(16))) unsigned char s_w[2][32 * PITCH];
-    __shared__ float s_g[PROJ ? KC * 16 : 1], s_b[PROJ ? KC * 16 : 1];
+    __shared__ __attribute__((aligned(16))) float s_stat[PROJ ? 4 * 2 * 2 * 32 : 4];   // [wave][tt][mean|rstd][32]
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, hf = lane >> 5;
     const int K = a.K;
     const int tiles_m = a.rows * (a.Lp >> 5);
 
-    if constexpr (PROJ) {
-        for (int i = tid; i < KC * 16; i += NT) {
-            s_g[i] = i < K ? bf16_to_f32(a.ln_g[i]) : 0.f;
-            s_b[i] = i < K ? bf16_to_f32(a.ln_b[i]) : 0.f;
-        }
-    }
-
     // ---- weight tile loader: 32 rows x 2*KC 16-byte pieces, consecutive threads along a row
     constexpr int PIECES = 32 * 2 * KC;
     constexpr int PER_THREAD = (PIECES + NT - 1) / NT;
-    const int ft_begin = blockIdx.y * a.tiles_per_split;
+    const int ft_begin = a.ft_first + blockIdx.y * a.tiles_per_split;
     int ft_end = ft_begin + a.tiles_per_split;
-    if (ft_end > a.N / 32) ft_end = a.N / 32;
+    if (ft_end > a.ft_first + a.ft_count) ft_end = a.ft_first + a.ft_count;
     uint4 wreg[PER_THREAD];
     auto load_w = [&](int ft) {
-        // first row of this 32-feature tile (a tile never straddles two weight matrices: Hd % 32 == 0)
-        const int sg = PROJ ? (ft * 32) / a.Hd : 0;
-        const bf16_t* wt = a.w[sg] + (size_t)(ft * 32 - sg * a.Hd) * K;
+        const bf16_t* wt = a.w + (size_t)ft * 32 * K;
 #pragma unroll
         for (int j = 0; j < PER_THREAD; ++j) {
             const int i = tid + j * NT;
@@ -275,15 +270,15 @@ __global__ __launch_bounds__(WAVES * 64) void k_gemm(GemmArgs a) {
         }
     };
     if (ft_begin < ft_end) load_w(ft_begin);
-    __syncthreads();   // s_g / s_b visible
 
-    // ---- token operand fragments (with LayerNorm for PROJ)
+    // ---- token operand fragments, raw
     Frag xa[2][KC];
     bool tile_ok[2];
     int tok[2];        // padded token index of this lane
+    float mean[2], rstd[2];
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
-        const int tg = (blockIdx.x * WAVES + wave) * 2 + tt;
+        const int tg = (blockIdx.x * 4 + wave) * 2 + tt;
         tile_ok[tt] = tg < tiles_m;
         const int p = tg * 32 + col;
         tok[tt] = p;
@@ -296,41 +291,39 @@ __global__ __launch_bounds__(WAVES * 64) void k_gemm(GemmArgs a) {
             xa[tt][s].u = make_uint4(0, 0, 0, 0);
             if (valid && (16 * s + 8 * hf) < K) xa[tt][s].u = ldg16(sp + 16 * s + 8 * hf);
         }
-        if constexpr (PROJ) {
+        mean[tt] = 0.f;
+        rstd[tt] = 0.f;
+    }
+    if constexpr (PROJ) {
+        // LayerNorm statistics of the raw rows: two passes over the registers, float32
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt) {
             float sum = 0.f;
 #pragma unroll
             for (int s = 0; s < KC; ++s)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) sum += lo_f32(xa[tt][s].w[i]) + hi_f32(xa[tt][s].w[i]);
+                for (int i = 0; i < 4; ++i) sum = add_pair(xa[tt][s].w[i], sum);
             sum += other_half(sum);
-            const float mean = sum / (float)K;
+            const float mu = sum / (float)K;
             float sq = 0.f;
 #pragma unroll
             for (int s = 0; s < KC; ++s) {
                 if (16 * s + 8 * hf < K) {
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        const float d0 = lo_f32(xa[tt][s].w[i]) - mean, d1 = hi_f32(xa[tt][s].w[i]) - mean;
+                        const float d0 = lo_f32(xa[tt][s].w[i]) - mu, d1 = hi_f32(xa[tt][s].w[i]) - mu;
                         sq += d0 * d0 + d1 * d1;
                     }
                 }
             }
             sq += other_half(sq);
-            const float rstd = rsqrtf(sq / (float)K + a.eps);
-#pragma unroll
-            for (int s = 0; s < KC; ++s) {
-                const int c0 = 16 * s + 8 * hf;
-                if (valid && c0 < K) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const float y0 = (lo_f32(xa[tt][s].w[i]) - mean) * rstd * s_g[c0 + 2 * i] + s_b[c0 + 2 * i];
-                        const float y1 =
-                            (hi_f32(xa[tt][s].w[i]) - mean) * rstd * s_g[c0 + 2 * i + 1] + s_b[c0 + 2 * i + 1];
-                        xa[tt][s].w[i] = pack2(y0, y1);
-                    }
-                } else {
-                    xa[tt][s].u = make_uint4(0, 0, 0, 0);
-                }
+            const int l = tok[tt] % a.Lp;
+            const bool valid = tile_ok[tt] && l < a.L;
+            mean[tt] = valid ? mu : 0.f;
+            rstd[tt] = valid ? rsqrtf(sq / (float)K + a.eps) : 0.f;
+            if (hf == 0) {
+                s_stat[((wave * 2 + tt) * 2 + 0) * 32 + col] = mean[tt];
+                s_stat[((wave * 2 + tt) * 2 + 1) * 32 + col] = rstd[tt];
             }
         }
     }
@@ -341,8 +334,9 @@ __global__ __launch_bounds__(WAVES * 64) void k_gemm(GemmArgs a) {
     for (int ft = ft_begin; ft < ft_end; ++ft) {
         const int buf = (ft - ft_begin) & 1;
         if (ft + 1 < ft_end) load_w(ft + 1);
-        const int seg = PROJ ? (ft * 32) / a.Hd : 0;           // 0 q, 1 k, 2 v, 3 gate
-        const bool tokens_by_features = PROJ && seg == 2;      // V: rows = tokens
+        // kind of this feature tile: 0 q, 1 k, 2 v, 3 gate, 4 pair bias
+        const int kind = PROJ ? (ft < a.nt_main ? (ft * 32) / a.Hd : 4) : 0;
+        const bool tokens_by_features = PROJ && kind == 2;      // V: rows = tokens
         f32x16 acc[2];
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt)
@@ -369,55 +363,85 @@ __global__ __launch_bounds__(WAVES * 64) void k_gemm(GemmArgs a) {
         }
 
         // ---- epilogue
+        if (tokens_by_features) {
+            // lane = feature (col), registers = tokens 8g + 4hf + e of the tile
+            const int nrow = ft * 32 + col;                     // row of the prepared matrix
+            const float sn = a.sn[nrow], cn = a.cn[nrow];
+            const int n = nrow - 2 * a.Hd;
+            const int h = n / a.D, e = n - h * a.D;
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
-            if (!tile_ok[tt]) continue;
-            if (tokens_by_features) {
-                // lane = feature (col), registers = tokens 8g + 4hf + e of the tile
-                const int n = ft * 32 + col - 2 * a.Hd;
-                const int h = n / a.D, e = n - h * a.D;
-                const int p0 = tok[tt] - col;                      // first token of the tile
+            for (int tt = 0; tt < 2; ++tt) {
+                if (!tile_ok[tt]) continue;
+                const int p0 = tok[tt] - col;                   // first token of the tile
                 const int rl = p0 / a.Lp, l0 = p0 - rl * a.Lp;
+                const float* st = s_stat + (wave * 2 + tt) * 64;
                 uint32_t pk[8];
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    pk[2 * g] = pack2(acc[tt][4 * g], acc[tt][4 * g + 1]);
-                    pk[2 * g + 1] = pack2(acc[tt][4 * g + 2], acc[tt][4 * g + 3]);
+                    const float4 mu = *reinterpret_cast<const float4*>(st + 8 * g + 4 * hf);
+                    const float4 rs = *reinterpret_cast<const float4*>(st + 32 + 8 * g + 4 * hf);
+                    const float y0 = rs.x * (acc[tt][4 * g] - mu.x * sn) + cn;
+                    const float y1 = rs.y * (acc[tt][4 * g + 1] - mu.y * sn) + cn;
+                    const float y2 = rs.z * (acc[tt][4 * g + 2] - mu.z * sn) + cn;
+                    const float y3 = rs.w * (acc[tt][4 * g + 3] - mu.w * sn) + cn;
+                    pk[2 * g] = pack2(y0, y1);
+                    pk[2 * g + 1] = pack2(y2, y3);
                 }
                 merge_halves(pk[0], pk[2]);
                 merge_halves(pk[1], pk[3]);
                 merge_halves(pk[4], pk[6]);
                 merge_halves(pk[5], pk[7]);
-                // lower half: tokens 0..7 (pk0,pk1,pk2,pk3 -> a0 a1 | b0 b1) ; see merge_halves
                 bf16_t* dst = a.vt + ((size_t)(rl * a.H + h) * a.D + e) * a.Lp + l0 + 8 * hf;
                 *reinterpret_cast<uint4*>(dst) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
                 *reinterpret_cast<uint4*>(dst + 16) = make_uint4(pk[4], pk[5], pk[6], pk[7]);
+            }
+        } else {
+            // lane = token (col), registers = features 8g + 4hf + e of the tile
+            const int nb = ft * 32;                              // first feature (row of w) of the tile
+            float sv[16], cv[16];
+            if constexpr (PROJ) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const float4 s4 = *reinterpret_cast<const float4*>(a.sn + nb + 8 * g + 4 * hf);
+                    const float4 c4 = *reinterpret_cast<const float4*>(a.cn + nb + 8 * g + 4 * hf);
+                    sv[4 * g] = s4.x; sv[4 * g + 1] = s4.y; sv[4 * g + 2] = s4.z; sv[4 * g + 3] = s4.w;
+                    cv[4 * g] = c4.x; cv[4 * g + 1] = c4.y; cv[4 * g + 2] = c4.z; cv[4 * g + 3] = c4.w;
+                }
             } else {
-                // lane = token (col), registers = features 8g + 4hf + e of the tile
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const uint2 r = ldg8(a.bvec + nb + 8 * g + 4 * hf);
+                    cv[4 * g] = lo_f32(r.x); cv[4 * g + 1] = hi_f32(r.x);
+                    cv[4 * g + 2] = lo_f32(r.y); cv[4 * g + 3] = hi_f32(r.y);
+                    sv[4 * g] = sv[4 * g + 1] = sv[4 * g + 2] = sv[4 * g + 3] = 0.f;
+                }
+            }
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt) {
+                if (!tile_ok[tt]) continue;
                 const int p = tok[tt];
                 const int rl = p / a.Lp, l = p - rl * a.Lp;
-                const int nb = ft * 32;                            // first feature of the tile
-                float bv[16];
-                if (!PROJ || seg == 3) {
-                    const bf16_t* bp = a.bvec + (PROJ ? nb - 3 * a.Hd : nb);
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const uint2 r = ldg8(bp + 8 * g + 4 * hf);
-                        bv[4 * g] = lo_f32(r.x); bv[4 * g + 1] = hi_f32(r.x);
-                        bv[4 * g + 2] = lo_f32(r.y); bv[4 * g + 3] = hi_f32(r.y);
-                    }
-                }
                 float val[16];
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    float t = acc[tt][v];
-                    if (PROJ) {
-                        if (seg == 0) t *= a.qscale;
-                        if (seg == 3) t = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-(t + bv[v]) * kLog2e));
+                    float t;
+                    if constexpr (PROJ) {
+                        t = rstd[tt] * (acc[tt][v] - mean[tt] * sv[v]) + cv[v];
+                        if (kind == 3) t = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-t * kLog2e));
                     } else {
-                        t += bv[v];
+                        t = acc[tt][v] + cv[v];
                     }
                     val[v] = t;
+                }
+                if (PROJ && kind == 4) {
+                    // pair bias: feature = head, token (rl, l) = pair (q, k)
+                    const size_t qk = (size_t)(a.r0 + rl) * a.Lp + l;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int h = 8 * (v >> 2) + 4 * hf + (v & 3);
+                        if (h < a.H) a.bias[(size_t)h * a.Lq * a.Lp + qk] = val[v];
+                    }
+                    continue;
                 }
                 uint32_t pk[8];
 #pragma unroll
@@ -429,14 +453,14 @@ __global__ __launch_bounds__(WAVES * 64) void k_gemm(GemmArgs a) {
                 merge_halves(pk[1], pk[3]);
                 merge_halves(pk[4], pk[6]);
                 merge_halves(pk[5], pk[7]);
-                if (l < a.L) {
-                    bf16_t* dst;
-                    if (PROJ) {
-                        bf16_t* base = seg == 0 ? a.q : (seg == 1 ? a.k : a.g);
-                        dst = base + (size_t)p * a.Hd + (nb - seg * a.Hd);
-                    } else {
-                        dst = a.out + ((int64_t)(a.r0 + rl) * a.sr + (int64_t)l * a.sl) * a.N + nb;
-                    }
+                bf16_t* dst = nullptr;
+                if constexpr (PROJ) {
+                    bf16_t* base = kind == 0 ? a.q : (kind == 1 ? a.k : a.g);
+                    dst = base + (size_t)p * a.Hd + (nb - kind * a.Hd);
+                } else if (l < a.L) {
+                    dst = a.out + ((int64_t)(a.r0 + rl) * a.sr + (int64_t)l * a.sl) * a.N + nb;
+                }
+                if (dst) {
                     *reinterpret_cast<uint4*>(dst + 8 * hf) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
                     *reinterpret_cast<uint4*>(dst + 16 + 8 * hf) = make_uint4(pk[4], pk[5], pk[6], pk[7]);
                 }
@@ -450,7 +474,15 @@ __global__ __launch_bounds__(WAVES * 64) void k_gemm(GemmArgs a) {
 // ====================================================================================
 // Attention.  Block = 4 wavefronts = 4 batch rows, same head, same 64 queries: the bias
 // tile [64 queries x 32 keys] is staged once per block in LDS and used by all four rows;
-// K rows and V^T columns go straight from global memory into operand registers.
+// K rows and V^T columns go straight from global memory into operand registers, one tile
+// ahead of their use.
+//
+// The q.k contraction has two extra slots.  Slot A multiplies 1 (key side) with -m_ref
+// (query side): the matrix core returns s - m_ref, m_ref being a per-query reference close
+// to the running maximum that is raised only when a tile exceeds it by more than kRaise
+// (then the accumulators are rescaled).  Slot B multiplies the mask term of the key (0 or
+// -inf) with 1.  For head dims below 32 a row of ones in V^T makes the matrix core
+// accumulate the softmax denominator as well.
 struct AttnArgs {
     const bf16_t *q, *k, *g, *vt;
     bf16_t* o;
@@ -461,13 +493,17 @@ struct AttnArgs {
 };
 
 constexpr int kBiasPitch = 36;   // floats per LDS bias row (32 + 4 pad)
+constexpr float kRaise = 10.f;   // log2 units
 
 template <int D, bool HAS_BIAS>
 __global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
-    constexpr int KS = (D + 15) / 16;   // 16-wide steps of the q.k contraction
+    constexpr int PCX = D / 8;              // index of the 8-slot piece holding the two extra slots
+    constexpr int KS = PCX / 2 + 1;         // 16-wide contraction steps
+    constexpr int SX = PCX / 2, HX = PCX % 2;
+    constexpr bool ONES_ROW = D < 32;       // V^T row D is all ones: O^T row D = softmax denominator
+    constexpr int LV = ONES_ROW ? 4 * (D / 8) : 0;   // its accumulator register (in the lower half-wave)
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     float* s_bias = reinterpret_cast<float*>(smem);                                  // [2][64][kBiasPitch]
-    uint32_t* s_mask = reinterpret_cast<uint32_t*>(smem + (HAS_BIAS ? 2 * 64 * kBiasPitch * 4 : 0));  // [4][Lp/32]
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, hf = lane >> 5;
     const int nt = a.Lp >> 5;
@@ -476,21 +512,7 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
     const int rl = row_ok ? rl_raw : a.rows - 1;
     const int h = blockIdx.y;
     const int q0 = blockIdx.x * 64;
-
-    // ---- key-validity bits of this wave's batch row, one word per 32-key tile
-    {
-        const float* mrow = a.mask ? a.mask + (int64_t)(a.r0 + rl) * a.sr : nullptr;
-        for (int t = 0; t < nt; t += 2) {
-            const int key = 32 * t + lane;
-            bool valid = key < a.L;
-            if (valid && mrow) valid = mrow[(int64_t)key * a.sl] != 0.f;
-            const unsigned long long b = __ballot(valid);
-            if (lane == 0) {
-                s_mask[wave * nt + t] = (uint32_t)b;
-                if (t + 1 < nt) s_mask[wave * nt + t + 1] = (uint32_t)(b >> 32);
-            }
-        }
-    }
+    const bool xlane = hf == HX;            // this lane carries the extra slots in step SX
 
     // ---- Q operand fragments: B operand, lane = query, 8 consecutive e
     Frag qf[2][KS];
@@ -502,67 +524,85 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             qf[j][s].u = make_uint4(0, 0, 0, 0);
-            if (16 * s + 8 * hf < D) qf[j][s].u = ldg16(qp + 16 * s + 8 * hf);
+            if (2 * s + hf < PCX) qf[j][s].u = ldg16(qp + 16 * s + 8 * hf);
         }
+        if (xlane) qf[j][SX].w[0] = 0x3f800000u;        // (-m_ref = 0, 1.0)
     }
 
-    // ---- bias tile pipeline
-    const int b_row = tid >> 3, b_c4 = tid & 7;     // thread loads rows b_row, b_row+32; floats 4*b_c4..+3
-    const float* bias_h = HAS_BIAS ? a.bias + ((size_t)h * a.Lq + q0) * a.Lp : nullptr;
-    float4 breg[2];
-    auto load_bias = [&](int kt) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-            breg[i] = *reinterpret_cast<const float4*>(bias_h + (size_t)(b_row + 32 * i) * a.Lp + 32 * kt + 4 * b_c4);
-    };
-    auto store_bias = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-            *reinterpret_cast<float4*>(s_bias + ((size_t)buf * 64 + b_row + 32 * i) * kBiasPitch + 4 * b_c4) = breg[i];
-    };
+    // ---- bias tile pipeline: thread loads rows b_row, b_row+32; floats 4*b_c4 .. +3
+    const int b_row = tid >> 3, b_c4 = tid & 7;
+    const float* bias_t = HAS_BIAS ? a.bias + ((size_t)h * a.Lq + q0 + b_row) * a.Lp + 4 * b_c4 : nullptr;
+    float* s_bias_t = s_bias + (size_t)b_row * kBiasPitch + 4 * b_c4;
+    float4 breg0, breg1;
     if constexpr (HAS_BIAS) {
-        load_bias(0);
-        store_bias(0);
+        breg0 = *reinterpret_cast<const float4*>(bias_t);
+        breg1 = *reinterpret_cast<const float4*>(bias_t + (size_t)32 * a.Lp);
+        *reinterpret_cast<float4*>(s_bias_t) = breg0;
+        *reinterpret_cast<float4*>(s_bias_t + 32 * kBiasPitch) = breg1;
     }
-    __syncthreads();
 
     // permuted key of S^T row m = col: rows 8g + 4b + e hold key 16*(g/2) + 8b + 4*(g%2) + e
     const int kperm = 16 * (col >> 4) + 8 * ((col >> 2) & 1) + 4 * ((col >> 3) & 1) + (col & 3);
-    const bf16_t* kbase = a.k + (size_t)rl * a.Lp * a.Hd + h * D;
-    const bf16_t* vbase = a.vt + ((size_t)(rl * a.H + h) * D + (col < D ? col : 0)) * a.Lp;
+    const bf16_t* kp = a.k + ((size_t)rl * a.Lp + kperm) * a.Hd + h * D + 8 * hf;
+    const bf16_t* vp = a.vt + ((size_t)(rl * a.H + h) * D + (col < D ? col : 0)) * a.Lp + 8 * hf;
+    const size_t kstep = (size_t)32 * a.Hd;
+    const float* mp = a.mask ? a.mask + (int64_t)(a.r0 + rl) * a.sr : nullptr;
+    const bool ones_lane = ONES_ROW && col == D;
+
+    // K fragments (A operand, lane = permuted key, 8 consecutive e), V^T fragments (A operand,
+    // lane = e, 8 consecutive keys) and the key's mask value, fetched one tile ahead.
+    Frag kf_n[KS], vf_n[2];
+    float mv_n;
+    auto fetch = [&](int kt) {
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            kf_n[s].u = make_uint4(0, 0, 0, 0);
+            if (2 * s + hf < PCX) kf_n[s].u = ldg16(kp + kt * kstep + 16 * s);
+        }
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            vf_n[c].u = make_uint4(0, 0, 0, 0);
+            if (col < D) vf_n[c].u = ldg16(vp + 32 * kt + 16 * c);
+            if (ones_lane) vf_n[c].u = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
+        }
+        const int key = 32 * kt + kperm;
+        mv_n = 1.f;
+        if (mp) mv_n = mp[(int64_t)(key < a.L ? key : a.L - 1) * a.sl];
+        if (key >= a.L) mv_n = 0.f;
+    };
+    fetch(0);
+    __syncthreads();
 
     f32x16 o_acc[2];
-    float m_run[2], l_run[2];
+    float m_ref[2], l_run[2];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-        m_run[j] = -INFINITY;
+        m_ref[j] = 0.f;
         l_run[j] = 0.f;
 #pragma unroll
         for (int v = 0; v < 16; ++v) o_acc[j][v] = 0.f;
     }
+    bool first = true;
 
     for (int kt = 0; kt < nt; ++kt) {
         const int buf = kt & 1;
-        if constexpr (HAS_BIAS)
-            if (kt + 1 < nt) load_bias(kt + 1);
-        const uint32_t bits = __builtin_amdgcn_readfirstlane(s_mask[wave * nt + kt]);
-        if (bits != 0u) {
-            // K fragments: A operand, lane = (permuted) key, 8 consecutive e
-            Frag kf[KS];
-            const bf16_t* kp = kbase + (size_t)(32 * kt + kperm) * a.Hd;
+        Frag kf[KS], vf[2];
 #pragma unroll
-            for (int s = 0; s < KS; ++s) {
-                kf[s].u = make_uint4(0, 0, 0, 0);
-                if (16 * s + 8 * hf < D) kf[s].u = ldg16(kp + 16 * s + 8 * hf);
-            }
-            // V^T fragments: A operand, lane = e, 8 consecutive (permuted = natural) keys
-            Frag vf[2];
+        for (int s = 0; s < KS; ++s) kf[s] = kf_n[s];
 #pragma unroll
-            for (int c = 0; c < 2; ++c) {
-                vf[c].u = make_uint4(0, 0, 0, 0);
-                if (col < D) vf[c].u = ldg16(vbase + 32 * kt + 16 * c + 8 * hf);
+        for (int c = 0; c < 2; ++c) vf[c] = vf_n[c];
+        const bool key_valid = mv_n != 0.f;
+        if (xlane) kf[SX].w[0] = key_valid ? 0x00003f80u : 0xff803f80u;   // (1.0, mask term)
+        if (kt + 1 < nt) {
+            fetch(kt + 1);
+            if constexpr (HAS_BIAS) {
+                breg0 = *reinterpret_cast<const float4*>(bias_t + 32 * (kt + 1));
+                breg1 = *reinterpret_cast<const float4*>(bias_t + (size_t)32 * a.Lp + 32 * (kt + 1));
             }
+        }
+        if (__any(key_valid)) {
             f32x16 s_acc[2];
+            float tmax[2];
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 if constexpr (HAS_BIAS) {
@@ -582,38 +622,39 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
 #pragma unroll
                 for (int s = 0; s < KS; ++s)
                     s_acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s].v, qf[j][s].v, s_acc[j], 0, 0, 0);
+                float t = s_acc[j][0];
+#pragma unroll
+                for (int v = 1; v < 16; ++v) t = fmaxf(t, s_acc[j][v]);
+                tmax[j] = fmaxf(t, other_half(t));
             }
-            if (bits != 0xffffffffu) {
-                // register v of this lane holds key 16*(v/8) + 8*hf + v%8 of the tile
-                const uint32_t mine = bits >> (8 * hf);
+            // s_acc holds s - m_ref (masked keys: -inf).  Raise the reference where needed.
+            if (first || __any(tmax[0] > kRaise || tmax[1] > kRaise)) {
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
+                for (int j = 0; j < 2; ++j) {
+                    const bool raise = first || tmax[j] > kRaise;
+                    const float new_ref = raise ? bf16_round(m_ref[j] + tmax[j]) : m_ref[j];
+                    const float delta = new_ref - m_ref[j];
+                    m_ref[j] = new_ref;
+                    const float sc = first ? 1.f : __builtin_amdgcn_exp2f(-delta);   // nothing accumulated yet
 #pragma unroll
-                    for (int v = 0; v < 16; ++v)
-                        if (!((mine >> (16 * (v >> 3) + (v & 7))) & 1u)) s_acc[j][v] = -INFINITY;
+                    for (int v = 0; v < 16; ++v) {
+                        o_acc[j][v] *= sc;
+                        s_acc[j][v] -= delta;
+                    }
+                    l_run[j] *= sc;
+                    if (xlane) qf[j][SX].w[0] = pack2(-new_ref, 1.f);
+                }
+                first = false;
             }
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
-                float tmax = s_acc[j][0];
-#pragma unroll
-                for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, s_acc[j][v]);
-                tmax = fmaxf(tmax, other_half(tmax));
-                const float m_new = fmaxf(m_run[j], tmax);
-                const float m_use = m_new == -INFINITY ? 0.f : m_new;
-                const float alpha = __builtin_amdgcn_exp2f(m_run[j] - m_use);
-                m_run[j] = m_new;
                 float psum = 0.f;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const float pv = __builtin_amdgcn_exp2f(s_acc[j][v] - m_use);
-                    s_acc[j][v] = pv;
-                    psum += pv;
+                    s_acc[j][v] = __builtin_amdgcn_exp2f(s_acc[j][v]);
+                    if constexpr (!ONES_ROW) psum += s_acc[j][v];
                 }
-                l_run[j] = l_run[j] * alpha + psum;
-                if (__any(alpha != 1.f)) {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) o_acc[j][v] *= alpha;
-                }
+                if constexpr (!ONES_ROW) l_run[j] += psum;
                 Frag pf[2];
 #pragma unroll
                 for (int c = 0; c < 2; ++c)
@@ -625,7 +666,10 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
             }
         }
         if constexpr (HAS_BIAS) {
-            if (kt + 1 < nt) store_bias(buf ^ 1);
+            if (kt + 1 < nt) {
+                *reinterpret_cast<float4*>(s_bias_t + (size_t)(buf ^ 1) * 64 * kBiasPitch) = breg0;
+                *reinterpret_cast<float4*>(s_bias_t + (size_t)(buf ^ 1) * 64 * kBiasPitch + 32 * kBiasPitch) = breg1;
+            }
             __syncthreads();
         }
     }
@@ -633,7 +677,14 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
     // ---- epilogue: normalise, gate, store.  o_acc[j]: lane = query, register v = e = 8*(v/4) + 4*hf + v%4
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-        const float l_tot = l_run[j] + other_half(l_run[j]);
+        float l_tot;
+        if constexpr (ONES_ROW) {
+            const float mine = o_acc[j][LV];
+            const float oth = other_half(mine);
+            l_tot = hf ? oth : mine;
+        } else {
+            l_tot = l_run[j] + other_half(l_run[j]);
+        }
         const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
         const int qi = q0 + 32 * j + col;
         if (row_ok && qi < a.L) {
@@ -655,65 +706,92 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
 
 // ====================================================================================
 // host side
-ff_status mfma_bias(const Problem& p, const ff_attn_weights& w, const void* x, const void* z, const Workspace& ws,
-                    hipStream_t st) {
-    const int Lp = round_up(p.L, 32), Lq = round_up(p.L, 64);
-    const bool row = p.mode == FF_MSA_ROW;
-    const int c = row ? p.c_z : p.c;
-    if (p.H > 8 || c > 512 || c % 8 != 0) return generic_bias_into(p, w, x, z, ws.bias, Lq, Lp, st);
-    int G = 4;
-    while (G * 8 < c) G <<= 1;
-    const int groups = 256 / G;
-    const int64_t pairs = (int64_t)p.L * p.L;
-    int64_t blocks = (pairs + groups - 1) / groups;
-    if (blocks > 256 * 32) blocks = 256 * 32;
-    const bf16_t* src = (const bf16_t*)(row ? z : x);
-    const int64_t sq = row ? p.L : p.sr, sk = row ? 1 : p.sl;
-    const bf16_t* g = (const bf16_t*)(row ? w.lnz_g : w.ln_g);
-    const bf16_t* b = (const bf16_t*)(row ? w.lnz_b : w.ln_b);
-    if (p.H <= 4)
-        hipLaunchKernelGGL((k_pair_bias<4>), dim3((unsigned)blocks), dim3(256), 0, st, src, sq, sk, c, g, b,
-                           (const bf16_t*)w.w_b, p.H, p.L, Lq, Lp, G, p.eps, ws.bias);
-    else
-        hipLaunchKernelGGL((k_pair_bias<8>), dim3((unsigned)blocks), dim3(256), 0, st, src, sq, sk, c, g, b,
-                           (const bf16_t*)w.w_b, p.H, p.L, Lq, Lp, G, p.eps, ws.bias);
-    return check_launch("pair bias");
-}
-
 template <bool PROJ>
 static void launch_gemm(const GemmArgs& a, int K, dim3 grid, hipStream_t st) {
     const int kc = K / 16;
-    if (kc <= 2) hipLaunchKernelGGL((k_gemm<2, PROJ, 4>), grid, dim3(256), 0, st, a);
-    else if (kc <= 4) hipLaunchKernelGGL((k_gemm<4, PROJ, 4>), grid, dim3(256), 0, st, a);
-    else if (kc <= 8) hipLaunchKernelGGL((k_gemm<8, PROJ, 4>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((k_gemm<16, PROJ, 4>), grid, dim3(256), 0, st, a);
+    if (kc <= 2) hipLaunchKernelGGL((k_gemm<2, PROJ>), grid, dim3(256), 0, st, a);
+    else if (kc <= 4) hipLaunchKernelGGL((k_gemm<4, PROJ>), grid, dim3(256), 0, st, a);
+    else if (kc <= 8) hipLaunchKernelGGL((k_gemm<8, PROJ>), grid, dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((k_gemm<16, PROJ>), grid, dim3(256), 0, st, a);
 }
 
+// blocks along the feature axis: enough blocks to fill 256 CUs about twice
 static int pick_split(int blocks_m, int tiles_n) {
-    // enough blocks to fill 256 CUs twice, without recomputing the LayerNorm prologue too often
     int split = 1;
-    while (blocks_m * split < 512 && split * 2 <= tiles_n && tiles_n % (split * 2) == 0 && split < 4) split *= 2;
+    while (blocks_m * split < 512 && split < tiles_n) ++split;
+    while (tiles_n % split != 0) ++split;      // equal shares
     return split;
+}
+
+static GemmArgs proj_args(const Problem& p, const MfmaWs& m, const Workspace& ws) {
+    const int Lp = round_up(p.L, 32), Lq = round_up(p.L, 64);
+    GemmArgs g{};
+    g.sr = p.sr; g.sl = p.sl; g.L = p.L; g.Lp = Lp; g.Lq = Lq; g.K = p.c; g.eps = p.eps;
+    g.w = m.wp; g.sn = m.sn; g.cn = m.cn; g.Hd = p.Hd; g.H = p.H; g.D = p.d;
+    g.nt_main = 4 * p.Hd / 32;
+    g.q = m.q; g.k = m.k; g.g = m.g; g.vt = m.vt; g.bias = ws.bias;
+    return g;
+}
+
+ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x, const void* z, const Workspace& ws,
+                       hipStream_t st) {
+    const MfmaWs m = split_ws(p, ws.chunk, ws);
+    const int Lp = round_up(p.L, 32), Lq = round_up(p.L, 64);
+    const float qscale = kLog2e / sqrtf((float)p.d);
+    const bool tri = p.mode == FF_TRI_START || p.mode == FF_TRI_END;
+    {
+        PrepArgs a{};
+        a.seg[0] = {(const bf16_t*)w.w_q, nullptr, p.Hd, p.Hd, qscale};
+        a.seg[1] = {(const bf16_t*)w.w_k, nullptr, p.Hd, p.Hd, 1.f};
+        a.seg[2] = {(const bf16_t*)w.w_v, nullptr, p.Hd, p.Hd, 1.f};
+        a.seg[3] = {(const bf16_t*)w.w_g, (const bf16_t*)w.b_g, p.Hd, p.Hd, 1.f};
+        a.seg[4] = {tri ? (const bf16_t*)w.w_b : nullptr, nullptr, tri ? p.H : 0, 32, kLog2e};
+        a.nseg = 5; a.K = p.c; a.gamma = (const bf16_t*)w.ln_g; a.beta = (const bf16_t*)w.ln_b;
+        a.wp = m.wp; a.sn = m.sn; a.cn = m.cn;
+        const int rows = 4 * p.Hd + 32;
+        hipLaunchKernelGGL(k_prep, dim3((rows + 3) / 4), dim3(256), 0, st, a);
+    }
+    if (p.mode == FF_MSA_ROW) {
+        const int off = 4 * p.Hd + 32;
+        PrepArgs a{};
+        a.seg[0] = {(const bf16_t*)w.w_b, nullptr, p.H, 32, kLog2e};
+        a.nseg = 1; a.K = p.c_z; a.gamma = (const bf16_t*)w.lnz_g; a.beta = (const bf16_t*)w.lnz_b;
+        a.wp = m.zwp; a.sn = m.sn + off; a.cn = m.cn + off;
+        hipLaunchKernelGGL(k_prep, dim3(8), dim3(256), 0, st, a);
+        // bias[h][i][j] from the pair representation: "batch rows" i, tokens j
+        GemmArgs g{};
+        g.src = (const bf16_t*)z; g.sr = p.L; g.sl = 1; g.r0 = 0; g.rows = p.L; g.L = p.L; g.Lp = Lp; g.Lq = Lq;
+        g.K = p.c_z; g.eps = p.eps; g.w = m.zwp; g.sn = m.sn + off; g.cn = m.cn + off;
+        g.Hd = p.Hd; g.H = p.H; g.D = p.d; g.nt_main = 0; g.bias = ws.bias;
+        g.ft_first = 0; g.ft_count = 1; g.tiles_per_split = 1;
+        const int blocks_m = (p.L * (Lp / 32) + 7) / 8;
+        launch_gemm<true>(g, p.c_z, dim3(blocks_m, 1), st);
+    } else if (tri && ws.chunk < p.R) {
+        // chunked triangle attention: the bias of all rows is needed before the first chunk
+        GemmArgs g = proj_args(p, m, ws);
+        g.src = (const bf16_t*)x; g.r0 = 0; g.rows = p.R;
+        g.ft_first = g.nt_main; g.ft_count = 1; g.tiles_per_split = 1;
+        const int blocks_m = (p.R * (Lp / 32) + 7) / 8;
+        launch_gemm<true>(g, p.c, dim3(blocks_m, 1), st);
+    }
+    return check_launch("prepare (mfma)");
 }
 
 ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, const float* mask, void* out,
                      const Workspace& ws, int r0, int rows, hipStream_t st) {
     const int Lp = round_up(p.L, 32), Lq = round_up(p.L, 64);
-    MfmaWs m = split_ws(p, ws.chunk, ws);
-
+    const MfmaWs m = split_ws(p, ws.chunk, ws);
+    const bool tri = p.mode == FF_TRI_START || p.mode == FF_TRI_END;
     const int tiles_m = rows * (Lp / 32);
     const int blocks_m = (tiles_m + 7) / 8;           // 4 waves x 2 token tiles
-    GemmArgs g{};
-    g.src = (const bf16_t*)x; g.sr = p.sr; g.sl = p.sl; g.r0 = r0; g.rows = rows; g.L = p.L; g.Lp = Lp;
-    g.K = p.c; g.ln_g = (const bf16_t*)w.ln_g; g.ln_b = (const bf16_t*)w.ln_b; g.eps = p.eps;
-    g.w[0] = (const bf16_t*)w.w_q; g.w[1] = (const bf16_t*)w.w_k; g.w[2] = (const bf16_t*)w.w_v;
-    g.w[3] = (const bf16_t*)w.w_g; g.bvec = (const bf16_t*)w.b_g;
-    g.Hd = p.Hd; g.H = p.H; g.D = p.d; g.qscale = kLog2e / sqrtf((float)p.d);
-    g.q = m.q; g.k = m.k; g.g = m.g; g.vt = m.vt; g.N = 4 * p.Hd;
     {
-        const int tiles_n = g.N / 32;
-        const int split = pick_split(blocks_m, tiles_n);
-        g.tiles_per_split = tiles_n / split;
+        GemmArgs g = proj_args(p, m, ws);
+        g.src = (const bf16_t*)x; g.r0 = r0; g.rows = rows;
+        // one chunk covering every row: the pair-bias tile rides along with the projections
+        const bool fused_bias = tri && ws.chunk >= p.R;
+        const int split = pick_split(blocks_m, g.nt_main);
+        g.ft_first = 0; g.ft_count = g.nt_main + (fused_bias ? 1 : 0);
+        g.tiles_per_split = (g.ft_count + split - 1) / split;
         launch_gemm<true>(g, p.c, dim3(blocks_m, split), st);
     }
 
@@ -722,12 +800,11 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
     a.sr = p.sr; a.sl = p.sl; a.r0 = r0; a.rows = rows; a.L = p.L; a.Lp = Lp; a.Lq = Lq; a.H = p.H; a.Hd = p.Hd;
     {
         dim3 grid(Lq / 64, p.H, (rows + 3) / 4);
-        const size_t mask_bytes = (size_t)4 * (Lp / 32) * 4;
         const size_t bias_bytes = (size_t)2 * 64 * kBiasPitch * 4;
-#define FF_ATTN(DD)                                                                                          \
-    do {                                                                                                     \
-        if (p.has_bias) hipLaunchKernelGGL((k_attn<DD, true>), grid, dim3(256), bias_bytes + mask_bytes, st, a); \
-        else hipLaunchKernelGGL((k_attn<DD, false>), grid, dim3(256), mask_bytes, st, a);                   \
+#define FF_ATTN(DD)                                                                                \
+    do {                                                                                           \
+        if (p.has_bias) hipLaunchKernelGGL((k_attn<DD, true>), grid, dim3(256), bias_bytes, st, a); \
+        else hipLaunchKernelGGL((k_attn<DD, false>), grid, dim3(256), 0, st, a);                   \
     } while (0)
         if (p.d == 8) FF_ATTN(8);
         else if (p.d == 16) FF_ATTN(16);
@@ -737,12 +814,13 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
     }
 
     GemmArgs o{};
-    o.src = m.o; o.sr = p.sr; o.sl = p.sl; o.r0 = r0; o.rows = rows; o.L = p.L; o.Lp = Lp;
-    o.K = p.Hd; o.w[0] = (const bf16_t*)w.w_o; o.bvec = (const bf16_t*)w.b_o;
+    o.src = m.o; o.sr = p.sr; o.sl = p.sl; o.r0 = r0; o.rows = rows; o.L = p.L; o.Lp = Lp; o.Lq = Lq;
+    o.K = p.Hd; o.w = (const bf16_t*)w.w_o; o.bvec = (const bf16_t*)w.b_o;
     o.Hd = p.Hd; o.H = p.H; o.D = p.d; o.out = (bf16_t*)out; o.N = p.c;
     {
         const int tiles_n = o.N / 32;
         const int split = pick_split(blocks_m, tiles_n);
+        o.ft_first = 0; o.ft_count = tiles_n;
         o.tiles_per_split = tiles_n / split;
         launch_gemm<false>(o, p.Hd, dim3(blocks_m, split), st);
     }
