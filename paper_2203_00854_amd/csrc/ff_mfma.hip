@@ -238,6 +238,8 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
     constexpr int PITCH = KC * 32 + 16;                 // bytes per weight row in LDS (padded)
     __shared__ __attribute__((aligned(16))) unsigned char s_w[2][32 * PITCH];
     __shared__ __attribute__((aligned(16))) float s_stat[PROJ ? 4 * 2 * 2 * 32 : 4];   // [wave][tt][mean|rstd][32]
+    constexpr int kMaxTiles = 33;                       // 4*Hd/32 + 1 with Hd <= 256
+    __shared__ __attribute__((aligned(16))) float s_sn[PROJ ? kMaxTiles * 32 : 4], s_cn[kMaxTiles * 32];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, hf = lane >> 5;
     const int K = a.K;
@@ -270,11 +272,20 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
         }
     };
     if (ft_begin < ft_end) load_w(ft_begin);
+    // per-feature sums / offsets of this block's tiles
+    for (int i = tid; i < (ft_end - ft_begin) * 32; i += NT) {
+        if constexpr (PROJ) {
+            s_sn[i] = a.sn[ft_begin * 32 + i];
+            s_cn[i] = a.cn[ft_begin * 32 + i];
+        } else {
+            s_cn[i] = bf16_to_f32(a.bvec[ft_begin * 32 + i]);
+        }
+    }
 
     // ---- token operand fragments, raw
     Frag xa[2][KC];
     bool tile_ok[2];
-    int tok[2];        // padded token index of this lane
+    int tok[2], tok_rl[2], tok_l[2];   // padded token index of this lane, its batch row and position
     float mean[2], rstd[2];
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
@@ -283,6 +294,8 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
         const int p = tg * 32 + col;
         tok[tt] = p;
         const int rl = p / a.Lp, l = p - rl * a.Lp;
+        tok_rl[tt] = rl;
+        tok_l[tt] = l;
         const bool valid = tile_ok[tt] && l < a.L;
         const bf16_t* sp = PROJ ? a.src + ((int64_t)(a.r0 + rl) * a.sr + (int64_t)l * a.sl) * K
                                 : a.src + (size_t)p * K;
@@ -317,8 +330,7 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
                 }
             }
             sq += other_half(sq);
-            const int l = tok[tt] % a.Lp;
-            const bool valid = tile_ok[tt] && l < a.L;
+            const bool valid = tile_ok[tt] && tok_l[tt] < a.L;
             mean[tt] = valid ? mu : 0.f;
             rstd[tt] = valid ? rsqrtf(sq / (float)K + a.eps) : 0.f;
             if (hf == 0) {
@@ -366,14 +378,13 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
         if (tokens_by_features) {
             // lane = feature (col), registers = tokens 8g + 4hf + e of the tile
             const int nrow = ft * 32 + col;                     // row of the prepared matrix
-            const float sn = a.sn[nrow], cn = a.cn[nrow];
+            const float sn = s_sn[(ft - ft_begin) * 32 + col], cn = s_cn[(ft - ft_begin) * 32 + col];
             const int n = nrow - 2 * a.Hd;
             const int h = n / a.D, e = n - h * a.D;
 #pragma unroll
             for (int tt = 0; tt < 2; ++tt) {
                 if (!tile_ok[tt]) continue;
-                const int p0 = tok[tt] - col;                   // first token of the tile
-                const int rl = p0 / a.Lp, l0 = p0 - rl * a.Lp;
+                const int rl = tok_rl[tt], l0 = tok_l[tt] - col;   // the tile lies inside one batch row
                 const float* st = s_stat + (wave * 2 + tt) * 64;
                 uint32_t pk[8];
 #pragma unroll
@@ -399,20 +410,15 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
             // lane = token (col), registers = features 8g + 4hf + e of the tile
             const int nb = ft * 32;                              // first feature (row of w) of the tile
             float sv[16], cv[16];
-            if constexpr (PROJ) {
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const float4 s4 = *reinterpret_cast<const float4*>(a.sn + nb + 8 * g + 4 * hf);
-                    const float4 c4 = *reinterpret_cast<const float4*>(a.cn + nb + 8 * g + 4 * hf);
+            for (int g = 0; g < 4; ++g) {
+                const int o = (ft - ft_begin) * 32 + 8 * g + 4 * hf;
+                const float4 c4 = *reinterpret_cast<const float4*>(s_cn + o);
+                cv[4 * g] = c4.x; cv[4 * g + 1] = c4.y; cv[4 * g + 2] = c4.z; cv[4 * g + 3] = c4.w;
+                if constexpr (PROJ) {
+                    const float4 s4 = *reinterpret_cast<const float4*>(s_sn + o);
                     sv[4 * g] = s4.x; sv[4 * g + 1] = s4.y; sv[4 * g + 2] = s4.z; sv[4 * g + 3] = s4.w;
-                    cv[4 * g] = c4.x; cv[4 * g + 1] = c4.y; cv[4 * g + 2] = c4.z; cv[4 * g + 3] = c4.w;
-                }
-            } else {
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const uint2 r = ldg8(a.bvec + nb + 8 * g + 4 * hf);
-                    cv[4 * g] = lo_f32(r.x); cv[4 * g + 1] = hi_f32(r.x);
-                    cv[4 * g + 2] = lo_f32(r.y); cv[4 * g + 3] = hi_f32(r.y);
+                } else {
                     sv[4 * g] = sv[4 * g + 1] = sv[4 * g + 2] = sv[4 * g + 3] = 0.f;
                 }
             }
@@ -420,7 +426,7 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
             for (int tt = 0; tt < 2; ++tt) {
                 if (!tile_ok[tt]) continue;
                 const int p = tok[tt];
-                const int rl = p / a.Lp, l = p - rl * a.Lp;
+                const int rl = tok_rl[tt], l = tok_l[tt];
                 float val[16];
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
@@ -563,12 +569,11 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
         for (int c = 0; c < 2; ++c) {
             vf_n[c].u = make_uint4(0, 0, 0, 0);
             if (col < D) vf_n[c].u = ldg16(vp + 32 * kt + 16 * c);
-            if (ones_lane) vf_n[c].u = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
         }
+        // nothing here may look at the loaded values: they are only waited for at their use
         const int key = 32 * kt + kperm;
         mv_n = 1.f;
         if (mp) mv_n = mp[(int64_t)(key < a.L ? key : a.L - 1) * a.sl];
-        if (key >= a.L) mv_n = 0.f;
     };
     fetch(0);
     __syncthreads();
@@ -590,8 +595,11 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
 #pragma unroll
         for (int s = 0; s < KS; ++s) kf[s] = kf_n[s];
 #pragma unroll
-        for (int c = 0; c < 2; ++c) vf[c] = vf_n[c];
-        const bool key_valid = mv_n != 0.f;
+        for (int c = 0; c < 2; ++c) {
+            vf[c] = vf_n[c];
+            if (ones_lane) vf[c].u = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
+        }
+        const bool key_valid = mv_n != 0.f && 32 * kt + kperm < a.L;
         if (xlane) kf[SX].w[0] = key_valid ? 0x00003f80u : 0xff803f80u;   // (1.0, mask term)
         if (kt + 1 < nt) {
             fetch(kt + 1);
