@@ -1,0 +1,236 @@
+#!/usr/bin/env python3
+"""Benchmark of the Evoformer gated-attention hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-others] [--no-cpu]
+
+One step = one pass of the whole hot path (LayerNorm, merged projections, pair bias,
+softmax(QK^T*scale + mask + bias) V, gate, output projection) over one synthetic input of the
+workload: one ff_gated_attention call (ff_attention_chunked for the chunked workload).
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+
+value = counted FLOP / time, counted FLOP = projections + bias projection + QK^T + PV +
+output projection (2*M*N*K each).  The default workload is the AlphaFold initial-training
+crop of the MSA row attention with pair bias (N_seq=128, N_res=256, c_m=256, H=8, d=32,
+bf16); the N_res=256 triangle modules and the N_res=2048 chunked triangle attention are
+timed as well and reported under "others".
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# published MI355X peaks used for the roofline fractions
+PEAK_MFMA_BF16_TFLOPS = 2500.0
+PEAK_HBM_GBS = 8000.0
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs (see profiles/); None until such a run has been summarised there.
+TRAFFIC_BYTES = {}
+
+
+def counted_flop(sp):
+    R, L = sp.batch_len
+    hd = sp.heads * sp.head_dim
+    f = {}
+    f["proj"] = 2.0 * R * L * sp.c * 4 * hd
+    if sp.mode == 0:
+        f["bias"] = 2.0 * L * L * sp.c_z * sp.heads
+    elif sp.mode in (2, 3):
+        f["bias"] = 2.0 * R * L * sp.c * sp.heads
+    else:
+        f["bias"] = 0.0
+    f["attn"] = 2 * 2.0 * R * sp.heads * L * L * sp.head_dim
+    f["out"] = 2.0 * R * L * hd * sp.c
+    f["total"] = sum(f.values())
+    return f
+
+
+def algorithmic_bytes(sp):
+    """Each operand once: x in, z in (row mode), out, weights."""
+    esz = 4 if sp.dtype == "f32" else 2
+    n = sp.n_a * sp.n_b * sp.c * esz
+    hd = sp.heads * sp.head_dim
+    w = (4 * hd * sp.c + hd * sp.c) * esz
+    z = sp.n_b * sp.n_b * sp.c_z * esz if sp.mode == 0 else 0
+    return 2 * n + z + w
+
+
+def time_workload(name, steps, warmup, copies=3, profile=True):
+    import torch
+    import paper_2203_00854_amd as P
+    from paper_2203_00854_amd import inputs as I
+
+    case = I.make_case(name)
+    sp = case.spec
+    desc, w, x, z, mask = P.to_device(case, "cuda:0")
+    chunk = sp.chunk_rows
+    big = x.numel() * x.element_size() > (1 << 29)
+    copies = 1 if big else copies
+    xs = [x] + [x.clone() for _ in range(copies - 1)]
+    zs = [z] + [z.clone() if z is not None else None for _ in range(copies - 1)]
+    outs = [torch.empty_like(x) for _ in range(copies)]
+    ws = torch.empty(P.ff_attention_workspace_bytes(desc, chunk), dtype=torch.uint8, device="cuda:0")
+
+    def step(i):
+        j = i % copies
+        if chunk:
+            P.ff_attention_chunked(desc, w, xs[j], zs[j], mask, chunk_rows=chunk, out=outs[j], ws=ws)
+        else:
+            P.ff_gated_attention(desc, w, xs[j], zs[j], mask, out=outs[j], ws=ws)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+
+    kernels = {}
+    if profile:
+        # the same steps again with the library's launch timer (HIP events on the launch stream)
+        P.ff_profile_enable(True)
+        for i in range(steps):
+            step(i)
+        torch.cuda.synchronize()
+        kernels = P.ff_profile_collect()
+        P.ff_profile_enable(False)
+    return case, desc, outs[(steps - 1) % copies], ms, kernels
+
+
+def kernel_rooflines(sp, kernels, steps):
+    fl = counted_flop(sp)
+    R, L = sp.batch_len
+    rows = []
+    tri_fused = sp.mode in (2, 3) and not sp.chunk_rows
+    per_step_flop = {
+        "k_gemm<PROJ>": fl["proj"] + (fl["bias"] if tri_fused else 0.0),
+        "k_attn": fl["attn"],
+        "k_gemm<OUT>": fl["out"],
+        "k_gemm<PROJ> (pair bias pass)": fl["bias"],
+    }
+    for name, (ms, cnt) in kernels.items():
+        per_launch_ms = ms / cnt
+        r = {"kernel": name, "launches_per_step": cnt / steps, "avg_us": per_launch_ms * 1e3,
+             "ms_per_step": ms / steps}
+        if name == "k_gemm<PROJ> (pair bias pass)":
+            # reads the pair representation once, writes the float32 bias
+            src = (L * L * sp.c_z if sp.mode == 0 else R * L * sp.c) * 2
+            byts = src + sp.heads * L * L * 4
+            a = byts / (ms / steps * 1e-3) / 1e9
+            r.update(bound="hbm", achieved=a, peak=PEAK_HBM_GBS, unit="GB/s", frac=a / PEAK_HBM_GBS)
+        elif name in per_step_flop:
+            a = per_step_flop[name] / (ms / steps * 1e-3) / 1e12
+            r.update(bound="mfma", achieved=a, peak=PEAK_MFMA_BF16_TFLOPS, unit="TFLOP/s",
+                     frac=a / PEAK_MFMA_BF16_TFLOPS)
+        r["traffic"] = TRAFFIC_BYTES.get((sp.name, name))
+        rows.append(r)
+    rows.sort(key=lambda r: -r["ms_per_step"])
+    return rows
+
+
+def cpu_baseline(case, runs=3):
+    """The float64 oracle as it stands, on the host cores, full module of the workload."""
+    import numpy as np
+    from oracle import evoformer_attention as O
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([d.get("num_threads", 1) for d in threadpool_info()] + [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    sp = case.spec
+    x = case.widened("x").astype(np.float64)
+    z = None if case.z is None else case.widened("z").astype(np.float64)
+    w = {k: v.astype(np.float64) for k, v in case.widened_weights().items()}
+    ts = []
+    ref = None
+    for _ in range(runs):
+        t0 = time.perf_counter()
+        ref = O.gated_attention(sp.mode, x, z, case.mask, w, sp.heads, sp.ln_eps)
+        ts.append(time.perf_counter() - t0)
+    ts.sort()
+    sec = ts[len(ts) // 2]
+    return ref, {"value": counted_flop(sp)["total"] / sec / 1e12, "unit": "TFLOP/s", "cores": threads,
+                 "kind": "oracle", "seconds_per_module": sec,
+                 "sample": f"full {sp.name} module (all {sp.batch_len[0]} batch rows), float64 numpy, median of {runs} runs"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c2_row_bf16_train")
+    ap.add_argument("--no-others", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
+
+    import numpy as np
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    import paper_2203_00854_amd as P
+    P.lib()          # fails loudly if libff.so has not been built
+
+    case, desc, out, ms, kernels = time_workload(args.workload, args.steps, args.warmup)
+    sp = case.spec
+    fl = counted_flop(sp)
+    value = fl["total"] / (ms * 1e-3) / 1e12
+    roof = kernel_rooflines(sp, kernels, args.steps)
+
+    line = {
+        "metric": "evoformer_attention_tflops", "value": value, "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16" if sp.dtype == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{sp.name}: gated attention mode {sp.mode}, x[{sp.n_a},{sp.n_b},{sp.c}], c_z={sp.c_z}, "
+                               f"H={sp.heads}, d={sp.head_dim}, mask {sp.mask}, one module per step",
+                   "path": P.ff_attention_path(desc), "counted_flop_per_step": fl["total"],
+                   "algorithmic_bytes_per_step": algorithmic_bytes(sp)},
+        "ms_per_module": ms,
+        "frac_mfma_peak_whole_module": value / PEAK_MFMA_BF16_TFLOPS,
+        "frac_hbm_peak_whole_module": algorithmic_bytes(sp) / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+    }
+    if roof:
+        d = roof[0]
+        line["roofline"] = {"kernel": d["kernel"], "bound": d.get("bound"), "achieved": d.get("achieved"),
+                            "peak": d.get("peak"), "unit": d.get("unit"), "frac": d.get("frac"),
+                            "traffic": d.get("traffic"), "avg_us": d["avg_us"]}
+        line["kernels"] = roof
+
+    if not args.no_cpu:
+        ref, base = cpu_baseline(case)
+        got = out.float().cpu().numpy().astype(np.float64)
+        base["gpu_vs_oracle_max_abs"] = float(np.max(np.abs(got - ref)))
+        base["gpu_vs_oracle_rel_l2"] = float(np.linalg.norm(got - ref) / np.linalg.norm(ref))
+        line["cpu_baseline"] = base
+
+    if not args.no_others:
+        others = {}
+        for name, st, wu in (("c3_tri_start_bf16_256", args.steps, args.warmup),
+                             ("c3_tri_end_bf16_256", args.steps, args.warmup),
+                             ("c4_col_bf16_extra", max(args.steps // 4, 5), 3),
+                             ("c5_tri_start_bf16_2048", max(args.steps // 40, 3), 1)):
+            c2, d2, _, ms2, k2 = time_workload(name, st, wu)
+            f2 = counted_flop(c2.spec)["total"]
+            others[name] = {"ms_per_module": ms2, "tflops": f2 / (ms2 * 1e-3) / 1e12, "steps": st,
+                            "chunk_rows": c2.spec.chunk_rows, "path": P.ff_attention_path(d2),
+                            "workspace_bytes": P.ff_attention_workspace_bytes(d2, c2.spec.chunk_rows),
+                            "kernels": [{k: r[k] for k in ("kernel", "avg_us", "launches_per_step", "frac", "bound")
+                                         if k in r} for r in kernel_rooflines(c2.spec, k2, st)]}
+            del c2
+            torch.cuda.empty_cache()
+        line["others"] = others
+
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

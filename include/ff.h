@@ -129,6 +129,18 @@ ff_status ff_attention_chunked(const ff_attn_desc* desc, const ff_attn_weights* 
  * benchmark report.  NULL if desc is invalid. */
 const char* ff_attention_path(const ff_attn_desc* desc);
 
+/* Launch timer, a diagnostic for benchmarks (no part of the attention path).  While it is on,
+ * every kernel launch of the library is bracketed by two HIP events recorded on the launch
+ * stream.  ff_profile_enable(on) clears earlier records.  ff_profile_collect waits for the
+ * recorded events and returns, per kernel kind k < ff_profile_kinds(), the summed duration in
+ * milliseconds and the number of launches (arrays of ff_profile_kinds() entries, host memory),
+ * then clears the records.  ff_profile_name(k) names the kind.  Not thread-safe against
+ * concurrent attention calls on other threads' streams beyond a mutex around the records. */
+void ff_profile_enable(int32_t on);
+int32_t ff_profile_kinds(void);
+const char* ff_profile_name(int32_t kind);
+ff_status ff_profile_collect(double* total_ms, int64_t* launches);
+
 /* Message for the last non-OK status returned on this thread ("" if none). */
 const char* ff_last_error(void);
 

@@ -61,6 +61,13 @@ def lib() -> C.CDLL:
         L.ff_attention_chunked.argtypes = common + [C.c_int32]
         L.ff_attention_path.restype = C.c_char_p
         L.ff_attention_path.argtypes = [C.POINTER(AttnDesc)]
+        L.ff_profile_enable.restype = None
+        L.ff_profile_enable.argtypes = [C.c_int32]
+        L.ff_profile_kinds.restype = C.c_int32
+        L.ff_profile_name.restype = C.c_char_p
+        L.ff_profile_name.argtypes = [C.c_int32]
+        L.ff_profile_collect.restype = C.c_int
+        L.ff_profile_collect.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         L.ff_last_error.restype = C.c_char_p
         L.ff_version.restype = C.c_char_p
         _lib = L
@@ -167,6 +174,19 @@ def ff_attention_chunked(desc: AttnDesc, w: Dict[str, "object"], x, z=None, mask
     _check(lib().ff_attention_chunked(C.byref(desc), C.byref(wts), _ptr(x), _ptr(z), _ptr(mask), _ptr(out), _ptr(ws),
                                       ws.numel(), _stream(), chunk_rows))
     return out
+
+
+def ff_profile_enable(on: bool):
+    lib().ff_profile_enable(1 if on else 0)
+
+
+def ff_profile_collect():
+    """{kernel kind name: (total milliseconds, launches)} since the timer was switched on."""
+    n = lib().ff_profile_kinds()
+    ms = (C.c_double * n)()
+    cnt = (C.c_int64 * n)()
+    _check(lib().ff_profile_collect(ms, cnt))
+    return {lib().ff_profile_name(i).decode(): (ms[i], cnt[i]) for i in range(n) if cnt[i]}
 
 
 # ------------------------------------------------------------------------- test/bench glue

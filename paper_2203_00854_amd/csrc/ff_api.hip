@@ -4,9 +4,52 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
+#include <vector>
+
 #include "ff_common.h"
 
 namespace ff {
+
+// ---- launch timer: HIP events around kernel launches, on the launch stream -------------
+static bool g_prof_on = false;
+static std::mutex g_prof_mu;
+struct ProfRec { int kind; hipEvent_t a, b; };
+static std::vector<ProfRec> g_prof;
+static std::vector<hipEvent_t> g_prof_pool;
+static const char* kKindNames[KK_COUNT] = {"k_prep", "k_gemm<PROJ> (pair bias pass)", "k_gemm<PROJ>", "k_attn",
+                                           "k_gemm<OUT>", "k_layernorm", "generic family"};
+
+static hipEvent_t prof_event() {
+    if (!g_prof_pool.empty()) {
+        hipEvent_t e = g_prof_pool.back();
+        g_prof_pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+void prof_begin(int kind, hipStream_t st) {
+    if (!g_prof_on) return;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    if (g_prof.size() >= (1u << 18)) return;
+    ProfRec r{kind, prof_event(), prof_event()};
+    if (!r.a || !r.b) return;
+    (void)hipEventRecord(r.a, st);
+    g_prof.push_back(r);
+}
+
+void prof_end(int kind, hipStream_t st) {
+    if (!g_prof_on) return;
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    for (size_t i = g_prof.size(); i-- > 0;)
+        if (g_prof[i].kind == kind) {
+            (void)hipEventRecord(g_prof[i].b, st);
+            return;
+        }
+}
 
 static thread_local char g_err[512] = "";
 
@@ -114,12 +157,21 @@ static ff_status run(const ff_attn_desc* desc, const ff_attn_weights* w, const v
     for (const void* q : wp) fast = fast && aligned16(q);
     Workspace ws;
     carve(p, chunk, &ws, wsp, fast);
-    st = fast ? mfma_prepare(p, *w, x, z, ws, stream) : generic_prepare(p, *w, x, z, ws, stream);
+    if (fast) {
+        st = mfma_prepare(p, *w, x, z, ws, stream);
+    } else {
+        Timed t(KK_GENERIC, stream);
+        st = generic_prepare(p, *w, x, z, ws, stream);
+    }
     if (st != FF_OK) return st;
     for (int r0 = 0; r0 < p.R; r0 += chunk) {
         int rows = p.R - r0 < chunk ? p.R - r0 : chunk;
-        st = fast ? mfma_chunk(p, *w, x, mask, out, ws, r0, rows, stream)
-                  : generic_chunk(p, *w, x, mask, out, ws, r0, rows, stream);
+        if (fast) {
+            st = mfma_chunk(p, *w, x, mask, out, ws, r0, rows, stream);
+        } else {
+            Timed t(KK_GENERIC, stream);
+            st = generic_chunk(p, *w, x, mask, out, ws, r0, rows, stream);
+        }
         if (st != FF_OK) return st;
     }
     return FF_OK;
@@ -138,6 +190,7 @@ ff_status ff_layernorm(const void* x, const void* gamma, const void* beta, void*
     if (!(eps >= 0.f)) return fail(FF_EINVAL, "eps must be >= 0");
     if (rows == 0) return FF_OK;
     if (!x || !gamma || !beta || !y) return fail(FF_EINVAL, "NULL pointer");
+    Timed t(KK_LAYERNORM, (hipStream_t)hip_stream);
     return layernorm_launch(x, gamma, beta, y, rows, c, eps, dt, (hipStream_t)hip_stream);
 }
 
@@ -167,6 +220,43 @@ const char* ff_attention_path(const ff_attn_desc* desc) {
     Problem p;
     if (make_problem(desc, &p) != FF_OK) return nullptr;
     return mfma_supported(p) ? "mfma_bf16" : "generic";
+}
+
+void ff_profile_enable(int32_t on) {
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    for (auto& r : g_prof) {
+        g_prof_pool.push_back(r.a);
+        g_prof_pool.push_back(r.b);
+    }
+    g_prof.clear();
+    g_prof_on = on != 0;
+}
+
+int32_t ff_profile_kinds(void) { return KK_COUNT; }
+
+const char* ff_profile_name(int32_t kind) { return (kind >= 0 && kind < KK_COUNT) ? kKindNames[kind] : nullptr; }
+
+ff_status ff_profile_collect(double* total_ms, int64_t* launches) {
+    if (!total_ms || !launches) return fail(FF_EINVAL, "NULL pointer");
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    for (int i = 0; i < KK_COUNT; ++i) {
+        total_ms[i] = 0.0;
+        launches[i] = 0;
+    }
+    ff_status st = FF_OK;
+    for (auto& r : g_prof) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess)
+            st = fail(FF_EHIP, "launch timer: event read failed");
+        else {
+            total_ms[r.kind] += ms;
+            launches[r.kind] += 1;
+        }
+        g_prof_pool.push_back(r.a);
+        g_prof_pool.push_back(r.b);
+    }
+    g_prof.clear();
+    return st;
 }
 
 const char* ff_last_error(void) { return g_err; }

@@ -67,6 +67,18 @@ struct Workspace {
     int chunk;         // batch rows per chunk the tensors above are sized for
 };
 
+// kernel kinds for the launch timer (ff_profile_* in the C ABI)
+enum KernelKind { KK_PREP = 0, KK_BIAS, KK_PROJ, KK_ATTN, KK_OUT, KK_LAYERNORM, KK_GENERIC, KK_COUNT };
+void prof_begin(int kind, hipStream_t st);
+void prof_end(int kind, hipStream_t st);
+// brackets the launches issued in its scope with HIP events when the timer is on
+struct Timed {
+    int kind;
+    hipStream_t st;
+    Timed(int k, hipStream_t s) : kind(k), st(s) { prof_begin(k, s); }
+    ~Timed() { prof_end(kind, st); }
+};
+
 // error plumbing (ff_api.hip)
 ff_status fail(ff_status st, const char* fmt, ...);
 ff_status check_launch(const char* what);

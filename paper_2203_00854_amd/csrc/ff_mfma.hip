@@ -757,6 +757,7 @@ ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x
         a.nseg = 5; a.K = p.c; a.gamma = (const bf16_t*)w.ln_g; a.beta = (const bf16_t*)w.ln_b;
         a.wp = m.wp; a.sn = m.sn; a.cn = m.cn;
         const int rows = 4 * p.Hd + 32;
+        Timed t(KK_PREP, st);
         hipLaunchKernelGGL(k_prep, dim3((rows + 3) / 4), dim3(256), 0, st, a);
     }
     if (p.mode == FF_MSA_ROW) {
@@ -765,7 +766,10 @@ ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x
         a.seg[0] = {(const bf16_t*)w.w_b, nullptr, p.H, 32, kLog2e};
         a.nseg = 1; a.K = p.c_z; a.gamma = (const bf16_t*)w.lnz_g; a.beta = (const bf16_t*)w.lnz_b;
         a.wp = m.zwp; a.sn = m.sn + off; a.cn = m.cn + off;
-        hipLaunchKernelGGL(k_prep, dim3(8), dim3(256), 0, st, a);
+        {
+            Timed t(KK_PREP, st);
+            hipLaunchKernelGGL(k_prep, dim3(8), dim3(256), 0, st, a);
+        }
         // bias[h][i][j] from the pair representation: "batch rows" i, tokens j
         GemmArgs g{};
         g.src = (const bf16_t*)z; g.sr = p.L; g.sl = 1; g.r0 = 0; g.rows = p.L; g.L = p.L; g.Lp = Lp; g.Lq = Lq;
@@ -773,6 +777,7 @@ ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x
         g.Hd = p.Hd; g.H = p.H; g.D = p.d; g.nt_main = 0; g.bias = ws.bias;
         g.ft_first = 0; g.ft_count = 1; g.tiles_per_split = 1;
         const int blocks_m = (p.L * (Lp / 32) + 7) / 8;
+        Timed t(KK_BIAS, st);
         launch_gemm<true>(g, p.c_z, dim3(blocks_m, 1), st);
     } else if (tri && ws.chunk < p.R) {
         // chunked triangle attention: the bias of all rows is needed before the first chunk
@@ -780,6 +785,7 @@ ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x
         g.src = (const bf16_t*)x; g.r0 = 0; g.rows = p.R;
         g.ft_first = g.nt_main; g.ft_count = 1; g.tiles_per_split = 1;
         const int blocks_m = (p.R * (Lp / 32) + 7) / 8;
+        Timed t(KK_BIAS, st);
         launch_gemm<true>(g, p.c, dim3(blocks_m, 1), st);
     }
     return check_launch("prepare (mfma)");
@@ -800,6 +806,7 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
         const int split = pick_split(blocks_m, g.nt_main);
         g.ft_first = 0; g.ft_count = g.nt_main + (fused_bias ? 1 : 0);
         g.tiles_per_split = (g.ft_count + split - 1) / split;
+        Timed t(KK_PROJ, st);
         launch_gemm<true>(g, p.c, dim3(blocks_m, split), st);
     }
 
@@ -807,6 +814,7 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
     a.q = m.q; a.k = m.k; a.g = m.g; a.vt = m.vt; a.o = m.o; a.bias = ws.bias; a.mask = mask;
     a.sr = p.sr; a.sl = p.sl; a.r0 = r0; a.rows = rows; a.L = p.L; a.Lp = Lp; a.Lq = Lq; a.H = p.H; a.Hd = p.Hd;
     {
+        Timed t(KK_ATTN, st);
         dim3 grid(Lq / 64, p.H, (rows + 3) / 4);
         const size_t bias_bytes = (size_t)2 * 64 * kBiasPitch * 4;
 #define FF_ATTN(DD)                                                                                \
@@ -830,6 +838,7 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
         const int split = pick_split(blocks_m, tiles_n);
         o.ft_first = 0; o.ft_count = tiles_n;
         o.tiles_per_split = tiles_n / split;
+        Timed t(KK_OUT, st);
         launch_gemm<false>(o, p.Hd, dim3(blocks_m, split), st);
     }
     return check_launch("attention chunk (mfma)");
