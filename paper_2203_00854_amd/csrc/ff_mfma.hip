@@ -28,9 +28,9 @@
 // 32-key tile is permuted; the same permutation is applied when K rows and V^T columns are
 // fetched, so nothing moves between the two contractions.
 //
-// Workspace layout of this family (Lp = L rounded up to 32, token p = rl*Lp + l):
-//   bias [H][Lq][Lp] float32 (times log2 e), Lq = L rounded up to 64
-//   q, k, g, o  [rows*Lp][Hd] bf16;  vt [rows][H][D][Lp] bf16
+// Workspace layout of this family (Lp = Lq = L rounded up to 64, token p = rl*Lp + l):
+//   bias [H][Lq][Lp] float32 (times log2 e)
+//   q, k [rows][H][Lp][D] bf16;  g, o [rows*Lp][Hd] bf16;  vt [rows][H][Lp/32][D][32] bf16
 //   prepared weights [(4*Hd + 32)][c] (+ [32][c_z] in row mode) bf16, their sums and offsets
 // Pad tokens (l in [L, Lp)) hold finite values everywhere; they are masked as keys.
 #include "ff_common.h"
@@ -92,7 +92,7 @@ struct MfmaWs {
 };
 
 static MfmaWs split_ws(const Problem& p, int chunk, const Workspace& ws) {
-    const size_t Lp = round_up(p.L, 32);
+    const size_t Lp = round_up(p.L, 64);
     const size_t n = (size_t)chunk * Lp * p.Hd;   // elements per tensor
     MfmaWs m;
     m.q = (bf16_t*)ws.qkvg;
@@ -124,7 +124,7 @@ bool mfma_supported(const Problem& p) {
 }
 
 size_t mfma_workspace(const Problem& p, int chunk, Workspace* ws, void* base) {
-    const size_t Lp = round_up(p.L, 32), Lq = round_up(p.L, 64);
+    const size_t Lp = round_up(p.L, 64), Lq = round_up(p.L, 64);
     size_t off = 0;
     char* b = (char*)base;
     ws->bias = nullptr;
@@ -402,7 +402,8 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
                 merge_halves(pk[1], pk[3]);
                 merge_halves(pk[4], pk[6]);
                 merge_halves(pk[5], pk[7]);
-                bf16_t* dst = a.vt + ((size_t)(rl * a.H + h) * a.D + e) * a.Lp + l0 + 8 * hf;
+                // v^T tiled by 32 keys: [row][head][l / 32][e][l % 32]
+                bf16_t* dst = a.vt + (((size_t)(rl * a.H + h) * (a.Lp >> 5) + (l0 >> 5)) * a.D + e) * 32 + 8 * hf;
                 *reinterpret_cast<uint4*>(dst) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
                 *reinterpret_cast<uint4*>(dst + 16) = make_uint4(pk[4], pk[5], pk[6], pk[7]);
             }
@@ -459,16 +460,25 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
                 merge_halves(pk[1], pk[3]);
                 merge_halves(pk[4], pk[6]);
                 merge_halves(pk[5], pk[7]);
-                bf16_t* dst = nullptr;
+                bf16_t *dst0 = nullptr, *dst1 = nullptr;   // features f0 .. f0+7 and f0+16 .. f0+23
                 if constexpr (PROJ) {
-                    bf16_t* base = kind == 0 ? a.q : (kind == 1 ? a.k : a.g);
-                    dst = base + (size_t)p * a.Hd + (nb - kind * a.Hd);
+                    const int f0 = nb - kind * a.Hd + 8 * hf;
+                    if (kind == 3) {                     // gate: token-major [token][Hd]
+                        dst0 = a.g + (size_t)p * a.Hd + f0;
+                        dst1 = dst0 + 16;
+                    } else {                             // q, k: head-major [row][head][l][d]
+                        bf16_t* base = kind == 0 ? a.q : a.k;
+                        const int h0 = f0 / a.D, h1 = (f0 + 16) / a.D;
+                        dst0 = base + ((size_t)(rl * a.H + h0) * a.Lp + l) * a.D + (f0 - h0 * a.D);
+                        dst1 = base + ((size_t)(rl * a.H + h1) * a.Lp + l) * a.D + (f0 + 16 - h1 * a.D);
+                    }
                 } else if (l < a.L) {
-                    dst = a.out + ((int64_t)(a.r0 + rl) * a.sr + (int64_t)l * a.sl) * a.N + nb;
+                    dst0 = a.out + ((int64_t)(a.r0 + rl) * a.sr + (int64_t)l * a.sl) * a.N + nb + 8 * hf;
+                    dst1 = dst0 + 16;
                 }
-                if (dst) {
-                    *reinterpret_cast<uint4*>(dst + 8 * hf) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-                    *reinterpret_cast<uint4*>(dst + 16 + 8 * hf) = make_uint4(pk[4], pk[5], pk[6], pk[7]);
+                if (dst0) {
+                    *reinterpret_cast<uint4*>(dst0) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+                    *reinterpret_cast<uint4*>(dst1) = make_uint4(pk[4], pk[5], pk[6], pk[7]);
                 }
             }
         }
@@ -498,7 +508,7 @@ struct AttnArgs {
     int r0, rows, L, Lp, Lq, H, Hd;
 };
 
-constexpr int kBiasPitch = 36;   // floats per LDS bias row (32 + 4 pad)
+constexpr int kBiasPitch = 68;   // floats per LDS bias row (64 + 4 pad): conflict-free 16-byte reads
 constexpr float kRaise = 10.f;   // log2 units
 
 template <int D, bool HAS_BIAS>
@@ -512,7 +522,6 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
     float* s_bias = reinterpret_cast<float*>(smem);                                  // [2][64][kBiasPitch]
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, hf = lane >> 5;
-    const int nt = a.Lp >> 5;
     const int rl_raw = blockIdx.z * 4 + wave;
     const bool row_ok = rl_raw < a.rows;
     const int rl = row_ok ? rl_raw : a.rows - 1;
@@ -524,9 +533,8 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
     Frag qf[2][KS];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-        int qi = q0 + 32 * j + col;
-        if (qi > a.Lp - 1) qi = a.Lp - 1;
-        const bf16_t* qp = a.q + ((size_t)rl * a.Lp + qi) * a.Hd + h * D;
+        const int qi = q0 + 32 * j + col;                       // < Lp
+        const bf16_t* qp = a.q + ((size_t)(rl * a.H + h) * a.Lp + qi) * D;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             qf[j][s].u = make_uint4(0, 0, 0, 0);
@@ -535,48 +543,66 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
         if (xlane) qf[j][SX].w[0] = 0x3f800000u;        // (-m_ref = 0, 1.0)
     }
 
-    // ---- bias tile pipeline: thread loads rows b_row, b_row+32; floats 4*b_c4 .. +3
-    const int b_row = tid >> 3, b_c4 = tid & 7;
+    // ---- bias tile pipeline: [64 queries][64 keys]; thread loads rows b_row + 16 i, floats 4*b_c4 .. +3
+    const int b_row = tid >> 4, b_c4 = tid & 15;
     const float* bias_t = HAS_BIAS ? a.bias + ((size_t)h * a.Lq + q0 + b_row) * a.Lp + 4 * b_c4 : nullptr;
     float* s_bias_t = s_bias + (size_t)b_row * kBiasPitch + 4 * b_c4;
-    float4 breg0, breg1;
+    // (four named registers: an array captured by a lambda would be spilled to scratch)
+    float4 bq0, bq1, bq2, bq3;
+    auto load_bias = [&](int it) {
+        const float* bp = bias_t + 64 * it;
+        bq0 = *reinterpret_cast<const float4*>(bp);
+        bq1 = *reinterpret_cast<const float4*>(bp + (size_t)16 * a.Lp);
+        bq2 = *reinterpret_cast<const float4*>(bp + (size_t)32 * a.Lp);
+        bq3 = *reinterpret_cast<const float4*>(bp + (size_t)48 * a.Lp);
+    };
+    auto store_bias = [&](int buf) {
+        float* sp = s_bias_t + (size_t)buf * 64 * kBiasPitch;
+        *reinterpret_cast<float4*>(sp) = bq0;
+        *reinterpret_cast<float4*>(sp + 16 * kBiasPitch) = bq1;
+        *reinterpret_cast<float4*>(sp + 32 * kBiasPitch) = bq2;
+        *reinterpret_cast<float4*>(sp + 48 * kBiasPitch) = bq3;
+    };
     if constexpr (HAS_BIAS) {
-        breg0 = *reinterpret_cast<const float4*>(bias_t);
-        breg1 = *reinterpret_cast<const float4*>(bias_t + (size_t)32 * a.Lp);
-        *reinterpret_cast<float4*>(s_bias_t) = breg0;
-        *reinterpret_cast<float4*>(s_bias_t + 32 * kBiasPitch) = breg1;
+        load_bias(0);
+        store_bias(0);
     }
 
     // permuted key of S^T row m = col: rows 8g + 4b + e hold key 16*(g/2) + 8b + 4*(g%2) + e
     const int kperm = 16 * (col >> 4) + 8 * ((col >> 2) & 1) + 4 * ((col >> 3) & 1) + (col & 3);
-    const bf16_t* kp = a.k + ((size_t)rl * a.Lp + kperm) * a.Hd + h * D + 8 * hf;
-    const bf16_t* vp = a.vt + ((size_t)(rl * a.H + h) * D + (col < D ? col : 0)) * a.Lp + 8 * hf;
-    const size_t kstep = (size_t)32 * a.Hd;
+    // k is [row][head][l][d], v^T is [row][head][l / 32][e][l % 32]: a 32-key tile of either is one
+    // contiguous block of 64*D bytes
+    const bf16_t* kp = a.k + ((size_t)(rl * a.H + h) * a.Lp + kperm) * D + 8 * hf;
+    const bf16_t* vp = a.vt + (size_t)(rl * a.H + h) * a.Lp * D + (col < D ? col : 0) * 32 + 8 * hf;
+    constexpr int kstep = 32 * D;
     const float* mp = a.mask ? a.mask + (int64_t)(a.r0 + rl) * a.sr : nullptr;
     const bool ones_lane = ONES_ROW && col == D;
 
-    // K fragments (A operand, lane = permuted key, 8 consecutive e), V^T fragments (A operand,
-    // lane = e, 8 consecutive keys) and the key's mask value, fetched one tile ahead.
-    Frag kf_n[KS], vf_n[2];
-    float mv_n;
-    auto fetch = [&](int kt) {
+    // Software pipeline over 32-key tiles i:
+    //   K(i+2), mask(i+2), V(i+1) are in flight (global -> registers) while
+    //   S^T(i+1) = K(i+1) Q^T runs on the matrix cores while
+    //   the vector unit takes the exponentials of tile i, followed by O^T += V^T(i) P^T(i).
+    // K and V use two register sets each (even / odd tiles); nothing looks at a loaded value
+    // before its use.  The bias tile in LDS covers 64 keys (an even and an odd tile).
+    Frag kb0[KS], kb1[KS], vb0[2], vb1[2];
+    float mv0 = 1.f, mv1 = 1.f;
+    auto fetch_k = [&](Frag (&kb)[KS], float& mv, int kt) {
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            kf_n[s].u = make_uint4(0, 0, 0, 0);
-            if (2 * s + hf < PCX) kf_n[s].u = ldg16(kp + kt * kstep + 16 * s);
+            kb[s].u = make_uint4(0, 0, 0, 0);
+            if (2 * s + hf < PCX) kb[s].u = ldg16(kp + kt * kstep + 16 * s);
         }
+        const int key = 32 * kt + kperm;
+        mv = 1.f;
+        if (mp) mv = mp[(int64_t)(key < a.L ? key : a.L - 1) * a.sl];
+    };
+    auto fetch_v = [&](Frag (&vb)[2], int kt) {
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
-            vf_n[c].u = make_uint4(0, 0, 0, 0);
-            if (col < D) vf_n[c].u = ldg16(vp + 32 * kt + 16 * c);
+            vb[c].u = make_uint4(0, 0, 0, 0);
+            if (col < D) vb[c].u = ldg16(vp + kt * kstep + 16 * c);
         }
-        // nothing here may look at the loaded values: they are only waited for at their use
-        const int key = 32 * kt + kperm;
-        mv_n = 1.f;
-        if (mp) mv_n = mp[(int64_t)(key < a.L ? key : a.L - 1) * a.sl];
     };
-    fetch(0);
-    __syncthreads();
 
     f32x16 o_acc[2];
     float m_ref[2], l_run[2];
@@ -589,97 +615,122 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
     }
     bool first = true;
 
-    for (int kt = 0; kt < nt; ++kt) {
-        const int buf = kt & 1;
-        Frag kf[KS], vf[2];
+    // S^T of tile kt into sa (bias tile as accumulator input); returns whether any key is valid
+    auto qk = [&](Frag (&kb)[KS], float mv, int kt, f32x16 (&sa)[2], const float* sb) -> bool {
+        const bool key_valid = mv != 0.f && 32 * kt + kperm < a.L;
+        if (!__any(key_valid)) return false;
+        if (xlane) kb[SX].w[0] = key_valid ? 0x00003f80u : 0xff803f80u;   // (1.0, mask term)
 #pragma unroll
-        for (int s = 0; s < KS; ++s) kf[s] = kf_n[s];
-#pragma unroll
-        for (int c = 0; c < 2; ++c) {
-            vf[c] = vf_n[c];
-            if (ones_lane) vf[c].u = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
-        }
-        const bool key_valid = mv_n != 0.f && 32 * kt + kperm < a.L;
-        if (xlane) kf[SX].w[0] = key_valid ? 0x00003f80u : 0xff803f80u;   // (1.0, mask term)
-        if (kt + 1 < nt) {
-            fetch(kt + 1);
+        for (int j = 0; j < 2; ++j) {
             if constexpr (HAS_BIAS) {
-                breg0 = *reinterpret_cast<const float4*>(bias_t + 32 * (kt + 1));
-                breg1 = *reinterpret_cast<const float4*>(bias_t + (size_t)32 * a.Lp + 32 * (kt + 1));
-            }
-        }
-        if (__any(key_valid)) {
-            f32x16 s_acc[2];
-            float tmax[2];
+                const float* br = sb + (size_t)(32 * j + col) * kBiasPitch + 32 * (kt & 1) + 8 * hf;
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                if constexpr (HAS_BIAS) {
-                    const float* br = s_bias + ((size_t)buf * 64 + 32 * j + col) * kBiasPitch + 8 * hf;
+                for (int c = 0; c < 2; ++c)
 #pragma unroll
-                    for (int c = 0; c < 2; ++c)
-#pragma unroll
-                        for (int i = 0; i < 2; ++i) {
-                            const float4 t = *reinterpret_cast<const float4*>(br + 16 * c + 4 * i);
-                            s_acc[j][8 * c + 4 * i] = t.x; s_acc[j][8 * c + 4 * i + 1] = t.y;
-                            s_acc[j][8 * c + 4 * i + 2] = t.z; s_acc[j][8 * c + 4 * i + 3] = t.w;
-                        }
-                } else {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) s_acc[j][v] = 0.f;
-                }
-#pragma unroll
-                for (int s = 0; s < KS; ++s)
-                    s_acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s].v, qf[j][s].v, s_acc[j], 0, 0, 0);
-                float t = s_acc[j][0];
-#pragma unroll
-                for (int v = 1; v < 16; ++v) t = fmaxf(t, s_acc[j][v]);
-                tmax[j] = fmaxf(t, other_half(t));
-            }
-            // s_acc holds s - m_ref (masked keys: -inf).  Raise the reference where needed.
-            if (first || __any(tmax[0] > kRaise || tmax[1] > kRaise)) {
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    const bool raise = first || tmax[j] > kRaise;
-                    const float new_ref = raise ? bf16_round(m_ref[j] + tmax[j]) : m_ref[j];
-                    const float delta = new_ref - m_ref[j];
-                    m_ref[j] = new_ref;
-                    const float sc = first ? 1.f : __builtin_amdgcn_exp2f(-delta);   // nothing accumulated yet
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        o_acc[j][v] *= sc;
-                        s_acc[j][v] -= delta;
+                    for (int i = 0; i < 2; ++i) {
+                        const float4 x4 = *reinterpret_cast<const float4*>(br + 16 * c + 4 * i);
+                        sa[j][8 * c + 4 * i] = x4.x; sa[j][8 * c + 4 * i + 1] = x4.y;
+                        sa[j][8 * c + 4 * i + 2] = x4.z; sa[j][8 * c + 4 * i + 3] = x4.w;
                     }
-                    l_run[j] *= sc;
-                    if (xlane) qf[j][SX].w[0] = pack2(-new_ref, 1.f);
-                }
-                first = false;
+            } else {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) sa[j][v] = 0.f;
             }
 #pragma unroll
+            for (int s = 0; s < KS; ++s)
+                sa[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb[s].v, qf[j][s].v, sa[j], 0, 0, 0);
+        }
+        return true;
+    };
+    // exponentials of tile sa and O^T update; sn is the tile already issued with the old reference
+    auto soft_pv = [&](f32x16 (&sa)[2], Frag (&vb)[2], f32x16 (&sn)[2], bool sn_live) {
+        if (ones_lane) {
+#pragma unroll
+            for (int c = 0; c < 2; ++c) vb[c].u = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
+        }
+        float tmax[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            float mx = sa[j][0];
+#pragma unroll
+            for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sa[j][v]);
+            tmax[j] = fmaxf(mx, other_half(mx));
+        }
+        // sa holds s - m_ref (masked keys: -inf).  Raise the reference where needed.
+        if (first || __any(tmax[0] > kRaise || tmax[1] > kRaise)) {
+#pragma unroll
             for (int j = 0; j < 2; ++j) {
-                float psum = 0.f;
+                const bool raise = first || tmax[j] > kRaise;
+                const float new_ref = raise ? bf16_round(m_ref[j] + tmax[j]) : m_ref[j];
+                const float delta = new_ref - m_ref[j];
+                m_ref[j] = new_ref;
+                const float sc = first ? 1.f : __builtin_amdgcn_exp2f(-delta);   // nothing accumulated yet
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    s_acc[j][v] = __builtin_amdgcn_exp2f(s_acc[j][v]);
-                    if constexpr (!ONES_ROW) psum += s_acc[j][v];
+                    o_acc[j][v] *= sc;
+                    sa[j][v] -= delta;
                 }
-                if constexpr (!ONES_ROW) l_run[j] += psum;
-                Frag pf[2];
+                if (sn_live) {
 #pragma unroll
-                for (int c = 0; c < 2; ++c)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) pf[c].w[i] = pack2(s_acc[j][8 * c + 2 * i], s_acc[j][8 * c + 2 * i + 1]);
-#pragma unroll
-                for (int c = 0; c < 2; ++c)
-                    o_acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[c].v, pf[c].v, o_acc[j], 0, 0, 0);
+                    for (int v = 0; v < 16; ++v) sn[j][v] -= delta;
+                }
+                l_run[j] *= sc;
+                if (xlane) qf[j][SX].w[0] = pack2(-new_ref, 1.f);
             }
+            first = false;
         }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            Frag pf[2];
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float p0 = __builtin_amdgcn_exp2f(sa[j][8 * c + 2 * i]);
+                    const float p1 = __builtin_amdgcn_exp2f(sa[j][8 * c + 2 * i + 1]);
+                    pf[c].w[i] = pack2(p0, p1);
+                    // denominator from the rounded weights, two per instruction
+                    if constexpr (!ONES_ROW) l_run[j] = add_pair(pf[c].w[i], l_run[j]);
+                }
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+                o_acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb[c].v, pf[c].v, o_acc[j], 0, 0, 0);
+        }
+    };
+
+    const int nt = a.Lp >> 5;               // even
+    fetch_k(kb0, mv0, 0);
+    fetch_k(kb1, mv1, 1);
+    fetch_v(vb0, 0);
+    if constexpr (HAS_BIAS) {
+        if (nt > 2) load_bias(1);
+    }
+    __syncthreads();                        // bias group 0 is in LDS
+    f32x16 s0[2], s1[2];
+    bool live0 = qk(kb0, mv0, 0, s0, s_bias), live1 = false;
+    int cur = 0;                            // LDS buffer of the current 64-key group
+    for (int i = 0; i < nt; i += 2) {
+        // ---- even tile i: K(i+2) -> set 0, V(i+1) -> set 1, S^T(i+1) -> s1, exponentials of s0
+        if (i + 2 < nt) fetch_k(kb0, mv0, i + 2);
+        fetch_v(vb1, i + 1);
+        live1 = qk(kb1, mv1, i + 1, s1, s_bias + (size_t)cur * 64 * kBiasPitch);
+        if (live0) soft_pv(s0, vb0, s1, live1);
         if constexpr (HAS_BIAS) {
-            if (kt + 1 < nt) {
-                *reinterpret_cast<float4*>(s_bias_t + (size_t)(buf ^ 1) * 64 * kBiasPitch) = breg0;
-                *reinterpret_cast<float4*>(s_bias_t + (size_t)(buf ^ 1) * 64 * kBiasPitch + 32 * kBiasPitch) = breg1;
-            }
+            if (i + 2 < nt) store_bias(cur ^ 1);
             __syncthreads();
         }
+        // ---- odd tile i+1: K(i+3) -> set 1, V(i+2) -> set 0, S^T(i+2) -> s0, exponentials of s1
+        live0 = false;
+        if (i + 2 < nt) {
+            fetch_k(kb1, mv1, i + 3);
+            fetch_v(vb0, i + 2);
+            if constexpr (HAS_BIAS) {
+                if (i + 4 < nt) load_bias((i >> 1) + 2);
+            }
+            live0 = qk(kb0, mv0, i + 2, s0, s_bias + (size_t)(cur ^ 1) * 64 * kBiasPitch);
+        }
+        if (live1) soft_pv(s1, vb1, s0, live0);
+        cur ^= 1;
     }
 
     // ---- epilogue: normalise, gate, store.  o_acc[j]: lane = query, register v = e = 8*(v/4) + 4*hf + v%4
@@ -732,7 +783,7 @@ static int pick_split(int blocks_m, int tiles_n) {
 }
 
 static GemmArgs proj_args(const Problem& p, const MfmaWs& m, const Workspace& ws) {
-    const int Lp = round_up(p.L, 32), Lq = round_up(p.L, 64);
+    const int Lp = round_up(p.L, 64), Lq = round_up(p.L, 64);
     GemmArgs g{};
     g.sr = p.sr; g.sl = p.sl; g.L = p.L; g.Lp = Lp; g.Lq = Lq; g.K = p.c; g.eps = p.eps;
     g.w = m.wp; g.sn = m.sn; g.cn = m.cn; g.Hd = p.Hd; g.H = p.H; g.D = p.d;
@@ -744,7 +795,7 @@ static GemmArgs proj_args(const Problem& p, const MfmaWs& m, const Workspace& ws
 ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x, const void* z, const Workspace& ws,
                        hipStream_t st) {
     const MfmaWs m = split_ws(p, ws.chunk, ws);
-    const int Lp = round_up(p.L, 32), Lq = round_up(p.L, 64);
+    const int Lp = round_up(p.L, 64), Lq = round_up(p.L, 64);
     const float qscale = kLog2e / sqrtf((float)p.d);
     const bool tri = p.mode == FF_TRI_START || p.mode == FF_TRI_END;
     {
@@ -793,7 +844,7 @@ ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x
 
 ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, const float* mask, void* out,
                      const Workspace& ws, int r0, int rows, hipStream_t st) {
-    const int Lp = round_up(p.L, 32), Lq = round_up(p.L, 64);
+    const int Lp = round_up(p.L, 64), Lq = round_up(p.L, 64);
     const MfmaWs m = split_ws(p, ws.chunk, ws);
     const bool tri = p.mode == FF_TRI_START || p.mode == FF_TRI_END;
     const int tiles_m = rows * (Lp / 32);
@@ -816,7 +867,7 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
     {
         Timed t(KK_ATTN, st);
         dim3 grid(Lq / 64, p.H, (rows + 3) / 4);
-        const size_t bias_bytes = (size_t)2 * 64 * kBiasPitch * 4;
+        const size_t bias_bytes = (size_t)2 * 64 * kBiasPitch * 4;   // two [64][kBiasPitch] float tiles
 #define FF_ATTN(DD)                                                                                \
     do {                                                                                           \
         if (p.has_bias) hipLaunchKernelGGL((k_attn<DD, true>), grid, dim3(256), bias_bytes, st, a); \
