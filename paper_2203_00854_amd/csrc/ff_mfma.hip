@@ -223,6 +223,7 @@ struct GemmArgs {
     const float *sn, *cn;  // PROJ: per-feature sums / offsets
     const bf16_t* bvec;    // OUT: b_o [N]
     int Hd, H, D;
+    float invD;            // 1 / D
     int nt_main;           // PROJ: 32-feature tiles of q|k|v|gate; tile nt_main is the pair-bias tile
     bf16_t *q, *k, *g, *vt;  // PROJ outputs
     float* bias;             // PROJ pair-bias output [H][Lq][Lp]
@@ -232,12 +233,12 @@ struct GemmArgs {
     int tiles_per_split;     // tiles per blockIdx.y
 };
 
-template <int KC, bool PROJ>
+template <int KC, bool PROJ, int TT>
 __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
     constexpr int NT = 256;
     constexpr int PITCH = KC * 32 + 16;                 // bytes per weight row in LDS (padded)
     __shared__ __attribute__((aligned(16))) unsigned char s_w[2][32 * PITCH];
-    __shared__ __attribute__((aligned(16))) float s_stat[PROJ ? 4 * 2 * 2 * 32 : 4];   // [wave][tt][mean|rstd][32]
+    __shared__ __attribute__((aligned(16))) float s_stat[PROJ ? 4 * TT * 2 * 32 : 4];   // [wave][tt][mean|rstd][32]
     constexpr int kMaxTiles = 33;                       // 4*Hd/32 + 1 with Hd <= 256
     __shared__ __attribute__((aligned(16))) float s_sn[PROJ ? kMaxTiles * 32 : 4], s_cn[kMaxTiles * 32];
 
@@ -283,13 +284,13 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
     }
 
     // ---- token operand fragments, raw
-    Frag xa[2][KC];
-    bool tile_ok[2];
-    int tok[2], tok_rl[2], tok_l[2];   // padded token index of this lane, its batch row and position
-    float mean[2], rstd[2];
+    Frag xa[TT][KC];
+    bool tile_ok[TT];
+    int tok[TT], tok_rl[TT], tok_l[TT];   // padded token index of this lane, its batch row and position
+    float mean[TT], rstd[TT];
 #pragma unroll
-    for (int tt = 0; tt < 2; ++tt) {
-        const int tg = (blockIdx.x * 4 + wave) * 2 + tt;
+    for (int tt = 0; tt < TT; ++tt) {
+        const int tg = (blockIdx.x * 4 + wave) * TT + tt;
         tile_ok[tt] = tg < tiles_m;
         const int p = tg * 32 + col;
         tok[tt] = p;
@@ -310,7 +311,7 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
     if constexpr (PROJ) {
         // LayerNorm statistics of the raw rows: two passes over the registers, float32
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt) {
+        for (int tt = 0; tt < TT; ++tt) {
             float sum = 0.f;
 #pragma unroll
             for (int s = 0; s < KC; ++s)
@@ -334,8 +335,8 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
             mean[tt] = valid ? mu : 0.f;
             rstd[tt] = valid ? rsqrtf(sq / (float)K + a.eps) : 0.f;
             if (hf == 0) {
-                s_stat[((wave * 2 + tt) * 2 + 0) * 32 + col] = mean[tt];
-                s_stat[((wave * 2 + tt) * 2 + 1) * 32 + col] = rstd[tt];
+                s_stat[((wave * TT + tt) * 2 + 0) * 32 + col] = mean[tt];
+                s_stat[((wave * TT + tt) * 2 + 1) * 32 + col] = rstd[tt];
             }
         }
     }
@@ -349,9 +350,9 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
         // kind of this feature tile: 0 q, 1 k, 2 v, 3 gate, 4 pair bias
         const int kind = PROJ ? (ft < a.nt_main ? (ft * 32) / a.Hd : 4) : 0;
         const bool tokens_by_features = PROJ && kind == 2;      // V: rows = tokens
-        f32x16 acc[2];
+        f32x16 acc[TT];
 #pragma unroll
-        for (int tt = 0; tt < 2; ++tt)
+        for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[tt][v] = 0.f;
         if (tokens_by_features) {
@@ -360,7 +361,7 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
                 Frag wf;
                 wf.u = *reinterpret_cast<const uint4*>(&s_w[buf][col * PITCH + (2 * s + hf) * 16]);
 #pragma unroll
-                for (int tt = 0; tt < 2; ++tt)
+                for (int tt = 0; tt < TT; ++tt)
                     acc[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[tt][s].v, wf.v, acc[tt], 0, 0, 0);
             }
         } else {
@@ -369,7 +370,7 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
                 Frag wf;
                 wf.u = *reinterpret_cast<const uint4*>(&s_w[buf][col * PITCH + (2 * s + hf) * 16]);
 #pragma unroll
-                for (int tt = 0; tt < 2; ++tt)
+                for (int tt = 0; tt < TT; ++tt)
                     acc[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf.v, xa[tt][s].v, acc[tt], 0, 0, 0);
             }
         }
@@ -380,12 +381,12 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
             const int nrow = ft * 32 + col;                     // row of the prepared matrix
             const float sn = s_sn[(ft - ft_begin) * 32 + col], cn = s_cn[(ft - ft_begin) * 32 + col];
             const int n = nrow - 2 * a.Hd;
-            const int h = n / a.D, e = n - h * a.D;
+            const int h = (int)(((float)n + 0.5f) * a.invD), e = n - h * a.D;
 #pragma unroll
-            for (int tt = 0; tt < 2; ++tt) {
+            for (int tt = 0; tt < TT; ++tt) {
                 if (!tile_ok[tt]) continue;
                 const int rl = tok_rl[tt], l0 = tok_l[tt] - col;   // the tile lies inside one batch row
-                const float* st = s_stat + (wave * 2 + tt) * 64;
+                const float* st = s_stat + (wave * TT + tt) * 64;
                 uint32_t pk[8];
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
@@ -424,7 +425,7 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
                 }
             }
 #pragma unroll
-            for (int tt = 0; tt < 2; ++tt) {
+            for (int tt = 0; tt < TT; ++tt) {
                 if (!tile_ok[tt]) continue;
                 const int p = tok[tt];
                 const int rl = tok_rl[tt], l = tok_l[tt];
@@ -468,7 +469,7 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
                         dst1 = dst0 + 16;
                     } else {                             // q, k: head-major [row][head][l][d]
                         bf16_t* base = kind == 0 ? a.q : a.k;
-                        const int h0 = f0 / a.D, h1 = (f0 + 16) / a.D;
+                        const int h0 = (int)(((float)f0 + 0.5f) * a.invD), h1 = (int)(((float)f0 + 16.5f) * a.invD);
                         dst0 = base + ((size_t)(rl * a.H + h0) * a.Lp + l) * a.D + (f0 - h0 * a.D);
                         dst1 = base + ((size_t)(rl * a.H + h1) * a.Lp + l) * a.D + (f0 + 16 - h1 * a.D);
                     }
@@ -765,13 +766,26 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
 
 // ====================================================================================
 // host side
+// token tiles per wavefront: two halve the LDS traffic per MFMA, one keeps enough registers free for
+// two or more wavefronts per SIMD when the contraction is long
+template <bool PROJ>
+static int gemm_tt(int K) { return (PROJ && K > 64) ? 1 : 2; }
+
+template <bool PROJ>
+static int gemm_blocks_m(int tiles_m, int K) { return (tiles_m + 4 * gemm_tt<PROJ>(K) - 1) / (4 * gemm_tt<PROJ>(K)); }
+
 template <bool PROJ>
 static void launch_gemm(const GemmArgs& a, int K, dim3 grid, hipStream_t st) {
     const int kc = K / 16;
-    if (kc <= 2) hipLaunchKernelGGL((k_gemm<2, PROJ>), grid, dim3(256), 0, st, a);
-    else if (kc <= 4) hipLaunchKernelGGL((k_gemm<4, PROJ>), grid, dim3(256), 0, st, a);
-    else if (kc <= 8) hipLaunchKernelGGL((k_gemm<8, PROJ>), grid, dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((k_gemm<16, PROJ>), grid, dim3(256), 0, st, a);
+    if (gemm_tt<PROJ>(K) == 1) {
+        if (kc <= 8) hipLaunchKernelGGL((k_gemm<8, PROJ, 1>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((k_gemm<16, PROJ, 1>), grid, dim3(256), 0, st, a);
+    } else {
+        if (kc <= 2) hipLaunchKernelGGL((k_gemm<2, PROJ, 2>), grid, dim3(256), 0, st, a);
+        else if (kc <= 4) hipLaunchKernelGGL((k_gemm<4, PROJ, 2>), grid, dim3(256), 0, st, a);
+        else if (kc <= 8) hipLaunchKernelGGL((k_gemm<8, PROJ, 2>), grid, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((k_gemm<16, PROJ, 2>), grid, dim3(256), 0, st, a);
+    }
 }
 
 // blocks along the feature axis: enough blocks to fill 256 CUs about twice
@@ -786,7 +800,7 @@ static GemmArgs proj_args(const Problem& p, const MfmaWs& m, const Workspace& ws
     const int Lp = round_up(p.L, 64), Lq = round_up(p.L, 64);
     GemmArgs g{};
     g.sr = p.sr; g.sl = p.sl; g.L = p.L; g.Lp = Lp; g.Lq = Lq; g.K = p.c; g.eps = p.eps;
-    g.w = m.wp; g.sn = m.sn; g.cn = m.cn; g.Hd = p.Hd; g.H = p.H; g.D = p.d;
+    g.w = m.wp; g.sn = m.sn; g.cn = m.cn; g.Hd = p.Hd; g.H = p.H; g.D = p.d; g.invD = 1.f / (float)p.d;
     g.nt_main = 4 * p.Hd / 32;
     g.q = m.q; g.k = m.k; g.g = m.g; g.vt = m.vt; g.bias = ws.bias;
     return g;
@@ -825,9 +839,9 @@ ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x
         GemmArgs g{};
         g.src = (const bf16_t*)z; g.sr = p.L; g.sl = 1; g.r0 = 0; g.rows = p.L; g.L = p.L; g.Lp = Lp; g.Lq = Lq;
         g.K = p.c_z; g.eps = p.eps; g.w = m.zwp; g.sn = m.sn + off; g.cn = m.cn + off;
-        g.Hd = p.Hd; g.H = p.H; g.D = p.d; g.nt_main = 0; g.bias = ws.bias;
+        g.Hd = p.Hd; g.H = p.H; g.D = p.d; g.invD = 1.f / (float)p.d; g.nt_main = 0; g.bias = ws.bias;
         g.ft_first = 0; g.ft_count = 1; g.tiles_per_split = 1;
-        const int blocks_m = (p.L * (Lp / 32) + 7) / 8;
+        const int blocks_m = gemm_blocks_m<true>(p.L * (Lp / 32), p.c_z);
         Timed t(KK_BIAS, st);
         launch_gemm<true>(g, p.c_z, dim3(blocks_m, 1), st);
     } else if (tri && ws.chunk < p.R) {
@@ -835,7 +849,7 @@ ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x
         GemmArgs g = proj_args(p, m, ws);
         g.src = (const bf16_t*)x; g.r0 = 0; g.rows = p.R;
         g.ft_first = g.nt_main; g.ft_count = 1; g.tiles_per_split = 1;
-        const int blocks_m = (p.R * (Lp / 32) + 7) / 8;
+        const int blocks_m = gemm_blocks_m<true>(p.R * (Lp / 32), p.c);
         Timed t(KK_BIAS, st);
         launch_gemm<true>(g, p.c, dim3(blocks_m, 1), st);
     }
@@ -848,7 +862,7 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
     const MfmaWs m = split_ws(p, ws.chunk, ws);
     const bool tri = p.mode == FF_TRI_START || p.mode == FF_TRI_END;
     const int tiles_m = rows * (Lp / 32);
-    const int blocks_m = (tiles_m + 7) / 8;           // 4 waves x 2 token tiles
+    const int blocks_m = gemm_blocks_m<true>(tiles_m, p.c);
     {
         GemmArgs g = proj_args(p, m, ws);
         g.src = (const bf16_t*)x; g.r0 = r0; g.rows = rows;
@@ -883,14 +897,15 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
     GemmArgs o{};
     o.src = m.o; o.sr = p.sr; o.sl = p.sl; o.r0 = r0; o.rows = rows; o.L = p.L; o.Lp = Lp; o.Lq = Lq;
     o.K = p.Hd; o.w = (const bf16_t*)w.w_o; o.bvec = (const bf16_t*)w.b_o;
-    o.Hd = p.Hd; o.H = p.H; o.D = p.d; o.out = (bf16_t*)out; o.N = p.c;
+    o.Hd = p.Hd; o.H = p.H; o.D = p.d; o.invD = 1.f / (float)p.d; o.out = (bf16_t*)out; o.N = p.c;
     {
         const int tiles_n = o.N / 32;
-        const int split = pick_split(blocks_m, tiles_n);
+        const int blocks_o = gemm_blocks_m<false>(tiles_m, p.Hd);
+        const int split = pick_split(blocks_o, tiles_n);
         o.ft_first = 0; o.ft_count = tiles_n;
         o.tiles_per_split = tiles_n / split;
         Timed t(KK_OUT, st);
-        launch_gemm<false>(o, p.Hd, dim3(blocks_m, split), st);
+        launch_gemm<false>(o, p.Hd, dim3(blocks_o, split), st);
     }
     return check_launch("attention chunk (mfma)");
 }
