@@ -30,7 +30,7 @@
 //
 // Workspace layout of this family (Lp = Lq = L rounded up to 64, token p = rl*Lp + l):
 //   bias [H][Lq][Lp] float32 (times log2 e)
-//   q, k [rows][H][Lp][D] bf16;  g, o [rows*Lp][Hd] bf16;  vt [rows][H][Lp/32][D][32] bf16
+//   q, k, g, o [rows][H][Lp][D] bf16;  vt [rows][H][Lp/32][D][32] bf16
 //   prepared weights [(4*Hd + 32)][c] (+ [32][c_z] in row mode) bf16, their sums and offsets
 // Pad tokens (l in [L, Lp)) hold finite values everywhere; they are masked as keys.
 #include "ff_common.h"
@@ -152,17 +152,17 @@ size_t mfma_workspace(const Problem& p, int chunk, Workspace* ws, void* base) {
 //   wp[n][k] = bf16(scale * W[n][k] * gamma[k]);  sn[n] = sum_k wp[n][k];
 //   cn[n] = scale * sum_k W[n][k] * beta[k] (+ extra[n])
 struct PrepSeg {
-    const bf16_t* w;        // [rows][K]
-    const bf16_t* extra;    // [rows] added to cn, or NULL
-    int rows, rows_pad;     // rows_pad - rows zero rows follow
+    const bf16_t* w;              // [rows][K]
+    const bf16_t* extra;          // [rows] added to cn, or NULL
+    const bf16_t *gamma, *beta;   // [K]
+    bf16_t* wp;                   // output rows of this segment [rows_pad][K]
+    float *sn, *cn;               // [rows_pad]
+    int rows, rows_pad, K;        // rows_pad - rows zero rows follow
     float scale;
 };
 struct PrepArgs {
-    PrepSeg seg[5];
-    int nseg, K;
-    const bf16_t *gamma, *beta;
-    bf16_t* wp;
-    float *sn, *cn;
+    PrepSeg seg[6];
+    int nseg;
 };
 
 __global__ __launch_bounds__(256) void k_prep(PrepArgs a) {
@@ -177,35 +177,28 @@ __global__ __launch_bounds__(256) void k_prep(PrepArgs a) {
         base += a.seg[i].rows_pad;
     }
     if (sg < 0) return;
-    const bf16_t* wsrc = nullptr;
-    const bf16_t* extra = nullptr;
-    int rows = 0;
-    float scale = 0.f;
+    PrepSeg sgm = a.seg[0];
 #pragma unroll
-    for (int i = 0; i < 5; ++i)
-        if (i == sg) {
-            wsrc = a.seg[i].w;
-            extra = a.seg[i].extra;
-            rows = a.seg[i].rows;
-            scale = a.seg[i].scale;
-        }
-    const bool real = local < rows;
+    for (int i = 1; i < 6; ++i)
+        if (i == sg) sgm = a.seg[i];
+    const bool real = local < sgm.rows;
+    const int K = sgm.K;
     float sum = 0.f, cst = 0.f;
-    for (int k = lane; k < a.K; k += 64) {
+    for (int k = lane; k < K; k += 64) {
         float r = 0.f;
         if (real) {
-            const float wv = bf16_to_f32(wsrc[(size_t)local * a.K + k]) * scale;
-            r = bf16_round(wv * bf16_to_f32(a.gamma[k]));
-            cst += wv * bf16_to_f32(a.beta[k]);
+            const float wv = bf16_to_f32(sgm.w[(size_t)local * K + k]) * sgm.scale;
+            r = bf16_round(wv * bf16_to_f32(sgm.gamma[k]));
+            cst += wv * bf16_to_f32(sgm.beta[k]);
         }
-        a.wp[(size_t)n * a.K + k] = f32_to_bf16(r);
+        sgm.wp[(size_t)local * K + k] = f32_to_bf16(r);
         sum += r;
     }
     sum = wave_sum(sum);
     cst = wave_sum(cst);
     if (lane == 0) {
-        a.sn[n] = sum;
-        a.cn[n] = cst + ((real && extra) ? bf16_to_f32(extra[local]) : 0.f);
+        sgm.sn[local] = sum;
+        sgm.cn[local] = cst + ((real && sgm.extra) ? bf16_to_f32(sgm.extra[local]) : 0.f);
     }
 }
 
@@ -298,12 +291,19 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
         tok_rl[tt] = rl;
         tok_l[tt] = l;
         const bool valid = tile_ok[tt] && l < a.L;
-        const bf16_t* sp = PROJ ? a.src + ((int64_t)(a.r0 + rl) * a.sr + (int64_t)l * a.sl) * K
-                                : a.src + (size_t)p * K;
+        const bf16_t* sp = a.src + ((int64_t)(a.r0 + rl) * a.sr + (int64_t)l * a.sl) * K;
 #pragma unroll
         for (int s = 0; s < KC; ++s) {
             xa[tt][s].u = make_uint4(0, 0, 0, 0);
-            if (valid && (16 * s + 8 * hf) < K) xa[tt][s].u = ldg16(sp + 16 * s + 8 * hf);
+            const int f = 16 * s + 8 * hf;
+            if constexpr (PROJ) {
+                if (valid && f < K) xa[tt][s].u = ldg16(sp + f);
+            } else {
+                // gated context, head-major [row][head][l][d]
+                const int hh = (int)(((float)f + 0.5f) * a.invD);
+                if (valid && f < K)
+                    xa[tt][s].u = ldg16(a.src + ((size_t)(rl * a.H + hh) * a.Lp + l) * a.D + (f - hh * a.D));
+            }
         }
         mean[tt] = 0.f;
         rstd[tt] = 0.f;
@@ -464,11 +464,8 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
                 bf16_t *dst0 = nullptr, *dst1 = nullptr;   // features f0 .. f0+7 and f0+16 .. f0+23
                 if constexpr (PROJ) {
                     const int f0 = nb - kind * a.Hd + 8 * hf;
-                    if (kind == 3) {                     // gate: token-major [token][Hd]
-                        dst0 = a.g + (size_t)p * a.Hd + f0;
-                        dst1 = dst0 + 16;
-                    } else {                             // q, k: head-major [row][head][l][d]
-                        bf16_t* base = kind == 0 ? a.q : a.k;
+                    {                                    // q, k, gate: head-major [row][head][l][d]
+                        bf16_t* base = kind == 0 ? a.q : (kind == 1 ? a.k : a.g);
                         const int h0 = (int)(((float)f0 + 0.5f) * a.invD), h1 = (int)(((float)f0 + 16.5f) * a.invD);
                         dst0 = base + ((size_t)(rl * a.H + h0) * a.Lp + l) * a.D + (f0 - h0 * a.D);
                         dst1 = base + ((size_t)(rl * a.H + h1) * a.Lp + l) * a.D + (f0 + 16 - h1 * a.D);
@@ -746,20 +743,27 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
             l_tot = l_run[j] + other_half(l_run[j]);
         }
         const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-        const int qi = q0 + 32 * j + col;
-        if (row_ok && qi < a.L) {
-            const size_t t = ((size_t)rl * a.Lp + qi) * a.Hd + h * D;
+        const int qi = q0 + 32 * j + col;                       // < Lp
+        // gate and context are head-major [row][head][l][d]: the wave's 32 queries are one
+        // contiguous block of 64*D bytes
+        const size_t t = ((size_t)(rl * a.H + h) * a.Lp + qi) * D;
+        uint32_t pk[8];
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int e0 = 8 * g + 4 * hf;
-                if (e0 < D) {
-                    const uint2 gr = ldg8(a.g + t + e0);
-                    uint2 ov;
-                    ov.x = pack2(o_acc[j][4 * g] * inv * lo_f32(gr.x), o_acc[j][4 * g + 1] * inv * hi_f32(gr.x));
-                    ov.y = pack2(o_acc[j][4 * g + 2] * inv * lo_f32(gr.y), o_acc[j][4 * g + 3] * inv * hi_f32(gr.y));
-                    *reinterpret_cast<uint2*>(a.o + t + e0) = ov;
-                }
-            }
+        for (int g = 0; g < 4; ++g) {
+            const int e0 = 8 * g + 4 * hf;
+            uint2 gr = make_uint2(0, 0);
+            if (e0 < D) gr = ldg8(a.g + t + e0);
+            pk[2 * g] = pack2(o_acc[j][4 * g] * inv * lo_f32(gr.x), o_acc[j][4 * g + 1] * inv * hi_f32(gr.x));
+            pk[2 * g + 1] = pack2(o_acc[j][4 * g + 2] * inv * lo_f32(gr.y), o_acc[j][4 * g + 3] * inv * hi_f32(gr.y));
+        }
+        merge_halves(pk[0], pk[2]);      // lower half-wave: e 0..7, upper: e 8..15
+        merge_halves(pk[1], pk[3]);
+        merge_halves(pk[4], pk[6]);      // lower: e 16..23, upper: e 24..31
+        merge_halves(pk[5], pk[7]);
+        if (row_ok && qi < a.L) {
+            if (8 * hf < D) *reinterpret_cast<uint4*>(a.o + t + 8 * hf) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+            if (16 + 8 * hf < D)
+                *reinterpret_cast<uint4*>(a.o + t + 16 + 8 * hf) = make_uint4(pk[4], pk[5], pk[6], pk[7]);
         }
     }
 }
@@ -813,28 +817,32 @@ ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x
     const float qscale = kLog2e / sqrtf((float)p.d);
     const bool tri = p.mode == FF_TRI_START || p.mode == FF_TRI_END;
     {
+        const bf16_t *gm = (const bf16_t*)w.ln_g, *bt = (const bf16_t*)w.ln_b;
+        const int Hd = p.Hd, c = p.c;
         PrepArgs a{};
-        a.seg[0] = {(const bf16_t*)w.w_q, nullptr, p.Hd, p.Hd, qscale};
-        a.seg[1] = {(const bf16_t*)w.w_k, nullptr, p.Hd, p.Hd, 1.f};
-        a.seg[2] = {(const bf16_t*)w.w_v, nullptr, p.Hd, p.Hd, 1.f};
-        a.seg[3] = {(const bf16_t*)w.w_g, (const bf16_t*)w.b_g, p.Hd, p.Hd, 1.f};
-        a.seg[4] = {tri ? (const bf16_t*)w.w_b : nullptr, nullptr, tri ? p.H : 0, 32, kLog2e};
-        a.nseg = 5; a.K = p.c; a.gamma = (const bf16_t*)w.ln_g; a.beta = (const bf16_t*)w.ln_b;
-        a.wp = m.wp; a.sn = m.sn; a.cn = m.cn;
-        const int rows = 4 * p.Hd + 32;
+        auto seg = [&](int i, const void* wsrc, const void* extra, int rows, int rows_pad, int row0, float scale) {
+            a.seg[i] = {(const bf16_t*)wsrc, (const bf16_t*)extra, gm, bt, m.wp + (size_t)row0 * c, m.sn + row0,
+                        m.cn + row0, rows, rows_pad, c, scale};
+        };
+        seg(0, w.w_q, nullptr, Hd, Hd, 0, qscale);
+        seg(1, w.w_k, nullptr, Hd, Hd, Hd, 1.f);
+        seg(2, w.w_v, nullptr, Hd, Hd, 2 * Hd, 1.f);
+        seg(3, w.w_g, w.b_g, Hd, Hd, 3 * Hd, 1.f);
+        seg(4, tri ? w.w_b : nullptr, nullptr, tri ? p.H : 0, 32, 4 * Hd, kLog2e);
+        a.nseg = 5;
+        int rows = 4 * Hd + 32;
+        if (p.mode == FF_MSA_ROW) {     // the pair-bias projection of z, with its own LayerNorm
+            const int off = 4 * Hd + 32;
+            a.seg[5] = {(const bf16_t*)w.w_b, nullptr, (const bf16_t*)w.lnz_g, (const bf16_t*)w.lnz_b, m.zwp,
+                        m.sn + off, m.cn + off, p.H, 32, p.c_z, kLog2e};
+            a.nseg = 6;
+            rows += 32;
+        }
         Timed t(KK_PREP, st);
         hipLaunchKernelGGL(k_prep, dim3((rows + 3) / 4), dim3(256), 0, st, a);
     }
     if (p.mode == FF_MSA_ROW) {
         const int off = 4 * p.Hd + 32;
-        PrepArgs a{};
-        a.seg[0] = {(const bf16_t*)w.w_b, nullptr, p.H, 32, kLog2e};
-        a.nseg = 1; a.K = p.c_z; a.gamma = (const bf16_t*)w.lnz_g; a.beta = (const bf16_t*)w.lnz_b;
-        a.wp = m.zwp; a.sn = m.sn + off; a.cn = m.cn + off;
-        {
-            Timed t(KK_PREP, st);
-            hipLaunchKernelGGL(k_prep, dim3(8), dim3(256), 0, st, a);
-        }
         // bias[h][i][j] from the pair representation: "batch rows" i, tokens j
         GemmArgs g{};
         g.src = (const bf16_t*)z; g.sr = p.L; g.sl = 1; g.r0 = 0; g.rows = p.L; g.L = p.L; g.Lp = Lp; g.Lq = Lq;
