@@ -168,6 +168,8 @@ def main():
     ap.add_argument("--workload", default="c2_row_bf16_train")
     ap.add_argument("--no-others", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy 5 times (reference for HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
@@ -178,6 +180,14 @@ def main():
         sys.exit("bench.py: no GPU visible")
     import paper_2203_00854_amd as P
     P.lib()          # fails loudly if libff.so has not been built
+
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     case, desc, out, ms, kernels = time_workload(args.workload, args.steps, args.warmup)
     sp = case.spec

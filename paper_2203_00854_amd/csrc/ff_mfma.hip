@@ -427,7 +427,6 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) {
                 if (!tile_ok[tt]) continue;
-                const int p = tok[tt];
                 const int rl = tok_rl[tt], l = tok_l[tt];
                 float val[16];
 #pragma unroll
@@ -486,8 +485,8 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
 }
 
 // ====================================================================================
-// Attention.  Block = 4 wavefronts = 4 batch rows, same head, same 64 queries: the bias
-// tile [64 queries x 32 keys] is staged once per block in LDS and used by all four rows;
+// Attention.  Block = RB wavefronts = RB batch rows, same head, same 64 queries: the bias
+// tile [64 queries x 64 keys] is staged once per block in LDS and used by all its rows;
 // K rows and V^T columns go straight from global memory into operand registers, one tile
 // ahead of their use.
 //
@@ -509,8 +508,8 @@ struct AttnArgs {
 constexpr int kBiasPitch = 68;   // floats per LDS bias row (64 + 4 pad): conflict-free 16-byte reads
 constexpr float kRaise = 10.f;   // log2 units
 
-template <int D, bool HAS_BIAS>
-__global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
+template <int D, bool HAS_BIAS, int RB>
+__global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
     constexpr int PCX = D / 8;              // index of the 8-slot piece holding the two extra slots
     constexpr int KS = PCX / 2 + 1;         // 16-wide contraction steps
     constexpr int SX = PCX / 2, HX = PCX % 2;
@@ -520,11 +519,19 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
     float* s_bias = reinterpret_cast<float*>(smem);                                  // [2][64][kBiasPitch]
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, hf = lane >> 5;
-    const int rl_raw = blockIdx.z * 4 + wave;
+    // Work-groups are handed to the 8 XCDs round-robin and each XCD has its own L2.  The blocks
+    // that share K and V (same rows and head, different queries) get consecutive slots of ONE
+    // XCD, so K and V are fetched into one L2 once instead of once per query block.
+    const int nq = a.Lp >> 6;
+    const int n_blocks = nq * a.H * ((a.rows + RB - 1) / RB);
+    const int per_xcd = (n_blocks + 7) >> 3;
+    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (logical >= n_blocks) return;
+    const int rl_raw = (logical / (nq * a.H)) * RB + wave;
     const bool row_ok = rl_raw < a.rows;
     const int rl = row_ok ? rl_raw : a.rows - 1;
-    const int h = blockIdx.y;
-    const int q0 = blockIdx.x * 64;
+    const int h = (logical / nq) % a.H;
+    const int q0 = (logical % nq) * 64;
     const bool xlane = hf == HX;            // this lane carries the extra slots in step SX
 
     // ---- Q operand fragments: B operand, lane = query, 8 consecutive e
@@ -542,24 +549,30 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a) {
     }
 
     // ---- bias tile pipeline: [64 queries][64 keys]; thread loads rows b_row + 16 i, floats 4*b_c4 .. +3
+    // thread loads rows b_row + (RB*4) i, floats 4*b_c4 .. +3 (16 threads per row of 64 floats)
+    constexpr int BP = 16 / RB;                    // passes over the 64 rows
     const int b_row = tid >> 4, b_c4 = tid & 15;
     const float* bias_t = HAS_BIAS ? a.bias + ((size_t)h * a.Lq + q0 + b_row) * a.Lp + 4 * b_c4 : nullptr;
     float* s_bias_t = s_bias + (size_t)b_row * kBiasPitch + 4 * b_c4;
-    // (four named registers: an array captured by a lambda would be spilled to scratch)
+    // (named registers: an array captured by a lambda would be spilled to scratch)
     float4 bq0, bq1, bq2, bq3;
     auto load_bias = [&](int it) {
         const float* bp = bias_t + 64 * it;
         bq0 = *reinterpret_cast<const float4*>(bp);
-        bq1 = *reinterpret_cast<const float4*>(bp + (size_t)16 * a.Lp);
-        bq2 = *reinterpret_cast<const float4*>(bp + (size_t)32 * a.Lp);
-        bq3 = *reinterpret_cast<const float4*>(bp + (size_t)48 * a.Lp);
+        if constexpr (BP > 1) bq1 = *reinterpret_cast<const float4*>(bp + (size_t)(RB * 4) * a.Lp);
+        if constexpr (BP > 2) {
+            bq2 = *reinterpret_cast<const float4*>(bp + (size_t)(RB * 8) * a.Lp);
+            bq3 = *reinterpret_cast<const float4*>(bp + (size_t)(RB * 12) * a.Lp);
+        }
     };
     auto store_bias = [&](int buf) {
         float* sp = s_bias_t + (size_t)buf * 64 * kBiasPitch;
         *reinterpret_cast<float4*>(sp) = bq0;
-        *reinterpret_cast<float4*>(sp + 16 * kBiasPitch) = bq1;
-        *reinterpret_cast<float4*>(sp + 32 * kBiasPitch) = bq2;
-        *reinterpret_cast<float4*>(sp + 48 * kBiasPitch) = bq3;
+        if constexpr (BP > 1) *reinterpret_cast<float4*>(sp + RB * 4 * kBiasPitch) = bq1;
+        if constexpr (BP > 2) {
+            *reinterpret_cast<float4*>(sp + RB * 8 * kBiasPitch) = bq2;
+            *reinterpret_cast<float4*>(sp + RB * 12 * kBiasPitch) = bq3;
+        }
     };
     if constexpr (HAS_BIAS) {
         load_bias(0);
@@ -888,18 +901,27 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
     a.sr = p.sr; a.sl = p.sl; a.r0 = r0; a.rows = rows; a.L = p.L; a.Lp = Lp; a.Lq = Lq; a.H = p.H; a.Hd = p.Hd;
     {
         Timed t(KK_ATTN, st);
-        dim3 grid(Lq / 64, p.H, (rows + 3) / 4);
+        // batch rows per block (one wavefront each): 8 halve the bias traffic of 4
+        const int rb = rows >= 8 ? 8 : 4;
+        const int n_blocks = (Lq / 64) * p.H * ((rows + rb - 1) / rb);
+        dim3 grid(((n_blocks + 7) / 8) * 8);
         const size_t bias_bytes = (size_t)2 * 64 * kBiasPitch * 4;   // two [64][kBiasPitch] float tiles
-#define FF_ATTN(DD)                                                                                \
-    do {                                                                                           \
-        if (p.has_bias) hipLaunchKernelGGL((k_attn<DD, true>), grid, dim3(256), bias_bytes, st, a); \
-        else hipLaunchKernelGGL((k_attn<DD, false>), grid, dim3(256), 0, st, a);                   \
+#define FF_ATTN2(DD, RBV)                                                                                     \
+    do {                                                                                                      \
+        if (p.has_bias) hipLaunchKernelGGL((k_attn<DD, true, RBV>), grid, dim3(RBV * 64), bias_bytes, st, a); \
+        else hipLaunchKernelGGL((k_attn<DD, false, RBV>), grid, dim3(RBV * 64), 0, st, a);                   \
+    } while (0)
+#define FF_ATTN(DD)                  \
+    do {                             \
+        if (rb == 8) FF_ATTN2(DD, 8); \
+        else FF_ATTN2(DD, 4);        \
     } while (0)
         if (p.d == 8) FF_ATTN(8);
         else if (p.d == 16) FF_ATTN(16);
         else if (p.d == 24) FF_ATTN(24);
         else FF_ATTN(32);
 #undef FF_ATTN
+#undef FF_ATTN2
     }
 
     GemmArgs o{};
