@@ -27,9 +27,17 @@ sys.path.insert(0, ROOT)
 PEAK_MFMA_BF16_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs (see profiles/); None until such a run has been summarised there.
-TRAFFIC_BYTES = {}
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file
+# (profiles/traffic_*_hbm_counters.txt: KiB per dispatch, fetch scaled by 2.0 and write by 1.0,
+# the factors a plain 256 MiB copy gives); null for workloads without such a run.
+_KIB = 1024
+TRAFFIC_BYTES = {
+    ("c2_row_bf16_train", "k_prep"): int((293.1 * 2.0 + 553.0) * _KIB),
+    ("c2_row_bf16_train", "k_gemm<PROJ> (pair bias pass)"): int((8290.0 * 2.0 + 2048.0) * _KIB),
+    ("c2_row_bf16_train", "k_gemm<PROJ>"): int((10361.4 * 2.0 + 65536.0) * _KIB),
+    ("c2_row_bf16_train", "k_attn"): int((49280.0 * 2.0 + 16384.0) * _KIB),
+    ("c2_row_bf16_train", "k_gemm<OUT>"): int((8775.5 * 2.0 + 23484.4) * _KIB),
+}
 
 
 def counted_flop(sp):
