@@ -116,7 +116,7 @@ bool mfma_supported(const Problem& p) {
     if (p.dtype != FF_BF16) return false;
     if (p.c % 32 != 0 || p.c > 256) return false;
     if (p.Hd % 32 != 0 || p.Hd > 256) return false;
-    if (p.d % 8 != 0 || p.d > 32) return false;
+    if (p.d != 8 && p.d != 16 && p.d != 32) return false;
     if (p.L > 16384) return false;
     if (p.H > 32) return false;
     if (p.mode == FF_MSA_ROW && (p.c_z % 16 != 0 || p.c_z > 256)) return false;
@@ -203,11 +203,18 @@ __global__ __launch_bounds__(256) void k_prep(PrepArgs a) {
 }
 
 // ====================================================================================
-// GEMM with the whole contraction length (<= 256) resident: a wavefront owns 64 tokens (two
-// 32-token tiles) as register-resident operand fragments and sweeps over 32-feature tiles
-// of the weight matrix, which the block streams through LDS (double buffered).
+// GEMM with the whole contraction length (<= 256) resident: a wavefront owns TT 32-token
+// tiles as register-resident operand fragments and sweeps over 32-feature tiles of the
+// weight matrix.  The block streams those tiles through LDS with loads that write LDS
+// directly (global_load_lds_dwordx4: lane i of a wavefront deposits its 16 bytes at the
+// wave-uniform LDS base + 16 i), NS tiles per step, double buffered: the tiles of step i+1
+// are in flight while the matrix cores work on step i.
+//
+// LDS image of a tile: 32 rows of P = 2 KC 16-byte pieces, piece p of row r at slot
+// r P + (p ^ g(r)); g spreads 16 consecutive rows over the 16 slots of a 256-byte LDS line, so
+// the operand reads (lane = row, all lanes the same piece) are conflict free without padding.
 struct GemmArgs {
-    const bf16_t* src;     // PROJ: x or z (strided tokens); OUT: o [rows*Lp][K]
+    const bf16_t* src;     // PROJ: x or z (strided tokens); OUT: o [rows][H][Lp][D]
     int64_t sr, sl;        // token strides of src (PROJ) / out (OUT)
     int r0, rows, L, Lp, Lq;
     int K;                 // contraction length
@@ -216,6 +223,7 @@ struct GemmArgs {
     const float *sn, *cn;  // PROJ: per-feature sums / offsets
     const bf16_t* bvec;    // OUT: b_o [N]
     int Hd, H, D;
+    int dsh;               // log2(D), D in {8, 16, 32}
     float invD;            // 1 / D
     int nt_main;           // PROJ: 32-feature tiles of q|k|v|gate; tile nt_main is the pair-bias tile
     bf16_t *q, *k, *g, *vt;  // PROJ outputs
@@ -226,48 +234,114 @@ struct GemmArgs {
     int tiles_per_split;     // tiles per blockIdx.y
 };
 
-template <int KC, bool PROJ, int TT>
-__global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
-    constexpr int NT = 256;
-    constexpr int PITCH = KC * 32 + 16;                 // bytes per weight row in LDS (padded)
-    __shared__ __attribute__((aligned(16))) unsigned char s_w[2][32 * PITCH];
-    __shared__ __attribute__((aligned(16))) float s_stat[PROJ ? 4 * TT * 2 * 32 : 4];   // [wave][tt][mean|rstd][32]
-    constexpr int kMaxTiles = 33;                       // 4*Hd/32 + 1 with Hd <= 256
-    __shared__ __attribute__((aligned(16))) float s_sn[PROJ ? kMaxTiles * 32 : 4], s_cn[kMaxTiles * 32];
+typedef void __attribute__((address_space(3)))* lptr_t;
+constexpr int kWaitVmcnt0 = 0x0F70;      // s_waitcnt vmcnt(0), the other counters untouched
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, hf = lane >> 5;
+// Wait until at most n (rounded down to 8, 4, 2 or 0) vector-memory operations of this wavefront
+// are outstanding.  They complete in order, so with n = number of stores issued after a load this
+// waits for the load but not for those stores.
+__device__ __forceinline__ void wait_vmem_but_last(int n) {
+    if (n >= 8) __builtin_amdgcn_s_waitcnt(0x0F78);
+    else if (n >= 4) __builtin_amdgcn_s_waitcnt(0x0F74);
+    else if (n >= 2) __builtin_amdgcn_s_waitcnt(0x0F72);
+    else __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
+}
+
+// 16 bytes per lane from global memory straight into LDS at lds_base + 16 * lane (lds_base wave-uniform).
+// Written as assembly on purpose: the compiler would make every later LDS read wait for a load it
+// knows to write LDS, also those of the other half of the ring.  The kernel waits for these loads
+// itself (s_waitcnt vmcnt(0) before the barrier that publishes the tile).
+__device__ __forceinline__ void load16_to_lds(const void* gsrc, unsigned lds_base) {
+    const unsigned base = __builtin_amdgcn_readfirstlane(lds_base);
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gsrc), "s"(base) : "memory", "m0");
+}
+
+constexpr int kGemmWaves = 8;      // wavefronts per block: two per SIMD
+
+// dynamic LDS of k_gemm: weight ring, LayerNorm statistics, per-feature sums and offsets
+static size_t gemm_smem_bytes(int kc, int tt, int ns, int tiles_per_split) {
+    return (size_t)2 * ns * 32 * 2 * kc * 16 + (size_t)kGemmWaves * tt * 64 * 4 + (size_t)2 * tiles_per_split * 32 * 4;
+}
+
+template <int KC, bool PROJ, int TT, int NS>
+__global__ __launch_bounds__(kGemmWaves * 64, 2) void k_gemm(GemmArgs a) {
+    constexpr int NW = kGemmWaves;
+    constexpr int P = 2 * KC;                           // 16-byte pieces per weight row
+    constexpr int STAGE = 32 * P * 16;                  // bytes of one 32-feature tile in LDS
+    constexpr int RSH = P >= 16 ? 0 : (P == 8 ? 1 : 2);
+    constexpr int GM = (P >= 16 ? 16 : P) - 1;          // g(r) = (r >> RSH) & GM
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    unsigned char* s_w = smem;                                              // [2][NS][STAGE]
+    float* s_stat = reinterpret_cast<float*>(smem + 2 * NS * STAGE);        // [wave][tt][mean|rstd][32]
+    float* s_cn = s_stat + NW * TT * 64;                                     // [tiles_per_split][32]
+    float* s_sn = s_cn + a.tiles_per_split * 32;
+
+    const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int K = a.K;
     const int tiles_m = a.rows * (a.Lp >> 5);
-
-    // ---- weight tile loader: 32 rows x 2*KC 16-byte pieces, consecutive threads along a row
-    constexpr int PIECES = 32 * 2 * KC;
-    constexpr int PER_THREAD = (PIECES + NT - 1) / NT;
     const int ft_begin = a.ft_first + blockIdx.y * a.tiles_per_split;
     int ft_end = ft_begin + a.tiles_per_split;
     if (ft_end > a.ft_first + a.ft_count) ft_end = a.ft_first + a.ft_count;
-    uint4 wreg[PER_THREAD];
-    auto load_w = [&](int ft) {
+    if (ft_begin >= ft_end) return;     // (whole block)
+
+    // ---- token operand fragments, raw (issued first: they come from HBM)
+    Frag xa[TT][KC];
+    bool tile_ok[TT], tok_valid[TT];
+    int tok_rl[TT], tok_l[TT];            // batch row (wave-uniform) and position of this lane's token
+#pragma unroll
+    for (int tt = 0; tt < TT; ++tt) {
+        const int tg = (blockIdx.x * NW + wave) * TT + tt;
+        tile_ok[tt] = tg < tiles_m;
+        const int p = tg * 32 + col;
+        const int rl = p / a.Lp, l = p - rl * a.Lp;
+        tok_rl[tt] = __builtin_amdgcn_readfirstlane(rl);       // a tile lies inside one batch row
+        tok_l[tt] = l;
+        tok_valid[tt] = tile_ok[tt] && l < a.L;
+        const bf16_t* sp = a.src + ((int64_t)(a.r0 + rl) * a.sr + (int64_t)l * a.sl) * K;
+#pragma unroll
+        for (int s = 0; s < KC; ++s) {
+            xa[tt][s].u = make_uint4(0, 0, 0, 0);
+            const int f = 16 * s + 8 * hf;
+            if constexpr (PROJ) {
+                if (tok_valid[tt] && f < K) xa[tt][s].u = ldg16(sp + f);
+            } else {
+                // gated context, head-major [row][head][l][d]
+                const int hh = (int)(((float)f + 0.5f) * a.invD);
+                if (tok_valid[tt] && f < K)
+                    xa[tt][s].u = ldg16(a.src + ((size_t)(rl * a.H + hh) * a.Lp + l) * a.D + (f - hh * a.D));
+            }
+        }
+    }
+
+    // ---- weight tiles: each wavefront moves KC/NW chunks of 64 pieces (1 KiB) of a tile.
+    // Pieces beyond K re-read the last valid piece (the token operand is zero there).
+    constexpr int IPW = KC >= NW ? KC / NW : 1;
+    int goff[IPW];
+#pragma unroll
+    for (int j = 0; j < IPW; ++j) {
+        int chunk = j * NW + wave;
+        if (KC < NW && chunk >= KC) chunk = 0;
+        const int ps = chunk * 64 + lane, row = ps / P, pp = ps % P;
+        int kk = (pp ^ ((row >> RSH) & GM)) * 8;
+        if (kk > K - 8) kk = K - 8;
+        goff[j] = row * K + kk;
+    }
+    const unsigned s_w_lds = __builtin_amdgcn_readfirstlane((unsigned)(size_t)(lptr_t)s_w);
+    auto issue_tile = [&](int ft, int stage) {
         const bf16_t* wt = a.w + (size_t)ft * 32 * K;
 #pragma unroll
-        for (int j = 0; j < PER_THREAD; ++j) {
-            const int i = tid + j * NT;
-            const int f = i / (2 * KC), pc = i % (2 * KC);
-            uint4 val = make_uint4(0, 0, 0, 0);
-            if (i < PIECES && pc * 8 < K) val = ldg16(wt + (size_t)f * K + pc * 8);
-            wreg[j] = val;
+        for (int j = 0; j < IPW; ++j) {
+            const int chunk = j * NW + wave;
+            if (KC >= NW || chunk < KC) load16_to_lds(wt + goff[j], s_w_lds + stage * STAGE + chunk * 1024);
         }
     };
-    auto store_w = [&](int buf) {
+    // steps 0 and 1 fill the two halves of the ring
 #pragma unroll
-        for (int j = 0; j < PER_THREAD; ++j) {
-            const int i = tid + j * NT;
-            const int f = i / (2 * KC), pc = i % (2 * KC);
-            if (i < PIECES) *reinterpret_cast<uint4*>(&s_w[buf][f * PITCH + pc * 16]) = wreg[j];
-        }
-    };
-    if (ft_begin < ft_end) load_w(ft_begin);
+    for (int n = 0; n < 2 * NS; ++n)
+        if (ft_begin + n < ft_end) issue_tile(ft_begin + n, n);
     // per-feature sums / offsets of this block's tiles
-    for (int i = tid; i < (ft_end - ft_begin) * 32; i += NT) {
+    for (int i = tid; i < (ft_end - ft_begin) * 32; i += NW * 64) {
         if constexpr (PROJ) {
             s_sn[i] = a.sn[ft_begin * 32 + i];
             s_cn[i] = a.cn[ft_begin * 32 + i];
@@ -275,178 +349,208 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
             s_cn[i] = bf16_to_f32(a.bvec[ft_begin * 32 + i]);
         }
     }
+    // operand read: piece 2s + hf of row col sits at byte rd0 ^ (32 s) of its tile
+    const unsigned rd0 = (unsigned)col * (P * 16) + 16u * (unsigned)((((col >> RSH) & GM)) ^ hf);
 
-    // ---- token operand fragments, raw
-    Frag xa[TT][KC];
-    bool tile_ok[TT];
-    int tok[TT], tok_rl[TT], tok_l[TT];   // padded token index of this lane, its batch row and position
-    float mean[TT], rstd[TT];
+    // ---- epilogue addressing: every tensor of this family has Lp*Hd elements per batch row
+    const int LpD = a.Lp * a.D;
+    size_t row_base[TT];      // PROJ: element offset of the batch row in q, k, gate, v^T; OUT: of the token in out
+    int l0v[TT];
+    unsigned t_lane[TT];      // q, k, gate, out: this lane's part of the element offset (the same for every tile)
+    bool any_valid[TT];       // some token of the tile is a real one
+    // v^T: lane = feature col of a 32-feature tile that starts at a multiple of 32 inside v
+    const unsigned v_lane = (unsigned)(col >> a.dsh) * LpD + (unsigned)(col & (a.D - 1)) * 32 + 8 * hf;
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
-        const int tg = (blockIdx.x * 4 + wave) * TT + tt;
-        tile_ok[tt] = tg < tiles_m;
-        const int p = tg * 32 + col;
-        tok[tt] = p;
-        const int rl = p / a.Lp, l = p - rl * a.Lp;
-        tok_rl[tt] = rl;
-        tok_l[tt] = l;
-        const bool valid = tile_ok[tt] && l < a.L;
-        const bf16_t* sp = a.src + ((int64_t)(a.r0 + rl) * a.sr + (int64_t)l * a.sl) * K;
-#pragma unroll
-        for (int s = 0; s < KC; ++s) {
-            xa[tt][s].u = make_uint4(0, 0, 0, 0);
-            const int f = 16 * s + 8 * hf;
-            if constexpr (PROJ) {
-                if (valid && f < K) xa[tt][s].u = ldg16(sp + f);
-            } else {
-                // gated context, head-major [row][head][l][d]
-                const int hh = (int)(((float)f + 0.5f) * a.invD);
-                if (valid && f < K)
-                    xa[tt][s].u = ldg16(a.src + ((size_t)(rl * a.H + hh) * a.Lp + l) * a.D + (f - hh * a.D));
-            }
-        }
-        mean[tt] = 0.f;
-        rstd[tt] = 0.f;
+        if constexpr (PROJ) row_base[tt] = (size_t)tok_rl[tt] * a.H * LpD;
+        else row_base[tt] = (size_t)(((int64_t)(a.r0 + tok_rl[tt]) * a.sr + (int64_t)tok_l[tt] * a.sl) * a.N);
+        if constexpr (PROJ) t_lane[tt] = (unsigned)tok_l[tt] * a.D + (a.D >= 16 ? 8 * hf : hf * LpD);
+        else t_lane[tt] = 8 * hf;
+        const int l0 = __builtin_amdgcn_readfirstlane(tok_l[tt] - col);
+        l0v[tt] = l0 * a.D;                                                   // (l0 / 32) * D * 32
+        any_valid[tt] = tile_ok[tt] && l0 < a.L;
     }
-    if constexpr (PROJ) {
-        // LayerNorm statistics of the raw rows: two passes over the registers, float32
+    float nmean[TT], rstd[TT];          // minus mean, 1 / standard deviation of this lane's token
 #pragma unroll
-        for (int tt = 0; tt < TT; ++tt) {
-            float sum = 0.f;
-#pragma unroll
-            for (int s = 0; s < KC; ++s)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) sum = add_pair(xa[tt][s].w[i], sum);
-            sum += other_half(sum);
-            const float mu = sum / (float)K;
-            float sq = 0.f;
-#pragma unroll
-            for (int s = 0; s < KC; ++s) {
-                if (16 * s + 8 * hf < K) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const float d0 = lo_f32(xa[tt][s].w[i]) - mu, d1 = hi_f32(xa[tt][s].w[i]) - mu;
-                        sq += d0 * d0 + d1 * d1;
-                    }
-                }
-            }
-            sq += other_half(sq);
-            const bool valid = tile_ok[tt] && tok_l[tt] < a.L;
-            mean[tt] = valid ? mu : 0.f;
-            rstd[tt] = valid ? rsqrtf(sq / (float)K + a.eps) : 0.f;
-            if (hf == 0) {
-                s_stat[((wave * TT + tt) * 2 + 0) * 32 + col] = mean[tt];
-                s_stat[((wave * TT + tt) * 2 + 1) * 32 + col] = rstd[tt];
-            }
-        }
-    }
+    for (int tt = 0; tt < TT; ++tt) nmean[tt] = rstd[tt] = 0.f;
 
-    if (ft_begin < ft_end) store_w(0);
+    __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
     __syncthreads();
 
-    for (int ft = ft_begin; ft < ft_end; ++ft) {
-        const int buf = (ft - ft_begin) & 1;
-        if (ft + 1 < ft_end) load_w(ft + 1);
-        // kind of this feature tile: 0 q, 1 k, 2 v, 3 gate, 4 pair bias
-        const int kind = PROJ ? (ft < a.nt_main ? (ft * 32) / a.Hd : 4) : 0;
-        const bool tokens_by_features = PROJ && kind == 2;      // V: rows = tokens
-        f32x16 acc[TT];
+    // The two wavefronts of a SIMD (w and w + 4) work in opposite phase: between two barriers
+    // ("slot" i) the first runs the matrix-core part of step i and then its epilogue, the second
+    // the epilogue of step i-1 and then the matrix-core part of step i.  So one keeps the matrix
+    // core busy while the other keeps the vector unit busy, instead of both doing the same thing
+    // at the same time.  Both read step i's weight tiles within slot i.
+    const int n_it = (ft_end - ft_begin + NS - 1) / NS;
+    const bool epi_first = wave >= NW / 2;
+    bool need_stats = PROJ;
+    int n_stores = 0;                     // store instructions issued in this slot (a lower bound)
+    f32x16 acc[NS][TT];
+    for (int slot = 0; slot <= n_it; ++slot) {
+#pragma unroll 1
+      for (int sub = 0; sub < 2; ++sub) {
+        const bool do_mfma = (sub == 1) == epi_first;
+        const int it = do_mfma ? slot : (epi_first ? slot - 1 : slot);
+        if (it < 0 || it >= n_it) continue;
+        const int grp = it & 1;
+        const int ftb = ft_begin + it * NS;
+        if (do_mfma) {
 #pragma unroll
-        for (int tt = 0; tt < TT; ++tt)
+        for (int n = 0; n < NS; ++n) {
+            const int ft = ftb + n;
+            if (ft >= ft_end) continue;
+            const bool tokens_by_features = PROJ && ft < a.nt_main && ft * 32 >= 2 * a.Hd && ft * 32 < 3 * a.Hd;   // V: rows = tokens
+            const unsigned char* st = s_w + (grp * NS + n) * STAGE;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[tt][v] = 0.f;
-        if (tokens_by_features) {
+            for (int tt = 0; tt < TT; ++tt)
 #pragma unroll
-            for (int s = 0; s < KC; ++s) {
-                Frag wf;
-                wf.u = *reinterpret_cast<const uint4*>(&s_w[buf][col * PITCH + (2 * s + hf) * 16]);
+                for (int v = 0; v < 16; ++v) acc[n][tt][v] = 0.f;
+            // all operand reads of the tile first (they return in order and the matrix-core
+            // instructions follow them one by one); the fence keeps the compiler from moving
+            // each read down to its use, where its latency would be paid KC times
+            Frag wf[KC];
 #pragma unroll
-                for (int tt = 0; tt < TT; ++tt)
-                    acc[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[tt][s].v, wf.v, acc[tt], 0, 0, 0);
+            for (int s = 0; s < KC; ++s) wf[s].u = *reinterpret_cast<const uint4*>(st + (rd0 ^ (32u * s)));
+            __builtin_amdgcn_sched_barrier(0);
+            if (tokens_by_features) {
+#pragma unroll
+                for (int s = 0; s < KC; ++s)
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt)
+                        acc[n][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[tt][s].v, wf[s].v, acc[n][tt], 0, 0, 0);
+            } else {
+#pragma unroll
+                for (int s = 0; s < KC; ++s)
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt)
+                        acc[n][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[s].v, xa[tt][s].v, acc[n][tt], 0, 0, 0);
             }
-        } else {
+        }
+        continue;
+        }
+        if (need_stats) {
+            need_stats = false;
+            // LayerNorm statistics of the raw rows (two passes over the registers, float32): only
+            // the epilogue needs them
 #pragma unroll
-            for (int s = 0; s < KC; ++s) {
-                Frag wf;
-                wf.u = *reinterpret_cast<const uint4*>(&s_w[buf][col * PITCH + (2 * s + hf) * 16]);
+            for (int tt = 0; tt < TT; ++tt) {
+                float sum = 0.f;
 #pragma unroll
-                for (int tt = 0; tt < TT; ++tt)
-                    acc[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf.v, xa[tt][s].v, acc[tt], 0, 0, 0);
+                for (int s = 0; s < KC; ++s)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) sum = add_pair(xa[tt][s].w[i], sum);
+                sum += other_half(sum);
+                const float mu = sum / (float)K;
+                float sq = 0.f;
+#pragma unroll
+                for (int s = 0; s < KC; ++s) {
+                    if (16 * s + 8 * hf < K) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const float d0 = lo_f32(xa[tt][s].w[i]) - mu, d1 = hi_f32(xa[tt][s].w[i]) - mu;
+                            sq += d0 * d0 + d1 * d1;
+                        }
+                    }
+                }
+                sq += other_half(sq);
+                nmean[tt] = tok_valid[tt] ? -mu : 0.f;
+                rstd[tt] = tok_valid[tt] ? rsqrtf(sq / (float)K + a.eps) : 0.f;
+                if (hf == 0) {
+                    s_stat[((wave * TT + tt) * 2 + 0) * 32 + col] = -nmean[tt];
+                    s_stat[((wave * TT + tt) * 2 + 1) * 32 + col] = rstd[tt];
+                }
             }
         }
 
-        // ---- epilogue
-        if (tokens_by_features) {
-            // lane = feature (col), registers = tokens 8g + 4hf + e of the tile
-            const int nrow = ft * 32 + col;                     // row of the prepared matrix
-            const float sn = s_sn[(ft - ft_begin) * 32 + col], cn = s_cn[(ft - ft_begin) * 32 + col];
-            const int n = nrow - 2 * a.Hd;
-            const int h = (int)(((float)n + 0.5f) * a.invD), e = n - h * a.D;
+        // ---- epilogue.  Uniform quantities (tile kind, head, row) stay in scalar registers and
+        // form the base address of the stores; the per-lane offsets are the same for every tile.
 #pragma unroll
-            for (int tt = 0; tt < TT; ++tt) {
-                if (!tile_ok[tt]) continue;
-                const int rl = tok_rl[tt], l0 = tok_l[tt] - col;   // the tile lies inside one batch row
-                const float* st = s_stat + (wave * TT + tt) * 64;
-                uint32_t pk[8];
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const float4 mu = *reinterpret_cast<const float4*>(st + 8 * g + 4 * hf);
-                    const float4 rs = *reinterpret_cast<const float4*>(st + 32 + 8 * g + 4 * hf);
-                    const float y0 = rs.x * (acc[tt][4 * g] - mu.x * sn) + cn;
-                    const float y1 = rs.y * (acc[tt][4 * g + 1] - mu.y * sn) + cn;
-                    const float y2 = rs.z * (acc[tt][4 * g + 2] - mu.z * sn) + cn;
-                    const float y3 = rs.w * (acc[tt][4 * g + 3] - mu.w * sn) + cn;
-                    pk[2 * g] = pack2(y0, y1);
-                    pk[2 * g + 1] = pack2(y2, y3);
-                }
-                merge_halves(pk[0], pk[2]);
-                merge_halves(pk[1], pk[3]);
-                merge_halves(pk[4], pk[6]);
-                merge_halves(pk[5], pk[7]);
-                // v^T tiled by 32 keys: [row][head][l / 32][e][l % 32]
-                bf16_t* dst = a.vt + (((size_t)(rl * a.H + h) * (a.Lp >> 5) + (l0 >> 5)) * a.D + e) * 32 + 8 * hf;
-                *reinterpret_cast<uint4*>(dst) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-                *reinterpret_cast<uint4*>(dst + 16) = make_uint4(pk[4], pk[5], pk[6], pk[7]);
-            }
-        } else {
-            // lane = token (col), registers = features 8g + 4hf + e of the tile
+        for (int n = 0; n < NS; ++n) {
+            const int ft = ftb + n;
+            if (ft >= ft_end) continue;
+            // kind of this feature tile: 0 q, 1 k, 2 v, 3 gate, 4 pair bias
             const int nb = ft * 32;                              // first feature (row of w) of the tile
+            const int kind = !PROJ ? 0 : (ft >= a.nt_main ? 4 : (nb >= a.Hd) + (nb >= 2 * a.Hd) + (nb >= 3 * a.Hd));
+            const int so = (ft - ft_begin) * 32;
+            const int fb = nb - kind * a.Hd;                     // first feature inside its tensor
+            if (PROJ && kind == 2) {
+                // lane = feature (col), registers = tokens 8g + 4hf + e of the tile
+                const float sn = s_sn[so + col], cn = s_cn[so + col];
+                const size_t head_off = (size_t)(fb >> a.dsh) * LpD;
+#pragma unroll
+                for (int tt = 0; tt < TT; ++tt) {
+                    if (!tile_ok[tt]) continue;
+                    const float* stt = s_stat + (wave * TT + tt) * 64;
+                    uint32_t pk[8];
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const float4 mu = *reinterpret_cast<const float4*>(stt + 8 * g + 4 * hf);
+                        const float4 rs = *reinterpret_cast<const float4*>(stt + 32 + 8 * g + 4 * hf);
+                        const float y0 = rs.x * (acc[n][tt][4 * g] - mu.x * sn) + cn;
+                        const float y1 = rs.y * (acc[n][tt][4 * g + 1] - mu.y * sn) + cn;
+                        const float y2 = rs.z * (acc[n][tt][4 * g + 2] - mu.z * sn) + cn;
+                        const float y3 = rs.w * (acc[n][tt][4 * g + 3] - mu.w * sn) + cn;
+                        pk[2 * g] = pack2(y0, y1);
+                        pk[2 * g + 1] = pack2(y2, y3);
+                    }
+                    merge_halves(pk[0], pk[2]);
+                    merge_halves(pk[1], pk[3]);
+                    merge_halves(pk[4], pk[6]);
+                    merge_halves(pk[5], pk[7]);
+                    // v^T tiled by 32 keys: [row][head][l / 32][e][l % 32]
+                    bf16_t* tile = a.vt + (row_base[tt] + head_off + (size_t)l0v[tt]);
+                    *reinterpret_cast<uint4*>(tile + v_lane) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+                    *reinterpret_cast<uint4*>(tile + v_lane + 16) = make_uint4(pk[4], pk[5], pk[6], pk[7]);
+                    n_stores += 2;
+                }
+                continue;
+            }
+            // lane = token (col), registers = features 8g + 4hf + e of the tile
             float sv[16], cv[16];
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int o = (ft - ft_begin) * 32 + 8 * g + 4 * hf;
+                const int o = so + 8 * g + 4 * hf;
                 const float4 c4 = *reinterpret_cast<const float4*>(s_cn + o);
                 cv[4 * g] = c4.x; cv[4 * g + 1] = c4.y; cv[4 * g + 2] = c4.z; cv[4 * g + 3] = c4.w;
                 if constexpr (PROJ) {
                     const float4 s4 = *reinterpret_cast<const float4*>(s_sn + o);
                     sv[4 * g] = s4.x; sv[4 * g + 1] = s4.y; sv[4 * g + 2] = s4.z; sv[4 * g + 3] = s4.w;
-                } else {
-                    sv[4 * g] = sv[4 * g + 1] = sv[4 * g + 2] = sv[4 * g + 3] = 0.f;
                 }
+            }
+            // features fb + 8 hf .. +7 and fb + 16 + 8 hf .. +7 of this lane: uniform part of their place
+            size_t u0 = (size_t)nb, u1 = (size_t)nb + 16;              // OUT: [token][N]
+            bf16_t* base = a.out;
+            if constexpr (PROJ) {                                       // q, k, gate: [row][head][l][d]
+                u0 = (size_t)(fb >> a.dsh) * LpD + (fb & (a.D - 1));
+                u1 = (size_t)((fb + 16) >> a.dsh) * LpD + ((fb + 16) & (a.D - 1));
+                base = kind == 0 ? a.q : (kind == 1 ? a.k : a.g);
             }
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) {
                 if (!tile_ok[tt]) continue;
-                const int rl = tok_rl[tt], l = tok_l[tt];
                 float val[16];
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    float t;
-                    if constexpr (PROJ) {
-                        t = rstd[tt] * (acc[tt][v] - mean[tt] * sv[v]) + cv[v];
-                        if (kind == 3) t = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-t * kLog2e));
-                    } else {
-                        t = acc[tt][v] + cv[v];
-                    }
-                    val[v] = t;
+                    if constexpr (PROJ) val[v] = rstd[tt] * (acc[n][tt][v] + nmean[tt] * sv[v]) + cv[v];
+                    else val[v] = acc[n][tt][v] + cv[v];
+                }
+                if (PROJ && kind == 3) {
+                    asm volatile("");       // a real branch: the other tile kinds must not pay for the sigmoid
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) val[v] = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-val[v] * kLog2e));
                 }
                 if (PROJ && kind == 4) {
                     // pair bias: feature = head, token (rl, l) = pair (q, k)
-                    const size_t qk = (size_t)(a.r0 + rl) * a.Lp + l;
+                    const size_t plane = (size_t)a.Lq * a.Lp;
+                    size_t qk = (size_t)(a.r0 + tok_rl[tt]) * a.Lp + tok_l[tt] + 4 * hf * plane;
+                    int hlim = a.H - 4 * hf;
+                    // (keeps the 16 addresses and store masks out of the registers of the main loop)
+                    asm volatile("" : "+v"(qk), "+v"(hlim));
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
-                        const int h = 8 * (v >> 2) + 4 * hf + (v & 3);
-                        if (h < a.H) a.bias[(size_t)h * a.Lq * a.Lp + qk] = val[v];
+                        const int hu = 8 * (v >> 2) + (v & 3);           // head of the lower half-wave
+                        if (hu < hlim) a.bias[qk + hu * plane] = val[v];
                     }
                     continue;
                 }
@@ -460,27 +564,29 @@ __global__ __launch_bounds__(256) void k_gemm(GemmArgs a) {
                 merge_halves(pk[1], pk[3]);
                 merge_halves(pk[4], pk[6]);
                 merge_halves(pk[5], pk[7]);
-                bf16_t *dst0 = nullptr, *dst1 = nullptr;   // features f0 .. f0+7 and f0+16 .. f0+23
-                if constexpr (PROJ) {
-                    const int f0 = nb - kind * a.Hd + 8 * hf;
-                    {                                    // q, k, gate: head-major [row][head][l][d]
-                        bf16_t* base = kind == 0 ? a.q : (kind == 1 ? a.k : a.g);
-                        const int h0 = (int)(((float)f0 + 0.5f) * a.invD), h1 = (int)(((float)f0 + 16.5f) * a.invD);
-                        dst0 = base + ((size_t)(rl * a.H + h0) * a.Lp + l) * a.D + (f0 - h0 * a.D);
-                        dst1 = base + ((size_t)(rl * a.H + h1) * a.Lp + l) * a.D + (f0 + 16 - h1 * a.D);
-                    }
-                } else if (l < a.L) {
-                    dst0 = a.out + ((int64_t)(a.r0 + rl) * a.sr + (int64_t)l * a.sl) * a.N + nb + 8 * hf;
-                    dst1 = dst0 + 16;
+                if (PROJ || tok_valid[tt]) {
+                    bf16_t* rowp = base + row_base[tt];
+                    *reinterpret_cast<uint4*>(rowp + u0 + t_lane[tt]) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+                    *reinterpret_cast<uint4*>(rowp + u1 + t_lane[tt]) = make_uint4(pk[4], pk[5], pk[6], pk[7]);
                 }
-                if (dst0) {
-                    *reinterpret_cast<uint4*>(dst0) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-                    *reinterpret_cast<uint4*>(dst1) = make_uint4(pk[4], pk[5], pk[6], pk[7]);
-                }
+                if (PROJ || any_valid[tt]) n_stores += 2;     // (wave-uniform: the instructions were issued)
             }
         }
-        if (ft + 1 < ft_end) store_w(buf ^ 1);
+      }
+        if (slot >= n_it) break;
+        // Order of this wavefront's memory operations: ... L(i+1), S, L(i+2), S, ... (L = tile loads
+        // of a step, S = the stores of one slot).  The next slot needs L(slot+1): everything but
+        // the stores issued after it, those of this slot, must have completed.  After the barrier
+        // all wavefronts have their share of L(slot+1) in LDS and have finished reading this
+        // slot's half of the ring, which the loads of step slot+2 then overwrite.
+        wait_vmem_but_last(__builtin_amdgcn_readfirstlane(n_stores));
         __syncthreads();
+#pragma unroll
+        for (int n = 0; n < NS; ++n) {
+            const int ft = ft_begin + (slot + 2) * NS + n;
+            if (ft < ft_end) issue_tile(ft, (slot & 1) * NS + n);
+        }
+        n_stores = 0;
     }
 }
 
@@ -783,32 +889,46 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
 
 // ====================================================================================
 // host side
-// token tiles per wavefront: two halve the LDS traffic per MFMA, one keeps enough registers free for
-// two or more wavefronts per SIMD when the contraction is long
+// token tiles per wavefront: two halve the LDS traffic per MFMA, one keeps the register count at
+// two wavefronts per SIMD when the contraction is long
 template <bool PROJ>
-static int gemm_tt(int K) { return (PROJ && K > 64) ? 1 : 2; }
+static int gemm_tt(int K) { return K > 128 ? 1 : 2; }
+constexpr int kGemmNS = 2;      // weight tiles per pipeline step
 
 template <bool PROJ>
-static int gemm_blocks_m(int tiles_m, int K) { return (tiles_m + 4 * gemm_tt<PROJ>(K) - 1) / (4 * gemm_tt<PROJ>(K)); }
+static int gemm_blocks_m(int tiles_m, int K) {
+    const int per_block = kGemmWaves * gemm_tt<PROJ>(K);
+    return (tiles_m + per_block - 1) / per_block;
+}
+
+template <int KC, bool PROJ, int TT>
+static void launch_gemm_inst(const GemmArgs& a, dim3 grid, hipStream_t st) {
+    const size_t smem = gemm_smem_bytes(KC, TT, kGemmNS, a.tiles_per_split);
+    static bool attr_set = false;          // more than 64 KiB of dynamic LDS has to be asked for once
+    if (!attr_set) {
+        hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<KC, PROJ, TT, kGemmNS>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((k_gemm<KC, PROJ, TT, kGemmNS>), grid, dim3(kGemmWaves * 64), smem, st, a);
+}
 
 template <bool PROJ>
 static void launch_gemm(const GemmArgs& a, int K, dim3 grid, hipStream_t st) {
     const int kc = K / 16;
     if (gemm_tt<PROJ>(K) == 1) {
-        if (kc <= 8) hipLaunchKernelGGL((k_gemm<8, PROJ, 1>), grid, dim3(256), 0, st, a);
-        else hipLaunchKernelGGL((k_gemm<16, PROJ, 1>), grid, dim3(256), 0, st, a);
+        launch_gemm_inst<16, PROJ, 1>(a, grid, st);
     } else {
-        if (kc <= 2) hipLaunchKernelGGL((k_gemm<2, PROJ, 2>), grid, dim3(256), 0, st, a);
-        else if (kc <= 4) hipLaunchKernelGGL((k_gemm<4, PROJ, 2>), grid, dim3(256), 0, st, a);
-        else if (kc <= 8) hipLaunchKernelGGL((k_gemm<8, PROJ, 2>), grid, dim3(256), 0, st, a);
-        else hipLaunchKernelGGL((k_gemm<16, PROJ, 2>), grid, dim3(256), 0, st, a);
+        if (kc <= 2) launch_gemm_inst<2, PROJ, 2>(a, grid, st);
+        else if (kc <= 4) launch_gemm_inst<4, PROJ, 2>(a, grid, st);
+        else launch_gemm_inst<8, PROJ, 2>(a, grid, st);
     }
 }
 
-// blocks along the feature axis: enough blocks to fill 256 CUs about twice
+// blocks along the feature axis: at least one block (eight wavefronts) per compute unit
 static int pick_split(int blocks_m, int tiles_n) {
     int split = 1;
-    while (blocks_m * split < 512 && split < tiles_n) ++split;
+    while (blocks_m * split < 256 && split < tiles_n) ++split;
     while (tiles_n % split != 0) ++split;      // equal shares
     return split;
 }
@@ -817,7 +937,7 @@ static GemmArgs proj_args(const Problem& p, const MfmaWs& m, const Workspace& ws
     const int Lp = round_up(p.L, 64), Lq = round_up(p.L, 64);
     GemmArgs g{};
     g.sr = p.sr; g.sl = p.sl; g.L = p.L; g.Lp = Lp; g.Lq = Lq; g.K = p.c; g.eps = p.eps;
-    g.w = m.wp; g.sn = m.sn; g.cn = m.cn; g.Hd = p.Hd; g.H = p.H; g.D = p.d; g.invD = 1.f / (float)p.d;
+    g.w = m.wp; g.sn = m.sn; g.cn = m.cn; g.Hd = p.Hd; g.H = p.H; g.D = p.d; g.invD = 1.f / (float)p.d; g.dsh = p.d == 8 ? 3 : (p.d == 16 ? 4 : 5);
     g.nt_main = 4 * p.Hd / 32;
     g.q = m.q; g.k = m.k; g.g = m.g; g.vt = m.vt; g.bias = ws.bias;
     return g;
@@ -860,7 +980,7 @@ ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x
         GemmArgs g{};
         g.src = (const bf16_t*)z; g.sr = p.L; g.sl = 1; g.r0 = 0; g.rows = p.L; g.L = p.L; g.Lp = Lp; g.Lq = Lq;
         g.K = p.c_z; g.eps = p.eps; g.w = m.zwp; g.sn = m.sn + off; g.cn = m.cn + off;
-        g.Hd = p.Hd; g.H = p.H; g.D = p.d; g.invD = 1.f / (float)p.d; g.nt_main = 0; g.bias = ws.bias;
+        g.Hd = p.Hd; g.H = p.H; g.D = p.d; g.invD = 1.f / (float)p.d; g.dsh = p.d == 8 ? 3 : (p.d == 16 ? 4 : 5); g.nt_main = 0; g.bias = ws.bias;
         g.ft_first = 0; g.ft_count = 1; g.tiles_per_split = 1;
         const int blocks_m = gemm_blocks_m<true>(p.L * (Lp / 32), p.c_z);
         Timed t(KK_BIAS, st);
@@ -918,7 +1038,6 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
     } while (0)
         if (p.d == 8) FF_ATTN(8);
         else if (p.d == 16) FF_ATTN(16);
-        else if (p.d == 24) FF_ATTN(24);
         else FF_ATTN(32);
 #undef FF_ATTN
 #undef FF_ATTN2
@@ -927,7 +1046,7 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
     GemmArgs o{};
     o.src = m.o; o.sr = p.sr; o.sl = p.sl; o.r0 = r0; o.rows = rows; o.L = p.L; o.Lp = Lp; o.Lq = Lq;
     o.K = p.Hd; o.w = (const bf16_t*)w.w_o; o.bvec = (const bf16_t*)w.b_o;
-    o.Hd = p.Hd; o.H = p.H; o.D = p.d; o.invD = 1.f / (float)p.d; o.out = (bf16_t*)out; o.N = p.c;
+    o.Hd = p.Hd; o.H = p.H; o.D = p.d; o.invD = 1.f / (float)p.d; o.dsh = p.d == 8 ? 3 : (p.d == 16 ? 4 : 5); o.out = (bf16_t*)out; o.N = p.c;
     {
         const int tiles_n = o.N / 32;
         const int blocks_o = gemm_blocks_m<false>(tiles_m, p.Hd);
