@@ -613,6 +613,7 @@ struct AttnArgs {
 
 constexpr int kBiasPitch = 68;   // floats per LDS bias row (64 + 4 pad): conflict-free 16-byte reads
 constexpr float kRaise = 10.f;   // log2 units
+constexpr float kOver = 1048576.f;   // 2^20: partial denominator (16 keys) that triggers a raise of the reference
 
 template <int D, bool HAS_BIAS, int RB>
 __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
@@ -765,50 +766,69 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
 #pragma unroll
             for (int c = 0; c < 2; ++c) vb[c].u = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
         }
-        float tmax[2];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
+        // sa holds s - m_ref (masked keys: -inf).  With the denominator in the vector unit
+        // (D = 32) only the first tile takes the maximum; later tiles are exponentiated as they
+        // are and a partial denominator beyond kOver (some s - m_ref above about 16) sends the
+        // query tile through raise_ref afterwards: rare, and the common tile saves the sixteen
+        // max operations per query.  With the denominator on the matrix core (D < 32) the
+        // maximum is taken for every tile, because there the overflow would already be accumulated.
+        auto tile_max = [&](int j) -> float {
             float mx = sa[j][0];
 #pragma unroll
             for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sa[j][v]);
-            tmax[j] = fmaxf(mx, other_half(mx));
-        }
-        // sa holds s - m_ref (masked keys: -inf).  Raise the reference where needed.
-        if (first || __any(tmax[0] > kRaise || tmax[1] > kRaise)) {
+            return fmaxf(mx, other_half(mx));
+        };
+        auto raise_ref = [&](int j, float tmax, bool always) {
+            const bool raise = always || tmax > kRaise;
+            const float new_ref = raise ? bf16_round(m_ref[j] + tmax) : m_ref[j];
+            const float delta = new_ref - m_ref[j];
+            m_ref[j] = new_ref;
+            const float sc = first ? 1.f : __builtin_amdgcn_exp2f(-delta);   // first: nothing accumulated yet
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const bool raise = first || tmax[j] > kRaise;
-                const float new_ref = raise ? bf16_round(m_ref[j] + tmax[j]) : m_ref[j];
-                const float delta = new_ref - m_ref[j];
-                m_ref[j] = new_ref;
-                const float sc = first ? 1.f : __builtin_amdgcn_exp2f(-delta);   // nothing accumulated yet
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    o_acc[j][v] *= sc;
-                    sa[j][v] -= delta;
-                }
-                if (sn_live) {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) sn[j][v] -= delta;
-                }
-                l_run[j] *= sc;
-                if (xlane) qf[j][SX].w[0] = pack2(-new_ref, 1.f);
+            for (int v = 0; v < 16; ++v) {
+                o_acc[j][v] *= sc;
+                sa[j][v] -= delta;
             }
-            first = false;
+            if (sn_live) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) sn[j][v] -= delta;
+            }
+            l_run[j] *= sc;
+            if (xlane) qf[j][SX].w[0] = pack2(-new_ref, 1.f);
+        };
+        if (ONES_ROW || first) {
+            const float t0 = tile_max(0), t1 = tile_max(1);
+            if (first || __any(t0 > kRaise || t1 > kRaise)) {
+                raise_ref(0, t0, first);
+                raise_ref(1, t1, first);
+                first = false;
+            }
         }
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             Frag pf[2];
+            float lt = 0.f;
+            auto exponentiate = [&]() {
+                lt = 0.f;
 #pragma unroll
-            for (int c = 0; c < 2; ++c)
+                for (int c = 0; c < 2; ++c)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float p0 = __builtin_amdgcn_exp2f(sa[j][8 * c + 2 * i]);
-                    const float p1 = __builtin_amdgcn_exp2f(sa[j][8 * c + 2 * i + 1]);
-                    pf[c].w[i] = pack2(p0, p1);
-                    // denominator from the rounded weights, two per instruction
-                    if constexpr (!ONES_ROW) l_run[j] = add_pair(pf[c].w[i], l_run[j]);
+                    for (int i = 0; i < 4; ++i) {
+                        const float p0 = __builtin_amdgcn_exp2f(sa[j][8 * c + 2 * i]);
+                        const float p1 = __builtin_amdgcn_exp2f(sa[j][8 * c + 2 * i + 1]);
+                        pf[c].w[i] = pack2(p0, p1);
+                        // denominator from the rounded weights, two per instruction
+                        if constexpr (!ONES_ROW) lt = add_pair(pf[c].w[i], lt);
+                    }
+            };
+            exponentiate();
+            if constexpr (!ONES_ROW) {
+                if (__any(!(lt <= kOver))) {
+                    raise_ref(j, tile_max(j), false);
+                    exponentiate();
                 }
+                l_run[j] += lt;
+            }
 #pragma unroll
             for (int c = 0; c < 2; ++c)
                 o_acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb[c].v, pf[c].v, o_acc[j], 0, 0, 0);

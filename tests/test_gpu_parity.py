@@ -190,6 +190,36 @@ def test_ragged_shapes(dtype, mode, n_a, n_b, c, H, d, c_z, mask):
     check(to_np(run_case(case)), oracle_case(case), dtype, case.spec.name)
 
 
+@pytest.mark.parametrize("mode", [COL, TS])
+def test_reference_is_raised_when_late_keys_dominate(mode):
+    """The keys of the last two 32-key tiles beat everything before them by tens of log2 units
+    for half of the queries (and lose by as much for the other half).  The kernel's running softmax
+    reference, fixed by the first tile, has to be raised when those keys arrive.  The tokens of a
+    group differ only by small noise, so the rounding of q and k is common to a group and the
+    usual tolerance holds."""
+    L, late = 160, 96
+    n_a, n_b = (L, 6) if mode == COL else (L, L)      # the pair representation is square
+    case = I.make_case(small_spec(mode, n_a, n_b, 64, 2, 32, dtype="bf16"))
+    key = I.stream_key(I.SEED, "late_keys", "x")
+    v = I.normal(key, 64)
+    noise = I.normal(I.stream_key(I.SEED, "late_keys", "noise"), n_a * n_b * 64).reshape(n_a, n_b, 64)
+    sign = np.where(np.arange(L) < late, -1.0, 1.0)
+    sign = sign[:, None, None] if mode == COL else sign[None, :, None]
+    case.x = I.to_storage(sign * v + 0.05 * noise, "bf16")
+    for name in ("w_q", "w_k"):
+        case.weights[name] = I.to_storage(5.0 * I.widen(case.weights[name]).astype(np.float64), "bf16")
+    # the jump really is there: logits of the late group minus logits of the early group
+    x, z, m, w = f64_inputs(case)
+    xh = O.layer_norm(x, w["ln_g"], w["ln_b"], case.spec.ln_eps)
+    tok = xh[:, 0] if mode == COL else xh[0]                  # [L, c]: one batch row
+    q = (tok @ w["w_q"].T).reshape(L, 2, 32)
+    k = (tok @ w["w_k"].T).reshape(L, 2, 32)
+    s = np.einsum("qhe,khe->hqk", q, k) / np.sqrt(32.0) * np.log2(np.e)
+    jump = s[:, :, late:].max(axis=2) - s[:, :, :32].max(axis=2)
+    assert jump.max() > 30.0
+    check(to_np(run_case(case)), oracle_case(case), "bf16", f"late keys dominate, mode {mode}")
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("mode,n_a,n_b,c,H,d,c_z,mask,chunk", [
     (ROW, 7, 70, 64, 2, 32, 24, "tail:5", 3),
