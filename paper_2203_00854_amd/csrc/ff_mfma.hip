@@ -754,10 +754,13 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) sa[j][v] = 0.f;
             }
-#pragma unroll
-            for (int s = 0; s < KS; ++s)
-                sa[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb[s].v, qf[j][s].v, sa[j], 0, 0, 0);
         }
+        // the two query tiles alternate, so that no matrix-core instruction waits for the one before it
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                sa[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kb[s].v, qf[j][s].v, sa[j], 0, 0, 0);
         return true;
     };
     // exponentials of tile sa and O^T update; sn is the tile already issued with the old reference
@@ -911,13 +914,12 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
 // host side
 // token tiles per wavefront: two halve the LDS traffic per MFMA, one keeps the register count at
 // two wavefronts per SIMD when the contraction is long
-template <bool PROJ>
-static int gemm_tt(int K) { return K > 128 ? 1 : 2; }
+// (and one when two would leave compute units without a block)
+static int gemm_tt(int K, int tiles_m) { return (K > 128 || tiles_m < 2 * kGemmWaves * 256) ? 1 : 2; }
 constexpr int kGemmNS = 2;      // weight tiles per pipeline step
 
-template <bool PROJ>
 static int gemm_blocks_m(int tiles_m, int K) {
-    const int per_block = kGemmWaves * gemm_tt<PROJ>(K);
+    const int per_block = kGemmWaves * gemm_tt(K, tiles_m);
     return (tiles_m + per_block - 1) / per_block;
 }
 
@@ -936,8 +938,11 @@ static void launch_gemm_inst(const GemmArgs& a, dim3 grid, hipStream_t st) {
 template <bool PROJ>
 static void launch_gemm(const GemmArgs& a, int K, dim3 grid, hipStream_t st) {
     const int kc = K / 16;
-    if (gemm_tt<PROJ>(K) == 1) {
-        launch_gemm_inst<16, PROJ, 1>(a, grid, st);
+    if (gemm_tt(K, a.rows * (a.Lp >> 5)) == 1) {
+        if (kc <= 2) launch_gemm_inst<2, PROJ, 1>(a, grid, st);
+        else if (kc <= 4) launch_gemm_inst<4, PROJ, 1>(a, grid, st);
+        else if (kc <= 8) launch_gemm_inst<8, PROJ, 1>(a, grid, st);
+        else launch_gemm_inst<16, PROJ, 1>(a, grid, st);
     } else {
         if (kc <= 2) launch_gemm_inst<2, PROJ, 2>(a, grid, st);
         else if (kc <= 4) launch_gemm_inst<4, PROJ, 2>(a, grid, st);
@@ -1002,7 +1007,7 @@ ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x
         g.K = p.c_z; g.eps = p.eps; g.w = m.zwp; g.sn = m.sn + off; g.cn = m.cn + off;
         g.Hd = p.Hd; g.H = p.H; g.D = p.d; g.invD = 1.f / (float)p.d; g.dsh = p.d == 8 ? 3 : (p.d == 16 ? 4 : 5); g.nt_main = 0; g.bias = ws.bias;
         g.ft_first = 0; g.ft_count = 1; g.tiles_per_split = 1;
-        const int blocks_m = gemm_blocks_m<true>(p.L * (Lp / 32), p.c_z);
+        const int blocks_m = gemm_blocks_m(p.L * (Lp / 32), p.c_z);
         Timed t(KK_BIAS, st);
         launch_gemm<true>(g, p.c_z, dim3(blocks_m, 1), st);
     } else if (tri && ws.chunk < p.R) {
@@ -1010,7 +1015,7 @@ ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x
         GemmArgs g = proj_args(p, m, ws);
         g.src = (const bf16_t*)x; g.r0 = 0; g.rows = p.R;
         g.ft_first = g.nt_main; g.ft_count = 1; g.tiles_per_split = 1;
-        const int blocks_m = gemm_blocks_m<true>(p.R * (Lp / 32), p.c);
+        const int blocks_m = gemm_blocks_m(p.R * (Lp / 32), p.c);
         Timed t(KK_BIAS, st);
         launch_gemm<true>(g, p.c, dim3(blocks_m, 1), st);
     }
@@ -1023,7 +1028,7 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
     const MfmaWs m = split_ws(p, ws.chunk, ws);
     const bool tri = p.mode == FF_TRI_START || p.mode == FF_TRI_END;
     const int tiles_m = rows * (Lp / 32);
-    const int blocks_m = gemm_blocks_m<true>(tiles_m, p.c);
+    const int blocks_m = gemm_blocks_m(tiles_m, p.c);
     {
         GemmArgs g = proj_args(p, m, ws);
         g.src = (const bf16_t*)x; g.r0 = r0; g.rows = rows;
@@ -1069,7 +1074,7 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
     o.Hd = p.Hd; o.H = p.H; o.D = p.d; o.invD = 1.f / (float)p.d; o.dsh = p.d == 8 ? 3 : (p.d == 16 ? 4 : 5); o.out = (bf16_t*)out; o.N = p.c;
     {
         const int tiles_n = o.N / 32;
-        const int blocks_o = gemm_blocks_m<false>(tiles_m, p.Hd);
+        const int blocks_o = gemm_blocks_m(tiles_m, p.Hd);
         const int split = pick_split(blocks_o, tiles_n);
         o.ft_first = 0; o.ft_count = tiles_n;
         o.tiles_per_split = tiles_n / split;
