@@ -35,6 +35,8 @@
 // Pad tokens (l in [L, Lp)) hold finite values everywhere; they are masked as keys.
 #include "ff_common.h"
 
+#include <type_traits>
+
 namespace ff {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
@@ -88,7 +90,7 @@ static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 struct MfmaWs {
     bf16_t *q, *k, *g, *vt, *o;
     bf16_t *wp, *zwp;      // prepared weights: main [(4Hd+32)][c], row-mode bias [32][c_z]
-    float *sn, *cn;        // [(4Hd+32) + 32] row sums of wp / zwp, and output offsets
+    uint4* aug;            // [(4Hd+32) + 32] per row of wp / zwp: its sum and output offset as bf16 pairs (see k_prep)
 };
 
 static MfmaWs split_ws(const Problem& p, int chunk, const Workspace& ws) {
@@ -106,9 +108,7 @@ static MfmaWs split_ws(const Problem& p, int chunk, const Workspace& ws) {
     pr += align256(rows_main * p.c * 2);
     m.zwp = (bf16_t*)pr;
     pr += align256((size_t)32 * (p.c_z > 0 ? p.c_z : 1) * 2);
-    m.sn = (float*)pr;
-    pr += align256((rows_main + 32) * 4);
-    m.cn = (float*)pr;
+    m.aug = (uint4*)pr;
     return m;
 }
 
@@ -141,7 +141,7 @@ size_t mfma_workspace(const Problem& p, int chunk, Workspace* ws, void* base) {
     ws->prep = b + off;
     const size_t rows_main = 4 * (size_t)p.Hd + 32;
     off += align256(rows_main * p.c * 2) + align256((size_t)32 * (p.c_z > 0 ? p.c_z : 1) * 2) +
-           2 * align256((rows_main + 32) * 4);
+           align256((rows_main + 32) * 16);
     ws->total = off;
     ws->chunk = chunk;
     return off;
@@ -151,12 +151,16 @@ size_t mfma_workspace(const Problem& p, int chunk, Workspace* ws, void* base) {
 // Weight preparation: one wavefront per output row n of the merged matrix.
 //   wp[n][k] = bf16(scale * W[n][k] * gamma[k]);  sn[n] = sum_k wp[n][k];
 //   cn[n] = scale * sum_k W[n][k] * beta[k] (+ extra[n])
+// sn and cn leave as one extra 8-slot piece of the contraction per row, split into bf16 pairs
+// (hi + lo): [sn_hi, sn_lo, sn_hi, cn_hi, cn_lo, cn_hi, 0, 0].  Against the token's piece
+// [m_hi, m_hi, m_lo, r_hi, r_hi, r_lo, 0, 0] (m = -mean, r = standard deviation) the matrix core
+// adds -mean*sn + r*cn to x W'^T, so that the GEMM epilogue is one multiplication by 1/r.
 struct PrepSeg {
     const bf16_t* w;              // [rows][K]
     const bf16_t* extra;          // [rows] added to cn, or NULL
     const bf16_t *gamma, *beta;   // [K]
     bf16_t* wp;                   // output rows of this segment [rows_pad][K]
-    float *sn, *cn;               // [rows_pad]
+    uint4* aug;                   // [rows_pad]
     int rows, rows_pad, K;        // rows_pad - rows zero rows follow
     float scale;
 };
@@ -197,8 +201,10 @@ __global__ __launch_bounds__(256) void k_prep(PrepArgs a) {
     sum = wave_sum(sum);
     cst = wave_sum(cst);
     if (lane == 0) {
-        sgm.sn[local] = sum;
-        sgm.cn[local] = cst + ((real && sgm.extra) ? bf16_to_f32(sgm.extra[local]) : 0.f);
+        const float cn = cst + ((real && sgm.extra) ? bf16_to_f32(sgm.extra[local]) : 0.f);
+        const float sn_hi = bf16_round(sum), sn_lo = bf16_round(sum - sn_hi);
+        const float cn_hi = bf16_round(cn), cn_lo = bf16_round(cn - cn_hi);
+        sgm.aug[local] = make_uint4(pack2(sn_hi, sn_lo), pack2(sn_hi, cn_hi), pack2(cn_lo, cn_hi), 0u);
     }
 }
 
@@ -220,7 +226,7 @@ struct GemmArgs {
     int K;                 // contraction length
     float eps;
     const bf16_t* w;       // PROJ: prepared weights [tiles*32][K]; OUT: w_o [N][K]
-    const float *sn, *cn;  // PROJ: per-feature sums / offsets
+    const uint4* aug;      // PROJ: per-feature extra piece of the contraction (sum and offset, see k_prep)
     const bf16_t* bvec;    // OUT: b_o [N]
     int Hd, H, D;
     int dsh;               // log2(D), D in {8, 16, 32}
@@ -260,8 +266,11 @@ constexpr int kGemmWaves = 8;      // wavefronts per block: two per SIMD
 
 // dynamic LDS of k_gemm: weight ring, LayerNorm statistics, per-feature sums and offsets
 static size_t gemm_smem_bytes(int kc, int tt, int ns, int tiles_per_split) {
-    return (size_t)2 * ns * 32 * 2 * kc * 16 + (size_t)kGemmWaves * tt * 64 * 4 + (size_t)2 * tiles_per_split * 32 * 4;
+    return (size_t)2 * ns * 32 * 2 * kc * 16 + (size_t)kGemmWaves * tt * 64 * 4 + (size_t)tiles_per_split * 32 * (4 + 16);
 }
+
+// tile kinds of k_gemm (q and k share their epilogue)
+enum { TK_Q = 0, TK_K = 1, TK_V = 2, TK_GATE = 3, TK_BIAS = 4, TK_OUT = 5 };
 
 template <int KC, bool PROJ, int TT, int NS>
 __global__ __launch_bounds__(kGemmWaves * 64, 2) void k_gemm(GemmArgs a) {
@@ -272,9 +281,9 @@ __global__ __launch_bounds__(kGemmWaves * 64, 2) void k_gemm(GemmArgs a) {
     constexpr int GM = (P >= 16 ? 16 : P) - 1;          // g(r) = (r >> RSH) & GM
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     unsigned char* s_w = smem;                                              // [2][NS][STAGE]
-    float* s_stat = reinterpret_cast<float*>(smem + 2 * NS * STAGE);        // [wave][tt][mean|rstd][32]
-    float* s_cn = s_stat + NW * TT * 64;                                     // [tiles_per_split][32]
-    float* s_sn = s_cn + a.tiles_per_split * 32;
+    float* s_stat = reinterpret_cast<float*>(smem + 2 * NS * STAGE);        // [wave][tt][2][32]: 1/std of the wave's tokens in [1]
+    float* s_cn = s_stat + NW * TT * 64;                                     // OUT: [tiles_per_split][32] output bias
+    uint4* s_aug = reinterpret_cast<uint4*>(s_cn + a.tiles_per_split * 32);  // PROJ: [tiles_per_split][32] extra piece per feature
 
     const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -287,17 +296,18 @@ __global__ __launch_bounds__(kGemmWaves * 64, 2) void k_gemm(GemmArgs a) {
 
     // ---- token operand fragments, raw (issued first: they come from HBM)
     Frag xa[TT][KC];
-    bool tile_ok[TT], tok_valid[TT];
+    bool tok_valid[TT];
     int tok_rl[TT], tok_l[TT];            // batch row (wave-uniform) and position of this lane's token
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
-        const int tg = (blockIdx.x * NW + wave) * TT + tt;
-        tile_ok[tt] = tg < tiles_m;
+        // (token tiles beyond the last one repeat it: the same values are stored twice)
+        int tg = (blockIdx.x * NW + wave) * TT + tt;
+        if (tg > tiles_m - 1) tg = tiles_m - 1;
         const int p = tg * 32 + col;
         const int rl = p / a.Lp, l = p - rl * a.Lp;
         tok_rl[tt] = __builtin_amdgcn_readfirstlane(rl);       // a tile lies inside one batch row
         tok_l[tt] = l;
-        tok_valid[tt] = tile_ok[tt] && l < a.L;
+        tok_valid[tt] = l < a.L;
         const bf16_t* sp = a.src + ((int64_t)(a.r0 + rl) * a.sr + (int64_t)l * a.sl) * K;
 #pragma unroll
         for (int s = 0; s < KC; ++s) {
@@ -343,8 +353,7 @@ __global__ __launch_bounds__(kGemmWaves * 64, 2) void k_gemm(GemmArgs a) {
     // per-feature sums / offsets of this block's tiles
     for (int i = tid; i < (ft_end - ft_begin) * 32; i += NW * 64) {
         if constexpr (PROJ) {
-            s_sn[i] = a.sn[ft_begin * 32 + i];
-            s_cn[i] = a.cn[ft_begin * 32 + i];
+            s_aug[i] = a.aug[ft_begin * 32 + i];
         } else {
             s_cn[i] = bf16_to_f32(a.bvec[ft_begin * 32 + i]);
         }
@@ -368,226 +377,284 @@ __global__ __launch_bounds__(kGemmWaves * 64, 2) void k_gemm(GemmArgs a) {
         else t_lane[tt] = 8 * hf;
         const int l0 = __builtin_amdgcn_readfirstlane(tok_l[tt] - col);
         l0v[tt] = l0 * a.D;                                                   // (l0 / 32) * D * 32
-        any_valid[tt] = tile_ok[tt] && l0 < a.L;
+        any_valid[tt] = l0 < a.L;
     }
-    float nmean[TT], rstd[TT];          // minus mean, 1 / standard deviation of this lane's token
+    float rstd[TT];           // 1 / standard deviation of this lane's token
+    Frag xaug[TT];            // its extra piece of the contraction: (-mean, standard deviation) as bf16 pairs (see k_prep)
 #pragma unroll
-    for (int tt = 0; tt < TT; ++tt) nmean[tt] = rstd[tt] = 0.f;
+    for (int tt = 0; tt < TT; ++tt) {
+        rstd[tt] = 0.f;
+        xaug[tt].u = make_uint4(0, 0, 0, 0);
+    }
 
     __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
     __syncthreads();
 
-    // The two wavefronts of a SIMD (w and w + 4) work in opposite phase: between two barriers
-    // ("slot" i) the first runs the matrix-core part of step i and then its epilogue, the second
-    // the epilogue of step i-1 and then the matrix-core part of step i.  So one keeps the matrix
-    // core busy while the other keeps the vector unit busy, instead of both doing the same thing
-    // at the same time.  Both read step i's weight tiles within slot i.
-    const int n_it = (ft_end - ft_begin + NS - 1) / NS;
-    const bool epi_first = wave >= NW / 2;
-    bool need_stats = PROJ;
-    int n_stores = 0;                     // store instructions issued in this slot (a lower bound)
-    f32x16 acc[NS][TT];
-    for (int slot = 0; slot <= n_it; ++slot) {
-#pragma unroll 1
-      for (int sub = 0; sub < 2; ++sub) {
-        const bool do_mfma = (sub == 1) == epi_first;
-        const int it = do_mfma ? slot : (epi_first ? slot - 1 : slot);
-        if (it < 0 || it >= n_it) continue;
-        const int grp = it & 1;
-        const int ftb = ft_begin + it * NS;
-        if (do_mfma) {
+    // Software pipeline inside every wavefront: the matrix-core instructions of tile i alternate,
+    // one contraction step at a time, with the vector instructions of the epilogue of tile i-1
+    // (a wavefront issues a vector instruction only every eight cycles or so and a 32x32x16
+    // matrix instruction lasts 32: the epilogue fits into the shadow of the matrix core).
+    // Two accumulator sets alternate between the roles "being computed" and "being stored".
+    constexpr int VPC = 16 / KC > 0 ? 16 / KC : 1;      // epilogue values per contraction step
+    constexpr int AHEAD = KC < 4 ? KC : 4;              // operand reads in flight (LDS latency is about two steps)
+    const int LpD2 = LpD;
+    int n_stores = 0;                     // store instructions issued in this step (a lower bound)
+    f32x16 acc[2][TT];
+
+    // matrix part of tile ftn (weights at st) into an[], epilogue of tile ftp (kind KP) from ap[]
+    auto tile_step = [&](auto vt_c, auto kp_c, auto next_c, f32x16 (&an)[TT], f32x16 (&ap)[TT], const unsigned char* st,
+                         int ftn, int ftp) {
+        constexpr bool VT = decltype(vt_c)::value;
+        constexpr int KP = decltype(kp_c)::value;
+        constexpr bool NEXT = decltype(next_c)::value;
+        // ---- epilogue state of tile ftp
+        const int nbp = ftp * 32;
+        const int so = (ftp - ft_begin) * 32;
+        // OUT: bias of four features, V: 1/std of four tokens; the group after the one in use is
+        // already on its way from LDS (c4n, rs4n), so that no step waits for it
+        float4 c4 = make_float4(0.f, 0.f, 0.f, 0.f), c4n = c4;
+        float4 rs4[TT], rs4n[TT];
+        auto fetch_group = [&](int g) {
+            if constexpr (KP == TK_OUT) {
+                c4n = *reinterpret_cast<const float4*>(s_cn + so + 8 * g + 4 * hf);
+            } else if constexpr (KP == TK_V) {
 #pragma unroll
-        for (int n = 0; n < NS; ++n) {
-            const int ft = ftb + n;
-            if (ft >= ft_end) continue;
-            const bool tokens_by_features = PROJ && ft < a.nt_main && ft * 32 >= 2 * a.Hd && ft * 32 < 3 * a.Hd;   // V: rows = tokens
-            const unsigned char* st = s_w + (grp * NS + n) * STAGE;
+                for (int tt = 0; tt < TT; ++tt)
+                    rs4n[tt] = *reinterpret_cast<const float4*>(s_stat + (wave * TT + tt) * 64 + 32 + 8 * g + 4 * hf);
+            }
+        };
+        if constexpr (KP == TK_OUT || KP == TK_V) fetch_group(0);
+        uint32_t pk[TT][8];
+        float pend[TT];
+        size_t qk_off[TT];
+        int hlim = 0;
+        if constexpr (KP == TK_BIAS) {
+            hlim = a.H - 4 * hf;
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt)
+                qk_off[tt] = (size_t)(a.r0 + tok_rl[tt]) * a.Lp + tok_l[tt] + (size_t)(4 * hf) * a.Lq * a.Lp;
+        }
+        // value v of the lane: one multiplication by 1/std (the matrix core has already added the
+        // LayerNorm mean and offset terms), the sigmoid for the gate, bf16
+        auto epi_value = [&](int v) {
+            const int g = v >> 2, e = v & 3;
+            if constexpr (KP == TK_OUT || KP == TK_V) {
+                if (e == 0) {
+                    c4 = c4n;
 #pragma unroll
-                for (int v = 0; v < 16; ++v) acc[n][tt][v] = 0.f;
-            // all operand reads of the tile first (they return in order and the matrix-core
-            // instructions follow them one by one); the fence keeps the compiler from moving
-            // each read down to its use, where its latency would be paid KC times
-            Frag wf[KC];
-#pragma unroll
-            for (int s = 0; s < KC; ++s) wf[s].u = *reinterpret_cast<const uint4*>(st + (rd0 ^ (32u * s)));
-            __builtin_amdgcn_sched_barrier(0);
-            if (tokens_by_features) {
-#pragma unroll
-                for (int s = 0; s < KC; ++s)
-#pragma unroll
-                    for (int tt = 0; tt < TT; ++tt)
-                        acc[n][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[tt][s].v, wf[s].v, acc[n][tt], 0, 0, 0);
-            } else {
-#pragma unroll
-                for (int s = 0; s < KC; ++s)
-#pragma unroll
-                    for (int tt = 0; tt < TT; ++tt)
-                        acc[n][tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[s].v, xa[tt][s].v, acc[n][tt], 0, 0, 0);
+                    for (int tt = 0; tt < TT; ++tt) rs4[tt] = rs4n[tt];
+                    if (g < 3) fetch_group(g + 1);
+                }
             }
-        }
-        continue;
-        }
-        if (need_stats) {
-            need_stats = false;
-            // LayerNorm statistics of the raw rows (two passes over the registers, float32): only
-            // the epilogue needs them
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) {
-                float sum = 0.f;
-#pragma unroll
-                for (int s = 0; s < KC; ++s)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) sum = add_pair(xa[tt][s].w[i], sum);
-                sum += other_half(sum);
-                const float mu = sum / (float)K;
-                float sq = 0.f;
-#pragma unroll
-                for (int s = 0; s < KC; ++s) {
-                    if (16 * s + 8 * hf < K) {
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            const float d0 = lo_f32(xa[tt][s].w[i]) - mu, d1 = hi_f32(xa[tt][s].w[i]) - mu;
-                            sq += d0 * d0 + d1 * d1;
-                        }
+                float t;
+                if constexpr (KP == TK_OUT) {
+                    t = ap[tt][v] + (e == 0 ? c4.x : (e == 1 ? c4.y : (e == 2 ? c4.z : c4.w)));
+                } else if constexpr (KP == TK_V) {
+                    // lane = feature, value = token 8g + 4hf + e
+                    t = ap[tt][v] * (e == 0 ? rs4[tt].x : (e == 1 ? rs4[tt].y : (e == 2 ? rs4[tt].z : rs4[tt].w)));
+                } else {
+                    t = ap[tt][v] * rstd[tt];
+                }
+                if constexpr (KP == TK_GATE) t = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-t * kLog2e));
+                if constexpr (KP == TK_BIAS) {
+                    // pair bias: feature = head, token (rl, l) = pair (q, k)
+                    const int hu = 8 * g + e;                    // head of the lower half-wave
+                    if (hu < hlim) a.bias[qk_off[tt] + (size_t)hu * a.Lq * a.Lp] = t;
+                } else {
+                    // (the empty statements pin the arithmetic to this contraction step: the
+                    // compiler would otherwise sink it below the matrix-core instructions)
+                    if (v & 1) {
+                        pk[tt][v >> 1] = pack2(pend[tt], t);
+                        asm volatile("" : "+v"(pk[tt][v >> 1]));
+                    } else {
+                        pend[tt] = t;
+                        asm volatile("" : "+v"(pend[tt]));
                     }
                 }
-                sq += other_half(sq);
-                nmean[tt] = tok_valid[tt] ? -mu : 0.f;
-                rstd[tt] = tok_valid[tt] ? rsqrtf(sq / (float)K + a.eps) : 0.f;
-                if (hf == 0) {
-                    s_stat[((wave * TT + tt) * 2 + 0) * 32 + col] = -nmean[tt];
-                    s_stat[((wave * TT + tt) * 2 + 1) * 32 + col] = rstd[tt];
-                }
             }
-        }
-
-        // ---- epilogue.  Uniform quantities (tile kind, head, row) stay in scalar registers and
-        // form the base address of the stores; the per-lane offsets are the same for every tile.
+        };
+        // ---- the pipeline: KC steps over the weight tile, then the extra piece (PROJ)
+        Frag wf[KC];
+        Frag waug;
+        if constexpr (NEXT) {
 #pragma unroll
-        for (int n = 0; n < NS; ++n) {
-            const int ft = ftb + n;
-            if (ft >= ft_end) continue;
-            // kind of this feature tile: 0 q, 1 k, 2 v, 3 gate, 4 pair bias
-            const int nb = ft * 32;                              // first feature (row of w) of the tile
-            const int kind = !PROJ ? 0 : (ft >= a.nt_main ? 4 : (nb >= a.Hd) + (nb >= 2 * a.Hd) + (nb >= 3 * a.Hd));
-            const int so = (ft - ft_begin) * 32;
-            const int fb = nb - kind * a.Hd;                     // first feature inside its tensor
-            if (PROJ && kind == 2) {
-                // lane = feature (col), registers = tokens 8g + 4hf + e of the tile
-                const float sn = s_sn[so + col], cn = s_cn[so + col];
-                const size_t head_off = (size_t)(fb >> a.dsh) * LpD;
+            for (int s = 0; s < AHEAD; ++s) wf[s].u = *reinterpret_cast<const uint4*>(st + (rd0 ^ (32u * s)));
+            if constexpr (PROJ) waug.u = s_aug[(ftn - ft_begin) * 32 + col];
+        }
+#pragma unroll
+        for (int s = 0; s < KC; ++s) {
+            if constexpr (NEXT) {
+                if (s + AHEAD < KC) wf[s + AHEAD].u = *reinterpret_cast<const uint4*>(st + (rd0 ^ (32u * (s + AHEAD))));
 #pragma unroll
                 for (int tt = 0; tt < TT; ++tt) {
-                    if (!tile_ok[tt]) continue;
-                    const float* stt = s_stat + (wave * TT + tt) * 64;
-                    uint32_t pk[8];
+                    f32x16 c = an[tt];
+                    if (s == 0) {
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const float4 mu = *reinterpret_cast<const float4*>(stt + 8 * g + 4 * hf);
-                        const float4 rs = *reinterpret_cast<const float4*>(stt + 32 + 8 * g + 4 * hf);
-                        const float y0 = rs.x * (acc[n][tt][4 * g] - mu.x * sn) + cn;
-                        const float y1 = rs.y * (acc[n][tt][4 * g + 1] - mu.y * sn) + cn;
-                        const float y2 = rs.z * (acc[n][tt][4 * g + 2] - mu.z * sn) + cn;
-                        const float y3 = rs.w * (acc[n][tt][4 * g + 3] - mu.w * sn) + cn;
-                        pk[2 * g] = pack2(y0, y1);
-                        pk[2 * g + 1] = pack2(y2, y3);
+                        for (int v = 0; v < 16; ++v) c[v] = 0.f;
                     }
-                    merge_halves(pk[0], pk[2]);
-                    merge_halves(pk[1], pk[3]);
-                    merge_halves(pk[4], pk[6]);
-                    merge_halves(pk[5], pk[7]);
-                    // v^T tiled by 32 keys: [row][head][l / 32][e][l % 32]
-                    bf16_t* tile = a.vt + (row_base[tt] + head_off + (size_t)l0v[tt]);
-                    *reinterpret_cast<uint4*>(tile + v_lane) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-                    *reinterpret_cast<uint4*>(tile + v_lane + 16) = make_uint4(pk[4], pk[5], pk[6], pk[7]);
-                    n_stores += 2;
+                    if constexpr (VT) an[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[tt][s].v, wf[s].v, c, 0, 0, 0);
+                    else an[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[s].v, xa[tt][s].v, c, 0, 0, 0);
                 }
-                continue;
             }
-            // lane = token (col), registers = features 8g + 4hf + e of the tile
-            float sv[16], cv[16];
+            if constexpr (KP != -1) {
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int o = so + 8 * g + 4 * hf;
-                const float4 c4 = *reinterpret_cast<const float4*>(s_cn + o);
-                cv[4 * g] = c4.x; cv[4 * g + 1] = c4.y; cv[4 * g + 2] = c4.z; cv[4 * g + 3] = c4.w;
-                if constexpr (PROJ) {
-                    const float4 s4 = *reinterpret_cast<const float4*>(s_sn + o);
-                    sv[4 * g] = s4.x; sv[4 * g + 1] = s4.y; sv[4 * g + 2] = s4.z; sv[4 * g + 3] = s4.w;
-                }
+                for (int vv = 0; vv < VPC; ++vv) epi_value(s * VPC + vv);
             }
-            // features fb + 8 hf .. +7 and fb + 16 + 8 hf .. +7 of this lane: uniform part of their place
-            size_t u0 = (size_t)nb, u1 = (size_t)nb + 16;              // OUT: [token][N]
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if constexpr (NEXT && PROJ) {
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) {
+                if constexpr (VT) an[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xaug[tt].v, waug.v, an[tt], 0, 0, 0);
+                else an[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(waug.v, xaug[tt].v, an[tt], 0, 0, 0);
+            }
+        }
+        // ---- stores of tile ftp
+        if constexpr (KP == TK_V) {
+            const size_t head_off = (size_t)((nbp - 2 * a.Hd) >> a.dsh) * LpD2;
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) {
+                merge_halves(pk[tt][0], pk[tt][2]);
+                merge_halves(pk[tt][1], pk[tt][3]);
+                merge_halves(pk[tt][4], pk[tt][6]);
+                merge_halves(pk[tt][5], pk[tt][7]);
+                // v^T tiled by 32 keys: [row][head][l / 32][e][l % 32]
+                bf16_t* tile = a.vt + (row_base[tt] + head_off + (size_t)l0v[tt]);
+                *reinterpret_cast<uint4*>(tile + v_lane) = make_uint4(pk[tt][0], pk[tt][1], pk[tt][2], pk[tt][3]);
+                *reinterpret_cast<uint4*>(tile + v_lane + 16) = make_uint4(pk[tt][4], pk[tt][5], pk[tt][6], pk[tt][7]);
+            }
+            n_stores += 2 * TT;
+        } else if constexpr (KP == TK_Q || KP == TK_GATE || KP == TK_OUT) {
+            // features f .. f+7 and f+16 .. f+23 (f = first feature of the tile + 8 hf): uniform part of their place
+            size_t u0 = (size_t)nbp, u1 = (size_t)nbp + 16;               // out: [token][N]
             bf16_t* base = a.out;
-            if constexpr (PROJ) {                                       // q, k, gate: [row][head][l][d]
-                u0 = (size_t)(fb >> a.dsh) * LpD + (fb & (a.D - 1));
-                u1 = (size_t)((fb + 16) >> a.dsh) * LpD + ((fb + 16) & (a.D - 1));
+            if constexpr (PROJ) {                                          // q, k, gate: [row][head][l][d]
+                const int kind = (nbp >= a.Hd) + (nbp >= 2 * a.Hd) + (nbp >= 3 * a.Hd);
+                const int f = nbp - kind * a.Hd;
+                u0 = (size_t)(f >> a.dsh) * LpD2 + (f & (a.D - 1));
+                u1 = (size_t)((f + 16) >> a.dsh) * LpD2 + ((f + 16) & (a.D - 1));
                 base = kind == 0 ? a.q : (kind == 1 ? a.k : a.g);
             }
 #pragma unroll
             for (int tt = 0; tt < TT; ++tt) {
-                if (!tile_ok[tt]) continue;
-                float val[16];
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    if constexpr (PROJ) val[v] = rstd[tt] * (acc[n][tt][v] + nmean[tt] * sv[v]) + cv[v];
-                    else val[v] = acc[n][tt][v] + cv[v];
-                }
-                if (PROJ && kind == 3) {
-                    asm volatile("");       // a real branch: the other tile kinds must not pay for the sigmoid
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) val[v] = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-val[v] * kLog2e));
-                }
-                if (PROJ && kind == 4) {
-                    // pair bias: feature = head, token (rl, l) = pair (q, k)
-                    const size_t plane = (size_t)a.Lq * a.Lp;
-                    size_t qk = (size_t)(a.r0 + tok_rl[tt]) * a.Lp + tok_l[tt] + 4 * hf * plane;
-                    int hlim = a.H - 4 * hf;
-                    // (keeps the 16 addresses and store masks out of the registers of the main loop)
-                    asm volatile("" : "+v"(qk), "+v"(hlim));
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int hu = 8 * (v >> 2) + (v & 3);           // head of the lower half-wave
-                        if (hu < hlim) a.bias[qk + hu * plane] = val[v];
-                    }
-                    continue;
-                }
-                uint32_t pk[8];
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    pk[2 * g] = pack2(val[4 * g], val[4 * g + 1]);
-                    pk[2 * g + 1] = pack2(val[4 * g + 2], val[4 * g + 3]);
-                }
-                merge_halves(pk[0], pk[2]);
-                merge_halves(pk[1], pk[3]);
-                merge_halves(pk[4], pk[6]);
-                merge_halves(pk[5], pk[7]);
+                merge_halves(pk[tt][0], pk[tt][2]);
+                merge_halves(pk[tt][1], pk[tt][3]);
+                merge_halves(pk[tt][4], pk[tt][6]);
+                merge_halves(pk[tt][5], pk[tt][7]);
+                bf16_t* rowp = base + row_base[tt];
                 if (PROJ || tok_valid[tt]) {
-                    bf16_t* rowp = base + row_base[tt];
-                    *reinterpret_cast<uint4*>(rowp + u0 + t_lane[tt]) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-                    *reinterpret_cast<uint4*>(rowp + u1 + t_lane[tt]) = make_uint4(pk[4], pk[5], pk[6], pk[7]);
+                    *reinterpret_cast<uint4*>(rowp + u0 + t_lane[tt]) = make_uint4(pk[tt][0], pk[tt][1], pk[tt][2], pk[tt][3]);
+                    *reinterpret_cast<uint4*>(rowp + u1 + t_lane[tt]) = make_uint4(pk[tt][4], pk[tt][5], pk[tt][6], pk[tt][7]);
                 }
                 if (PROJ || any_valid[tt]) n_stores += 2;     // (wave-uniform: the instructions were issued)
             }
         }
-      }
-        if (slot >= n_it) break;
+    };
+    // kind of tile ft: q and k share their epilogue
+    auto kind_of = [&](int ft) -> int {
+        if constexpr (!PROJ) return TK_OUT;
+        if (ft >= a.nt_main) return TK_BIAS;
+        const int k = (ft * 32 >= a.Hd) + (ft * 32 >= 2 * a.Hd) + (ft * 32 >= 3 * a.Hd);
+        return k == TK_K ? TK_Q : k;
+    };
+    using std::integral_constant;
+    auto run_step = [&](int kn, int kp, f32x16 (&an)[TT], f32x16 (&ap)[TT], const unsigned char* st, int ftn, int ftp) {
+#define FF_STEP(KPV)                                                                                                         \
+    do {                                                                                                                     \
+        if (kn < 0) tile_step(integral_constant<bool, false>{}, integral_constant<int, KPV>{},                               \
+                              integral_constant<bool, false>{}, an, ap, st, ftn, ftp);                                            \
+        else if (kn == TK_V) tile_step(integral_constant<bool, true>{}, integral_constant<int, KPV>{},                       \
+                                       integral_constant<bool, true>{}, an, ap, st, ftn, ftp);                                    \
+        else tile_step(integral_constant<bool, false>{}, integral_constant<int, KPV>{}, integral_constant<bool, true>{}, an, \
+                       ap, st, ftn, ftp);                                                                                         \
+    } while (0)
+        if constexpr (PROJ) {
+            switch (kp) {
+                case TK_Q: FF_STEP(TK_Q); break;
+                case TK_V: FF_STEP(TK_V); break;
+                case TK_GATE: FF_STEP(TK_GATE); break;
+                case TK_BIAS: FF_STEP(TK_BIAS); break;
+                default: FF_STEP(-1); break;
+            }
+        } else {
+            if (kp == TK_OUT) FF_STEP(TK_OUT);
+            else FF_STEP(-1);
+        }
+#undef FF_STEP
+    };
+
+    if constexpr (PROJ) {
+        // LayerNorm statistics of the raw rows (two passes over the registers, float32)
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+            float sum = 0.f;
+#pragma unroll
+            for (int s = 0; s < KC; ++s)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) sum = add_pair(xa[tt][s].w[i], sum);
+            sum += other_half(sum);
+            const float mu = sum / (float)K;
+            float sq = 0.f;
+#pragma unroll
+            for (int s = 0; s < KC; ++s) {
+                if (16 * s + 8 * hf < K) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float d0 = lo_f32(xa[tt][s].w[i]) - mu, d1 = hi_f32(xa[tt][s].w[i]) - mu;
+                        sq += d0 * d0 + d1 * d1;
+                    }
+                }
+            }
+            sq += other_half(sq);
+            const float var = sq / (float)K + a.eps;
+            rstd[tt] = tok_valid[tt] ? rsqrtf(var) : 0.f;
+            const float m = tok_valid[tt] ? -mu : 0.f, r = var * rstd[tt];
+            const float m_hi = bf16_round(m), m_lo = bf16_round(m - m_hi);
+            const float r_hi = bf16_round(r), r_lo = bf16_round(r - r_hi);
+            if (hf == 0) {
+                xaug[tt].u = make_uint4(pack2(m_hi, m_hi), pack2(m_lo, r_hi), pack2(r_hi, r_lo), 0u);
+                s_stat[((wave * TT + tt) * 2 + 1) * 32 + col] = rstd[tt];
+            }
+        }
+    }
+
+    const int n_it = (ft_end - ft_begin + NS - 1) / NS;
+    int kp = -1, ftp = ft_begin;
+    bool last_in_1 = false;
+    for (int it = 0; it < n_it; ++it) {
+        const int ftb = ft_begin + it * NS;
+        const bool two = ftb + 1 < ft_end;
+        const unsigned char* st = s_w + ((it & 1) * NS) * STAGE;
+        run_step(kind_of(ftb), kp, acc[0], acc[1], st, ftb, ftp);
+        kp = kind_of(ftb);
+        ftp = ftb;
+        last_in_1 = false;
+        if (two) {
+            run_step(kind_of(ftb + 1), kp, acc[1], acc[0], st + STAGE, ftb + 1, ftp);
+            kp = kind_of(ftb + 1);
+            ftp = ftb + 1;
+            last_in_1 = true;
+        }
+        if (it + 1 >= n_it) break;
         // Order of this wavefront's memory operations: ... L(i+1), S, L(i+2), S, ... (L = tile loads
-        // of a step, S = the stores of one slot).  The next slot needs L(slot+1): everything but
-        // the stores issued after it, those of this slot, must have completed.  After the barrier
-        // all wavefronts have their share of L(slot+1) in LDS and have finished reading this
-        // slot's half of the ring, which the loads of step slot+2 then overwrite.
+        // of a step, S = the stores issued during one step).  The next step needs L(it+1):
+        // everything but the stores issued after it, those of this step, must have completed.
+        // After the barrier all wavefronts have their share of L(it+1) in LDS and have finished
+        // reading this step's half of the ring, which the loads of step it+2 then overwrite.
         wait_vmem_but_last(__builtin_amdgcn_readfirstlane(n_stores));
         __syncthreads();
 #pragma unroll
         for (int n = 0; n < NS; ++n) {
-            const int ft = ft_begin + (slot + 2) * NS + n;
-            if (ft < ft_end) issue_tile(ft, (slot & 1) * NS + n);
+            const int ft = ft_begin + (it + 2) * NS + n;
+            if (ft < ft_end) issue_tile(ft, (it & 1) * NS + n);
         }
         n_stores = 0;
     }
+    // epilogue of the last tile
+    if (last_in_1) run_step(-1, kp, acc[0], acc[1], s_w, ftp, ftp);
+    else run_step(-1, kp, acc[1], acc[0], s_w, ftp, ftp);
 }
 
 // ====================================================================================
@@ -915,11 +982,13 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
 // token tiles per wavefront: two halve the LDS traffic per MFMA, one keeps the register count at
 // two wavefronts per SIMD when the contraction is long
 // (and one when two would leave compute units without a block)
-static int gemm_tt(int K, int tiles_m) { return (K > 128 || tiles_m < 2 * kGemmWaves * 256) ? 1 : 2; }
+static int gemm_tt(bool proj, int K, int tiles_m) {
+    return (K > (proj ? 64 : 128) || tiles_m < 2 * kGemmWaves * 256) ? 1 : 2;
+}
 constexpr int kGemmNS = 2;      // weight tiles per pipeline step
 
-static int gemm_blocks_m(int tiles_m, int K) {
-    const int per_block = kGemmWaves * gemm_tt(K, tiles_m);
+static int gemm_blocks_m(bool proj, int tiles_m, int K) {
+    const int per_block = kGemmWaves * gemm_tt(proj, K, tiles_m);
     return (tiles_m + per_block - 1) / per_block;
 }
 
@@ -938,7 +1007,7 @@ static void launch_gemm_inst(const GemmArgs& a, dim3 grid, hipStream_t st) {
 template <bool PROJ>
 static void launch_gemm(const GemmArgs& a, int K, dim3 grid, hipStream_t st) {
     const int kc = K / 16;
-    if (gemm_tt(K, a.rows * (a.Lp >> 5)) == 1) {
+    if (gemm_tt(PROJ, K, a.rows * (a.Lp >> 5)) == 1) {
         if (kc <= 2) launch_gemm_inst<2, PROJ, 1>(a, grid, st);
         else if (kc <= 4) launch_gemm_inst<4, PROJ, 1>(a, grid, st);
         else if (kc <= 8) launch_gemm_inst<8, PROJ, 1>(a, grid, st);
@@ -946,7 +1015,7 @@ static void launch_gemm(const GemmArgs& a, int K, dim3 grid, hipStream_t st) {
     } else {
         if (kc <= 2) launch_gemm_inst<2, PROJ, 2>(a, grid, st);
         else if (kc <= 4) launch_gemm_inst<4, PROJ, 2>(a, grid, st);
-        else launch_gemm_inst<8, PROJ, 2>(a, grid, st);
+        else if constexpr (!PROJ) launch_gemm_inst<8, PROJ, 2>(a, grid, st);
     }
 }
 
@@ -962,7 +1031,7 @@ static GemmArgs proj_args(const Problem& p, const MfmaWs& m, const Workspace& ws
     const int Lp = round_up(p.L, 64), Lq = round_up(p.L, 64);
     GemmArgs g{};
     g.sr = p.sr; g.sl = p.sl; g.L = p.L; g.Lp = Lp; g.Lq = Lq; g.K = p.c; g.eps = p.eps;
-    g.w = m.wp; g.sn = m.sn; g.cn = m.cn; g.Hd = p.Hd; g.H = p.H; g.D = p.d; g.invD = 1.f / (float)p.d; g.dsh = p.d == 8 ? 3 : (p.d == 16 ? 4 : 5);
+    g.w = m.wp; g.aug = m.aug; g.Hd = p.Hd; g.H = p.H; g.D = p.d; g.invD = 1.f / (float)p.d; g.dsh = p.d == 8 ? 3 : (p.d == 16 ? 4 : 5);
     g.nt_main = 4 * p.Hd / 32;
     g.q = m.q; g.k = m.k; g.g = m.g; g.vt = m.vt; g.bias = ws.bias;
     return g;
@@ -979,8 +1048,8 @@ ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x
         const int Hd = p.Hd, c = p.c;
         PrepArgs a{};
         auto seg = [&](int i, const void* wsrc, const void* extra, int rows, int rows_pad, int row0, float scale) {
-            a.seg[i] = {(const bf16_t*)wsrc, (const bf16_t*)extra, gm, bt, m.wp + (size_t)row0 * c, m.sn + row0,
-                        m.cn + row0, rows, rows_pad, c, scale};
+            a.seg[i] = {(const bf16_t*)wsrc, (const bf16_t*)extra, gm, bt, m.wp + (size_t)row0 * c, m.aug + row0,
+                        rows, rows_pad, c, scale};
         };
         seg(0, w.w_q, nullptr, Hd, Hd, 0, qscale);
         seg(1, w.w_k, nullptr, Hd, Hd, Hd, 1.f);
@@ -992,7 +1061,7 @@ ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x
         if (p.mode == FF_MSA_ROW) {     // the pair-bias projection of z, with its own LayerNorm
             const int off = 4 * Hd + 32;
             a.seg[5] = {(const bf16_t*)w.w_b, nullptr, (const bf16_t*)w.lnz_g, (const bf16_t*)w.lnz_b, m.zwp,
-                        m.sn + off, m.cn + off, p.H, 32, p.c_z, kLog2e};
+                        m.aug + off, p.H, 32, p.c_z, kLog2e};
             a.nseg = 6;
             rows += 32;
         }
@@ -1004,10 +1073,10 @@ ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x
         // bias[h][i][j] from the pair representation: "batch rows" i, tokens j
         GemmArgs g{};
         g.src = (const bf16_t*)z; g.sr = p.L; g.sl = 1; g.r0 = 0; g.rows = p.L; g.L = p.L; g.Lp = Lp; g.Lq = Lq;
-        g.K = p.c_z; g.eps = p.eps; g.w = m.zwp; g.sn = m.sn + off; g.cn = m.cn + off;
+        g.K = p.c_z; g.eps = p.eps; g.w = m.zwp; g.aug = m.aug + off;
         g.Hd = p.Hd; g.H = p.H; g.D = p.d; g.invD = 1.f / (float)p.d; g.dsh = p.d == 8 ? 3 : (p.d == 16 ? 4 : 5); g.nt_main = 0; g.bias = ws.bias;
         g.ft_first = 0; g.ft_count = 1; g.tiles_per_split = 1;
-        const int blocks_m = gemm_blocks_m(p.L * (Lp / 32), p.c_z);
+        const int blocks_m = gemm_blocks_m(true, p.L * (Lp / 32), p.c_z);
         Timed t(KK_BIAS, st);
         launch_gemm<true>(g, p.c_z, dim3(blocks_m, 1), st);
     } else if (tri && ws.chunk < p.R) {
@@ -1015,7 +1084,7 @@ ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x
         GemmArgs g = proj_args(p, m, ws);
         g.src = (const bf16_t*)x; g.r0 = 0; g.rows = p.R;
         g.ft_first = g.nt_main; g.ft_count = 1; g.tiles_per_split = 1;
-        const int blocks_m = gemm_blocks_m(p.R * (Lp / 32), p.c);
+        const int blocks_m = gemm_blocks_m(true, p.R * (Lp / 32), p.c);
         Timed t(KK_BIAS, st);
         launch_gemm<true>(g, p.c, dim3(blocks_m, 1), st);
     }
@@ -1028,7 +1097,7 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
     const MfmaWs m = split_ws(p, ws.chunk, ws);
     const bool tri = p.mode == FF_TRI_START || p.mode == FF_TRI_END;
     const int tiles_m = rows * (Lp / 32);
-    const int blocks_m = gemm_blocks_m(tiles_m, p.c);
+    const int blocks_m = gemm_blocks_m(true, tiles_m, p.c);
     {
         GemmArgs g = proj_args(p, m, ws);
         g.src = (const bf16_t*)x; g.r0 = r0; g.rows = rows;
@@ -1074,7 +1143,7 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
     o.Hd = p.Hd; o.H = p.H; o.D = p.d; o.invD = 1.f / (float)p.d; o.dsh = p.d == 8 ? 3 : (p.d == 16 ? 4 : 5); o.out = (bf16_t*)out; o.N = p.c;
     {
         const int tiles_n = o.N / 32;
-        const int blocks_o = gemm_blocks_m(tiles_m, p.Hd);
+        const int blocks_o = gemm_blocks_m(false, tiles_m, p.Hd);
         const int split = pick_split(blocks_o, tiles_n);
         o.ft_first = 0; o.ft_count = tiles_n;
         o.tiles_per_split = tiles_n / split;
