@@ -748,10 +748,7 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
             *reinterpret_cast<float4*>(sp + RB * 12 * kBiasPitch) = bq3;
         }
     };
-    if constexpr (HAS_BIAS) {
-        load_bias(0);
-        store_bias(0);
-    }
+    if constexpr (HAS_BIAS) load_bias(0);      // (stored to LDS after the first K and V loads have been issued)
 
     // permuted key of S^T row m = col: rows 8g + 4b + e hold key 16*(g/2) + 8b + 4*(g%2) + e
     const int kperm = 16 * (col >> 4) + 8 * ((col >> 2) & 1) + 4 * ((col >> 3) & 1) + (col & 3);
@@ -800,11 +797,10 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
     }
     bool first = true;
 
-    // S^T of tile kt into sa (bias tile as accumulator input); returns whether any key is valid
-    auto qk = [&](Frag (&kb)[KS], float mv, int kt, f32x16 (&sa)[2], const float* sb) -> bool {
-        const bool key_valid = mv != 0.f && 32 * kt + kperm < a.L;
-        if (!__any(key_valid)) return false;
-        if (xlane) kb[SX].w[0] = key_valid ? 0x00003f80u : 0xff803f80u;   // (1.0, mask term)
+    // S^T of tile kt into sa in two parts: the bias tile as accumulator input (LDS reads, issued
+    // early: the loads of the next K and V tiles hide their latency), then the contraction, which
+    // returns whether any key of the tile is valid
+    auto qk_bias = [&](int kt, f32x16 (&sa)[2], const float* sb) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             if constexpr (HAS_BIAS) {
@@ -822,6 +818,11 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
                 for (int v = 0; v < 16; ++v) sa[j][v] = 0.f;
             }
         }
+    };
+    auto qk_mma = [&](Frag (&kb)[KS], float mv, int kt, f32x16 (&sa)[2]) -> bool {
+        const bool key_valid = mv != 0.f && 32 * kt + kperm < a.L;
+        if (!__any(key_valid)) return false;
+        if (xlane) kb[SX].w[0] = key_valid ? 0x00003f80u : 0xff803f80u;   // (1.0, mask term)
         // the two query tiles alternate, so that no matrix-core instruction waits for the one before it
 #pragma unroll
         for (int s = 0; s < KS; ++s)
@@ -910,17 +911,20 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
     fetch_k(kb1, mv1, 1);
     fetch_v(vb0, 0);
     if constexpr (HAS_BIAS) {
+        store_bias(0);
         if (nt > 2) load_bias(1);
     }
     __syncthreads();                        // bias group 0 is in LDS
     f32x16 s0[2], s1[2];
-    bool live0 = qk(kb0, mv0, 0, s0, s_bias), live1 = false;
+    qk_bias(0, s0, s_bias);
+    bool live0 = qk_mma(kb0, mv0, 0, s0), live1 = false;
     int cur = 0;                            // LDS buffer of the current 64-key group
     for (int i = 0; i < nt; i += 2) {
         // ---- even tile i: K(i+2) -> set 0, V(i+1) -> set 1, S^T(i+1) -> s1, exponentials of s0
+        qk_bias(i + 1, s1, s_bias + (size_t)cur * 64 * kBiasPitch);
         if (i + 2 < nt) fetch_k(kb0, mv0, i + 2);
         fetch_v(vb1, i + 1);
-        live1 = qk(kb1, mv1, i + 1, s1, s_bias + (size_t)cur * 64 * kBiasPitch);
+        live1 = qk_mma(kb1, mv1, i + 1, s1);
         if (live0) soft_pv(s0, vb0, s1, live1);
         if constexpr (HAS_BIAS) {
             if (i + 2 < nt) store_bias(cur ^ 1);
@@ -929,12 +933,13 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
         // ---- odd tile i+1: K(i+3) -> set 1, V(i+2) -> set 0, S^T(i+2) -> s0, exponentials of s1
         live0 = false;
         if (i + 2 < nt) {
+            qk_bias(i + 2, s0, s_bias + (size_t)(cur ^ 1) * 64 * kBiasPitch);
             fetch_k(kb1, mv1, i + 3);
             fetch_v(vb0, i + 2);
             if constexpr (HAS_BIAS) {
                 if (i + 4 < nt) load_bias((i >> 1) + 2);
             }
-            live0 = qk(kb0, mv0, i + 2, s0, s_bias + (size_t)(cur ^ 1) * 64 * kBiasPitch);
+            live0 = qk_mma(kb0, mv0, i + 2, s0);
         }
         if (live1) soft_pv(s1, vb1, s0, live0);
         cur ^= 1;
