@@ -32,11 +32,11 @@ PEAK_HBM_GBS = 8000.0
 # the factors a plain 256 MiB copy gives); null for workloads without such a run.
 _KIB = 1024
 TRAFFIC_BYTES = {
-    ("c2_row_bf16_train", "k_prep"): int((293.1 * 2.0 + 553.0) * _KIB),
-    ("c2_row_bf16_train", "k_gemm<PROJ> (pair bias pass)"): int((8290.0 * 2.0 + 2048.0) * _KIB),
-    ("c2_row_bf16_train", "k_gemm<PROJ>"): int((10361.4 * 2.0 + 65536.0) * _KIB),
-    ("c2_row_bf16_train", "k_attn"): int((49280.0 * 2.0 + 16384.0) * _KIB),
-    ("c2_row_bf16_train", "k_gemm<OUT>"): int((8775.5 * 2.0 + 23484.4) * _KIB),
+    ("c2_row_bf16_train", "k_prep"): int((292.0 * 2.0 + 553.0) * _KIB),
+    ("c2_row_bf16_train", "k_gemm<PROJ> (pair bias pass)"): int((8341.5 * 2.0 + 2048.0) * _KIB),
+    ("c2_row_bf16_train", "k_gemm<PROJ>"): int((10502.0 * 2.0 + 65536.0) * _KIB),
+    ("c2_row_bf16_train", "k_attn"): int((49292.0 * 2.0 + 16384.0) * _KIB),
+    ("c2_row_bf16_train", "k_gemm<OUT>"): int((8767.7 * 2.0 + 20737.8) * _KIB),
 }
 
 
@@ -112,30 +112,37 @@ def time_workload(name, steps, warmup, copies=3, profile=True):
 
 
 def kernel_rooflines(sp, kernels, steps):
+    """Per kernel: counted flop and algorithmic HBM bytes of one step (each operand of the kernel
+    once), the two roofline ceilings they give at the published peaks, and the one that binds."""
     fl = counted_flop(sp)
     R, L = sp.batch_len
-    rows = []
+    rows_per_launch = sp.chunk_rows if sp.chunk_rows else R
+    hd = sp.heads * sp.head_dim
+    tok = R * L                                    # tokens per step (all launches of a step together)
     tri_fused = sp.mode in (2, 3) and not sp.chunk_rows
-    per_step_flop = {
-        "k_gemm<PROJ>": fl["proj"] + (fl["bias"] if tri_fused else 0.0),
-        "k_attn": fl["attn"],
-        "k_gemm<OUT>": fl["out"],
-        "k_gemm<PROJ> (pair bias pass)": fl["bias"],
+    bias_out = sp.heads * L * L * 4
+    per_step = {   # name -> (flop, bytes)
+        "k_prep": (0.0, 2.0 * ((4 * hd + sp.heads) * sp.c * 2)),
+        "k_gemm<PROJ>": (fl["proj"] + (fl["bias"] if tri_fused else 0.0),
+                         tok * (sp.c + 4 * hd) * 2 + (4 * hd + 32) * sp.c * 2 + (bias_out if tri_fused else 0)),
+        "k_attn": (fl["attn"], tok * 5 * hd * 2 + (bias_out * (R // rows_per_launch) if sp.mode != 1 else 0)),
+        "k_gemm<OUT>": (fl["out"], tok * (hd + sp.c) * 2 + hd * sp.c * 2),
+        "k_gemm<PROJ> (pair bias pass)": (fl["bias"], (L * L * sp.c_z if sp.mode == 0 else tok * sp.c) * 2 + bias_out),
     }
+    rows = []
     for name, (ms, cnt) in kernels.items():
-        per_launch_ms = ms / cnt
-        r = {"kernel": name, "launches_per_step": cnt / steps, "avg_us": per_launch_ms * 1e3,
-             "ms_per_step": ms / steps}
-        if name == "k_gemm<PROJ> (pair bias pass)":
-            # reads the pair representation once, writes the float32 bias
-            src = (L * L * sp.c_z if sp.mode == 0 else R * L * sp.c) * 2
-            byts = src + sp.heads * L * L * 4
-            a = byts / (ms / steps * 1e-3) / 1e9
-            r.update(bound="hbm", achieved=a, peak=PEAK_HBM_GBS, unit="GB/s", frac=a / PEAK_HBM_GBS)
-        elif name in per_step_flop:
-            a = per_step_flop[name] / (ms / steps * 1e-3) / 1e12
-            r.update(bound="mfma", achieved=a, peak=PEAK_MFMA_BF16_TFLOPS, unit="TFLOP/s",
-                     frac=a / PEAK_MFMA_BF16_TFLOPS)
+        r = {"kernel": name, "launches_per_step": cnt / steps, "avg_us": ms / cnt * 1e3, "ms_per_step": ms / steps}
+        if name in per_step:
+            flop, byts = per_step[name]
+            sec = ms / steps * 1e-3
+            tf, gb = flop / sec / 1e12, byts / sec / 1e9
+            r.update(achieved_tflops=tf, frac_mfma=tf / PEAK_MFMA_BF16_TFLOPS, achieved_gbs=gb, frac_hbm=gb / PEAK_HBM_GBS,
+                     flop_per_step=flop, algorithmic_bytes_per_step=byts)
+            # the ceiling that binds is the one that needs more time at its peak
+            if flop / (PEAK_MFMA_BF16_TFLOPS * 1e12) >= byts / (PEAK_HBM_GBS * 1e9):
+                r.update(bound="mfma", achieved=tf, peak=PEAK_MFMA_BF16_TFLOPS, unit="TFLOP/s", frac=tf / PEAK_MFMA_BF16_TFLOPS)
+            else:
+                r.update(bound="hbm", achieved=gb, peak=PEAK_HBM_GBS, unit="GB/s", frac=gb / PEAK_HBM_GBS)
         r["traffic"] = TRAFFIC_BYTES.get((sp.name, name))
         rows.append(r)
     rows.sort(key=lambda r: -r["ms_per_step"])

@@ -813,9 +813,6 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
                         sa[j][8 * c + 4 * i] = x4.x; sa[j][8 * c + 4 * i + 1] = x4.y;
                         sa[j][8 * c + 4 * i + 2] = x4.z; sa[j][8 * c + 4 * i + 3] = x4.w;
                     }
-            } else {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) sa[j][v] = 0.f;
             }
         }
     };
@@ -823,6 +820,12 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
         const bool key_valid = mv != 0.f && 32 * kt + kperm < a.L;
         if (!__any(key_valid)) return false;
         if (xlane) kb[SX].w[0] = key_valid ? 0x00003f80u : 0xff803f80u;   // (1.0, mask term)
+        if constexpr (!HAS_BIAS) {          // (zero accumulator input: a constant operand of the first step)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) sa[j][v] = 0.f;
+        }
         // the two query tiles alternate, so that no matrix-core instruction waits for the one before it
 #pragma unroll
         for (int s = 0; s < KS; ++s)
