@@ -149,6 +149,38 @@ def kernel_rooflines(sp, kernels, steps):
     return rows
 
 
+def time_layernorm(steps):
+    """ff_layernorm alone (the stand-alone entry point; inside the attention the LayerNorm is
+    part of the projection GEMM): rows x c as in the MSA and pair representations of the
+    workloads, bf16, HBM bound with 2 * rows * c * 2 bytes per call."""
+    import torch
+    import paper_2203_00854_amd as P
+    P.ff_profile_enable(True)
+    res = {}
+    for name, rows, c in (("msa 128x256 rows, c=256", 128 * 256, 256), ("pair 256x256 rows, c=128", 256 * 256, 128),
+                          ("pair 2048x2048 rows, c=128", 2048 * 2048, 128)):
+        x = torch.randn(rows, c, device="cuda:0").to(torch.bfloat16)
+        g = torch.ones(c, device="cuda:0", dtype=torch.bfloat16)
+        b = torch.zeros(c, device="cuda:0", dtype=torch.bfloat16)
+        y = torch.empty_like(x)
+        n = max(steps // 4, 5)
+        for _ in range(3):
+            P.ff_layernorm(x, g, b, out=y)
+        torch.cuda.synchronize()
+        P.ff_profile_collect()
+        for _ in range(n):
+            P.ff_layernorm(x, g, b, out=y)
+        torch.cuda.synchronize()
+        k = P.ff_profile_collect()
+        ms, cnt = k.get("k_layernorm", next(iter(k.values())))
+        us = ms / cnt * 1e3
+        gbs = 2.0 * rows * c * 2 / (us * 1e-6) / 1e9
+        res[name] = {"avg_us": us, "achieved_gbs": gbs, "frac_hbm": gbs / PEAK_HBM_GBS}
+        del x, y
+    P.ff_profile_enable(False)
+    return res
+
+
 def cpu_baseline(case, runs=3):
     """The float64 oracle as it stands, on the host cores, full module of the workload."""
     import numpy as np
@@ -253,6 +285,7 @@ def main():
             del c2
             torch.cuda.empty_cache()
         line["others"] = others
+        line["layernorm"] = time_layernorm(args.steps)
 
     print(json.dumps(line))
 

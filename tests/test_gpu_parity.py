@@ -220,6 +220,21 @@ def test_reference_is_raised_when_late_keys_dominate(mode):
     check(to_np(run_case(case)), oracle_case(case), "bf16", f"late keys dominate, mode {mode}")
 
 
+@pytest.mark.parametrize("mode", [ROW, TS])
+def test_large_token_means(mode):
+    """Activations with a mean of twelve standard deviations per token.  The matrix-core family
+    never subtracts the mean from x: the term -mean * (row sum of the folded weights) enters the
+    contraction as bf16 hi + lo pairs and has to cancel a product that is an order of magnitude
+    larger than the result."""
+    n_a, n_b = (6, 96) if mode == ROW else (96, 96)
+    case = I.make_case(small_spec(mode, n_a, n_b, 128, 4, 32, c_z=32, dtype="bf16", mask="tail:7"))
+    off = I.normal(I.stream_key(I.SEED, "large_means", "offset"), n_a * n_b).reshape(n_a, n_b, 1)
+    case.x = I.to_storage(6.0 + 2.0 * off + 0.5 * I.widen(case.x).astype(np.float64), "bf16")
+    if case.z is not None:
+        case.z = I.to_storage(-5.0 + 0.4 * I.widen(case.z).astype(np.float64), "bf16")
+    check(to_np(run_case(case)), oracle_case(case), "bf16", f"large token means, mode {mode}")
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("mode,n_a,n_b,c,H,d,c_z,mask,chunk", [
     (ROW, 7, 70, 64, 2, 32, 24, "tail:5", 3),
