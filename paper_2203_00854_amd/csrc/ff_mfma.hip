@@ -5,10 +5,10 @@
 //               weight matrix (Section 5.2 "merge GEMM"), with per-feature sums so that the
 //               LayerNorm can be finished in the GEMM epilogue
 //   k_gemm<PROJ> merged projection straight from the raw input: with W' = W*gamma,
-//               LN(x) W^T = rstd * (x W'^T - mean * rowsum(W')) + W beta, so the matrix cores
-//               read x as it lies in HBM and the statistics (float32, two passes over the
-//               register-resident row) only meet the result in the epilogue.  Epilogue:
-//               q scaled, gate = sigmoid(. + b_g), q,k,gate token-major, v transposed,
+//               LN(x) W^T = rstd * (x W'^T - mean * rowsum(W') + std * W beta), so the matrix cores
+//               read x as it lies in HBM; the mean and offset terms are one extra contraction
+//               step (operands split into bf16 hi + lo pairs) and the epilogue is a multiplication
+//               by rstd: q scaled, gate = sigmoid(. + b_g), q,k,gate head-major, v transposed,
 //               pair-bias columns as float32 [H][Lq][Lp]
 //   k_attn      flash-style attention: S^T = K Q^T on the matrix cores with the bias tile as
 //               accumulator input; the key mask and the running reference maximum ride in
