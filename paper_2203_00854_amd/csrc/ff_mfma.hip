@@ -1005,7 +1005,7 @@ static void launch_gemm_inst(const GemmArgs& a, dim3 grid, hipStream_t st) {
     const size_t smem = gemm_smem_bytes(KC, TT, kGemmNS, a.tiles_per_split);
     static bool attr_set = false;          // more than 64 KiB of dynamic LDS has to be asked for once
     if (!attr_set) {
-        hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<KC, PROJ, TT, kGemmNS>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<KC, PROJ, TT, kGemmNS>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
         attr_set = true;
     }
