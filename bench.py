@@ -33,7 +33,7 @@ PEAK_HBM_GBS = 8000.0
 _KIB = 1024
 TRAFFIC_BYTES = {
     ("c2_row_bf16_train", "k_prep"): int((292.0 * 2.0 + 553.0) * _KIB),
-    ("c2_row_bf16_train", "k_gemm<PROJ> (pair bias pass)"): int((8341.5 * 2.0 + 2048.0) * _KIB),
+    ("c2_row_bf16_train", "pair bias pass"): int((8341.5 * 2.0 + 2048.0) * _KIB),
     ("c2_row_bf16_train", "k_gemm<PROJ>"): int((10502.0 * 2.0 + 65536.0) * _KIB),
     ("c2_row_bf16_train", "k_attn"): int((49292.0 * 2.0 + 16384.0) * _KIB),
     ("c2_row_bf16_train", "k_gemm<OUT>"): int((8767.7 * 2.0 + 20737.8) * _KIB),
@@ -127,7 +127,10 @@ def kernel_rooflines(sp, kernels, steps):
                          tok * (sp.c + 4 * hd) * 2 + (4 * hd + 32) * sp.c * 2 + (bias_out if tri_fused else 0)),
         "k_attn": (fl["attn"], tok * 5 * hd * 2 + (bias_out * (R // rows_per_launch) if sp.mode != 1 else 0)),
         "k_gemm<OUT>": (fl["out"], tok * (hd + sp.c) * 2 + hd * sp.c * 2),
-        "k_gemm<PROJ> (pair bias pass)": (fl["bias"], (L * L * sp.c_z if sp.mode == 0 else tok * sp.c) * 2 + bias_out),
+        # row mode: k_prep_bias (z once, the float32 bias, and the weight preparation in the same
+        # launch); chunked triangle modes: the pair-bias tile of k_gemm<PROJ> over all of x
+        "pair bias pass": (fl["bias"], (L * L * sp.c_z if sp.mode == 0 else tok * sp.c) * 2 + bias_out
+                           + (2.0 * (4 * hd + sp.heads) * sp.c * 2 if sp.mode == 0 else 0.0)),
     }
     rows = []
     for name, (ms, cnt) in kernels.items():

@@ -17,7 +17,7 @@ static std::mutex g_prof_mu;
 struct ProfRec { int kind; hipEvent_t a, b; };
 static std::vector<ProfRec> g_prof;
 static std::vector<hipEvent_t> g_prof_pool;
-static const char* kKindNames[KK_COUNT] = {"k_prep", "k_gemm<PROJ> (pair bias pass)", "k_gemm<PROJ>", "k_attn",
+static const char* kKindNames[KK_COUNT] = {"k_prep", "pair bias pass", "k_gemm<PROJ>", "k_attn",
                                            "k_gemm<OUT>", "k_layernorm", "generic family"};
 
 static hipEvent_t prof_event() {

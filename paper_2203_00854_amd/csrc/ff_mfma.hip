@@ -169,9 +169,8 @@ struct PrepArgs {
     int nseg;
 };
 
-__global__ __launch_bounds__(256) void k_prep(PrepArgs a) {
-    const int lane = threadIdx.x & 63;
-    const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+// row n of the concatenated segments, by one wavefront
+__device__ __forceinline__ void prep_row(const PrepArgs& a, int n, int lane) {
     int base = 0, sg = -1, local = 0;
     for (int i = 0; i < a.nseg; ++i) {
         if (sg < 0 && n < base + a.seg[i].rows_pad) {
@@ -188,15 +187,26 @@ __global__ __launch_bounds__(256) void k_prep(PrepArgs a) {
     const bool real = local < sgm.rows;
     const int K = sgm.K;
     float sum = 0.f, cst = 0.f;
-    for (int k = lane; k < K; k += 64) {
-        float r = 0.f;
-        if (real) {
-            const float wv = bf16_to_f32(sgm.w[(size_t)local * K + k]) * sgm.scale;
-            r = bf16_round(wv * bf16_to_f32(sgm.gamma[k]));
-            cst += wv * bf16_to_f32(sgm.beta[k]);
+    // K <= 256: at most four elements per lane, all loads issued before the first use
+    bf16_t wv[4], gv[4], bv[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int k = lane + 64 * i;
+        const bool in = real && k < K;
+        wv[i] = in ? sgm.w[(size_t)local * K + k] : (bf16_t)0;
+        gv[i] = in ? sgm.gamma[k] : (bf16_t)0;
+        bv[i] = in ? sgm.beta[k] : (bf16_t)0;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int k = lane + 64 * i;
+        if (k < K) {
+            const float w = bf16_to_f32(wv[i]) * sgm.scale;
+            const float r = bf16_round(w * bf16_to_f32(gv[i]));
+            cst += w * bf16_to_f32(bv[i]);
+            sgm.wp[(size_t)local * K + k] = f32_to_bf16(r);
+            sum += r;
         }
-        sgm.wp[(size_t)local * K + k] = f32_to_bf16(r);
-        sum += r;
     }
     sum = wave_sum(sum);
     cst = wave_sum(cst);
@@ -205,6 +215,143 @@ __global__ __launch_bounds__(256) void k_prep(PrepArgs a) {
         const float sn_hi = bf16_round(sum), sn_lo = bf16_round(sum - sn_hi);
         const float cn_hi = bf16_round(cn), cn_lo = bf16_round(cn - cn_hi);
         sgm.aug[local] = make_uint4(pack2(sn_hi, sn_lo), pack2(sn_hi, cn_hi), pack2(cn_lo, cn_hi), 0u);
+    }
+}
+
+__global__ __launch_bounds__(256) void k_prep(PrepArgs a) {
+    prep_row(a, blockIdx.x * 4 + (threadIdx.x >> 6), threadIdx.x & 63);
+}
+
+// ====================================================================================
+// Row mode: the pair bias b[h][i][j] = log2(e) * sum_c LN_z(z[i][j])_c W_b[h][c] and the weight
+// preparation in ONE launch (they do not depend on each other).  Blocks below bias_blocks take
+// 256 pairs each (one 32-pair tile per wavefront, the folded 32 x K weight tile built by the block
+// itself in LDS, same algebra as k_gemm's pair-bias tile); the blocks above them run prep_row.
+struct PrepBiasArgs {
+    PrepArgs prep;
+    int bias_blocks;
+    const bf16_t* z;             // [L][L][K]
+    const bf16_t *w_b, *gamma, *beta;   // [H][K], [K], [K]
+    float* bias;                 // [H][Lq][Lp]
+    int L, Lp, Lq, K, H;
+    float eps;
+};
+
+template <int KC>
+__global__ __launch_bounds__(512) void k_prep_bias(PrepBiasArgs a) {
+    const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    if ((int)blockIdx.x >= a.bias_blocks) {
+        prep_row(a.prep, ((int)blockIdx.x - a.bias_blocks) * 8 + wave, lane);
+        return;
+    }
+    constexpr int PITCH = KC * 32 + 16;                 // bytes per weight row in LDS (padded: conflict-free reads)
+    __shared__ __attribute__((aligned(16))) unsigned char s_w[32 * PITCH];
+    __shared__ uint4 s_aug[32];
+    const int K = a.K;
+
+    // ---- pairs of this wavefront: raw operand fragments (issued first)
+    const int tiles_m = a.L * (a.Lp >> 5);
+    int tg = blockIdx.x * 8 + wave;
+    if (tg > tiles_m - 1) tg = tiles_m - 1;             // (repeats the last tile: same values stored twice)
+    const int pr = tg * 32 + col;
+    const int qi = pr / a.Lp, kj = pr - qi * a.Lp;
+    const bool valid = kj < a.L;
+    Frag xa[KC];
+    const bf16_t* zp = a.z + ((size_t)qi * a.L + kj) * K;
+#pragma unroll
+    for (int s = 0; s < KC; ++s) {
+        xa[s].u = make_uint4(0, 0, 0, 0);
+        const int f = 16 * s + 8 * hf;
+        if (valid && f < K) xa[s].u = ldg16(zp + f);
+    }
+
+    // ---- the folded weight tile: 16 threads per row, 8-element pieces
+    {
+        const int row = tid >> 4, sub = tid & 15;
+        float sum = 0.f, cst = 0.f;
+#pragma unroll
+        for (int pc = sub; pc < 2 * KC; pc += 16) {
+            uint32_t outw[4] = {0u, 0u, 0u, 0u};
+            if (row < a.H && pc * 8 < K) {
+                Frag wv, gv, bv;
+                wv.u = ldg16(a.w_b + (size_t)row * K + pc * 8);
+                gv.u = ldg16(a.gamma + pc * 8);
+                bv.u = ldg16(a.beta + pc * 8);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float w0 = lo_f32(wv.w[i]) * kLog2e, w1 = hi_f32(wv.w[i]) * kLog2e;
+                    const float r0 = bf16_round(w0 * lo_f32(gv.w[i])), r1 = bf16_round(w1 * hi_f32(gv.w[i]));
+                    cst += w0 * lo_f32(bv.w[i]) + w1 * hi_f32(bv.w[i]);
+                    sum += r0 + r1;
+                    outw[i] = pack2(r0, r1);
+                }
+            }
+            *reinterpret_cast<uint4*>(&s_w[row * PITCH + pc * 16]) = make_uint4(outw[0], outw[1], outw[2], outw[3]);
+        }
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) {
+            sum += __shfl_xor(sum, o, 64);
+            cst += __shfl_xor(cst, o, 64);
+        }
+        if (sub == 0) {
+            const float sn_hi = bf16_round(sum), sn_lo = bf16_round(sum - sn_hi);
+            const float cn_hi = bf16_round(cst), cn_lo = bf16_round(cst - cn_hi);
+            s_aug[row] = make_uint4(pack2(sn_hi, sn_lo), pack2(sn_hi, cn_hi), pack2(cn_lo, cn_hi), 0u);
+        }
+    }
+
+    // ---- LayerNorm statistics of the wavefront's pairs (two passes over the registers)
+    float sum = 0.f;
+#pragma unroll
+    for (int s = 0; s < KC; ++s)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sum = add_pair(xa[s].w[i], sum);
+    sum += other_half(sum);
+    const float mu = sum / (float)K;
+    float sq = 0.f;
+#pragma unroll
+    for (int s = 0; s < KC; ++s) {
+        if (16 * s + 8 * hf < K) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float d0 = lo_f32(xa[s].w[i]) - mu, d1 = hi_f32(xa[s].w[i]) - mu;
+                sq += d0 * d0 + d1 * d1;
+            }
+        }
+    }
+    sq += other_half(sq);
+    const float var = sq / (float)K + a.eps;
+    const float rstd = valid ? rsqrtf(var) : 0.f;
+    const float m = valid ? -mu : 0.f, r = var * rstd;
+    const float m_hi = bf16_round(m), m_lo = bf16_round(m - m_hi);
+    const float r_hi = bf16_round(r), r_lo = bf16_round(r - r_hi);
+    Frag xaug;
+    xaug.u = make_uint4(0, 0, 0, 0);
+    if (hf == 0) xaug.u = make_uint4(pack2(m_hi, m_hi), pack2(m_lo, r_hi), pack2(r_hi, r_lo), 0u);
+
+    __syncthreads();
+    f32x16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+#pragma unroll
+    for (int s = 0; s < KC; ++s) {
+        Frag wf;
+        wf.u = *reinterpret_cast<const uint4*>(&s_w[col * PITCH + (2 * s + hf) * 16]);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf.v, xa[s].v, acc, 0, 0, 0);
+    }
+    {
+        Frag wa;
+        wa.u = s_aug[col];
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa.v, xaug.v, acc, 0, 0, 0);
+    }
+    // lane = pair (qi, kj), register v = head 8*(v/4) + 4*hf + v%4
+    float* bp = a.bias + (size_t)qi * a.Lp + kj;
+    const size_t plane = (size_t)a.Lq * a.Lp;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int h = 8 * (v >> 2) + 4 * hf + (v & 3);
+        if (h < a.H) bp[(size_t)h * plane] = acc[v] * rstd;
     }
 }
 
@@ -1065,29 +1212,28 @@ ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x
         seg(3, w.w_g, w.b_g, Hd, Hd, 3 * Hd, 1.f);
         seg(4, tri ? w.w_b : nullptr, nullptr, tri ? p.H : 0, 32, 4 * Hd, kLog2e);
         a.nseg = 5;
-        int rows = 4 * Hd + 32;
-        if (p.mode == FF_MSA_ROW) {     // the pair-bias projection of z, with its own LayerNorm
-            const int off = 4 * Hd + 32;
-            a.seg[5] = {(const bf16_t*)w.w_b, nullptr, (const bf16_t*)w.lnz_g, (const bf16_t*)w.lnz_b, m.zwp,
-                        m.aug + off, p.H, 32, p.c_z, kLog2e};
-            a.nseg = 6;
-            rows += 32;
+        const int rows = 4 * Hd + 32;
+        if (p.mode == FF_MSA_ROW) {
+            // the pair-bias projection of z (its own LayerNorm) shares the launch
+            PrepBiasArgs b{};
+            b.prep = a;
+            b.bias_blocks = (p.L * (Lp / 32) + 7) / 8;
+            b.z = (const bf16_t*)z; b.w_b = (const bf16_t*)w.w_b;
+            b.gamma = (const bf16_t*)w.lnz_g; b.beta = (const bf16_t*)w.lnz_b;
+            b.bias = ws.bias; b.L = p.L; b.Lp = Lp; b.Lq = Lq; b.K = p.c_z; b.H = p.H; b.eps = p.eps;
+            const dim3 grid(b.bias_blocks + (rows + 7) / 8);
+            const int kc = (p.c_z + 15) / 16;
+            Timed t(KK_BIAS, st);
+            if (kc <= 2) hipLaunchKernelGGL(k_prep_bias<2>, grid, dim3(512), 0, st, b);
+            else if (kc <= 4) hipLaunchKernelGGL(k_prep_bias<4>, grid, dim3(512), 0, st, b);
+            else if (kc <= 8) hipLaunchKernelGGL(k_prep_bias<8>, grid, dim3(512), 0, st, b);
+            else hipLaunchKernelGGL(k_prep_bias<16>, grid, dim3(512), 0, st, b);
+        } else {
+            Timed t(KK_PREP, st);
+            hipLaunchKernelGGL(k_prep, dim3((rows + 3) / 4), dim3(256), 0, st, a);
         }
-        Timed t(KK_PREP, st);
-        hipLaunchKernelGGL(k_prep, dim3((rows + 3) / 4), dim3(256), 0, st, a);
     }
-    if (p.mode == FF_MSA_ROW) {
-        const int off = 4 * p.Hd + 32;
-        // bias[h][i][j] from the pair representation: "batch rows" i, tokens j
-        GemmArgs g{};
-        g.src = (const bf16_t*)z; g.sr = p.L; g.sl = 1; g.r0 = 0; g.rows = p.L; g.L = p.L; g.Lp = Lp; g.Lq = Lq;
-        g.K = p.c_z; g.eps = p.eps; g.w = m.zwp; g.aug = m.aug + off;
-        g.Hd = p.Hd; g.H = p.H; g.D = p.d; g.invD = 1.f / (float)p.d; g.dsh = p.d == 8 ? 3 : (p.d == 16 ? 4 : 5); g.nt_main = 0; g.bias = ws.bias;
-        g.ft_first = 0; g.ft_count = 1; g.tiles_per_split = 1;
-        const int blocks_m = gemm_blocks_m(true, p.L * (Lp / 32), p.c_z);
-        Timed t(KK_BIAS, st);
-        launch_gemm<true>(g, p.c_z, dim3(blocks_m, 1), st);
-    } else if (tri && ws.chunk < p.R) {
+    if (tri && ws.chunk < p.R) {
         // chunked triangle attention: the bias of all rows is needed before the first chunk
         GemmArgs g = proj_args(p, m, ws);
         g.src = (const bf16_t*)x; g.r0 = 0; g.rows = p.R;
