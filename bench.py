@@ -32,11 +32,10 @@ PEAK_HBM_GBS = 8000.0
 # the factors a plain 256 MiB copy gives); null for workloads without such a run.
 _KIB = 1024
 TRAFFIC_BYTES = {
-    ("c2_row_bf16_train", "k_prep"): int((292.0 * 2.0 + 553.0) * _KIB),
-    ("c2_row_bf16_train", "pair bias pass"): int((8341.5 * 2.0 + 2048.0) * _KIB),
-    ("c2_row_bf16_train", "k_gemm<PROJ>"): int((10502.0 * 2.0 + 65536.0) * _KIB),
-    ("c2_row_bf16_train", "k_attn"): int((49292.0 * 2.0 + 16384.0) * _KIB),
-    ("c2_row_bf16_train", "k_gemm<OUT>"): int((8767.7 * 2.0 + 20737.8) * _KIB),
+    ("c2_row_bf16_train", "pair bias pass"): int((8535.6 * 2.0 + 2592.5) * _KIB),
+    ("c2_row_bf16_train", "k_gemm<PROJ>"): int((10498.0 * 2.0 + 65536.0) * _KIB),
+    ("c2_row_bf16_train", "k_attn"): int((49287.0 * 2.0 + 16384.0) * _KIB),
+    ("c2_row_bf16_train", "k_gemm<OUT>"): int((8774.0 * 2.0 + 22106.8) * _KIB),
 }
 
 
