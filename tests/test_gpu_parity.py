@@ -190,6 +190,23 @@ def test_ragged_shapes(dtype, mode, n_a, n_b, c, H, d, c_z, mask):
     check(to_np(run_case(case)), oracle_case(case), dtype, case.spec.name)
 
 
+@pytest.mark.parametrize("name", ["c2_row_bf16_train", "c3_tri_start_bf16_256", "c3_tri_end_bf16_256",
+                                  "c4_col_bf16_extra", "c5_tri_start_bf16_2048"])
+def test_bf16_configs_run_on_the_matrix_core_family(name):
+    """The bfloat16 workloads of the benchmark must not fall back to the float32 vector family
+    (device tensors from the binding are 16-byte aligned, which that family choice requires)."""
+    sp = I.SPECS[name]
+    desc = P.AttnDesc(sp.mode, P.FF_BF16, sp.n_a, sp.n_b, sp.c, sp.c_z, sp.heads, sp.head_dim, sp.ln_eps)
+    assert P.ff_attention_path(desc) == "mfma_bf16"
+
+
+def test_long_ragged_sequence_column_mode():
+    """4100 attended positions (129 tiles of 32 keys, the last one ragged, 36 masked) for a few
+    batch rows, head dim 32: many tiles per wavefront, a tail that is neither a multiple of 32 nor of 64."""
+    case = I.make_case(small_spec(COL, 4100, 3, 64, 2, 32, dtype="bf16", mask="tail:36"))
+    check(to_np(run_case(case)), oracle_case(case), "bf16", "long ragged column attention")
+
+
 @pytest.mark.parametrize("mode", [COL, TS])
 def test_reference_is_raised_when_late_keys_dominate(mode):
     """The keys of the last two 32-key tiles beat everything before them by tens of log2 units
