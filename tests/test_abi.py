@@ -122,3 +122,22 @@ def test_layernorm_argument_errors():
 def test_path_selection_reports_a_family():
     assert P.ff_attention_path(good_desc(dtype=P.FF_F32)) == "generic"
     assert P.ff_attention_path(good_desc(n_a=128, n_b=256, c=256, c_z=128, heads=8, head_dim=32)) in ("mfma_bf16", "generic")
+
+
+def test_workspace_never_holds_the_score_tensor_of_section_3_2():
+    """Section 3.2 of the paper: the attention score tensor of a triangle module takes
+    N_r^3 * N_head * 2 bytes, more than 20 GB over 48 layers at N_r = 384 (the fixture holds the
+    paper's figures).  The formula reproduces the stated bound, and the workspace this library
+    asks for at that shape stays three orders of magnitude below one layer's score tensor."""
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "attention_activation_memory.txt")
+    row = [l.split() for l in open(path) if l.strip() and not l.startswith("#")][0]
+    n_r, heads, esz, layers, stated = (int(v) for v in row)
+    per_layer = n_r ** 3 * heads * esz
+    assert per_layer * layers > stated
+    assert per_layer * layers < 1.2 * stated            # "can exceed 20 GB": 21.7 GB
+    desc = good_desc(mode=P.FF_TRI_START, n_a=n_r, n_b=n_r, c=128, c_z=0, heads=heads, head_dim=32)
+    need = P.ff_attention_workspace_bytes(desc, 64)
+    assert need * 8 < per_layer
+    # chunking bounds it: the whole-module workspace grows with the rows, the chunked one does not
+    assert P.ff_attention_workspace_bytes(desc, 0) > need
