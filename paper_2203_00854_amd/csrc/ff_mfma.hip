@@ -223,14 +223,16 @@ __global__ __launch_bounds__(256) void k_prep(PrepArgs a) {
 }
 
 // ====================================================================================
-// Row mode: the pair bias b[h][i][j] = log2(e) * sum_c LN_z(z[i][j])_c W_b[h][c] and the weight
-// preparation in ONE launch (they do not depend on each other).  Blocks below bias_blocks take
+// The pair bias b[h][i][j] = log2(e) * sum_c LN(z[i][j])_c W_b[h][c] as a pass of its own (row mode:
+// over the pair representation with its own LayerNorm; chunked triangle modes: over all of x before
+// the first chunk) and the weight preparation in ONE launch (they do not depend on each other).  Blocks below bias_blocks take
 // 256 pairs each (one 32-pair tile per wavefront, the folded 32 x K weight tile built by the block
 // itself in LDS, same algebra as k_gemm's pair-bias tile); the blocks above them run prep_row.
 struct PrepBiasArgs {
     PrepArgs prep;
     int bias_blocks;
-    const bf16_t* z;             // [L][L][K]
+    const bf16_t* z;             // pair (i, j) at z + (i*sr + j*sl)*K
+    int64_t sr, sl;
     const bf16_t *w_b, *gamma, *beta;   // [H][K], [K], [K]
     float* bias;                 // [H][Lq][Lp]
     int L, Lp, Lq, K, H;
@@ -258,7 +260,7 @@ __global__ __launch_bounds__(512) void k_prep_bias(PrepBiasArgs a) {
     const int qi = pr / a.Lp, kj = pr - qi * a.Lp;
     const bool valid = kj < a.L;
     Frag xa[KC];
-    const bf16_t* zp = a.z + ((size_t)qi * a.L + kj) * K;
+    const bf16_t* zp = a.z + ((int64_t)qi * a.sr + (int64_t)kj * a.sl) * K;
 #pragma unroll
     for (int s = 0; s < KC; ++s) {
         xa[s].u = make_uint4(0, 0, 0, 0);
@@ -1213,16 +1215,24 @@ ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x
         seg(4, tri ? w.w_b : nullptr, nullptr, tri ? p.H : 0, 32, 4 * Hd, kLog2e);
         a.nseg = 5;
         const int rows = 4 * Hd + 32;
-        if (p.mode == FF_MSA_ROW) {
-            // the pair-bias projection of z (its own LayerNorm) shares the launch
+        const bool chunked_tri = tri && ws.chunk < p.R;
+        if (p.mode == FF_MSA_ROW || chunked_tri) {
+            // the pair-bias pass shares the launch: row mode projects z (own LayerNorm); chunked
+            // triangle attention needs the bias of all rows before the first chunk
             PrepBiasArgs b{};
             b.prep = a;
             b.bias_blocks = (p.L * (Lp / 32) + 7) / 8;
-            b.z = (const bf16_t*)z; b.w_b = (const bf16_t*)w.w_b;
-            b.gamma = (const bf16_t*)w.lnz_g; b.beta = (const bf16_t*)w.lnz_b;
-            b.bias = ws.bias; b.L = p.L; b.Lp = Lp; b.Lq = Lq; b.K = p.c_z; b.H = p.H; b.eps = p.eps;
+            b.w_b = (const bf16_t*)w.w_b;
+            if (chunked_tri) {
+                b.z = (const bf16_t*)x; b.sr = p.sr; b.sl = p.sl; b.K = p.c;
+                b.gamma = gm; b.beta = bt;
+            } else {
+                b.z = (const bf16_t*)z; b.sr = p.L; b.sl = 1; b.K = p.c_z;
+                b.gamma = (const bf16_t*)w.lnz_g; b.beta = (const bf16_t*)w.lnz_b;
+            }
+            b.bias = ws.bias; b.L = p.L; b.Lp = Lp; b.Lq = Lq; b.H = p.H; b.eps = p.eps;
             const dim3 grid(b.bias_blocks + (rows + 7) / 8);
-            const int kc = (p.c_z + 15) / 16;
+            const int kc = (b.K + 15) / 16;
             Timed t(KK_BIAS, st);
             if (kc <= 2) hipLaunchKernelGGL(k_prep_bias<2>, grid, dim3(512), 0, st, b);
             else if (kc <= 4) hipLaunchKernelGGL(k_prep_bias<4>, grid, dim3(512), 0, st, b);
@@ -1232,15 +1242,6 @@ ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x
             Timed t(KK_PREP, st);
             hipLaunchKernelGGL(k_prep, dim3((rows + 3) / 4), dim3(256), 0, st, a);
         }
-    }
-    if (tri && ws.chunk < p.R) {
-        // chunked triangle attention: the bias of all rows is needed before the first chunk
-        GemmArgs g = proj_args(p, m, ws);
-        g.src = (const bf16_t*)x; g.r0 = 0; g.rows = p.R;
-        g.ft_first = g.nt_main; g.ft_count = 1; g.tiles_per_split = 1;
-        const int blocks_m = gemm_blocks_m(true, p.R * (Lp / 32), p.c);
-        Timed t(KK_BIAS, st);
-        launch_gemm<true>(g, p.c, dim3(blocks_m, 1), st);
     }
     return check_launch("prepare (mfma)");
 }
