@@ -827,11 +827,12 @@ struct AttnArgs {
     int r0, rows, L, Lp, Lq, H, Hd;
 };
 
-constexpr int kBiasPitch = 68;   // floats per LDS bias row (64 + 4 pad): conflict-free 16-byte reads
+// keys per bias tile in LDS (one barrier per tile): 64, or 128 for long sequences (GK template parameter)
+constexpr int kBiasPad = 4;      // floats added to an LDS bias row: conflict-free 16-byte reads
 constexpr float kRaise = 10.f;   // log2 units
 constexpr float kOver = 1048576.f;   // 2^20: partial denominator (16 keys) that triggers a raise of the reference
 
-template <int D, bool HAS_BIAS, int RB>
+template <int D, bool HAS_BIAS, int RB, int GK>
 __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
     constexpr int PCX = D / 8;              // index of the 8-slot piece holding the two extra slots
     constexpr int KS = PCX / 2 + 1;         // 16-wide contraction steps
@@ -839,6 +840,7 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
     constexpr bool ONES_ROW = D < 32;       // V^T row D is all ones: O^T row D = softmax denominator
     constexpr int LV = ONES_ROW ? 4 * (D / 8) : 0;   // its accumulator register (in the lower half-wave)
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr int TPG = GK / 32, kBiasPitch = GK + kBiasPad;
     float* s_bias = reinterpret_cast<float*>(smem);                                  // [2][64][kBiasPitch]
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, hf = lane >> 5;
@@ -871,30 +873,32 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
         if (xlane) qf[j][SX].w[0] = 0x3f800000u;        // (-m_ref = 0, 1.0)
     }
 
-    // ---- bias tile pipeline: [64 queries][64 keys]; thread loads rows b_row + 16 i, floats 4*b_c4 .. +3
-    // thread loads rows b_row + (RB*4) i, floats 4*b_c4 .. +3 (16 threads per row of 64 floats)
-    constexpr int BP = 16 / RB;                    // passes over the 64 rows
-    const int b_row = tid >> 4, b_c4 = tid & 15;
-    const float* bias_t = HAS_BIAS ? a.bias + ((size_t)h * a.Lq + q0 + b_row) * a.Lp + 4 * b_c4 : nullptr;
+    // ---- bias tile pipeline: [64 queries][GK keys]; GK/4 threads per row, RPP rows per pass
+    constexpr int TPR = GK / 4, RPP = RB * 64 / TPR, BP = 64 / RPP;
+    static_assert(BP == 2 || BP == 4, "bias tile passes");
+    const int b_row = tid / TPR, b_c4 = tid % TPR;
+    const float* bias_t = HAS_BIAS ? a.bias + ((size_t)h * a.Lq + q0 + b_row) * a.Lp : nullptr;
     float* s_bias_t = s_bias + (size_t)b_row * kBiasPitch + 4 * b_c4;
     // (named registers: an array captured by a lambda would be spilled to scratch)
     float4 bq0, bq1, bq2, bq3;
-    auto load_bias = [&](int it) {
-        const float* bp = bias_t + 64 * it;
+    auto load_bias = [&](int g) {
+        int colk = GK * g + 4 * b_c4;              // (a last group that is only half there repeats valid keys)
+        if (colk > a.Lp - 4) colk = a.Lp - 4;
+        const float* bp = bias_t + colk;
         bq0 = *reinterpret_cast<const float4*>(bp);
-        if constexpr (BP > 1) bq1 = *reinterpret_cast<const float4*>(bp + (size_t)(RB * 4) * a.Lp);
+        bq1 = *reinterpret_cast<const float4*>(bp + (size_t)RPP * a.Lp);
         if constexpr (BP > 2) {
-            bq2 = *reinterpret_cast<const float4*>(bp + (size_t)(RB * 8) * a.Lp);
-            bq3 = *reinterpret_cast<const float4*>(bp + (size_t)(RB * 12) * a.Lp);
+            bq2 = *reinterpret_cast<const float4*>(bp + (size_t)(2 * RPP) * a.Lp);
+            bq3 = *reinterpret_cast<const float4*>(bp + (size_t)(3 * RPP) * a.Lp);
         }
     };
     auto store_bias = [&](int buf) {
         float* sp = s_bias_t + (size_t)buf * 64 * kBiasPitch;
         *reinterpret_cast<float4*>(sp) = bq0;
-        if constexpr (BP > 1) *reinterpret_cast<float4*>(sp + RB * 4 * kBiasPitch) = bq1;
+        *reinterpret_cast<float4*>(sp + RPP * kBiasPitch) = bq1;
         if constexpr (BP > 2) {
-            *reinterpret_cast<float4*>(sp + RB * 8 * kBiasPitch) = bq2;
-            *reinterpret_cast<float4*>(sp + RB * 12 * kBiasPitch) = bq3;
+            *reinterpret_cast<float4*>(sp + 2 * RPP * kBiasPitch) = bq2;
+            *reinterpret_cast<float4*>(sp + 3 * RPP * kBiasPitch) = bq3;
         }
     };
     if constexpr (HAS_BIAS) load_bias(0);      // (stored to LDS after the first K and V loads have been issued)
@@ -949,11 +953,12 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
     // S^T of tile kt into sa in two parts: the bias tile as accumulator input (LDS reads, issued
     // early: the loads of the next K and V tiles hide their latency), then the contraction, which
     // returns whether any key of the tile is valid
-    auto qk_bias = [&](int kt, f32x16 (&sa)[2], const float* sb) {
+    auto qk_bias = [&](int kt, f32x16 (&sa)[2]) {
+        const float* sb = s_bias + (size_t)((kt / TPG) & 1) * 64 * kBiasPitch;
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             if constexpr (HAS_BIAS) {
-                const float* br = sb + (size_t)(32 * j + col) * kBiasPitch + 32 * (kt & 1) + 8 * hf;
+                const float* br = sb + (size_t)(32 * j + col) * kBiasPitch + 32 * (kt % TPG) + 8 * hf;
 #pragma unroll
                 for (int c = 0; c < 2; ++c)
 #pragma unroll
@@ -1064,37 +1069,40 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
     fetch_v(vb0, 0);
     if constexpr (HAS_BIAS) {
         store_bias(0);
-        if (nt > 2) load_bias(1);
+        if (TPG == 2 && nt > 2) load_bias(1);
     }
     __syncthreads();                        // bias group 0 is in LDS
     f32x16 s0[2], s1[2];
-    qk_bias(0, s0, s_bias);
+    qk_bias(0, s0);
     bool live0 = qk_mma(kb0, mv0, 0, s0), live1 = false;
-    int cur = 0;                            // LDS buffer of the current 64-key group
+    // The bias of key group g (TPG tiles) sits in LDS buffer g & 1.  It is loaded to registers one
+    // and a half iterations before tile g*TPG is first touched, stored and published (the only
+    // barrier of the group) at the end of the even half of the iteration before.
     for (int i = 0; i < nt; i += 2) {
         // ---- even tile i: K(i+2) -> set 0, V(i+1) -> set 1, S^T(i+1) -> s1, exponentials of s0
-        qk_bias(i + 1, s1, s_bias + (size_t)cur * 64 * kBiasPitch);
+        qk_bias(i + 1, s1);
         if (i + 2 < nt) fetch_k(kb0, mv0, i + 2);
         fetch_v(vb1, i + 1);
         live1 = qk_mma(kb1, mv1, i + 1, s1);
         if (live0) soft_pv(s0, vb0, s1, live1);
         if constexpr (HAS_BIAS) {
-            if (i + 2 < nt) store_bias(cur ^ 1);
-            __syncthreads();
+            if ((i + 2) % TPG == 0 && i + 2 < nt) {
+                store_bias(((i + 2) / TPG) & 1);
+                __syncthreads();
+            }
         }
         // ---- odd tile i+1: K(i+3) -> set 1, V(i+2) -> set 0, S^T(i+2) -> s0, exponentials of s1
         live0 = false;
         if (i + 2 < nt) {
-            qk_bias(i + 2, s0, s_bias + (size_t)(cur ^ 1) * 64 * kBiasPitch);
+            qk_bias(i + 2, s0);
             fetch_k(kb1, mv1, i + 3);
             fetch_v(vb0, i + 2);
             if constexpr (HAS_BIAS) {
-                if (i + 4 < nt) load_bias((i >> 1) + 2);
+                if ((i + 4) % TPG == 0 && i + 4 < nt) load_bias((i + 4) / TPG);
             }
             live0 = qk_mma(kb0, mv0, i + 2, s0);
         }
         if (live1) soft_pv(s1, vb1, s0, live0);
-        cur ^= 1;
     }
 
     // ---- epilogue: normalise, gate, store.  o_acc[j]: lane = query, register v = e = 8*(v/4) + 4*hf + v%4
@@ -1182,6 +1190,17 @@ static int pick_split(int blocks_m, int tiles_n) {
     while (blocks_m * split < 256 && split < tiles_n) ++split;
     while (tiles_n % split != 0) ++split;      // equal shares
     return split;
+}
+
+template <int D, bool HAS_BIAS, int RB, int GK>
+static void launch_attn(dim3 grid, size_t smem, hipStream_t st, const AttnArgs& a) {
+    static bool attr_set = false;          // more than 64 KiB of dynamic LDS has to be asked for once
+    if (!attr_set && smem > 64 * 1024) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn<D, HAS_BIAS, RB, GK>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((k_attn<D, HAS_BIAS, RB, GK>), grid, dim3(RB * 64), smem, st, a);
 }
 
 static GemmArgs proj_args(const Problem& p, const MfmaWs& m, const Workspace& ws) {
@@ -1274,11 +1293,14 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
         const int rb = rows >= 8 ? 8 : 4;
         const int n_blocks = (Lq / 64) * p.H * ((rows + rb - 1) / rb);
         dim3 grid(((n_blocks + 7) / 8) * 8);
-        const size_t bias_bytes = (size_t)2 * 64 * kBiasPitch * 4;   // two [64][kBiasPitch] float tiles
-#define FF_ATTN2(DD, RBV)                                                                                     \
-    do {                                                                                                      \
-        if (p.has_bias) hipLaunchKernelGGL((k_attn<DD, true, RBV>), grid, dim3(RBV * 64), bias_bytes, st, a); \
-        else hipLaunchKernelGGL((k_attn<DD, false, RBV>), grid, dim3(RBV * 64), 0, st, a);                   \
+        // keys per bias tile: 128 halve the barriers of long sequences, 64 keep the first tile of short ones small
+        const int gk = (rb == 8 && Lp >= 512) ? 128 : 64;
+        const size_t bias_bytes = (size_t)2 * 64 * (gk + kBiasPad) * 4;   // two float tiles
+#define FF_ATTN2(DD, RBV)                                                   \
+    do {                                                                    \
+        if (p.has_bias && gk == 128) launch_attn<DD, true, 8, 128>(grid, bias_bytes, st, a); \
+        else if (p.has_bias) launch_attn<DD, true, RBV, 64>(grid, bias_bytes, st, a);        \
+        else launch_attn<DD, false, RBV, 64>(grid, 0, st, a);                                \
     } while (0)
 #define FF_ATTN(DD)                  \
     do {                             \

@@ -180,6 +180,8 @@ SHAPES = [
     (COL, 520, 5, 64, 8, 8, 0, "tail:100"),
     (ROW, 3, 40, 48, 3, 24, 20, "tail:3"),       # head_dim 24, channels not a power of two
     (TS, 33, 33, 100, 2, 64, 0, "none"),         # head_dim 64
+    (TS, 530, 530, 32, 2, 32, 0, "tail:11"),     # 17 key tiles: the last 128-key bias group is only half there
+    (ROW, 9, 700, 64, 2, 32, 16, "random:0.9"),  # 22 key tiles, nine batch rows (a ragged second block of rows)
 ]
 
 
