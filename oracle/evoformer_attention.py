@@ -18,7 +18,9 @@ What the paper fixes and where:
     attention bias, and the pair stack uses "similar blocks"          (Section 2.3);
   * the softmax input is the scaled logits plus a mask term plus a bias term
                                                                        (Section 5.2);
-  * the gate is bias + sigmoid + element-wise product                 (Section 5.2, JIT fusion).
+  * the gate is bias + sigmoid + element-wise product                 (Section 5.2, JIT fusion);
+  * each module ends in bias + dropout + add, the residual update of the representation
+    (Section 5.2, JIT fusion; dropout is the identity outside training).
 The paper prints no equations for the four modules and defers to AlphaFold 2; the index
 placement below is AlphaFold's published MSA row attention with pair bias, MSA column
 attention and triangle attention around the starting / ending node.
@@ -154,6 +156,21 @@ def gated_attention(mode, x, z, mask, w, heads, eps=1e-5, rows=None):
     if rows is not None:
         return res
     return res if along_b else res.transpose(1, 0, 2)
+
+
+def gated_attention_residual(mode, x, z, mask, w, heads, eps=1e-5, rows=None):
+    """The module together with the residual add that closes it in the Evoformer block:
+    x + gated_attention(x) (Section 5.2 lists "bias + dropout + add" as the module's last
+    fused step; b_o is the bias, dropout is the identity at inference, x is what is added).
+    rows as in gated_attention: [len(rows), L, c] for the chosen batch rows."""
+    y = gated_attention(mode, x, z, mask, w, heads, eps, rows)
+    x = np.asarray(x, _F)
+    if rows is None:
+        return x + y
+    rows = list(rows)
+    if mode in (MODE_ROW, MODE_TRI_START):
+        return x[rows, :, :] + y
+    return x[:, rows, :].transpose(1, 0, 2) + y
 
 
 def attention_weights(mode, x, z, mask, w, heads, eps, r, h):

@@ -103,6 +103,24 @@ def test_brute_force_tiny(mode, n_a, n_b, mask):
     assert max_abs(got, ref) < 1e-12
 
 
+@pytest.mark.parametrize("mode,n_a,n_b,mask", [
+    (ROW, 3, 5, "tail:2"), (COL, 5, 3, "tail:2"), (TS, 5, 5, "outer:0.7"), (TE, 4, 4, "random:0.6"),
+])
+def test_residual_update_brute_force(mode, n_a, n_b, mask):
+    """x + module(x), element by element, with the module from the scalar brute force."""
+    case = I.make_case(small_spec(mode, n_a, n_b, c=4, heads=2, d=2, c_z=3, mask=mask))
+    x, z, m, w = f64_inputs(case)
+    got = O.gated_attention_residual(mode, x, z, m, w, 2, EPS)
+    y = brute_force(mode, x, z, m, w, 2, EPS)
+    ref = np.empty_like(y)
+    for a in range(n_a):
+        for b in range(n_b):
+            for ch in range(4):
+                ref[a, b, ch] = x[a, b, ch] + y[a, b, ch]
+    assert got.shape == x.shape
+    assert max_abs(got, ref) < 1e-12
+
+
 def test_brute_force_config1_rows():
     """Benchmark config 1 (row mode, N_seq=8, N_res=32, c_m=32, c_z=16, H=4, d=8), two
     sequences of it by brute force."""
@@ -332,6 +350,32 @@ def test_weights_sum_to_one_and_masked_are_zero(mode, n_a, n_b):
             assert ((P >= 0) & (P <= 1)).all()
         else:
             assert (P == 0).all()
+
+
+@pytest.mark.parametrize("mode,n_a,n_b", [(ROW, 4, 9), (COL, 9, 4), (TS, 6, 6), (TE, 6, 6)])
+def test_residual_update_closed_forms(mode, n_a, n_b):
+    """W_o = 0: the update adds b_o to every token.  Fully masked batch rows: likewise.
+    A subset of batch rows comes back in the module's own (batch row, position) order."""
+    x, z, m, w = _case(mode, n_a, n_b, mask="tail:2")
+    w0 = dict(w)
+    w0["w_o"] = np.zeros_like(w["w_o"])
+    got = O.gated_attention_residual(mode, x, z, m, w0, 2, EPS)
+    assert max_abs(got, x + w["b_o"]) == 0.0
+    got = O.gated_attention_residual(mode, x, z, np.zeros_like(m), w, 2, EPS)
+    assert max_abs(got, x + w["b_o"]) == 0.0
+    full = O.gated_attention_residual(mode, x, z, m, w, 2, EPS)
+    assert max_abs(full - x, O.gated_attention(mode, x, z, m, w, 2, EPS)) < 1e-13
+    rows = [2, 0]
+    sub = O.gated_attention_residual(mode, x, z, m, w, 2, EPS, rows=rows)
+    ref = full[rows] if mode in (ROW, TS) else full[:, rows].transpose(1, 0, 2)
+    assert max_abs(sub, ref) == 0.0
+
+
+def test_residual_update_triangle_end_is_transposed_triangle_start():
+    x, z, m, w = _case(TS, 6, 6, mask="outer:0.7")
+    a = O.gated_attention_residual(TE, x, None, m, w, 2, EPS)
+    b = O.gated_attention_residual(TS, x.transpose(1, 0, 2), None, m.T, w, 2, EPS).transpose(1, 0, 2)
+    assert max_abs(a, b) < 1e-13
 
 
 def test_fully_masked_row_gives_output_bias():
