@@ -124,6 +124,21 @@ ff_status ff_attention_chunked(const ff_attn_desc* desc, const ff_attn_weights* 
                                void* out, void* ws, size_t ws_bytes, void* hip_stream,
                                int32_t chunk_rows);
 
+/* The module together with the residual update that closes it in the Evoformer block
+ * (Section 5.2 lists "bias + dropout + add" as the last fused step of a module; dropout is
+ * the identity at inference):
+ *   out = x + ((gate * context) W_o^T + b_o)
+ * The sum is formed in float32 and rounded to the tensor dtype once.  Arguments as for
+ * ff_attention_chunked, with chunk_rows = 0 meaning all batch rows at once.  out may be x
+ * itself (the representation is updated in place, saving a second [n_a, n_b, c] tensor:
+ * 1 GiB at N_res = 2048) or must not overlap x at all; it must not overlap z or ws.
+ * In the triangle modes the bias is taken from x as it was before the call.
+ * Errors as for ff_attention_chunked; chunk_rows < 0 -> FF_EINVAL. */
+ff_status ff_gated_attention_residual(const ff_attn_desc* desc, const ff_attn_weights* w,
+                                      const void* x, const void* z, const float* mask,
+                                      void* out, void* ws, size_t ws_bytes, void* hip_stream,
+                                      int32_t chunk_rows);
+
 /* Name of the kernel family that ff_gated_attention would pick for this shape:
  * "mfma_bf16" (matrix-core path) or "generic" (float32 vector path).  For tests and the
  * benchmark report.  NULL if desc is invalid. */

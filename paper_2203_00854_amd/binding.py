@@ -59,6 +59,8 @@ def lib() -> C.CDLL:
         L.ff_gated_attention.argtypes = common
         L.ff_attention_chunked.restype = C.c_int
         L.ff_attention_chunked.argtypes = common + [C.c_int32]
+        L.ff_gated_attention_residual.restype = C.c_int
+        L.ff_gated_attention_residual.argtypes = common + [C.c_int32]
         L.ff_attention_path.restype = C.c_char_p
         L.ff_attention_path.argtypes = [C.POINTER(AttnDesc)]
         L.ff_profile_enable.restype = None
@@ -173,6 +175,23 @@ def ff_attention_chunked(desc: AttnDesc, w: Dict[str, "object"], x, z=None, mask
     wts = make_weights(w)
     _check(lib().ff_attention_chunked(C.byref(desc), C.byref(wts), _ptr(x), _ptr(z), _ptr(mask), _ptr(out), _ptr(ws),
                                       ws.numel(), _stream(), chunk_rows))
+    return out
+
+
+def ff_gated_attention_residual(desc: AttnDesc, w: Dict[str, "object"], x, z=None, mask=None, chunk_rows: int = 0,
+                                out=None, ws=None, in_place: bool = False):
+    """x + module(x); chunk_rows = 0 takes all batch rows at once.  in_place=True updates x itself."""
+    import torch
+    assert x.is_cuda and x.is_contiguous()
+    if in_place:
+        out = x
+    elif out is None:
+        out = torch.empty_like(x)
+    if ws is None:
+        ws = _alloc_ws(ff_attention_workspace_bytes(desc, max(chunk_rows, 0)), x.device)
+    wts = make_weights(w)
+    _check(lib().ff_gated_attention_residual(C.byref(desc), C.byref(wts), _ptr(x), _ptr(z), _ptr(mask), _ptr(out),
+                                             _ptr(ws), ws.numel(), _stream(), chunk_rows))
     return out
 
 

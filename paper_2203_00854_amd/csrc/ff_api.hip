@@ -123,7 +123,7 @@ static bool overlaps(const void* a, size_t an, const void* b, size_t bn) {
 
 static ff_status run(const ff_attn_desc* desc, const ff_attn_weights* w, const void* x, const void* z,
                      const float* mask, void* out, void* wsp, size_t ws_bytes, void* stream_, int chunk_rows,
-                     bool chunked) {
+                     bool chunked, bool residual = false) {
     Problem p;
     ff_status st = make_problem(desc, &p);
     if (st != FF_OK) return st;
@@ -142,8 +142,12 @@ static ff_status run(const ff_attn_desc* desc, const ff_attn_weights* w, const v
     const size_t esz = p.dtype == FF_F32 ? 4 : 2;
     const size_t x_bytes = (size_t)p.n_a * p.n_b * p.c * esz;
     const size_t z_bytes = (size_t)p.n_b * p.n_b * p.c_z * esz;
-    if (overlaps(out, x_bytes, x, x_bytes) || (z && overlaps(out, x_bytes, z, z_bytes)))
-        return fail(FF_EINVAL, "out must not overlap x or z");
+    // (the residual update may replace x in place: every kernel has read x, or the part of it that a
+    // chunk needs, before the output projection of that chunk stores, and an element of the
+    // residual is read by the very lane that stores it)
+    if ((overlaps(out, x_bytes, x, x_bytes) && !(residual && out == x)) || (z && overlaps(out, x_bytes, z, z_bytes)))
+        return fail(FF_EINVAL, residual ? "out must be x itself or not overlap x, and must not overlap z"
+                                        : "out must not overlap x or z");
     int chunk = chunked ? (chunk_rows < p.R ? chunk_rows : p.R) : p.R;
     const size_t need = workspace_need(p, chunk);
     if (!wsp) return fail(FF_EINVAL, "workspace is NULL (%zu bytes needed)", need);
@@ -167,10 +171,10 @@ static ff_status run(const ff_attn_desc* desc, const ff_attn_weights* w, const v
     for (int r0 = 0; r0 < p.R; r0 += chunk) {
         int rows = p.R - r0 < chunk ? p.R - r0 : chunk;
         if (fast) {
-            st = mfma_chunk(p, *w, x, mask, out, ws, r0, rows, stream);
+            st = mfma_chunk(p, *w, x, mask, residual ? x : nullptr, out, ws, r0, rows, stream);
         } else {
             Timed t(KK_GENERIC, stream);
-            st = generic_chunk(p, *w, x, mask, out, ws, r0, rows, stream);
+            st = generic_chunk(p, *w, x, mask, residual ? x : nullptr, out, ws, r0, rows, stream);
         }
         if (st != FF_OK) return st;
     }
@@ -214,6 +218,13 @@ ff_status ff_attention_chunked(const ff_attn_desc* desc, const ff_attn_weights* 
                                const float* mask, void* out, void* ws, size_t ws_bytes, void* hip_stream,
                                int32_t chunk_rows) {
     return run(desc, w, x, z, mask, out, ws, ws_bytes, hip_stream, chunk_rows, true);
+}
+
+ff_status ff_gated_attention_residual(const ff_attn_desc* desc, const ff_attn_weights* w, const void* x,
+                                      const void* z, const float* mask, void* out, void* ws, size_t ws_bytes,
+                                      void* hip_stream, int32_t chunk_rows) {
+    if (chunk_rows < 0) return fail(FF_EINVAL, "chunk_rows must be >= 0 (got %d)", chunk_rows);
+    return run(desc, w, x, z, mask, out, ws, ws_bytes, hip_stream, chunk_rows, chunk_rows > 0, true);
 }
 
 const char* ff_attention_path(const ff_attn_desc* desc) {

@@ -93,8 +93,9 @@ ff_status generic_prepare(const Problem& p, const ff_attn_weights& w, const void
 // the generic bias kernel writing into a [H][Lq][Lp] tensor (both families use it)
 ff_status generic_bias_into(const Problem& p, const ff_attn_weights& w, const void* x, const void* z, float* bias,
                             int Lq, int Lp, hipStream_t stream);
+// res: NULL, or a tensor laid out like out that is added to the module's output (may be out itself)
 ff_status generic_chunk(const Problem& p, const ff_attn_weights& w, const void* x, const float* mask,
-                        void* out, const Workspace& ws, int r0, int rows, hipStream_t stream);
+                        const void* res, void* out, const Workspace& ws, int r0, int rows, hipStream_t stream);
 
 // bf16 matrix-core path (ff_mfma_*.hip)
 bool mfma_supported(const Problem& p);
@@ -102,7 +103,7 @@ size_t mfma_workspace(const Problem& p, int chunk, Workspace* ws, void* base);
 ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x, const void* z,
                        const Workspace& ws, hipStream_t stream);
 ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, const float* mask,
-                     void* out, const Workspace& ws, int r0, int rows, hipStream_t stream);
+                     const void* res, void* out, const Workspace& ws, int r0, int rows, hipStream_t stream);
 
 // LayerNorm (ff_layernorm.hip)
 ff_status layernorm_launch(const void* x, const void* g, const void* b, void* y, int64_t rows, int c,

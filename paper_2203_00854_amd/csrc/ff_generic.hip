@@ -113,6 +113,7 @@ struct GenericGemmArgs {
     int Hd;
     float qscale;
     void* cdst;            // qkvg or out
+    const void* res;       // !PROJ: residual added to the output (laid out like out, may be out itself) or NULL
 };
 
 template <typename T, bool PROJ>
@@ -187,7 +188,10 @@ __global__ __launch_bounds__(256) void k_gemm_generic(GenericGemmArgs g) {
             } else {
                 v += to_f32<T>(((const T*)g.bvec)[n]);
                 const int rl = t / g.L, l = t % g.L;
-                ((T*)g.cdst)[((int64_t)(g.r0 + rl) * g.sr + (int64_t)l * g.sl) * g.N + n] = from_f32<T>(v);
+                const int64_t at = ((int64_t)(g.r0 + rl) * g.sr + (int64_t)l * g.sl) * g.N + n;
+                // (the thread that stores an element is the one that read it: in place is safe)
+                if (g.res) v += to_f32<T>(((const T*)g.res)[at]);
+                ((T*)g.cdst)[at] = from_f32<T>(v);
             }
         }
     }
@@ -274,8 +278,8 @@ static ff_status bias_t(const Problem& p, const ff_attn_weights& w, const void* 
 }
 
 template <typename T>
-static ff_status chunk_t(const Problem& p, const ff_attn_weights& w, const void* x, const float* mask, void* out,
-                         const Workspace& ws, int r0, int rows, hipStream_t st) {
+static ff_status chunk_t(const Problem& p, const ff_attn_weights& w, const void* x, const float* mask, const void* res,
+                         void* out, const Workspace& ws, int r0, int rows, hipStream_t st) {
     const int tokens = rows * p.L;
     hipLaunchKernelGGL((k_stats_generic<T>), dim3((tokens + 3) / 4), dim3(256), 0, st, (const T*)x, p.sr, p.sl, p.c,
                        p.L, r0, tokens, p.eps, ws.stats);
@@ -301,7 +305,7 @@ static ff_status chunk_t(const Problem& p, const ff_attn_weights& w, const void*
 
     GenericGemmArgs o{};
     o.a = ws.o; o.sr = p.sr; o.sl = p.sl; o.L = p.L; o.r0 = r0; o.tokens = tokens;
-    o.K = p.Hd; o.N = p.c; o.w[0] = w.w_o; o.bvec = w.b_o; o.Hd = p.Hd; o.cdst = out;
+    o.K = p.Hd; o.N = p.c; o.w[0] = w.w_o; o.bvec = w.b_o; o.Hd = p.Hd; o.cdst = out; o.res = res;
     hipLaunchKernelGGL((k_gemm_generic<T, false>), dim3((tokens + 63) / 64, (o.N + 63) / 64), dim3(256), 0, st, o);
     return check_launch("attention chunk (generic)");
 }
@@ -318,10 +322,10 @@ ff_status generic_bias_into(const Problem& p, const ff_attn_weights& w, const vo
                              : bias_t<bf16_t>(p, w, x, z, bias, Lq, Lp, stream);
 }
 
-ff_status generic_chunk(const Problem& p, const ff_attn_weights& w, const void* x, const float* mask, void* out,
-                        const Workspace& ws, int r0, int rows, hipStream_t stream) {
-    return p.dtype == FF_F32 ? chunk_t<float>(p, w, x, mask, out, ws, r0, rows, stream)
-                             : chunk_t<bf16_t>(p, w, x, mask, out, ws, r0, rows, stream);
+ff_status generic_chunk(const Problem& p, const ff_attn_weights& w, const void* x, const float* mask,
+                        const void* res, void* out, const Workspace& ws, int r0, int rows, hipStream_t stream) {
+    return p.dtype == FF_F32 ? chunk_t<float>(p, w, x, mask, res, out, ws, r0, rows, stream)
+                             : chunk_t<bf16_t>(p, w, x, mask, res, out, ws, r0, rows, stream);
 }
 
 }  // namespace ff

@@ -384,6 +384,7 @@ struct GemmArgs {
     bf16_t *q, *k, *g, *vt;  // PROJ outputs
     float* bias;             // PROJ pair-bias output [H][Lq][Lp]
     bf16_t* out;             // OUT output, token (r,l) at (r*sr + l*sl)*N
+    const bf16_t* res;       // OUT with RES: added to the output, laid out like out (may be out itself)
     int N;                   // OUT: features
     int ft_first, ft_count;  // range of feature tiles of this launch
     int tiles_per_split;     // tiles per blockIdx.y
@@ -421,8 +422,9 @@ static size_t gemm_smem_bytes(int kc, int tt, int ns, int tiles_per_split) {
 // tile kinds of k_gemm (q and k share their epilogue)
 enum { TK_Q = 0, TK_K = 1, TK_V = 2, TK_GATE = 3, TK_BIAS = 4, TK_OUT = 5 };
 
-template <int KC, bool PROJ, int TT, int NS>
+template <int KC, bool PROJ, int TT, int NS, bool RES>
 __global__ __launch_bounds__(kGemmWaves * 64, 2) void k_gemm(GemmArgs a) {
+    static_assert(!(PROJ && RES), "the residual belongs to the output projection");
     constexpr int NW = kGemmWaves;
     constexpr int P = 2 * KC;                           // 16-byte pieces per weight row
     constexpr int STAGE = 32 * P * 16;                  // bytes of one 32-feature tile in LDS
@@ -445,18 +447,21 @@ __global__ __launch_bounds__(kGemmWaves * 64, 2) void k_gemm(GemmArgs a) {
 
     // ---- token operand fragments, raw (issued first: they come from HBM)
     Frag xa[TT][KC];
-    bool tok_valid[TT];
+    bool tok_valid[TT], tile_off[TT];     // tile_off (wave-uniform): a repeated tile that must not be stored
     int tok_rl[TT], tok_l[TT];            // batch row (wave-uniform) and position of this lane's token
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
         // (token tiles beyond the last one repeat it: the same values are stored twice)
         int tg = (blockIdx.x * NW + wave) * TT + tt;
-        if (tg > tiles_m - 1) tg = tiles_m - 1;
+        const bool repeated = tg > tiles_m - 1;
+        if (repeated) tg = tiles_m - 1;
         const int p = tg * 32 + col;
         const int rl = p / a.Lp, l = p - rl * a.Lp;
         tok_rl[tt] = __builtin_amdgcn_readfirstlane(rl);       // a tile lies inside one batch row
         tok_l[tt] = l;
-        tok_valid[tt] = l < a.L;
+        // (with a residual that may be the output itself a tile must be added and stored once only)
+        tile_off[tt] = RES && repeated;
+        tok_valid[tt] = l < a.L && !tile_off[tt];
         const bf16_t* sp = a.src + ((int64_t)(a.r0 + rl) * a.sr + (int64_t)l * a.sl) * K;
 #pragma unroll
         for (int s = 0; s < KC; ++s) {
@@ -521,12 +526,16 @@ __global__ __launch_bounds__(kGemmWaves * 64, 2) void k_gemm(GemmArgs a) {
 #pragma unroll
     for (int tt = 0; tt < TT; ++tt) {
         if constexpr (PROJ) row_base[tt] = (size_t)tok_rl[tt] * a.H * LpD;
-        else row_base[tt] = (size_t)(((int64_t)(a.r0 + tok_rl[tt]) * a.sr + (int64_t)tok_l[tt] * a.sl) * a.N);
+        else {
+            // (pad tokens take the address of the last real one: they load the residual, never store)
+            const int lc = tok_l[tt] < a.L ? tok_l[tt] : a.L - 1;
+            row_base[tt] = (size_t)(((int64_t)(a.r0 + tok_rl[tt]) * a.sr + (int64_t)lc * a.sl) * a.N);
+        }
         if constexpr (PROJ) t_lane[tt] = (unsigned)tok_l[tt] * a.D + (a.D >= 16 ? 8 * hf : hf * LpD);
         else t_lane[tt] = 8 * hf;
         const int l0 = __builtin_amdgcn_readfirstlane(tok_l[tt] - col);
         l0v[tt] = l0 * a.D;                                                   // (l0 / 32) * D * 32
-        any_valid[tt] = l0 < a.L;
+        any_valid[tt] = l0 < a.L && !tile_off[tt];
     }
     float rstd[TT];           // 1 / standard deviation of this lane's token
     Frag xaug[TT];            // its extra piece of the contraction: (-mean, standard deviation) as bf16 pairs (see k_prep)
@@ -534,6 +543,36 @@ __global__ __launch_bounds__(kGemmWaves * 64, 2) void k_gemm(GemmArgs a) {
     for (int tt = 0; tt < TT; ++tt) {
         rstd[tt] = 0.f;
         xaug[tt].u = make_uint4(0, 0, 0, 0);
+    }
+
+    // ---- residual (RES): the matrix core adds it.  Two more contraction steps multiply a
+    // selection matrix (feature f of the tile picks slot f, then f - 16) with the residual
+    // values of 16 features per token: 1.0 * bf16 into the float32 accumulator is exact, the
+    // operand is the token's row as it lies in memory (16 bytes per lane, the very bytes the
+    // lane stores later, so the output may replace the residual in place), and the sum is
+    // rounded to bf16 once.  ra feeds the first tile of a pipeline step, rb the second; each is
+    // reloaded for the next step as soon as its matrix instructions have been issued.
+    Frag sel[2];
+    Frag ra[TT][2], rb[TT][2];
+    auto load_res = [&](Frag (&r)[TT][2], int ft) {
+        if (ft > ft_end - 1) ft = ft_end - 1;            // (past the end: a harmless repeat)
+#pragma unroll
+        for (int tt = 0; tt < TT; ++tt) {
+            const bf16_t* rp = a.res + row_base[tt] + (size_t)ft * 32 + 8 * hf;
+            r[tt][0].u = ldg16(rp);
+            r[tt][1].u = ldg16(rp + 16);
+        }
+    };
+    if constexpr (RES) {
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            const int k = col - 16 * m - 8 * hf;             // slot of this lane's feature inside its piece
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                sel[m].w[i] = (k >> 1) == i ? ((k & 1) ? 0x3f800000u : 0x00003f80u) : 0u;
+        }
+        load_res(ra, ft_begin);
+        load_res(rb, ft_begin + 1);
     }
 
     __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
@@ -547,12 +586,12 @@ __global__ __launch_bounds__(kGemmWaves * 64, 2) void k_gemm(GemmArgs a) {
     constexpr int VPC = 16 / KC > 0 ? 16 / KC : 1;      // epilogue values per contraction step
     constexpr int AHEAD = KC < 4 ? KC : 4;              // operand reads in flight (LDS latency is about two steps)
     const int LpD2 = LpD;
-    int n_stores = 0;                     // store instructions issued in this step (a lower bound)
+    int n_stores = 0;                     // stores and residual loads issued in this step (a lower bound)
     f32x16 acc[2][TT];
 
     // matrix part of tile ftn (weights at st) into an[], epilogue of tile ftp (kind KP) from ap[]
-    auto tile_step = [&](auto vt_c, auto kp_c, auto next_c, f32x16 (&an)[TT], f32x16 (&ap)[TT], const unsigned char* st,
-                         int ftn, int ftp) {
+    auto tile_step = [&](auto vt_c, auto kp_c, auto next_c, f32x16 (&an)[TT], f32x16 (&ap)[TT], Frag (&rn)[TT][2],
+                         const unsigned char* st, int ftn, int ftp) {
         constexpr bool VT = decltype(vt_c)::value;
         constexpr int KP = decltype(kp_c)::value;
         constexpr bool NEXT = decltype(next_c)::value;
@@ -660,6 +699,13 @@ __global__ __launch_bounds__(kGemmWaves * 64, 2) void k_gemm(GemmArgs a) {
                 else an[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(waug.v, xaug[tt].v, an[tt], 0, 0, 0);
             }
         }
+        if constexpr (NEXT && RES) {
+#pragma unroll
+            for (int tt = 0; tt < TT; ++tt) {
+                an[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sel[0].v, rn[tt][0].v, an[tt], 0, 0, 0);
+                an[tt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(sel[1].v, rn[tt][1].v, an[tt], 0, 0, 0);
+            }
+        }
         // ---- stores of tile ftp
         if constexpr (KP == TK_V) {
             const size_t head_off = (size_t)((nbp - 2 * a.Hd) >> a.dsh) * LpD2;
@@ -709,15 +755,16 @@ __global__ __launch_bounds__(kGemmWaves * 64, 2) void k_gemm(GemmArgs a) {
         return k == TK_K ? TK_Q : k;
     };
     using std::integral_constant;
-    auto run_step = [&](int kn, int kp, f32x16 (&an)[TT], f32x16 (&ap)[TT], const unsigned char* st, int ftn, int ftp) {
+    auto run_step = [&](int kn, int kp, f32x16 (&an)[TT], f32x16 (&ap)[TT], Frag (&rn)[TT][2], const unsigned char* st,
+                        int ftn, int ftp) {
 #define FF_STEP(KPV)                                                                                                         \
     do {                                                                                                                     \
         if (kn < 0) tile_step(integral_constant<bool, false>{}, integral_constant<int, KPV>{},                               \
-                              integral_constant<bool, false>{}, an, ap, st, ftn, ftp);                                            \
+                              integral_constant<bool, false>{}, an, ap, rn, st, ftn, ftp);                                        \
         else if (kn == TK_V) tile_step(integral_constant<bool, true>{}, integral_constant<int, KPV>{},                       \
-                                       integral_constant<bool, true>{}, an, ap, st, ftn, ftp);                                    \
+                                       integral_constant<bool, true>{}, an, ap, rn, st, ftn, ftp);                                \
         else tile_step(integral_constant<bool, false>{}, integral_constant<int, KPV>{}, integral_constant<bool, true>{}, an, \
-                       ap, st, ftn, ftp);                                                                                         \
+                       ap, rn, st, ftn, ftp);                                                                                     \
     } while (0)
         if constexpr (PROJ) {
             switch (kp) {
@@ -776,15 +823,23 @@ __global__ __launch_bounds__(kGemmWaves * 64, 2) void k_gemm(GemmArgs a) {
         const int ftb = ft_begin + it * NS;
         const bool two = ftb + 1 < ft_end;
         const unsigned char* st = s_w + ((it & 1) * NS) * STAGE;
-        run_step(kind_of(ftb), kp, acc[0], acc[1], st, ftb, ftp);
+        run_step(kind_of(ftb), kp, acc[0], acc[1], ra, st, ftb, ftp);
         kp = kind_of(ftb);
         ftp = ftb;
         last_in_1 = false;
+        if constexpr (RES) {
+            load_res(ra, ftb + NS);
+            n_stores += 2 * TT;
+        }
         if (two) {
-            run_step(kind_of(ftb + 1), kp, acc[1], acc[0], st + STAGE, ftb + 1, ftp);
+            run_step(kind_of(ftb + 1), kp, acc[1], acc[0], rb, st + STAGE, ftb + 1, ftp);
             kp = kind_of(ftb + 1);
             ftp = ftb + 1;
             last_in_1 = true;
+            if constexpr (RES) {
+                load_res(rb, ftb + 1 + NS);
+                n_stores += 2 * TT;
+            }
         }
         if (it + 1 >= n_it) break;
         // Order of this wavefront's memory operations: ... L(i+1), S, L(i+2), S, ... (L = tile loads
@@ -802,8 +857,8 @@ __global__ __launch_bounds__(kGemmWaves * 64, 2) void k_gemm(GemmArgs a) {
         n_stores = 0;
     }
     // epilogue of the last tile
-    if (last_in_1) run_step(-1, kp, acc[0], acc[1], s_w, ftp, ftp);
-    else run_step(-1, kp, acc[1], acc[0], s_w, ftp, ftp);
+    if (last_in_1) run_step(-1, kp, acc[0], acc[1], ra, s_w, ftp, ftp);
+    else run_step(-1, kp, acc[1], acc[0], ra, s_w, ftp, ftp);
 }
 
 // ====================================================================================
@@ -1157,30 +1212,30 @@ static int gemm_blocks_m(bool proj, int tiles_m, int K) {
     return (tiles_m + per_block - 1) / per_block;
 }
 
-template <int KC, bool PROJ, int TT>
+template <int KC, bool PROJ, int TT, bool RES>
 static void launch_gemm_inst(const GemmArgs& a, dim3 grid, hipStream_t st) {
     const size_t smem = gemm_smem_bytes(KC, TT, kGemmNS, a.tiles_per_split);
     static bool attr_set = false;          // more than 64 KiB of dynamic LDS has to be asked for once
     if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<KC, PROJ, TT, kGemmNS>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<KC, PROJ, TT, kGemmNS, RES>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
         attr_set = true;
     }
-    hipLaunchKernelGGL((k_gemm<KC, PROJ, TT, kGemmNS>), grid, dim3(kGemmWaves * 64), smem, st, a);
+    hipLaunchKernelGGL((k_gemm<KC, PROJ, TT, kGemmNS, RES>), grid, dim3(kGemmWaves * 64), smem, st, a);
 }
 
-template <bool PROJ>
+template <bool PROJ, bool RES>
 static void launch_gemm(const GemmArgs& a, int K, dim3 grid, hipStream_t st) {
     const int kc = K / 16;
     if (gemm_tt(PROJ, K, a.rows * (a.Lp >> 5)) == 1) {
-        if (kc <= 2) launch_gemm_inst<2, PROJ, 1>(a, grid, st);
-        else if (kc <= 4) launch_gemm_inst<4, PROJ, 1>(a, grid, st);
-        else if (kc <= 8) launch_gemm_inst<8, PROJ, 1>(a, grid, st);
-        else launch_gemm_inst<16, PROJ, 1>(a, grid, st);
+        if (kc <= 2) launch_gemm_inst<2, PROJ, 1, RES>(a, grid, st);
+        else if (kc <= 4) launch_gemm_inst<4, PROJ, 1, RES>(a, grid, st);
+        else if (kc <= 8) launch_gemm_inst<8, PROJ, 1, RES>(a, grid, st);
+        else launch_gemm_inst<16, PROJ, 1, RES>(a, grid, st);
     } else {
-        if (kc <= 2) launch_gemm_inst<2, PROJ, 2>(a, grid, st);
-        else if (kc <= 4) launch_gemm_inst<4, PROJ, 2>(a, grid, st);
-        else if constexpr (!PROJ) launch_gemm_inst<8, PROJ, 2>(a, grid, st);
+        if (kc <= 2) launch_gemm_inst<2, PROJ, 2, RES>(a, grid, st);
+        else if (kc <= 4) launch_gemm_inst<4, PROJ, 2, RES>(a, grid, st);
+        else if constexpr (!PROJ) launch_gemm_inst<8, PROJ, 2, RES>(a, grid, st);
     }
 }
 
@@ -1265,8 +1320,8 @@ ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x
     return check_launch("prepare (mfma)");
 }
 
-ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, const float* mask, void* out,
-                     const Workspace& ws, int r0, int rows, hipStream_t st) {
+ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, const float* mask, const void* res,
+                     void* out, const Workspace& ws, int r0, int rows, hipStream_t st) {
     const int Lp = round_up(p.L, 64), Lq = round_up(p.L, 64);
     const MfmaWs m = split_ws(p, ws.chunk, ws);
     const bool tri = p.mode == FF_TRI_START || p.mode == FF_TRI_END;
@@ -1281,7 +1336,7 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
         g.ft_first = 0; g.ft_count = g.nt_main + (fused_bias ? 1 : 0);
         g.tiles_per_split = (g.ft_count + split - 1) / split;
         Timed t(KK_PROJ, st);
-        launch_gemm<true>(g, p.c, dim3(blocks_m, split), st);
+        launch_gemm<true, false>(g, p.c, dim3(blocks_m, split), st);
     }
 
     AttnArgs a{};
@@ -1325,7 +1380,9 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
         o.ft_first = 0; o.ft_count = tiles_n;
         o.tiles_per_split = tiles_n / split;
         Timed t(KK_OUT, st);
-        launch_gemm<false>(o, p.Hd, dim3(blocks_o, split), st);
+        o.res = (const bf16_t*)res;
+        if (res) launch_gemm<false, true>(o, p.Hd, dim3(blocks_o, split), st);
+        else launch_gemm<false, false>(o, p.Hd, dim3(blocks_o, split), st);
     }
     return check_launch("attention chunk (mfma)");
 }

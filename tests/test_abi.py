@@ -20,8 +20,8 @@ def header_functions():
 
 def test_header_declares_the_boundary():
     names = header_functions()
-    for n in ("ff_layernorm", "ff_gated_attention", "ff_attention_chunked", "ff_attention_workspace_bytes",
-              "ff_last_error"):
+    for n in ("ff_layernorm", "ff_gated_attention", "ff_attention_chunked", "ff_gated_attention_residual",
+              "ff_attention_workspace_bytes", "ff_last_error"):
         assert n in names
 
 
@@ -108,6 +108,13 @@ def test_argument_errors_before_any_launch():
     assert lib.ff_gated_attention(C.byref(dc), C.byref(wc), X, Z, None, OUT, WS, 1 << 40, None) == B.FF_EINVAL  # z given
     assert lib.ff_attention_chunked(C.byref(d), C.byref(w), X, Z, None, OUT, WS, need, None, 0) == B.FF_EINVAL
     assert "chunk_rows" in P.last_error()
+    # the residual update: out may be x itself, but not a shifted view of it, and never z
+    upd = lambda *a: lib.ff_gated_attention_residual(C.byref(d), C.byref(w), *a)
+    assert upd(X, Z, None, X + 64, WS, need, None, 0) == B.FF_EINVAL
+    assert "x itself" in P.last_error()
+    assert upd(X, Z, None, Z, WS, need, None, 0) == B.FF_EINVAL
+    assert upd(X, Z, None, X, WS, need, None, -1) == B.FF_EINVAL
+    assert upd(X, Z, None, X, WS, need - 1, None, 0) == B.FF_EWORKSPACE     # in place passes the overlap check
 
 
 def test_layernorm_argument_errors():
