@@ -11,8 +11,8 @@ Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 value = counted FLOP / time, counted FLOP = projections + bias projection + QK^T + PV +
 output projection (2*M*N*K each).  The default workload is the AlphaFold initial-training
 crop of the MSA row attention with pair bias (N_seq=128, N_res=256, c_m=256, H=8, d=32,
-bf16); the N_res=256 triangle modules and the N_res=2048 chunked triangle attention are
-timed as well and reported under "others".
+bf16); the N_res=256 triangle modules, the N_res=2048 chunked triangle attention and the
+paper's fine-tuning shapes are timed as well and reported under "others".
 """
 import argparse
 import json
@@ -278,7 +278,13 @@ def main():
         for name, st, wu in (("c3_tri_start_bf16_256", args.steps, args.warmup),
                              ("c3_tri_end_bf16_256", args.steps, args.warmup),
                              ("c4_col_bf16_extra", max(args.steps // 4, 5), 3),
-                             ("c5_tri_start_bf16_2048", max(args.steps // 40, 3), 1)):
+                             ("c5_tri_start_bf16_2048", max(args.steps // 40, 3), 1),
+                             # the paper's fine-tuning shapes (Table 1: N_res 384, N_seq 512, N_extra_seq 5120)
+                             ("ft_row_bf16_512x384", max(args.steps // 10, 5), 3),
+                             ("ft_col_bf16_512x384", max(args.steps // 10, 5), 3),
+                             ("ft_tri_start_bf16_384", max(args.steps // 4, 5), 3),
+                             ("ft_tri_end_bf16_384", max(args.steps // 4, 5), 3),
+                             ("ft_col_bf16_extra_5120", max(args.steps // 40, 3), 1)):
             c2, d2, _, ms2, k2 = time_workload(name, st, wu)
             f2 = counted_flop(c2.spec)["total"]
             others[name] = {"ms_per_module": ms2, "tflops": f2 / (ms2 * 1e-3) / 1e12, "steps": st,

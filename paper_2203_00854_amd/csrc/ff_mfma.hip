@@ -169,6 +169,44 @@ struct PrepArgs {
     int nseg;
 };
 
+// One row of a folded matrix by one wavefront: store(k, bf16(scale * w[k] * gamma[k])) for k < K and
+// the row's extra piece as the return value (valid in every lane).  Every kernel that folds a row
+// goes through here, so that the same weights give the same bits wherever they are prepared (the
+// pair bias of the triangle modes is prepared by k_prep when it rides along with the projections
+// and by k_prep_bias when the rows are chunked, and both must give the same output bits).
+template <typename Store>
+__device__ __forceinline__ uint4 fold_row(const bf16_t* wrow, const bf16_t* gamma, const bf16_t* beta, int K, float scale,
+                                          bool real, float extra, int lane, Store&& store) {
+    float sum = 0.f, cst = 0.f;
+    // K <= 256: at most four elements per lane, all loads issued before the first use
+    bf16_t wv[4], gv[4], bv[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int k = lane + 64 * i;
+        const bool in = real && k < K;
+        wv[i] = in ? wrow[k] : (bf16_t)0;
+        gv[i] = in ? gamma[k] : (bf16_t)0;
+        bv[i] = in ? beta[k] : (bf16_t)0;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int k = lane + 64 * i;
+        if (k < K) {
+            const float w = bf16_to_f32(wv[i]) * scale;
+            const float r = bf16_round(w * bf16_to_f32(gv[i]));
+            cst += w * bf16_to_f32(bv[i]);
+            store(k, f32_to_bf16(r));
+            sum += r;
+        }
+    }
+    sum = wave_sum(sum);
+    cst = wave_sum(cst);
+    const float cn = cst + extra;
+    const float sn_hi = bf16_round(sum), sn_lo = bf16_round(sum - sn_hi);
+    const float cn_hi = bf16_round(cn), cn_lo = bf16_round(cn - cn_hi);
+    return make_uint4(pack2(sn_hi, sn_lo), pack2(sn_hi, cn_hi), pack2(cn_lo, cn_hi), 0u);
+}
+
 // row n of the concatenated segments, by one wavefront
 __device__ __forceinline__ void prep_row(const PrepArgs& a, int n, int lane) {
     int base = 0, sg = -1, local = 0;
@@ -186,36 +224,11 @@ __device__ __forceinline__ void prep_row(const PrepArgs& a, int n, int lane) {
         if (i == sg) sgm = a.seg[i];
     const bool real = local < sgm.rows;
     const int K = sgm.K;
-    float sum = 0.f, cst = 0.f;
-    // K <= 256: at most four elements per lane, all loads issued before the first use
-    bf16_t wv[4], gv[4], bv[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int k = lane + 64 * i;
-        const bool in = real && k < K;
-        wv[i] = in ? sgm.w[(size_t)local * K + k] : (bf16_t)0;
-        gv[i] = in ? sgm.gamma[k] : (bf16_t)0;
-        bv[i] = in ? sgm.beta[k] : (bf16_t)0;
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int k = lane + 64 * i;
-        if (k < K) {
-            const float w = bf16_to_f32(wv[i]) * sgm.scale;
-            const float r = bf16_round(w * bf16_to_f32(gv[i]));
-            cst += w * bf16_to_f32(bv[i]);
-            sgm.wp[(size_t)local * K + k] = f32_to_bf16(r);
-            sum += r;
-        }
-    }
-    sum = wave_sum(sum);
-    cst = wave_sum(cst);
-    if (lane == 0) {
-        const float cn = cst + ((real && sgm.extra) ? bf16_to_f32(sgm.extra[local]) : 0.f);
-        const float sn_hi = bf16_round(sum), sn_lo = bf16_round(sum - sn_hi);
-        const float cn_hi = bf16_round(cn), cn_lo = bf16_round(cn - cn_hi);
-        sgm.aug[local] = make_uint4(pack2(sn_hi, sn_lo), pack2(sn_hi, cn_hi), pack2(cn_lo, cn_hi), 0u);
-    }
+    const float extra = (real && sgm.extra) ? bf16_to_f32(sgm.extra[local]) : 0.f;
+    bf16_t* wp = sgm.wp + (size_t)local * K;
+    const uint4 piece = fold_row(sgm.w + (size_t)local * K, sgm.gamma, sgm.beta, K, sgm.scale, real, extra, lane,
+                                 [&](int k, bf16_t v) { wp[k] = v; });
+    if (lane == 0) sgm.aug[local] = piece;
 }
 
 __global__ __launch_bounds__(256) void k_prep(PrepArgs a) {
@@ -268,39 +281,15 @@ __global__ __launch_bounds__(512) void k_prep_bias(PrepBiasArgs a) {
         if (valid && f < K) xa[s].u = ldg16(zp + f);
     }
 
-    // ---- the folded weight tile: 16 threads per row, 8-element pieces
-    {
-        const int row = tid >> 4, sub = tid & 15;
-        float sum = 0.f, cst = 0.f;
-#pragma unroll
-        for (int pc = sub; pc < 2 * KC; pc += 16) {
-            uint32_t outw[4] = {0u, 0u, 0u, 0u};
-            if (row < a.H && pc * 8 < K) {
-                Frag wv, gv, bv;
-                wv.u = ldg16(a.w_b + (size_t)row * K + pc * 8);
-                gv.u = ldg16(a.gamma + pc * 8);
-                bv.u = ldg16(a.beta + pc * 8);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const float w0 = lo_f32(wv.w[i]) * kLog2e, w1 = hi_f32(wv.w[i]) * kLog2e;
-                    const float r0 = bf16_round(w0 * lo_f32(gv.w[i])), r1 = bf16_round(w1 * hi_f32(gv.w[i]));
-                    cst += w0 * lo_f32(bv.w[i]) + w1 * hi_f32(bv.w[i]);
-                    sum += r0 + r1;
-                    outw[i] = pack2(r0, r1);
-                }
-            }
-            *reinterpret_cast<uint4*>(&s_w[row * PITCH + pc * 16]) = make_uint4(outw[0], outw[1], outw[2], outw[3]);
-        }
-#pragma unroll
-        for (int o = 8; o > 0; o >>= 1) {
-            sum += __shfl_xor(sum, o, 64);
-            cst += __shfl_xor(cst, o, 64);
-        }
-        if (sub == 0) {
-            const float sn_hi = bf16_round(sum), sn_lo = bf16_round(sum - sn_hi);
-            const float cn_hi = bf16_round(cst), cn_lo = bf16_round(cst - cn_hi);
-            s_aug[row] = make_uint4(pack2(sn_hi, sn_lo), pack2(sn_hi, cn_hi), pack2(cn_lo, cn_hi), 0u);
-        }
+    // ---- the folded weight tile: zeros, then one wavefront per head row (fold_row)
+    for (int i = tid; i < 32 * PITCH / 16; i += 512) reinterpret_cast<uint4*>(s_w)[i] = make_uint4(0, 0, 0, 0);
+    if (tid < 32) s_aug[tid] = make_uint4(0, 0, 0, 0);
+    __syncthreads();
+    for (int row = wave; row < a.H; row += 8) {
+        bf16_t* dst = reinterpret_cast<bf16_t*>(&s_w[row * PITCH]);
+        const uint4 piece = fold_row(a.w_b + (size_t)row * K, a.gamma, a.beta, K, kLog2e, true, 0.f, lane,
+                                     [&](int k, bf16_t v) { dst[k] = v; });
+        if (lane == 0) s_aug[row] = piece;
     }
 
     // ---- LayerNorm statistics of the wavefront's pairs (two passes over the registers)

@@ -184,6 +184,20 @@ SPECS = {
     "c5_tri_start_bf16_2048": CaseSpec("c5_tri_start_bf16_2048", MODE_TRI_START, "bf16", 2048, 2048, 128, 0, 4, 32, "none", chunk_rows=64),
 }
 
+# The paper's second training setting (Table 1, fine-tuning: N_res = 384, N_seq = 512,
+# N_extra_seq = 5120) at the same channel and head counts; padding as in the workloads above
+# (a trailing tenth of the attended axis, a Bernoulli(0.95) residue mask for the pair modules).
+SPECS.update({
+    "ft_row_bf16_512x384": CaseSpec("ft_row_bf16_512x384", MODE_ROW, "bf16", 512, 384, 256, 128, 8, 32, "tail:38"),
+    "ft_col_bf16_512x384": CaseSpec("ft_col_bf16_512x384", MODE_COL, "bf16", 512, 384, 256, 0, 8, 32, "tail:51",
+                                    stream="ft_row_bf16_512x384"),
+    "ft_tri_start_bf16_384": CaseSpec("ft_tri_start_bf16_384", MODE_TRI_START, "bf16", 384, 384, 128, 0, 4, 32,
+                                      "outer:0.95", stream="ft_tri_bf16_384"),
+    "ft_tri_end_bf16_384": CaseSpec("ft_tri_end_bf16_384", MODE_TRI_END, "bf16", 384, 384, 128, 0, 4, 32,
+                                    "outer:0.95", stream="ft_tri_bf16_384"),
+    "ft_col_bf16_extra_5120": CaseSpec("ft_col_bf16_extra_5120", MODE_COL, "bf16", 5120, 384, 64, 0, 8, 8, "tail:512"),
+})
+
 
 def make_mask(spec: CaseSpec, seed: int = SEED) -> Optional[np.ndarray]:
     """0/1 float32 mask [n_a, n_b], or None.  The entry at (a, b) says whether token
