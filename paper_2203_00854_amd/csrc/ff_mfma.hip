@@ -68,12 +68,43 @@ __device__ __forceinline__ float add_pair(uint32_t w, float acc) {
                                            false);
 }
 
+// sum of the squares of the two bf16 halves of w, added to acc (v_dot2c_f32_bf16: exact products)
+__device__ __forceinline__ float add_pair_sq(uint32_t w, float acc) {
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), __builtin_bit_cast(bf16x2, w), acc, false);
+}
+
 // value of the other half-wave's lane (l ^ 32)
 __device__ __forceinline__ float other_half(float v) {
     auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
     // r[0] = {lower half of v, lower half of v}, r[1] = {upper half, upper half}
     return (threadIdx.x & 32) ? __uint_as_float(r[0]) : __uint_as_float(r[1]);
 }
+
+// LayerNorm statistics of a token whose K channels lie in the KC fragments of the two lanes
+// (col, hf = 0 | 1), channels beyond K being zero: mean and variance + eps, float32, in one pass
+// over the registers.  sum x and sum x^2 are accumulated from exact bf16 products (two channels
+// per instruction), var = sum x^2 / K - mean^2: the cancellation costs a relative error of
+// about 2^-22 (1 + mean^2 / var) of the variance, 2e-5 for a mean of twelve standard
+// deviations.  (The two-pass form, sum (x - mean)^2, took 450 vector instructions per lane for
+// K = 256, a quarter of this wavefront's work before its first matrix instruction.)
+// Every kernel takes the statistics from here, so that they agree bit for bit.
+template <int KC>
+__device__ __forceinline__ void token_stats(const Frag (&xa)[KC], int K, float eps, float& mu, float& var) {
+    float sum = 0.f, sq = 0.f;
+#pragma unroll
+    for (int s = 0; s < KC; ++s)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            sum = add_pair(xa[s].w[i], sum);
+            sq = add_pair_sq(xa[s].w[i], sq);
+        }
+    sum += other_half(sum);
+    sq += other_half(sq);
+    const float inv_k = 1.f / (float)K;
+    mu = sum * inv_k;
+    var = fmaxf(sq * inv_k - mu * mu, 0.f) + eps;
+}
+
 // After the call lanes of the lower half hold (a of lower lane, a of upper lane) and lanes of
 // the upper half hold (b of lower lane, b of upper lane): two 4-element groups that are
 // adjacent in memory end up in one lane.
@@ -292,27 +323,9 @@ __global__ __launch_bounds__(512) void k_prep_bias(PrepBiasArgs a) {
         if (lane == 0) s_aug[row] = piece;
     }
 
-    // ---- LayerNorm statistics of the wavefront's pairs (two passes over the registers)
-    float sum = 0.f;
-#pragma unroll
-    for (int s = 0; s < KC; ++s)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) sum = add_pair(xa[s].w[i], sum);
-    sum += other_half(sum);
-    const float mu = sum / (float)K;
-    float sq = 0.f;
-#pragma unroll
-    for (int s = 0; s < KC; ++s) {
-        if (16 * s + 8 * hf < K) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float d0 = lo_f32(xa[s].w[i]) - mu, d1 = hi_f32(xa[s].w[i]) - mu;
-                sq += d0 * d0 + d1 * d1;
-            }
-        }
-    }
-    sq += other_half(sq);
-    const float var = sq / (float)K + a.eps;
+    // ---- LayerNorm statistics of the wavefront's pairs
+    float mu, var;
+    token_stats<KC>(xa, K, a.eps, mu, var);
     const float rstd = valid ? rsqrtf(var) : 0.f;
     const float m = valid ? -mu : 0.f, r = var * rstd;
     const float m_hi = bf16_round(m), m_lo = bf16_round(m - m_hi);
@@ -771,29 +784,11 @@ __global__ __launch_bounds__(kGemmWaves * 64, 2) void k_gemm(GemmArgs a) {
     };
 
     if constexpr (PROJ) {
-        // LayerNorm statistics of the raw rows (two passes over the registers, float32)
+        // LayerNorm statistics of the raw rows (token_stats)
 #pragma unroll
         for (int tt = 0; tt < TT; ++tt) {
-            float sum = 0.f;
-#pragma unroll
-            for (int s = 0; s < KC; ++s)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) sum = add_pair(xa[tt][s].w[i], sum);
-            sum += other_half(sum);
-            const float mu = sum / (float)K;
-            float sq = 0.f;
-#pragma unroll
-            for (int s = 0; s < KC; ++s) {
-                if (16 * s + 8 * hf < K) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const float d0 = lo_f32(xa[tt][s].w[i]) - mu, d1 = hi_f32(xa[tt][s].w[i]) - mu;
-                        sq += d0 * d0 + d1 * d1;
-                    }
-                }
-            }
-            sq += other_half(sq);
-            const float var = sq / (float)K + a.eps;
+            float mu, var;
+            token_stats<KC>(xa[tt], K, a.eps, mu, var);
             rstd[tt] = tok_valid[tt] ? rsqrtf(var) : 0.f;
             const float m = tok_valid[tt] ? -mu : 0.f, r = var * rstd[tt];
             const float m_hi = bf16_round(m), m_lo = bf16_round(m - m_hi);
