@@ -32,10 +32,10 @@ PEAK_HBM_GBS = 8000.0
 # the factors a plain 256 MiB copy gives); null for workloads without such a run.
 _KIB = 1024
 TRAFFIC_BYTES = {
-    ("c2_row_bf16_train", "pair bias pass"): int((8535.6 * 2.0 + 2592.5) * _KIB),
-    ("c2_row_bf16_train", "k_gemm<PROJ>"): int((10498.0 * 2.0 + 65536.0) * _KIB),
-    ("c2_row_bf16_train", "k_attn"): int((49287.0 * 2.0 + 16384.0) * _KIB),
-    ("c2_row_bf16_train", "k_gemm<OUT>"): int((8774.0 * 2.0 + 22106.8) * _KIB),
+    ("c2_row_bf16_train", "pair bias pass"): int((8533.3 * 2.0 + 2592.5) * _KIB),
+    ("c2_row_bf16_train", "k_gemm<PROJ>"): int((10485.0 * 2.0 + 65536.0) * _KIB),
+    ("c2_row_bf16_train", "k_attn"): int((57014.8 * 2.0 + 16384.0) * _KIB),
+    ("c2_row_bf16_train", "k_gemm<OUT>"): int((8773.5 * 2.0 + 21021.7) * _KIB),
 }
 
 

@@ -864,6 +864,7 @@ struct AttnArgs {
     const float* mask;     // caller's mask or NULL
     int64_t sr, sl;
     int r0, rows, L, Lp, Lq, H, Hd;
+    float inv_nq, inv_nqh;   // 1 / (Lp / 64), 1 / (Lp / 64 * H): quotients of item indices below 2^22 without an integer division
 };
 
 // keys per bias tile in LDS (one barrier per tile): 64, or 128 for long sequences (GK template parameter)
@@ -871,7 +872,7 @@ constexpr int kBiasPad = 4;      // floats added to an LDS bias row: conflict-fr
 constexpr float kRaise = 10.f;   // log2 units
 constexpr float kOver = 1048576.f;   // 2^20: partial denominator (16 keys) that triggers a raise of the reference
 
-template <int D, bool HAS_BIAS, int RB, int GK>
+template <int D, bool HAS_BIAS, int RB, int GK, bool PERSIST>
 __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
     constexpr int PCX = D / 8;              // index of the 8-slot piece holding the two extra slots
     constexpr int KS = PCX / 2 + 1;         // 16-wide contraction steps
@@ -882,45 +883,74 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
     constexpr int TPG = GK / 32, kBiasPitch = GK + kBiasPad;
     float* s_bias = reinterpret_cast<float*>(smem);                                  // [2][64][kBiasPitch]
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, col = lane & 31, hf = lane >> 5;
+    const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // (scalar: so is everything that places the wavefront's item)
     // Work-groups are handed to the 8 XCDs round-robin and each XCD has its own L2.  The blocks
     // that share K and V (same rows and head, different queries) get consecutive slots of ONE
     // XCD, so K and V are fetched into one L2 once instead of once per query block.
+    // The grid is persistent: at most one block per set of RB wave slots of a compute unit, each
+    // taking the items (RB batch rows x one head x 64 queries) slot, slot + stride, ... of its XCD.
+    // The operands of an item's first tiles are fetched while the block still works on the last
+    // tile and the epilogue of the item before, so that only the first item of a block waits for
+    // memory before its first matrix instruction.
     const int nq = a.Lp >> 6;
-    const int n_blocks = nq * a.H * ((a.rows + RB - 1) / RB);
-    const int per_xcd = (n_blocks + 7) >> 3;
-    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (logical >= n_blocks) return;
-    const int rl_raw = (logical / (nq * a.H)) * RB + wave;
-    const bool row_ok = rl_raw < a.rows;
-    const int rl = row_ok ? rl_raw : a.rows - 1;
-    const int h = (logical / nq) % a.H;
-    const int q0 = (logical % nq) * 64;
+    const int n_items = nq * a.H * ((a.rows + RB - 1) / RB);
+    const int per_xcd = (n_items + 7) >> 3;
+    const int slot_stride = gridDim.x >> 3;
+    int slot = blockIdx.x >> 3;
+    auto item_at = [&](int sl) __attribute__((always_inline)) -> int {                  // item of slot sl of this XCD, -1 if there is none
+        const int lg = (blockIdx.x & 7) * per_xcd + sl;
+        return (sl < per_xcd && lg < n_items) ? lg : -1;
+    };
+    int logical = item_at(slot);
+    if (logical < 0) return;                              // (whole block)
+    int rl, h, q0;                                        // of the item whose operands are fetched next
+    bool row_ok;
+    auto place = [&](int lg) __attribute__((always_inline)) {
+        // lg = (block of RB rows * H + head) * nq + query tile; float quotients, corrected by one
+        // where the rounding went the wrong way (exact for lg < 2^22, which the host checks)
+        const int nqh = nq * a.H;
+        int rb = (int)(((float)lg + 0.5f) * a.inv_nqh);
+        rb -= rb * nqh > lg;
+        rb += (rb + 1) * nqh <= lg;
+        const int rem = lg - rb * nqh;
+        int hh = (int)(((float)rem + 0.5f) * a.inv_nq);
+        hh -= hh * nq > rem;
+        hh += (hh + 1) * nq <= rem;
+        const int rl_raw = rb * RB + wave;
+        row_ok = rl_raw < a.rows;
+        rl = row_ok ? rl_raw : a.rows - 1;
+        h = hh;
+        q0 = (rem - hh * nq) * 64;
+    };
+    place(logical);
     const bool xlane = hf == HX;            // this lane carries the extra slots in step SX
 
     // ---- Q operand fragments: B operand, lane = query, 8 consecutive e
     Frag qf[2][KS];
+    auto fetch_q = [&]() __attribute__((always_inline)) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int qi = q0 + 32 * j + col;                       // < Lp
-        const bf16_t* qp = a.q + ((size_t)(rl * a.H + h) * a.Lp + qi) * D;
+        for (int j = 0; j < 2; ++j) {
+            const int qi = q0 + 32 * j + col;                       // < Lp
+            const bf16_t* qp = a.q + ((size_t)(rl * a.H + h) * a.Lp + qi) * D;
 #pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            qf[j][s].u = make_uint4(0, 0, 0, 0);
-            if (2 * s + hf < PCX) qf[j][s].u = ldg16(qp + 16 * s + 8 * hf);
+            for (int s = 0; s < KS; ++s) {
+                qf[j][s].u = make_uint4(0, 0, 0, 0);
+                if (2 * s + hf < PCX) qf[j][s].u = ldg16(qp + 16 * s + 8 * hf);
+            }
         }
-        if (xlane) qf[j][SX].w[0] = 0x3f800000u;        // (-m_ref = 0, 1.0)
-    }
+    };
+    fetch_q();
 
     // ---- bias tile pipeline: [64 queries][GK keys]; GK/4 threads per row, RPP rows per pass
     constexpr int TPR = GK / 4, RPP = RB * 64 / TPR, BP = 64 / RPP;
     static_assert(BP == 2 || BP == 4, "bias tile passes");
     const int b_row = tid / TPR, b_c4 = tid % TPR;
-    const float* bias_t = HAS_BIAS ? a.bias + ((size_t)h * a.Lq + q0 + b_row) * a.Lp : nullptr;
+    const float* bias_t = nullptr;
     float* s_bias_t = s_bias + (size_t)b_row * kBiasPitch + 4 * b_c4;
     // (named registers: an array captured by a lambda would be spilled to scratch)
     float4 bq0, bq1, bq2, bq3;
-    auto load_bias = [&](int g) {
+    auto load_bias = [&](int g) __attribute__((always_inline)) {
         int colk = GK * g + 4 * b_c4;              // (a last group that is only half there repeats valid keys)
         if (colk > a.Lp - 4) colk = a.Lp - 4;
         const float* bp = bias_t + colk;
@@ -931,7 +961,7 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
             bq3 = *reinterpret_cast<const float4*>(bp + (size_t)(3 * RPP) * a.Lp);
         }
     };
-    auto store_bias = [&](int buf) {
+    auto store_bias = [&](int buf) __attribute__((always_inline)) {
         float* sp = s_bias_t + (size_t)buf * 64 * kBiasPitch;
         *reinterpret_cast<float4*>(sp) = bq0;
         *reinterpret_cast<float4*>(sp + RPP * kBiasPitch) = bq1;
@@ -940,16 +970,22 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
             *reinterpret_cast<float4*>(sp + 3 * RPP * kBiasPitch) = bq3;
         }
     };
-    if constexpr (HAS_BIAS) load_bias(0);      // (stored to LDS after the first K and V loads have been issued)
 
     // permuted key of S^T row m = col: rows 8g + 4b + e hold key 16*(g/2) + 8b + 4*(g%2) + e
     const int kperm = 16 * (col >> 4) + 8 * ((col >> 2) & 1) + 4 * ((col >> 3) & 1) + (col & 3);
     // k is [row][head][l][d], v^T is [row][head][l / 32][e][l % 32]: a 32-key tile of either is one
     // contiguous block of 64*D bytes
-    const bf16_t* kp = a.k + ((size_t)(rl * a.H + h) * a.Lp + kperm) * D + 8 * hf;
-    const bf16_t* vp = a.vt + (size_t)(rl * a.H + h) * a.Lp * D + (col < D ? col : 0) * 32 + 8 * hf;
+    const bf16_t *kp, *vp;
+    const float* mp;
     constexpr int kstep = 32 * D;
-    const float* mp = a.mask ? a.mask + (int64_t)(a.r0 + rl) * a.sr : nullptr;
+    auto set_pointers = [&]() __attribute__((always_inline)) {             // operands of the item (rl, h, q0)
+        kp = a.k + ((size_t)(rl * a.H + h) * a.Lp + kperm) * D + 8 * hf;
+        vp = a.vt + (size_t)(rl * a.H + h) * a.Lp * D + (col < D ? col : 0) * 32 + 8 * hf;
+        mp = a.mask ? a.mask + (int64_t)(a.r0 + rl) * a.sr : nullptr;
+        if constexpr (HAS_BIAS) bias_t = a.bias + ((size_t)h * a.Lq + q0 + b_row) * a.Lp;
+    };
+    set_pointers();
+    if constexpr (HAS_BIAS) load_bias(0);      // (stored to LDS after the first K and V loads have been issued)
     const bool ones_lane = ONES_ROW && col == D;
 
     // Software pipeline over 32-key tiles i:
@@ -960,7 +996,7 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
     // before its use.  The bias tile in LDS covers 64 keys (an even and an odd tile).
     Frag kb0[KS], kb1[KS], vb0[2], vb1[2];
     float mv0 = 1.f, mv1 = 1.f;
-    auto fetch_k = [&](Frag (&kb)[KS], float& mv, int kt) {
+    auto fetch_k = [&](Frag (&kb)[KS], float& mv, int kt) __attribute__((always_inline)) {
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             kb[s].u = make_uint4(0, 0, 0, 0);
@@ -970,7 +1006,7 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
         mv = 1.f;
         if (mp) mv = mp[(int64_t)(key < a.L ? key : a.L - 1) * a.sl];
     };
-    auto fetch_v = [&](Frag (&vb)[2], int kt) {
+    auto fetch_v = [&](Frag (&vb)[2], int kt) __attribute__((always_inline)) {
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
             vb[c].u = make_uint4(0, 0, 0, 0);
@@ -980,20 +1016,14 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
 
     f32x16 o_acc[2];
     float m_ref[2], l_run[2];
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        m_ref[j] = 0.f;
-        l_run[j] = 0.f;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) o_acc[j][v] = 0.f;
-    }
     bool first = true;
+    int gbase = 0;          // bias groups staged so far (all items): group g of the item uses LDS buffer (gbase + g) & 1
 
     // S^T of tile kt into sa in two parts: the bias tile as accumulator input (LDS reads, issued
     // early: the loads of the next K and V tiles hide their latency), then the contraction, which
     // returns whether any key of the tile is valid
-    auto qk_bias = [&](int kt, f32x16 (&sa)[2]) {
-        const float* sb = s_bias + (size_t)((kt / TPG) & 1) * 64 * kBiasPitch;
+    auto qk_bias = [&](int kt, f32x16 (&sa)[2]) __attribute__((always_inline)) {
+        const float* sb = s_bias + (size_t)((kt / TPG + gbase) & 1) * 64 * kBiasPitch;
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             if constexpr (HAS_BIAS) {
@@ -1009,7 +1039,7 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
             }
         }
     };
-    auto qk_mma = [&](Frag (&kb)[KS], float mv, int kt, f32x16 (&sa)[2]) -> bool {
+    auto qk_mma = [&](Frag (&kb)[KS], float mv, int kt, f32x16 (&sa)[2]) __attribute__((always_inline)) -> bool {
         const bool key_valid = mv != 0.f && 32 * kt + kperm < a.L;
         if (!__any(key_valid)) return false;
         if (xlane) kb[SX].w[0] = key_valid ? 0x00003f80u : 0xff803f80u;   // (1.0, mask term)
@@ -1028,7 +1058,7 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
         return true;
     };
     // exponentials of tile sa and O^T update; sn is the tile already issued with the old reference
-    auto soft_pv = [&](f32x16 (&sa)[2], Frag (&vb)[2], f32x16 (&sn)[2], bool sn_live) {
+    auto soft_pv = [&](f32x16 (&sa)[2], Frag (&vb)[2], f32x16 (&sn)[2], bool sn_live) __attribute__((always_inline)) {
         if (ones_lane) {
 #pragma unroll
             for (int c = 0; c < 2; ++c) vb[c].u = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
@@ -1039,13 +1069,13 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
         // query tile through raise_ref afterwards: rare, and the common tile saves the sixteen
         // max operations per query.  With the denominator on the matrix core (D < 32) the
         // maximum is taken for every tile, because there the overflow would already be accumulated.
-        auto tile_max = [&](int j) -> float {
+        auto tile_max = [&](int j) __attribute__((always_inline)) -> float {
             float mx = sa[j][0];
 #pragma unroll
             for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sa[j][v]);
             return fmaxf(mx, other_half(mx));
         };
-        auto raise_ref = [&](int j, float tmax, bool always) {
+        auto raise_ref = [&](int j, float tmax, bool always) __attribute__((always_inline)) {
             const bool raise = always || tmax > kRaise;
             const float new_ref = raise ? bf16_round(m_ref[j] + tmax) : m_ref[j];
             const float delta = new_ref - m_ref[j];
@@ -1075,7 +1105,7 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
         for (int j = 0; j < 2; ++j) {
             Frag pf[2];
             float lt = 0.f;
-            auto exponentiate = [&]() {
+            auto exponentiate = [&]() __attribute__((always_inline)) {
                 lt = 0.f;
 #pragma unroll
                 for (int c = 0; c < 2; ++c)
@@ -1106,33 +1136,80 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
     fetch_k(kb0, mv0, 0);
     fetch_k(kb1, mv1, 1);
     fetch_v(vb0, 0);
+    f32x16 s0[2], s1[2];
+    uint2 gate[2][4];       // gate values of the item's queries, fetched during its last tile
+  for (;;) {
+    // ---- an item begins: its Q, K(0), K(1), V(0) and first bias group are on their way or here
+    const int e_rl = rl, e_h = h, e_q0 = q0;        // the epilogue's copy: (rl, h, q0) move on to the next item before it
+    const bool e_row_ok = row_ok;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        m_ref[j] = 0.f;
+        l_run[j] = 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o_acc[j][v] = 0.f;
+        if (xlane) qf[j][SX].w[0] = 0x3f800000u;        // (-m_ref = 0, 1.0)
+    }
+    first = true;
     if constexpr (HAS_BIAS) {
-        store_bias(0);
+        // (group 0 goes to the buffer that the last group of the item before does not use; every
+        // wavefront finished with the group before that one when it passed the last barrier)
+        store_bias(gbase & 1);
         if (TPG == 2 && nt > 2) load_bias(1);
     }
     __syncthreads();                        // bias group 0 is in LDS
-    f32x16 s0[2], s1[2];
     qk_bias(0, s0);
     bool live0 = qk_mma(kb0, mv0, 0, s0), live1 = false;
-    // The bias of key group g (TPG tiles) sits in LDS buffer g & 1.  It is loaded to registers one
+    // (long sequences, PERSIST = false: one item per block.  There the start of an item is a few per
+    // cent of its time, and blocks handed out as compute units fall free even out the differences
+    // between compute units that a fixed share of 24 long items per block adds up: 3 % at 1024 keys)
+    const int next = PERSIST ? item_at(slot + slot_stride) : -1;
+    // The bias of key group g (TPG tiles) sits in LDS buffer (gbase + g) & 1.  It is loaded to registers one
     // and a half iterations before tile g*TPG is first touched, stored and published (the only
     // barrier of the group) at the end of the even half of the iteration before.
-    for (int i = 0; i < nt; i += 2) {
+    // (the last pair of tiles has a body of its own: the loop proper then holds no load that
+    // depends on a condition, which keeps the compiler's wait counts exact)
+    auto tile_pair = [&](int i, auto last_c) __attribute__((always_inline)) {
+        constexpr bool LAST = decltype(last_c)::value;
         // ---- even tile i: K(i+2) -> set 0, V(i+1) -> set 1, S^T(i+1) -> s1, exponentials of s0
         qk_bias(i + 1, s1);
-        if (i + 2 < nt) fetch_k(kb0, mv0, i + 2);
+        if constexpr (!LAST) fetch_k(kb0, mv0, i + 2);
         fetch_v(vb1, i + 1);
+        if constexpr (LAST) {
+            // no tile i+2.  The gate values of the epilogue set out, then the operands of the next
+            // item's first tiles as their registers fall free: K set 0 here, K set 1, V set 0, the
+            // bias registers and Q (its last matrix instruction has been issued; if the last
+            // exponentials still raise the reference, what they write into the Q operand is
+            // overwritten when the next item begins) half a pair later.  A block's last item
+            // fetches its own first tiles again instead: loads that do not depend on a condition
+            // keep the compiler's wait counts exact, so that the epilogue waits for the gate
+            // values only.
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const size_t t = ((size_t)(rl * a.H + h) * a.Lp + q0 + 32 * j + col) * D;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    gate[j][g] = make_uint2(0, 0);
+                    if (8 * g + 4 * hf < D) gate[j][g] = ldg8(a.g + t + 8 * g + 4 * hf);
+                }
+            }
+            if constexpr (PERSIST) {
+                place(next >= 0 ? next : logical);
+                set_pointers();
+                fetch_k(kb0, mv0, 0);
+            }
+        }
         live1 = qk_mma(kb1, mv1, i + 1, s1);
         if (live0) soft_pv(s0, vb0, s1, live1);
-        if constexpr (HAS_BIAS) {
-            if ((i + 2) % TPG == 0 && i + 2 < nt) {
-                store_bias(((i + 2) / TPG) & 1);
+        if constexpr (HAS_BIAS && !LAST) {
+            if ((i + 2) % TPG == 0) {
+                store_bias(((i + 2) / TPG + gbase) & 1);
                 __syncthreads();
             }
         }
         // ---- odd tile i+1: K(i+3) -> set 1, V(i+2) -> set 0, S^T(i+2) -> s0, exponentials of s1
         live0 = false;
-        if (i + 2 < nt) {
+        if constexpr (!LAST) {
             qk_bias(i + 2, s0);
             fetch_k(kb1, mv1, i + 3);
             fetch_v(vb0, i + 2);
@@ -1140,9 +1217,16 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
                 if ((i + 4) % TPG == 0 && i + 4 < nt) load_bias((i + 4) / TPG);
             }
             live0 = qk_mma(kb0, mv0, i + 2, s0);
+        } else if constexpr (PERSIST) {
+            fetch_k(kb1, mv1, 1);
+            fetch_v(vb0, 0);
+            if constexpr (HAS_BIAS) load_bias(0);
+            fetch_q();
         }
         if (live1) soft_pv(s1, vb1, s0, live0);
-    }
+    };
+    for (int i = 0; i + 2 < nt; i += 2) tile_pair(i, std::integral_constant<bool, false>{});
+    tile_pair(nt - 2, std::integral_constant<bool, true>{});
 
     // ---- epilogue: normalise, gate, store.  o_acc[j]: lane = query, register v = e = 8*(v/4) + 4*hf + v%4
 #pragma unroll
@@ -1156,16 +1240,14 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
             l_tot = l_run[j] + other_half(l_run[j]);
         }
         const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-        const int qi = q0 + 32 * j + col;                       // < Lp
+        const int qi = e_q0 + 32 * j + col;                       // < Lp
         // gate and context are head-major [row][head][l][d]: the wave's 32 queries are one
         // contiguous block of 64*D bytes
-        const size_t t = ((size_t)(rl * a.H + h) * a.Lp + qi) * D;
+        const size_t t = ((size_t)(e_rl * a.H + e_h) * a.Lp + qi) * D;
         uint32_t pk[8];
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            const int e0 = 8 * g + 4 * hf;
-            uint2 gr = make_uint2(0, 0);
-            if (e0 < D) gr = ldg8(a.g + t + e0);
+            const uint2 gr = gate[j][g];              // elements 8g + 4hf .. + 3 (zero beyond D)
             pk[2 * g] = pack2(o_acc[j][4 * g] * inv * lo_f32(gr.x), o_acc[j][4 * g + 1] * inv * hi_f32(gr.x));
             pk[2 * g + 1] = pack2(o_acc[j][4 * g + 2] * inv * lo_f32(gr.y), o_acc[j][4 * g + 3] * inv * hi_f32(gr.y));
         }
@@ -1173,12 +1255,17 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
         merge_halves(pk[1], pk[3]);
         merge_halves(pk[4], pk[6]);      // lower: e 16..23, upper: e 24..31
         merge_halves(pk[5], pk[7]);
-        if (row_ok && qi < a.L) {
+        if (e_row_ok && qi < a.L) {
             if (8 * hf < D) *reinterpret_cast<uint4*>(a.o + t + 8 * hf) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
             if (16 + 8 * hf < D)
                 *reinterpret_cast<uint4*>(a.o + t + 16 + 8 * hf) = make_uint4(pk[4], pk[5], pk[6], pk[7]);
         }
     }
+    if (next < 0) break;
+    logical = next;
+    slot += slot_stride;
+    gbase += (nt + TPG - 1) / TPG;
+  }
 }
 
 // ====================================================================================
@@ -1231,15 +1318,28 @@ static int pick_split(int blocks_m, int tiles_n) {
     return split;
 }
 
-template <int D, bool HAS_BIAS, int RB, int GK>
+static int compute_units() {
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            n = v;
+        else
+            n = 256;
+    }
+    return n;
+}
+
+template <int D, bool HAS_BIAS, int RB, int GK, bool PERSIST>
 static void launch_attn(dim3 grid, size_t smem, hipStream_t st, const AttnArgs& a) {
     static bool attr_set = false;          // more than 64 KiB of dynamic LDS has to be asked for once
     if (!attr_set && smem > 64 * 1024) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn<D, HAS_BIAS, RB, GK>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn<D, HAS_BIAS, RB, GK, PERSIST>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
         attr_set = true;
     }
-    hipLaunchKernelGGL((k_attn<D, HAS_BIAS, RB, GK>), grid, dim3(RB * 64), smem, st, a);
+    hipLaunchKernelGGL((k_attn<D, HAS_BIAS, RB, GK, PERSIST>), grid, dim3(RB * 64), smem, st, a);
 }
 
 static GemmArgs proj_args(const Problem& p, const MfmaWs& m, const Workspace& ws) {
@@ -1326,20 +1426,35 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
     AttnArgs a{};
     a.q = m.q; a.k = m.k; a.g = m.g; a.vt = m.vt; a.o = m.o; a.bias = ws.bias; a.mask = mask;
     a.sr = p.sr; a.sl = p.sl; a.r0 = r0; a.rows = rows; a.L = p.L; a.Lp = Lp; a.Lq = Lq; a.H = p.H; a.Hd = p.Hd;
+    a.inv_nq = 1.f / (float)(Lp / 64); a.inv_nqh = 1.f / (float)((Lp / 64) * p.H);
     {
         Timed t(KK_ATTN, st);
         // batch rows per block (one wavefront each): 8 halve the bias traffic of 4
         const int rb = rows >= 8 ? 8 : 4;
-        const int n_blocks = (Lq / 64) * p.H * ((rows + rb - 1) / rb);
-        dim3 grid(((n_blocks + 7) / 8) * 8);
+        const int64_t n_items64 = (int64_t)(Lq / 64) * p.H * ((rows + rb - 1) / rb);
+        if (n_items64 >= (1 << 22))
+            return fail(FF_EUNSUPPORTED, "attention: %lld blocks of work in one launch (limit 4194303): use fewer rows per chunk",
+                        (long long)n_items64);
+        const int n_items = (int)n_items64;
         // keys per bias tile: 128 halve the barriers of long sequences, 64 keep the first tile of short ones small
-        const int gk = (rb == 8 && Lp >= 512) ? 128 : 64;
+        const int gk = (p.has_bias && rb == 8 && Lp >= 512) ? 128 : 64;
+        // short sequences: persistent blocks, one per rb wave slots of a compute unit (the kernel
+        // keeps two wavefronts per SIMD), each working through its share of the items
+        const bool persist = Lp < 512;
+        const int resident = compute_units() * (8 / rb);
+        const int n_blocks = (!persist || n_items < resident) ? n_items : resident;
+        dim3 grid(((n_blocks + 7) / 8) * 8);
         const size_t bias_bytes = (size_t)2 * 64 * (gk + kBiasPad) * 4;   // two float tiles
+#define FF_ATTN3(DD, HB, RBV, GKV, SM)                                       \
+    do {                                                                     \
+        if (persist) launch_attn<DD, HB, RBV, GKV, true>(grid, SM, st, a);   \
+        else launch_attn<DD, HB, RBV, GKV, false>(grid, SM, st, a);          \
+    } while (0)
 #define FF_ATTN2(DD, RBV)                                                   \
     do {                                                                    \
-        if (p.has_bias && gk == 128) launch_attn<DD, true, 8, 128>(grid, bias_bytes, st, a); \
-        else if (p.has_bias) launch_attn<DD, true, RBV, 64>(grid, bias_bytes, st, a);        \
-        else launch_attn<DD, false, RBV, 64>(grid, 0, st, a);                                \
+        if (p.has_bias && gk == 128) launch_attn<DD, true, 8, 128, false>(grid, bias_bytes, st, a); \
+        else if (p.has_bias) FF_ATTN3(DD, true, RBV, 64, bias_bytes);                        \
+        else FF_ATTN3(DD, false, RBV, 64, 0);                                                \
     } while (0)
 #define FF_ATTN(DD)                  \
     do {                             \
@@ -1351,6 +1466,7 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
         else FF_ATTN(32);
 #undef FF_ATTN
 #undef FF_ATTN2
+#undef FF_ATTN3
     }
 
     GemmArgs o{};
