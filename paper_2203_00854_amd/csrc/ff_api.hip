@@ -156,7 +156,7 @@ static ff_status run(const ff_attn_desc* desc, const ff_attn_weights* w, const v
     if (overlaps(out, x_bytes, wsp, need)) return fail(FF_EINVAL, "out must not overlap the workspace");
 
     hipStream_t stream = (hipStream_t)stream_;
-    bool fast = mfma_supported(p) && aligned16(x) && aligned16(out) && aligned16(z);
+    bool fast = mfma_supported(p) && mfma_chunk_ok(p, chunk) && aligned16(x) && aligned16(out) && aligned16(z);
     const void* wp[] = {w->ln_g, w->ln_b, w->lnz_g, w->lnz_b, w->w_q, w->w_k, w->w_v, w->w_b, w->w_g, w->b_g, w->w_o, w->b_o};
     for (const void* q : wp) fast = fast && aligned16(q);
     Workspace ws;

@@ -99,6 +99,8 @@ ff_status generic_chunk(const Problem& p, const ff_attn_weights& w, const void* 
 
 // bf16 matrix-core path (ff_mfma_*.hip)
 bool mfma_supported(const Problem& p);
+// whether `chunk` batch rows per launch are within the family's limits (else the generic family runs)
+bool mfma_chunk_ok(const Problem& p, int chunk);
 size_t mfma_workspace(const Problem& p, int chunk, Workspace* ws, void* base);
 ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x, const void* z,
                        const Workspace& ws, hipStream_t stream);

@@ -1318,6 +1318,17 @@ static int pick_split(int blocks_m, int tiles_n) {
     return split;
 }
 
+// work items of one attention launch over `rows` batch rows
+static int64_t attn_items(const Problem& p, int rows) {
+    const int rb = rows >= 8 ? 8 : 4;
+    return (int64_t)(round_up(p.L, 64) / 64) * p.H * ((rows + rb - 1) / rb);
+}
+
+bool mfma_chunk_ok(const Problem& p, int chunk) {
+    // the attention kernel splits item indices with float reciprocals, exact below 2^22
+    return attn_items(p, chunk) < (1 << 22);
+}
+
 static int compute_units() {
     static int n = 0;
     if (n == 0) {
@@ -1431,11 +1442,7 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
         Timed t(KK_ATTN, st);
         // batch rows per block (one wavefront each): 8 halve the bias traffic of 4
         const int rb = rows >= 8 ? 8 : 4;
-        const int64_t n_items64 = (int64_t)(Lq / 64) * p.H * ((rows + rb - 1) / rb);
-        if (n_items64 >= (1 << 22))
-            return fail(FF_EUNSUPPORTED, "attention: %lld blocks of work in one launch (limit 4194303): use fewer rows per chunk",
-                        (long long)n_items64);
-        const int n_items = (int)n_items64;
+        const int n_items = (int)attn_items(p, rows);          // < 2^22: mfma_chunk_ok
         // keys per bias tile: 128 halve the barriers of long sequences, 64 keep the first tile of short ones small
         const int gk = (p.has_bias && rb == 8 && Lp >= 512) ? 128 : 64;
         // short sequences: persistent blocks, one per rb wave slots of a compute unit (the kernel
