@@ -209,16 +209,17 @@ def test_long_ragged_sequence_column_mode():
     check(to_np(run_case(case)), oracle_case(case), "bf16", "long ragged column attention")
 
 
-@pytest.mark.parametrize("mode", [COL, TS])
-def test_reference_is_raised_when_late_keys_dominate(mode):
+@pytest.mark.parametrize("mode,heads,d", [(COL, 2, 32), (TS, 2, 32), (COL, 8, 8), (TS, 4, 16)])
+def test_reference_is_raised_when_late_keys_dominate(mode, heads, d):
     """The keys of the last two 32-key tiles beat everything before them by tens of log2 units
     for half of the queries (and lose by as much for the other half).  The kernel's running softmax
     reference, fixed by the first tile, has to be raised when those keys arrive.  The tokens of a
     group differ only by small noise, so the rounding of q and k is common to a group and the
-    usual tolerance holds."""
+    usual tolerance holds.  Head dims below 32 take the kernel's other route (the maximum of every
+    tile, the next tile's contraction issued from inside the exponentials)."""
     L, late = 160, 96
     n_a, n_b = (L, 6) if mode == COL else (L, L)      # the pair representation is square
-    case = I.make_case(small_spec(mode, n_a, n_b, 64, 2, 32, dtype="bf16"))
+    case = I.make_case(small_spec(mode, n_a, n_b, 64, heads, d, dtype="bf16"))
     key = I.stream_key(I.SEED, "late_keys", "x")
     v = I.normal(key, 64)
     noise = I.normal(I.stream_key(I.SEED, "late_keys", "noise"), n_a * n_b * 64).reshape(n_a, n_b, 64)
@@ -231,12 +232,12 @@ def test_reference_is_raised_when_late_keys_dominate(mode):
     x, z, m, w = f64_inputs(case)
     xh = O.layer_norm(x, w["ln_g"], w["ln_b"], case.spec.ln_eps)
     tok = xh[:, 0] if mode == COL else xh[0]                  # [L, c]: one batch row
-    q = (tok @ w["w_q"].T).reshape(L, 2, 32)
-    k = (tok @ w["w_k"].T).reshape(L, 2, 32)
-    s = np.einsum("qhe,khe->hqk", q, k) / np.sqrt(32.0) * np.log2(np.e)
+    q = (tok @ w["w_q"].T).reshape(L, heads, d)
+    k = (tok @ w["w_k"].T).reshape(L, heads, d)
+    s = np.einsum("qhe,khe->hqk", q, k) / np.sqrt(float(d)) * np.log2(np.e)
     jump = s[:, :, late:].max(axis=2) - s[:, :, :32].max(axis=2)
     assert jump.max() > 30.0
-    check(to_np(run_case(case)), oracle_case(case), "bf16", f"late keys dominate, mode {mode}")
+    check(to_np(run_case(case)), oracle_case(case), "bf16", f"late keys dominate, mode {mode}, d {d}")
 
 
 @pytest.mark.parametrize("mode", [ROW, TS])
