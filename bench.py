@@ -112,6 +112,43 @@ def time_workload(name, steps, warmup, copies=3, profile=True, residual=False):
     return case, desc, outs[(steps - 1) % copies], ms, kernels
 
 
+def time_graph_replay(name, steps, warmup):
+    """The same step recorded once into a HIP graph and replayed (the library only enqueues kernels,
+    so a call can be captured); one resident copy of the inputs."""
+    import torch
+    import paper_2203_00854_amd as P
+    from paper_2203_00854_amd import inputs as I
+    case = I.make_case(name)
+    desc, w, x, z, mask = P.to_device(case, "cuda:0")
+    chunk = case.spec.chunk_rows
+    out = torch.empty_like(x)
+    ws = torch.empty(P.ff_attention_workspace_bytes(desc, chunk), dtype=torch.uint8, device="cuda:0")
+
+    def step():
+        if chunk:
+            P.ff_attention_chunked(desc, w, x, z, mask, chunk_rows=chunk, out=out, ws=ws)
+        else:
+            P.ff_gated_attention(desc, w, x, z, mask, out=out, ws=ws)
+
+    step()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for _ in range(warmup):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
 def kernel_rooflines(sp, kernels, steps):
     """Per kernel: counted flop and algorithmic HBM bytes of one step (each operand of the kernel
     once), the two roofline ceilings they give at the published peaks, and the one that binds."""
@@ -307,6 +344,9 @@ def main():
             del c2
             torch.cuda.empty_cache()
         line["residual_update"] = upd
+        line["hip_graph_replay"] = {"workload": args.workload, "ms_per_step":
+                                    time_graph_replay(args.workload, args.steps, args.warmup),
+                                    "note": "one captured step replayed; one resident input copy"}
         line["layernorm"] = time_layernorm(args.steps)
 
     print(json.dumps(line))

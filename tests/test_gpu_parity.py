@@ -313,3 +313,49 @@ def test_workspace_too_small_is_an_error_not_a_fault():
     with pytest.raises(P.FFError) as e:
         P.ff_gated_attention(desc, w, x, z, mask, ws=ws)
     assert e.value.status == 3
+
+
+@pytest.mark.parametrize("mode,n_a,n_b,c,H,d,c_z,chunk", [
+    (ROW, 16, 128, 128, 4, 32, 64, 0), (TS, 96, 96, 64, 2, 16, 0, 40), (COL, 200, 12, 64, 8, 8, 0, 0),
+])
+def test_calls_can_be_captured_in_a_hip_graph(mode, n_a, n_b, c, H, d, c_z, chunk):
+    """The library only enqueues kernels on the caller's stream (no allocation, no synchronisation,
+    no memset), so a call can be recorded into a HIP graph.  Every replay, with eager work and
+    synchronisations in between, must reproduce the eager bits."""
+    case = I.make_case(small_spec(mode, n_a, n_b, c, H, d, c_z=c_z, dtype="bf16", mask="tail:5"))
+    desc, w, x, z, mask = P.to_device(case, DEV)
+    ws = torch.empty(P.ff_attention_workspace_bytes(desc, chunk), dtype=torch.uint8, device=DEV)
+
+    def call(out):
+        if chunk:
+            P.ff_attention_chunked(desc, w, x, z, mask, chunk_rows=chunk, out=out, ws=ws)
+        else:
+            P.ff_gated_attention(desc, w, x, z, mask, out=out, ws=ws)
+
+    eager = torch.empty_like(x)
+    call(eager)                                    # (also the one-time kernel attribute set-up)
+    torch.cuda.synchronize()
+    out = torch.zeros_like(x)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            call(out)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        out.fill_(float("nan"))
+        ws.random_(0, 255)                         # the workspace carries nothing from call to call
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), rep
+    x2 = x.clone()
+    x.mul_(0.5)                                    # new input values through the same pointers
+    ref2 = torch.empty_like(x)
+    call(ref2)
+    graph.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(out, ref2)
+    assert not torch.equal(ref2, eager)
+    x.copy_(x2)
