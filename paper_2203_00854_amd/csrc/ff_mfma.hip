@@ -61,6 +61,17 @@ __device__ __forceinline__ float bf16_round(float f) { return lo_f32(pack2(f, 0.
 
 __device__ __forceinline__ uint4 ldg16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
 __device__ __forceinline__ uint2 ldg8(const void* p) { return *reinterpret_cast<const uint2*>(p); }
+// The same loads and a store with the address split into a wave-uniform base (scalar registers)
+// and a 32-bit byte offset per lane: one instruction, no address arithmetic in the vector unit.
+__device__ __forceinline__ uint4 ldg16(const void* base, uint32_t lane_bytes) {
+    return *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(base) + lane_bytes);
+}
+__device__ __forceinline__ uint2 ldg8(const void* base, uint32_t lane_bytes) {
+    return *reinterpret_cast<const uint2*>(reinterpret_cast<const char*>(base) + lane_bytes);
+}
+__device__ __forceinline__ void stg16(void* base, uint32_t lane_bytes, uint4 v) {
+    *reinterpret_cast<uint4*>(reinterpret_cast<char*>(base) + lane_bytes) = v;
+}
 
 // sum of the two bf16 halves of w, added to acc (v_dot2c_f32_bf16)
 __device__ __forceinline__ float add_pair(uint32_t w, float acc) {
@@ -917,48 +928,61 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
         int hh = (int)(((float)rem + 0.5f) * a.inv_nq);
         hh -= hh * nq > rem;
         hh += (hh + 1) * nq <= rem;
-        const int rl_raw = rb * RB + wave;
+        // (the float quotients pass through vector registers: back to scalar ones, so that every
+        // address built from them has a scalar base)
+        const int rl_raw = __builtin_amdgcn_readfirstlane(rb) * RB + wave;
         row_ok = rl_raw < a.rows;
         rl = row_ok ? rl_raw : a.rows - 1;
-        h = hh;
-        q0 = (rem - hh * nq) * 64;
+        h = __builtin_amdgcn_readfirstlane(hh);
+        q0 = (rem - h * nq) * 64;
     };
     place(logical);
     const bool xlane = hf == HX;            // this lane carries the extra slots in step SX
+    // Addresses: every tensor of this kernel has Lp*D elements per (batch row, head); item_off is
+    // that block's element offset (scalar), the per-lane parts are 32-bit byte offsets that never change.
+    size_t item_off = 0;
+    // permuted key of S^T row m = col: rows 8g + 4b + e hold key 16*(g/2) + 8b + 4*(g%2) + e
+    const int kperm = 16 * (col >> 4) + 8 * ((col >> 2) & 1) + 4 * ((col >> 3) & 1) + (col & 3);
+    const uint32_t qg_lane = (uint32_t)(col * D + 8 * hf) * 2;                       // q, o: query col, elements 8hf..
+    const uint32_t k_lane = (uint32_t)(kperm * D + 8 * hf) * 2;                      // k: key kperm of a tile
+    const uint32_t v_lane = (uint32_t)((col < D ? col : 0) * 32 + 8 * hf) * 2;       // v^T: element col, keys 8hf..
+    const uint32_t gate_lane = (uint32_t)(col * D + 4 * hf) * 2;                     // gate: query col, elements 4hf..
 
     // ---- Q operand fragments: B operand, lane = query, 8 consecutive e
     Frag qf[2][KS];
     auto fetch_q = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-            const int qi = q0 + 32 * j + col;                       // < Lp
-            const bf16_t* qp = a.q + ((size_t)(rl * a.H + h) * a.Lp + qi) * D;
+            const bf16_t* qp = a.q + item_off + (size_t)(q0 + 32 * j) * D;      // (uniform; query q0 + 32j + col < Lp)
 #pragma unroll
             for (int s = 0; s < KS; ++s) {
                 qf[j][s].u = make_uint4(0, 0, 0, 0);
-                if (2 * s + hf < PCX) qf[j][s].u = ldg16(qp + 16 * s + 8 * hf);
+                if (2 * s + hf < PCX) qf[j][s].u = ldg16(qp + 16 * s, qg_lane);
             }
         }
     };
-    fetch_q();
 
     // ---- bias tile pipeline: [64 queries][GK keys]; GK/4 threads per row, RPP rows per pass
     constexpr int TPR = GK / 4, RPP = RB * 64 / TPR, BP = 64 / RPP;
     static_assert(BP == 2 || BP == 4, "bias tile passes");
     const int b_row = tid / TPR, b_c4 = tid % TPR;
-    const float* bias_t = nullptr;
+    const float* bias_t = nullptr;            // (scalar) row q0 of the item's head
+    const uint32_t b_lane = (uint32_t)(b_row * a.Lp) * 4;
     float* s_bias_t = s_bias + (size_t)b_row * kBiasPitch + 4 * b_c4;
     // (named registers: an array captured by a lambda would be spilled to scratch)
     float4 bq0, bq1, bq2, bq3;
     auto load_bias = [&](int g) __attribute__((always_inline)) {
         int colk = GK * g + 4 * b_c4;              // (a last group that is only half there repeats valid keys)
         if (colk > a.Lp - 4) colk = a.Lp - 4;
-        const float* bp = bias_t + colk;
-        bq0 = *reinterpret_cast<const float4*>(bp);
-        bq1 = *reinterpret_cast<const float4*>(bp + (size_t)RPP * a.Lp);
+        const uint32_t off = b_lane + (uint32_t)colk * 4;
+        auto ld = [&](const float* base) __attribute__((always_inline)) {
+            return *reinterpret_cast<const float4*>(reinterpret_cast<const char*>(base) + off);
+        };
+        bq0 = ld(bias_t);
+        bq1 = ld(bias_t + (size_t)RPP * a.Lp);
         if constexpr (BP > 2) {
-            bq2 = *reinterpret_cast<const float4*>(bp + (size_t)(2 * RPP) * a.Lp);
-            bq3 = *reinterpret_cast<const float4*>(bp + (size_t)(3 * RPP) * a.Lp);
+            bq2 = ld(bias_t + (size_t)(2 * RPP) * a.Lp);
+            bq3 = ld(bias_t + (size_t)(3 * RPP) * a.Lp);
         }
     };
     auto store_bias = [&](int buf) __attribute__((always_inline)) {
@@ -971,20 +995,19 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
         }
     };
 
-    // permuted key of S^T row m = col: rows 8g + 4b + e hold key 16*(g/2) + 8b + 4*(g%2) + e
-    const int kperm = 16 * (col >> 4) + 8 * ((col >> 2) & 1) + 4 * ((col >> 3) & 1) + (col & 3);
     // k is [row][head][l][d], v^T is [row][head][l / 32][e][l % 32]: a 32-key tile of either is one
     // contiguous block of 64*D bytes
-    const bf16_t *kp, *vp;
     const float* mp;
+    const bool has_mask = a.mask != nullptr;
+    const int msl = (int)a.sl;                     // (1 or n_b)
     constexpr int kstep = 32 * D;
     auto set_pointers = [&]() __attribute__((always_inline)) {             // operands of the item (rl, h, q0)
-        kp = a.k + ((size_t)(rl * a.H + h) * a.Lp + kperm) * D + 8 * hf;
-        vp = a.vt + (size_t)(rl * a.H + h) * a.Lp * D + (col < D ? col : 0) * 32 + 8 * hf;
-        mp = a.mask ? a.mask + (int64_t)(a.r0 + rl) * a.sr : nullptr;
-        if constexpr (HAS_BIAS) bias_t = a.bias + ((size_t)h * a.Lq + q0 + b_row) * a.Lp;
+        item_off = (size_t)(rl * a.H + h) * a.Lp * D;
+        mp = has_mask ? a.mask + (int64_t)(a.r0 + rl) * a.sr : nullptr;
+        if constexpr (HAS_BIAS) bias_t = a.bias + ((size_t)h * a.Lq + q0) * a.Lp;
     };
     set_pointers();
+    fetch_q();
     if constexpr (HAS_BIAS) load_bias(0);      // (stored to LDS after the first K and V loads have been issued)
     const bool ones_lane = ONES_ROW && col == D;
 
@@ -997,20 +1020,39 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
     Frag kb0[KS], kb1[KS], vb0[2], vb1[2];
     float mv0 = 1.f, mv1 = 1.f;
     auto fetch_k = [&](Frag (&kb)[KS], float& mv, int kt) __attribute__((always_inline)) {
+        // (the empty statement hides the lane offset from the loop optimiser, which would otherwise
+        // add it to the tile's base once and carry a 64-bit pointer per lane through the loop)
+        // and the tile index from being folded into an immediate offset that does not fit the instruction)
+        uint32_t lane_off = k_lane;
+        asm volatile("" : "+v"(lane_off));
+        int kts = kt;
+        asm volatile("" : "+s"(kts));
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             kb[s].u = make_uint4(0, 0, 0, 0);
-            if (2 * s + hf < PCX) kb[s].u = ldg16(kp + kt * kstep + 16 * s);
+            if (2 * s + hf < PCX) kb[s].u = ldg16(a.k + item_off + (size_t)kts * kstep + 16 * s, lane_off);
         }
-        const int key = 32 * kt + kperm;
+        // mask value of the lane's key (whoever uses mv pins it first, or the compiler compares it
+        // with zero right here and waits for every load just issued).  Keys beyond L - 1 read the
+        // entry of key L - 1; scalar base of the tile + 32-bit lane offset.
         mv = 1.f;
-        if (mp) mv = mp[(int64_t)(key < a.L ? key : a.L - 1) * a.sl];
+        if (has_mask) {
+            int k0 = 32 * kts;
+            if (k0 > ((a.L - 1) & ~31)) k0 = (a.L - 1) & ~31;
+            const int lk = kperm < a.L - 1 - k0 ? kperm : a.L - 1 - k0;          // >= 0
+            mv = *reinterpret_cast<const float*>(reinterpret_cast<const char*>(mp + (int64_t)k0 * msl) +
+                                                 (uint32_t)(lk * msl) * 4u);
+        }
     };
     auto fetch_v = [&](Frag (&vb)[2], int kt) __attribute__((always_inline)) {
+        uint32_t lane_off = v_lane;
+        asm volatile("" : "+v"(lane_off));
+        int kts = kt;
+        asm volatile("" : "+s"(kts));
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
             vb[c].u = make_uint4(0, 0, 0, 0);
-            if (col < D) vb[c].u = ldg16(vp + kt * kstep + 16 * c);
+            if (col < D) vb[c].u = ldg16(a.vt + item_off + (size_t)kts * kstep + 16 * c, lane_off);
         }
     };
 
@@ -1040,7 +1082,8 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
         }
     };
     auto qk_mma = [&](Frag (&kb)[KS], float mv, int kt, f32x16 (&sa)[2]) __attribute__((always_inline)) -> bool {
-        const bool key_valid = mv != 0.f && 32 * kt + kperm < a.L;
+        asm volatile("" : "+v"(mv));
+        const bool key_valid = (!has_mask || mv != 0.f) && 32 * kt + kperm < a.L;
         if (!__any(key_valid)) return false;
         if (xlane) kb[SX].w[0] = key_valid ? 0x00003f80u : 0xff803f80u;   // (1.0, mask term)
         if constexpr (!HAS_BIAS) {          // (zero accumulator input: a constant operand of the first step)
@@ -1073,7 +1116,8 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
         constexpr bool FUSE = decltype(fuse_c)::value;
         bool next_live = sn_live;
         if constexpr (FUSE) {
-            const bool key_valid = mvn != 0.f && 32 * ktn + kperm < a.L;
+            asm volatile("" : "+v"(mvn));
+            const bool key_valid = (!has_mask || mvn != 0.f) && 32 * ktn + kperm < a.L;
             next_live = __any(key_valid);           // (a tile without valid keys is still contracted: all -inf, never used)
             if (xlane) kbn[SX].w[0] = key_valid ? 0x00003f80u : 0xff803f80u;   // (1.0, mask term)
             if constexpr (!HAS_BIAS) {
@@ -1249,11 +1293,11 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
             // values only.
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
-                const size_t t = ((size_t)(rl * a.H + h) * a.Lp + q0 + 32 * j + col) * D;
+                const bf16_t* gp = a.g + item_off + (size_t)(q0 + 32 * j) * D;
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     gate[j][g] = make_uint2(0, 0);
-                    if (8 * g + 4 * hf < D) gate[j][g] = ldg8(a.g + t + 8 * g + 4 * hf);
+                    if (8 * g + 4 * hf < D) gate[j][g] = ldg8(gp + 8 * g, gate_lane);
                 }
             }
             if constexpr (PERSIST) {
@@ -1319,7 +1363,7 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
         const int qi = e_q0 + 32 * j + col;                       // < Lp
         // gate and context are head-major [row][head][l][d]: the wave's 32 queries are one
         // contiguous block of 64*D bytes
-        const size_t t = ((size_t)(e_rl * a.H + e_h) * a.Lp + qi) * D;
+        bf16_t* op = a.o + (size_t)(e_rl * a.H + e_h) * a.Lp * D + (size_t)(e_q0 + 32 * j) * D;   // (uniform)
         uint32_t pk[8];
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
@@ -1332,9 +1376,8 @@ __global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
         merge_halves(pk[4], pk[6]);      // lower: e 16..23, upper: e 24..31
         merge_halves(pk[5], pk[7]);
         if (e_row_ok && qi < a.L) {
-            if (8 * hf < D) *reinterpret_cast<uint4*>(a.o + t + 8 * hf) = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-            if (16 + 8 * hf < D)
-                *reinterpret_cast<uint4*>(a.o + t + 16 + 8 * hf) = make_uint4(pk[4], pk[5], pk[6], pk[7]);
+            if (8 * hf < D) stg16(op, qg_lane, make_uint4(pk[0], pk[1], pk[2], pk[3]));
+            if (16 + 8 * hf < D) stg16(op + 16, qg_lane, make_uint4(pk[4], pk[5], pk[6], pk[7]));
         }
     }
     if (next < 0) break;
@@ -1394,9 +1437,18 @@ static int pick_split(int blocks_m, int tiles_n) {
     return split;
 }
 
+// Batch rows per attention block (one wavefront each).  With a bias, 8 rows halve the bias traffic
+// of 4.  Without one nothing is shared inside a block, and for head dims below 32 the kernel needs
+// at most 168 registers: blocks of 4 wavefronts then fit three to a compute unit (three
+// wavefronts per SIMD) where a block of 8 leaves a third of the register file empty.
+static int attn_rows_per_block(const Problem& p, int rows) {
+    if (rows < 8) return 4;
+    return (!p.has_bias && p.d < 32) ? 4 : 8;
+}
+
 // work items of one attention launch over `rows` batch rows
 static int64_t attn_items(const Problem& p, int rows) {
-    const int rb = rows >= 8 ? 8 : 4;
+    const int rb = attn_rows_per_block(p, rows);
     return (int64_t)(round_up(p.L, 64) / 64) * p.H * ((rows + rb - 1) / rb);
 }
 
@@ -1419,14 +1471,29 @@ static int compute_units() {
 }
 
 template <int D, bool HAS_BIAS, int RB, int GK, bool PERSIST>
-static void launch_attn(dim3 grid, size_t smem, hipStream_t st, const AttnArgs& a) {
+static void launch_attn(int n_items, size_t smem, hipStream_t st, const AttnArgs& a) {
     static bool attr_set = false;          // more than 64 KiB of dynamic LDS has to be asked for once
     if (!attr_set && smem > 64 * 1024) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn<D, HAS_BIAS, RB, GK, PERSIST>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
         attr_set = true;
     }
-    hipLaunchKernelGGL((k_attn<D, HAS_BIAS, RB, GK, PERSIST>), grid, dim3(RB * 64), smem, st, a);
+    int n_blocks = n_items;
+    if constexpr (PERSIST) {
+        // persistent blocks: as many as the chip holds at once (registers and LDS of this
+        // instantiation decide how many fit a compute unit), each working through its share of the items
+        static int per_cu = 0;
+        if (per_cu == 0) {
+            int nb = 0;
+            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, reinterpret_cast<const void*>(&k_attn<D, HAS_BIAS, RB, GK, PERSIST>),
+                                                             RB * 64, smem) != hipSuccess || nb < 1)
+                nb = 1;
+            per_cu = nb;
+        }
+        const int resident = compute_units() * per_cu;
+        if (n_blocks > resident) n_blocks = resident;
+    }
+    hipLaunchKernelGGL((k_attn<D, HAS_BIAS, RB, GK, PERSIST>), dim3(((n_blocks + 7) / 8) * 8), dim3(RB * 64), smem, st, a);
 }
 
 static GemmArgs proj_args(const Problem& p, const MfmaWs& m, const Workspace& ws) {
@@ -1516,26 +1583,22 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
     a.inv_nq = 1.f / (float)(Lp / 64); a.inv_nqh = 1.f / (float)((Lp / 64) * p.H);
     {
         Timed t(KK_ATTN, st);
-        // batch rows per block (one wavefront each): 8 halve the bias traffic of 4
-        const int rb = rows >= 8 ? 8 : 4;
+        const int rb = attn_rows_per_block(p, rows);
         const int n_items = (int)attn_items(p, rows);          // < 2^22: mfma_chunk_ok
         // keys per bias tile: 128 halve the barriers of long sequences, 64 keep the first tile of short ones small
         const int gk = (p.has_bias && rb == 8 && Lp >= 512) ? 128 : 64;
         // short sequences: persistent blocks, one per rb wave slots of a compute unit (the kernel
         // keeps two wavefronts per SIMD), each working through its share of the items
         const bool persist = Lp < 512;
-        const int resident = compute_units() * (8 / rb);
-        const int n_blocks = (!persist || n_items < resident) ? n_items : resident;
-        dim3 grid(((n_blocks + 7) / 8) * 8);
         const size_t bias_bytes = (size_t)2 * 64 * (gk + kBiasPad) * 4;   // two float tiles
 #define FF_ATTN3(DD, HB, RBV, GKV, SM)                                       \
     do {                                                                     \
-        if (persist) launch_attn<DD, HB, RBV, GKV, true>(grid, SM, st, a);   \
-        else launch_attn<DD, HB, RBV, GKV, false>(grid, SM, st, a);          \
+        if (persist) launch_attn<DD, HB, RBV, GKV, true>(n_items, SM, st, a);   \
+        else launch_attn<DD, HB, RBV, GKV, false>(n_items, SM, st, a);          \
     } while (0)
 #define FF_ATTN2(DD, RBV)                                                   \
     do {                                                                    \
-        if (p.has_bias && gk == 128) launch_attn<DD, true, 8, 128, false>(grid, bias_bytes, st, a); \
+        if (p.has_bias && gk == 128) launch_attn<DD, true, 8, 128, false>(n_items, bias_bytes, st, a); \
         else if (p.has_bias) FF_ATTN3(DD, true, RBV, 64, bias_bytes);                        \
         else FF_ATTN3(DD, false, RBV, 64, 0);                                                \
     } while (0)
