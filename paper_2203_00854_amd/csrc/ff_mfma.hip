@@ -883,8 +883,11 @@ constexpr int kBiasPad = 4;      // floats added to an LDS bias row: conflict-fr
 constexpr float kRaise = 10.f;   // log2 units
 constexpr float kOver = 1048576.f;   // 2^20: partial denominator (16 keys) that triggers a raise of the reference
 
+// (bias-free 4-row blocks for head dims below 32 are held to 168 registers, three wavefronts per
+// SIMD: d = 8 fits as it is, d = 16 spills fifteen registers and is still 9 % faster; at d = 32 the
+// same bound costs more in spills than the third wavefront brings)
 template <int D, bool HAS_BIAS, int RB, int GK, bool PERSIST>
-__global__ __launch_bounds__(RB * 64) void k_attn(AttnArgs a) {
+__global__ __launch_bounds__(RB * 64, (RB == 4 && !HAS_BIAS && D < 32) ? 3 : 2) void k_attn(AttnArgs a) {
     constexpr int PCX = D / 8;              // index of the 8-slot piece holding the two extra slots
     constexpr int KS = PCX / 2 + 1;         // 16-wide contraction steps
     constexpr int SX = PCX / 2, HX = PCX % 2;
