@@ -26,6 +26,9 @@ sys.path.insert(0, ROOT)
 # published MI355X peaks used for the roofline fractions
 PEAK_MFMA_BF16_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
+# plain (unpacked) float32 vector instructions: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-operations per second
+# (the published 157.3 TFLOP/s is this rate x 2 for the packed forms, which this build switches off, x 2 for FMA)
+PEAK_VALU_GLANEOPS = 256 * 4 * 16 * 2.4
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file
 # (profiles/traffic_*_hbm_counters.txt: KiB per dispatch, fetch scaled by 2.0 and write by 1.0,
@@ -170,6 +173,11 @@ def kernel_rooflines(sp, kernels, steps):
         "pair bias pass": (fl["bias"], (L * L * sp.c_z if sp.mode == 0 else tok * sp.c) * 2 + bias_out
                            + (2.0 * (4 * hd + sp.heads) * sp.c * 2 if sp.mode == 0 else 0.0)),
     }
+    # vector-unit work of the attention kernel that no design can avoid, in lane-operations per score
+    # element: exp2 at half rate (2), half a pack (two elements per instruction), and either half a
+    # partial-denominator instruction (d = 32) or one maximum (d < 32, where the matrix core sums the
+    # denominator but every tile takes its maximum)
+    alu_per_step = {"k_attn": R * sp.heads * L * L * (3.0 if sp.head_dim >= 32 else 3.5)}
     rows = []
     for name, (ms, cnt) in kernels.items():
         r = {"kernel": name, "launches_per_step": cnt / steps, "avg_us": ms / cnt * 1e3, "ms_per_step": ms / steps}
@@ -180,7 +188,14 @@ def kernel_rooflines(sp, kernels, steps):
             r.update(achieved_tflops=tf, frac_mfma=tf / PEAK_MFMA_BF16_TFLOPS, achieved_gbs=gb, frac_hbm=gb / PEAK_HBM_GBS,
                      flop_per_step=flop, algorithmic_bytes_per_step=byts)
             # the ceiling that binds is the one that needs more time at its peak
-            if flop / (PEAK_MFMA_BF16_TFLOPS * 1e12) >= byts / (PEAK_HBM_GBS * 1e9):
+            t_mfma, t_hbm = flop / (PEAK_MFMA_BF16_TFLOPS * 1e12), byts / (PEAK_HBM_GBS * 1e9)
+            t_alu = alu_per_step.get(name, 0.0) / (PEAK_VALU_GLANEOPS * 1e9)
+            if t_alu > 0.0:
+                gl = alu_per_step[name] / sec / 1e9
+                r.update(achieved_glaneops=gl, frac_alu=gl / PEAK_VALU_GLANEOPS, alu_laneops_per_step=alu_per_step[name])
+            if t_alu >= t_mfma and t_alu >= t_hbm:
+                r.update(bound="alu", achieved=gl, peak=PEAK_VALU_GLANEOPS, unit="Glane-op/s", frac=gl / PEAK_VALU_GLANEOPS)
+            elif t_mfma >= t_hbm:
                 r.update(bound="mfma", achieved=tf, peak=PEAK_MFMA_BF16_TFLOPS, unit="TFLOP/s", frac=tf / PEAK_MFMA_BF16_TFLOPS)
             else:
                 r.update(bound="hbm", achieved=gb, peak=PEAK_HBM_GBS, unit="GB/s", frac=gb / PEAK_HBM_GBS)
