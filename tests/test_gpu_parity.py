@@ -182,6 +182,11 @@ SHAPES = [
     (TS, 33, 33, 100, 2, 64, 0, "none"),         # head_dim 64
     (TS, 530, 530, 32, 2, 32, 0, "tail:11"),     # 17 key tiles: the last 128-key bias group is only half there
     (ROW, 9, 700, 64, 2, 32, 16, "random:0.9"),  # 22 key tiles, nine batch rows (a ragged second block of rows)
+    # many short items per persistent attention block: one bias group per item (the LDS buffers alternate from
+    # item to item), four-row blocks without a bias, and six bias groups per item at d = 32
+    (ROW, 1500, 40, 32, 4, 8, 16, "random:0.7"),
+    (COL, 70, 1100, 32, 2, 16, 0, "tail:7"),
+    (TS, 330, 330, 32, 4, 32, 0, "outer:0.9"),
 ]
 
 
