@@ -30,16 +30,28 @@ PEAK_HBM_GBS = 8000.0
 # (the published 157.3 TFLOP/s is this rate x 2 for the packed forms, which this build switches off, x 2 for FMA)
 PEAK_VALU_GLANEOPS = 256 * 4 * 16 * 2.4
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file
-# (profiles/traffic_*_hbm_counters.txt: KiB per dispatch, fetch scaled by 2.0 and write by 1.0,
-# the factors a plain 256 MiB copy gives); null for workloads without such a run.
-_KIB = 1024
-TRAFFIC_BYTES = {
-    ("c2_row_bf16_train", "pair bias pass"): int((8533.3 * 2.0 + 2592.5) * _KIB),
-    ("c2_row_bf16_train", "k_gemm<PROJ>"): int((10485.0 * 2.0 + 65536.0) * _KIB),
-    ("c2_row_bf16_train", "k_attn"): int((57014.8 * 2.0 + 16384.0) * _KIB),
-    ("c2_row_bf16_train", "k_gemm<OUT>"): int((8773.5 * 2.0 + 21021.7) * _KIB),
-}
+# Peaks measured on an MI355X of this machine with the library's own probes (a bare loop of bf16
+# 32x32x16 matrix instructions; a plain 256 MiB copy): bench.py measures both again in every run
+# (the "calibration" object of the line) and quotes fractions against the published peaks and
+# against what it has just measured.
+
+# HBM bytes per launch come from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this file, whose
+# summaries (profiles/traffic_<workload>_hbm_counters.txt) end in machine-readable lines
+#   traffic_bytes_per_launch <kernel kind> = <bytes>
+# (KiB per dispatch, each counter scaled by the factor that the same counter gives for a plain copy
+# of known size in the same run).  Workloads without such a file, or a tree without profiles/,
+# report null.
+def traffic_bytes(workload):
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload}_hbm_counters.txt")
+    out = {}
+    try:
+        for ln in open(path):
+            if ln.startswith("traffic_bytes_per_launch "):
+                name, _, val = ln[len("traffic_bytes_per_launch "):].rpartition("=")
+                out[name.strip()] = int(float(val))
+    except OSError:
+        pass
+    return out
 
 
 def counted_flop(sp):
@@ -152,9 +164,15 @@ def time_graph_replay(name, steps, warmup):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
-def kernel_rooflines(sp, kernels, steps):
-    """Per kernel: counted flop and algorithmic HBM bytes of one step (each operand of the kernel
-    once), the two roofline ceilings they give at the published peaks, and the one that binds."""
+def kernel_rooflines(sp, kernels, steps, measured=None):
+    """Per kernel: counted flop and HBM bytes of one step, and the roofline that bounds it.
+
+    A dense contraction (the two GEMMs) is priced against the bf16 matrix peak: frac = counted flop /
+    duration / peak.  Its HBM figure is given beside it twice: with the operands the METHOD needs
+    (x and weights in; for the output projection, out written) and with the intermediates this
+    implementation moves through HBM as well (q, k, v, gate, context).  The attention kernel at
+    head dims <= 32 is bound by the vector unit ("alu"), the pair-bias pass by HBM.
+    measured: {"mfma_tflops": ..., "copy_gbs": ...} from this run's probes, for the second set of fractions."""
     fl = counted_flop(sp)
     R, L = sp.batch_len
     rows_per_launch = sp.chunk_rows if sp.chunk_rows else R
@@ -162,47 +180,85 @@ def kernel_rooflines(sp, kernels, steps):
     tok = R * L                                    # tokens per step (all launches of a step together)
     tri_fused = sp.mode in (2, 3) and not sp.chunk_rows
     bias_out = sp.heads * L * L * 4
-    per_step = {   # name -> (flop, bytes)
-        "k_prep": (0.0, 2.0 * ((4 * hd + sp.heads) * sp.c * 2)),
+    w_main = (4 * hd + 32) * sp.c * 2
+    per_step = {   # name -> (flop, bytes the method needs, bytes with this implementation's intermediates, natural bound)
+        "k_prep": (0.0, 2.0 * ((4 * hd + sp.heads) * sp.c * 2), None, "hbm"),
         "k_gemm<PROJ>": (fl["proj"] + (fl["bias"] if tri_fused else 0.0),
-                         tok * (sp.c + 4 * hd) * 2 + (4 * hd + 32) * sp.c * 2 + (bias_out if tri_fused else 0)),
-        "k_attn": (fl["attn"], tok * 5 * hd * 2 + (bias_out * (R // rows_per_launch) if sp.mode != 1 else 0)),
-        "k_gemm<OUT>": (fl["out"], tok * (hd + sp.c) * 2 + hd * sp.c * 2),
+                         tok * sp.c * 2 + w_main,
+                         tok * (sp.c + 4 * hd) * 2 + w_main + (bias_out if tri_fused else 0), "mfma"),
+        "k_attn": (fl["attn"], None,
+                   tok * 5 * hd * 2 + (bias_out * (R // rows_per_launch) if sp.mode != 1 else 0), "alu"),
+        "k_gemm<OUT>": (fl["out"], tok * sp.c * 2 + hd * sp.c * 2, tok * (hd + sp.c) * 2 + hd * sp.c * 2, "mfma"),
         # row mode: k_prep_bias (z once, the float32 bias, and the weight preparation in the same
-        # launch); chunked triangle modes: the pair-bias tile of k_gemm<PROJ> over all of x
+        # launch); chunked triangle modes: the pair-bias pass over all of x
         "pair bias pass": (fl["bias"], (L * L * sp.c_z if sp.mode == 0 else tok * sp.c) * 2 + bias_out
-                           + (2.0 * (4 * hd + sp.heads) * sp.c * 2 if sp.mode == 0 else 0.0)),
+                           + (2.0 * (4 * hd + sp.heads) * sp.c * 2 if sp.mode == 0 else 0.0), None, "hbm"),
     }
     # vector-unit work of the attention kernel that no design can avoid, in lane-operations per score
     # element: exp2 at half rate (2), half a pack (two elements per instruction), and either half a
     # partial-denominator instruction (d = 32) or one maximum (d < 32, where the matrix core sums the
     # denominator but every tile takes its maximum)
     alu_per_step = {"k_attn": R * sp.heads * L * L * (3.0 if sp.head_dim >= 32 else 3.5)}
+    traffic = traffic_bytes(sp.name)
     rows = []
     for name, (ms, cnt) in kernels.items():
         r = {"kernel": name, "launches_per_step": cnt / steps, "avg_us": ms / cnt * 1e3, "ms_per_step": ms / steps}
         if name in per_step:
-            flop, byts = per_step[name]
+            flop, b_method, b_impl, bound = per_step[name]
             sec = ms / steps * 1e-3
-            tf, gb = flop / sec / 1e12, byts / sec / 1e9
-            r.update(achieved_tflops=tf, frac_mfma=tf / PEAK_MFMA_BF16_TFLOPS, achieved_gbs=gb, frac_hbm=gb / PEAK_HBM_GBS,
-                     flop_per_step=flop, algorithmic_bytes_per_step=byts)
-            # the ceiling that binds is the one that needs more time at its peak
-            t_mfma, t_hbm = flop / (PEAK_MFMA_BF16_TFLOPS * 1e12), byts / (PEAK_HBM_GBS * 1e9)
-            t_alu = alu_per_step.get(name, 0.0) / (PEAK_VALU_GLANEOPS * 1e9)
-            if t_alu > 0.0:
+            tf = flop / sec / 1e12
+            r.update(flop_per_step=flop, achieved_tflops=tf, frac_mfma=tf / PEAK_MFMA_BF16_TFLOPS)
+            if b_method is not None:
+                r.update(method_bytes_per_step=b_method, method_gbs=b_method / sec / 1e9,
+                         frac_hbm_method_bytes=b_method / sec / 1e9 / PEAK_HBM_GBS)
+            if b_impl is not None:
+                r.update(bytes_with_intermediates_per_step=b_impl, gbs_with_intermediates=b_impl / sec / 1e9,
+                         frac_hbm_with_intermediates=b_impl / sec / 1e9 / PEAK_HBM_GBS)
+            if name in alu_per_step:
                 gl = alu_per_step[name] / sec / 1e9
                 r.update(achieved_glaneops=gl, frac_alu=gl / PEAK_VALU_GLANEOPS, alu_laneops_per_step=alu_per_step[name])
-            if t_alu >= t_mfma and t_alu >= t_hbm:
-                r.update(bound="alu", achieved=gl, peak=PEAK_VALU_GLANEOPS, unit="Glane-op/s", frac=gl / PEAK_VALU_GLANEOPS)
-            elif t_mfma >= t_hbm:
+            if bound == "alu":
+                # (at head dims of 64 and more the matrix core would bind; the workloads here have d <= 32)
+                r.update(bound="alu", achieved=r["achieved_glaneops"], peak=PEAK_VALU_GLANEOPS, unit="Glane-op/s",
+                         frac=r["frac_alu"])
+            elif bound == "mfma":
                 r.update(bound="mfma", achieved=tf, peak=PEAK_MFMA_BF16_TFLOPS, unit="TFLOP/s", frac=tf / PEAK_MFMA_BF16_TFLOPS)
+                if measured and measured.get("mfma_tflops"):
+                    r["frac_of_measured_peak"] = tf / measured["mfma_tflops"]
             else:
+                gb = b_method / sec / 1e9
                 r.update(bound="hbm", achieved=gb, peak=PEAK_HBM_GBS, unit="GB/s", frac=gb / PEAK_HBM_GBS)
-        r["traffic"] = TRAFFIC_BYTES.get((sp.name, name))
+                if measured and measured.get("copy_gbs"):
+                    r["frac_of_measured_peak"] = gb / measured["copy_gbs"]
+        r["traffic"] = traffic.get(name)
         rows.append(r)
     rows.sort(key=lambda r: -r["ms_per_step"])
     return rows
+
+
+def calibrate():
+    """What this GPU sustains on the library's two probes: a bare loop of bf16 32x32x16 matrix
+    instructions and a plain 256 MiB copy (read + written bytes per second)."""
+    import torch
+    import paper_2203_00854_amd as P
+    sink = torch.empty(P.lib().ff_probe_sink_bytes(), dtype=torch.uint8, device="cuda:0")
+    src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda:0").fill_(1)
+    dst = torch.empty_like(src)
+    P.ff_probe_mfma(sink, 2000)
+    P.ff_probe_copy(dst, src)
+    torch.cuda.synchronize()
+    P.ff_profile_enable(True)
+    flop = 0.0
+    for _ in range(5):
+        flop = P.ff_probe_mfma(sink, 20000)
+        P.ff_probe_copy(dst, src)
+    torch.cuda.synchronize()
+    k = P.ff_profile_collect()
+    P.ff_profile_enable(False)
+    ms_m, n_m = k["probe: mfma loop"]
+    ms_c, n_c = k["probe: copy"]
+    return {"mfma_tflops": flop / (ms_m / n_m * 1e-3) / 1e12, "copy_gbs": 2.0 * (256 << 20) / (ms_c / n_c * 1e-3) / 1e9,
+            "note": "library probes, HIP-event timed: 32x32x16 bf16 matrix-instruction loop, 256 MiB copy (read + written)"}
 
 
 def time_layernorm(steps):
@@ -292,11 +348,13 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    measured = calibrate()
     case, desc, out, ms, kernels = time_workload(args.workload, args.steps, args.warmup)
+    path_taken = P.ff_attention_last_path()
     sp = case.spec
     fl = counted_flop(sp)
     value = fl["total"] / (ms * 1e-3) / 1e12
-    roof = kernel_rooflines(sp, kernels, args.steps)
+    roof = kernel_rooflines(sp, kernels, args.steps, measured)
 
     line = {
         "metric": "evoformer_attention_tflops", "value": value, "unit": "TFLOP/s", "n_gpus": 1,
@@ -305,18 +363,29 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{sp.name}: gated attention mode {sp.mode}, x[{sp.n_a},{sp.n_b},{sp.c}], c_z={sp.c_z}, "
                                f"H={sp.heads}, d={sp.head_dim}, mask {sp.mask}, one module per step",
-                   "path": P.ff_attention_path(desc), "counted_flop_per_step": fl["total"],
+                   "path": path_taken, "counted_flop_per_step": fl["total"],
                    "algorithmic_bytes_per_step": algorithmic_bytes(sp)},
         "ms_per_module": ms,
         "frac_mfma_peak_whole_module": value / PEAK_MFMA_BF16_TFLOPS,
         "frac_hbm_peak_whole_module": algorithmic_bytes(sp) / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        "calibration": measured,
+        "frac_measured_mfma_whole_module": value / measured["mfma_tflops"],
     }
     if roof:
         d = roof[0]
         line["roofline"] = {"kernel": d["kernel"], "bound": d.get("bound"), "achieved": d.get("achieved"),
                             "peak": d.get("peak"), "unit": d.get("unit"), "frac": d.get("frac"),
-                            "traffic": d.get("traffic"), "avg_us": d["avg_us"]}
+                            "traffic": d.get("traffic"), "avg_us": d["avg_us"],
+                            "frac_of_measured_peak": d.get("frac_of_measured_peak")}
         line["kernels"] = roof
+        # HBM bytes the whole module moved (counter runs) over the bytes the method needs
+        tr = [r.get("traffic") for r in roof]
+        if tr and all(t is not None for t in tr):
+            line["traffic_bytes_whole_module"] = sum(t * r["launches_per_step"] for t, r in zip(tr, roof))
+            line["traffic_ratio"] = line["traffic_bytes_whole_module"] / algorithmic_bytes(sp)
+        else:
+            line["traffic_bytes_whole_module"] = None
+            line["traffic_ratio"] = None
 
     if not args.no_cpu:
         ref, base = cpu_baseline(case)
@@ -327,7 +396,8 @@ def main():
 
     if not args.no_others:
         others = {}
-        for name, st, wu in (("c3_tri_start_bf16_256", args.steps, args.warmup),
+        for name, st, wu in (("c1_row_f32_tiny", args.steps, args.warmup),
+                             ("c3_tri_start_bf16_256", args.steps, args.warmup),
                              ("c3_tri_end_bf16_256", args.steps, args.warmup),
                              ("c4_col_bf16_extra", max(args.steps // 4, 5), 3),
                              ("c5_tri_start_bf16_2048", max(args.steps // 40, 3), 1),
@@ -340,10 +410,10 @@ def main():
             c2, d2, _, ms2, k2 = time_workload(name, st, wu)
             f2 = counted_flop(c2.spec)["total"]
             others[name] = {"ms_per_module": ms2, "tflops": f2 / (ms2 * 1e-3) / 1e12, "steps": st,
-                            "chunk_rows": c2.spec.chunk_rows, "path": P.ff_attention_path(d2),
+                            "chunk_rows": c2.spec.chunk_rows, "path": P.ff_attention_last_path(),
                             "workspace_bytes": P.ff_attention_workspace_bytes(d2, c2.spec.chunk_rows),
                             "kernels": [{k: r[k] for k in ("kernel", "avg_us", "launches_per_step", "frac", "bound")
-                                         if k in r} for r in kernel_rooflines(c2.spec, k2, st)]}
+                                         if k in r} for r in kernel_rooflines(c2.spec, k2, st, measured)]}
             del c2
             torch.cuda.empty_cache()
         line["others"] = others

@@ -15,8 +15,11 @@
  *
  * Conventions for every entry point
  *   - All tensor pointers are DEVICE pointers owned by the caller.  The library never
- *     allocates or frees device memory and keeps no state between calls (scratch memory
- *     is the caller's workspace argument).
+ *     allocates or frees device memory (scratch memory is the caller's workspace argument)
+ *     and no call depends on an earlier one.  What it keeps inside the process is
+ *     bookkeeping only: device properties and per-kernel launch attributes looked up on first
+ *     use (initialised once, safely under concurrent first calls), the thread-local last
+ *     error and last kernel family, and the launch timer's records while that is on.
  *   - Tensors are dense, row-major, in the dtype named by the call (float32 or bfloat16).
  *     Weights have the tensor dtype.  The mask is always float32.
  *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = the default
@@ -139,10 +142,16 @@ ff_status ff_gated_attention_residual(const ff_attn_desc* desc, const ff_attn_we
                                       void* out, void* ws, size_t ws_bytes, void* hip_stream,
                                       int32_t chunk_rows);
 
-/* Name of the kernel family that ff_gated_attention would pick for this shape:
- * "mfma_bf16" (matrix-core path) or "generic" (float32 vector path).  For tests and the
- * benchmark report.  NULL if desc is invalid. */
+/* Name of the kernel family the SHAPE allows: "mfma_bf16" (matrix-core path) or "generic"
+ * (float32 vector path).  NULL if desc is invalid.  A call takes the matrix-core family only
+ * if, in addition, x, z, out and every weight pointer are 16-byte aligned and the chunk has
+ * fewer than 2^22 attention work items; ff_attention_last_path tells what a call really took. */
 const char* ff_attention_path(const ff_attn_desc* desc);
+
+/* Kernel family that the last attention call on this thread launched ("mfma_bf16" or
+ * "generic"; "" before the first call or if that call was rejected before choosing).  This
+ * is an observation, not a prediction: tests and the benchmark report assert on it. */
+const char* ff_attention_last_path(void);
 
 /* Launch timer, a diagnostic for benchmarks (no part of the attention path).  While it is on,
  * every kernel launch of the library is bracketed by two HIP events recorded on the launch
@@ -155,6 +164,21 @@ void ff_profile_enable(int32_t on);
 int32_t ff_profile_kinds(void);
 const char* ff_profile_name(int32_t kind);
 ff_status ff_profile_collect(double* total_ms, int64_t* launches);
+
+/* Calibration probes for the benchmark report (no part of the attention path): what this GPU
+ * sustains on a bare loop of 32x32x16 bf16 matrix instructions and on a plain copy, so that
+ * roofline fractions can be quoted against measured as well as published peaks.  Both only
+ * enqueue one kernel on hip_stream; time them with the launch timer above (kinds
+ * "probe: mfma loop", "probe: copy").
+ *   ff_probe_mfma: sink = device buffer of ff_probe_sink_bytes() bytes (receives sums nobody reads);
+ *                  iters >= 1 rounds of four matrix instructions per wavefront; *flop (host) receives
+ *                  the floating-point operations the launch performs.
+ *   ff_probe_copy: dst[i] = src[i] for `bytes` bytes (device pointers and size multiples of 16):
+ *                  `bytes` read + `bytes` written.
+ * FF_EINVAL for bad arguments, FF_EHIP if the launch fails. */
+size_t ff_probe_sink_bytes(void);
+ff_status ff_probe_mfma(void* sink, int32_t iters, double* flop, void* hip_stream);
+ff_status ff_probe_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
 
 /* Message for the last non-OK status returned on this thread ("" if none). */
 const char* ff_last_error(void);

@@ -63,6 +63,8 @@ def lib() -> C.CDLL:
         L.ff_gated_attention_residual.argtypes = common + [C.c_int32]
         L.ff_attention_path.restype = C.c_char_p
         L.ff_attention_path.argtypes = [C.POINTER(AttnDesc)]
+        L.ff_attention_last_path.restype = C.c_char_p
+        L.ff_attention_last_path.argtypes = []
         L.ff_profile_enable.restype = None
         L.ff_profile_enable.argtypes = [C.c_int32]
         L.ff_profile_kinds.restype = C.c_int32
@@ -70,6 +72,12 @@ def lib() -> C.CDLL:
         L.ff_profile_name.argtypes = [C.c_int32]
         L.ff_profile_collect.restype = C.c_int
         L.ff_profile_collect.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_int64)]
+        L.ff_probe_sink_bytes.restype = C.c_size_t
+        L.ff_probe_sink_bytes.argtypes = []
+        L.ff_probe_mfma.restype = C.c_int
+        L.ff_probe_mfma.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.c_void_p]
+        L.ff_probe_copy.restype = C.c_int
+        L.ff_probe_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.ff_last_error.restype = C.c_char_p
         L.ff_version.restype = C.c_char_p
         _lib = L
@@ -144,6 +152,11 @@ def ff_attention_path(desc: AttnDesc) -> str:
     return p.decode()
 
 
+def ff_attention_last_path() -> str:
+    """Kernel family the last attention call on this thread really launched."""
+    return lib().ff_attention_last_path().decode()
+
+
 def _alloc_ws(nbytes: int, device):
     import torch
     return torch.empty(nbytes, dtype=torch.uint8, device=device)
@@ -206,6 +219,21 @@ def ff_profile_collect():
     cnt = (C.c_int64 * n)()
     _check(lib().ff_profile_collect(ms, cnt))
     return {lib().ff_profile_name(i).decode(): (ms[i], cnt[i]) for i in range(n) if cnt[i]}
+
+
+def ff_probe_mfma(sink, iters: int) -> float:
+    """Enqueue the matrix-instruction probe; returns the flop of the launch."""
+    flop = C.c_double(0.0)
+    assert sink.numel() * sink.element_size() >= lib().ff_probe_sink_bytes()
+    _check(lib().ff_probe_mfma(_ptr(sink), iters, C.byref(flop), _stream()))
+    return flop.value
+
+
+def ff_probe_copy(dst, src):
+    """Enqueue the copy probe over the whole of two equally sized contiguous tensors."""
+    n = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == n
+    _check(lib().ff_probe_copy(_ptr(dst), _ptr(src), n, _stream()))
 
 
 # ------------------------------------------------------------------------- test/bench glue

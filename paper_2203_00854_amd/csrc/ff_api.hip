@@ -18,7 +18,8 @@ struct ProfRec { int kind; hipEvent_t a, b; };
 static std::vector<ProfRec> g_prof;
 static std::vector<hipEvent_t> g_prof_pool;
 static const char* kKindNames[KK_COUNT] = {"k_prep", "pair bias pass", "k_gemm<PROJ>", "k_attn",
-                                           "k_gemm<OUT>", "k_layernorm", "generic family"};
+                                           "k_gemm<OUT>", "k_layernorm", "generic family", "probe: mfma loop",
+                                           "probe: copy"};
 
 static hipEvent_t prof_event() {
     if (!g_prof_pool.empty()) {
@@ -52,6 +53,7 @@ void prof_end(int kind, hipStream_t st) {
 }
 
 static thread_local char g_err[512] = "";
+static thread_local const char* g_last_path = "";     // kernel family of this thread's last attention call
 
 ff_status fail(ff_status st, const char* fmt, ...) {
     va_list ap;
@@ -161,6 +163,7 @@ static ff_status run(const ff_attn_desc* desc, const ff_attn_weights* w, const v
     for (const void* q : wp) fast = fast && aligned16(q);
     Workspace ws;
     carve(p, chunk, &ws, wsp, fast);
+    g_last_path = fast ? "mfma_bf16" : "generic";
     if (fast) {
         st = mfma_prepare(p, *w, x, z, ws, stream);
     } else {
@@ -232,6 +235,8 @@ const char* ff_attention_path(const ff_attn_desc* desc) {
     if (make_problem(desc, &p) != FF_OK) return nullptr;
     return mfma_supported(p) ? "mfma_bf16" : "generic";
 }
+
+const char* ff_attention_last_path(void) { return g_last_path; }
 
 void ff_profile_enable(int32_t on) {
     std::lock_guard<std::mutex> lk(g_prof_mu);

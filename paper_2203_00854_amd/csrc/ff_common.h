@@ -68,7 +68,8 @@ struct Workspace {
 };
 
 // kernel kinds for the launch timer (ff_profile_* in the C ABI)
-enum KernelKind { KK_PREP = 0, KK_BIAS, KK_PROJ, KK_ATTN, KK_OUT, KK_LAYERNORM, KK_GENERIC, KK_COUNT };
+enum KernelKind { KK_PREP = 0, KK_BIAS, KK_PROJ, KK_ATTN, KK_OUT, KK_LAYERNORM, KK_GENERIC, KK_PROBE_MFMA, KK_PROBE_COPY,
+                  KK_COUNT };
 void prof_begin(int kind, hipStream_t st);
 void prof_end(int kind, hipStream_t st);
 // brackets the launches issued in its scope with HIP events when the timer is on

@@ -370,6 +370,17 @@ __global__ __launch_bounds__(512) void k_prep_bias(PrepBiasArgs a) {
     }
 }
 
+// Rows q in [L, Lq) of the bias tensor [H][Lq][Lp] belong to pad queries: no kernel computes them, but
+// the attention kernel stages whole 64-query tiles.  Zeros there keep its lanes for pad queries (never
+// stored) on the common path whatever the caller's workspace held before.
+__global__ __launch_bounds__(256) void k_zero_bias_pad(float* bias, int L, int Lq, int Lp, int H) {
+    const int per_head = (Lq - L) * Lp;
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= per_head * H) return;
+    const int h = i / per_head, r = i - h * per_head;
+    bias[((size_t)h * Lq + L) * Lp + r] = 0.f;
+}
+
 // ====================================================================================
 // GEMM with the whole contraction length (<= 256) resident: a wavefront owns TT 32-token
 // tiles as register-resident operand fragments and sweeps over 32-feature tiles of the
@@ -1405,31 +1416,37 @@ static int gemm_blocks_m(bool proj, int tiles_m, int K) {
     return (tiles_m + per_block - 1) / per_block;
 }
 
+// More than 64 KiB of dynamic LDS has to be asked for once per kernel.  The request is the
+// initialiser of a function-local static: the language runs it exactly once, also when several
+// threads make their first call together, and every caller sees its result.
+template <typename Kernel>
+static hipError_t allow_large_lds(Kernel kernel) {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               96 * 1024);
+}
+
 template <int KC, bool PROJ, int TT, bool RES>
-static void launch_gemm_inst(const GemmArgs& a, dim3 grid, hipStream_t st) {
+static ff_status launch_gemm_inst(const GemmArgs& a, dim3 grid, hipStream_t st) {
     const size_t smem = gemm_smem_bytes(KC, TT, kGemmNS, a.tiles_per_split);
-    static bool attr_set = false;          // more than 64 KiB of dynamic LDS has to be asked for once
-    if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<KC, PROJ, TT, kGemmNS, RES>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
-        attr_set = true;
-    }
+    static const hipError_t attr = allow_large_lds(&k_gemm<KC, PROJ, TT, kGemmNS, RES>);
+    if (attr != hipSuccess) return fail(FF_EHIP, "k_gemm: dynamic LDS limit: %s", hipGetErrorString(attr));
     hipLaunchKernelGGL((k_gemm<KC, PROJ, TT, kGemmNS, RES>), grid, dim3(kGemmWaves * 64), smem, st, a);
+    return FF_OK;
 }
 
 template <bool PROJ, bool RES>
-static void launch_gemm(const GemmArgs& a, int K, dim3 grid, hipStream_t st) {
+static ff_status launch_gemm(const GemmArgs& a, int K, dim3 grid, hipStream_t st) {
     const int kc = K / 16;
     if (gemm_tt(PROJ, K, a.rows * (a.Lp >> 5)) == 1) {
-        if (kc <= 2) launch_gemm_inst<2, PROJ, 1, RES>(a, grid, st);
-        else if (kc <= 4) launch_gemm_inst<4, PROJ, 1, RES>(a, grid, st);
-        else if (kc <= 8) launch_gemm_inst<8, PROJ, 1, RES>(a, grid, st);
-        else launch_gemm_inst<16, PROJ, 1, RES>(a, grid, st);
-    } else {
-        if (kc <= 2) launch_gemm_inst<2, PROJ, 2, RES>(a, grid, st);
-        else if (kc <= 4) launch_gemm_inst<4, PROJ, 2, RES>(a, grid, st);
-        else if constexpr (!PROJ) launch_gemm_inst<8, PROJ, 2, RES>(a, grid, st);
+        if (kc <= 2) return launch_gemm_inst<2, PROJ, 1, RES>(a, grid, st);
+        if (kc <= 4) return launch_gemm_inst<4, PROJ, 1, RES>(a, grid, st);
+        if (kc <= 8) return launch_gemm_inst<8, PROJ, 1, RES>(a, grid, st);
+        return launch_gemm_inst<16, PROJ, 1, RES>(a, grid, st);
     }
+    if (kc <= 2) return launch_gemm_inst<2, PROJ, 2, RES>(a, grid, st);
+    if (kc <= 4) return launch_gemm_inst<4, PROJ, 2, RES>(a, grid, st);
+    if constexpr (!PROJ) return launch_gemm_inst<8, PROJ, 2, RES>(a, grid, st);
+    return fail(FF_EUNSUPPORTED, "k_gemm: no instantiation for K = %d with two token tiles", K);
 }
 
 // blocks along the feature axis: at least one block (eight wavefronts) per compute unit
@@ -1460,43 +1477,45 @@ bool mfma_chunk_ok(const Problem& p, int chunk) {
     return attn_items(p, chunk) < (1 << 22);
 }
 
+static int query_compute_units() {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+        return v;
+    return 256;
+}
+// (queried once; a function-local static is initialised exactly once, also under concurrent first calls)
 static int compute_units() {
-    static int n = 0;
-    if (n == 0) {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
-            n = v;
-        else
-            n = 256;
-    }
+    static const int n = query_compute_units();
     return n;
 }
 
+// blocks of this attention instantiation that one compute unit holds at once
 template <int D, bool HAS_BIAS, int RB, int GK, bool PERSIST>
-static void launch_attn(int n_items, size_t smem, hipStream_t st, const AttnArgs& a) {
-    static bool attr_set = false;          // more than 64 KiB of dynamic LDS has to be asked for once
-    if (!attr_set && smem > 64 * 1024) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn<D, HAS_BIAS, RB, GK, PERSIST>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
-        attr_set = true;
-    }
+static int attn_blocks_per_cu(size_t smem) {
+    int nb = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, reinterpret_cast<const void*>(&k_attn<D, HAS_BIAS, RB, GK, PERSIST>),
+                                                     RB * 64, smem) != hipSuccess || nb < 1)
+        nb = 1;
+    return nb;
+}
+
+template <int D, bool HAS_BIAS, int RB, int GK, bool PERSIST>
+static ff_status launch_attn(int n_items, size_t smem, hipStream_t st, const AttnArgs& a) {
+    // (the LDS of an instantiation is fixed by its template parameters: at most 66 KiB, asked for once)
+    static const hipError_t attr =
+        GK > 64 ? allow_large_lds(&k_attn<D, HAS_BIAS, RB, GK, PERSIST>) : hipSuccess;
+    if (attr != hipSuccess) return fail(FF_EHIP, "k_attn: dynamic LDS limit: %s", hipGetErrorString(attr));
     int n_blocks = n_items;
     if constexpr (PERSIST) {
         // persistent blocks: as many as the chip holds at once (registers and LDS of this
         // instantiation decide how many fit a compute unit), each working through its share of the items
-        static int per_cu = 0;
-        if (per_cu == 0) {
-            int nb = 0;
-            if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, reinterpret_cast<const void*>(&k_attn<D, HAS_BIAS, RB, GK, PERSIST>),
-                                                             RB * 64, smem) != hipSuccess || nb < 1)
-                nb = 1;
-            per_cu = nb;
-        }
+        static const int per_cu = attn_blocks_per_cu<D, HAS_BIAS, RB, GK, PERSIST>(smem);
         const int resident = compute_units() * per_cu;
         if (n_blocks > resident) n_blocks = resident;
     }
     hipLaunchKernelGGL((k_attn<D, HAS_BIAS, RB, GK, PERSIST>), dim3(((n_blocks + 7) / 8) * 8), dim3(RB * 64), smem, st, a);
+    return FF_OK;
 }
 
 static GemmArgs proj_args(const Problem& p, const MfmaWs& m, const Workspace& ws) {
@@ -1558,6 +1577,11 @@ ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x
             hipLaunchKernelGGL(k_prep, dim3((rows + 3) / 4), dim3(256), 0, st, a);
         }
     }
+    if (p.has_bias && Lq > p.L) {
+        const int n = (Lq - p.L) * Lp * p.H;
+        Timed t(KK_PREP, st);
+        hipLaunchKernelGGL(k_zero_bias_pad, dim3((n + 255) / 256), dim3(256), 0, st, ws.bias, p.L, Lq, Lp, p.H);
+    }
     return check_launch("prepare (mfma)");
 }
 
@@ -1577,7 +1601,8 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
         g.ft_first = 0; g.ft_count = g.nt_main + (fused_bias ? 1 : 0);
         g.tiles_per_split = (g.ft_count + split - 1) / split;
         Timed t(KK_PROJ, st);
-        launch_gemm<true, false>(g, p.c, dim3(blocks_m, split), st);
+        const ff_status ls = launch_gemm<true, false>(g, p.c, dim3(blocks_m, split), st);
+        if (ls != FF_OK) return ls;
     }
 
     AttnArgs a{};
@@ -1586,6 +1611,7 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
     a.inv_nq = 1.f / (float)(Lp / 64); a.inv_nqh = 1.f / (float)((Lp / 64) * p.H);
     {
         Timed t(KK_ATTN, st);
+        ff_status ls = FF_OK;
         const int rb = attn_rows_per_block(p, rows);
         const int n_items = (int)attn_items(p, rows);          // < 2^22: mfma_chunk_ok
         // keys per bias tile: 128 halve the barriers of long sequences, 64 keep the first tile of short ones small
@@ -1596,12 +1622,12 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
         const size_t bias_bytes = (size_t)2 * 64 * (gk + kBiasPad) * 4;   // two float tiles
 #define FF_ATTN3(DD, HB, RBV, GKV, SM)                                       \
     do {                                                                     \
-        if (persist) launch_attn<DD, HB, RBV, GKV, true>(n_items, SM, st, a);   \
-        else launch_attn<DD, HB, RBV, GKV, false>(n_items, SM, st, a);          \
+        if (persist) ls = launch_attn<DD, HB, RBV, GKV, true>(n_items, SM, st, a);   \
+        else ls = launch_attn<DD, HB, RBV, GKV, false>(n_items, SM, st, a);          \
     } while (0)
 #define FF_ATTN2(DD, RBV)                                                   \
     do {                                                                    \
-        if (p.has_bias && gk == 128) launch_attn<DD, true, 8, 128, false>(n_items, bias_bytes, st, a); \
+        if (p.has_bias && gk == 128) ls = launch_attn<DD, true, 8, 128, false>(n_items, bias_bytes, st, a); \
         else if (p.has_bias) FF_ATTN3(DD, true, RBV, 64, bias_bytes);                        \
         else FF_ATTN3(DD, false, RBV, 64, 0);                                                \
     } while (0)
@@ -1616,6 +1642,7 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
 #undef FF_ATTN
 #undef FF_ATTN2
 #undef FF_ATTN3
+        if (ls != FF_OK) return ls;
     }
 
     GemmArgs o{};
@@ -1630,8 +1657,9 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
         o.tiles_per_split = tiles_n / split;
         Timed t(KK_OUT, st);
         o.res = (const bf16_t*)res;
-        if (res) launch_gemm<false, true>(o, p.Hd, dim3(blocks_o, split), st);
-        else launch_gemm<false, false>(o, p.Hd, dim3(blocks_o, split), st);
+        const ff_status ls = res ? launch_gemm<false, true>(o, p.Hd, dim3(blocks_o, split), st)
+                                 : launch_gemm<false, false>(o, p.Hd, dim3(blocks_o, split), st);
+        if (ls != FF_OK) return ls;
     }
     return check_launch("attention chunk (mfma)");
 }

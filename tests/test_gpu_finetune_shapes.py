@@ -34,6 +34,7 @@ def test_fine_tuning_shapes(name, rows):
     desc = P.AttnDesc(sp.mode, P.FF_BF16, sp.n_a, sp.n_b, sp.c, sp.c_z, sp.heads, sp.head_dim, sp.ln_eps)
     assert P.ff_attention_path(desc) == "mfma_bf16"
     got = to_np(run_case(case))
+    assert P.ff_attention_last_path() == "mfma_bf16"
     check(sampled(got, sp.mode, rows), oracle_case(case, rows=rows), "bf16", name)
     # chunked (a ragged last chunk) reproduces the bits
     assert torch.equal(run_case(case, chunk_rows=100), run_case(case))
@@ -41,8 +42,10 @@ def test_fine_tuning_shapes(name, rows):
 
 def test_extra_msa_column_attention_5120_sequences():
     """160 key tiles of 32 per column, head dim 8, the last 512 sequences padding; the oracle
-    materialises the 5120 x 5120 scores of each head for two columns."""
+    materialises the 5120 x 5120 scores of each head for six columns: both sides of a boundary
+    between the attention kernel's 4-row blocks, the first and last column, two in the middle at
+    other positions inside their blocks."""
     case = I.make_case("ft_col_bf16_extra_5120")
     got = to_np(run_case(case))
-    rows = [1, 382]
+    rows = [0, 3, 4, 190, 257, 383]
     check(sampled(got, COL, rows), oracle_case(case, rows=rows), "bf16", "extra MSA, 5120 sequences")

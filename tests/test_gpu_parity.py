@@ -45,6 +45,14 @@ def run_case(case, chunk_rows=None):
     return out
 
 
+def spread(n, count, step, first=3):
+    """count indices below n, `step` apart modulo n (step coprime to n and odd, so that the sample
+    walks through every residue modulo 8 and 64: every wavefront slot of a block, odd and even
+    blocks, first and last rows of a chunk)."""
+    assert np.gcd(step, n) == 1
+    return sorted({(first + step * k) % n for k in range(count)})
+
+
 def oracle_case(case, rows=None):
     x, z, m, w = f64_inputs(case)
     sp = case.spec
@@ -127,25 +135,38 @@ def test_config3_end_equals_transposed_start_on_gpu():
 
 def test_config4_column_bf16_extra_msa():
     """All 384 residue columns run on the GPU; the oracle (about 0.4 s per column on the host)
-    evaluates every 8th one, which covers every 64-key tile and the padded tail."""
+    evaluates 96 of them, 37 apart modulo 384: every position inside the attention kernel's 4-row
+    blocks, odd and even blocks, the first and the last column."""
     case = I.make_case("c4_col_bf16_extra")
     got = to_np(run_case(case))
-    rows = list(range(3, 384, 8))
+    assert P.ff_attention_last_path() == "mfma_bf16"
+    rows = sorted(set(spread(384, 94, 37)) | {0, 383})
+    assert {r % 8 for r in rows} == set(range(8))
     ref = oracle_case(case, rows=rows)                       # [len(rows), L, c]
     check(got[:, rows].transpose(1, 0, 2), ref, "bf16", "config4 sampled columns")
 
 
 def test_config5_long_sequence_chunked_sampled_rows():
     """N_res = 2048 triangle-start, chunk = 64 rows, in the launch configuration the benchmark
-    times.  The oracle evaluates 32 batch rows (one in every chunk) exactly: a batch row
-    depends only on its own tokens plus the bias, which the oracle builds from all of x."""
+    times.  The oracle evaluates 256 batch rows exactly (a batch row depends only on its own
+    tokens plus the bias, which the oracle builds from all of x): eight in every chunk, at every
+    position modulo 8 (the wavefront slots of the attention kernel's 8-row blocks) and modulo 64
+    (first and last rows of chunks included).  Every one of the 2048 rows is then compared, bit
+    for bit, with the unchunked call."""
     case = I.make_case("c5_tri_start_bf16_2048")
     desc, w, x, z, mask = P.to_device(case, DEV)
     free0 = torch.cuda.mem_get_info()[0]
     out = P.ff_attention_chunked(desc, w, x, None, None, chunk_rows=64)
     torch.cuda.synchronize()
+    assert P.ff_attention_last_path() == "mfma_bf16"
     assert P.ff_attention_workspace_bytes(desc, 64) < 1 << 30
-    rows = list(range(5, 2048, 64))
+    whole = P.ff_gated_attention(desc, w, x, None, None)       # workspace 5.4 GiB: q, k, v, gate, context of all rows
+    torch.cuda.synchronize()
+    assert torch.equal(out, whole)
+    del whole
+    rows = sorted(set(spread(2048, 254, 265, first=5)) | {0, 2047})
+    assert {r % 8 for r in rows} == set(range(8)) and {r // 64 for r in rows} == set(range(32))
+    assert any(r % 64 == 0 for r in rows) and any(r % 64 == 63 for r in rows)
     got = to_np(out[rows])
     del out
     xw = case.widened("x")
@@ -205,6 +226,22 @@ def test_bf16_configs_run_on_the_matrix_core_family(name):
     sp = I.SPECS[name]
     desc = P.AttnDesc(sp.mode, P.FF_BF16, sp.n_a, sp.n_b, sp.c, sp.c_z, sp.heads, sp.head_dim, sp.ln_eps)
     assert P.ff_attention_path(desc) == "mfma_bf16"
+
+
+def test_last_path_reports_the_family_that_really_ran():
+    """The shape alone allows the matrix-core family; a weight view that is not 16-byte aligned
+    sends the call to the float32 vector family, and the library says so."""
+    case = I.make_case(small_spec(COL, 40, 6, 64, 4, 16, dtype="bf16", mask="tail:3"))
+    desc, w, x, z, mask = P.to_device(case, DEV)
+    a = P.ff_gated_attention(desc, w, x, z, mask)
+    assert P.ff_attention_last_path() == "mfma_bf16"
+    shifted = torch.empty(w["b_o"].numel() + 1, dtype=w["b_o"].dtype, device=DEV)
+    shifted[1:] = w["b_o"]
+    w2 = dict(w, b_o=shifted[1:])
+    b = P.ff_gated_attention(desc, w2, x, z, mask)
+    torch.cuda.synchronize()
+    assert P.ff_attention_path(desc) == "mfma_bf16" and P.ff_attention_last_path() == "generic"
+    check(to_np(b), to_np(a), "bf16", "generic family against matrix-core family")
 
 
 def test_long_ragged_sequence_column_mode():
