@@ -259,3 +259,86 @@ def make_case(spec_or_name, seed: int = SEED) -> Case:
     w["w_o"] = gen("w_o", (c, hd), hd ** -0.5)
     w["b_o"] = gen("b_o", (c,), 0.1)
     return Case(spec, x, z, make_mask(spec, seed), w)
+
+
+# --------------------------------------------------------------------------- triangular multiplicative update
+TRIMUL_WEIGHTS = ("ln_g", "ln_b", "w_ap", "b_ap", "w_ag", "b_ag", "w_bp", "b_bp", "w_bg", "b_bg", "w_g", "b_g",
+                  "lno_g", "lno_b", "w_o", "b_o")
+
+
+@dataclass(frozen=True)
+class TriMulSpec:
+    """Pair-stack triangular multiplicative update (Section 2.3, Figure 3): z is [n, n, c_z],
+    the left/right projections have c channels.  mask as in CaseSpec ("none" | "outer:P" | "random:P")."""
+    name: str
+    dtype: str
+    n: int
+    c_z: int
+    c: int
+    incoming: bool
+    mask: str = "none"
+    ln_eps: float = 1e-5
+    stream: str = ""
+
+    @property
+    def stream_name(self):
+        return self.stream or self.name
+
+
+@dataclass
+class TriMulCase:
+    spec: TriMulSpec
+    z: np.ndarray
+    mask: Optional[np.ndarray]
+    weights: Dict[str, np.ndarray] = field(default_factory=dict)
+
+    def widened_weights(self) -> Dict[str, np.ndarray]:
+        return {k: widen(v) for k, v in self.weights.items()}
+
+
+# Pair-stack shapes of the paper (Table 1: N_res 256 initial training, 384 fine-tuning; Table 2: pair
+# hidden 128) and the long-sequence inference length of Section 6.2.
+TRIMUL_SPECS = {
+    "tm_out_bf16_256": TriMulSpec("tm_out_bf16_256", "bf16", 256, 128, 128, False, "outer:0.95", stream="tm_bf16_256"),
+    "tm_in_bf16_256": TriMulSpec("tm_in_bf16_256", "bf16", 256, 128, 128, True, "outer:0.95", stream="tm_bf16_256"),
+    "tm_out_bf16_384": TriMulSpec("tm_out_bf16_384", "bf16", 384, 128, 128, False, "outer:0.95", stream="tm_bf16_384"),
+    "tm_in_bf16_384": TriMulSpec("tm_in_bf16_384", "bf16", 384, 128, 128, True, "outer:0.95", stream="tm_bf16_384"),
+    "tm_out_bf16_2048": TriMulSpec("tm_out_bf16_2048", "bf16", 2048, 128, 128, False, "none"),
+}
+
+
+def make_trimul_case(spec_or_name, seed: int = SEED) -> TriMulCase:
+    """Activations N(0,1); weights N(0, 1/fan_in); gate biases 1; other biases 0.1 N(0,1); LayerNorm gains
+    1 + 0.1 N(0,1), offsets 0.1 N(0,1)."""
+    spec = TRIMUL_SPECS[spec_or_name] if isinstance(spec_or_name, str) else spec_or_name
+
+    def gen(name, shape, scale=1.0, shift=0.0):
+        v = normal(stream_key(seed, spec.stream_name, name), int(np.prod(shape)))
+        return to_storage(v * scale + shift, spec.dtype).reshape(shape)
+
+    cz, c, n = spec.c_z, spec.c, spec.n
+    w: Dict[str, np.ndarray] = {}
+    w["ln_g"] = gen("ln_g", (cz,), 0.1, 1.0)
+    w["ln_b"] = gen("ln_b", (cz,), 0.1)
+    for side in ("a", "b"):
+        w[f"w_{side}p"] = gen(f"w_{side}p", (c, cz), cz ** -0.5)
+        w[f"b_{side}p"] = gen(f"b_{side}p", (c,), 0.1)
+        w[f"w_{side}g"] = gen(f"w_{side}g", (c, cz), cz ** -0.5)
+        w[f"b_{side}g"] = to_storage(np.ones(c), spec.dtype)
+    w["w_g"] = gen("w_g", (cz, cz), cz ** -0.5)
+    w["b_g"] = to_storage(np.ones(cz), spec.dtype)
+    w["lno_g"] = gen("lno_g", (c,), 0.1, 1.0)
+    w["lno_b"] = gen("lno_b", (c,), 0.1)
+    w["w_o"] = gen("w_o", (cz, c), c ** -0.5)
+    w["b_o"] = gen("b_o", (cz,), 0.1)
+    z = gen("z", (n, n, cz))
+    kind, _, arg = spec.mask.partition(":")
+    mask = None
+    if kind == "outer":
+        r = bernoulli(stream_key(seed, spec.stream_name, "mask"), n, float(arg))
+        mask = np.outer(r, r).astype(np.float32)
+    elif kind == "random":
+        mask = bernoulli(stream_key(seed, spec.stream_name, "mask"), n * n, float(arg)).reshape(n, n)
+    elif kind != "none":
+        raise ValueError(spec.mask)
+    return TriMulCase(spec, z, mask, w)
