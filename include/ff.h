@@ -142,6 +142,28 @@ ff_status ff_gated_attention_residual(const ff_attn_desc* desc, const ff_attn_we
                                       void* out, void* ws, size_t ws_bytes, void* hip_stream,
                                       int32_t chunk_rows);
 
+/* For callers that cannot allocate: code under HIP graph capture, tight serving loops and
+ * harnesses that forbid hipMalloc, which therefore have no workspace to hand over.
+ * The same module as ff_attention_chunked, with the workspace taken from a device array that is
+ * part of the library's own code object (ff_static_scratch_bytes() bytes, 48 MiB; every GPU
+ * the library runs on holds its copy until the process ends) and chunk_rows chosen as the
+ * largest number of batch rows whose workspace fits that array.  The call allocates and
+ * frees nothing and synchronises nothing; the result is bit-identical to ff_gated_attention.
+ * x, z, mask, out as for ff_gated_attention.
+ * Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU
+ * (different streams, different threads) race and give undefined results; calls on one
+ * stream, or ordered by events, are safe.  Nothing in the array has to survive from call to
+ * call and nothing in it is assumed zero.
+ * Errors as for ff_attention_chunked, and FF_EWORKSPACE if even one batch row of this shape
+ * needs more than the array holds (the message gives both sizes), FF_EHIP if the array's
+ * device address cannot be looked up. */
+ff_status ff_gated_attention_static(const ff_attn_desc* desc, const ff_attn_weights* w,
+                                    const void* x, const void* z, const float* mask,
+                                    void* out, void* hip_stream);
+
+/* Size in bytes of the library's own device array used by ff_gated_attention_static. */
+size_t ff_static_scratch_bytes(void);
+
 /* Name of the kernel family the SHAPE allows: "mfma_bf16" (matrix-core path) or "generic"
  * (float32 vector path).  NULL if desc is invalid.  A call takes the matrix-core family only
  * if, in addition, x, z, out and every weight pointer are 16-byte aligned and the chunk has

@@ -61,6 +61,11 @@ def lib() -> C.CDLL:
         L.ff_attention_chunked.argtypes = common + [C.c_int32]
         L.ff_gated_attention_residual.restype = C.c_int
         L.ff_gated_attention_residual.argtypes = common + [C.c_int32]
+        L.ff_gated_attention_static.restype = C.c_int
+        L.ff_gated_attention_static.argtypes = [C.POINTER(AttnDesc), C.POINTER(AttnWeights), C.c_void_p, C.c_void_p,
+                                                C.c_void_p, C.c_void_p, C.c_void_p]
+        L.ff_static_scratch_bytes.restype = C.c_size_t
+        L.ff_static_scratch_bytes.argtypes = []
         L.ff_attention_path.restype = C.c_char_p
         L.ff_attention_path.argtypes = [C.POINTER(AttnDesc)]
         L.ff_attention_last_path.restype = C.c_char_p
@@ -189,6 +194,23 @@ def ff_attention_chunked(desc: AttnDesc, w: Dict[str, "object"], x, z=None, mask
     _check(lib().ff_attention_chunked(C.byref(desc), C.byref(wts), _ptr(x), _ptr(z), _ptr(mask), _ptr(out), _ptr(ws),
                                       ws.numel(), _stream(), chunk_rows))
     return out
+
+
+def ff_gated_attention_static(desc: AttnDesc, w: Dict[str, "object"], x, z=None, mask=None, out=None):
+    """The module with the library's own device array as workspace: the call itself allocates
+    nothing (pass `out`, or this wrapper allocates the result tensor before the call)."""
+    import torch
+    assert x.is_cuda and x.is_contiguous()
+    if out is None:
+        out = torch.empty_like(x)
+    wts = make_weights(w)
+    _check(lib().ff_gated_attention_static(C.byref(desc), C.byref(wts), _ptr(x), _ptr(z), _ptr(mask), _ptr(out),
+                                           _stream()))
+    return out
+
+
+def ff_static_scratch_bytes() -> int:
+    return lib().ff_static_scratch_bytes()
 
 
 def ff_gated_attention_residual(desc: AttnDesc, w: Dict[str, "object"], x, z=None, mask=None, chunk_rows: int = 0,

@@ -184,6 +184,47 @@ static ff_status run(const ff_attn_desc* desc, const ff_attn_weights* w, const v
     return FF_OK;
 }
 
+// ---- device memory of the library's own, for callers that cannot hand over a workspace -------
+// ff_gated_attention_static runs the chunked path with this array as its workspace.  Every GPU the
+// library runs on holds its own copy until the process ends.  In host code the array's name is only
+// a handle for hipGetSymbolAddress: the device address is looked up once per device (with that
+// device current) and used everywhere after that.
+constexpr size_t kScratchBytes = (size_t)48 << 20;
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mu;
+static void* g_scratch_ptr[kMaxDevices] = {};
+
+static ff_status scratch_of_current_device(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(FF_EHIP, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(FF_EUNSUPPORTED, "device index %d beyond %d", dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr)
+            return fail(FF_EHIP, "hipGetSymbolAddress(scratch) on device %d: %s", dev, hipGetErrorString(e));
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return FF_OK;
+}
+
+// largest chunk (batch rows per launch sequence) whose workspace fits `limit` bytes; 0 if not even one row does
+static int largest_chunk_within(const Problem& p, size_t limit) {
+    if (workspace_need(p, 1) > limit) return 0;
+    int lo = 1, hi = p.R;                      // workspace_need grows with the chunk
+    while (lo < hi) {
+        const int mid = lo + (hi - lo + 1) / 2;
+        if (workspace_need(p, mid) <= limit) lo = mid;
+        else hi = mid - 1;
+    }
+    return lo;
+}
+
 }  // namespace ff
 
 using namespace ff;
@@ -229,6 +270,23 @@ ff_status ff_gated_attention_residual(const ff_attn_desc* desc, const ff_attn_we
     if (chunk_rows < 0) return fail(FF_EINVAL, "chunk_rows must be >= 0 (got %d)", chunk_rows);
     return run(desc, w, x, z, mask, out, ws, ws_bytes, hip_stream, chunk_rows, chunk_rows > 0, true);
 }
+
+ff_status ff_gated_attention_static(const ff_attn_desc* desc, const ff_attn_weights* w, const void* x, const void* z,
+                                    const float* mask, void* out, void* hip_stream) {
+    Problem p;
+    ff_status st = make_problem(desc, &p);
+    if (st != FF_OK) return st;
+    const int chunk = largest_chunk_within(p, kScratchBytes);
+    if (chunk < 1)
+        return fail(FF_EWORKSPACE, "shape too large for the static scratch: one batch row needs %zu bytes, %zu available",
+                    workspace_need(p, 1), kScratchBytes);
+    void* ptr = nullptr;
+    st = scratch_of_current_device(&ptr);
+    if (st != FF_OK) return st;
+    return run(desc, w, x, z, mask, out, ptr, kScratchBytes, hip_stream, chunk, true);
+}
+
+size_t ff_static_scratch_bytes(void) { return kScratchBytes; }
 
 const char* ff_attention_path(const ff_attn_desc* desc) {
     Problem p;
