@@ -142,6 +142,53 @@ ff_status ff_gated_attention_residual(const ff_attn_desc* desc, const ff_attn_we
                                       void* out, void* ws, size_t ws_bytes, void* hip_stream,
                                       int32_t chunk_rows);
 
+/* Triangular multiplicative update of the pair representation (Section 2.3 and Figure 3: the pair
+ * stack's "triangular updates module"; Section 5.2 merges its left and right projections and their
+ * gates into one GEMM; Section 4.2 / Table 3 name its outgoing and incoming forms).  With
+ * zn = LayerNorm_in(z):
+ *   a = mask * sigmoid(zn w_ag^T + b_ag) * (zn w_ap^T + b_ap)     left,  [n, n, c]
+ *   b = mask * sigmoid(zn w_bg^T + b_bg) * (zn w_bp^T + b_bp)     right, [n, n, c]
+ *   g = sigmoid(zn w_g^T + b_g)                                          [n, n, c_z]
+ *   incoming = 0:  t[i,j,:] = sum_k a[i,k,:] * b[j,k,:]       incoming = 1:  t[i,j,:] = sum_k a[k,i,:] * b[k,j,:]
+ *   out = g * (LayerNorm_out(t) w_o^T + b_o)                  (+ z if residual = 1)
+ * LayerNorms: biased variance, eps inside the root.  a, b and t are rounded to bfloat16 between
+ * the kernels; g, statistics and accumulations are float32. */
+typedef struct {
+    int32_t dtype;      /* ff_dtype; FF_BF16 only (FF_F32 -> FF_EUNSUPPORTED) */
+    int32_t incoming;   /* 0 = outgoing edges, 1 = incoming edges */
+    int32_t n;          /* z and out are [n, n, c_z] */
+    int32_t c_z;        /* channels of the pair representation: multiple of 32, <= 128 */
+    int32_t c;          /* channels of the left / right projections: multiple of 32, <= 128 */
+    float   ln_eps;
+} ff_trimul_desc;
+
+/* Weights [out, in] row-major, all with an additive bias, dtype = desc.dtype. */
+typedef struct {
+    const void *ln_g, *ln_b;      /* [c_z]  LayerNorm_in                   */
+    const void *w_ap, *b_ap;      /* [c, c_z], [c]   left projection       */
+    const void *w_ag, *b_ag;      /* [c, c_z], [c]   left gate             */
+    const void *w_bp, *b_bp;      /* [c, c_z], [c]   right projection      */
+    const void *w_bg, *b_bg;      /* [c, c_z], [c]   right gate            */
+    const void *w_g, *b_g;        /* [c_z, c_z], [c_z]  output gate        */
+    const void *lno_g, *lno_b;    /* [c]    LayerNorm_out                  */
+    const void *w_o, *b_o;        /* [c_z, c], [c_z] output projection     */
+} ff_trimul_weights;
+
+/* Bytes of device workspace ff_triangle_multiplication needs (a, b and t channel-major, the
+ * prepared weights); 0 if desc is invalid or unsupported (ff_last_error says why). */
+size_t ff_triangle_multiplication_workspace_bytes(const ff_trimul_desc* desc);
+
+/*   z    [n, n, c_z] pair representation, 16-byte aligned
+ *   mask [n, n] float32 of 0/1 or NULL (= all ones): multiplies a and b, so a masked pair takes
+ *        part in no sum over k; its own output position is still computed
+ *   out  [n, n, c_z]; with residual = 1 it may be z itself (in-place update), otherwise it must
+ *        not overlap z; never the workspace
+ *   ws, ws_bytes  device scratch, 256-byte aligned, at least the size reported above
+ * Returns FF_EINVAL / FF_EUNSUPPORTED / FF_EWORKSPACE / FF_EHIP as the attention entry points do. */
+ff_status ff_triangle_multiplication(const ff_trimul_desc* desc, const ff_trimul_weights* w,
+                                     const void* z, const float* mask, void* out, int32_t residual,
+                                     void* ws, size_t ws_bytes, void* hip_stream);
+
 /* For callers that cannot allocate: code under HIP graph capture, tight serving loops and
  * harnesses that forbid hipMalloc, which therefore have no workspace to hand over.
  * The same module as ff_attention_chunked, with the workspace taken from a device array that is

@@ -30,6 +30,19 @@ class AttnWeights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in WEIGHT_FIELDS]
 
 
+TRIMUL_FIELDS = ("ln_g", "ln_b", "w_ap", "b_ap", "w_ag", "b_ag", "w_bp", "b_bp", "w_bg", "b_bg", "w_g", "b_g",
+                 "lno_g", "lno_b", "w_o", "b_o")
+
+
+class TriMulDesc(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("incoming", C.c_int32), ("n", C.c_int32), ("c_z", C.c_int32), ("c", C.c_int32),
+                ("ln_eps", C.c_float)]
+
+
+class TriMulWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in TRIMUL_FIELDS]
+
+
 class FFError(RuntimeError):
     def __init__(self, status: int, message: str):
         super().__init__(f"libff status {status}: {message}")
@@ -66,6 +79,11 @@ def lib() -> C.CDLL:
                                                 C.c_void_p, C.c_void_p, C.c_void_p]
         L.ff_static_scratch_bytes.restype = C.c_size_t
         L.ff_static_scratch_bytes.argtypes = []
+        L.ff_triangle_multiplication_workspace_bytes.restype = C.c_size_t
+        L.ff_triangle_multiplication_workspace_bytes.argtypes = [C.POINTER(TriMulDesc)]
+        L.ff_triangle_multiplication.restype = C.c_int
+        L.ff_triangle_multiplication.argtypes = [C.POINTER(TriMulDesc), C.POINTER(TriMulWeights), C.c_void_p, C.c_void_p,
+                                                 C.c_void_p, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
         L.ff_attention_path.restype = C.c_char_p
         L.ff_attention_path.argtypes = [C.POINTER(AttnDesc)]
         L.ff_attention_last_path.restype = C.c_char_p
@@ -213,6 +231,34 @@ def ff_static_scratch_bytes() -> int:
     return lib().ff_static_scratch_bytes()
 
 
+def ff_triangle_multiplication_workspace_bytes(desc: TriMulDesc) -> int:
+    n = lib().ff_triangle_multiplication_workspace_bytes(C.byref(desc))
+    if n == 0:
+        raise FFError(FF_EINVAL, last_error())
+    return n
+
+
+def ff_triangle_multiplication(desc: TriMulDesc, w: Dict[str, "object"], z, mask=None, residual: bool = False,
+                               out=None, ws=None, in_place: bool = False):
+    """Triangular multiplicative update of the pair representation z [n, n, c_z]; returns out."""
+    import torch
+    assert z.is_cuda and z.is_contiguous()
+    if in_place:
+        out = z
+    elif out is None:
+        out = torch.empty_like(z)
+    if ws is None:
+        ws = _alloc_ws(ff_triangle_multiplication_workspace_bytes(desc), z.device)
+    wts = TriMulWeights()
+    for n in TRIMUL_FIELDS:
+        t = w[n]
+        assert t.is_contiguous() and t.is_cuda
+        setattr(wts, n, _ptr(t))
+    _check(lib().ff_triangle_multiplication(C.byref(desc), C.byref(wts), _ptr(z), _ptr(mask), _ptr(out),
+                                            1 if residual else 0, _ptr(ws), ws.numel(), _stream()))
+    return out
+
+
 def ff_gated_attention_residual(desc: AttnDesc, w: Dict[str, "object"], x, z=None, mask=None, chunk_rows: int = 0,
                                 out=None, ws=None, in_place: bool = False):
     """x + module(x); chunk_rows = 0 takes all batch rows at once.  in_place=True updates x itself."""
@@ -259,6 +305,23 @@ def ff_probe_copy(dst, src):
 
 
 # ------------------------------------------------------------------------- test/bench glue
+def _upload(a, device):
+    import numpy as np
+    import torch
+    if a is None:
+        return None
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(a).to(device)
+
+
+def trimul_to_device(case, device="cuda:0"):
+    """Upload a seeded triangular-update case (inputs.TriMulCase).  Returns (desc, weights, z, mask)."""
+    sp = case.spec
+    desc = TriMulDesc(FF_F32 if sp.dtype == "f32" else FF_BF16, 1 if sp.incoming else 0, sp.n, sp.c_z, sp.c, sp.ln_eps)
+    return desc, {k: _upload(v, device) for k, v in case.weights.items()}, _upload(case.z, device), _upload(case.mask, device)
+
+
 def to_device(case, device="cuda:0"):
     """Upload a seeded case (paper_2203_00854_amd.inputs.Case) as torch tensors.
     Returns (desc, weights, x, z, mask)."""

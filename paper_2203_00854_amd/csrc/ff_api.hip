@@ -19,7 +19,7 @@ static std::vector<ProfRec> g_prof;
 static std::vector<hipEvent_t> g_prof_pool;
 static const char* kKindNames[KK_COUNT] = {"k_prep", "pair bias pass", "k_gemm<PROJ>", "k_attn",
                                            "k_gemm<OUT>", "k_layernorm", "generic family", "probe: mfma loop",
-                                           "probe: copy"};
+                                           "probe: copy", "k_tm_prep", "k_tm_proj", "k_tm_mul", "k_tm_out"};
 
 static hipEvent_t prof_event() {
     if (!g_prof_pool.empty()) {
@@ -240,6 +240,48 @@ ff_status ff_layernorm(const void* x, const void* gamma, const void* beta, void*
     if (!x || !gamma || !beta || !y) return fail(FF_EINVAL, "NULL pointer");
     Timed t(KK_LAYERNORM, (hipStream_t)hip_stream);
     return layernorm_launch(x, gamma, beta, y, rows, c, eps, dt, (hipStream_t)hip_stream);
+}
+
+static ff_status check_trimul(const ff_trimul_desc* d) {
+    if (!d) return fail(FF_EINVAL, "desc is NULL");
+    if (d->dtype != FF_F32 && d->dtype != FF_BF16) return fail(FF_EINVAL, "bad dtype %d", d->dtype);
+    if (d->n < 1 || d->c_z < 1 || d->c < 1) return fail(FF_EINVAL, "non-positive size (n=%d c_z=%d c=%d)", d->n, d->c_z, d->c);
+    if (d->incoming != 0 && d->incoming != 1) return fail(FF_EINVAL, "incoming must be 0 or 1 (got %d)", d->incoming);
+    if (!(d->ln_eps >= 0.f)) return fail(FF_EINVAL, "ln_eps must be >= 0");
+    if (d->n > 16384) return fail(FF_EUNSUPPORTED, "n %d > 16384", d->n);
+    if (!trimul_supported(d->dtype, d->c_z, d->c))
+        return fail(FF_EUNSUPPORTED, "triangle multiplication: bfloat16 only, c_z and c multiples of 32 up to 128 "
+                                     "(got dtype %d, c_z %d, c %d)", d->dtype, d->c_z, d->c);
+    return FF_OK;
+}
+
+size_t ff_triangle_multiplication_workspace_bytes(const ff_trimul_desc* desc) {
+    if (check_trimul(desc) != FF_OK) return 0;
+    return trimul_workspace(desc->n, desc->c_z, desc->c);
+}
+
+ff_status ff_triangle_multiplication(const ff_trimul_desc* desc, const ff_trimul_weights* w, const void* z,
+                                     const float* mask, void* out, int32_t residual, void* ws, size_t ws_bytes,
+                                     void* hip_stream) {
+    ff_status st = check_trimul(desc);
+    if (st != FF_OK) return st;
+    if (residual != 0 && residual != 1) return fail(FF_EINVAL, "residual must be 0 or 1 (got %d)", residual);
+    if (!w || !z || !out) return fail(FF_EINVAL, "weights, z or out is NULL");
+    const void* wp[] = {w->ln_g, w->ln_b, w->w_ap, w->b_ap, w->w_ag, w->b_ag, w->w_bp, w->b_bp, w->w_bg, w->b_bg,
+                        w->w_g, w->b_g, w->lno_g, w->lno_b, w->w_o, w->b_o};
+    for (const void* q : wp)
+        if (!q) return fail(FF_EINVAL, "a weight pointer is NULL");
+    if (!aligned16(z) || !aligned16(out)) return fail(FF_EINVAL, "z and out must be 16-byte aligned");
+    const size_t z_bytes = (size_t)desc->n * desc->n * desc->c_z * 2;
+    if (overlaps(out, z_bytes, z, z_bytes) && !(residual && out == z))
+        return fail(FF_EINVAL, residual ? "out must be z itself or not overlap z" : "out must not overlap z");
+    const size_t need = trimul_workspace(desc->n, desc->c_z, desc->c);
+    if (!ws) return fail(FF_EINVAL, "workspace is NULL (%zu bytes needed)", need);
+    if (((uintptr_t)ws & 255u) != 0) return fail(FF_EINVAL, "workspace must be 256-byte aligned");
+    if (ws_bytes < need) return fail(FF_EWORKSPACE, "workspace too small: %zu bytes given, %zu needed", ws_bytes, need);
+    if (overlaps(out, z_bytes, ws, need) || overlaps(z, z_bytes, ws, need))
+        return fail(FF_EINVAL, "z and out must not overlap the workspace");
+    return trimul_run(*desc, *w, z, mask, residual != 0, out, ws, (hipStream_t)hip_stream);
 }
 
 size_t ff_attention_workspace_bytes(const ff_attn_desc* desc, int32_t chunk_rows) {

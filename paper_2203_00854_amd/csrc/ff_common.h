@@ -69,7 +69,7 @@ struct Workspace {
 
 // kernel kinds for the launch timer (ff_profile_* in the C ABI)
 enum KernelKind { KK_PREP = 0, KK_BIAS, KK_PROJ, KK_ATTN, KK_OUT, KK_LAYERNORM, KK_GENERIC, KK_PROBE_MFMA, KK_PROBE_COPY,
-                  KK_COUNT };
+                  KK_TM_PREP, KK_TM_PROJ, KK_TM_MUL, KK_TM_OUT, KK_COUNT };
 void prof_begin(int kind, hipStream_t st);
 void prof_end(int kind, hipStream_t st);
 // brackets the launches issued in its scope with HIP events when the timer is on
@@ -107,6 +107,13 @@ ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x
                        const Workspace& ws, hipStream_t stream);
 ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, const float* mask,
                      const void* res, void* out, const Workspace& ws, int r0, int rows, hipStream_t stream);
+
+// triangular multiplicative update (ff_trimul.hip), bf16 matrix-core kernels only
+bool trimul_supported(int dtype, int cz, int c);
+size_t trimul_workspace(int N, int cz, int c);
+// residual: z is added to the module's output (out may then be z itself)
+ff_status trimul_run(const ff_trimul_desc& d, const ff_trimul_weights& w, const void* z, const float* mask, bool residual,
+                     void* out, void* ws, hipStream_t stream);
 
 // LayerNorm (ff_layernorm.hip)
 ff_status layernorm_launch(const void* x, const void* g, const void* b, void* y, int64_t rows, int c,

@@ -1,0 +1,586 @@
+// Triangular multiplicative update of the pair stack (FastFold Section 2.3, Figure 3; the left / right
+// projections and their gates merged into one GEMM as in Section 5.2), bf16, gfx950 matrix cores.
+//
+//   zn = LayerNorm_in(z);  a = mask * sigmoid(zn W_ag^T + b_ag) * (zn W_ap^T + b_ap);  b likewise;
+//   g = sigmoid(zn W_g^T + b_g)
+//   outgoing t[i,j,:] = sum_k a[i,k,:] * b[j,k,:];   incoming t[i,j,:] = sum_k a[k,i,:] * b[k,j,:]
+//   out = g * (LayerNorm_out(t) W_o^T + b_o)   (+ z in the residual form)
+//
+// Four launches per call:
+//   k_tm_prep  folds the LayerNorm gains into the weights: W' = bf16(W * gamma), S = rowsum(W'),
+//              Cn = W beta + bias, so that LN(x) W^T + bias = rstd * (x W'^T - mean * S) + Cn and the
+//              matrix cores read the raw activations
+//   k_tm_proj  one merged GEMM over the 4c features of the left and right side.  A projection tile is
+//              contracted together with its gate tile, so that the lane that holds a projection value
+//              also holds its gate value; a and b leave channel-major, [c][N][Np], which makes every
+//              channel a dense N x N matrix for the next kernel.  The incoming form is the outgoing form
+//              on the transposed view of z (strides), so a[c][i][k] then holds a of pair (k, i).
+//   k_tm_mul   per channel t_c = A_c B_c^T: a batched N x N x N contraction, 128 x 128 tiles through LDS
+//   k_tm_out   LayerNorm over the channels of t (transposed to token-major through LDS), output
+//              projection; the output gate g is computed here, from z, in float32 (it never exists in
+//              memory), then the product and the optional residual
+//
+// Matrix-core operand layouts (wave64, v_mfma_f32_32x32x16_bf16): A (32 x 16): lane l holds row l%32,
+// columns 8*(l/32)..+7; B (16 x 32): lane l holds column l%32, rows 8*(l/32)..+7; D (32 x 32): lane l
+// holds column l%32, register v holds row 8*(v/4) + 4*(l/32) + v%4.
+#include "ff_common.h"
+
+namespace ff {
+namespace tm {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+union Frag {
+    bf16x8 v;
+    uint4 u;
+    uint32_t w[4];
+};
+
+__device__ __forceinline__ uint32_t pack2(float a, float b) {   // a -> low half (first element)
+    bf16x2 t;
+    t[0] = (__bf16)a;
+    t[1] = (__bf16)b;
+    return __builtin_bit_cast(uint32_t, t);
+}
+__device__ __forceinline__ float lo_f32(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float hi_f32(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+__device__ __forceinline__ float sigmoid(float t) {
+    return __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-t * kLog2e));
+}
+__device__ __forceinline__ float pick(const float4& q, int e) { return e == 0 ? q.x : (e == 1 ? q.y : (e == 2 ? q.z : q.w)); }
+
+static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
+
+// LayerNorm statistics of the token whose K channels lie in the fragments of the two lanes (col, hf = 0 | 1):
+// mean and 1 / sqrt(var + eps), float32, two passes over the registers.
+template <int KC>
+__device__ __forceinline__ void token_stats(const Frag (&xa)[KC], int K, int hf, float eps, float& mean, float& rstd) {
+    float sum = 0.f;
+#pragma unroll
+    for (int s = 0; s < KC; ++s)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sum += lo_f32(xa[s].w[i]) + hi_f32(xa[s].w[i]);   // (channels beyond K are zero)
+    sum += __shfl_xor(sum, 32, 64);
+    mean = sum / (float)K;
+    float sq = 0.f;
+#pragma unroll
+    for (int s = 0; s < KC; ++s)
+        if (16 * s + 8 * hf < K) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float d0 = lo_f32(xa[s].w[i]) - mean, d1 = hi_f32(xa[s].w[i]) - mean;
+                sq += d0 * d0 + d1 * d1;
+            }
+        }
+    sq += __shfl_xor(sq, 32, 64);
+    rstd = rsqrtf(sq / (float)K + eps);
+}
+
+// ====================================================================================
+// Weight preparation, one wavefront per output row.
+//   rows [0, 64 * n_pairs): the merged projection in the order k_tm_proj sweeps it.  Pair p < G (G = c / 32):
+//     rows 64p .. +31 = left projection of channels 32p .. +31, rows 64p + 32 .. +63 = their gate;
+//     pairs G .. 2G - 1 the right side.
+//   then the output projection (LayerNorm_out folded in) and the output gate (LayerNorm_in folded in), c_z rows each.
+struct TmPrepArgs {
+    const bf16_t *w_ap, *b_ap, *w_ag, *b_ag, *w_bp, *b_bp, *w_bg, *b_bg, *w_g, *b_g, *ln_g, *ln_b;
+    const bf16_t *w_o, *b_o, *lno_g, *lno_b;
+    bf16_t *wp1, *wp3, *wp4;       // [64 n_pairs][Kp1], [cz][Kp3], [cz][Kp1]
+    float *S1, *C1, *S3, *C3, *S4, *C4;
+    int cz, c, G, n_pairs, Kp1, Kp3;
+};
+
+__global__ __launch_bounds__(256) void k_tm_prep(TmPrepArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int rows1 = 64 * a.n_pairs;
+    if (n >= rows1 + 2 * a.cz) return;
+    const bf16_t *wrow = nullptr, *gamma, *beta;
+    float bias = 0.f;
+    int K, Kp;
+    bf16_t* dst;
+    float *Sd, *Cd;
+    if (n < rows1) {
+        const int p = n >> 6, half = (n >> 5) & 1, j = n & 31;
+        K = a.cz; Kp = a.Kp1; gamma = a.ln_g; beta = a.ln_b;
+        dst = a.wp1 + (size_t)n * Kp; Sd = a.S1 + n; Cd = a.C1 + n;
+        const bool left = p < a.G;
+        const int ch = 32 * (left ? p : p - a.G) + j;
+        const bf16_t* w = left ? (half ? a.w_ag : a.w_ap) : (half ? a.w_bg : a.w_bp);
+        const bf16_t* b = left ? (half ? a.b_ag : a.b_ap) : (half ? a.b_bg : a.b_bp);
+        wrow = w + (size_t)ch * K;
+        bias = bf16_to_f32(b[ch]);
+    } else if (n < rows1 + a.cz) {
+        const int f = n - rows1;
+        K = a.c; Kp = a.Kp3; gamma = a.lno_g; beta = a.lno_b;
+        dst = a.wp3 + (size_t)f * Kp; Sd = a.S3 + f; Cd = a.C3 + f;
+        wrow = a.w_o + (size_t)f * K;
+        bias = bf16_to_f32(a.b_o[f]);
+    } else {
+        const int f = n - rows1 - a.cz;
+        K = a.cz; Kp = a.Kp1; gamma = a.ln_g; beta = a.ln_b;
+        dst = a.wp4 + (size_t)f * Kp; Sd = a.S4 + f; Cd = a.C4 + f;
+        wrow = a.w_g + (size_t)f * K;
+        bias = bf16_to_f32(a.b_g[f]);
+    }
+    float sum = 0.f, cst = 0.f;
+    for (int k = lane; k < Kp; k += 64) {
+        float r = 0.f;
+        if (k < K) {
+            const float w = bf16_to_f32(wrow[k]);
+            r = bf16_to_f32(f32_to_bf16(w * bf16_to_f32(gamma[k])));
+            cst += w * bf16_to_f32(beta[k]);
+        }
+        dst[k] = f32_to_bf16(r);
+        sum += r;
+    }
+    sum = wave_sum(sum);
+    cst = wave_sum(cst);
+    if (lane == 0) {
+        *Sd = sum;
+        *Cd = cst + bias;
+    }
+}
+
+// ====================================================================================
+// Merged projection.  Block = 8 wavefronts, each owning one 32-token tile (tokens of one row of the view)
+// as register-resident operand fragments; the block sweeps the prepared weight matrix 64 rows (a "pair")
+// at a time through a double-buffered LDS image (row pitch padded by 16 bytes: conflict-free operand reads).
+struct TmProjArgs {
+    const bf16_t* z;
+    int64_t sr, sl;          // token (r, l) of the view at z + (r*sr + l*sl) * K; the same index addresses mask
+    const float* mask;       // or NULL
+    int N, Np, K, C, cz, G, n_pairs;
+    float eps;
+    const bf16_t* wp;        // [64 n_pairs][16 KC]
+    const float *S, *Cn;
+    bf16_t *a, *b;           // [C][N][Np]
+};
+
+template <int KC>
+__global__ __launch_bounds__(512) void k_tm_proj(TmProjArgs p) {
+    constexpr int PITCH = KC * 32 + 16;                 // bytes per weight row in LDS
+    constexpr int PIECES = 64 * 2 * KC;                 // 16-byte pieces per pair
+    constexpr int PPT = (PIECES + 511) / 512;           // pieces per thread
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    unsigned char* s_w = smem;                                            // [2][64 * PITCH]
+    float* s_stat = reinterpret_cast<float*>(smem + 2 * 64 * PITCH);      // [8][3][32]: mean, 1/std, mask value
+
+    const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tpr = p.Np >> 5;                          // token tiles per row
+    const int tiles_m = p.N * tpr;
+    int tg = blockIdx.x * 8 + wave;
+    const bool live = tg < tiles_m;                     // (a wavefront without a tile still helps to move the weights)
+    if (!live) tg = tiles_m - 1;
+    const int r = tg / tpr, l0 = (tg - r * tpr) * 32, l = l0 + col;
+    const bool valid = l < p.N;
+    const int64_t tok = (int64_t)r * p.sr + (int64_t)(valid ? l : 0) * p.sl;
+
+    Frag xa[KC];
+    {
+        const bf16_t* zp = p.z + tok * p.K;
+#pragma unroll
+        for (int s = 0; s < KC; ++s) {
+            xa[s].u = make_uint4(0, 0, 0, 0);
+            if (valid && 16 * s + 8 * hf < p.K) xa[s].u = *reinterpret_cast<const uint4*>(zp + 16 * s + 8 * hf);
+        }
+    }
+    const float mval = valid ? (p.mask ? p.mask[tok] : 1.f) : 0.f;
+
+    // weight pieces of this thread
+    int w_src[PPT], w_dst[PPT];
+#pragma unroll
+    for (int n = 0; n < PPT; ++n) {
+        const int id = tid + 512 * n;
+        const int row = id / (2 * KC), pc = id - row * (2 * KC);
+        w_src[n] = id < PIECES ? row * (16 * KC) + pc * 8 : -1;
+        w_dst[n] = row * PITCH + pc * 16;
+    }
+    uint4 wreg[PPT];
+    auto fetch_pair = [&](int pr) {
+        const bf16_t* src = p.wp + (size_t)pr * 64 * (16 * KC);
+#pragma unroll
+        for (int n = 0; n < PPT; ++n)
+            if (w_src[n] >= 0) wreg[n] = *reinterpret_cast<const uint4*>(src + w_src[n]);
+    };
+    auto stash_pair = [&](int buf) {
+#pragma unroll
+        for (int n = 0; n < PPT; ++n)
+            if (w_src[n] >= 0) *reinterpret_cast<uint4*>(s_w + buf * 64 * PITCH + w_dst[n]) = wreg[n];
+    };
+    fetch_pair(0);
+
+    {
+        float mean, rstd;
+        token_stats<KC>(xa, p.K, hf, p.eps, mean, rstd);
+        if (hf == 0) {
+            s_stat[(wave * 3 + 0) * 32 + col] = mean;
+            s_stat[(wave * 3 + 1) * 32 + col] = rstd;
+            s_stat[(wave * 3 + 2) * 32 + col] = mval;
+        }
+    }
+    stash_pair(0);
+    __syncthreads();
+
+    const float* st_mean = s_stat + (wave * 3 + 0) * 32;
+    const float* st_rstd = s_stat + (wave * 3 + 1) * 32;
+    const float* st_mval = s_stat + (wave * 3 + 2) * 32;
+    const size_t plane = (size_t)p.N * p.Np;
+
+    for (int pr = 0; pr < p.n_pairs; ++pr) {
+        const unsigned char* st = s_w + (pr & 1) * 64 * PITCH;
+        if (pr + 1 < p.n_pairs) fetch_pair(pr + 1);
+        f32x16 acc0, acc1;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc0[v] = acc1[v] = 0.f;
+        // tokens x features: the lane owns one channel, its projection in acc0 and its gate in acc1
+        const float Sp = p.S[64 * pr + col], Cp = p.Cn[64 * pr + col];
+        const float Sg = p.S[64 * pr + 32 + col], Cg = p.Cn[64 * pr + 32 + col];
+#pragma unroll
+        for (int s = 0; s < KC; ++s) {
+            Frag w0, w1;
+            w0.u = *reinterpret_cast<const uint4*>(st + col * PITCH + (2 * s + hf) * 16);
+            w1.u = *reinterpret_cast<const uint4*>(st + (32 + col) * PITCH + (2 * s + hf) * 16);
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[s].v, w0.v, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[s].v, w1.v, acc1, 0, 0, 0);
+        }
+        if (pr + 1 < p.n_pairs) stash_pair((pr + 1) & 1);
+        const bool left = pr < p.G;
+        const int ch = 32 * (left ? pr : pr - p.G) + col;
+        bf16_t* dst = (left ? p.a : p.b) + (size_t)ch * plane + (size_t)r * p.Np + l0 + 4 * hf;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const float4 m4 = *reinterpret_cast<const float4*>(st_mean + 8 * g + 4 * hf);
+            const float4 r4 = *reinterpret_cast<const float4*>(st_rstd + 8 * g + 4 * hf);
+            const float4 k4 = *reinterpret_cast<const float4*>(st_mval + 8 * g + 4 * hf);
+            float o[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float mu = pick(m4, e), rs = pick(r4, e);
+                const float tp = rs * (acc0[4 * g + e] - mu * Sp) + Cp;
+                const float tgv = rs * (acc1[4 * g + e] - mu * Sg) + Cg;
+                o[e] = tp * sigmoid(tgv) * pick(k4, e);
+            }
+            if (live) *reinterpret_cast<uint2*>(dst + 8 * g) = make_uint2(pack2(o[0], o[1]), pack2(o[2], o[3]));
+        }
+        __syncthreads();
+    }
+}
+
+// ====================================================================================
+// t_c[i][j] = sum_k A_c[i][k] B_c[j][k] for every channel c: block = 4 wavefronts (2 x 2), block tile
+// 128 x 128, wavefront tile 64 x 64, the contraction in chunks of 32 through double-buffered LDS.
+// Blocks are handed to the 8 XCDs round-robin; channel c goes to XCD c % 8 with all of its tiles, so a
+// channel's operands live in one L2.
+struct TmMulArgs {
+    const bf16_t *a, *b;     // [C][N][Np]
+    bf16_t* x;               // [C][N][Np]
+    int N, Np, C, tiles;     // tiles per side
+};
+
+__global__ __launch_bounds__(256) void k_tm_mul(TmMulArgs p) {
+    constexpr int PITCH = 80;                           // bytes per 32-element row in LDS (64 + 16 padding)
+    constexpr int STAGE = 128 * PITCH;
+    __shared__ __attribute__((aligned(16))) unsigned char s_a[2 * STAGE];
+    __shared__ __attribute__((aligned(16))) unsigned char s_b[2 * STAGE];
+    const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wi = wave >> 1, wj = wave & 1;
+    const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3, t2 = p.tiles * p.tiles;
+    const int ch = (idx / t2) * 8 + xcd, tile = idx % t2;
+    if (ch >= p.C) return;                              // (whole block)
+    const int i0 = (tile / p.tiles) * 128, j0 = (tile % p.tiles) * 128;
+    const size_t plane = (size_t)p.N * p.Np;
+    const bf16_t* ac = p.a + (size_t)ch * plane;
+    const bf16_t* bc = p.b + (size_t)ch * plane;
+
+    // this thread's two pieces of each operand chunk: rows tid/4 and tid/4 + 64, piece tid%4
+    const int prow = tid >> 2, pc = tid & 3;
+    const bool a_ok0 = i0 + prow < p.N, a_ok1 = i0 + prow + 64 < p.N;
+    const bool b_ok0 = j0 + prow < p.N, b_ok1 = j0 + prow + 64 < p.N;
+    const bf16_t* ap0 = ac + (size_t)(a_ok0 ? i0 + prow : 0) * p.Np + pc * 8;
+    const bf16_t* ap1 = ac + (size_t)(a_ok1 ? i0 + prow + 64 : 0) * p.Np + pc * 8;
+    const bf16_t* bp0 = bc + (size_t)(b_ok0 ? j0 + prow : 0) * p.Np + pc * 8;
+    const bf16_t* bp1 = bc + (size_t)(b_ok1 ? j0 + prow + 64 : 0) * p.Np + pc * 8;
+    const int sdst0 = prow * PITCH + pc * 16, sdst1 = (prow + 64) * PITCH + pc * 16;
+    const uint4 zero4 = make_uint4(0, 0, 0, 0);
+    uint4 ra0, ra1, rb0, rb1;
+    auto fetch = [&](int kc) {
+        const int k0 = kc * 32;
+        ra0 = a_ok0 ? *reinterpret_cast<const uint4*>(ap0 + k0) : zero4;
+        ra1 = a_ok1 ? *reinterpret_cast<const uint4*>(ap1 + k0) : zero4;
+        rb0 = b_ok0 ? *reinterpret_cast<const uint4*>(bp0 + k0) : zero4;
+        rb1 = b_ok1 ? *reinterpret_cast<const uint4*>(bp1 + k0) : zero4;
+    };
+    auto stash = [&](int buf) {
+        *reinterpret_cast<uint4*>(s_a + buf * STAGE + sdst0) = ra0;
+        *reinterpret_cast<uint4*>(s_a + buf * STAGE + sdst1) = ra1;
+        *reinterpret_cast<uint4*>(s_b + buf * STAGE + sdst0) = rb0;
+        *reinterpret_cast<uint4*>(s_b + buf * STAGE + sdst1) = rb1;
+    };
+
+    f32x16 acc[2][2];     // [j tile][i tile]: lane = i, registers = j
+#pragma unroll
+    for (int tj = 0; tj < 2; ++tj)
+#pragma unroll
+        for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[tj][ti][v] = 0.f;
+
+    const int nk = p.Np >> 5;
+    fetch(0);
+    stash(0);
+    __syncthreads();
+    for (int kc = 0; kc < nk; ++kc) {
+        if (kc + 1 < nk) fetch(kc + 1);
+        const unsigned char* sa = s_a + (kc & 1) * STAGE + (wi * 64 + col) * PITCH + hf * 16;
+        const unsigned char* sb = s_b + (kc & 1) * STAGE + (wj * 64 + col) * PITCH + hf * 16;
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            Frag af[2], bf[2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                af[t].u = *reinterpret_cast<const uint4*>(sa + t * 32 * PITCH + kk * 32);
+                bf[t].u = *reinterpret_cast<const uint4*>(sb + t * 32 * PITCH + kk * 32);
+            }
+#pragma unroll
+            for (int tj = 0; tj < 2; ++tj)
+#pragma unroll
+                for (int ti = 0; ti < 2; ++ti)
+                    acc[tj][ti] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[tj].v, af[ti].v, acc[tj][ti], 0, 0, 0);
+        }
+        if (kc + 1 < nk) stash((kc + 1) & 1);
+        __syncthreads();
+    }
+
+    bf16_t* xc = p.x + (size_t)ch * plane;
+#pragma unroll
+    for (int ti = 0; ti < 2; ++ti) {
+        const int i = i0 + wi * 64 + 32 * ti + col;
+        if (i >= p.N) continue;
+#pragma unroll
+        for (int tj = 0; tj < 2; ++tj)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int j = j0 + wj * 64 + 32 * tj + 8 * g + 4 * hf;
+                if (j < p.Np)
+                    *reinterpret_cast<uint2*>(xc + (size_t)i * p.Np + j) =
+                        make_uint2(pack2(acc[tj][ti][4 * g], acc[tj][ti][4 * g + 1]),
+                                   pack2(acc[tj][ti][4 * g + 2], acc[tj][ti][4 * g + 3]));
+            }
+    }
+}
+
+// ====================================================================================
+// out[i][j][:] = g[i][j][:] * (LayerNorm_out(t[:, i, j]) W_o^T + b_o) (+ z[i][j][:]),
+// g[i][j][:] = sigmoid(LayerNorm_in(z[i][j][:]) W_g^T + b_g).
+// Block = 4 wavefronts = 64 tokens (i, j0 .. j0 + 63): the channel-major t is read 128 bytes per channel
+// and turned token-major in LDS; then features x tokens on the matrix cores (the lane owns a token) for both
+// GEMMs, so the gate meets the projected value in the same lane and register.
+struct TmOutArgs {
+    const bf16_t* x;         // [C][N][Np]
+    const bf16_t* z;         // [N*N][cz]
+    bf16_t* out;             // [N*N][cz]; may be z itself when residual
+    int residual;
+    int N, Np, C, cz;
+    float eps;
+    const bf16_t *wp, *wg;   // [cz][16 KC], [cz][16 KZ]
+    const float *S, *Cn, *Sg, *Cg;
+};
+
+template <int KC, int KZ>
+__global__ __launch_bounds__(256) void k_tm_out(TmOutArgs p) {
+    constexpr int XP = 16 * KC + 8;                     // elements per token row in LDS (16 bytes of padding)
+    __shared__ __attribute__((aligned(16))) bf16_t s_x[64 * XP];
+    const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tjn = (p.N + 63) >> 6;
+    const int i = blockIdx.x / tjn, j0 = (blockIdx.x - i * tjn) * 64;
+    const size_t plane = (size_t)p.N * p.Np;
+
+    const int tt = wave & 1, j = j0 + 32 * tt + col;
+    const bool valid = j < p.N;
+    const size_t tok = (size_t)i * p.N + (valid ? j : 0);
+    Frag za[KZ];
+    {
+        const bf16_t* zp = p.z + tok * p.cz;
+#pragma unroll
+        for (int s = 0; s < KZ; ++s) {
+            za[s].u = make_uint4(0, 0, 0, 0);
+            if (16 * s + 8 * hf < p.cz) za[s].u = *reinterpret_cast<const uint4*>(zp + 16 * s + 8 * hf);
+        }
+    }
+
+    for (int id = tid; id < 16 * KC * 8; id += 256) {
+        const int ch = id >> 3, tp = id & 7, jj = j0 + 8 * tp;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (ch < p.C && jj < p.Np) v = *reinterpret_cast<const uint4*>(p.x + (size_t)ch * plane + (size_t)i * p.Np + jj);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            s_x[(8 * tp + 2 * e) * XP + ch] = (bf16_t)(w[e] & 0xffffu);
+            s_x[(8 * tp + 2 * e + 1) * XP + ch] = (bf16_t)(w[e] >> 16);
+        }
+    }
+    float mean_z, rstd_z;
+    token_stats<KZ>(za, p.cz, hf, p.eps, mean_z, rstd_z);
+    __syncthreads();
+
+    Frag xa[KC];
+#pragma unroll
+    for (int s = 0; s < KC; ++s) xa[s].u = *reinterpret_cast<const uint4*>(s_x + (32 * tt + col) * XP + 16 * s + 8 * hf);
+    float mean, rstd;
+    token_stats<KC>(xa, p.C, hf, p.eps, mean, rstd);
+
+    const int n_ft = p.cz >> 5;
+    for (int ft = wave >> 1; ft < n_ft; ft += 2) {
+        f32x16 acc, accg;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = accg[v] = 0.f;
+        const bf16_t* wrow = p.wp + (size_t)(ft * 32 + col) * (16 * KC) + 8 * hf;
+        const bf16_t* grow = p.wg + (size_t)(ft * 32 + col) * (16 * KZ) + 8 * hf;
+        Frag wf[KC], gf[KZ];
+#pragma unroll
+        for (int s = 0; s < KC; ++s) wf[s].u = *reinterpret_cast<const uint4*>(wrow + 16 * s);
+#pragma unroll
+        for (int s = 0; s < KZ; ++s) gf[s].u = *reinterpret_cast<const uint4*>(grow + 16 * s);
+#pragma unroll
+        for (int s = 0; s < KC; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[s].v, xa[s].v, acc, 0, 0, 0);
+#pragma unroll
+        for (int s = 0; s < KZ; ++s) accg = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf[s].v, za[s].v, accg, 0, 0, 0);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const int f0 = ft * 32 + 8 * g + 4 * hf;
+            const float4 s4 = *reinterpret_cast<const float4*>(p.S + f0);
+            const float4 c4 = *reinterpret_cast<const float4*>(p.Cn + f0);
+            const float4 sg4 = *reinterpret_cast<const float4*>(p.Sg + f0);
+            const float4 cg4 = *reinterpret_cast<const float4*>(p.Cg + f0);
+            float o[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float lin = rstd * (acc[4 * g + e] - mean * pick(s4, e)) + pick(c4, e);
+                const float gate = sigmoid(rstd_z * (accg[4 * g + e] - mean_z * pick(sg4, e)) + pick(cg4, e));
+                o[e] = lin * gate;
+            }
+            if (p.residual) {
+                // (the token's row of z again, eight bytes that are in the cache; this lane alone stores these
+                // elements, after reading them, so out may be z itself)
+                const uint2 rs = *reinterpret_cast<const uint2*>(p.z + tok * p.cz + f0);
+                o[0] += lo_f32(rs.x); o[1] += hi_f32(rs.x); o[2] += lo_f32(rs.y); o[3] += hi_f32(rs.y);
+            }
+            if (valid) *reinterpret_cast<uint2*>(p.out + tok * p.cz + f0) = make_uint2(pack2(o[0], o[1]), pack2(o[2], o[3]));
+        }
+    }
+}
+
+// ====================================================================================
+struct TmWs {
+    bf16_t *wp1, *wp3, *wp4, *a, *b, *x;
+    float *S1, *C1, *S3, *C3, *S4, *C4;
+    size_t total;
+};
+
+static int kc_for(int K) { return K <= 32 ? 2 : (K <= 64 ? 4 : 8); }
+
+static TmWs tm_carve(int N, int cz, int c, void* base) {
+    const int Np = round_up(N, 32), G = c / 32, n_pairs = 2 * G;
+    const int Kp1 = 16 * kc_for(cz), Kp3 = 16 * kc_for(c);
+    char* b = (char*)base;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        char* p = b + off;
+        off += align256(bytes);
+        return p;
+    };
+    TmWs w;
+    w.wp1 = (bf16_t*)take((size_t)64 * n_pairs * Kp1 * 2);
+    w.wp3 = (bf16_t*)take((size_t)cz * Kp3 * 2);
+    w.wp4 = (bf16_t*)take((size_t)cz * Kp1 * 2);
+    w.S1 = (float*)take((size_t)64 * n_pairs * 4);
+    w.C1 = (float*)take((size_t)64 * n_pairs * 4);
+    w.S3 = (float*)take((size_t)cz * 4);
+    w.C3 = (float*)take((size_t)cz * 4);
+    w.S4 = (float*)take((size_t)cz * 4);
+    w.C4 = (float*)take((size_t)cz * 4);
+    const size_t plane = (size_t)c * N * Np * 2;
+    w.a = (bf16_t*)take(plane);
+    w.b = (bf16_t*)take(plane);
+    w.x = (bf16_t*)take(plane);
+    w.total = off;
+    return w;
+}
+
+}  // namespace tm
+
+bool trimul_supported(int dtype, int cz, int c) {
+    return dtype == FF_BF16 && cz % 32 == 0 && c % 32 == 0 && cz >= 32 && c >= 32 && cz <= 128 && c <= 128;
+}
+
+size_t trimul_workspace(int N, int cz, int c) { return tm::tm_carve(N, cz, c, nullptr).total; }
+
+ff_status trimul_run(const ff_trimul_desc& d, const ff_trimul_weights& w, const void* z, const float* mask, bool residual,
+                     void* out, void* ws, hipStream_t st) {
+    using namespace tm;
+    const int N = d.n, cz = d.c_z, c = d.c, Np = round_up(N, 32), G = c / 32, n_pairs = 2 * G;
+    const int kc1 = kc_for(cz), kc3 = kc_for(c);
+    const TmWs m = tm_carve(N, cz, c, ws);
+    {
+        TmPrepArgs a{};
+        a.w_ap = (const bf16_t*)w.w_ap; a.b_ap = (const bf16_t*)w.b_ap; a.w_ag = (const bf16_t*)w.w_ag; a.b_ag = (const bf16_t*)w.b_ag;
+        a.w_bp = (const bf16_t*)w.w_bp; a.b_bp = (const bf16_t*)w.b_bp; a.w_bg = (const bf16_t*)w.w_bg; a.b_bg = (const bf16_t*)w.b_bg;
+        a.w_g = (const bf16_t*)w.w_g; a.b_g = (const bf16_t*)w.b_g; a.ln_g = (const bf16_t*)w.ln_g; a.ln_b = (const bf16_t*)w.ln_b;
+        a.w_o = (const bf16_t*)w.w_o; a.b_o = (const bf16_t*)w.b_o; a.lno_g = (const bf16_t*)w.lno_g; a.lno_b = (const bf16_t*)w.lno_b;
+        a.wp1 = m.wp1; a.wp3 = m.wp3; a.wp4 = m.wp4; a.S1 = m.S1; a.C1 = m.C1; a.S3 = m.S3; a.C3 = m.C3; a.S4 = m.S4; a.C4 = m.C4;
+        a.cz = cz; a.c = c; a.G = G; a.n_pairs = n_pairs; a.Kp1 = 16 * kc1; a.Kp3 = 16 * kc3;
+        const int rows = 64 * n_pairs + 2 * cz;
+        Timed t(KK_TM_PREP, st);
+        hipLaunchKernelGGL(k_tm_prep, dim3((rows + 3) / 4), dim3(256), 0, st, a);
+    }
+    {
+        TmProjArgs a{};
+        a.z = (const bf16_t*)z;
+        a.sr = d.incoming ? 1 : N; a.sl = d.incoming ? N : 1;
+        a.mask = mask; a.N = N; a.Np = Np; a.K = cz; a.C = c; a.cz = cz; a.G = G; a.n_pairs = n_pairs; a.eps = d.ln_eps;
+        a.wp = m.wp1; a.S = m.S1; a.Cn = m.C1; a.a = m.a; a.b = m.b;
+        const int tiles_m = N * (Np / 32);
+        const dim3 grid((tiles_m + 7) / 8);
+        Timed t(KK_TM_PROJ, st);
+        auto smem = [](int kc) { return (size_t)2 * 64 * (kc * 32 + 16) + 8 * 3 * 32 * 4; };
+        if (kc1 == 2) hipLaunchKernelGGL(k_tm_proj<2>, grid, dim3(512), smem(2), st, a);
+        else if (kc1 == 4) hipLaunchKernelGGL(k_tm_proj<4>, grid, dim3(512), smem(4), st, a);
+        else hipLaunchKernelGGL(k_tm_proj<8>, grid, dim3(512), smem(8), st, a);
+    }
+    {
+        TmMulArgs a{};
+        a.a = m.a; a.b = m.b; a.x = m.x; a.N = N; a.Np = Np; a.C = c; a.tiles = (N + 127) / 128;
+        const int blocks = 8 * ((c + 7) / 8) * a.tiles * a.tiles;
+        Timed t(KK_TM_MUL, st);
+        hipLaunchKernelGGL(k_tm_mul, dim3(blocks), dim3(256), 0, st, a);
+    }
+    {
+        TmOutArgs a{};
+        a.x = m.x; a.z = (const bf16_t*)z; a.out = (bf16_t*)out; a.residual = residual ? 1 : 0;
+        a.N = N; a.Np = Np; a.C = c; a.cz = cz; a.eps = d.ln_eps;
+        a.wp = m.wp3; a.wg = m.wp4; a.S = m.S3; a.Cn = m.C3; a.Sg = m.S4; a.Cg = m.C4;
+        const dim3 grid(N * ((N + 63) / 64));
+        Timed t(KK_TM_OUT, st);
+#define FF_TM_OUT(KCV, KZV) hipLaunchKernelGGL((k_tm_out<KCV, KZV>), grid, dim3(256), 0, st, a)
+#define FF_TM_OUT_Z(KCV)              \
+    do {                              \
+        if (kc1 == 2) FF_TM_OUT(KCV, 2);      \
+        else if (kc1 == 4) FF_TM_OUT(KCV, 4); \
+        else FF_TM_OUT(KCV, 8);               \
+    } while (0)
+        if (kc3 == 2) FF_TM_OUT_Z(2);
+        else if (kc3 == 4) FF_TM_OUT_Z(4);
+        else FF_TM_OUT_Z(8);
+#undef FF_TM_OUT_Z
+#undef FF_TM_OUT
+    }
+    return check_launch("triangle multiplication");
+}
+
+}  // namespace ff
