@@ -261,6 +261,61 @@ def calibrate():
             "note": "library probes, HIP-event timed: 32x32x16 bf16 matrix-instruction loop, 256 MiB copy (read + written)"}
 
 
+def trimul_flop(sp):
+    n, cz, c = sp.n, sp.c_z, sp.c
+    f = {"k_tm_proj": 2.0 * n * n * cz * 4 * c, "k_tm_mul": 2.0 * c * n ** 3, "k_tm_out": 2.0 * n * n * (c * cz + cz * cz)}
+    f["total"] = sum(f.values())
+    return f
+
+
+def time_trimul(name, steps, warmup, measured):
+    """Triangular multiplicative update (ff_triangle_multiplication): one module per step, three resident
+    input copies; counted flop = left/right projections with gates + output gate + the N^3 contraction per
+    channel + output projection.  Every kernel of it is a dense contraction, priced against the bf16 matrix peak."""
+    import torch
+    import paper_2203_00854_amd as P
+    from paper_2203_00854_amd import inputs as I
+    case = I.make_trimul_case(name)
+    sp = case.spec
+    desc, w, z, mask = P.trimul_to_device(case, "cuda:0")
+    copies = 1 if z.numel() * 2 > (1 << 29) else 3
+    zs = [z] + [z.clone() for _ in range(copies - 1)]
+    outs = [torch.empty_like(z) for _ in range(copies)]
+    ws = torch.empty(P.ff_triangle_multiplication_workspace_bytes(desc), dtype=torch.uint8, device="cuda:0")
+
+    def step(i):
+        P.ff_triangle_multiplication(desc, w, zs[i % copies], mask, out=outs[i % copies], ws=ws)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    P.ff_profile_enable(True)
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    kernels = P.ff_profile_collect()
+    P.ff_profile_enable(False)
+    fl = trimul_flop(sp)
+    rows = []
+    for kname, (kms, cnt) in kernels.items():
+        r = {"kernel": kname, "avg_us": kms / cnt * 1e3}
+        if kname in fl:
+            tf = fl[kname] / (kms / cnt * 1e-3) / 1e12
+            r.update(bound="mfma", achieved_tflops=tf, frac=tf / PEAK_MFMA_BF16_TFLOPS, frac_of_measured_peak=tf / measured["mfma_tflops"])
+        rows.append(r)
+    rows.sort(key=lambda r: -r["avg_us"])
+    n_bytes = sp.n * sp.n * sp.c_z * 2
+    return {"ms_per_module": ms, "tflops": fl["total"] / (ms * 1e-3) / 1e12, "frac_mfma_peak_whole_module":
+            fl["total"] / (ms * 1e-3) / 1e12 / PEAK_MFMA_BF16_TFLOPS, "steps": steps, "counted_flop_per_step": fl["total"],
+            "algorithmic_bytes_per_step": 2 * n_bytes, "workspace_bytes": P.ff_triangle_multiplication_workspace_bytes(desc),
+            "kernels": rows}
+
+
 def time_layernorm(steps):
     """ff_layernorm alone (the stand-alone entry point; inside the attention the LayerNorm is
     part of the projection GEMM): rows x c as in the MSA and pair representations of the
@@ -327,6 +382,7 @@ def main():
     ap.add_argument("--workload", default="c2_row_bf16_train")
     ap.add_argument("--no-others", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--trimul-only", action="store_true", help="time only the triangular multiplicative update shapes")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy 5 times (reference for HBM traffic counters)")
     args = ap.parse_args()
@@ -349,6 +405,11 @@ def main():
         del src, dst
 
     measured = calibrate()
+    if args.trimul_only:
+        print(json.dumps({name: time_trimul(name, st, 3, measured) for name, st in
+                          (("tm_out_bf16_256", args.steps), ("tm_in_bf16_256", args.steps), ("tm_out_bf16_384", args.steps),
+                           ("tm_out_bf16_2048", 3))}))
+        return
     case, desc, out, ms, kernels = time_workload(args.workload, args.steps, args.warmup)
     path_taken = P.ff_attention_last_path()
     sp = case.spec
@@ -417,6 +478,13 @@ def main():
             del c2
             torch.cuda.empty_cache()
         line["others"] = others
+        # the pair stack's triangular multiplicative update at the paper's shapes
+        line["triangle_multiplication"] = {
+            name: time_trimul(name, st, wu, measured)
+            for name, st, wu in (("tm_out_bf16_256", args.steps, args.warmup), ("tm_in_bf16_256", args.steps, args.warmup),
+                                 ("tm_out_bf16_384", max(args.steps // 4, 5), 3), ("tm_in_bf16_384", max(args.steps // 4, 5), 3),
+                                 ("tm_out_bf16_2048", max(args.steps // 40, 3), 1))}
+        torch.cuda.empty_cache()
         # the module with the residual add that closes it in the Evoformer block fused into the output
         # projection (ff_gated_attention_residual): x + module(x) in one pass
         upd = {}

@@ -161,7 +161,7 @@ struct TmProjArgs {
 };
 
 template <int KC>
-__global__ __launch_bounds__(512) void k_tm_proj(TmProjArgs p) {
+__global__ __launch_bounds__(512, 2) void k_tm_proj(TmProjArgs p) {
     constexpr int PITCH = KC * 32 + 16;                 // bytes per weight row in LDS
     constexpr int PIECES = 64 * 2 * KC;                 // 16-byte pieces per pair
     constexpr int PPT = (PIECES + 511) / 512;           // pieces per thread
@@ -191,27 +191,26 @@ __global__ __launch_bounds__(512) void k_tm_proj(TmProjArgs p) {
     }
     const float mval = valid ? (p.mask ? p.mask[tok] : 1.f) : 0.f;
 
-    // weight pieces of this thread
-    int w_src[PPT], w_dst[PPT];
-#pragma unroll
-    for (int n = 0; n < PPT; ++n) {
-        const int id = tid + 512 * n;
-        const int row = id / (2 * KC), pc = id - row * (2 * KC);
-        w_src[n] = id < PIECES ? row * (16 * KC) + pc * 8 : -1;
-        w_dst[n] = row * PITCH + pc * 16;
-    }
-    uint4 wreg[PPT];
-    auto fetch_pair = [&](int pr) {
-        const bf16_t* src = p.wp + (size_t)pr * 64 * (16 * KC);
-#pragma unroll
-        for (int n = 0; n < PPT; ++n)
-            if (w_src[n] >= 0) wreg[n] = *reinterpret_cast<const uint4*>(src + w_src[n]);
-    };
-    auto stash_pair = [&](int buf) {
-#pragma unroll
-        for (int n = 0; n < PPT; ++n)
-            if (w_src[n] >= 0) *reinterpret_cast<uint4*>(s_w + buf * 64 * PITCH + w_dst[n]) = wreg[n];
-    };
+    // weight pieces of this thread (at most two; named registers: arrays captured by a lambda end up in scratch memory)
+    static_assert(PPT <= 2, "pieces per thread");
+    const int id0 = tid, id1 = tid + 512;
+    const int row0 = id0 / (2 * KC), pc0 = id0 - row0 * (2 * KC);
+    const int row1 = id1 / (2 * KC), pc1 = id1 - row1 * (2 * KC);
+    const bool has0 = id0 < PIECES, has1 = PPT > 1 && id1 < PIECES;
+    const int w_src0 = row0 * (16 * KC) + pc0 * 8, w_dst0 = row0 * PITCH + pc0 * 16;
+    const int w_src1 = row1 * (16 * KC) + pc1 * 8, w_dst1 = row1 * PITCH + pc1 * 16;
+    uint4 wreg0 = make_uint4(0, 0, 0, 0), wreg1 = wreg0;
+#define fetch_pair(PR)                                                                 \
+    do {                                                                               \
+        const bf16_t* src_ = p.wp + (size_t)(PR) * 64 * (16 * KC);                     \
+        if (has0) wreg0 = *reinterpret_cast<const uint4*>(src_ + w_src0);              \
+        if (has1) wreg1 = *reinterpret_cast<const uint4*>(src_ + w_src1);              \
+    } while (0)
+#define stash_pair(BUF)                                                                       \
+    do {                                                                                      \
+        if (has0) *reinterpret_cast<uint4*>(s_w + (BUF) * 64 * PITCH + w_dst0) = wreg0;       \
+        if (has1) *reinterpret_cast<uint4*>(s_w + (BUF) * 64 * PITCH + w_dst1) = wreg1;       \
+    } while (0)
     fetch_pair(0);
 
     {
@@ -224,6 +223,10 @@ __global__ __launch_bounds__(512) void k_tm_proj(TmProjArgs p) {
         }
     }
     stash_pair(0);
+    if (p.n_pairs > 1) {
+        fetch_pair(1);
+        stash_pair(1);
+    }
     __syncthreads();
 
     const float* st_mean = s_stat + (wave * 3 + 0) * 32;
@@ -231,9 +234,14 @@ __global__ __launch_bounds__(512) void k_tm_proj(TmProjArgs p) {
     const float* st_mval = s_stat + (wave * 3 + 2) * 32;
     const size_t plane = (size_t)p.N * p.Np;
 
+    // Pair pr + 2 is fetched into registers before the matrix instructions of pair pr (so that its latency hides
+    // behind them, and so that these loads precede the epilogue's stores in the wavefront's memory order:
+    // waiting for a load then does not wait for stores issued after it) and written to the LDS half that pair pr
+    // occupied once every wavefront has passed the barrier.
     for (int pr = 0; pr < p.n_pairs; ++pr) {
         const unsigned char* st = s_w + (pr & 1) * 64 * PITCH;
-        if (pr + 1 < p.n_pairs) fetch_pair(pr + 1);
+        const bool more = pr + 2 < p.n_pairs;
+        if (more) fetch_pair(pr + 2);
         f32x16 acc0, acc1;
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc0[v] = acc1[v] = 0.f;
@@ -248,7 +256,6 @@ __global__ __launch_bounds__(512) void k_tm_proj(TmProjArgs p) {
             acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[s].v, w0.v, acc0, 0, 0, 0);
             acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[s].v, w1.v, acc1, 0, 0, 0);
         }
-        if (pr + 1 < p.n_pairs) stash_pair((pr + 1) & 1);
         const bool left = pr < p.G;
         const int ch = 32 * (left ? pr : pr - p.G) + col;
         bf16_t* dst = (left ? p.a : p.b) + (size_t)ch * plane + (size_t)r * p.Np + l0 + 4 * hf;
@@ -268,12 +275,15 @@ __global__ __launch_bounds__(512) void k_tm_proj(TmProjArgs p) {
             if (live) *reinterpret_cast<uint2*>(dst + 8 * g) = make_uint2(pack2(o[0], o[1]), pack2(o[2], o[3]));
         }
         __syncthreads();
+        if (more) stash_pair(pr & 1);
     }
+#undef fetch_pair
+#undef stash_pair
 }
 
 // ====================================================================================
 // t_c[i][j] = sum_k A_c[i][k] B_c[j][k] for every channel c: block = 4 wavefronts (2 x 2), block tile
-// 128 x 128, wavefront tile 64 x 64, the contraction in chunks of 32 through double-buffered LDS.
+// 128 x 128, wavefront tile 64 x 64, the contraction in chunks of 64 through double-buffered LDS.
 // Blocks are handed to the 8 XCDs round-robin; channel c goes to XCD c % 8 with all of its tiles, so a
 // channel's operands live in one L2.
 struct TmMulArgs {
@@ -282,11 +292,15 @@ struct TmMulArgs {
     int N, Np, C, tiles;     // tiles per side
 };
 
-__global__ __launch_bounds__(256) void k_tm_mul(TmMulArgs p) {
-    constexpr int PITCH = 80;                           // bytes per 32-element row in LDS (64 + 16 padding)
-    constexpr int STAGE = 128 * PITCH;
-    __shared__ __attribute__((aligned(16))) unsigned char s_a[2 * STAGE];
-    __shared__ __attribute__((aligned(16))) unsigned char s_b[2 * STAGE];
+constexpr int kMulPitch = 144;                          // bytes per 64-element row in LDS (128 + 16 padding)
+constexpr int kMulStage = 128 * kMulPitch;
+constexpr size_t kMulSmem = 4 * (size_t)kMulStage;      // two operands, two buffers
+
+__global__ __launch_bounds__(256, 2) void k_tm_mul(TmMulArgs p) {
+    constexpr int PITCH = kMulPitch, STAGE = kMulStage;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    unsigned char* s_a = smem;                  // [2][STAGE]
+    unsigned char* s_b = smem + 2 * STAGE;      // [2][STAGE]
     const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wi = wave >> 1, wj = wave & 1;
     const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3, t2 = p.tiles * p.tiles;
@@ -297,30 +311,51 @@ __global__ __launch_bounds__(256) void k_tm_mul(TmMulArgs p) {
     const bf16_t* ac = p.a + (size_t)ch * plane;
     const bf16_t* bc = p.b + (size_t)ch * plane;
 
-    // this thread's two pieces of each operand chunk: rows tid/4 and tid/4 + 64, piece tid%4
-    const int prow = tid >> 2, pc = tid & 3;
-    const bool a_ok0 = i0 + prow < p.N, a_ok1 = i0 + prow + 64 < p.N;
-    const bool b_ok0 = j0 + prow < p.N, b_ok1 = j0 + prow + 64 < p.N;
-    const bf16_t* ap0 = ac + (size_t)(a_ok0 ? i0 + prow : 0) * p.Np + pc * 8;
-    const bf16_t* ap1 = ac + (size_t)(a_ok1 ? i0 + prow + 64 : 0) * p.Np + pc * 8;
-    const bf16_t* bp0 = bc + (size_t)(b_ok0 ? j0 + prow : 0) * p.Np + pc * 8;
-    const bf16_t* bp1 = bc + (size_t)(b_ok1 ? j0 + prow + 64 : 0) * p.Np + pc * 8;
-    const int sdst0 = prow * PITCH + pc * 16, sdst1 = (prow + 64) * PITCH + pc * 16;
+    // this thread's four pieces of each operand chunk: rows tid/8 + 32n, piece tid%8 (16 bytes = 8 positions of k)
+    // (named registers and macros: arrays captured by a lambda end up in scratch memory)
+    const int prow = tid >> 3, pc = tid & 7;
+    const bool a_ok0 = i0 + prow < p.N, a_ok1 = i0 + prow + 32 < p.N, a_ok2 = i0 + prow + 64 < p.N, a_ok3 = i0 + prow + 96 < p.N;
+    const bool b_ok0 = j0 + prow < p.N, b_ok1 = j0 + prow + 32 < p.N, b_ok2 = j0 + prow + 64 < p.N, b_ok3 = j0 + prow + 96 < p.N;
+    const size_t row32 = (size_t)32 * p.Np;
+    const bf16_t* ap = ac + (size_t)(a_ok0 ? i0 + prow : 0) * p.Np + pc * 8;     // rows + 32n: ap + n * row32 (guarded)
+    const bf16_t* bp = bc + (size_t)(b_ok0 ? j0 + prow : 0) * p.Np + pc * 8;
+    const int sdst = prow * PITCH + pc * 16;
     const uint4 zero4 = make_uint4(0, 0, 0, 0);
-    uint4 ra0, ra1, rb0, rb1;
-    auto fetch = [&](int kc) {
-        const int k0 = kc * 32;
-        ra0 = a_ok0 ? *reinterpret_cast<const uint4*>(ap0 + k0) : zero4;
-        ra1 = a_ok1 ? *reinterpret_cast<const uint4*>(ap1 + k0) : zero4;
-        rb0 = b_ok0 ? *reinterpret_cast<const uint4*>(bp0 + k0) : zero4;
-        rb1 = b_ok1 ? *reinterpret_cast<const uint4*>(bp1 + k0) : zero4;
-    };
-    auto stash = [&](int buf) {
-        *reinterpret_cast<uint4*>(s_a + buf * STAGE + sdst0) = ra0;
-        *reinterpret_cast<uint4*>(s_a + buf * STAGE + sdst1) = ra1;
-        *reinterpret_cast<uint4*>(s_b + buf * STAGE + sdst0) = rb0;
-        *reinterpret_cast<uint4*>(s_b + buf * STAGE + sdst1) = rb1;
-    };
+    uint4 ra0 = zero4, ra1 = zero4, ra2 = zero4, ra3 = zero4, rb0 = zero4, rb1 = zero4, rb2 = zero4, rb3 = zero4;
+#define fetch(KCH)                                                                                     \
+    do {                                                                                               \
+        const int k0_ = (KCH) * 64;                                                                    \
+        const bool k_ok_ = k0_ + pc * 8 < p.Np;   /* Np is a multiple of 32: the last chunk may be half there */ \
+        ra0 = zero4;                                                                                   \
+        if (a_ok0 && k_ok_) ra0 = *reinterpret_cast<const uint4*>(ap + k0_);   \
+        ra1 = zero4;                                                                                   \
+        if (a_ok1 && k_ok_) ra1 = *reinterpret_cast<const uint4*>(ap + row32 + k0_);   \
+        ra2 = zero4;                                                                                   \
+        if (a_ok2 && k_ok_) ra2 = *reinterpret_cast<const uint4*>(ap + 2 * row32 + k0_);   \
+        ra3 = zero4;                                                                                   \
+        if (a_ok3 && k_ok_) ra3 = *reinterpret_cast<const uint4*>(ap + 3 * row32 + k0_);   \
+        rb0 = zero4;                                                                                   \
+        if (b_ok0 && k_ok_) rb0 = *reinterpret_cast<const uint4*>(bp + k0_);   \
+        rb1 = zero4;                                                                                   \
+        if (b_ok1 && k_ok_) rb1 = *reinterpret_cast<const uint4*>(bp + row32 + k0_);   \
+        rb2 = zero4;                                                                                   \
+        if (b_ok2 && k_ok_) rb2 = *reinterpret_cast<const uint4*>(bp + 2 * row32 + k0_);   \
+        rb3 = zero4;                                                                                   \
+        if (b_ok3 && k_ok_) rb3 = *reinterpret_cast<const uint4*>(bp + 3 * row32 + k0_);   \
+    } while (0)
+#define stash(BUF)                                                                           \
+    do {                                                                                     \
+        unsigned char* da_ = s_a + (BUF) * STAGE + sdst;                                     \
+        unsigned char* db_ = s_b + (BUF) * STAGE + sdst;                                     \
+        *reinterpret_cast<uint4*>(da_) = ra0;                                                \
+        *reinterpret_cast<uint4*>(da_ + 32 * PITCH) = ra1;                                   \
+        *reinterpret_cast<uint4*>(da_ + 64 * PITCH) = ra2;                                   \
+        *reinterpret_cast<uint4*>(da_ + 96 * PITCH) = ra3;                                   \
+        *reinterpret_cast<uint4*>(db_) = rb0;                                                \
+        *reinterpret_cast<uint4*>(db_ + 32 * PITCH) = rb1;                                   \
+        *reinterpret_cast<uint4*>(db_ + 64 * PITCH) = rb2;                                   \
+        *reinterpret_cast<uint4*>(db_ + 96 * PITCH) = rb3;                                   \
+    } while (0)
 
     f32x16 acc[2][2];     // [j tile][i tile]: lane = i, registers = j
 #pragma unroll
@@ -330,31 +365,38 @@ __global__ __launch_bounds__(256) void k_tm_mul(TmMulArgs p) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[tj][ti][v] = 0.f;
 
-    const int nk = p.Np >> 5;
+    const int nk = (p.Np + 63) >> 6;
     fetch(0);
     stash(0);
+    if (nk > 1) {
+        fetch(1);
+        stash(1);
+    }
     __syncthreads();
+    // chunk kc + 2 travels to registers while the matrix cores work on chunk kc, and takes over its LDS half
+    // after the barrier
     for (int kc = 0; kc < nk; ++kc) {
-        if (kc + 1 < nk) fetch(kc + 1);
+        const bool more = kc + 2 < nk;
+        if (more) fetch(kc + 2);
         const unsigned char* sa = s_a + (kc & 1) * STAGE + (wi * 64 + col) * PITCH + hf * 16;
         const unsigned char* sb = s_b + (kc & 1) * STAGE + (wj * 64 + col) * PITCH + hf * 16;
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            Frag af[2], bf[2];
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                af[t].u = *reinterpret_cast<const uint4*>(sa + t * 32 * PITCH + kk * 32);
-                bf[t].u = *reinterpret_cast<const uint4*>(sb + t * 32 * PITCH + kk * 32);
-            }
-#pragma unroll
-            for (int tj = 0; tj < 2; ++tj)
-#pragma unroll
-                for (int ti = 0; ti < 2; ++ti)
-                    acc[tj][ti] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[tj].v, af[ti].v, acc[tj][ti], 0, 0, 0);
+        for (int kk = 0; kk < 4; ++kk) {
+            Frag af0, af1, bf0, bf1;
+            af0.u = *reinterpret_cast<const uint4*>(sa + kk * 32);
+            af1.u = *reinterpret_cast<const uint4*>(sa + 32 * PITCH + kk * 32);
+            bf0.u = *reinterpret_cast<const uint4*>(sb + kk * 32);
+            bf1.u = *reinterpret_cast<const uint4*>(sb + 32 * PITCH + kk * 32);
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf0.v, af0.v, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf0.v, af1.v, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf1.v, af0.v, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf1.v, af1.v, acc[1][1], 0, 0, 0);
         }
-        if (kc + 1 < nk) stash((kc + 1) & 1);
         __syncthreads();
+        if (more) stash(kc & 1);
     }
+#undef fetch
+#undef stash
 
     bf16_t* xc = p.x + (size_t)ch * plane;
 #pragma unroll
@@ -377,9 +419,9 @@ __global__ __launch_bounds__(256) void k_tm_mul(TmMulArgs p) {
 // ====================================================================================
 // out[i][j][:] = g[i][j][:] * (LayerNorm_out(t[:, i, j]) W_o^T + b_o) (+ z[i][j][:]),
 // g[i][j][:] = sigmoid(LayerNorm_in(z[i][j][:]) W_g^T + b_g).
-// Block = 4 wavefronts = 64 tokens (i, j0 .. j0 + 63): the channel-major t is read 128 bytes per channel
-// and turned token-major in LDS; then features x tokens on the matrix cores (the lane owns a token) for both
-// GEMMs, so the gate meets the projected value in the same lane and register.
+// Block = 4 wavefronts, both folded weight matrices resident in LDS, each wavefront working through 32-token
+// tiles (i, j0 .. j0 + 31); features x tokens on the matrix cores (the lane owns a token) for both GEMMs, so the
+// gate meets the projected value in the same lane and register.
 struct TmOutArgs {
     const bf16_t* x;         // [C][N][Np]
     const bf16_t* z;         // [N*N][cz]
@@ -393,85 +435,95 @@ struct TmOutArgs {
 
 template <int KC, int KZ>
 __global__ __launch_bounds__(256) void k_tm_out(TmOutArgs p) {
-    constexpr int XP = 16 * KC + 8;                     // elements per token row in LDS (16 bytes of padding)
-    __shared__ __attribute__((aligned(16))) bf16_t s_x[64 * XP];
+    constexpr int PC = KC * 32 + 16, PZ = KZ * 32 + 16;     // bytes per weight row in LDS (padded: conflict-free operand reads)
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    unsigned char* s_wo = smem;                             // [cz][PC]
+    unsigned char* s_wg = smem + (size_t)p.cz * PC;         // [cz][PZ]
     const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int tjn = (p.N + 63) >> 6;
-    const int i = blockIdx.x / tjn, j0 = (blockIdx.x - i * tjn) * 64;
-    const size_t plane = (size_t)p.N * p.Np;
-
-    const int tt = wave & 1, j = j0 + 32 * tt + col;
-    const bool valid = j < p.N;
-    const size_t tok = (size_t)i * p.N + (valid ? j : 0);
-    Frag za[KZ];
-    {
-        const bf16_t* zp = p.z + tok * p.cz;
-#pragma unroll
-        for (int s = 0; s < KZ; ++s) {
-            za[s].u = make_uint4(0, 0, 0, 0);
-            if (16 * s + 8 * hf < p.cz) za[s].u = *reinterpret_cast<const uint4*>(zp + 16 * s + 8 * hf);
-        }
+    for (int id = tid; id < p.cz * 2 * KC; id += 256) {
+        const int row = id / (2 * KC), pc = id - row * (2 * KC);
+        *reinterpret_cast<uint4*>(s_wo + row * PC + pc * 16) = *reinterpret_cast<const uint4*>(p.wp + (size_t)row * (16 * KC) + pc * 8);
     }
-
-    for (int id = tid; id < 16 * KC * 8; id += 256) {
-        const int ch = id >> 3, tp = id & 7, jj = j0 + 8 * tp;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (ch < p.C && jj < p.Np) v = *reinterpret_cast<const uint4*>(p.x + (size_t)ch * plane + (size_t)i * p.Np + jj);
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            s_x[(8 * tp + 2 * e) * XP + ch] = (bf16_t)(w[e] & 0xffffu);
-            s_x[(8 * tp + 2 * e + 1) * XP + ch] = (bf16_t)(w[e] >> 16);
-        }
+    for (int id = tid; id < p.cz * 2 * KZ; id += 256) {
+        const int row = id / (2 * KZ), pc = id - row * (2 * KZ);
+        *reinterpret_cast<uint4*>(s_wg + row * PZ + pc * 16) = *reinterpret_cast<const uint4*>(p.wg + (size_t)row * (16 * KZ) + pc * 8);
     }
-    float mean_z, rstd_z;
-    token_stats<KZ>(za, p.cz, hf, p.eps, mean_z, rstd_z);
     __syncthreads();
 
-    Frag xa[KC];
+    const size_t plane = (size_t)p.N * p.Np;
+    const int tpr = p.Np >> 5, tiles_m = p.N * tpr, n_ft = p.cz >> 5;
+    for (int t = blockIdx.x * 4 + wave; t < tiles_m; t += gridDim.x * 4) {
+        const int i = t / tpr, j0 = (t - i * tpr) * 32, j = j0 + col;       // j < Np
+        const bool valid = j < p.N;
+        const size_t tok = (size_t)i * p.N + (valid ? j : 0);
+        Frag za[KZ], xa[KC];
+        {
+            const bf16_t* zp = p.z + tok * p.cz;
 #pragma unroll
-    for (int s = 0; s < KC; ++s) xa[s].u = *reinterpret_cast<const uint4*>(s_x + (32 * tt + col) * XP + 16 * s + 8 * hf);
-    float mean, rstd;
-    token_stats<KC>(xa, p.C, hf, p.eps, mean, rstd);
+            for (int s = 0; s < KZ; ++s) {
+                za[s].u = make_uint4(0, 0, 0, 0);
+                if (16 * s + 8 * hf < p.cz) za[s].u = *reinterpret_cast<const uint4*>(zp + 16 * s + 8 * hf);
+            }
+            // t is channel-major: the eight channels of an operand fragment are eight 2-byte loads, each of
+            // them 64 contiguous bytes across the half-wave (the order of the contraction index is free as
+            // long as both operands agree, and the weights keep the natural order)
+            const bf16_t* xp = p.x + (size_t)i * p.Np + j;
+#pragma unroll
+            for (int s = 0; s < KC; ++s) {
+                xa[s].u = make_uint4(0, 0, 0, 0);
+                if (16 * s + 8 * hf < p.C) {
+                    const bf16_t* xc = xp + (size_t)(16 * s + 8 * hf) * plane;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        xa[s].w[e] = (uint32_t)xc[(size_t)(2 * e) * plane] | ((uint32_t)xc[(size_t)(2 * e + 1) * plane] << 16);
+                }
+            }
+        }
+        float mean_z, rstd_z, mean, rstd;
+        token_stats<KZ>(za, p.cz, hf, p.eps, mean_z, rstd_z);
+        token_stats<KC>(xa, p.C, hf, p.eps, mean, rstd);
 
-    const int n_ft = p.cz >> 5;
-    for (int ft = wave >> 1; ft < n_ft; ft += 2) {
-        f32x16 acc, accg;
+        for (int ft = 0; ft < n_ft; ++ft) {
+            f32x16 acc, accg;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[v] = accg[v] = 0.f;
-        const bf16_t* wrow = p.wp + (size_t)(ft * 32 + col) * (16 * KC) + 8 * hf;
-        const bf16_t* grow = p.wg + (size_t)(ft * 32 + col) * (16 * KZ) + 8 * hf;
-        Frag wf[KC], gf[KZ];
+            for (int v = 0; v < 16; ++v) acc[v] = accg[v] = 0.f;
+            const unsigned char* wrow = s_wo + (ft * 32 + col) * PC + hf * 16;
+            const unsigned char* grow = s_wg + (ft * 32 + col) * PZ + hf * 16;
 #pragma unroll
-        for (int s = 0; s < KC; ++s) wf[s].u = *reinterpret_cast<const uint4*>(wrow + 16 * s);
-#pragma unroll
-        for (int s = 0; s < KZ; ++s) gf[s].u = *reinterpret_cast<const uint4*>(grow + 16 * s);
-#pragma unroll
-        for (int s = 0; s < KC; ++s) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[s].v, xa[s].v, acc, 0, 0, 0);
-#pragma unroll
-        for (int s = 0; s < KZ; ++s) accg = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf[s].v, za[s].v, accg, 0, 0, 0);
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int f0 = ft * 32 + 8 * g + 4 * hf;
-            const float4 s4 = *reinterpret_cast<const float4*>(p.S + f0);
-            const float4 c4 = *reinterpret_cast<const float4*>(p.Cn + f0);
-            const float4 sg4 = *reinterpret_cast<const float4*>(p.Sg + f0);
-            const float4 cg4 = *reinterpret_cast<const float4*>(p.Cg + f0);
-            float o[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float lin = rstd * (acc[4 * g + e] - mean * pick(s4, e)) + pick(c4, e);
-                const float gate = sigmoid(rstd_z * (accg[4 * g + e] - mean_z * pick(sg4, e)) + pick(cg4, e));
-                o[e] = lin * gate;
+            for (int s = 0; s < KC; ++s) {
+                Frag wf;
+                wf.u = *reinterpret_cast<const uint4*>(wrow + 32 * s);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf.v, xa[s].v, acc, 0, 0, 0);
             }
-            if (p.residual) {
-                // (the token's row of z again, eight bytes that are in the cache; this lane alone stores these
-                // elements, after reading them, so out may be z itself)
-                const uint2 rs = *reinterpret_cast<const uint2*>(p.z + tok * p.cz + f0);
-                o[0] += lo_f32(rs.x); o[1] += hi_f32(rs.x); o[2] += lo_f32(rs.y); o[3] += hi_f32(rs.y);
+#pragma unroll
+            for (int s = 0; s < KZ; ++s) {
+                Frag gf;
+                gf.u = *reinterpret_cast<const uint4*>(grow + 32 * s);
+                accg = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf.v, za[s].v, accg, 0, 0, 0);
             }
-            if (valid) *reinterpret_cast<uint2*>(p.out + tok * p.cz + f0) = make_uint2(pack2(o[0], o[1]), pack2(o[2], o[3]));
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int f0 = ft * 32 + 8 * g + 4 * hf;
+                const float4 s4 = *reinterpret_cast<const float4*>(p.S + f0);
+                const float4 c4 = *reinterpret_cast<const float4*>(p.Cn + f0);
+                const float4 sg4 = *reinterpret_cast<const float4*>(p.Sg + f0);
+                const float4 cg4 = *reinterpret_cast<const float4*>(p.Cg + f0);
+                float o[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float lin = rstd * (acc[4 * g + e] - mean * pick(s4, e)) + pick(c4, e);
+                    const float gate = sigmoid(rstd_z * (accg[4 * g + e] - mean_z * pick(sg4, e)) + pick(cg4, e));
+                    o[e] = lin * gate;
+                }
+                if (p.residual) {
+                    // (the token's row of z again, eight bytes that are in the cache; this lane alone stores these
+                    // elements, after every lane of the wavefront has read its fragments of the row, so out may be z itself)
+                    const uint2 rs = *reinterpret_cast<const uint2*>(p.z + tok * p.cz + f0);
+                    o[0] += lo_f32(rs.x); o[1] += hi_f32(rs.x); o[2] += lo_f32(rs.y); o[3] += hi_f32(rs.y);
+                }
+                if (valid) *reinterpret_cast<uint2*>(p.out + tok * p.cz + f0) = make_uint2(pack2(o[0], o[1]), pack2(o[2], o[3]));
+            }
         }
     }
 }
@@ -557,17 +609,31 @@ ff_status trimul_run(const ff_trimul_desc& d, const ff_trimul_weights& w, const 
         TmMulArgs a{};
         a.a = m.a; a.b = m.b; a.x = m.x; a.N = N; a.Np = Np; a.C = c; a.tiles = (N + 127) / 128;
         const int blocks = 8 * ((c + 7) / 8) * a.tiles * a.tiles;
+        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_tm_mul),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMulSmem);
+        if (attr != hipSuccess) return fail(FF_EHIP, "k_tm_mul: dynamic LDS limit: %s", hipGetErrorString(attr));
         Timed t(KK_TM_MUL, st);
-        hipLaunchKernelGGL(k_tm_mul, dim3(blocks), dim3(256), 0, st, a);
+        hipLaunchKernelGGL(k_tm_mul, dim3(blocks), dim3(256), kMulSmem, st, a);
     }
     {
         TmOutArgs a{};
         a.x = m.x; a.z = (const bf16_t*)z; a.out = (bf16_t*)out; a.residual = residual ? 1 : 0;
         a.N = N; a.Np = Np; a.C = c; a.cz = cz; a.eps = d.ln_eps;
         a.wp = m.wp3; a.wg = m.wp4; a.S = m.S3; a.Cn = m.C3; a.Sg = m.S4; a.Cg = m.C4;
-        const dim3 grid(N * ((N + 63) / 64));
+        const int tiles_m = N * (Np / 32);
+        int blocks = (tiles_m + 3) / 4;
+        if (blocks > 512) blocks = 512;                 // two blocks per compute unit, each working through its share of the tiles
+        const dim3 grid(blocks);
+        const size_t smem = (size_t)cz * (kc3 * 32 + 16) + (size_t)cz * (kc1 * 32 + 16);
+        hipError_t attr = hipSuccess;
         Timed t(KK_TM_OUT, st);
-#define FF_TM_OUT(KCV, KZV) hipLaunchKernelGGL((k_tm_out<KCV, KZV>), grid, dim3(256), 0, st, a)
+#define FF_TM_OUT(KCV, KZV)                                                                                          \
+    do {                                                                                                             \
+        static const hipError_t once = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_tm_out<KCV, KZV>),      \
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);  \
+        attr = once;                                                                                                 \
+        if (once == hipSuccess) hipLaunchKernelGGL((k_tm_out<KCV, KZV>), grid, dim3(256), smem, st, a);             \
+    } while (0)
 #define FF_TM_OUT_Z(KCV)              \
     do {                              \
         if (kc1 == 2) FF_TM_OUT(KCV, 2);      \
@@ -579,6 +645,7 @@ ff_status trimul_run(const ff_trimul_desc& d, const ff_trimul_weights& w, const 
         else FF_TM_OUT_Z(8);
 #undef FF_TM_OUT_Z
 #undef FF_TM_OUT
+        if (attr != hipSuccess) return fail(FF_EHIP, "k_tm_out: dynamic LDS limit: %s", hipGetErrorString(attr));
     }
     return check_launch("triangle multiplication");
 }
