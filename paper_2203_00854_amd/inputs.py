@@ -342,3 +342,76 @@ def make_trimul_case(spec_or_name, seed: int = SEED) -> TriMulCase:
     elif kind != "none":
         raise ValueError(spec.mask)
     return TriMulCase(spec, z, mask, w)
+
+
+# --------------------------------------------------------------------------- global column attention (extra-MSA stack)
+@dataclass(frozen=True)
+class GlobalSpec:
+    """MSA column global attention: m is [n_seq, n_res, c]; H heads of d channels for the query and
+    the gate, one shared key / value head of d channels.  mask as in CaseSpec ("none" | "tail:K" | "random:P"),
+    "tail" padding the last K sequences."""
+    name: str
+    dtype: str
+    n_seq: int
+    n_res: int
+    c: int
+    heads: int
+    head_dim: int
+    mask: str = "none"
+    ln_eps: float = 1e-5
+    stream: str = ""
+
+    @property
+    def stream_name(self):
+        return self.stream or self.name
+
+
+@dataclass
+class GlobalCase:
+    spec: GlobalSpec
+    m: np.ndarray
+    mask: Optional[np.ndarray]
+    weights: Dict[str, np.ndarray] = field(default_factory=dict)
+
+    def widened_weights(self) -> Dict[str, np.ndarray]:
+        return {k: widen(v) for k, v in self.weights.items()}
+
+
+# Extra-MSA shapes of the paper (Table 1: N_extra_seq 1024 / 5120, N_res 256 / 384) with AlphaFold's
+# extra-MSA channel count (64) and 8 heads of 8 channels, as in the column-attention workload.
+GLOBAL_SPECS = {
+    "gca_bf16_1024x384": GlobalSpec("gca_bf16_1024x384", "bf16", 1024, 384, 64, 8, 8, "tail:102"),
+    "gca_bf16_5120x384": GlobalSpec("gca_bf16_5120x384", "bf16", 5120, 384, 64, 8, 8, "tail:512"),
+}
+
+
+def make_global_case(spec_or_name, seed: int = SEED) -> GlobalCase:
+    spec = GLOBAL_SPECS[spec_or_name] if isinstance(spec_or_name, str) else spec_or_name
+
+    def gen(name, shape, scale=1.0, shift=0.0):
+        v = normal(stream_key(seed, spec.stream_name, name), int(np.prod(shape)))
+        return to_storage(v * scale + shift, spec.dtype).reshape(shape)
+
+    c, hd, d = spec.c, spec.heads * spec.head_dim, spec.head_dim
+    w: Dict[str, np.ndarray] = {}
+    w["ln_g"] = gen("ln_g", (c,), 0.1, 1.0)
+    w["ln_b"] = gen("ln_b", (c,), 0.1)
+    w["w_q"] = gen("w_q", (hd, c), c ** -0.5)
+    w["w_k"] = gen("w_k", (d, c), c ** -0.5)
+    w["w_v"] = gen("w_v", (d, c), c ** -0.5)
+    w["w_g"] = gen("w_g", (hd, c), c ** -0.5)
+    w["b_g"] = to_storage(np.ones(hd), spec.dtype)
+    w["w_o"] = gen("w_o", (c, hd), hd ** -0.5)
+    w["b_o"] = gen("b_o", (c,), 0.1)
+    m = gen("m", (spec.n_seq, spec.n_res, c))
+    kind, _, arg = spec.mask.partition(":")
+    mask = None
+    if kind == "tail":
+        mask = np.ones((spec.n_seq, spec.n_res), np.float32)
+        mask[spec.n_seq - int(arg):, :] = 0.0
+    elif kind == "random":
+        mask = bernoulli(stream_key(seed, spec.stream_name, "mask"), spec.n_seq * spec.n_res, float(arg)).reshape(
+            spec.n_seq, spec.n_res)
+    elif kind != "none":
+        raise ValueError(spec.mask)
+    return GlobalCase(spec, m, mask, w)
