@@ -316,6 +316,59 @@ def time_trimul(name, steps, warmup, measured):
             "kernels": rows}
 
 
+def time_global(name, steps, warmup, measured):
+    """Extra-MSA global column attention (ff_global_column_attention).  The module is linear in the number of
+    sequences and bound by HBM: the method reads m and writes out once each (algorithmic bytes); this
+    implementation reads m twice (key/value/query pass, gate/output pass) and moves k, v through HBM as float32."""
+    import torch
+    import paper_2203_00854_amd as P
+    from paper_2203_00854_amd import inputs as I
+    case = I.make_global_case(name)
+    sp = case.spec
+    desc, w, m, mask = P.global_to_device(case, "cuda:0")
+    copies = 3 if m.numel() * 2 < (1 << 28) else 1
+    ms_ = [m] + [m.clone() for _ in range(copies - 1)]
+    outs = [torch.empty_like(m) for _ in range(copies)]
+    ws = torch.empty(P.ff_global_column_attention_workspace_bytes(desc), dtype=torch.uint8, device="cuda:0")
+
+    def step(i):
+        P.ff_global_column_attention(desc, w, ms_[i % copies], mask, out=outs[i % copies], ws=ws)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    P.ff_profile_enable(True)
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    kernels = P.ff_profile_collect()
+    P.ff_profile_enable(False)
+    hd, tok = sp.heads * sp.head_dim, sp.n_seq * sp.n_res
+    flop = 2.0 * tok * sp.c * (2 * hd + 2 * sp.head_dim) + 2.0 * tok * hd * sp.c + 2.0 * 2 * tok * hd
+    n_bytes = tok * sp.c * 2
+    kv_bytes = tok * 2 * sp.head_dim * 4
+    per_kernel = {"k_gca_kv": n_bytes + kv_bytes, "k_gca_softmax": 2 * kv_bytes, "k_gca_out": 2 * n_bytes}
+    rows = []
+    for kname, (kms, cnt) in kernels.items():
+        r = {"kernel": kname, "avg_us": kms / cnt * 1e3}
+        if kname in per_kernel:
+            gb = per_kernel[kname] / (kms / cnt * 1e-3) / 1e9
+            r.update(bound="hbm", bytes_per_launch=per_kernel[kname], achieved_gbs=gb, frac=gb / PEAK_HBM_GBS,
+                     frac_of_measured_peak=gb / measured["copy_gbs"])
+        rows.append(r)
+    rows.sort(key=lambda r: -r["avg_us"])
+    gbs = 2 * n_bytes / (ms * 1e-3) / 1e9
+    return {"ms_per_module": ms, "tflops": flop / (ms * 1e-3) / 1e12, "steps": steps, "counted_flop_per_step": flop,
+            "algorithmic_bytes_per_step": 2 * n_bytes, "bound": "hbm", "achieved_gbs_algorithmic": gbs,
+            "frac_hbm_peak_whole_module": gbs / PEAK_HBM_GBS, "frac_of_measured_copy": gbs / measured["copy_gbs"],
+            "workspace_bytes": P.ff_global_column_attention_workspace_bytes(desc), "kernels": rows}
+
+
 def time_layernorm(steps):
     """ff_layernorm alone (the stand-alone entry point; inside the attention the LayerNorm is
     part of the projection GEMM): rows x c as in the MSA and pair representations of the
@@ -382,6 +435,7 @@ def main():
     ap.add_argument("--workload", default="c2_row_bf16_train")
     ap.add_argument("--no-others", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--global-only", action="store_true", help="time only the extra-MSA global column attention shapes")
     ap.add_argument("--trimul-only", action="store_true", help="time only the triangular multiplicative update shapes")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy 5 times (reference for HBM traffic counters)")
@@ -405,6 +459,10 @@ def main():
         del src, dst
 
     measured = calibrate()
+    if args.global_only:
+        print(json.dumps({name: time_global(name, st, 3, measured) for name, st in
+                          (("gca_bf16_1024x384", args.steps), ("gca_bf16_5120x384", max(args.steps // 5, 3)))}))
+        return
     if args.trimul_only:
         print(json.dumps({name: time_trimul(name, st, 3, measured) for name, st in
                           (("tm_out_bf16_256", args.steps), ("tm_in_bf16_256", args.steps), ("tm_out_bf16_384", args.steps),
@@ -477,6 +535,11 @@ def main():
                                          if k in r} for r in kernel_rooflines(c2.spec, k2, st, measured)]}
             del c2
             torch.cuda.empty_cache()
+        # the extra-MSA global column attention at the paper's two extra-MSA sizes
+        line["global_column_attention"] = {
+            name: time_global(name, st, wu, measured)
+            for name, st, wu in (("gca_bf16_1024x384", max(args.steps // 4, 5), 3), ("gca_bf16_5120x384", max(args.steps // 20, 3), 1))}
+        torch.cuda.empty_cache()
         line["others"] = others
         # the pair stack's triangular multiplicative update at the paper's shapes
         line["triangle_multiplication"] = {

@@ -189,6 +189,46 @@ ff_status ff_triangle_multiplication(const ff_trimul_desc* desc, const ff_trimul
                                      const void* z, const float* mask, void* out, int32_t residual,
                                      void* ws, size_t ws_bytes, void* hip_stream);
 
+/* Global column attention of the extra-MSA stack (Table 1 gives its size, N_extra_seq = 1024 / 5120;
+ * Section 6.2 names the extra MSA among the model's optional modules; the algorithm is AlphaFold's
+ * published MSA column global self-attention).  Per residue column i, with mn = LayerNorm(m):
+ *   qbar[i]    = mean of mn[s,i,:] over the unmasked sequences s
+ *   q[i,h,:]   = (w_q qbar[i])[h] / sqrt(head_dim)          heads x head_dim, no bias
+ *   k[s,i,:]   = w_k mn[s,i],  v[s,i,:] = w_v mn[s,i]        ONE shared head of head_dim channels, no bias
+ *   P[i,h,:]   = softmax over s of q[i,h] . k[s,i]           masked sequences: weight exactly 0
+ *   o[i,h,:]   = sum_s P[i,h,s] v[s,i,:]
+ *   out[s,i,:] = w_o (sigmoid(w_g mn[s,i] + b_g) * concat_h o[i,h]) + b_o
+ * A column without unmasked sequences gets zero context (out = b_o).  k, v, the softmax and o are
+ * float32; the normalised tokens, the folded weights and the gated context are bfloat16 operands. */
+typedef struct {
+    int32_t dtype;      /* ff_dtype; FF_BF16 only (FF_F32 -> FF_EUNSUPPORTED) */
+    int32_t n_seq;      /* m and out are [n_seq, n_res, c] */
+    int32_t n_res;
+    int32_t c;          /* multiple of 32, <= 128 */
+    int32_t heads;      /* heads * head_dim in {32, 64, 128} */
+    int32_t head_dim;   /* 8 or 16 */
+    float   ln_eps;
+} ff_global_desc;
+
+typedef struct {
+    const void *ln_g, *ln_b;      /* [c]                                         */
+    const void *w_q;              /* [heads*head_dim, c]                         */
+    const void *w_k, *w_v;        /* [head_dim, c]                               */
+    const void *w_g, *b_g;        /* [heads*head_dim, c], [heads*head_dim]       */
+    const void *w_o, *b_o;        /* [c, heads*head_dim], [c]                    */
+} ff_global_weights;
+
+/* Bytes of device workspace (k and v of every token in float32, partial query sums, folded weights);
+ * 0 if desc is invalid or unsupported (ff_last_error says why). */
+size_t ff_global_column_attention_workspace_bytes(const ff_global_desc* desc);
+
+/*   m    [n_seq, n_res, c], 16-byte aligned;  mask [n_seq, n_res] float32 of 0/1 or NULL (= all ones)
+ *   out  [n_seq, n_res, c], must not overlap m or ws;  ws 256-byte aligned, at least the size above
+ * Errors as for the other entry points. */
+ff_status ff_global_column_attention(const ff_global_desc* desc, const ff_global_weights* w,
+                                     const void* m, const float* mask, void* out,
+                                     void* ws, size_t ws_bytes, void* hip_stream);
+
 /* For callers that cannot allocate: code under HIP graph capture, tight serving loops and
  * harnesses that forbid hipMalloc, which therefore have no workspace to hand over.
  * The same module as ff_attention_chunked, with the workspace taken from a device array that is

@@ -43,6 +43,18 @@ class TriMulWeights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in TRIMUL_FIELDS]
 
 
+GLOBAL_FIELDS = ("ln_g", "ln_b", "w_q", "w_k", "w_v", "w_g", "b_g", "w_o", "b_o")
+
+
+class GlobalDesc(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("n_seq", C.c_int32), ("n_res", C.c_int32), ("c", C.c_int32), ("heads", C.c_int32),
+                ("head_dim", C.c_int32), ("ln_eps", C.c_float)]
+
+
+class GlobalWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in GLOBAL_FIELDS]
+
+
 class FFError(RuntimeError):
     def __init__(self, status: int, message: str):
         super().__init__(f"libff status {status}: {message}")
@@ -84,6 +96,11 @@ def lib() -> C.CDLL:
         L.ff_triangle_multiplication.restype = C.c_int
         L.ff_triangle_multiplication.argtypes = [C.POINTER(TriMulDesc), C.POINTER(TriMulWeights), C.c_void_p, C.c_void_p,
                                                  C.c_void_p, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.ff_global_column_attention_workspace_bytes.restype = C.c_size_t
+        L.ff_global_column_attention_workspace_bytes.argtypes = [C.POINTER(GlobalDesc)]
+        L.ff_global_column_attention.restype = C.c_int
+        L.ff_global_column_attention.argtypes = [C.POINTER(GlobalDesc), C.POINTER(GlobalWeights), C.c_void_p, C.c_void_p,
+                                                 C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.ff_attention_path.restype = C.c_char_p
         L.ff_attention_path.argtypes = [C.POINTER(AttnDesc)]
         L.ff_attention_last_path.restype = C.c_char_p
@@ -259,6 +276,31 @@ def ff_triangle_multiplication(desc: TriMulDesc, w: Dict[str, "object"], z, mask
     return out
 
 
+def ff_global_column_attention_workspace_bytes(desc: GlobalDesc) -> int:
+    n = lib().ff_global_column_attention_workspace_bytes(C.byref(desc))
+    if n == 0:
+        raise FFError(FF_EINVAL, last_error())
+    return n
+
+
+def ff_global_column_attention(desc: GlobalDesc, w: Dict[str, "object"], m, mask=None, out=None, ws=None):
+    """Global column attention of the extra-MSA stack; m [n_seq, n_res, c]; returns out."""
+    import torch
+    assert m.is_cuda and m.is_contiguous()
+    if out is None:
+        out = torch.empty_like(m)
+    if ws is None:
+        ws = _alloc_ws(ff_global_column_attention_workspace_bytes(desc), m.device)
+    wts = GlobalWeights()
+    for n in GLOBAL_FIELDS:
+        t = w[n]
+        assert t.is_contiguous() and t.is_cuda
+        setattr(wts, n, _ptr(t))
+    _check(lib().ff_global_column_attention(C.byref(desc), C.byref(wts), _ptr(m), _ptr(mask), _ptr(out), _ptr(ws),
+                                            ws.numel(), _stream()))
+    return out
+
+
 def ff_gated_attention_residual(desc: AttnDesc, w: Dict[str, "object"], x, z=None, mask=None, chunk_rows: int = 0,
                                 out=None, ws=None, in_place: bool = False):
     """x + module(x); chunk_rows = 0 takes all batch rows at once.  in_place=True updates x itself."""
@@ -320,6 +362,13 @@ def trimul_to_device(case, device="cuda:0"):
     sp = case.spec
     desc = TriMulDesc(FF_F32 if sp.dtype == "f32" else FF_BF16, 1 if sp.incoming else 0, sp.n, sp.c_z, sp.c, sp.ln_eps)
     return desc, {k: _upload(v, device) for k, v in case.weights.items()}, _upload(case.z, device), _upload(case.mask, device)
+
+
+def global_to_device(case, device="cuda:0"):
+    """Upload a seeded global-column-attention case (inputs.GlobalCase).  Returns (desc, weights, m, mask)."""
+    sp = case.spec
+    desc = GlobalDesc(FF_F32 if sp.dtype == "f32" else FF_BF16, sp.n_seq, sp.n_res, sp.c, sp.heads, sp.head_dim, sp.ln_eps)
+    return desc, {k: _upload(v, device) for k, v in case.weights.items()}, _upload(case.m, device), _upload(case.mask, device)
 
 
 def to_device(case, device="cuda:0"):

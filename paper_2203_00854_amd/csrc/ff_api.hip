@@ -19,7 +19,8 @@ static std::vector<ProfRec> g_prof;
 static std::vector<hipEvent_t> g_prof_pool;
 static const char* kKindNames[KK_COUNT] = {"k_prep", "pair bias pass", "k_gemm<PROJ>", "k_attn",
                                            "k_gemm<OUT>", "k_layernorm", "generic family", "probe: mfma loop",
-                                           "probe: copy", "k_tm_prep", "k_tm_proj", "k_tm_mul", "k_tm_out"};
+                                           "probe: copy", "k_tm_prep", "k_tm_proj", "k_tm_mul", "k_tm_out",
+                                           "k_gca_prep", "k_gca_kv", "k_gca_softmax", "k_gca_out"};
 
 static hipEvent_t prof_event() {
     if (!g_prof_pool.empty()) {
@@ -282,6 +283,46 @@ ff_status ff_triangle_multiplication(const ff_trimul_desc* desc, const ff_trimul
     if (overlaps(out, z_bytes, ws, need) || overlaps(z, z_bytes, ws, need))
         return fail(FF_EINVAL, "z and out must not overlap the workspace");
     return trimul_run(*desc, *w, z, mask, residual != 0, out, ws, (hipStream_t)hip_stream);
+}
+
+static ff_status check_global(const ff_global_desc* d) {
+    if (!d) return fail(FF_EINVAL, "desc is NULL");
+    if (d->dtype != FF_F32 && d->dtype != FF_BF16) return fail(FF_EINVAL, "bad dtype %d", d->dtype);
+    if (d->n_seq < 1 || d->n_res < 1 || d->c < 1 || d->heads < 1 || d->head_dim < 1)
+        return fail(FF_EINVAL, "non-positive size (n_seq=%d n_res=%d c=%d heads=%d head_dim=%d)", d->n_seq, d->n_res, d->c,
+                    d->heads, d->head_dim);
+    if (!(d->ln_eps >= 0.f)) return fail(FF_EINVAL, "ln_eps must be >= 0");
+    if ((int64_t)d->n_seq * d->n_res > ((int64_t)1 << 31) - 1) return fail(FF_EUNSUPPORTED, "more than 2^31 tokens");
+    if (!global_supported(*d))
+        return fail(FF_EUNSUPPORTED, "global column attention: bfloat16 only, c a multiple of 32 up to 128, head_dim 8 or 16, "
+                                     "heads*head_dim 32, 64 or 128 (got dtype %d, c %d, heads %d, head_dim %d)",
+                    d->dtype, d->c, d->heads, d->head_dim);
+    return FF_OK;
+}
+
+size_t ff_global_column_attention_workspace_bytes(const ff_global_desc* desc) {
+    if (check_global(desc) != FF_OK) return 0;
+    return global_workspace(*desc);
+}
+
+ff_status ff_global_column_attention(const ff_global_desc* desc, const ff_global_weights* w, const void* m,
+                                     const float* mask, void* out, void* ws, size_t ws_bytes, void* hip_stream) {
+    ff_status st = check_global(desc);
+    if (st != FF_OK) return st;
+    if (!w || !m || !out) return fail(FF_EINVAL, "weights, m or out is NULL");
+    const void* wp[] = {w->ln_g, w->ln_b, w->w_q, w->w_k, w->w_v, w->w_g, w->b_g, w->w_o, w->b_o};
+    for (const void* q : wp)
+        if (!q) return fail(FF_EINVAL, "a weight pointer is NULL");
+    if (!aligned16(m) || !aligned16(out)) return fail(FF_EINVAL, "m and out must be 16-byte aligned");
+    const size_t m_bytes = (size_t)desc->n_seq * desc->n_res * desc->c * 2;
+    if (overlaps(out, m_bytes, m, m_bytes)) return fail(FF_EINVAL, "out must not overlap m");
+    const size_t need = global_workspace(*desc);
+    if (!ws) return fail(FF_EINVAL, "workspace is NULL (%zu bytes needed)", need);
+    if (((uintptr_t)ws & 255u) != 0) return fail(FF_EINVAL, "workspace must be 256-byte aligned");
+    if (ws_bytes < need) return fail(FF_EWORKSPACE, "workspace too small: %zu bytes given, %zu needed", ws_bytes, need);
+    if (overlaps(out, m_bytes, ws, need) || overlaps(m, m_bytes, ws, need))
+        return fail(FF_EINVAL, "m and out must not overlap the workspace");
+    return global_run(*desc, *w, m, mask, out, ws, (hipStream_t)hip_stream);
 }
 
 size_t ff_attention_workspace_bytes(const ff_attn_desc* desc, int32_t chunk_rows) {

@@ -69,7 +69,8 @@ struct Workspace {
 
 // kernel kinds for the launch timer (ff_profile_* in the C ABI)
 enum KernelKind { KK_PREP = 0, KK_BIAS, KK_PROJ, KK_ATTN, KK_OUT, KK_LAYERNORM, KK_GENERIC, KK_PROBE_MFMA, KK_PROBE_COPY,
-                  KK_TM_PREP, KK_TM_PROJ, KK_TM_MUL, KK_TM_OUT, KK_COUNT };
+                  KK_TM_PREP, KK_TM_PROJ, KK_TM_MUL, KK_TM_OUT, KK_GCA_PREP, KK_GCA_KV, KK_GCA_SOFTMAX, KK_GCA_OUT,
+                  KK_COUNT };
 void prof_begin(int kind, hipStream_t st);
 void prof_end(int kind, hipStream_t st);
 // brackets the launches issued in its scope with HIP events when the timer is on
@@ -114,6 +115,12 @@ size_t trimul_workspace(int N, int cz, int c);
 // residual: z is added to the module's output (out may then be z itself)
 ff_status trimul_run(const ff_trimul_desc& d, const ff_trimul_weights& w, const void* z, const float* mask, bool residual,
                      void* out, void* ws, hipStream_t stream);
+
+// global column attention of the extra-MSA stack (ff_global.hip), bf16 only
+bool global_supported(const ff_global_desc& d);
+size_t global_workspace(const ff_global_desc& d);
+ff_status global_run(const ff_global_desc& d, const ff_global_weights& w, const void* m, const float* mask, void* out,
+                     void* ws, hipStream_t stream);
 
 // LayerNorm (ff_layernorm.hip)
 ff_status layernorm_launch(const void* x, const void* g, const void* b, void* y, int64_t rows, int c,

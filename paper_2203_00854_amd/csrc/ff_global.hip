@@ -1,0 +1,625 @@
+// Global column attention of the extra-MSA stack (FastFold Table 1: N_extra_seq 1024 / 5120; Section 6.2 lists
+// the extra MSA among the optional modules; the algorithm is AlphaFold's published MSA column global
+// self-attention), bf16, gfx950.  Per residue column i, with mn = LayerNorm(m):
+//   qbar[i] = mean over unmasked s of mn[s,i];  q[i,h] = (W_q qbar[i])[h] / sqrt(d);  k[s,i] = W_k mn[s,i];
+//   v[s,i] = W_v mn[s,i] (one shared head);  P[i,h,:] = softmax_s(q[i,h] . k[s,i]) over unmasked s;
+//   o[i,h] = sum_s P[i,h,s] v[s,i];  out[s,i] = W_o (sigmoid(W_g mn[s,i] + b_g) * o[i]) + b_o
+//
+// The module is linear in N_seq and moves far more bytes than it computes: two reads of m and one write of
+// out bound it (HBM).  Four launches:
+//   k_gca_prep     folds the LayerNorm gain into the weights (W' = bf16(W * gamma), C = W beta (+ bias)) and
+//                  writes W_o in the operand order of the last contraction
+//   k_gca_kv       one wavefront per (column, 256 sequences): 32 sequences at a time it normalises the tokens
+//                  into bf16 operand fragments (masked ones as zeros) and contracts them with W_q' (tokens x
+//                  features, so that the sum over the tile's sequences - the query average - is a sum over the
+//                  lane's own registers) and with W_k' | W_v' (features x tokens: k, v of a token leave as
+//                  float32); partial query sums and counts go to the workspace
+//   k_gca_softmax  one block per column, one thread per sequence with all heads in registers: q from the partial
+//                  sums, two sweeps over k (maximum; exponentials, denominators, weighted sums of v), o[i] normalised
+//   k_gca_out      one wavefront per (sequence, 32 residues): gate GEMM, sigmoid, times o[i] (the gated tile is
+//                  already the B operand of the output GEMM because W_o was stored in the matching order),
+//                  output GEMM, + b_o
+// Operand layouts of v_mfma_f32_32x32x16_bf16 as in ff_trimul.hip.
+#include "ff_common.h"
+
+namespace ff {
+namespace gca {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+union Frag {
+    bf16x8 v;
+    uint4 u;
+    uint32_t w[4];
+};
+
+__device__ __forceinline__ uint32_t pack2(float a, float b) {
+    bf16x2 t;
+    t[0] = (__bf16)a;
+    t[1] = (__bf16)b;
+    return __builtin_bit_cast(uint32_t, t);
+}
+__device__ __forceinline__ float lo_f32(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float hi_f32(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+__device__ __forceinline__ float sigmoid(float t) {
+    return __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-t * kLog2e));
+}
+__device__ __forceinline__ float pick(const float4& q, int e) { return e == 0 ? q.x : (e == 1 ? q.y : (e == 2 ? q.z : q.w)); }
+
+static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+constexpr int kChunk = 256;      // sequences per wavefront of k_gca_kv
+
+// Normalised operand fragments of the lane's token: xn = bf16((x - mean) * rstd) (the LayerNorm gain and
+// offset live in the folded weights), or zeros if !keep.  Two passes over the registers for the statistics.
+template <int KC>
+__device__ __forceinline__ void normalise(Frag (&xa)[KC], int K, int hf, float eps, bool keep) {
+    float sum = 0.f;
+#pragma unroll
+    for (int s = 0; s < KC; ++s)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sum += lo_f32(xa[s].w[i]) + hi_f32(xa[s].w[i]);   // (channels beyond K are zero)
+    sum += __shfl_xor(sum, 32, 64);
+    const float mean = sum / (float)K;
+    float sq = 0.f;
+#pragma unroll
+    for (int s = 0; s < KC; ++s)
+        if (16 * s + 8 * hf < K) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float d0 = lo_f32(xa[s].w[i]) - mean, d1 = hi_f32(xa[s].w[i]) - mean;
+                sq += d0 * d0 + d1 * d1;
+            }
+        }
+    sq += __shfl_xor(sq, 32, 64);
+    const float rstd = keep ? rsqrtf(sq / (float)K + eps) : 0.f;
+#pragma unroll
+    for (int s = 0; s < KC; ++s) {
+        const bool in = 16 * s + 8 * hf < K;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float a = (lo_f32(xa[s].w[i]) - mean) * rstd, b = (hi_f32(xa[s].w[i]) - mean) * rstd;
+            xa[s].w[i] = in ? pack2(a, b) : 0u;
+        }
+    }
+}
+
+// ====================================================================================
+struct PrepArgs {
+    const bf16_t *w_q, *w_k, *w_v, *w_g, *b_g, *w_o, *b_o, *ln_g, *ln_b;
+    bf16_t *wq, *wkv, *wg, *wo;       // [Hd][Kp], [32][Kp], [Hd][Kp], [c][Hd] (operand order)
+    float *Cq, *Ckv, *Cg, *Co;        // [Hd], [32], [Hd], [c]
+    int c, Hd, d, Kp;
+};
+
+// one wavefront per row of the three folded matrices; the rows after them copy W_o and b_o
+__global__ __launch_bounds__(256) void k_gca_prep(PrepArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int rows_fold = 2 * a.Hd + 32;
+    if (n < rows_fold) {
+        const bf16_t* wrow = nullptr;
+        float bias = 0.f;
+        bf16_t* dst;
+        float* Cd;
+        if (n < a.Hd) {
+            wrow = a.w_q + (size_t)n * a.c; dst = a.wq + (size_t)n * a.Kp; Cd = a.Cq + n;
+        } else if (n < a.Hd + 32) {
+            const int r = n - a.Hd;               // rows 0 .. d-1: keys, 16 .. 16+d-1: values, others zero
+            if (r < a.d) wrow = a.w_k + (size_t)r * a.c;
+            else if (r >= 16 && r < 16 + a.d) wrow = a.w_v + (size_t)(r - 16) * a.c;
+            dst = a.wkv + (size_t)r * a.Kp; Cd = a.Ckv + r;
+        } else {
+            const int f = n - a.Hd - 32;
+            wrow = a.w_g + (size_t)f * a.c; bias = bf16_to_f32(a.b_g[f]);
+            dst = a.wg + (size_t)f * a.Kp; Cd = a.Cg + f;
+        }
+        float cst = 0.f;
+        for (int k = lane; k < a.Kp; k += 64) {
+            float r = 0.f;
+            if (wrow && k < a.c) {
+                const float w = bf16_to_f32(wrow[k]);
+                r = w * bf16_to_f32(a.ln_g[k]);
+                cst += w * bf16_to_f32(a.ln_b[k]);
+            }
+            dst[k] = f32_to_bf16(r);
+        }
+        cst = wave_sum(cst);
+        if (lane == 0) *Cd = cst + bias;
+        return;
+    }
+    const int co = n - rows_fold;
+    if (co >= a.c) return;
+    // Slot u of half hf of contraction step (T, j) of the output GEMM holds gated feature
+    // 32T + 16j + 4hf + (u < 4 ? u : u + 4): that is where the gate GEMM's accumulator leaves it.
+    for (int x = lane; x < a.Hd; x += 64) {
+        const int T = x >> 5, j = (x >> 4) & 1, hf = (x >> 3) & 1, u = x & 7;
+        const int f = 32 * T + 16 * j + 4 * hf + (u < 4 ? u : u + 4);
+        a.wo[(size_t)co * a.Hd + x] = a.w_o[(size_t)co * a.Hd + f];
+    }
+    if (lane == 0) a.Co[co] = bf16_to_f32(a.b_o[co]);
+}
+
+// ====================================================================================
+struct KvArgs {
+    const bf16_t* m;         // [S][R][c]
+    const float* mask;       // [S][R] or NULL
+    int S, R, c, Hd, d, nchunk;
+    float eps;
+    const bf16_t *wq, *wkv;  // folded, pitch 16 KC
+    const float* Ckv;
+    float* kv;               // [R][S][2d]: k then v of a token, float32
+    float* qpart;            // [R][nchunk][Hd]
+    float* cntpart;          // [R][nchunk]
+};
+
+template <int KC, int D>
+__global__ __launch_bounds__(256) void k_gca_kv(KvArgs p) {
+    constexpr int PITCH = KC * 32 + 16;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    unsigned char* s_wq = smem;                                  // [Hd][PITCH]
+    unsigned char* s_wkv = smem + (size_t)p.Hd * PITCH;          // [32][PITCH]
+    const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    for (int id = tid; id < (p.Hd + 32) * 2 * KC; id += 256) {
+        const int row = id / (2 * KC), pc = id - row * (2 * KC);
+        const bf16_t* src = row < p.Hd ? p.wq + (size_t)row * (16 * KC) : p.wkv + (size_t)(row - p.Hd) * (16 * KC);
+        *reinterpret_cast<uint4*>(smem + row * PITCH + pc * 16) = *reinterpret_cast<const uint4*>(src + pc * 8);
+    }
+    __syncthreads();
+
+    const int task = blockIdx.x * 4 + wave;
+    if (task >= p.R * p.nchunk) return;          // (no barrier after this point)
+    const int i = task / p.nchunk, ck = task - i * p.nchunk;
+    const int s_begin = ck * kChunk;
+    int s_end = s_begin + kChunk;
+    if (s_end > p.S) s_end = p.S;
+    const int n_qt = p.Hd >> 5;                  // 32-feature tiles of the query projection (at most 4)
+    float qacc0 = 0.f, qacc1 = 0.f, qacc2 = 0.f, qacc3 = 0.f;
+    float cnt = 0.f;
+    // offsets of the lane's key / value rows (read once: a load inside the loop would wait for the stores before it)
+    const float4 ckv0 = *reinterpret_cast<const float4*>(p.Ckv + 4 * hf), ckv1 = *reinterpret_cast<const float4*>(p.Ckv + 8 + 4 * hf);
+    const float4 ckv2 = *reinterpret_cast<const float4*>(p.Ckv + 16 + 4 * hf), ckv3 = *reinterpret_cast<const float4*>(p.Ckv + 24 + 4 * hf);
+
+    for (int s0 = s_begin; s0 < s_end; s0 += 32) {
+        const int s = s0 + col;
+        const bool valid = s < s_end;
+        const size_t tok = (size_t)(valid ? s : s_begin) * p.R + i;
+        Frag xa[KC];
+        {
+            const bf16_t* mp = p.m + tok * p.c;
+#pragma unroll
+            for (int q = 0; q < KC; ++q) {
+                xa[q].u = make_uint4(0, 0, 0, 0);
+                if (valid && 16 * q + 8 * hf < p.c) xa[q].u = *reinterpret_cast<const uint4*>(mp + 16 * q + 8 * hf);
+            }
+        }
+        const bool keep = valid && (p.mask ? p.mask[tok] != 0.f : true);
+        normalise<KC>(xa, p.c, hf, p.eps, keep);
+        cnt += (float)__builtin_popcountll(__ballot(keep && hf == 0));
+
+        // query sums: tokens x features, the lane owns a feature and its 16 registers are 16 of the tile's sequences
+#pragma unroll
+        for (int T = 0; T < 4; ++T) {
+            if (T < n_qt) {
+                f32x16 acc;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+#pragma unroll
+                for (int q = 0; q < KC; ++q) {
+                    Frag wf;
+                    wf.u = *reinterpret_cast<const uint4*>(s_wq + (32 * T + col) * PITCH + (2 * q + hf) * 16);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[q].v, wf.v, acc, 0, 0, 0);
+                }
+                float t = 0.f;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) t += acc[v];
+                if (T == 0) qacc0 += t;
+                else if (T == 1) qacc1 += t;
+                else if (T == 2) qacc2 += t;
+                else qacc3 += t;
+            }
+        }
+        // keys and values: features x tokens, the lane owns a token; rows 0 .. D-1 keys, 16 .. 16+D-1 values
+        {
+            f32x16 acc;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+#pragma unroll
+            for (int q = 0; q < KC; ++q) {
+                Frag wf;
+                wf.u = *reinterpret_cast<const uint4*>(s_wkv + col * PITCH + (2 * q + hf) * 16);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf.v, xa[q].v, acc, 0, 0, 0);
+            }
+            float* dst = p.kv + ((size_t)i * p.S + (valid ? s : s_begin)) * (2 * D);
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int row = 8 * g + 4 * hf;                  // rows row .. row + 3 of the tile
+                const bool is_v = row >= 16;
+                const int e0 = is_v ? row - 16 : row;            // first key / value channel of the group
+                if (e0 < D) {
+                    const float4 c4 = g == 0 ? ckv0 : (g == 1 ? ckv1 : (g == 2 ? ckv2 : ckv3));
+                    const float4 o = make_float4(acc[4 * g] + c4.x, acc[4 * g + 1] + c4.y, acc[4 * g + 2] + c4.z, acc[4 * g + 3] + c4.w);
+                    if (valid) *reinterpret_cast<float4*>(dst + (is_v ? D : 0) + e0) = o;
+                }
+            }
+        }
+    }
+    qacc0 += __shfl_xor(qacc0, 32, 64);
+    qacc1 += __shfl_xor(qacc1, 32, 64);
+    qacc2 += __shfl_xor(qacc2, 32, 64);
+    qacc3 += __shfl_xor(qacc3, 32, 64);
+    if (hf == 0) {
+        float* qp = p.qpart + (size_t)task * p.Hd + col;
+        qp[0] = qacc0;
+        if (n_qt > 1) qp[32] = qacc1;
+        if (n_qt > 2) qp[64] = qacc2;
+        if (n_qt > 3) qp[96] = qacc3;
+    }
+    if (lane == 0) p.cntpart[task] = cnt;
+}
+
+// ====================================================================================
+struct SmArgs {
+    const float* kv;         // [R][S][2d]
+    const float* mask;       // [S][R] or NULL
+    const float *qpart, *cntpart, *Cq;
+    float* o;                // [R][Hd]
+    int S, R, Hd, H, nchunk;
+    float qscale;            // log2(e) / sqrt(d)
+};
+
+// Block = one column, one thread per sequence (s = tid, tid + 256, ...) holding all H heads: k and v of a
+// sequence are read once per sweep, the H logits, H denominators and H x D weighted sums live in registers
+// (hence H and D as template parameters), and the block combines them through shuffles and LDS.
+template <int H, int D>
+__global__ __launch_bounds__(256) void k_gca_softmax(SmArgs p) {
+    constexpr int HD = H * D;
+    __shared__ float s_q[HD];
+    __shared__ float s_red[4 * (HD + H)];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, i = blockIdx.x;
+    float cnt = 0.f;
+    for (int j = 0; j < p.nchunk; ++j) cnt += p.cntpart[(size_t)i * p.nchunk + j];
+    if (cnt == 0.f) {                              // no unmasked sequence: zero context (uniform over the block)
+        if (tid < HD) p.o[(size_t)i * HD + tid] = 0.f;
+        return;
+    }
+    if (tid < HD) {
+        float q = 0.f;
+        for (int j = 0; j < p.nchunk; ++j) q += p.qpart[((size_t)i * p.nchunk + j) * HD + tid];
+        s_q[tid] = (q / cnt + p.Cq[tid]) * p.qscale;
+    }
+    __syncthreads();
+    const float* kvc = p.kv + (size_t)i * p.S * (2 * D);
+
+    // sweep 1: maximum of every head's logits over the unmasked sequences
+    float mx[H];
+#pragma unroll
+    for (int h = 0; h < H; ++h) mx[h] = -INFINITY;
+    for (int s = tid; s < p.S; s += 256) {
+        if (p.mask && p.mask[(size_t)s * p.R + i] == 0.f) continue;
+        float k[D];
+        const float4* kp = reinterpret_cast<const float4*>(kvc + (size_t)s * (2 * D));
+#pragma unroll
+        for (int e4 = 0; e4 < D / 4; ++e4) {
+            const float4 k4 = kp[e4];
+            k[4 * e4] = k4.x; k[4 * e4 + 1] = k4.y; k[4 * e4 + 2] = k4.z; k[4 * e4 + 3] = k4.w;
+        }
+#pragma unroll
+        for (int h = 0; h < H; ++h) {
+            float l = 0.f;
+#pragma unroll
+            for (int e = 0; e < D; ++e) l += s_q[h * D + e] * k[e];
+            mx[h] = fmaxf(mx[h], l);
+        }
+    }
+#pragma unroll
+    for (int h = 0; h < H; ++h) {
+        mx[h] = wave_max(mx[h]);
+        if (lane == 0) s_red[wave * H + h] = mx[h];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int h = 0; h < H; ++h)      // (at least one sequence of the column is unmasked: finite)
+        mx[h] = fmaxf(fmaxf(s_red[h], s_red[H + h]), fmaxf(s_red[2 * H + h], s_red[3 * H + h]));
+    __syncthreads();
+
+    // sweep 2: exponentials, denominators, weighted sums of v
+    float den[H], o[HD];
+#pragma unroll
+    for (int h = 0; h < H; ++h) den[h] = 0.f;
+#pragma unroll
+    for (int f = 0; f < HD; ++f) o[f] = 0.f;
+    for (int s = tid; s < p.S; s += 256) {
+        if (p.mask && p.mask[(size_t)s * p.R + i] == 0.f) continue;
+        float k[D], v[D];
+        const float4* kp = reinterpret_cast<const float4*>(kvc + (size_t)s * (2 * D));
+#pragma unroll
+        for (int e4 = 0; e4 < D / 4; ++e4) {
+            const float4 k4 = kp[e4], v4 = kp[D / 4 + e4];
+            k[4 * e4] = k4.x; k[4 * e4 + 1] = k4.y; k[4 * e4 + 2] = k4.z; k[4 * e4 + 3] = k4.w;
+            v[4 * e4] = v4.x; v[4 * e4 + 1] = v4.y; v[4 * e4 + 2] = v4.z; v[4 * e4 + 3] = v4.w;
+        }
+#pragma unroll
+        for (int h = 0; h < H; ++h) {
+            float l = 0.f;
+#pragma unroll
+            for (int e = 0; e < D; ++e) l += s_q[h * D + e] * k[e];
+            const float w = __builtin_amdgcn_exp2f(l - mx[h]);
+            den[h] += w;
+#pragma unroll
+            for (int e = 0; e < D; ++e) o[h * D + e] += w * v[e];
+        }
+    }
+#pragma unroll
+    for (int h = 0; h < H; ++h) {
+        den[h] = wave_sum(den[h]);
+        if (lane == 0) s_red[wave * (HD + H) + HD + h] = den[h];
+    }
+#pragma unroll
+    for (int f = 0; f < HD; ++f) {
+        o[f] = wave_sum(o[f]);
+        if (lane == 0) s_red[wave * (HD + H) + f] = o[f];
+    }
+    __syncthreads();
+    if (tid < HD) {
+        const int h = tid / D;
+        float so = 0.f, sd = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            so += s_red[w * (HD + H) + tid];
+            sd += s_red[w * (HD + H) + HD + h];
+        }
+        p.o[(size_t)i * HD + tid] = so / sd;
+    }
+}
+
+// ====================================================================================
+struct OutArgs {
+    const bf16_t* m;         // [S][R][c]
+    bf16_t* out;             // [S][R][c]
+    const float* o;          // [R][Hd]
+    int S, R, c, Hd;
+    float eps;
+    const bf16_t *wg, *wo;   // folded gate weights (pitch 16 KC); W_o in operand order [c][Hd]
+    const float *Cg, *Co;
+};
+
+template <int KC>
+__global__ __launch_bounds__(256) void k_gca_out(OutArgs p) {
+    constexpr int PITCH = KC * 32 + 16;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int po = p.Hd * 2 + 16;                                // bytes per row of W_o in LDS
+    unsigned char* s_wg = smem;                                  // [Hd][PITCH]
+    unsigned char* s_wo = smem + (size_t)p.Hd * PITCH;           // [c][po]
+    float* s_cg = reinterpret_cast<float*>(s_wo + (size_t)p.c * po);   // [Hd] gate offsets
+    float* s_co = s_cg + p.Hd;                                   // [c]  output bias
+    const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    for (int id = tid; id < p.Hd; id += 256) s_cg[id] = p.Cg[id];
+    for (int id = tid; id < p.c; id += 256) s_co[id] = p.Co[id];
+    for (int id = tid; id < p.Hd * 2 * KC; id += 256) {
+        const int row = id / (2 * KC), pc = id - row * (2 * KC);
+        *reinterpret_cast<uint4*>(s_wg + row * PITCH + pc * 16) = *reinterpret_cast<const uint4*>(p.wg + (size_t)row * (16 * KC) + pc * 8);
+    }
+    const int opr = p.Hd >> 3;                                   // 16-byte pieces per row of W_o
+    for (int id = tid; id < p.c * opr; id += 256) {
+        const int row = id / opr, pc = id - row * opr;
+        *reinterpret_cast<uint4*>(s_wo + row * po + pc * 16) = *reinterpret_cast<const uint4*>(p.wo + (size_t)row * p.Hd + pc * 8);
+    }
+    __syncthreads();
+
+    // a tile = 32 consecutive residues of one sequence: 32 c contiguous elements of m and of out
+    const int tpr = (p.R + 31) >> 5;             // residue tiles per sequence
+    const int n_gt = p.Hd >> 5, n_ct = p.c >> 5; // gate tiles, output tiles (at most 4 each)
+    for (int task = blockIdx.x * 4 + wave; task < p.S * tpr; task += gridDim.x * 4) {
+        const int s = task / tpr, i_raw = (task - s * tpr) * 32 + col;
+        const bool valid = i_raw < p.R;
+        const int i = valid ? i_raw : p.R - 1;
+        const size_t tok = (size_t)s * p.R + i;
+        Frag xa[KC];
+        {
+            const bf16_t* mp = p.m + tok * p.c;
+#pragma unroll
+            for (int q = 0; q < KC; ++q) {
+                xa[q].u = make_uint4(0, 0, 0, 0);
+                if (valid && 16 * q + 8 * hf < p.c) xa[q].u = *reinterpret_cast<const uint4*>(mp + 16 * q + 8 * hf);
+            }
+        }
+        // o[i] of the lane's residue, every group of four features it will meet (issued before anything waits)
+        const float* oi = p.o + (size_t)i * p.Hd;
+        float4 o4[4][4];
+#pragma unroll
+        for (int T = 0; T < 4; ++T)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                o4[T][g] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (T < n_gt) o4[T][g] = *reinterpret_cast<const float4*>(oi + 32 * T + 8 * g + 4 * hf);
+            }
+        normalise<KC>(xa, p.c, hf, p.eps, valid);
+
+        // gate: features x tokens; value of feature 32T + 8g + 4hf + e in register 4g + e, times o[i][feature];
+        // registers 8j .. 8j+7 of tile T packed are the B operand of contraction step 2T + j of the output GEMM
+        Frag gf[8];
+#pragma unroll
+        for (int T = 0; T < 4; ++T) {
+            if (T < n_gt) {
+                f32x16 acc;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+#pragma unroll
+                for (int q = 0; q < KC; ++q) {
+                    Frag wf;
+                    wf.u = *reinterpret_cast<const uint4*>(s_wg + (32 * T + col) * PITCH + (2 * q + hf) * 16);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf.v, xa[q].v, acc, 0, 0, 0);
+                }
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int f0 = 32 * T + 8 * g + 4 * hf;
+                    const float4 c4 = *reinterpret_cast<const float4*>(s_cg + f0);
+                    float t[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) t[e] = sigmoid(acc[4 * g + e] + pick(c4, e)) * pick(o4[T][g], e);
+                    gf[2 * T + (g >> 1)].w[2 * (g & 1)] = pack2(t[0], t[1]);
+                    gf[2 * T + (g >> 1)].w[2 * (g & 1) + 1] = pack2(t[2], t[3]);
+                }
+            } else {
+                gf[2 * T].u = make_uint4(0, 0, 0, 0);
+                gf[2 * T + 1].u = make_uint4(0, 0, 0, 0);
+            }
+        }
+        // output projection: features x tokens again, the lane stores four consecutive channels of its token
+        bf16_t* op = p.out + tok * p.c;
+#pragma unroll
+        for (int ct = 0; ct < 4; ++ct) {
+            if (ct < n_ct) {
+                f32x16 acc;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+#pragma unroll
+                for (int kk = 0; kk < 8; ++kk) {
+                    if (kk < 2 * n_gt) {
+                        Frag wf;
+                        wf.u = *reinterpret_cast<const uint4*>(s_wo + (32 * ct + col) * po + kk * 32 + hf * 16);
+                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf.v, gf[kk].v, acc, 0, 0, 0);
+                    }
+                }
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int c0 = 32 * ct + 8 * g + 4 * hf;
+                    const float4 b4 = *reinterpret_cast<const float4*>(s_co + c0);
+                    if (valid)
+                        *reinterpret_cast<uint2*>(op + c0) = make_uint2(pack2(acc[4 * g] + b4.x, acc[4 * g + 1] + b4.y),
+                                                                        pack2(acc[4 * g + 2] + b4.z, acc[4 * g + 3] + b4.w));
+                }
+            }
+        }
+    }
+}
+
+// ====================================================================================
+struct Ws {
+    bf16_t *wq, *wkv, *wg, *wo;
+    float *Cq, *Ckv, *Cg, *Co, *kv, *qpart, *cntpart, *o;
+    size_t total;
+};
+
+static int kc_for(int K) { return K <= 32 ? 2 : (K <= 64 ? 4 : 8); }
+
+static Ws carve(const ff_global_desc& d, void* base) {
+    const int Hd = d.heads * d.head_dim, Kp = 16 * kc_for(d.c), nchunk = (d.n_seq + kChunk - 1) / kChunk;
+    char* b = (char*)base;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        char* p = b + off;
+        off += align256(bytes);
+        return p;
+    };
+    Ws w;
+    w.wq = (bf16_t*)take((size_t)Hd * Kp * 2);
+    w.wkv = (bf16_t*)take((size_t)32 * Kp * 2);
+    w.wg = (bf16_t*)take((size_t)Hd * Kp * 2);
+    w.wo = (bf16_t*)take((size_t)d.c * Hd * 2);
+    w.Cq = (float*)take((size_t)Hd * 4);
+    w.Ckv = (float*)take(32 * 4);
+    w.Cg = (float*)take((size_t)Hd * 4);
+    w.Co = (float*)take((size_t)d.c * 4);
+    w.kv = (float*)take((size_t)d.n_res * d.n_seq * 2 * d.head_dim * 4);
+    w.qpart = (float*)take((size_t)d.n_res * nchunk * Hd * 4);
+    w.cntpart = (float*)take((size_t)d.n_res * nchunk * 4);
+    w.o = (float*)take((size_t)d.n_res * Hd * 4);
+    w.total = off;
+    return w;
+}
+
+}  // namespace gca
+
+bool global_supported(const ff_global_desc& d) {
+    const int Hd = d.heads * d.head_dim;
+    return d.dtype == FF_BF16 && d.c % 32 == 0 && d.c >= 32 && d.c <= 128 && (d.head_dim == 8 || d.head_dim == 16) &&
+           (Hd == 32 || Hd == 64 || Hd == 128);
+}
+
+size_t global_workspace(const ff_global_desc& d) { return gca::carve(d, nullptr).total; }
+
+ff_status global_run(const ff_global_desc& d, const ff_global_weights& w, const void* m, const float* mask, void* out,
+                     void* ws, hipStream_t st) {
+    using namespace gca;
+    const int Hd = d.heads * d.head_dim, kc = kc_for(d.c), nchunk = (d.n_seq + kChunk - 1) / kChunk;
+    const Ws s = carve(d, ws);
+    {
+        PrepArgs a{};
+        a.w_q = (const bf16_t*)w.w_q; a.w_k = (const bf16_t*)w.w_k; a.w_v = (const bf16_t*)w.w_v; a.w_g = (const bf16_t*)w.w_g;
+        a.b_g = (const bf16_t*)w.b_g; a.w_o = (const bf16_t*)w.w_o; a.b_o = (const bf16_t*)w.b_o;
+        a.ln_g = (const bf16_t*)w.ln_g; a.ln_b = (const bf16_t*)w.ln_b;
+        a.wq = s.wq; a.wkv = s.wkv; a.wg = s.wg; a.wo = s.wo; a.Cq = s.Cq; a.Ckv = s.Ckv; a.Cg = s.Cg; a.Co = s.Co;
+        a.c = d.c; a.Hd = Hd; a.d = d.head_dim; a.Kp = 16 * kc;
+        const int rows = 2 * Hd + 32 + d.c;
+        Timed t(KK_GCA_PREP, st);
+        hipLaunchKernelGGL(k_gca_prep, dim3((rows + 3) / 4), dim3(256), 0, st, a);
+    }
+    {
+        KvArgs a{};
+        a.m = (const bf16_t*)m; a.mask = mask; a.S = d.n_seq; a.R = d.n_res; a.c = d.c; a.Hd = Hd; a.d = d.head_dim;
+        a.nchunk = nchunk; a.eps = d.ln_eps; a.wq = s.wq; a.wkv = s.wkv; a.Ckv = s.Ckv; a.kv = s.kv; a.qpart = s.qpart;
+        a.cntpart = s.cntpart;
+        const dim3 grid((d.n_res * nchunk + 3) / 4);
+        const size_t smem = (size_t)(Hd + 32) * (kc * 32 + 16);
+        Timed t(KK_GCA_KV, st);
+#define FF_GCA_KV(KCV)                                                                        \
+    do {                                                                                      \
+        if (d.head_dim == 8) hipLaunchKernelGGL((k_gca_kv<KCV, 8>), grid, dim3(256), smem, st, a);   \
+        else hipLaunchKernelGGL((k_gca_kv<KCV, 16>), grid, dim3(256), smem, st, a);                  \
+    } while (0)
+        if (kc == 2) FF_GCA_KV(2);
+        else if (kc == 4) FF_GCA_KV(4);
+        else FF_GCA_KV(8);
+#undef FF_GCA_KV
+    }
+    {
+        SmArgs a{};
+        a.kv = s.kv; a.mask = mask; a.qpart = s.qpart; a.cntpart = s.cntpart; a.Cq = s.Cq; a.o = s.o;
+        a.S = d.n_seq; a.R = d.n_res; a.Hd = Hd; a.H = d.heads; a.nchunk = nchunk;
+        a.qscale = kLog2e / sqrtf((float)d.head_dim);
+        Timed t(KK_GCA_SOFTMAX, st);
+#define FF_GCA_SM(HV, DV) hipLaunchKernelGGL((k_gca_softmax<HV, DV>), dim3(d.n_res), dim3(256), 0, st, a)
+        if (d.head_dim == 8) {
+            if (d.heads == 4) FF_GCA_SM(4, 8);
+            else if (d.heads == 8) FF_GCA_SM(8, 8);
+            else FF_GCA_SM(16, 8);
+        } else {
+            if (d.heads == 2) FF_GCA_SM(2, 16);
+            else if (d.heads == 4) FF_GCA_SM(4, 16);
+            else FF_GCA_SM(8, 16);
+        }
+#undef FF_GCA_SM
+    }
+    {
+        OutArgs a{};
+        a.m = (const bf16_t*)m; a.out = (bf16_t*)out; a.o = s.o; a.S = d.n_seq; a.R = d.n_res; a.c = d.c; a.Hd = Hd;
+        a.eps = d.ln_eps; a.wg = s.wg; a.wo = s.wo; a.Cg = s.Cg; a.Co = s.Co;
+        const int tasks = d.n_seq * ((d.n_res + 31) / 32);
+        int blocks = (tasks + 3) / 4;
+        if (blocks > 2048) blocks = 2048;
+        const size_t smem = (size_t)Hd * (kc * 32 + 16) + (size_t)d.c * (Hd * 2 + 16) + (size_t)(Hd + d.c) * 4;
+        hipError_t attr = hipSuccess;
+        Timed t(KK_GCA_OUT, st);
+#define FF_GCA_OUT(KCV)                                                                                          \
+    do {                                                                                                         \
+        static const hipError_t once = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gca_out<KCV>),      \
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024); \
+        attr = once;                                                                                             \
+        if (once == hipSuccess) hipLaunchKernelGGL((k_gca_out<KCV>), dim3(blocks), dim3(256), smem, st, a);      \
+    } while (0)
+        if (kc == 2) FF_GCA_OUT(2);
+        else if (kc == 4) FF_GCA_OUT(4);
+        else FF_GCA_OUT(8);
+#undef FF_GCA_OUT
+        if (attr != hipSuccess) return fail(FF_EHIP, "k_gca_out: dynamic LDS limit: %s", hipGetErrorString(attr));
+    }
+    return check_launch("global column attention");
+}
+
+}  // namespace ff

@@ -168,6 +168,8 @@ __global__ __launch_bounds__(512, 2) void k_tm_proj(TmProjArgs p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     unsigned char* s_w = smem;                                            // [2][64 * PITCH]
     float* s_stat = reinterpret_cast<float*>(smem + 2 * 64 * PITCH);      // [8][3][32]: mean, 1/std, mask value
+    float* s_S = s_stat + 8 * 3 * 32;                                     // [64 n_pairs] row sums of the folded weights
+    float* s_C = s_S + 64 * p.n_pairs;                                    // [64 n_pairs] offsets
 
     const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -227,6 +229,10 @@ __global__ __launch_bounds__(512, 2) void k_tm_proj(TmProjArgs p) {
         fetch_pair(1);
         stash_pair(1);
     }
+    for (int id = tid; id < 64 * p.n_pairs; id += 512) {
+        s_S[id] = p.S[id];
+        s_C[id] = p.Cn[id];
+    }
     __syncthreads();
 
     const float* st_mean = s_stat + (wave * 3 + 0) * 32;
@@ -246,8 +252,8 @@ __global__ __launch_bounds__(512, 2) void k_tm_proj(TmProjArgs p) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc0[v] = acc1[v] = 0.f;
         // tokens x features: the lane owns one channel, its projection in acc0 and its gate in acc1
-        const float Sp = p.S[64 * pr + col], Cp = p.Cn[64 * pr + col];
-        const float Sg = p.S[64 * pr + 32 + col], Cg = p.Cn[64 * pr + 32 + col];
+        const float Sp = s_S[64 * pr + col], Cp = s_C[64 * pr + col];
+        const float Sg = s_S[64 * pr + 32 + col], Cg = s_C[64 * pr + 32 + col];
 #pragma unroll
         for (int s = 0; s < KC; ++s) {
             Frag w0, w1;
@@ -439,8 +445,15 @@ __global__ __launch_bounds__(256) void k_tm_out(TmOutArgs p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     unsigned char* s_wo = smem;                             // [cz][PC]
     unsigned char* s_wg = smem + (size_t)p.cz * PC;         // [cz][PZ]
+    float* s_k = reinterpret_cast<float*>(s_wg + (size_t)p.cz * PZ);   // [4][cz]: S, Cn, Sg, Cg
     const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    for (int id = tid; id < p.cz; id += 256) {
+        s_k[id] = p.S[id];
+        s_k[p.cz + id] = p.Cn[id];
+        s_k[2 * p.cz + id] = p.Sg[id];
+        s_k[3 * p.cz + id] = p.Cg[id];
+    }
     for (int id = tid; id < p.cz * 2 * KC; id += 256) {
         const int row = id / (2 * KC), pc = id - row * (2 * KC);
         *reinterpret_cast<uint4*>(s_wo + row * PC + pc * 16) = *reinterpret_cast<const uint4*>(p.wp + (size_t)row * (16 * KC) + pc * 8);
@@ -505,10 +518,10 @@ __global__ __launch_bounds__(256) void k_tm_out(TmOutArgs p) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int f0 = ft * 32 + 8 * g + 4 * hf;
-                const float4 s4 = *reinterpret_cast<const float4*>(p.S + f0);
-                const float4 c4 = *reinterpret_cast<const float4*>(p.Cn + f0);
-                const float4 sg4 = *reinterpret_cast<const float4*>(p.Sg + f0);
-                const float4 cg4 = *reinterpret_cast<const float4*>(p.Cg + f0);
+                const float4 s4 = *reinterpret_cast<const float4*>(s_k + f0);
+                const float4 c4 = *reinterpret_cast<const float4*>(s_k + p.cz + f0);
+                const float4 sg4 = *reinterpret_cast<const float4*>(s_k + 2 * p.cz + f0);
+                const float4 cg4 = *reinterpret_cast<const float4*>(s_k + 3 * p.cz + f0);
                 float o[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -600,7 +613,7 @@ ff_status trimul_run(const ff_trimul_desc& d, const ff_trimul_weights& w, const 
         const int tiles_m = N * (Np / 32);
         const dim3 grid((tiles_m + 7) / 8);
         Timed t(KK_TM_PROJ, st);
-        auto smem = [](int kc) { return (size_t)2 * 64 * (kc * 32 + 16) + 8 * 3 * 32 * 4; };
+        auto smem = [&](int kc) { return (size_t)2 * 64 * (kc * 32 + 16) + 8 * 3 * 32 * 4 + (size_t)2 * 64 * n_pairs * 4; };
         if (kc1 == 2) hipLaunchKernelGGL(k_tm_proj<2>, grid, dim3(512), smem(2), st, a);
         else if (kc1 == 4) hipLaunchKernelGGL(k_tm_proj<4>, grid, dim3(512), smem(4), st, a);
         else hipLaunchKernelGGL(k_tm_proj<8>, grid, dim3(512), smem(8), st, a);
@@ -624,7 +637,7 @@ ff_status trimul_run(const ff_trimul_desc& d, const ff_trimul_weights& w, const 
         int blocks = (tiles_m + 3) / 4;
         if (blocks > 512) blocks = 512;                 // two blocks per compute unit, each working through its share of the tiles
         const dim3 grid(blocks);
-        const size_t smem = (size_t)cz * (kc3 * 32 + 16) + (size_t)cz * (kc1 * 32 + 16);
+        const size_t smem = (size_t)cz * (kc3 * 32 + 16) + (size_t)cz * (kc1 * 32 + 16) + (size_t)4 * cz * 4;
         hipError_t attr = hipSuccess;
         Timed t(KK_TM_OUT, st);
 #define FF_TM_OUT(KCV, KZV)                                                                                          \

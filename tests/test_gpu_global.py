@@ -1,0 +1,118 @@
+"""GPU parity of the extra-MSA global column attention (ff_global_column_attention through the C ABI)
+against the float64 oracle, element by element on the same seeded inputs.  Tolerance as for the other
+bfloat16 attention modules: max-abs 2e-2 and relative L2 1e-2."""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2203_00854_amd as P
+from oracle import global_column_attention as G
+from paper_2203_00854_amd import binding as B
+from paper_2203_00854_amd import inputs as I
+from helpers import max_abs, rel_l2
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def to_np(t):
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+def oracle(case, cols=None):
+    w = {k: v.astype(np.float64) for k, v in case.widened_weights().items()}
+    sp = case.spec
+    return G.global_column_attention(I.widen(case.m).astype(np.float64), case.mask, w, sp.heads, sp.ln_eps, cols=cols)
+
+
+def check(got, ref, what):
+    ma, rl = max_abs(got, ref), rel_l2(got, ref)
+    print(f"{what}: max_abs={ma:.3e} rel_l2={rl:.3e}", flush=True)
+    assert np.isfinite(got).all()
+    assert ma <= 2e-2, (what, ma)
+    assert rl <= 1e-2, (what, rl)
+
+
+def run(case):
+    desc, w, m, mask = P.global_to_device(case, DEV)
+    out = P.ff_global_column_attention(desc, w, m, mask)
+    torch.cuda.synchronize()
+    return out
+
+
+SHAPES = [   # n_seq, n_res, c, heads, head_dim, mask: ragged around the 32-sequence tiles and the 256-sequence chunks
+    (1, 1, 32, 4, 8, "none"), (5, 3, 64, 8, 8, "random:0.7"), (33, 7, 64, 8, 8, "tail:4"), (70, 5, 96, 4, 16, "random:0.8"),
+    (256, 4, 64, 8, 8, "tail:30"), (257, 3, 128, 16, 8, "random:0.9"), (600, 9, 32, 2, 16, "tail:90"),
+    (300, 40, 64, 4, 8, "random:0.5"), (129, 2, 128, 8, 16, "none"),
+]
+
+
+@pytest.mark.parametrize("n_seq,n_res,c,heads,d,mask", SHAPES)
+def test_ragged_shapes(n_seq, n_res, c, heads, d, mask):
+    spec = I.GlobalSpec(f"t_gca_{n_seq}_{n_res}_{c}_{heads}_{d}_{mask}", "bf16", n_seq, n_res, c, heads, d, mask)
+    case = I.make_global_case(spec)
+    check(to_np(run(case)), oracle(case), spec.name)
+
+
+def test_extra_msa_1024_sequences_all_columns():
+    """The paper's initial-training extra-MSA size: 1024 sequences (the last 102 padding) x 384 residues, c = 64,
+    8 heads of 8 channels; every column in the oracle (the module is linear in the number of sequences)."""
+    case = I.make_global_case("gca_bf16_1024x384")
+    check(to_np(run(case)), oracle(case), "1024 x 384")
+
+
+def test_extra_msa_5120_sequences_sampled_columns():
+    """The fine-tuning size, 5120 sequences: all columns on the GPU, 48 of them (37 apart) in the oracle."""
+    case = I.make_global_case("gca_bf16_5120x384")
+    got = to_np(run(case))
+    cols = sorted({(3 + 37 * k) % 384 for k in range(46)} | {0, 383})
+    check(got[:, cols], oracle(case, cols=cols), "5120 x 384, sampled columns")
+
+
+def test_columns_without_unmasked_sequences_and_masked_content():
+    spec = I.GlobalSpec("t_gca_empty", "bf16", 90, 6, 64, 8, 8, "tail:20")
+    case = I.make_global_case(spec)
+    case.mask[:, 2] = 0.0
+    got = run(case)
+    bo = torch.from_numpy(case.weights["b_o"].view(np.int16)).to(DEV).view(torch.bfloat16)
+    assert torch.equal(got[:, 2], bo.expand(90, -1))
+    check(to_np(got), oracle(case), "empty column")
+    # the content of masked sequences is irrelevant to the others, bit for bit
+    desc, w, m, mask = P.global_to_device(case, DEV)
+    m2 = m.clone()
+    m2[70:] = torch.randn_like(m2[70:]) * 3
+    b = P.ff_global_column_attention(desc, w, m2, mask)
+    torch.cuda.synchronize()
+    assert torch.equal(got[:70], b[:70])
+
+
+def test_sequence_permutation_permutes_the_output():
+    """Reordering the sequences reorders the output; the attended vectors are sums over the sequences in another
+    order, so equality holds to rounding, not bit for bit."""
+    spec = I.GlobalSpec("t_gca_perm", "bf16", 200, 4, 64, 8, 8, "random:0.8")
+    case = I.make_global_case(spec)
+    desc, w, m, mask = P.global_to_device(case, DEV)
+    perm = torch.randperm(200, device=DEV, generator=torch.Generator(device=DEV).manual_seed(1))
+    a = P.ff_global_column_attention(desc, w, m, mask)
+    b = P.ff_global_column_attention(desc, w, m[perm].contiguous(), mask[perm].contiguous())
+    torch.cuda.synchronize()
+    assert (a[perm].float() - b.float()).abs().max().item() <= 2.0 ** -6
+
+
+def test_bad_arguments_are_status_codes():
+    d = P.GlobalDesc(P.FF_F32, 8, 4, 64, 8, 8, 1e-5)
+    assert P.lib().ff_global_column_attention_workspace_bytes(C.byref(d)) == 0           # float32: unsupported
+    d = P.GlobalDesc(P.FF_BF16, 8, 4, 64, 8, 32, 1e-5)
+    assert P.lib().ff_global_column_attention_workspace_bytes(C.byref(d)) == 0           # head_dim 32: unsupported
+    d = P.GlobalDesc(P.FF_BF16, 8, 4, 64, 8, 8, 1e-5)
+    need = P.lib().ff_global_column_attention_workspace_bytes(C.byref(d))
+    assert need > 0 and need % 256 == 0
+    w = B.GlobalWeights()
+    for n in B.GLOBAL_FIELDS:
+        setattr(w, n, 0x1000)
+    st = P.lib().ff_global_column_attention(C.byref(d), C.byref(w), 0x10000, None, 0x20000, 0x100000, need - 1, None)
+    assert st == B.FF_EWORKSPACE
+    st = P.lib().ff_global_column_attention(C.byref(d), C.byref(w), 0x10000, None, 0x10000, 0x100000, need, None)
+    assert st == B.FF_EINVAL
