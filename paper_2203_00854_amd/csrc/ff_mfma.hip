@@ -877,8 +877,8 @@ __global__ __launch_bounds__(kGemmWaves * 64, 2) void k_gemm(GemmArgs a) {
 // (query side): the matrix core returns s - m_ref, m_ref being a per-query reference close
 // to the running maximum that is raised only when a tile exceeds it by more than kRaise
 // (then the accumulators are rescaled).  Slot B multiplies the mask term of the key (0 or
-// -inf) with 1.  For head dims below 32 a row of ones in V^T makes the matrix core
-// accumulate the softmax denominator as well.
+// -inf) with 1.  The softmax denominator is summed by the vector unit from the rounded weights,
+// two at a time.
 struct AttnArgs {
     const bf16_t *q, *k, *g, *vt;
     bf16_t* o;
@@ -897,13 +897,18 @@ constexpr float kOver = 1048576.f;   // 2^20: partial denominator (16 keys) that
 // (bias-free 4-row blocks for head dims below 32 are held to 168 registers, three wavefronts per
 // SIMD: d = 8 fits as it is, d = 16 spills fifteen registers and is still 9 % faster; at d = 32 the
 // same bound costs more in spills than the third wavefront brings)
+#ifndef FF_SKEW
+#define FF_SKEW 0
+#endif
+#define FF_SKEW_WAVES()                                                     \
+    do {                                                                    \
+        if (FF_SKEW > 0 && RB == 8 && wave >= 4) __builtin_amdgcn_s_sleep(FF_SKEW); \
+    } while (0)
 template <int D, bool HAS_BIAS, int RB, int GK, bool PERSIST>
 __global__ __launch_bounds__(RB * 64, (RB == 4 && !HAS_BIAS && D < 32) ? 3 : 2) void k_attn(AttnArgs a) {
     constexpr int PCX = D / 8;              // index of the 8-slot piece holding the two extra slots
     constexpr int KS = PCX / 2 + 1;         // 16-wide contraction steps
     constexpr int SX = PCX / 2, HX = PCX % 2;
-    constexpr bool ONES_ROW = D < 32;       // V^T row D is all ones: O^T row D = softmax denominator
-    constexpr int LV = ONES_ROW ? 4 * (D / 8) : 0;   // its accumulator register (in the lower half-wave)
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     constexpr int TPG = GK / 32, kBiasPitch = GK + kBiasPad;
     float* s_bias = reinterpret_cast<float*>(smem);                                  // [2][64][kBiasPitch]
@@ -1023,7 +1028,6 @@ __global__ __launch_bounds__(RB * 64, (RB == 4 && !HAS_BIAS && D < 32) ? 3 : 2) 
     set_pointers();
     fetch_q();
     if constexpr (HAS_BIAS) load_bias(0);      // (stored to LDS after the first K and V loads have been issued)
-    const bool ones_lane = ONES_ROW && col == D;
 
     // Software pipeline over 32-key tiles i:
     //   K(i+2), mask(i+2), V(i+1) are in flight (global -> registers) while
@@ -1141,16 +1145,12 @@ __global__ __launch_bounds__(RB * 64, (RB == 4 && !HAS_BIAS && D < 32) ? 3 : 2) 
                     for (int v = 0; v < 16; ++v) sn[j][v] = 0.f;
             }
         }
-        if (ones_lane) {
-#pragma unroll
-            for (int c = 0; c < 2; ++c) vb[c].u = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);
-        }
-        // sa holds s - m_ref (masked keys: -inf).  With the denominator in the vector unit
-        // (D = 32) only the first tile takes the maximum; later tiles are exponentiated as they
-        // are and a partial denominator beyond kOver (some s - m_ref above about 16) sends the
-        // query tile through raise_ref afterwards: rare, and the common tile saves the sixteen
-        // max operations per query.  With the denominator on the matrix core (D < 32) the
-        // maximum is taken for every tile, because there the overflow would already be accumulated.
+        // sa holds s - m_ref (masked keys: -inf).  Only the first tile takes the maximum; later tiles
+        // are exponentiated as they are and a partial denominator beyond kOver (some s - m_ref above
+        // about 16) sends the query tile through raise_ref afterwards: rare, and the common tile
+        // saves the sixteen max operations per query.  (For head dims below 32 a row of ones in V^T
+        // could let the matrix core sum the denominator, but an overflow would then already be
+        // accumulated, so every tile would need its maximum: 3 % slower at d = 8 in a same-box comparison.)
         auto tile_max = [&](int j) __attribute__((always_inline)) -> float {
             float mx = sa[j][0];
 #pragma unroll
@@ -1175,7 +1175,7 @@ __global__ __launch_bounds__(RB * 64, (RB == 4 && !HAS_BIAS && D < 32) ? 3 : 2) 
             l_run[j] *= sc;
             if (xlane) qf[j][SX].w[0] = pack2(-new_ref, 1.f);
         };
-        if (ONES_ROW || first) {
+        if (first) {
             const float t0 = tile_max(0), t1 = tile_max(1);
             if (first || __any(t0 > kRaise || t1 > kRaise)) {
                 raise_ref(0, t0, first, !FUSE && sn_live);      // (FUSE: the next tile has not begun)
@@ -1206,7 +1206,7 @@ __global__ __launch_bounds__(RB * 64, (RB == 4 && !HAS_BIAS && D < 32) ? 3 : 2) 
                             const float p1 = __builtin_amdgcn_exp2f(sa[j][8 * c + 2 * i + 1]);
                             pf[c].w[i] = pack2(p0, p1);
                             // denominator from the rounded weights, two per instruction
-                            if constexpr (!ONES_ROW) lt = add_pair(pf[c].w[i], lt);
+                            lt = add_pair(pf[c].w[i], lt);
                         }
                 } else {
                     // (between two fences: the exponentials of group g + 1, then pack and partial
@@ -1222,7 +1222,7 @@ __global__ __launch_bounds__(RB * 64, (RB == 4 && !HAS_BIAS && D < 32) ? 3 : 2) 
                         }
                         uint32_t& w = pf[g >> 2].w[g & 3];
                         w = pack2(e0, e1);
-                        if constexpr (!ONES_ROW) lt = add_pair(w, lt);
+                        lt = add_pair(w, lt);
                         asm volatile("" : "+v"(w));
                         if ((g & 1) && (g >> 1) < KS) next_mma(1 - j, g >> 1);
                         __builtin_amdgcn_sched_barrier(0);
@@ -1232,15 +1232,13 @@ __global__ __launch_bounds__(RB * 64, (RB == 4 && !HAS_BIAS && D < 32) ? 3 : 2) 
                 }
             };
             exponentiate(std::integral_constant<bool, FUSE>{});
-            if constexpr (!ONES_ROW) {
-                if (__any(!(lt <= kOver))) {
-                    // (FUSE: the next tile of query tile 1 was issued during query tile 0, that of
-                    // query tile 0 is issued during query tile 1)
-                    raise_ref(j, tile_max(j), false, FUSE ? j == 1 : sn_live);
-                    exponentiate(std::integral_constant<bool, false>{});
-                }
-                l_run[j] += lt;
+            if (__any(!(lt <= kOver))) {
+                // (FUSE: the next tile of query tile 1 was issued during query tile 0, that of
+                // query tile 0 is issued during query tile 1)
+                raise_ref(j, tile_max(j), false, FUSE ? j == 1 : sn_live);
+                exponentiate(std::integral_constant<bool, false>{});
             }
+            l_run[j] += lt;
 #pragma unroll
             for (int c = 0; c < 2; ++c)
                 o_acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vb[c].v, pf[c].v, o_acc[j], 0, 0, 0);
@@ -1274,6 +1272,7 @@ __global__ __launch_bounds__(RB * 64, (RB == 4 && !HAS_BIAS && D < 32) ? 3 : 2) 
         if (TPG == 2 && nt > 2) load_bias(1);
     }
     __syncthreads();                        // bias group 0 is in LDS
+    FF_SKEW_WAVES();
     qk_bias(0, s0);
     bool live0 = qk_mma(kb0, mv0, 0, s0), live1 = false;
     // (long sequences, PERSIST = false: one item per block.  There the start of an item is a few per
@@ -1331,6 +1330,7 @@ __global__ __launch_bounds__(RB * 64, (RB == 4 && !HAS_BIAS && D < 32) ? 3 : 2) 
             if ((i + 2) % TPG == 0) {
                 store_bias(((i + 2) / TPG + gbase) & 1);
                 __syncthreads();
+                FF_SKEW_WAVES();
             }
         }
         // ---- odd tile i+1: K(i+3) -> set 1, V(i+2) -> set 0, S^T(i+2) -> s0, exponentials of s1
@@ -1365,14 +1365,7 @@ __global__ __launch_bounds__(RB * 64, (RB == 4 && !HAS_BIAS && D < 32) ? 3 : 2) 
     // ---- epilogue: normalise, gate, store.  o_acc[j]: lane = query, register v = e = 8*(v/4) + 4*hf + v%4
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-        float l_tot;
-        if constexpr (ONES_ROW) {
-            const float mine = o_acc[j][LV];
-            const float oth = other_half(mine);
-            l_tot = hf ? oth : mine;
-        } else {
-            l_tot = l_run[j] + other_half(l_run[j]);
-        }
+        const float l_tot = l_run[j] + other_half(l_run[j]);
         const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
         const int qi = e_q0 + 32 * j + col;                       // < Lp
         // gate and context are head-major [row][head][l][d]: the wave's 32 queries are one
