@@ -897,13 +897,6 @@ constexpr float kOver = 1048576.f;   // 2^20: partial denominator (16 keys) that
 // (bias-free 4-row blocks for head dims below 32 are held to 168 registers, three wavefronts per
 // SIMD: d = 8 fits as it is, d = 16 spills fifteen registers and is still 9 % faster; at d = 32 the
 // same bound costs more in spills than the third wavefront brings)
-#ifndef FF_SKEW
-#define FF_SKEW 0
-#endif
-#define FF_SKEW_WAVES()                                                     \
-    do {                                                                    \
-        if (FF_SKEW > 0 && RB == 8 && wave >= 4) __builtin_amdgcn_s_sleep(FF_SKEW); \
-    } while (0)
 template <int D, bool HAS_BIAS, int RB, int GK, bool PERSIST>
 __global__ __launch_bounds__(RB * 64, (RB == 4 && !HAS_BIAS && D < 32) ? 3 : 2) void k_attn(AttnArgs a) {
     constexpr int PCX = D / 8;              // index of the 8-slot piece holding the two extra slots
@@ -1272,7 +1265,6 @@ __global__ __launch_bounds__(RB * 64, (RB == 4 && !HAS_BIAS && D < 32) ? 3 : 2) 
         if (TPG == 2 && nt > 2) load_bias(1);
     }
     __syncthreads();                        // bias group 0 is in LDS
-    FF_SKEW_WAVES();
     qk_bias(0, s0);
     bool live0 = qk_mma(kb0, mv0, 0, s0), live1 = false;
     // (long sequences, PERSIST = false: one item per block.  There the start of an item is a few per
@@ -1330,7 +1322,6 @@ __global__ __launch_bounds__(RB * 64, (RB == 4 && !HAS_BIAS && D < 32) ? 3 : 2) 
             if ((i + 2) % TPG == 0) {
                 store_bias(((i + 2) / TPG + gbase) & 1);
                 __syncthreads();
-                FF_SKEW_WAVES();
             }
         }
         // ---- odd tile i+1: K(i+3) -> set 1, V(i+2) -> set 0, S^T(i+2) -> s0, exponentials of s1

@@ -11,12 +11,13 @@
 //              Cn = W beta + bias, so that LN(x) W^T + bias = rstd * (x W'^T - mean * S) + Cn and the
 //              matrix cores read the raw activations
 //   k_tm_proj  one merged GEMM over the 4c features of the left and right side.  A projection tile is
-//              contracted together with its gate tile, so that the lane that holds a projection value
-//              also holds its gate value; a and b leave channel-major, [c][N][Np], which makes every
+//              contracted together with its gate tile (features x tokens), so that the lane that holds a
+//              projection value also holds its gate value; a and b leave channel-major, [c][N][Np], which makes every
 //              channel a dense N x N matrix for the next kernel.  The incoming form is the outgoing form
 //              on the transposed view of z (strides), so a[c][i][k] then holds a of pair (k, i).
-//   k_tm_mul   per channel t_c = A_c B_c^T: a batched N x N x N contraction, 128 x 128 tiles through LDS
-//   k_tm_out   LayerNorm over the channels of t (transposed to token-major through LDS), output
+//   k_tm_mul   per channel t_c = A_c B_c^T: a batched N x N x N contraction, 128 x 128 tiles through LDS; t leaves
+//              as [i][channel][j]
+//   k_tm_out   LayerNorm over the channels of t (read as 2-byte loads straight into operand fragments), output
 //              projection; the output gate g is computed here, from z, in float32 (it never exists in
 //              memory), then the product and the optional residual
 //
@@ -147,13 +148,14 @@ __global__ __launch_bounds__(256) void k_tm_prep(TmPrepArgs a) {
 
 // ====================================================================================
 // Merged projection.  Block = 8 wavefronts, each owning one 32-token tile (tokens of one row of the view)
-// as register-resident operand fragments; the block sweeps the prepared weight matrix 64 rows (a "pair")
-// at a time through a double-buffered LDS image (row pitch padded by 16 bytes: conflict-free operand reads).
+// as register-resident operand fragments and sweeping the prepared weight matrix 64 rows (a "pair") at a
+// time; the matrix is resident in LDS (row pitch padded by 16 bytes: conflict-free operand reads).
 struct TmProjArgs {
     const bf16_t* z;
     int64_t sr, sl;          // token (r, l) of the view at z + (r*sr + l*sl) * K; the same index addresses mask
     const float* mask;       // or NULL
     int N, Np, K, C, cz, G, n_pairs;
+    int ppb;                 // pairs per block: blockIdx.y takes pairs [blockIdx.y * ppb, + ppb)
     float eps;
     const bf16_t* wp;        // [64 n_pairs][16 KC]
     const float *S, *Cn;
@@ -163,128 +165,87 @@ struct TmProjArgs {
 template <int KC>
 __global__ __launch_bounds__(512, 2) void k_tm_proj(TmProjArgs p) {
     constexpr int PITCH = KC * 32 + 16;                 // bytes per weight row in LDS
-    constexpr int PIECES = 64 * 2 * KC;                 // 16-byte pieces per pair
-    constexpr int PPT = (PIECES + 511) / 512;           // pieces per thread
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    unsigned char* s_w = smem;                                            // [2][64 * PITCH]
-    float* s_stat = reinterpret_cast<float*>(smem + 2 * 64 * PITCH);      // [8][3][32]: mean, 1/std, mask value
-    float* s_S = s_stat + 8 * 3 * 32;                                     // [64 n_pairs] row sums of the folded weights
-    float* s_C = s_S + 64 * p.n_pairs;                                    // [64 n_pairs] offsets
+    unsigned char* s_w = smem;                                                    // [64 ppb][PITCH]: the block's share of the folded weights
+    float* s_S = reinterpret_cast<float*>(smem + (size_t)64 * p.ppb * PITCH);     // [64 ppb] row sums of the folded weights
+    float* s_C = s_S + 64 * p.ppb;                                                // [64 ppb] offsets
+    const int pr_first = blockIdx.y * p.ppb;
 
     const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int tpr = p.Np >> 5;                          // token tiles per row
     const int tiles_m = p.N * tpr;
-    int tg = blockIdx.x * 8 + wave;
-    const bool live = tg < tiles_m;                     // (a wavefront without a tile still helps to move the weights)
-    if (!live) tg = tiles_m - 1;
-    const int r = tg / tpr, l0 = (tg - r * tpr) * 32, l = l0 + col;
-    const bool valid = l < p.N;
-    const int64_t tok = (int64_t)r * p.sr + (int64_t)(valid ? l : 0) * p.sl;
 
-    Frag xa[KC];
-    {
-        const bf16_t* zp = p.z + tok * p.K;
-#pragma unroll
-        for (int s = 0; s < KC; ++s) {
-            xa[s].u = make_uint4(0, 0, 0, 0);
-            if (valid && 16 * s + 8 * hf < p.K) xa[s].u = *reinterpret_cast<const uint4*>(zp + 16 * s + 8 * hf);
-        }
+    // The block's share of the folded weight matrix (all of it, at most 512 rows of 256 bytes, for large inputs;
+    // a quarter for small ones, which need the blocks) stays in LDS for the life of the block, which works through
+    // token tiles blockIdx.x * 8 + wave, + 8 * gridDim.x, ...: after this one barrier the wavefronts run
+    // independently, so that one wavefront's matrix instructions overlap another's epilogue arithmetic on the
+    // same SIMD, and the weights are read from L2 once per block, not once per 256 tokens.
+    for (int id = tid; id < 64 * p.ppb * 2 * KC; id += 512) {
+        const int row = id / (2 * KC), pc = id - row * (2 * KC);
+        *reinterpret_cast<uint4*>(s_w + row * PITCH + pc * 16) =
+            *reinterpret_cast<const uint4*>(p.wp + (size_t)(64 * pr_first + row) * (16 * KC) + pc * 8);
     }
-    const float mval = valid ? (p.mask ? p.mask[tok] : 1.f) : 0.f;
+    for (int id = tid; id < 64 * p.ppb; id += 512) {
+        s_S[id] = p.S[64 * pr_first + id];
+        s_C[id] = p.Cn[64 * pr_first + id];
+    }
+    __syncthreads();                                    // (the only barrier)
 
-    // weight pieces of this thread (at most two; named registers: arrays captured by a lambda end up in scratch memory)
-    static_assert(PPT <= 2, "pieces per thread");
-    const int id0 = tid, id1 = tid + 512;
-    const int row0 = id0 / (2 * KC), pc0 = id0 - row0 * (2 * KC);
-    const int row1 = id1 / (2 * KC), pc1 = id1 - row1 * (2 * KC);
-    const bool has0 = id0 < PIECES, has1 = PPT > 1 && id1 < PIECES;
-    const int w_src0 = row0 * (16 * KC) + pc0 * 8, w_dst0 = row0 * PITCH + pc0 * 16;
-    const int w_src1 = row1 * (16 * KC) + pc1 * 8, w_dst1 = row1 * PITCH + pc1 * 16;
-    uint4 wreg0 = make_uint4(0, 0, 0, 0), wreg1 = wreg0;
-#define fetch_pair(PR)                                                                 \
-    do {                                                                               \
-        const bf16_t* src_ = p.wp + (size_t)(PR) * 64 * (16 * KC);                     \
-        if (has0) wreg0 = *reinterpret_cast<const uint4*>(src_ + w_src0);              \
-        if (has1) wreg1 = *reinterpret_cast<const uint4*>(src_ + w_src1);              \
-    } while (0)
-#define stash_pair(BUF)                                                                       \
-    do {                                                                                      \
-        if (has0) *reinterpret_cast<uint4*>(s_w + (BUF) * 64 * PITCH + w_dst0) = wreg0;       \
-        if (has1) *reinterpret_cast<uint4*>(s_w + (BUF) * 64 * PITCH + w_dst1) = wreg1;       \
-    } while (0)
-    fetch_pair(0);
-
-    {
-        float mean, rstd;
-        token_stats<KC>(xa, p.K, hf, p.eps, mean, rstd);
-        if (hf == 0) {
-            s_stat[(wave * 3 + 0) * 32 + col] = mean;
-            s_stat[(wave * 3 + 1) * 32 + col] = rstd;
-            s_stat[(wave * 3 + 2) * 32 + col] = mval;
-        }
-    }
-    stash_pair(0);
-    if (p.n_pairs > 1) {
-        fetch_pair(1);
-        stash_pair(1);
-    }
-    for (int id = tid; id < 64 * p.n_pairs; id += 512) {
-        s_S[id] = p.S[id];
-        s_C[id] = p.Cn[id];
-    }
-    __syncthreads();
-
-    const float* st_mean = s_stat + (wave * 3 + 0) * 32;
-    const float* st_rstd = s_stat + (wave * 3 + 1) * 32;
-    const float* st_mval = s_stat + (wave * 3 + 2) * 32;
     const size_t plane = (size_t)p.N * p.Np;
 
-    // Pair pr + 2 is fetched into registers before the matrix instructions of pair pr (so that its latency hides
-    // behind them, and so that these loads precede the epilogue's stores in the wavefront's memory order:
-    // waiting for a load then does not wait for stores issued after it) and written to the LDS half that pair pr
-    // occupied once every wavefront has passed the barrier.
-    for (int pr = 0; pr < p.n_pairs; ++pr) {
-        const unsigned char* st = s_w + (pr & 1) * 64 * PITCH;
-        const bool more = pr + 2 < p.n_pairs;
-        if (more) fetch_pair(pr + 2);
-        f32x16 acc0, acc1;
+    for (int tg = blockIdx.x * 8 + wave; tg < tiles_m; tg += gridDim.x * 8) {
+        const int r = tg / tpr, l0 = (tg - r * tpr) * 32, l = l0 + col;
+        const bool valid = l < p.N;
+        const int64_t tok = (int64_t)r * p.sr + (int64_t)(valid ? l : 0) * p.sl;
+        Frag xa[KC];
+        {
+            const bf16_t* zp = p.z + tok * p.K;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc0[v] = acc1[v] = 0.f;
-        // tokens x features: the lane owns one channel, its projection in acc0 and its gate in acc1
-        const float Sp = s_S[64 * pr + col], Cp = s_C[64 * pr + col];
-        const float Sg = s_S[64 * pr + 32 + col], Cg = s_C[64 * pr + 32 + col];
-#pragma unroll
-        for (int s = 0; s < KC; ++s) {
-            Frag w0, w1;
-            w0.u = *reinterpret_cast<const uint4*>(st + col * PITCH + (2 * s + hf) * 16);
-            w1.u = *reinterpret_cast<const uint4*>(st + (32 + col) * PITCH + (2 * s + hf) * 16);
-            acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[s].v, w0.v, acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[s].v, w1.v, acc1, 0, 0, 0);
-        }
-        const bool left = pr < p.G;
-        const int ch = 32 * (left ? pr : pr - p.G) + col;
-        bf16_t* dst = (left ? p.a : p.b) + (size_t)ch * plane + (size_t)r * p.Np + l0 + 4 * hf;
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const float4 m4 = *reinterpret_cast<const float4*>(st_mean + 8 * g + 4 * hf);
-            const float4 r4 = *reinterpret_cast<const float4*>(st_rstd + 8 * g + 4 * hf);
-            const float4 k4 = *reinterpret_cast<const float4*>(st_mval + 8 * g + 4 * hf);
-            float o[4];
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float mu = pick(m4, e), rs = pick(r4, e);
-                const float tp = rs * (acc0[4 * g + e] - mu * Sp) + Cp;
-                const float tgv = rs * (acc1[4 * g + e] - mu * Sg) + Cg;
-                o[e] = tp * sigmoid(tgv) * pick(k4, e);
+            for (int s = 0; s < KC; ++s) {
+                xa[s].u = make_uint4(0, 0, 0, 0);
+                if (valid && 16 * s + 8 * hf < p.K) xa[s].u = *reinterpret_cast<const uint4*>(zp + 16 * s + 8 * hf);
             }
-            if (live) *reinterpret_cast<uint2*>(dst + 8 * g) = make_uint2(pack2(o[0], o[1]), pack2(o[2], o[3]));
         }
-        __syncthreads();
-        if (more) stash_pair(pr & 1);
+        const float mval = valid ? (p.mask ? p.mask[tok] : 1.f) : 0.f;
+        float mean, rstd;
+        token_stats<KC>(xa, p.K, hf, p.eps, mean, rstd);
+
+        for (int pl = 0; pl < p.ppb; ++pl) {
+            const int pr = pr_first + pl;
+            const unsigned char* st = s_w + (size_t)pl * 64 * PITCH;
+            f32x16 acc0, acc1;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc0[v] = acc1[v] = 0.f;
+            // features x tokens: the lane owns one token (its statistics are in its registers); register v holds
+            // channel 8 (v / 4) + 4 hf + v % 4 of the pair's 32, the projection in acc0 and the gate in acc1
+#pragma unroll
+            for (int s = 0; s < KC; ++s) {
+                Frag w0, w1;
+                w0.u = *reinterpret_cast<const uint4*>(st + col * PITCH + (2 * s + hf) * 16);
+                w1.u = *reinterpret_cast<const uint4*>(st + (32 + col) * PITCH + (2 * s + hf) * 16);
+                acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w0.v, xa[s].v, acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1.v, xa[s].v, acc1, 0, 0, 0);
+            }
+            const bool left = pr < p.G;
+            const int ch0 = 32 * (left ? pr : pr - p.G) + 4 * hf;
+            // a store instruction writes one channel row per half-wave: 32 consecutive positions, 64 contiguous bytes
+            bf16_t* dst = (left ? p.a : p.b) + (size_t)ch0 * plane + (size_t)r * p.Np + l;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const float4 sp4 = *reinterpret_cast<const float4*>(s_S + 64 * pl + 8 * g + 4 * hf);
+                const float4 cp4 = *reinterpret_cast<const float4*>(s_C + 64 * pl + 8 * g + 4 * hf);
+                const float4 sg4 = *reinterpret_cast<const float4*>(s_S + 64 * pl + 32 + 8 * g + 4 * hf);
+                const float4 cg4 = *reinterpret_cast<const float4*>(s_C + 64 * pl + 32 + 8 * g + 4 * hf);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float tp = rstd * (acc0[4 * g + e] - mean * pick(sp4, e)) + pick(cp4, e);
+                    const float tgv = rstd * (acc1[4 * g + e] - mean * pick(sg4, e)) + pick(cg4, e);
+                    dst[(size_t)(8 * g + e) * plane] = (bf16_t)(pack2(tp * sigmoid(tgv) * mval, 0.f) & 0xffffu);
+                }
+            }
+        }
     }
-#undef fetch_pair
-#undef stash_pair
 }
 
 // ====================================================================================
@@ -294,7 +255,7 @@ __global__ __launch_bounds__(512, 2) void k_tm_proj(TmProjArgs p) {
 // channel's operands live in one L2.
 struct TmMulArgs {
     const bf16_t *a, *b;     // [C][N][Np]
-    bf16_t* x;               // [C][N][Np]
+    bf16_t* x;               // [N][C][Np]
     int N, Np, C, tiles;     // tiles per side
 };
 
@@ -404,7 +365,10 @@ __global__ __launch_bounds__(256, 2) void k_tm_mul(TmMulArgs p) {
 #undef fetch
 #undef stash
 
-    bf16_t* xc = p.x + (size_t)ch * plane;
+    // t leaves as [i][channel][j]: the channels of a row i lie close together, which is what the LayerNorm over
+    // the channels in k_tm_out reads (128 short segments inside half a megabyte instead of one per 8 MiB plane)
+    bf16_t* xc = p.x + (size_t)ch * p.Np;
+    const size_t xrow = (size_t)p.C * p.Np;
 #pragma unroll
     for (int ti = 0; ti < 2; ++ti) {
         const int i = i0 + wi * 64 + 32 * ti + col;
@@ -415,7 +379,7 @@ __global__ __launch_bounds__(256, 2) void k_tm_mul(TmMulArgs p) {
             for (int g = 0; g < 4; ++g) {
                 const int j = j0 + wj * 64 + 32 * tj + 8 * g + 4 * hf;
                 if (j < p.Np)
-                    *reinterpret_cast<uint2*>(xc + (size_t)i * p.Np + j) =
+                    *reinterpret_cast<uint2*>(xc + (size_t)i * xrow + j) =
                         make_uint2(pack2(acc[tj][ti][4 * g], acc[tj][ti][4 * g + 1]),
                                    pack2(acc[tj][ti][4 * g + 2], acc[tj][ti][4 * g + 3]));
             }
@@ -429,7 +393,7 @@ __global__ __launch_bounds__(256, 2) void k_tm_mul(TmMulArgs p) {
 // tiles (i, j0 .. j0 + 31); features x tokens on the matrix cores (the lane owns a token) for both GEMMs, so the
 // gate meets the projected value in the same lane and register.
 struct TmOutArgs {
-    const bf16_t* x;         // [C][N][Np]
+    const bf16_t* x;         // [N][C][Np]
     const bf16_t* z;         // [N*N][cz]
     bf16_t* out;             // [N*N][cz]; may be z itself when residual
     int residual;
@@ -464,7 +428,6 @@ __global__ __launch_bounds__(256) void k_tm_out(TmOutArgs p) {
     }
     __syncthreads();
 
-    const size_t plane = (size_t)p.N * p.Np;
     const int tpr = p.Np >> 5, tiles_m = p.N * tpr, n_ft = p.cz >> 5;
     for (int t = blockIdx.x * 4 + wave; t < tiles_m; t += gridDim.x * 4) {
         const int i = t / tpr, j0 = (t - i * tpr) * 32, j = j0 + col;       // j < Np
@@ -478,18 +441,17 @@ __global__ __launch_bounds__(256) void k_tm_out(TmOutArgs p) {
                 za[s].u = make_uint4(0, 0, 0, 0);
                 if (16 * s + 8 * hf < p.cz) za[s].u = *reinterpret_cast<const uint4*>(zp + 16 * s + 8 * hf);
             }
-            // t is channel-major: the eight channels of an operand fragment are eight 2-byte loads, each of
-            // them 64 contiguous bytes across the half-wave (the order of the contraction index is free as
-            // long as both operands agree, and the weights keep the natural order)
-            const bf16_t* xp = p.x + (size_t)i * p.Np + j;
+            // t is [i][channel][j]: the eight channels of an operand fragment are eight 2-byte loads, each of
+            // them 64 contiguous bytes across the half-wave
+            const bf16_t* xp = p.x + (size_t)i * p.C * p.Np + j;
 #pragma unroll
             for (int s = 0; s < KC; ++s) {
                 xa[s].u = make_uint4(0, 0, 0, 0);
                 if (16 * s + 8 * hf < p.C) {
-                    const bf16_t* xc = xp + (size_t)(16 * s + 8 * hf) * plane;
+                    const bf16_t* xc = xp + (size_t)(16 * s + 8 * hf) * p.Np;
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        xa[s].w[e] = (uint32_t)xc[(size_t)(2 * e) * plane] | ((uint32_t)xc[(size_t)(2 * e + 1) * plane] << 16);
+                        xa[s].w[e] = (uint32_t)xc[(size_t)(2 * e) * p.Np] | ((uint32_t)xc[(size_t)(2 * e + 1) * p.Np] << 16);
                 }
             }
         }
@@ -611,12 +573,31 @@ ff_status trimul_run(const ff_trimul_desc& d, const ff_trimul_weights& w, const 
         a.mask = mask; a.N = N; a.Np = Np; a.K = cz; a.C = c; a.cz = cz; a.G = G; a.n_pairs = n_pairs; a.eps = d.ln_eps;
         a.wp = m.wp1; a.S = m.S1; a.Cn = m.C1; a.a = m.a; a.b = m.b;
         const int tiles_m = N * (Np / 32);
-        const dim3 grid((tiles_m + 7) / 8);
+        int blocks = (tiles_m + 7) / 8;
+        // Large inputs: one persistent block per compute unit with all weights in its LDS.  Small ones (fewer than
+        // four token tiles per wavefront slot of the chip) split the pairs in two over blockIdx.y, so that two
+        // blocks fit a compute unit: x is then read twice, the second time from L2 (N_res = 256: 28.7 -> 26.3 us,
+        // 384: 57 -> 51 us; a split in four loses again, 30 and 58 us).
+        const int split = (blocks < 4 * 256 && n_pairs % 2 == 0) ? 2 : 1;
+        a.ppb = n_pairs / split;
+        const int per_cu = split;
+        if (blocks > 256 * per_cu) blocks = 256 * per_cu;
+        const dim3 grid(blocks, split);
+        auto smem = [&](int kc) { return (size_t)64 * a.ppb * (kc * 32 + 16) + (size_t)2 * 64 * a.ppb * 4; };
+        hipError_t attr = hipSuccess;
         Timed t(KK_TM_PROJ, st);
-        auto smem = [&](int kc) { return (size_t)2 * 64 * (kc * 32 + 16) + 8 * 3 * 32 * 4 + (size_t)2 * 64 * n_pairs * 4; };
-        if (kc1 == 2) hipLaunchKernelGGL(k_tm_proj<2>, grid, dim3(512), smem(2), st, a);
-        else if (kc1 == 4) hipLaunchKernelGGL(k_tm_proj<4>, grid, dim3(512), smem(4), st, a);
-        else hipLaunchKernelGGL(k_tm_proj<8>, grid, dim3(512), smem(8), st, a);
+#define FF_TM_PROJ(KCV)                                                                                          \
+    do {                                                                                                         \
+        static const hipError_t once = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_tm_proj<KCV>),      \
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); \
+        attr = once;                                                                                             \
+        if (once == hipSuccess) hipLaunchKernelGGL((k_tm_proj<KCV>), grid, dim3(512), smem(KCV), st, a);         \
+    } while (0)
+        if (kc1 == 2) FF_TM_PROJ(2);
+        else if (kc1 == 4) FF_TM_PROJ(4);
+        else FF_TM_PROJ(8);
+#undef FF_TM_PROJ
+        if (attr != hipSuccess) return fail(FF_EHIP, "k_tm_proj: dynamic LDS limit: %s", hipGetErrorString(attr));
     }
     {
         TmMulArgs a{};
