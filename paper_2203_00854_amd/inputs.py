@@ -415,3 +415,67 @@ def make_global_case(spec_or_name, seed: int = SEED) -> GlobalCase:
     elif kind != "none":
         raise ValueError(spec.mask)
     return GlobalCase(spec, m, mask, w)
+
+
+# --------------------------------------------------------------------------- attention core (for its backward pass)
+@dataclass(frozen=True)
+class CoreSpec:
+    """Operands of the fused attention core: q, k, v, g, do are [rows, heads, length, head_dim]; bias is
+    [heads, length, length] float32 (or absent), mask [rows, length] ("none" | "tail:K" | "random:P")."""
+    name: str
+    rows: int
+    heads: int
+    length: int
+    head_dim: int
+    has_bias: bool = True
+    mask: str = "none"
+    stream: str = ""
+
+    @property
+    def stream_name(self):
+        return self.stream or self.name
+
+
+@dataclass
+class CoreCase:
+    spec: CoreSpec
+    tensors: Dict[str, np.ndarray] = field(default_factory=dict)   # q, k, v, g, do: bf16 bit patterns; bias: float32
+    mask: Optional[np.ndarray] = None
+
+
+# the attention cores of the paper's training shapes (Table 1 / Table 2): MSA row attention (128 rows, 8 heads of
+# 32, 256 residues, pair bias) and triangle attention (256 rows, 4 heads of 32, 256 residues)
+CORE_SPECS = {
+    "core_row_256": CoreSpec("core_row_256", 128, 8, 256, 32, True, "tail:16"),
+    "core_tri_256": CoreSpec("core_tri_256", 256, 4, 256, 32, True, "random:0.95"),
+}
+
+
+def make_core_case(spec_or_name, seed: int = SEED) -> CoreCase:
+    """q, k, v ~ N(0,1) (what the projections of normalised activations give), g = sigmoid of N(1,1), bias ~ N(0,1),
+    do ~ N(0,1); all but the bias rounded to bfloat16."""
+    spec = CORE_SPECS[spec_or_name] if isinstance(spec_or_name, str) else spec_or_name
+    shape = (spec.rows, spec.heads, spec.length, spec.head_dim)
+    n = int(np.prod(shape))
+
+    def gen(name, count):
+        return normal(stream_key(seed, spec.stream_name, name), count)
+
+    t: Dict[str, np.ndarray] = {}
+    for name in ("q", "k", "v", "do"):
+        t[name] = to_storage(gen(name, n), "bf16").reshape(shape)
+    t["g"] = to_storage(1.0 / (1.0 + np.exp(-(gen("g", n) + 1.0))), "bf16").reshape(shape)
+    if spec.has_bias:
+        t["bias"] = gen("bias", spec.heads * spec.length * spec.length).astype(np.float32).reshape(
+            spec.heads, spec.length, spec.length)
+    kind, _, arg = spec.mask.partition(":")
+    mask = None
+    if kind == "tail":
+        mask = np.ones((spec.rows, spec.length), np.float32)
+        mask[:, spec.length - int(arg):] = 0.0
+    elif kind == "random":
+        mask = bernoulli(stream_key(seed, spec.stream_name, "mask"), spec.rows * spec.length, float(arg)).reshape(
+            spec.rows, spec.length)
+    elif kind != "none":
+        raise ValueError(spec.mask)
+    return CoreCase(spec, t, mask)
