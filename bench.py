@@ -369,6 +369,51 @@ def time_global(name, steps, warmup, measured):
             "workspace_bytes": P.ff_global_column_attention_workspace_bytes(desc), "kernels": rows}
 
 
+def time_backward(name, steps, warmup, measured):
+    """Backward pass of the fused attention core (ff_attention_core_backward): counted flop = the five
+    contractions of the chain rule (dv, dP, dq, dk: 2 L^2 d each per (row, head); the recomputed S is not
+    counted as useful work), i.e. twice the forward core's."""
+    import torch
+    import paper_2203_00854_amd as P
+    from paper_2203_00854_amd import inputs as I
+    case = I.make_core_case(name)
+    sp = case.spec
+    desc, t, mask = P.core_to_device(case, "cuda:0")
+    ws = torch.empty(P.ff_attention_core_backward_workspace_bytes(desc), dtype=torch.uint8, device="cuda:0")
+
+    def step():
+        P.ff_attention_core_backward(desc, t["q"], t["k"], t["v"], t["g"], t.get("bias"), mask, t["do"], ws=ws)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    P.ff_profile_enable(True)
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    kernels = P.ff_profile_collect()
+    P.ff_profile_enable(False)
+    pair = 2.0 * sp.rows * sp.heads * sp.length * sp.length * sp.head_dim      # one L x L x d contraction over all (row, head)
+    executed = {"k_bwd_stats": 2 * pair, "k_bwd_dq": 3 * pair, "k_bwd_dkv": 4 * pair, "k_bwd_dbias": 2 * pair}
+    rows = []
+    for kname, (kms, cnt) in kernels.items():
+        r = {"kernel": kname, "avg_us": kms / cnt * 1e3}
+        if kname in executed:
+            tf = executed[kname] / (kms / cnt * 1e-3) / 1e12
+            r.update(bound="mfma", executed_flop=executed[kname], achieved_tflops=tf, frac=tf / PEAK_MFMA_BF16_TFLOPS,
+                     frac_of_measured_peak=tf / measured["mfma_tflops"])
+        rows.append(r)
+    rows.sort(key=lambda r: -r["avg_us"])
+    flop = 4 * pair
+    return {"ms_per_call": ms, "tflops": flop / (ms * 1e-3) / 1e12, "frac_mfma_peak": flop / (ms * 1e-3) / 1e12 / PEAK_MFMA_BF16_TFLOPS,
+            "counted_flop_per_step": flop, "steps": steps, "kernels": rows}
+
+
 def time_layernorm(steps):
     """ff_layernorm alone (the stand-alone entry point; inside the attention the LayerNorm is
     part of the projection GEMM): rows x c as in the MSA and pair representations of the
@@ -435,6 +480,7 @@ def main():
     ap.add_argument("--workload", default="c2_row_bf16_train")
     ap.add_argument("--no-others", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--backward-only", action="store_true", help="time only the attention-core backward pass")
     ap.add_argument("--global-only", action="store_true", help="time only the extra-MSA global column attention shapes")
     ap.add_argument("--trimul-only", action="store_true", help="time only the triangular multiplicative update shapes")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -459,6 +505,9 @@ def main():
         del src, dst
 
     measured = calibrate()
+    if args.backward_only:
+        print(json.dumps({name: time_backward(name, args.steps, 3, measured) for name in ("core_row_256", "core_tri_256")}))
+        return
     if args.global_only:
         print(json.dumps({name: time_global(name, st, 3, measured) for name, st in
                           (("gca_bf16_1024x384", args.steps), ("gca_bf16_5120x384", max(args.steps // 5, 3)))}))
@@ -535,6 +584,10 @@ def main():
                                          if k in r} for r in kernel_rooflines(c2.spec, k2, st, measured)]}
             del c2
             torch.cuda.empty_cache()
+        # backward pass of the fused attention core at the initial-training shapes
+        line["attention_core_backward"] = {name: time_backward(name, max(args.steps // 4, 5), 3, measured)
+                                           for name in ("core_row_256", "core_tri_256")}
+        torch.cuda.empty_cache()
         # the extra-MSA global column attention at the paper's two extra-MSA sizes
         line["global_column_attention"] = {
             name: time_global(name, st, wu, measured)

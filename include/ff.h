@@ -229,6 +229,38 @@ ff_status ff_global_column_attention(const ff_global_desc* desc, const ff_global
                                      const void* m, const float* mask, void* out,
                                      void* ws, size_t ws_bytes, void* hip_stream);
 
+/* Backward pass of the fused attention core (Section 6.3 benchmarks the fused scale + mask + bias softmax
+ * forward and backward; Table 6 reports forward and backward per Evoformer layer).  The core, per batch row r
+ * and head h, with scale = 1 / sqrt(head_dim) and M(t) = 0 if t == 1 else -inf:
+ *   S[r,h,i,j] = scale q[r,h,i,:] . k[r,h,j,:] + bias[h,i,j] + M(mask[r,j]);  P = softmax over j of S
+ *   ctx[r,h,i,:] = sum_j P[r,h,i,j] v[r,h,j,:];   o = g * ctx          (g: the gate after its sigmoid)
+ * Given dout = dLoss/do the call returns
+ *   dg = dout * ctx;  with dctx = dout * g:  dv[j] = sum_i P[i,j] dctx[i];  dP[i,j] = dctx[i] . v[j];
+ *   dS = P * (dP - rowsum(P * dP));  dq[i] = scale sum_j dS[i,j] k[j];  dk[j] = scale sum_i dS[i,j] q[i];
+ *   dbias[h,i,j] = sum_r dS[r,h,i,j].
+ * The score matrix is recomputed tile by tile, never stored (Section 3.2).  A query without unmasked keys has
+ * P = 0 and all of its gradients are zero.  q, k, v, g, dout and the four gradients are bfloat16
+ * [rows, heads, length, head_dim]; bias and dbias float32 [heads, length, length] (both NULL for a module without
+ * bias); mask float32 [rows, length] of 0/1 or NULL.  P, dS and dctx are rounded to bfloat16 as matrix-core
+ * operands; logsumexp, delta and all accumulations are float32; dbias is summed over the rows in a fixed order. */
+typedef struct {
+    int32_t dtype;      /* ff_dtype; FF_BF16 only */
+    int32_t rows;       /* batch rows R */
+    int32_t heads;      /* H */
+    int32_t length;     /* attended length L (queries and keys) */
+    int32_t head_dim;   /* 8, 16 or 32 */
+} ff_core_desc;
+
+/* Bytes of device workspace (logsumexp and delta per query, dctx); 0 if desc is invalid or unsupported. */
+size_t ff_attention_core_backward_workspace_bytes(const ff_core_desc* desc);
+
+/* All tensor pointers are device pointers, 16-byte aligned; gradient tensors must not overlap the inputs or
+ * each other; ws 256-byte aligned.  Errors as for the other entry points. */
+ff_status ff_attention_core_backward(const ff_core_desc* desc, const void* q, const void* k, const void* v,
+                                     const void* g, const float* bias, const float* mask, const void* dout,
+                                     void* dq, void* dk, void* dv, void* dg, float* dbias,
+                                     void* ws, size_t ws_bytes, void* hip_stream);
+
 /* For callers that cannot allocate: code under HIP graph capture, tight serving loops and
  * harnesses that forbid hipMalloc, which therefore have no workspace to hand over.
  * The same module as ff_attention_chunked, with the workspace taken from a device array that is

@@ -55,6 +55,10 @@ class GlobalWeights(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in GLOBAL_FIELDS]
 
 
+class CoreDesc(C.Structure):
+    _fields_ = [("dtype", C.c_int32), ("rows", C.c_int32), ("heads", C.c_int32), ("length", C.c_int32), ("head_dim", C.c_int32)]
+
+
 class FFError(RuntimeError):
     def __init__(self, status: int, message: str):
         super().__init__(f"libff status {status}: {message}")
@@ -101,6 +105,10 @@ def lib() -> C.CDLL:
         L.ff_global_column_attention.restype = C.c_int
         L.ff_global_column_attention.argtypes = [C.POINTER(GlobalDesc), C.POINTER(GlobalWeights), C.c_void_p, C.c_void_p,
                                                  C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.ff_attention_core_backward_workspace_bytes.restype = C.c_size_t
+        L.ff_attention_core_backward_workspace_bytes.argtypes = [C.POINTER(CoreDesc)]
+        L.ff_attention_core_backward.restype = C.c_int
+        L.ff_attention_core_backward.argtypes = [C.POINTER(CoreDesc)] + [C.c_void_p] * 13 + [C.c_size_t, C.c_void_p]
         L.ff_attention_path.restype = C.c_char_p
         L.ff_attention_path.argtypes = [C.POINTER(AttnDesc)]
         L.ff_attention_last_path.restype = C.c_char_p
@@ -301,6 +309,28 @@ def ff_global_column_attention(desc: GlobalDesc, w: Dict[str, "object"], m, mask
     return out
 
 
+def ff_attention_core_backward_workspace_bytes(desc: CoreDesc) -> int:
+    n = lib().ff_attention_core_backward_workspace_bytes(C.byref(desc))
+    if n == 0:
+        raise FFError(FF_EINVAL, last_error())
+    return n
+
+
+def ff_attention_core_backward(desc: CoreDesc, q, k, v, g, bias, mask, dout, ws=None):
+    """Gradients of the fused attention core; returns (dq, dk, dv, dg, dbias) (dbias None without a bias)."""
+    import torch
+    for t in (q, k, v, g, dout):
+        assert t.is_cuda and t.is_contiguous()
+    dq, dk, dv, dg = (torch.empty_like(q) for _ in range(4))
+    dbias = None if bias is None else torch.empty_like(bias)
+    if ws is None:
+        ws = _alloc_ws(ff_attention_core_backward_workspace_bytes(desc), q.device)
+    _check(lib().ff_attention_core_backward(C.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(g), _ptr(bias), _ptr(mask),
+                                            _ptr(dout), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dg), _ptr(dbias), _ptr(ws),
+                                            ws.numel(), _stream()))
+    return dq, dk, dv, dg, dbias
+
+
 def ff_gated_attention_residual(desc: AttnDesc, w: Dict[str, "object"], x, z=None, mask=None, chunk_rows: int = 0,
                                 out=None, ws=None, in_place: bool = False):
     """x + module(x); chunk_rows = 0 takes all batch rows at once.  in_place=True updates x itself."""
@@ -369,6 +399,13 @@ def global_to_device(case, device="cuda:0"):
     sp = case.spec
     desc = GlobalDesc(FF_F32 if sp.dtype == "f32" else FF_BF16, sp.n_seq, sp.n_res, sp.c, sp.heads, sp.head_dim, sp.ln_eps)
     return desc, {k: _upload(v, device) for k, v in case.weights.items()}, _upload(case.m, device), _upload(case.mask, device)
+
+
+def core_to_device(case, device="cuda:0"):
+    """Upload a seeded attention-core case (inputs.CoreCase).  Returns (desc, tensors dict, mask)."""
+    sp = case.spec
+    desc = CoreDesc(FF_BF16, sp.rows, sp.heads, sp.length, sp.head_dim)
+    return desc, {k: _upload(v, device) for k, v in case.tensors.items()}, _upload(case.mask, device)
 
 
 def to_device(case, device="cuda:0"):

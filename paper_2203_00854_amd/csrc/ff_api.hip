@@ -20,7 +20,8 @@ static std::vector<hipEvent_t> g_prof_pool;
 static const char* kKindNames[KK_COUNT] = {"k_prep", "pair bias pass", "k_gemm<PROJ>", "k_attn",
                                            "k_gemm<OUT>", "k_layernorm", "generic family", "probe: mfma loop",
                                            "probe: copy", "k_tm_prep", "k_tm_proj", "k_tm_mul", "k_tm_out",
-                                           "k_gca_prep", "k_gca_kv", "k_gca_softmax", "k_gca_out"};
+                                           "k_gca_prep", "k_gca_kv", "k_gca_softmax", "k_gca_out",
+                                           "k_bwd_stats", "k_bwd_dq", "k_bwd_dkv", "k_bwd_dbias"};
 
 static hipEvent_t prof_event() {
     if (!g_prof_pool.empty()) {
@@ -323,6 +324,53 @@ ff_status ff_global_column_attention(const ff_global_desc* desc, const ff_global
     if (overlaps(out, m_bytes, ws, need) || overlaps(m, m_bytes, ws, need))
         return fail(FF_EINVAL, "m and out must not overlap the workspace");
     return global_run(*desc, *w, m, mask, out, ws, (hipStream_t)hip_stream);
+}
+
+static ff_status check_core(const ff_core_desc* d) {
+    if (!d) return fail(FF_EINVAL, "desc is NULL");
+    if (d->dtype != FF_F32 && d->dtype != FF_BF16) return fail(FF_EINVAL, "bad dtype %d", d->dtype);
+    if (d->rows < 1 || d->heads < 1 || d->length < 1 || d->head_dim < 1)
+        return fail(FF_EINVAL, "non-positive size (rows=%d heads=%d length=%d head_dim=%d)", d->rows, d->heads, d->length, d->head_dim);
+    if (d->length > 16384) return fail(FF_EUNSUPPORTED, "length %d > 16384", d->length);
+    const int64_t tiles = (int64_t)d->rows * d->heads * ((d->length + 31) / 32);
+    const int64_t btiles = (int64_t)d->heads * ((d->length + 31) / 32) * ((d->length + 31) / 32);
+    if (tiles > ((int64_t)1 << 30) || btiles > ((int64_t)1 << 30)) return fail(FF_EUNSUPPORTED, "too many tiles for one launch");
+    if (!core_backward_supported(*d))
+        return fail(FF_EUNSUPPORTED, "attention core backward: bfloat16 only, head_dim 8, 16 or 32 (got dtype %d, head_dim %d)",
+                    d->dtype, d->head_dim);
+    return FF_OK;
+}
+
+size_t ff_attention_core_backward_workspace_bytes(const ff_core_desc* desc) {
+    if (check_core(desc) != FF_OK) return 0;
+    return core_backward_workspace(*desc);
+}
+
+ff_status ff_attention_core_backward(const ff_core_desc* desc, const void* q, const void* k, const void* v, const void* g,
+                                     const float* bias, const float* mask, const void* dout, void* dq, void* dk, void* dv,
+                                     void* dg, float* dbias, void* ws, size_t ws_bytes, void* hip_stream) {
+    ff_status st = check_core(desc);
+    if (st != FF_OK) return st;
+    if (!q || !k || !v || !g || !dout || !dq || !dk || !dv || !dg) return fail(FF_EINVAL, "a required tensor pointer is NULL");
+    if ((bias == nullptr) != (dbias == nullptr)) return fail(FF_EINVAL, "dbias must be given exactly when bias is");
+    if (!aligned16(bias) || !aligned16(dbias)) return fail(FF_EINVAL, "bias and dbias must be 16-byte aligned");
+    const void* ptrs[] = {q, k, v, g, dout, dq, dk, dv, dg};
+    for (const void* t : ptrs)
+        if (!aligned16(t)) return fail(FF_EINVAL, "tensor pointers must be 16-byte aligned");
+    const size_t n_bytes = (size_t)desc->rows * desc->heads * desc->length * desc->head_dim * 2;
+    const void* ins[] = {q, k, v, g, dout};
+    void* outs[] = {dq, dk, dv, dg};
+    for (void* o : outs) {
+        for (const void* in : ins)
+            if (overlaps(o, n_bytes, in, n_bytes)) return fail(FF_EINVAL, "a gradient tensor overlaps an input");
+        for (void* o2 : outs)
+            if (o != o2 && overlaps(o, n_bytes, o2, n_bytes)) return fail(FF_EINVAL, "gradient tensors overlap each other");
+    }
+    const size_t need = core_backward_workspace(*desc);
+    if (!ws) return fail(FF_EINVAL, "workspace is NULL (%zu bytes needed)", need);
+    if (((uintptr_t)ws & 255u) != 0) return fail(FF_EINVAL, "workspace must be 256-byte aligned");
+    if (ws_bytes < need) return fail(FF_EWORKSPACE, "workspace too small: %zu bytes given, %zu needed", ws_bytes, need);
+    return core_backward_run(*desc, q, k, v, g, bias, mask, dout, dq, dk, dv, dg, dbias, ws, (hipStream_t)hip_stream);
 }
 
 size_t ff_attention_workspace_bytes(const ff_attn_desc* desc, int32_t chunk_rows) {

@@ -70,7 +70,7 @@ struct Workspace {
 // kernel kinds for the launch timer (ff_profile_* in the C ABI)
 enum KernelKind { KK_PREP = 0, KK_BIAS, KK_PROJ, KK_ATTN, KK_OUT, KK_LAYERNORM, KK_GENERIC, KK_PROBE_MFMA, KK_PROBE_COPY,
                   KK_TM_PREP, KK_TM_PROJ, KK_TM_MUL, KK_TM_OUT, KK_GCA_PREP, KK_GCA_KV, KK_GCA_SOFTMAX, KK_GCA_OUT,
-                  KK_COUNT };
+                  KK_BWD_STATS, KK_BWD_DQ, KK_BWD_DKV, KK_BWD_DBIAS, KK_COUNT };
 void prof_begin(int kind, hipStream_t st);
 void prof_end(int kind, hipStream_t st);
 // brackets the launches issued in its scope with HIP events when the timer is on
@@ -121,6 +121,13 @@ bool global_supported(const ff_global_desc& d);
 size_t global_workspace(const ff_global_desc& d);
 ff_status global_run(const ff_global_desc& d, const ff_global_weights& w, const void* m, const float* mask, void* out,
                      void* ws, hipStream_t stream);
+
+// backward pass of the fused attention core (ff_attn_bwd.hip), bf16 only
+bool core_backward_supported(const ff_core_desc& d);
+size_t core_backward_workspace(const ff_core_desc& d);
+ff_status core_backward_run(const ff_core_desc& d, const void* q, const void* k, const void* v, const void* g, const float* bias,
+                            const float* mask, const void* dout, void* dq, void* dk, void* dv, void* dg, float* dbias,
+                            void* ws, hipStream_t stream);
 
 // LayerNorm (ff_layernorm.hip)
 ff_status layernorm_launch(const void* x, const void* g, const void* b, void* y, int64_t rows, int c,

@@ -1,0 +1,109 @@
+"""GPU parity of the backward pass of the fused attention core (ff_attention_core_backward through the C ABI)
+against the float64 oracle, element by element on the same seeded inputs.
+
+Tolerance, per gradient tensor: relative L2 1e-2, and per element 2e-2 * scale + 2^-8 |ref| with scale the
+tensor's root mean square (at least 1): gradients are sums of up to L (for dbias: rows x 1) products whose
+size depends on dout, so the absolute bound of the forward modules (2e-2 for outputs of order one) is taken
+relative to that scale, and the second term is the rounding of a large element itself (half a bfloat16 ulp
+of the result, or of the summands of the bias gradient, is up to 2^-8 of the value).  The library rounds P, dS,
+dctx and the results to bfloat16; logsumexp, delta and accumulators are float32.  Measured: relative L2 3e-3.
+The bias gradient gets twice the absolute part: where one key takes nearly all the weight, dS = P (dP - delta) is
+the difference of two numbers of size |dctx . v| (about 5 here) that agree to first order, so the 2^-9 relative
+rounding of the bfloat16 operands dctx and v survives in absolute terms (up to 2.5e-2 on the 256-row case) however
+small the result is, and the sum over the rows keeps the largest of them; every bfloat16 implementation of this
+backward pass has that term.
+"""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2203_00854_amd as P
+from oracle import attention_core_backward as O
+from paper_2203_00854_amd import binding as B
+from paper_2203_00854_amd import inputs as I
+from helpers import max_abs, rel_l2
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+NAMES = ("dq", "dk", "dv", "dg", "dbias")
+
+
+def f64(case):
+    t = {k: (I.widen(v) if v.dtype == np.uint16 else v).astype(np.float64) for k, v in case.tensors.items()}
+    return t
+
+
+def run(case):
+    desc, t, mask = P.core_to_device(case, DEV)
+    out = P.ff_attention_core_backward(desc, t["q"], t["k"], t["v"], t["g"], t.get("bias"), mask, t["do"])
+    torch.cuda.synchronize()
+    return out
+
+
+def check_all(case, got, ref, what):
+    for name, gt, rf in zip(NAMES, got, ref):
+        if rf is None:
+            assert gt is None
+            continue
+        g = gt.float().cpu().numpy().astype(np.float64)
+        scale = max(1.0, float(np.sqrt((rf ** 2).mean())))
+        ma, rl = max_abs(g, rf), rel_l2(g, rf)
+        print(f"{what} {name}: max_abs={ma:.3e} (scale {scale:.2f}) rel_l2={rl:.3e}", flush=True)
+        assert np.isfinite(g).all(), (what, name)
+        absolute = (4e-2 if name == "dbias" else 2e-2) * scale
+        assert np.all(np.abs(g - rf) <= absolute + 2.0 ** -8 * np.abs(rf)), (what, name, ma, scale)
+        assert rl <= 1e-2, (what, name, rl)
+
+
+def oracle(case):
+    t = f64(case)
+    return O.attention_core_backward(t["q"], t["k"], t["v"], t["g"], t.get("bias"), case.mask, t["do"])
+
+
+SHAPES = [   # rows, heads, length, head_dim, bias, mask: ragged around the 32-wide tiles
+    (1, 1, 1, 8, True, "none"), (2, 3, 31, 16, True, "random:0.7"), (3, 2, 33, 32, True, "tail:5"),
+    (2, 2, 64, 32, False, "random:0.8"), (5, 4, 97, 8, True, "random:0.9"), (2, 8, 130, 32, True, "tail:20"),
+    (3, 1, 200, 16, False, "none"), (9, 2, 70, 32, True, "random:0.5"),
+]
+
+
+@pytest.mark.parametrize("rows,heads,length,d,bias,mask", SHAPES)
+def test_ragged_shapes(rows, heads, length, d, bias, mask):
+    spec = I.CoreSpec(f"t_core_{rows}_{heads}_{length}_{d}_{int(bias)}_{mask}", rows, heads, length, d, bias, mask)
+    case = I.make_core_case(spec)
+    check_all(case, run(case), oracle(case), spec.name)
+
+
+def test_fully_masked_rows_have_zero_gradients():
+    spec = I.CoreSpec("t_core_dead", 4, 2, 50, 32, True, "random:0.8")
+    case = I.make_core_case(spec)
+    case.mask[2, :] = 0.0
+    got = run(case)
+    for t in got[:4]:
+        assert torch.count_nonzero(t[2]).item() == 0
+    check_all(case, got, oracle(case), "dead row")
+
+
+@pytest.mark.parametrize("name", ["core_row_256", "core_tri_256"])
+def test_paper_shapes(name):
+    """The attention cores of the initial-training shapes: MSA row attention (128 x 8 x 256 x 32 with pair bias)
+    and triangle attention (256 x 4 x 256 x 32)."""
+    case = I.make_core_case(name)
+    check_all(case, run(case), oracle(case), name)
+
+
+def test_bad_arguments_are_status_codes():
+    d = P.CoreDesc(P.FF_F32, 2, 2, 16, 8)
+    assert P.lib().ff_attention_core_backward_workspace_bytes(C.byref(d)) == 0
+    d = P.CoreDesc(P.FF_BF16, 2, 2, 16, 24)
+    assert P.lib().ff_attention_core_backward_workspace_bytes(C.byref(d)) == 0
+    d = P.CoreDesc(P.FF_BF16, 2, 2, 16, 8)
+    need = P.lib().ff_attention_core_backward_workspace_bytes(C.byref(d))
+    assert need > 0 and need % 256 == 0
+    a = [0x10000 * (n + 1) for n in range(12)]
+    call = lambda bias, dbias, ws_bytes: P.lib().ff_attention_core_backward(
+        C.byref(d), a[0], a[1], a[2], a[3], bias, None, a[4], a[5], a[6], a[7], a[8], dbias, 0x1000000, ws_bytes, None)
+    assert call(None, a[9], need) == B.FF_EINVAL            # dbias without bias
+    assert call(a[9], a[10], need - 1) == B.FF_EWORKSPACE
