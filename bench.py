@@ -480,6 +480,8 @@ def main():
     ap.add_argument("--workload", default="c2_row_bf16_train")
     ap.add_argument("--no-others", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--calibration-only", action="store_true", help="run only the two calibration probes")
+    ap.add_argument("--layernorm-only", action="store_true", help="time only ff_layernorm at the three bench shapes")
     ap.add_argument("--backward-only", action="store_true", help="time only the attention-core backward pass")
     ap.add_argument("--global-only", action="store_true", help="time only the extra-MSA global column attention shapes")
     ap.add_argument("--trimul-only", action="store_true", help="time only the triangular multiplicative update shapes")
@@ -505,6 +507,12 @@ def main():
         del src, dst
 
     measured = calibrate()
+    if args.calibration_only:
+        print(json.dumps({"calibration": measured}))
+        return
+    if args.layernorm_only:
+        print(json.dumps({"calibration": measured, "layernorm": time_layernorm(args.steps)}))
+        return
     if args.backward_only:
         print(json.dumps({name: time_backward(name, args.steps, 3, measured) for name in ("core_row_256", "core_tri_256")}))
         return
