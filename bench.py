@@ -195,10 +195,10 @@ def kernel_rooflines(sp, kernels, steps, measured=None):
                            + (2.0 * (4 * hd + sp.heads) * sp.c * 2 if sp.mode == 0 else 0.0), None, "hbm"),
     }
     # vector-unit work of the attention kernel that no design can avoid, in lane-operations per score
-    # element: exp2 at half rate (2), half a pack (two elements per instruction), and either half a
-    # partial-denominator instruction (d = 32) or one maximum (d < 32, where the matrix core sums the
-    # denominator but every tile takes its maximum)
-    alu_per_step = {"k_attn": R * sp.heads * L * L * (3.0 if sp.head_dim >= 32 else 3.5)}
+    # element: exp2 at half rate (2), half a pack (two elements per instruction) and half a
+    # partial-denominator instruction (two elements per dot instruction); the maximum is taken for the
+    # first key tile only
+    alu_per_step = {"k_attn": R * sp.heads * L * L * 3.0}
     traffic = traffic_bytes(sp.name)
     rows = []
     for name, (ms, cnt) in kernels.items():
