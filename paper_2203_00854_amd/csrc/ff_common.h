@@ -109,6 +109,9 @@ ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x
 ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, const float* mask,
                      const void* res, void* out, const Workspace& ws, int r0, int rows, hipStream_t stream);
 
+// compute units of the current device (queried once; 256 if the query fails); sizes the persistent grids
+int compute_units();
+
 // triangular multiplicative update (ff_trimul.hip), bf16 matrix-core kernels only
 bool trimul_supported(int dtype, int cz, int c);
 size_t trimul_workspace(int N, int cz, int c);

@@ -14,8 +14,9 @@
 //                  features, so that the sum over the tile's sequences - the query average - is a sum over the
 //                  lane's own registers) and with W_k' | W_v' (features x tokens: k, v of a token leave as
 //                  float32); partial query sums and counts go to the workspace
-//   k_gca_softmax  one block per column, one thread per sequence with all heads in registers: q from the partial
-//                  sums, two sweeps over k (maximum; exponentials, denominators, weighted sums of v), o[i] normalised
+//   k_gca_softmax  one block per column, a thread per sequence with all heads in registers: q from the partial
+//                  sums, one sweep over k and v (running maximum per thread, exponentials, denominators,
+//                  weighted sums of v), o[i] normalised
 //   k_gca_out      one wavefront per (sequence, 32 residues): gate GEMM, sigmoid, times o[i] (the gated tile is
 //                  already the B operand of the output GEMM because W_o was stored in the matching order),
 //                  output GEMM, + b_o
@@ -271,106 +272,167 @@ struct SmArgs {
     float qscale;            // log2(e) / sqrt(d)
 };
 
-// Block = one column, one thread per sequence (s = tid, tid + 256, ...) holding all H heads: k and v of a
-// sequence are read once per sweep, the H logits, H denominators and H x D weighted sums live in registers
-// (hence H and D as template parameters), and the block combines them through shuffles and LDS.
-template <int H, int D>
-__global__ __launch_bounds__(256) void k_gca_softmax(SmArgs p) {
-    constexpr int HD = H * D;
+// Sums (or maxima) of N per-lane values over the 64 lanes, N a power of two up to 64.  Instead of N butterflies
+// of six exchanges each, every exchange step halves the number of values a lane still carries (the lane keeps
+// one half of its values and hands the other half to its partner), N - 1 exchanges in all (plus the plain
+// butterfly over the remaining steps when N < 64).  Afterwards v[0] of lane l is the result for value index
+// l >> log2(64 / N).  Exchanges go through the LDS crossbar, which is what bounds this kernel otherwise.
+template <int N, int n, bool MAX>
+__device__ __forceinline__ void wave_reduce_scatter_step(float (&v)[N], int lane, int o) {
+    if constexpr (n > 1) {
+        const bool up = (lane & o) != 0;
+#pragma unroll
+        for (int f = 0; f < n / 2; ++f) {
+            const float send = up ? v[f] : v[f + n / 2];
+            const float keep = up ? v[f + n / 2] : v[f];
+            const float recv = __shfl_xor(send, o, 64);
+            v[f] = MAX ? fmaxf(keep, recv) : keep + recv;
+        }
+        wave_reduce_scatter_step<N, n / 2, MAX>(v, lane, o >> 1);
+    } else {
+        for (; o > 0; o >>= 1) {
+            const float recv = __shfl_xor(v[0], o, 64);
+            v[0] = MAX ? fmaxf(v[0], recv) : v[0] + recv;
+        }
+    }
+}
+template <int N, bool MAX>
+__device__ __forceinline__ void wave_reduce_scatter(float (&v)[N], int lane) {
+    static_assert(N >= 1 && N <= 64 && (N & (N - 1)) == 0, "a power of two up to 64");
+    wave_reduce_scatter_step<N, N, MAX>(v, lane, 32);
+}
+
+// Block = one column, NT threads; a thread takes the sequences s = tid, tid + NT, ... and holds all H heads:
+// k and v of a sequence are read ONCE (one sweep: every thread keeps a running maximum per head and rescales
+// its own partial sums when that maximum rises, so no pass over the logits precedes the exponentials), the H
+// denominators and H x D weighted sums live in registers (hence H and D as template parameters), and the
+// block combines the threads' partial results, each brought to the common maximum, through shuffles and LDS.
+template <int H, int D, int NT>
+__global__ __launch_bounds__(NT) void k_gca_softmax(SmArgs p) {
+    constexpr int HD = H * D, NW = NT / 64, PW = HD + 2 * H;
     __shared__ float s_q[HD];
-    __shared__ float s_red[4 * (HD + H)];
+    __shared__ float s_red[NW * PW > NT ? NW * PW : NT];   // per wavefront: weighted sums, denominators, maxima (first: query partial sums)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, i = blockIdx.x;
+    // partial counts and query sums of the column's chunks: spread over the lanes / the threads so that the loads
+    // do not queue behind each other (a column of 5120 sequences has 20 chunks)
     float cnt = 0.f;
-    for (int j = 0; j < p.nchunk; ++j) cnt += p.cntpart[(size_t)i * p.nchunk + j];
+    for (int j = lane; j < p.nchunk; j += 64) cnt += p.cntpart[(size_t)i * p.nchunk + j];
+    cnt = wave_sum(cnt);
     if (cnt == 0.f) {                              // no unmasked sequence: zero context (uniform over the block)
         if (tid < HD) p.o[(size_t)i * HD + tid] = 0.f;
         return;
     }
-    if (tid < HD) {
+    {
+        constexpr int G = NT / HD;                 // threads per feature
+        const int f = tid % HD, g = tid / HD;
         float q = 0.f;
-        for (int j = 0; j < p.nchunk; ++j) q += p.qpart[((size_t)i * p.nchunk + j) * HD + tid];
-        s_q[tid] = (q / cnt + p.Cq[tid]) * p.qscale;
+        for (int j = g; j < p.nchunk; j += G) q += p.qpart[((size_t)i * p.nchunk + j) * HD + f];
+        s_red[g * HD + f] = q;
+        __syncthreads();
+        if (tid < HD) {
+            float t = 0.f;
+#pragma unroll
+            for (int gg = 0; gg < G; ++gg) t += s_red[gg * HD + tid];
+            s_q[tid] = (t / cnt + p.Cq[tid]) * p.qscale;
+        }
     }
     __syncthreads();
     const float* kvc = p.kv + (size_t)i * p.S * (2 * D);
 
-    // sweep 1: maximum of every head's logits over the unmasked sequences
-    float mx[H];
+    float mx[H], den[H], o[HD];
 #pragma unroll
-    for (int h = 0; h < H; ++h) mx[h] = -INFINITY;
-    for (int s = tid; s < p.S; s += 256) {
-        if (p.mask && p.mask[(size_t)s * p.R + i] == 0.f) continue;
-        float k[D];
-        const float4* kp = reinterpret_cast<const float4*>(kvc + (size_t)s * (2 * D));
-#pragma unroll
-        for (int e4 = 0; e4 < D / 4; ++e4) {
-            const float4 k4 = kp[e4];
-            k[4 * e4] = k4.x; k[4 * e4 + 1] = k4.y; k[4 * e4 + 2] = k4.z; k[4 * e4 + 3] = k4.w;
-        }
-#pragma unroll
-        for (int h = 0; h < H; ++h) {
-            float l = 0.f;
-#pragma unroll
-            for (int e = 0; e < D; ++e) l += s_q[h * D + e] * k[e];
-            mx[h] = fmaxf(mx[h], l);
-        }
-    }
-#pragma unroll
-    for (int h = 0; h < H; ++h) {
-        mx[h] = wave_max(mx[h]);
-        if (lane == 0) s_red[wave * H + h] = mx[h];
-    }
-    __syncthreads();
-#pragma unroll
-    for (int h = 0; h < H; ++h)      // (at least one sequence of the column is unmasked: finite)
-        mx[h] = fmaxf(fmaxf(s_red[h], s_red[H + h]), fmaxf(s_red[2 * H + h], s_red[3 * H + h]));
-    __syncthreads();
-
-    // sweep 2: exponentials, denominators, weighted sums of v
-    float den[H], o[HD];
-#pragma unroll
-    for (int h = 0; h < H; ++h) den[h] = 0.f;
+    for (int h = 0; h < H; ++h) { mx[h] = -INFINITY; den[h] = 0.f; }
 #pragma unroll
     for (int f = 0; f < HD; ++f) o[f] = 0.f;
-    for (int s = tid; s < p.S; s += 256) {
-        if (p.mask && p.mask[(size_t)s * p.R + i] == 0.f) continue;
-        float k[D], v[D];
-        const float4* kp = reinterpret_cast<const float4*>(kvc + (size_t)s * (2 * D));
+    // U sequences at a time: their loads (k, v and the mask entry, none of which depends on another) are all in
+    // flight before the first is used; k and v of a masked sequence exist (finite) and are simply not used
+    constexpr int U = 64 / (2 * D);
+    for (int s0 = tid; s0 < p.S; s0 += U * NT) {
+        float4 kv4[U][2 * D / 4];
+        float mk[U];
 #pragma unroll
-        for (int e4 = 0; e4 < D / 4; ++e4) {
-            const float4 k4 = kp[e4], v4 = kp[D / 4 + e4];
-            k[4 * e4] = k4.x; k[4 * e4 + 1] = k4.y; k[4 * e4 + 2] = k4.z; k[4 * e4 + 3] = k4.w;
-            v[4 * e4] = v4.x; v[4 * e4 + 1] = v4.y; v[4 * e4 + 2] = v4.z; v[4 * e4 + 3] = v4.w;
+        for (int u = 0; u < U; ++u) {
+            const int s = s0 + u * NT;
+            mk[u] = 0.f;
+#pragma unroll
+            for (int e4 = 0; e4 < 2 * D / 4; ++e4) kv4[u][e4] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (s < p.S) {
+                const float4* kp = reinterpret_cast<const float4*>(kvc + (size_t)s * (2 * D));
+#pragma unroll
+                for (int e4 = 0; e4 < 2 * D / 4; ++e4) kv4[u][e4] = kp[e4];
+                mk[u] = 1.f;
+                if (p.mask) mk[u] = p.mask[(size_t)s * p.R + i];
+            }
         }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (mk[u] == 0.f) continue;
+            float k[D], v[D];
+#pragma unroll
+            for (int e4 = 0; e4 < D / 4; ++e4) {
+                const float4 k4 = kv4[u][e4], v4 = kv4[u][D / 4 + e4];
+                k[4 * e4] = k4.x; k[4 * e4 + 1] = k4.y; k[4 * e4 + 2] = k4.z; k[4 * e4 + 3] = k4.w;
+                v[4 * e4] = v4.x; v[4 * e4 + 1] = v4.y; v[4 * e4 + 2] = v4.z; v[4 * e4 + 3] = v4.w;
+            }
+#pragma unroll
+            for (int h = 0; h < H; ++h) {
+                float l = 0.f;
+#pragma unroll
+                for (int e = 0; e < D; ++e) l += s_q[h * D + e] * k[e];
+                const float m_new = fmaxf(mx[h], l);
+                const float a = __builtin_amdgcn_exp2f(mx[h] - m_new);      // 0 for the thread's first sequence
+                const float w = __builtin_amdgcn_exp2f(l - m_new);
+                mx[h] = m_new;
+                den[h] = den[h] * a + w;
+#pragma unroll
+                for (int e = 0; e < D; ++e) o[h * D + e] = o[h * D + e] * a + w * v[e];
+            }
+        }
+    }
+    // bring the lanes of a wavefront to its maximum (a lane without any sequence has -inf and all-zero sums)
+    {
+        float M[H];
+#pragma unroll
+        for (int h = 0; h < H; ++h) M[h] = mx[h];
+        wave_reduce_scatter<H, true>(M, lane);            // lane l: maximum of head l / (64 / H)
 #pragma unroll
         for (int h = 0; h < H; ++h) {
-            float l = 0.f;
+            const float Mh = __shfl(M[0], h * (64 / H), 64);
+            const float sc = mx[h] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mx[h] - Mh);
+            den[h] *= sc;
 #pragma unroll
-            for (int e = 0; e < D; ++e) l += s_q[h * D + e] * k[e];
-            const float w = __builtin_amdgcn_exp2f(l - mx[h]);
-            den[h] += w;
-#pragma unroll
-            for (int e = 0; e < D; ++e) o[h * D + e] += w * v[e];
+            for (int e = 0; e < D; ++e) o[h * D + e] *= sc;
         }
+        if ((lane & (64 / H - 1)) == 0) s_red[wave * PW + HD + H + lane / (64 / H)] = M[0];
+        wave_reduce_scatter<H, false>(den, lane);
+        if ((lane & (64 / H - 1)) == 0) s_red[wave * PW + HD + lane / (64 / H)] = den[0];
     }
+    if constexpr (HD <= 64) {
+        wave_reduce_scatter<HD, false>(o, lane);
+        if ((lane & (64 / HD - 1)) == 0) s_red[wave * PW + lane / (64 / HD)] = o[0];
+    } else {
+        static_assert(HD == 128, "the weighted sums are reduced 64 at a time");
+        float o1[64], o2[64];
 #pragma unroll
-    for (int h = 0; h < H; ++h) {
-        den[h] = wave_sum(den[h]);
-        if (lane == 0) s_red[wave * (HD + H) + HD + h] = den[h];
-    }
-#pragma unroll
-    for (int f = 0; f < HD; ++f) {
-        o[f] = wave_sum(o[f]);
-        if (lane == 0) s_red[wave * (HD + H) + f] = o[f];
+        for (int f = 0; f < 64; ++f) { o1[f] = o[f]; o2[f] = o[64 + f]; }
+        wave_reduce_scatter<64, false>(o1, lane);
+        wave_reduce_scatter<64, false>(o2, lane);
+        s_red[wave * PW + lane] = o1[0];
+        s_red[wave * PW + 64 + lane] = o2[0];
     }
     __syncthreads();
     if (tid < HD) {
         const int h = tid / D;
+        float M = -INFINITY;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) M = fmaxf(M, s_red[w * PW + HD + H + h]);      // finite: cnt > 0
         float so = 0.f, sd = 0.f;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-            so += s_red[w * (HD + H) + tid];
-            sd += s_red[w * (HD + H) + HD + h];
+        for (int w = 0; w < NW; ++w) {
+            const float mw = s_red[w * PW + HD + H + h];
+            const float sc = mw == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(mw - M);
+            so += s_red[w * PW + tid] * sc;
+            sd += s_red[w * PW + HD + h] * sc;
         }
         p.o[(size_t)i * HD + tid] = so / sd;
     }
@@ -387,7 +449,7 @@ struct OutArgs {
     const float *Cg, *Co;
 };
 
-template <int KC>
+template <int KC, int NGT>       // contraction steps of the gate GEMM (c / 16, rounded up to 2, 4, 8); gate tiles H d / 32
 __global__ __launch_bounds__(256) void k_gca_out(OutArgs p) {
     constexpr int PITCH = KC * 32 + 16;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -396,8 +458,14 @@ __global__ __launch_bounds__(256) void k_gca_out(OutArgs p) {
     unsigned char* s_wo = smem + (size_t)p.Hd * PITCH;           // [c][po]
     float* s_cg = reinterpret_cast<float*>(s_wo + (size_t)p.c * po);   // [Hd] gate offsets
     float* s_co = s_cg + p.Hd;                                   // [c]  output bias
+    const int pt = p.c * 2 + 16;                                 // bytes per token row of the staged output tile
     const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // the wavefront's own staging area for one output tile [32 tokens][c]: results leave the accumulators as 8-byte
+    // pieces of 32 different tokens; written to memory like that every store instruction would touch 32 lines, so
+    // they are gathered here and leave as whole contiguous kilobytes (only this wavefront reads or writes the area;
+    // a wavefront's LDS operations complete in order)
+    unsigned char* s_tile = reinterpret_cast<unsigned char*>(s_co + p.c) + (size_t)wave * 32 * pt;
     for (int id = tid; id < p.Hd; id += 256) s_cg[id] = p.Cg[id];
     for (int id = tid; id < p.c; id += 256) s_co[id] = p.Co[id];
     for (int id = tid; id < p.Hd * 2 * KC; id += 256) {
@@ -411,67 +479,74 @@ __global__ __launch_bounds__(256) void k_gca_out(OutArgs p) {
     }
     __syncthreads();
 
-    // a tile = 32 consecutive residues of one sequence: 32 c contiguous elements of m and of out
+    // a tile = 32 consecutive residues of one sequence: 32 c contiguous elements of m and of out.  A wavefront
+    // keeps ONE residue tile and walks over the sequences: the attended vectors o[i] of its 32 residues are the
+    // same for every sequence, so they are read once, and the tokens of the next sequence are on their way while
+    // this one is worked on.
     const int tpr = (p.R + 31) >> 5;             // residue tiles per sequence
-    const int n_gt = p.Hd >> 5, n_ct = p.c >> 5; // gate tiles, output tiles (at most 4 each)
-    for (int task = blockIdx.x * 4 + wave; task < p.S * tpr; task += gridDim.x * 4) {
-        const int s = task / tpr, i_raw = (task - s * tpr) * 32 + col;
-        const bool valid = i_raw < p.R;
-        const int i = valid ? i_raw : p.R - 1;
-        const size_t tok = (size_t)s * p.R + i;
-        Frag xa[KC];
-        {
-            const bf16_t* mp = p.m + tok * p.c;
-#pragma unroll
-            for (int q = 0; q < KC; ++q) {
-                xa[q].u = make_uint4(0, 0, 0, 0);
-                if (valid && 16 * q + 8 * hf < p.c) xa[q].u = *reinterpret_cast<const uint4*>(mp + 16 * q + 8 * hf);
-            }
-        }
-        // o[i] of the lane's residue, every group of four features it will meet (issued before anything waits)
+    const int n_ct = p.c >> 5;                   // output tiles (at most 4)
+    const int gw = blockIdx.x * 4 + wave, ng = (gridDim.x * 4) / tpr;      // ng >= 1: wavefronts per residue tile
+    const int rt = gw % tpr, sg = gw / tpr;
+    if (sg >= ng || sg >= p.S) return;           // (no barrier after this point)
+    const int i_raw = rt * 32 + col;
+    const bool valid = i_raw < p.R;
+    const int i = valid ? i_raw : p.R - 1;
+    float4 o4[NGT][4];
+    {
         const float* oi = p.o + (size_t)i * p.Hd;
-        float4 o4[4][4];
 #pragma unroll
-        for (int T = 0; T < 4; ++T)
+        for (int T = 0; T < NGT; ++T)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                o4[T][g] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (T < n_gt) o4[T][g] = *reinterpret_cast<const float4*>(oi + 32 * T + 8 * g + 4 * hf);
-            }
+            for (int g = 0; g < 4; ++g) o4[T][g] = *reinterpret_cast<const float4*>(oi + 32 * T + 8 * g + 4 * hf);
+    }
+    Frag xn[KC];
+    {
+        const bf16_t* mp = p.m + ((size_t)sg * p.R + i) * p.c;
+#pragma unroll
+        for (int q = 0; q < KC; ++q) {
+            xn[q].u = make_uint4(0, 0, 0, 0);
+            if (valid && 16 * q + 8 * hf < p.c) xn[q].u = *reinterpret_cast<const uint4*>(mp + 16 * q + 8 * hf);
+        }
+    }
+    for (int s = sg; s < p.S; s += ng) {
+        Frag xa[KC];
+#pragma unroll
+        for (int q = 0; q < KC; ++q) xa[q].u = xn[q].u;
+        {
+            const int sn = s + ng < p.S ? s + ng : s;        // (the last round fetches its own tokens again)
+            const bf16_t* mp = p.m + ((size_t)sn * p.R + i) * p.c;
+#pragma unroll
+            for (int q = 0; q < KC; ++q)
+                if (valid && 16 * q + 8 * hf < p.c) xn[q].u = *reinterpret_cast<const uint4*>(mp + 16 * q + 8 * hf);
+        }
         normalise<KC>(xa, p.c, hf, p.eps, valid);
 
         // gate: features x tokens; value of feature 32T + 8g + 4hf + e in register 4g + e, times o[i][feature];
         // registers 8j .. 8j+7 of tile T packed are the B operand of contraction step 2T + j of the output GEMM
-        Frag gf[8];
+        Frag gf[2 * NGT];
 #pragma unroll
-        for (int T = 0; T < 4; ++T) {
-            if (T < n_gt) {
-                f32x16 acc;
+        for (int T = 0; T < NGT; ++T) {
+            f32x16 acc;
 #pragma unroll
-                for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+            for (int v = 0; v < 16; ++v) acc[v] = 0.f;
 #pragma unroll
-                for (int q = 0; q < KC; ++q) {
-                    Frag wf;
-                    wf.u = *reinterpret_cast<const uint4*>(s_wg + (32 * T + col) * PITCH + (2 * q + hf) * 16);
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf.v, xa[q].v, acc, 0, 0, 0);
-                }
+            for (int q = 0; q < KC; ++q) {
+                Frag wf;
+                wf.u = *reinterpret_cast<const uint4*>(s_wg + (32 * T + col) * PITCH + (2 * q + hf) * 16);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf.v, xa[q].v, acc, 0, 0, 0);
+            }
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int f0 = 32 * T + 8 * g + 4 * hf;
-                    const float4 c4 = *reinterpret_cast<const float4*>(s_cg + f0);
-                    float t[4];
+            for (int g = 0; g < 4; ++g) {
+                const int f0 = 32 * T + 8 * g + 4 * hf;
+                const float4 c4 = *reinterpret_cast<const float4*>(s_cg + f0);
+                float t[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) t[e] = sigmoid(acc[4 * g + e] + pick(c4, e)) * pick(o4[T][g], e);
-                    gf[2 * T + (g >> 1)].w[2 * (g & 1)] = pack2(t[0], t[1]);
-                    gf[2 * T + (g >> 1)].w[2 * (g & 1) + 1] = pack2(t[2], t[3]);
-                }
-            } else {
-                gf[2 * T].u = make_uint4(0, 0, 0, 0);
-                gf[2 * T + 1].u = make_uint4(0, 0, 0, 0);
+                for (int e = 0; e < 4; ++e) t[e] = sigmoid(acc[4 * g + e] + pick(c4, e)) * pick(o4[T][g], e);
+                gf[2 * T + (g >> 1)].w[2 * (g & 1)] = pack2(t[0], t[1]);
+                gf[2 * T + (g >> 1)].w[2 * (g & 1) + 1] = pack2(t[2], t[3]);
             }
         }
-        // output projection: features x tokens again, the lane stores four consecutive channels of its token
-        bf16_t* op = p.out + tok * p.c;
+        // output projection: features x tokens again, the lane holds four consecutive channels of its token
 #pragma unroll
         for (int ct = 0; ct < 4; ++ct) {
             if (ct < n_ct) {
@@ -479,21 +554,28 @@ __global__ __launch_bounds__(256) void k_gca_out(OutArgs p) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) acc[v] = 0.f;
 #pragma unroll
-                for (int kk = 0; kk < 8; ++kk) {
-                    if (kk < 2 * n_gt) {
-                        Frag wf;
-                        wf.u = *reinterpret_cast<const uint4*>(s_wo + (32 * ct + col) * po + kk * 32 + hf * 16);
-                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf.v, gf[kk].v, acc, 0, 0, 0);
-                    }
+                for (int kk = 0; kk < 2 * NGT; ++kk) {
+                    Frag wf;
+                    wf.u = *reinterpret_cast<const uint4*>(s_wo + (32 * ct + col) * po + kk * 32 + hf * 16);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf.v, gf[kk].v, acc, 0, 0, 0);
                 }
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const int c0 = 32 * ct + 8 * g + 4 * hf;
                     const float4 b4 = *reinterpret_cast<const float4*>(s_co + c0);
-                    if (valid)
-                        *reinterpret_cast<uint2*>(op + c0) = make_uint2(pack2(acc[4 * g] + b4.x, acc[4 * g + 1] + b4.y),
-                                                                        pack2(acc[4 * g + 2] + b4.z, acc[4 * g + 3] + b4.w));
+                    *reinterpret_cast<uint2*>(s_tile + col * pt + c0 * 2) = make_uint2(pack2(acc[4 * g] + b4.x, acc[4 * g + 1] + b4.y),
+                                                                                       pack2(acc[4 * g + 2] + b4.z, acc[4 * g + 3] + b4.w));
                 }
+            }
+        }
+        // the tile is 32 c contiguous elements of out (residues i0 .. i0 + 31 of sequence s): 16 bytes per lane
+        {
+            const int i0 = rt * 32, ppr = p.c >> 3;                         // 16-byte pieces per token
+            unsigned char* ob = reinterpret_cast<unsigned char*>(p.out + ((size_t)s * p.R + i0) * p.c);
+            for (int id = lane; id < 32 * ppr; id += 64) {
+                const int row = id / ppr, pc = id - row * ppr;
+                const uint4 v = *reinterpret_cast<const uint4*>(s_tile + row * pt + pc * 16);
+                if (i0 + row < p.R) *reinterpret_cast<uint4*>(ob + (size_t)id * 16) = v;
             }
         }
     }
@@ -584,7 +666,11 @@ ff_status global_run(const ff_global_desc& d, const ff_global_weights& w, const 
         a.S = d.n_seq; a.R = d.n_res; a.Hd = Hd; a.H = d.heads; a.nchunk = nchunk;
         a.qscale = kLog2e / sqrtf((float)d.head_dim);
         Timed t(KK_GCA_SOFTMAX, st);
-#define FF_GCA_SM(HV, DV) hipLaunchKernelGGL((k_gca_softmax<HV, DV>), dim3(d.n_res), dim3(256), 0, st, a)
+#define FF_GCA_SM(HV, DV)                                                                                          \
+    do {                                                                                                           \
+        constexpr int NT = 256;                                                                                    \
+        hipLaunchKernelGGL((k_gca_softmax<HV, DV, NT>), dim3(d.n_res), dim3(NT), 0, st, a);                        \
+    } while (0)
         if (d.head_dim == 8) {
             if (d.heads == 4) FF_GCA_SM(4, 8);
             else if (d.heads == 8) FF_GCA_SM(8, 8);
@@ -601,21 +687,30 @@ ff_status global_run(const ff_global_desc& d, const ff_global_weights& w, const 
         a.m = (const bf16_t*)m; a.out = (bf16_t*)out; a.o = s.o; a.S = d.n_seq; a.R = d.n_res; a.c = d.c; a.Hd = Hd;
         a.eps = d.ln_eps; a.wg = s.wg; a.wo = s.wo; a.Cg = s.Cg; a.Co = s.Co;
         const int tasks = d.n_seq * ((d.n_res + 31) / 32);
-        int blocks = (tasks + 3) / 4;
-        if (blocks > 2048) blocks = 2048;
-        const size_t smem = (size_t)Hd * (kc * 32 + 16) + (size_t)d.c * (Hd * 2 + 16) + (size_t)(Hd + d.c) * 4;
+        int blocks = (tasks + 3) / 4;                                   // at least one wavefront per residue tile
+        if (blocks > 3 * compute_units()) blocks = 3 * compute_units();
+        if (blocks * 4 < (d.n_res + 31) / 32) blocks = ((d.n_res + 31) / 32 + 3) / 4;
+        const size_t smem = (size_t)Hd * (kc * 32 + 16) + (size_t)d.c * (Hd * 2 + 16) + (size_t)(Hd + d.c) * 4 +
+                            (size_t)4 * 32 * (d.c * 2 + 16);       // weights, offsets, one output tile per wavefront
         hipError_t attr = hipSuccess;
         Timed t(KK_GCA_OUT, st);
-#define FF_GCA_OUT(KCV)                                                                                          \
+#define FF_GCA_OUT(KCV, NGTV)                                                                                    \
     do {                                                                                                         \
-        static const hipError_t once = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gca_out<KCV>),      \
-                                                           hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024); \
+        static const hipError_t once = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gca_out<KCV, NGTV>), \
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, 112 * 1024); \
         attr = once;                                                                                             \
-        if (once == hipSuccess) hipLaunchKernelGGL((k_gca_out<KCV>), dim3(blocks), dim3(256), smem, st, a);      \
+        if (once == hipSuccess) hipLaunchKernelGGL((k_gca_out<KCV, NGTV>), dim3(blocks), dim3(256), smem, st, a); \
     } while (0)
-        if (kc == 2) FF_GCA_OUT(2);
-        else if (kc == 4) FF_GCA_OUT(4);
-        else FF_GCA_OUT(8);
+#define FF_GCA_OUT_K(KCV)                                                                                        \
+    do {                                                                                                         \
+        if (Hd == 32) FF_GCA_OUT(KCV, 1);                                                                        \
+        else if (Hd == 64) FF_GCA_OUT(KCV, 2);                                                                   \
+        else FF_GCA_OUT(KCV, 4);                                                                                 \
+    } while (0)
+        if (kc == 2) FF_GCA_OUT_K(2);
+        else if (kc == 4) FF_GCA_OUT_K(4);
+        else FF_GCA_OUT_K(8);
+#undef FF_GCA_OUT_K
 #undef FF_GCA_OUT
         if (attr != hipSuccess) return fail(FF_EHIP, "k_gca_out: dynamic LDS limit: %s", hipGetErrorString(attr));
     }

@@ -1469,7 +1469,7 @@ static int query_compute_units() {
     return 256;
 }
 // (queried once; a function-local static is initialised exactly once, also under concurrent first calls)
-static int compute_units() {
+int compute_units() {
     static const int n = query_compute_units();
     return n;
 }

@@ -581,7 +581,7 @@ ff_status trimul_run(const ff_trimul_desc& d, const ff_trimul_weights& w, const 
         const int split = (blocks < 4 * 256 && n_pairs % 2 == 0) ? 2 : 1;
         a.ppb = n_pairs / split;
         const int per_cu = split;
-        if (blocks > 256 * per_cu) blocks = 256 * per_cu;
+        if (blocks > compute_units() * per_cu) blocks = compute_units() * per_cu;
         const dim3 grid(blocks, split);
         auto smem = [&](int kc) { return (size_t)64 * a.ppb * (kc * 32 + 16) + (size_t)2 * 64 * a.ppb * 4; };
         hipError_t attr = hipSuccess;
