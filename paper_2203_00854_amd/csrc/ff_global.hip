@@ -9,7 +9,7 @@
 // out bound it (HBM).  Four launches:
 //   k_gca_prep     folds the LayerNorm gain into the weights (W' = bf16(W * gamma), C = W beta (+ bias)) and
 //                  writes W_o in the operand order of the last contraction
-//   k_gca_kv       one wavefront per (column, 256 sequences): 32 sequences at a time it normalises the tokens
+//   k_gca_kv       one wavefront per (column, up to 256 sequences): 32 sequences at a time it normalises the tokens
 //                  into bf16 operand fragments (masked ones as zeros) and contracts them with W_q' (tokens x
 //                  features, so that the sum over the tile's sequences - the query average - is a sum over the
 //                  lane's own registers) and with W_k' | W_v' (features x tokens: k, v of a token leave as
@@ -51,7 +51,13 @@ __device__ __forceinline__ float pick(const float4& q, int e) { return e == 0 ? 
 
 static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-constexpr int kChunk = 256;      // sequences per wavefront of k_gca_kv
+// Sequences per wavefront of k_gca_kv (a multiple of 32): 256, or fewer while that leaves fewer than four
+// wavefronts per SIMD (a wavefront walks its sequences one 32-tile after the other)
+static int chunk_for(int n_seq, int n_res) {
+    int chunk = 256;
+    while (chunk > 32 && (int64_t)n_res * ((n_seq + chunk - 1) / chunk) < 4096) chunk >>= 1;
+    return chunk;
+}
 
 // Normalised operand fragments of the lane's token: xn = bf16((x - mean) * rstd) (the LayerNorm gain and
 // offset live in the folded weights), or zeros if !keep.  Two passes over the registers for the statistics.
@@ -147,7 +153,7 @@ __global__ __launch_bounds__(256) void k_gca_prep(PrepArgs a) {
 struct KvArgs {
     const bf16_t* m;         // [S][R][c]
     const float* mask;       // [S][R] or NULL
-    int S, R, c, Hd, d, nchunk;
+    int S, R, c, Hd, d, nchunk, chunk;
     float eps;
     const bf16_t *wq, *wkv;  // folded, pitch 16 KC
     const float* Ckv;
@@ -174,8 +180,8 @@ __global__ __launch_bounds__(256) void k_gca_kv(KvArgs p) {
     const int task = blockIdx.x * 4 + wave;
     if (task >= p.R * p.nchunk) return;          // (no barrier after this point)
     const int i = task / p.nchunk, ck = task - i * p.nchunk;
-    const int s_begin = ck * kChunk;
-    int s_end = s_begin + kChunk;
+    const int s_begin = ck * p.chunk;
+    int s_end = s_begin + p.chunk;
     if (s_end > p.S) s_end = p.S;
     const int n_qt = p.Hd >> 5;                  // 32-feature tiles of the query projection (at most 4)
     float qacc0 = 0.f, qacc1 = 0.f, qacc2 = 0.f, qacc3 = 0.f;
@@ -184,20 +190,36 @@ __global__ __launch_bounds__(256) void k_gca_kv(KvArgs p) {
     const float4 ckv0 = *reinterpret_cast<const float4*>(p.Ckv + 4 * hf), ckv1 = *reinterpret_cast<const float4*>(p.Ckv + 8 + 4 * hf);
     const float4 ckv2 = *reinterpret_cast<const float4*>(p.Ckv + 16 + 4 * hf), ckv3 = *reinterpret_cast<const float4*>(p.Ckv + 24 + 4 * hf);
 
+    // the tokens and mask entries of the next 32 sequences are requested before this tile is worked on
+    Frag xn[KC];
+    float mkn = 1.f;
+    {
+        const int s = s_begin + col;
+        const size_t tok = (size_t)(s < s_end ? s : s_begin) * p.R + i;
+        const bf16_t* mp = p.m + tok * p.c;
+#pragma unroll
+        for (int q = 0; q < KC; ++q) {
+            xn[q].u = make_uint4(0, 0, 0, 0);
+            if (16 * q + 8 * hf < p.c) xn[q].u = *reinterpret_cast<const uint4*>(mp + 16 * q + 8 * hf);
+        }
+        if (p.mask) mkn = p.mask[tok];
+    }
     for (int s0 = s_begin; s0 < s_end; s0 += 32) {
         const int s = s0 + col;
         const bool valid = s < s_end;
-        const size_t tok = (size_t)(valid ? s : s_begin) * p.R + i;
         Frag xa[KC];
+#pragma unroll
+        for (int q = 0; q < KC; ++q) xa[q].u = xn[q].u;
+        const bool keep = valid && mkn != 0.f;
         {
+            const int sn = s + 32;                         // (beyond the chunk: the chunk's first token again, unused)
+            const size_t tok = (size_t)(sn < s_end ? sn : s_begin) * p.R + i;
             const bf16_t* mp = p.m + tok * p.c;
 #pragma unroll
-            for (int q = 0; q < KC; ++q) {
-                xa[q].u = make_uint4(0, 0, 0, 0);
-                if (valid && 16 * q + 8 * hf < p.c) xa[q].u = *reinterpret_cast<const uint4*>(mp + 16 * q + 8 * hf);
-            }
+            for (int q = 0; q < KC; ++q)
+                if (16 * q + 8 * hf < p.c) xn[q].u = *reinterpret_cast<const uint4*>(mp + 16 * q + 8 * hf);
+            if (p.mask) mkn = p.mask[tok];
         }
-        const bool keep = valid && (p.mask ? p.mask[tok] != 0.f : true);
         normalise<KC>(xa, p.c, hf, p.eps, keep);
         cnt += (float)__builtin_popcountll(__ballot(keep && hf == 0));
 
@@ -591,7 +613,7 @@ struct Ws {
 static int kc_for(int K) { return K <= 32 ? 2 : (K <= 64 ? 4 : 8); }
 
 static Ws carve(const ff_global_desc& d, void* base) {
-    const int Hd = d.heads * d.head_dim, Kp = 16 * kc_for(d.c), nchunk = (d.n_seq + kChunk - 1) / kChunk;
+    const int Hd = d.heads * d.head_dim, Kp = 16 * kc_for(d.c), chunk = chunk_for(d.n_seq, d.n_res), nchunk = (d.n_seq + chunk - 1) / chunk;
     char* b = (char*)base;
     size_t off = 0;
     auto take = [&](size_t bytes) {
@@ -629,7 +651,7 @@ size_t global_workspace(const ff_global_desc& d) { return gca::carve(d, nullptr)
 ff_status global_run(const ff_global_desc& d, const ff_global_weights& w, const void* m, const float* mask, void* out,
                      void* ws, hipStream_t st) {
     using namespace gca;
-    const int Hd = d.heads * d.head_dim, kc = kc_for(d.c), nchunk = (d.n_seq + kChunk - 1) / kChunk;
+    const int Hd = d.heads * d.head_dim, kc = kc_for(d.c), chunk = gca::chunk_for(d.n_seq, d.n_res), nchunk = (d.n_seq + chunk - 1) / chunk;
     const Ws s = carve(d, ws);
     {
         PrepArgs a{};
@@ -645,7 +667,7 @@ ff_status global_run(const ff_global_desc& d, const ff_global_weights& w, const 
     {
         KvArgs a{};
         a.m = (const bf16_t*)m; a.mask = mask; a.S = d.n_seq; a.R = d.n_res; a.c = d.c; a.Hd = Hd; a.d = d.head_dim;
-        a.nchunk = nchunk; a.eps = d.ln_eps; a.wq = s.wq; a.wkv = s.wkv; a.Ckv = s.Ckv; a.kv = s.kv; a.qpart = s.qpart;
+        a.nchunk = nchunk; a.chunk = chunk; a.eps = d.ln_eps; a.wq = s.wq; a.wkv = s.wkv; a.Ckv = s.Ckv; a.kv = s.kv; a.qpart = s.qpart;
         a.cntpart = s.cntpart;
         const dim3 grid((d.n_res * nchunk + 3) / 4);
         const size_t smem = (size_t)(Hd + 32) * (kc * 32 + 16);
