@@ -148,20 +148,16 @@ constexpr int kTilePitch = 36;       // floats per row of a staged 32 x 32 bias 
 
 // The bias tile [i0 .. i0+31][j0 .. j0+31] of head h, times log2(e), in the accumulator layout with lane = query:
 // register v = key j0 + 8(v/4) + 4hf + v%4 of query i0 + col.  Read from memory in whole rows (a load instruction
-// covers eight 128-byte rows) into the wavefront's own LDS tile and picked up from there; zeros without a bias
-// or outside the matrix.
-__device__ __forceinline__ void bias_tile_by_query(f32x16& b, const Args& a, int h, int i0, int j0, float* tile, int lane, int col, int hf) {
-    if (!a.bias) {
-        b = zero16();
-        return;
-    }
+// covers eight 128-byte rows; bias_rows_fetch, which can run a tile ahead) and turned through the wavefront's own
+// LDS tile (bias_rows_to_tile); zeros without a bias or outside the matrix.
+__device__ __forceinline__ void bias_rows_fetch(float4 (&rows)[4], const Args& a, int h, int i0, int j0, int lane) {
     const bool vec = (a.L & 3) == 0;
     const int c4 = (lane & 7) * 4;
 #pragma unroll
     for (int n = 0; n < 4; ++n) {
         const int row = 8 * n + (lane >> 3), i = i0 + row, j = j0 + c4;
         float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (i < a.L) {
+        if (a.bias && i < a.L) {
             const float* p = a.bias + ((size_t)h * a.L + i) * a.L + j;
             if (vec && j + 3 < a.L) v = *reinterpret_cast<const float4*>(p);
             else {
@@ -171,11 +167,16 @@ __device__ __forceinline__ void bias_tile_by_query(f32x16& b, const Args& a, int
                 if (j + 3 < a.L) v.w = p[3];
             }
         }
-        *reinterpret_cast<float4*>(tile + row * kTilePitch + c4) = v;
+        rows[n] = v;
     }
+}
+__device__ __forceinline__ void bias_rows_to_tile(f32x16& b, const float4 (&rows)[4], float* tile, int lane, int col, int hf) {
+    const int c4 = (lane & 7) * 4;
+#pragma unroll
+    for (int n = 0; n < 4; ++n) *reinterpret_cast<float4*>(tile + (8 * n + (lane >> 3)) * kTilePitch + c4) = rows[n];
     // (LDS operations of one wavefront are carried out in order and the compiler keeps a load behind a store that
-    // may alias it, so the lanes see each other's rows without any wait; a fence here would also wait for the K and
-    // V loads in flight and serialise the tiles)
+    // may alias it, so the lanes see each other's rows without any wait; a fence here would also wait for the
+    // loads in flight and serialise the tiles)
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
@@ -183,6 +184,15 @@ __device__ __forceinline__ void bias_tile_by_query(f32x16& b, const Args& a, int
         b[4 * g] = v.x * kLog2e; b[4 * g + 1] = v.y * kLog2e; b[4 * g + 2] = v.z * kLog2e; b[4 * g + 3] = v.w * kLog2e;
     }
     __builtin_amdgcn_wave_barrier();
+}
+__device__ __forceinline__ void bias_tile_by_query(f32x16& b, const Args& a, int h, int i0, int j0, float* tile, int lane, int col, int hf) {
+    if (!a.bias) {
+        b = zero16();
+        return;
+    }
+    float4 rows[4];
+    bias_rows_fetch(rows, a, h, i0, j0, lane);
+    bias_rows_to_tile(b, rows, tile, lane, col, hf);
 }
 
 // Bit n of the result: key j0 + n may be attended to in batch row r (inside the sequence and not masked).
@@ -216,54 +226,194 @@ __device__ __forceinline__ void logits_by_key(f32x16& s, const Args& a, int r, i
 }
 
 // ====================================================================================
+// Staging of a 32-position tile of one (row, head) for the four wavefronts of a block, which all contract with it:
+// the row-major tile of two tensors (x, y: [32][D]), their position-contiguous tiles (xT, yT: [D][32]) and two
+// float vectors of the 32 positions.  The block copies 16-byte pieces global -> registers -> LDS, one tile ahead
+// of the tile being worked on (two LDS stages, one barrier per tile); a wavefront reads its operand fragments
+// from LDS just before the matrix instructions that use them.
+constexpr int kStPitch = 80;                          // bytes per staged row: 32 bf16 + 16 bytes, 16-byte aligned
+constexpr int kStRowsX = 0, kStRowsY = 32 * kStPitch, kStColsX = 64 * kStPitch, kStColsY = 96 * kStPitch;
+constexpr int kStVecA = 128 * kStPitch, kStVecB = kStVecA + 128, kStBytes = kStVecB + 128;
+
+struct TileSrc {
+    const bf16_t *x, *y;         // [L][D] of the (row, head), or NULL (tile not needed: zeros)
+    const bf16_t *xT, *yT;       // [D][Lp] of the (row, head), or NULL
+    const float *va, *vb;        // [Lp] of the (row, head), or NULL
+    int L, Lp;
+};
+
+// 16-byte piece `id` of the tile at position n0: where it comes from (NULL: zeros) and where it goes in the stage
+template <int D>
+__device__ __forceinline__ const uint4* stage_piece(const TileSrc& t, int n0, int id, int& dst) {
+    constexpr int PR = D / 8, NR = 32 * PR, NC = 4 * D;
+    if (id < 2 * NR) {
+        const bool second = id >= NR;
+        const int k = second ? id - NR : id, n = k / PR, pc = k - n * PR;
+        dst = (second ? kStRowsY : kStRowsX) + n * kStPitch + pc * 16;
+        const bf16_t* src = second ? t.y : t.x;
+        if (!src || n0 + n >= t.L) return nullptr;
+        return reinterpret_cast<const uint4*>(src + (size_t)(n0 + n) * D + 8 * pc);
+    }
+    id -= 2 * NR;
+    if (id < 2 * NC) {
+        const bool second = id >= NC;
+        const int k = second ? id - NC : id, e = k >> 2, pc = k & 3;
+        dst = (second ? kStColsY : kStColsX) + e * kStPitch + pc * 16;
+        const bf16_t* src = second ? t.yT : t.xT;
+        if (!src) return nullptr;
+        return reinterpret_cast<const uint4*>(src + (size_t)e * t.Lp + n0 + 8 * pc);
+    }
+    id -= 2 * NC;
+    const bool second = id >= 8;
+    const int pc = second ? id - 8 : id;
+    dst = (second ? kStVecB : kStVecA) + pc * 16;
+    const float* src = second ? t.vb : t.va;
+    if (!src) return nullptr;
+    return reinterpret_cast<const uint4*>(src + n0 + 4 * pc);
+}
+template <int D> constexpr int stage_pieces() { return 2 * 32 * (D / 8) + 2 * 4 * D + 16; }
+
+// the (up to three) pieces of thread tid: requested from memory ...
+template <int D>
+__device__ __forceinline__ void stage_fetch(const TileSrc& t, int n0, int tid, uint4& r0, uint4& r1, uint4& r2) {
+    constexpr int N = stage_pieces<D>();
+    int dst;
+    r0 = r1 = r2 = make_uint4(0, 0, 0, 0);
+    if (tid < N) {
+        const uint4* p = stage_piece<D>(t, n0, tid, dst);
+        if (p) r0 = *p;
+    }
+    if (N > 256 && tid + 256 < N) {
+        const uint4* p = stage_piece<D>(t, n0, tid + 256, dst);
+        if (p) r1 = *p;
+    }
+    if (N > 512 && tid + 512 < N) {
+        const uint4* p = stage_piece<D>(t, n0, tid + 512, dst);
+        if (p) r2 = *p;
+    }
+}
+// ... and put into the stage
+template <int D>
+__device__ __forceinline__ void stage_store(const TileSrc& t, int n0, int tid, unsigned char* stage, const uint4& r0, const uint4& r1,
+                                            const uint4& r2) {
+    constexpr int N = stage_pieces<D>();
+    int dst;
+    if (tid < N) {
+        stage_piece<D>(t, n0, tid, dst);
+        *reinterpret_cast<uint4*>(stage + dst) = r0;
+    }
+    if (N > 256 && tid + 256 < N) {
+        stage_piece<D>(t, n0, tid + 256, dst);
+        *reinterpret_cast<uint4*>(stage + dst) = r1;
+    }
+    if (N > 512 && tid + 512 < N) {
+        stage_piece<D>(t, n0, tid + 512, dst);
+        *reinterpret_cast<uint4*>(stage + dst) = r2;
+    }
+}
+// operand fragments out of a stage: rows of the lane's position (as load_rows), channels of the lane (as load_cols)
+template <int D>
+__device__ __forceinline__ void staged_rows(Frag (&f)[(D + 15) / 16], const unsigned char* rows, int col, int hf) {
+#pragma unroll
+    for (int s = 0; s < (D + 15) / 16; ++s) {
+        f[s].u = make_uint4(0, 0, 0, 0);
+        if (16 * s + 8 * hf < D) f[s].u = *reinterpret_cast<const uint4*>(rows + col * kStPitch + (16 * s + 8 * hf) * 2);
+    }
+}
+template <int D>
+__device__ __forceinline__ void staged_cols(Frag (&f)[2], const unsigned char* cols, int col, int hf) {
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        f[s].u = make_uint4(0, 0, 0, 0);
+        if (col < D) {
+            const unsigned char* p = cols + col * kStPitch + (16 * s + 4 * hf) * 2;
+            const uint2 lo = *reinterpret_cast<const uint2*>(p), hi = *reinterpret_cast<const uint2*>(p + 16);
+            f[s].u = make_uint4(lo.x, lo.y, hi.x, hi.y);
+        }
+    }
+}
+
+// ====================================================================================
+// Block = four consecutive query tiles of one (row, head); the key-side tiles (k rows, v position-contiguous) are
+// staged once per block and key tile; the bias rows and the key-mask entries of the next tile are requested
+// while this one is worked on.
 template <int D>
 __global__ __launch_bounds__(256) void k_bwd_stats(Args a) {
     constexpr int KS = (D + 15) / 16;
-    const int lane = threadIdx.x & 63, col = lane & 31, hf = lane >> 5;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int nt = a.Lp >> 5;
-    const int task = blockIdx.x * 4 + wave;
-    if (task >= a.R * a.H * nt) return;
-    const int rh = task / nt, i0 = (task - rh * nt) * 32, r = rh / a.H, h = rh - r * a.H, i = i0 + col;
-    const size_t base = (size_t)rh * a.L * D;
+    __shared__ __attribute__((aligned(16))) unsigned char s_stage[2 * kStBytes];
     __shared__ __attribute__((aligned(16))) float s_tile[4 * 32 * kTilePitch];
+    const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nt = a.Lp >> 5, bpr = (nt + 3) >> 2;
+    const int rh = blockIdx.x / bpr, it = (blockIdx.x - rh * bpr) * 4 + wave;
+    const int r = rh / a.H, h = rh - r * a.H, i0 = it * 32, i = i0 + col;
+    const bool active = it < nt;
+    const size_t base = (size_t)rh * a.L * D;
     float* tile = s_tile + wave * 32 * kTilePitch;
+    TileSrc src;
+    src.x = a.k + base; src.y = nullptr; src.xT = nullptr; src.yT = a.vT + (size_t)rh * D * a.Lp;
+    src.va = nullptr; src.vb = nullptr; src.L = a.L; src.Lp = a.Lp;
     Frag qf[KS];
-    load_rows<D>(qf, a.q + base, i0, a.L, col, hf);
+    load_rows<D>(qf, a.q + base, active ? i0 : 0, a.L, col, hf);
+    float4 brow[4];
+    bias_rows_fetch(brow, a, h, active ? i0 : 0, 0, lane);
+    float mk = 1.f;
+    if (a.mask && col < a.L) mk = a.mask[(size_t)r * a.L + col];
+    {
+        uint4 r0, r1, r2;
+        stage_fetch<D>(src, 0, tid, r0, r1, r2);
+        stage_store<D>(src, 0, tid, s_stage, r0, r1, r2);
+    }
+    __syncthreads();
 
     float m = -INFINITY, l = 0.f;
     f32x16 ctx = zero16();          // ctx^T: lane = query, register v = channel 8(v/4) + 4hf + v%4
-    for (int j0 = 0; j0 < a.L; j0 += 32) {
-        Frag kf[KS], vt[2], pf[2];
-        load_rows<D>(kf, a.k + base, j0, a.L, col, hf);
-        load_cols<D>(vt, a.vT + (size_t)rh * D * a.Lp, j0, a.Lp, col, hf);
-        const uint32_t keys = valid_keys(a, r, j0, col);
-        f32x16 bt;
-        bias_tile_by_query(bt, a, h, i0, j0, tile, lane, col, hf);
-        f32x16 s = zero16();
-#pragma unroll
-        for (int t = 0; t < KS; ++t) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t].v, qf[t].v, s, 0, 0, 0);
-        logits_by_query(s, bt, keys, i < a.L, a.qscale2, hf);
-        float tmax = s[0];
-#pragma unroll
-        for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, s[v]);
-        tmax = fmaxf(tmax, other_half(tmax));
-        const float m_new = fmaxf(m, tmax);
-        // (nothing valid so far: every weight of the tile is zero and nothing is rescaled)
-        const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m - m_new);
-        float lt = 0.f;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            s[v] = m_new == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(s[v] - m_new);
-            lt += s[v];
-            ctx[v] *= alpha;
+    int st = 0;
+    for (int j0 = 0; j0 < a.L; j0 += 32, st ^= 1) {
+        const unsigned char* stage = s_stage + st * kStBytes;
+        const bool more = j0 + 32 < a.L;     // (uniform)
+        uint4 r0, r1, r2;
+        if (more) stage_fetch<D>(src, j0 + 32, tid, r0, r1, r2);
+        const uint32_t keys = (uint32_t)__ballot(j0 + col < a.L && mk != 0.f);
+        f32x16 bt = zero16();
+        if (a.bias) bias_rows_to_tile(bt, brow, tile, lane, col, hf);
+        if (more) {
+            if (a.bias) bias_rows_fetch(brow, a, h, active ? i0 : 0, j0 + 32, lane);
+            mk = 1.f;
+            if (a.mask && j0 + 32 + col < a.L) mk = a.mask[(size_t)r * a.L + j0 + 32 + col];
         }
-        l = l * alpha + lt;
-        m = m_new;
-        pack_rows(pf, s);
+        if (active) {
+            Frag kf[KS], vt[2], pf[2];
+            staged_rows<D>(kf, stage + kStRowsX, col, hf);
+            staged_cols<D>(vt, stage + kStColsY, col, hf);
+            f32x16 s = zero16();
 #pragma unroll
-        for (int t = 0; t < 2; ++t) ctx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt[t].v, pf[t].v, ctx, 0, 0, 0);
+            for (int t = 0; t < KS; ++t) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t].v, qf[t].v, s, 0, 0, 0);
+            logits_by_query(s, bt, keys, i < a.L, a.qscale2, hf);
+            float tmax = s[0];
+#pragma unroll
+            for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, s[v]);
+            tmax = fmaxf(tmax, other_half(tmax));
+            const float m_new = fmaxf(m, tmax);
+            // (nothing valid so far: every weight of the tile is zero and nothing is rescaled)
+            const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m - m_new);
+            float lt = 0.f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                s[v] = m_new == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(s[v] - m_new);
+                lt += s[v];
+                ctx[v] *= alpha;
+            }
+            l = l * alpha + lt;
+            m = m_new;
+            pack_rows(pf, s);
+#pragma unroll
+            for (int t = 0; t < 2; ++t) ctx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt[t].v, pf[t].v, ctx, 0, 0, 0);
+        }
+        if (more) stage_store<D>(src, j0 + 32, tid, s_stage + (st ^ 1) * kStBytes, r0, r1, r2);
+        __syncthreads();
     }
+    if (!active) return;             // (no barrier after this point)
     const float l_tot = l + other_half(l);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
     // a query without unmasked keys: logsumexp = +inf makes every recomputed weight exp2(s - inf) = 0
@@ -312,46 +462,75 @@ __global__ __launch_bounds__(256) void k_bwd_stats(Args a) {
 }
 
 // ====================================================================================
+// Block = four consecutive query tiles of one (row, head); staged per key tile: k rows, v rows, k position-contiguous.
 template <int D>
 __global__ __launch_bounds__(256) void k_bwd_dq(Args a) {
     constexpr int KS = (D + 15) / 16;
-    const int lane = threadIdx.x & 63, col = lane & 31, hf = lane >> 5;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int nt = a.Lp >> 5;
-    const int task = blockIdx.x * 4 + wave;
-    if (task >= a.R * a.H * nt) return;
-    const int rh = task / nt, i0 = (task - rh * nt) * 32, r = rh / a.H, h = rh - r * a.H, i = i0 + col;
-    const size_t base = (size_t)rh * a.L * D;
+    __shared__ __attribute__((aligned(16))) unsigned char s_stage[2 * kStBytes];
     __shared__ __attribute__((aligned(16))) float s_tile[4 * 32 * kTilePitch];
+    const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nt = a.Lp >> 5, bpr = (nt + 3) >> 2;
+    const int rh = blockIdx.x / bpr, it = (blockIdx.x - rh * bpr) * 4 + wave;
+    const int r = rh / a.H, h = rh - r * a.H, i0 = it * 32, i = i0 + col;
+    const bool active = it < nt;
+    const size_t base = (size_t)rh * a.L * D;
     float* tile = s_tile + wave * 32 * kTilePitch;
+    TileSrc src;
+    src.x = a.k + base; src.y = a.v + base; src.xT = a.kT + (size_t)rh * D * a.Lp; src.yT = nullptr;
+    src.va = nullptr; src.vb = nullptr; src.L = a.L; src.Lp = a.Lp;
     Frag qf[KS], dcf[KS];
-    load_rows<D>(qf, a.q + base, i0, a.L, col, hf);
-    load_rows<D>(dcf, a.dctx + base, i0, a.L, col, hf);
-    const float lse = a.lse[(size_t)rh * a.Lp + i], delta = a.delta[(size_t)rh * a.Lp + i];
+    load_rows<D>(qf, a.q + base, active ? i0 : 0, a.L, col, hf);
+    load_rows<D>(dcf, a.dctx + base, active ? i0 : 0, a.L, col, hf);
+    const float lse = a.lse[(size_t)rh * a.Lp + (active ? i : col)], delta = a.delta[(size_t)rh * a.Lp + (active ? i : col)];
+    float4 brow[4];
+    bias_rows_fetch(brow, a, h, active ? i0 : 0, 0, lane);
+    float mk = 1.f;
+    if (a.mask && col < a.L) mk = a.mask[(size_t)r * a.L + col];
+    {
+        uint4 r0, r1, r2;
+        stage_fetch<D>(src, 0, tid, r0, r1, r2);
+        stage_store<D>(src, 0, tid, s_stage, r0, r1, r2);
+    }
+    __syncthreads();
 
     f32x16 dq = zero16();           // dq^T: lane = query, register = channel
-    for (int j0 = 0; j0 < a.L; j0 += 32) {
-        Frag kf[KS], vf[KS], kt[2], dsf[2];
-        load_rows<D>(kf, a.k + base, j0, a.L, col, hf);
-        load_rows<D>(vf, a.v + base, j0, a.L, col, hf);
-        load_cols<D>(kt, a.kT + (size_t)rh * D * a.Lp, j0, a.Lp, col, hf);
-        const uint32_t keys = valid_keys(a, r, j0, col);
-        f32x16 bt;
-        bias_tile_by_query(bt, a, h, i0, j0, tile, lane, col, hf);
-        f32x16 s = zero16(), dp = zero16();
-#pragma unroll
-        for (int t = 0; t < KS; ++t) {
-            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t].v, qf[t].v, s, 0, 0, 0);
-            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t].v, dcf[t].v, dp, 0, 0, 0);
+    int st = 0;
+    for (int j0 = 0; j0 < a.L; j0 += 32, st ^= 1) {
+        const unsigned char* stage = s_stage + st * kStBytes;
+        const bool more = j0 + 32 < a.L;     // (uniform)
+        uint4 r0, r1, r2;
+        if (more) stage_fetch<D>(src, j0 + 32, tid, r0, r1, r2);
+        const uint32_t keys = (uint32_t)__ballot(j0 + col < a.L && mk != 0.f);
+        f32x16 bt = zero16();
+        if (a.bias) bias_rows_to_tile(bt, brow, tile, lane, col, hf);
+        if (more) {
+            if (a.bias) bias_rows_fetch(brow, a, h, active ? i0 : 0, j0 + 32, lane);
+            mk = 1.f;
+            if (a.mask && j0 + 32 + col < a.L) mk = a.mask[(size_t)r * a.L + j0 + 32 + col];
         }
-        logits_by_query(s, bt, keys, i < a.L, a.qscale2, hf);
+        if (active) {
+            Frag kf[KS], vf[KS], kt[2], dsf[2];
+            staged_rows<D>(kf, stage + kStRowsX, col, hf);
+            staged_rows<D>(vf, stage + kStRowsY, col, hf);
+            f32x16 s = zero16(), dp = zero16();
 #pragma unroll
-        for (int v = 0; v < 16; ++v) s[v] = __builtin_amdgcn_exp2f(s[v] - lse) * (dp[v] - delta);
-        pack_rows(dsf, s);
+            for (int t = 0; t < KS; ++t) {
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t].v, qf[t].v, s, 0, 0, 0);
+                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t].v, dcf[t].v, dp, 0, 0, 0);
+            }
+            staged_cols<D>(kt, stage + kStColsX, col, hf);
+            logits_by_query(s, bt, keys, i < a.L, a.qscale2, hf);
 #pragma unroll
-        for (int t = 0; t < 2; ++t) dq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt[t].v, dsf[t].v, dq, 0, 0, 0);
+            for (int v = 0; v < 16; ++v) s[v] = __builtin_amdgcn_exp2f(s[v] - lse) * (dp[v] - delta);
+            pack_rows(dsf, s);
+#pragma unroll
+            for (int t = 0; t < 2; ++t) dq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt[t].v, dsf[t].v, dq, 0, 0, 0);
+        }
+        if (more) stage_store<D>(src, j0 + 32, tid, s_stage + (st ^ 1) * kStBytes, r0, r1, r2);
+        __syncthreads();
     }
-    if (i < a.L) {
+    if (active && i < a.L) {
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
             const int e0 = 8 * gq + 4 * hf;
@@ -364,57 +543,100 @@ __global__ __launch_bounds__(256) void k_bwd_dq(Args a) {
 }
 
 // ====================================================================================
+// Block = four consecutive key tiles of one (row, head); the query-side tiles (q, dctx, their position-contiguous
+// copies, logsumexp, delta) are staged once per block and query tile.
 template <int D>
 __global__ __launch_bounds__(256) void k_bwd_dkv(Args a) {
     constexpr int KS = (D + 15) / 16;
-    const int lane = threadIdx.x & 63, col = lane & 31, hf = lane >> 5;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int nt = a.Lp >> 5;
-    const int task = blockIdx.x * 4 + wave;
-    if (task >= a.R * a.H * nt) return;
-    const int rh = task / nt, j0 = (task - rh * nt) * 32, r = rh / a.H, h = rh - r * a.H, j = j0 + col;
+    __shared__ __attribute__((aligned(16))) unsigned char s_stage[2 * kStBytes];
+    const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nt = a.Lp >> 5, bpr = (nt + 3) >> 2;               // key tiles, blocks per (row, head)
+    const int rh = blockIdx.x / bpr, jt = (blockIdx.x - rh * bpr) * 4 + wave;
+    const int r = rh / a.H, h = rh - r * a.H, j0 = jt * 32, j = j0 + col;
+    const bool active = jt < nt;                                 // (a block's last wavefronts may have no key tile)
     const size_t base = (size_t)rh * a.L * D;
-    Frag kf[KS], vf[KS];
-    load_rows<D>(kf, a.k + base, j0, a.L, col, hf);
-    load_rows<D>(vf, a.v + base, j0, a.L, col, hf);
+    TileSrc src;
+    src.x = a.q + base; src.y = a.dctx + base;
+    src.xT = a.qT + (size_t)rh * D * a.Lp; src.yT = a.dctxT + (size_t)rh * D * a.Lp;
+    src.va = a.lse + (size_t)rh * a.Lp; src.vb = a.delta + (size_t)rh * a.Lp;
+    src.L = a.L; src.Lp = a.Lp;
 
-    f32x16 dk = zero16(), dv = zero16();     // dk^T, dv^T: lane = key, register = channel
-    for (int i0 = 0; i0 < a.L; i0 += 32) {
-        Frag qf[KS], dcf[KS], qt[2], dct[2], pf[2], dsf[2];
-        load_rows<D>(qf, a.q + base, i0, a.L, col, hf);
-        load_rows<D>(dcf, a.dctx + base, i0, a.L, col, hf);
-        load_cols<D>(qt, a.qT + (size_t)rh * D * a.Lp, i0, a.Lp, col, hf);
-        load_cols<D>(dct, a.dctxT + (size_t)rh * D * a.Lp, i0, a.Lp, col, hf);
-        f32x16 s = zero16(), dp = zero16();      // lane = key, register v = query i0 + 8(v/4) + 4hf + v%4
+    Frag kf[KS], vf[KS];
+    load_rows<D>(kf, a.k + base, active ? j0 : 0, a.L, col, hf);
+    load_rows<D>(vf, a.v + base, active ? j0 : 0, a.L, col, hf);
+    const bool key_ok = active && j < a.L && (!a.mask || a.mask[(size_t)r * a.L + j] != 0.f);
+    // the lane's bias column, times log2(e), for the queries of the coming tile: register v = query i0 + 8(v/4) + 4hf + v%4
+    const float* bcol = a.bias ? a.bias + (size_t)h * a.L * a.L + (j < a.L ? j : 0) : nullptr;
+    f32x16 bn = zero16();
+    if (bcol) {
 #pragma unroll
-        for (int t = 0; t < KS; ++t) {
-            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[t].v, kf[t].v, s, 0, 0, 0);
-            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dcf[t].v, vf[t].v, dp, 0, 0, 0);
-        }
-        logits_by_key(s, a, r, h, i0, j, hf);
-        const float* lp = a.lse + (size_t)rh * a.Lp + i0 + 4 * hf;
-        const float* dp_ = a.delta + (size_t)rh * a.Lp + i0 + 4 * hf;
-#pragma unroll
-        for (int gq = 0; gq < 4; ++gq) {
-            const float4 l4 = *reinterpret_cast<const float4*>(lp + 8 * gq);
-            const float4 d4 = *reinterpret_cast<const float4*>(dp_ + 8 * gq);
-            const float ls[4] = {l4.x, l4.y, l4.z, l4.w}, ds_[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float p = __builtin_amdgcn_exp2f(s[4 * gq + e] - ls[e]);
-                s[4 * gq + e] = p;
-                dp[4 * gq + e] = p * (dp[4 * gq + e] - ds_[e]);
-            }
-        }
-        pack_rows(pf, s);
-        pack_rows(dsf, dp);
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            dv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dct[t].v, pf[t].v, dv, 0, 0, 0);
-            dk = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt[t].v, dsf[t].v, dk, 0, 0, 0);
+        for (int v = 0; v < 16; ++v) {
+            const int i = 8 * (v >> 2) + 4 * hf + (v & 3);
+            if (i < a.L) bn[v] = bcol[(size_t)i * a.L];
         }
     }
-    if (j < a.L) {
+    {
+        uint4 r0, r1, r2;
+        stage_fetch<D>(src, 0, tid, r0, r1, r2);
+        stage_store<D>(src, 0, tid, s_stage, r0, r1, r2);
+    }
+    __syncthreads();
+
+    f32x16 dk = zero16(), dv = zero16();     // dk^T, dv^T: lane = key, register = channel
+    int st = 0;
+    for (int i0 = 0; i0 < a.L; i0 += 32, st ^= 1) {
+        const unsigned char* stage = s_stage + st * kStBytes;
+        const bool more = i0 + 32 < a.L;     // (uniform)
+        uint4 r0, r1, r2;
+        if (more) stage_fetch<D>(src, i0 + 32, tid, r0, r1, r2);
+        f32x16 bt = bn;
+        if (bcol && more) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int i = i0 + 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
+                bn[v] = 0.f;
+                if (i < a.L) bn[v] = bcol[(size_t)i * a.L];
+            }
+        }
+        if (active) {
+            Frag qf[KS], dcf[KS], qt[2], dct[2], pf[2], dsf[2];
+            staged_rows<D>(qf, stage + kStRowsX, col, hf);
+            staged_rows<D>(dcf, stage + kStRowsY, col, hf);
+            f32x16 s = zero16(), dp = zero16();      // lane = key, register v = query i0 + 8(v/4) + 4hf + v%4
+#pragma unroll
+            for (int t = 0; t < KS; ++t) {
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[t].v, kf[t].v, s, 0, 0, 0);
+                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dcf[t].v, vf[t].v, dp, 0, 0, 0);
+            }
+            staged_cols<D>(qt, stage + kStColsX, col, hf);
+            staged_cols<D>(dct, stage + kStColsY, col, hf);
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const float4 l4 = *reinterpret_cast<const float4*>(stage + kStVecA + (8 * gq + 4 * hf) * 4);
+                const float4 d4 = *reinterpret_cast<const float4*>(stage + kStVecB + (8 * gq + 4 * hf) * 4);
+                const float ls[4] = {l4.x, l4.y, l4.z, l4.w}, ds_[4] = {d4.x, d4.y, d4.z, d4.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int v = 4 * gq + e;
+                    // (a query beyond L has logsumexp +inf: weight 0; a masked key or one beyond L: weight 0)
+                    const float p = key_ok ? __builtin_amdgcn_exp2f(s[v] * a.qscale2 + bt[v] * kLog2e - ls[e]) : 0.f;
+                    s[v] = p;
+                    dp[v] = p * (dp[v] - ds_[e]);
+                }
+            }
+            pack_rows(pf, s);
+            pack_rows(dsf, dp);
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                dv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dct[t].v, pf[t].v, dv, 0, 0, 0);
+                dk = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt[t].v, dsf[t].v, dk, 0, 0, 0);
+            }
+        }
+        if (more) stage_store<D>(src, i0 + 32, tid, s_stage + (st ^ 1) * kStBytes, r0, r1, r2);
+        __syncthreads();
+    }
+    if (active && j < a.L) {
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
             const int e0 = 8 * gq + 4 * hf;
@@ -446,16 +668,38 @@ __global__ __launch_bounds__(256) void k_bwd_dbias(Args a) {
     f32x16 bt;
     bias_tile_by_query(bt, a, h, i0, j0, s_tile + wave * 32 * kTilePitch, lane, col, hf);
     f32x16 acc = zero16();          // lane = query i, register v = key j0 + 8(v/4) + 4hf + v%4
-    for (int r = r_begin; r < r_end; ++r) {
-        const int rh = r * a.H + h;
+    // the operands of the next batch row are requested before this one is worked on (the last round asks for its
+    // own again: a load under a condition would make every wait in the loop a wait for all loads)
+    Frag qn[KS], dcn[KS], kn[KS], vn[KS];
+    float lse_n, delta_n, mk_n = 1.f;
+    {
+        const int rh = r_begin * a.H + h;
         const size_t base = (size_t)rh * a.L * D;
+        load_rows<D>(qn, a.q + base, i0, a.L, col, hf);
+        load_rows<D>(dcn, a.dctx + base, i0, a.L, col, hf);
+        load_rows<D>(kn, a.k + base, j0, a.L, col, hf);
+        load_rows<D>(vn, a.v + base, j0, a.L, col, hf);
+        lse_n = a.lse[(size_t)rh * a.Lp + i];
+        delta_n = a.delta[(size_t)rh * a.Lp + i];
+        if (a.mask && j0 + col < a.L) mk_n = a.mask[(size_t)r_begin * a.L + j0 + col];
+    }
+    for (int r = r_begin; r < r_end; ++r) {
         Frag qf[KS], dcf[KS], kf[KS], vf[KS];
-        load_rows<D>(qf, a.q + base, i0, a.L, col, hf);
-        load_rows<D>(dcf, a.dctx + base, i0, a.L, col, hf);
-        load_rows<D>(kf, a.k + base, j0, a.L, col, hf);
-        load_rows<D>(vf, a.v + base, j0, a.L, col, hf);
-        const float lse = a.lse[(size_t)rh * a.Lp + i], delta = a.delta[(size_t)rh * a.Lp + i];
-        const uint32_t keys = valid_keys(a, r, j0, col);
+#pragma unroll
+        for (int t = 0; t < KS; ++t) { qf[t].u = qn[t].u; dcf[t].u = dcn[t].u; kf[t].u = kn[t].u; vf[t].u = vn[t].u; }
+        const float lse = lse_n, delta = delta_n;
+        const uint32_t keys = (uint32_t)__ballot(j0 + col < a.L && mk_n != 0.f);
+        {
+            const int rn = r + 1 < r_end ? r + 1 : r, rh = rn * a.H + h;
+            const size_t base = (size_t)rh * a.L * D;
+            load_rows<D>(qn, a.q + base, i0, a.L, col, hf);
+            load_rows<D>(dcn, a.dctx + base, i0, a.L, col, hf);
+            load_rows<D>(kn, a.k + base, j0, a.L, col, hf);
+            load_rows<D>(vn, a.v + base, j0, a.L, col, hf);
+            lse_n = a.lse[(size_t)rh * a.Lp + i];
+            delta_n = a.delta[(size_t)rh * a.Lp + i];
+            if (a.mask && j0 + col < a.L) mk_n = a.mask[(size_t)rn * a.L + j0 + col];
+        }
         f32x16 s = zero16(), dp = zero16();
 #pragma unroll
         for (int t = 0; t < KS; ++t) {
@@ -544,9 +788,10 @@ ff_status core_backward_run(const ff_core_desc& d, const void* q, const void* k,
     } while (0)
     const dim3 gt(g1.x, 3);
     FF_BWD(k_bwd_transpose, gt, KK_BWD_STATS);
-    FF_BWD(k_bwd_stats, g1, KK_BWD_STATS);
-    FF_BWD(k_bwd_dq, g1, KK_BWD_DQ);
-    FF_BWD(k_bwd_dkv, g1, KK_BWD_DKV);
+    const dim3 g4((unsigned)(rh * ((nt + 3) / 4)));          // blocks of four tiles of one (row, head)
+    FF_BWD(k_bwd_stats, g4, KK_BWD_STATS);
+    FF_BWD(k_bwd_dq, g4, KK_BWD_DQ);
+    FF_BWD(k_bwd_dkv, g4, KK_BWD_DKV);
     if (bias) {
         FF_BWD(k_bwd_dbias, g2, KK_BWD_DBIAS);
         if (a.row_chunks > 1) {
