@@ -58,6 +58,9 @@ struct Args {
     const bf16_t *q, *k, *v, *g, *dout;      // [R][H][L][D]
     const float* bias;                       // [H][L][L] or NULL
     const float* mask;                       // [R][L] or NULL
+    const float* mrow;                       // mask entry of (r, j): mrow[r * mstride + j] (without a mask: a row of ones, stride 0)
+    int mstride;
+    float* ones;                             // workspace [Lp]: that row of ones (written by k_bwd_transpose)
     bf16_t *dq, *dk, *dv, *dg;               // [R][H][L][D]
     float* dbias;                            // [H][L][L] or NULL
     float* dbias_part;                       // workspace [row_chunks][H][L][L] (partial sums over the rows of a chunk)
@@ -68,18 +71,19 @@ struct Args {
     int R, H, L, Lp;
     float qscale2;                           // log2(e) / sqrt(D)
     float scale;                             // 1 / sqrt(D)
+    float sqrt_d;                            // sqrt(D)
 };
 
 // Row fragments of the 32 positions n0 .. n0+31 of x [L][D] (x already offset to its (row, head)): lane (n, hf)
 // holds channels 16 s + 8 hf .. + 7 of position n0 + col; zeros beyond L or D.
-template <int D>
+template <int D, bool FULL = false>       // FULL: the caller knows n0 + 31 < L
 __device__ __forceinline__ void load_rows(Frag (&f)[(D + 15) / 16], const bf16_t* x, int n0, int L, int col, int hf) {
     constexpr int KS = (D + 15) / 16;
     const int n = n0 + col;
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
         f[s].u = make_uint4(0, 0, 0, 0);
-        if (n < L && 16 * s + 8 * hf < D) f[s].u = *reinterpret_cast<const uint4*>(x + (size_t)n * D + 16 * s + 8 * hf);
+        if ((FULL || n < L) && 16 * s + 8 * hf < D) f[s].u = *reinterpret_cast<const uint4*>(x + (size_t)n * D + 16 * s + 8 * hf);
     }
 }
 
@@ -107,6 +111,8 @@ __global__ __launch_bounds__(256) void k_bwd_transpose(Args a) {
     const int lane = threadIdx.x & 63, col = lane & 31, hf = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nt = a.Lp >> 5;
+    if (blockIdx.x == 0 && blockIdx.y == 0)
+        for (int n = threadIdx.x; n < a.Lp; n += 256) a.ones[n] = 1.f;
     const int task = blockIdx.x * 4 + wave;
     if (task >= a.R * a.H * nt) return;
     const int rh = task / nt, n0 = (task - rh * nt) * 32, n = n0 + col;
@@ -146,34 +152,48 @@ __device__ __forceinline__ f32x16 zero16() {
 
 constexpr int kTilePitch = 36;       // floats per row of a staged 32 x 32 bias tile (16-byte aligned rows, conflict-free reads)
 
-// The bias tile [i0 .. i0+31][j0 .. j0+31] of head h, times log2(e), in the accumulator layout with lane = query:
-// register v = key j0 + 8(v/4) + 4hf + v%4 of query i0 + col.  Read from memory in whole rows (a load instruction
-// covers eight 128-byte rows; bias_rows_fetch, which can run a tile ahead) and turned through the wavefront's own
-// LDS tile (bias_rows_to_tile); zeros without a bias or outside the matrix.
+// The logits enter the matrix core's accumulator already holding what is added to q.k: S = (q.k + B) * scale with
+// B[i][j] = bias[h][i][j] * sqrt(d) for a key that may be attended to and -inf for one that is masked or beyond L
+// (exp2 of the base-2 logit then gives weight 0 without any select).  The tile B [i0 .. i0+31][j0 .. j0+31] in the
+// accumulator layout with lane = query: register v = key j0 + 8(v/4) + 4hf + v%4 of query i0 + col.  The bias is
+// read from memory in whole rows (a load instruction covers eight 128-byte rows; bias_rows_fetch, which can run
+// tiles ahead), scaled, given the keys' -inf and turned through the wavefront's own LDS tile (bias_rows_to_tile).
+// FULL: L is a multiple of 32, nothing is out of range.
+template <bool FULL>
 __device__ __forceinline__ void bias_rows_fetch(float4 (&rows)[4], const Args& a, int h, int i0, int j0, int lane) {
-    const bool vec = (a.L & 3) == 0;
     const int c4 = (lane & 7) * 4;
 #pragma unroll
     for (int n = 0; n < 4; ++n) {
         const int row = 8 * n + (lane >> 3), i = i0 + row, j = j0 + c4;
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (a.bias && i < a.L) {
-            const float* p = a.bias + ((size_t)h * a.L + i) * a.L + j;
-            if (vec && j + 3 < a.L) v = *reinterpret_cast<const float4*>(p);
-            else {
-                if (j < a.L) v.x = p[0];
-                if (j + 1 < a.L) v.y = p[1];
-                if (j + 2 < a.L) v.z = p[2];
-                if (j + 3 < a.L) v.w = p[3];
+        const float* p = a.bias + ((size_t)h * a.L + i) * a.L + j;
+        if (FULL) {
+            rows[n] = *reinterpret_cast<const float4*>(p);
+        } else {
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (i < a.L) {
+                if ((a.L & 3) == 0 && j + 3 < a.L) v = *reinterpret_cast<const float4*>(p);
+                else {
+                    if (j < a.L) v.x = p[0];
+                    if (j + 1 < a.L) v.y = p[1];
+                    if (j + 2 < a.L) v.z = p[2];
+                    if (j + 3 < a.L) v.w = p[3];
+                }
             }
+            rows[n] = v;
         }
-        rows[n] = v;
     }
 }
-__device__ __forceinline__ void bias_rows_to_tile(f32x16& b, const float4 (&rows)[4], float* tile, int lane, int col, int hf) {
+// keys: bit n set if key j0 + n may be attended to
+__device__ __forceinline__ void bias_rows_to_tile(f32x16& b, const float4 (&rows)[4], uint32_t keys, float sqrt_d, float* tile, int lane,
+                                                  int col, int hf) {
     const int c4 = (lane & 7) * 4;
+    const uint32_t kb = keys >> c4;
+    const float m0 = (kb & 1u) ? 0.f : -INFINITY, m1 = (kb & 2u) ? 0.f : -INFINITY;
+    const float m2 = (kb & 4u) ? 0.f : -INFINITY, m3 = (kb & 8u) ? 0.f : -INFINITY;
 #pragma unroll
-    for (int n = 0; n < 4; ++n) *reinterpret_cast<float4*>(tile + (8 * n + (lane >> 3)) * kTilePitch + c4) = rows[n];
+    for (int n = 0; n < 4; ++n)
+        *reinterpret_cast<float4*>(tile + (8 * n + (lane >> 3)) * kTilePitch + c4) =
+            make_float4(rows[n].x * sqrt_d + m0, rows[n].y * sqrt_d + m1, rows[n].z * sqrt_d + m2, rows[n].w * sqrt_d + m3);
     // (LDS operations of one wavefront are carried out in order and the compiler keeps a load behind a store that
     // may alias it, so the lanes see each other's rows without any wait; a fence here would also wait for the
     // loads in flight and serialise the tiles)
@@ -181,48 +201,28 @@ __device__ __forceinline__ void bias_rows_to_tile(f32x16& b, const float4 (&rows
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
         const float4 v = *reinterpret_cast<const float4*>(tile + col * kTilePitch + 8 * g + 4 * hf);
-        b[4 * g] = v.x * kLog2e; b[4 * g + 1] = v.y * kLog2e; b[4 * g + 2] = v.z * kLog2e; b[4 * g + 3] = v.w * kLog2e;
+        b[4 * g] = v.x; b[4 * g + 1] = v.y; b[4 * g + 2] = v.z; b[4 * g + 3] = v.w;
     }
     __builtin_amdgcn_wave_barrier();
 }
-__device__ __forceinline__ void bias_tile_by_query(f32x16& b, const Args& a, int h, int i0, int j0, float* tile, int lane, int col, int hf) {
-    if (!a.bias) {
-        b = zero16();
-        return;
-    }
-    float4 rows[4];
-    bias_rows_fetch(rows, a, h, i0, j0, lane);
-    bias_rows_to_tile(b, rows, tile, lane, col, hf);
-}
-
-// Bit n of the result: key j0 + n may be attended to in batch row r (inside the sequence and not masked).
-__device__ __forceinline__ uint32_t valid_keys(const Args& a, int r, int j0, int col) {
-    const int j = j0 + col;
-    const bool ok = j < a.L && (!a.mask || a.mask[(size_t)r * a.L + j] != 0.f);
-    return (uint32_t)__ballot(ok);          // (lanes 32 .. 63 repeat lanes 0 .. 31: the low word is enough)
-}
-
-// S^T tile in base-2 logits for the wavefront's queries (lane = query i, register v = key j0 + 8(v/4) + 4hf + v%4):
-// acc * qscale2 + bias tile, -inf for keys that are masked or beyond L (and for queries beyond L).
-__device__ __forceinline__ void logits_by_query(f32x16& s, const f32x16& b, uint32_t keys, bool query_ok, float qscale2, int hf) {
+// the same tile with lane = key: register v = query i0 + 8(v/4) + 4hf + v%4 of key j0 + col; kterm is the lane's own
+// 0 / -inf
+__device__ __forceinline__ void bias_rows_to_tile_by_key(f32x16& b, const float4 (&rows)[4], float kterm, float sqrt_d, float* tile,
+                                                         int lane, int col, int hf) {
+    const int c4 = (lane & 7) * 4;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const int n = 8 * (v >> 2) + (v & 3);
-        const bool ok = query_ok && ((keys >> (n + 4 * hf)) & 1u);
-        s[v] = ok ? s[v] * qscale2 + b[v] : -INFINITY;
-    }
-}
-
-// the same with lane = key j and register v = query i0 + 8(v/4) + 4hf + v%4
-__device__ __forceinline__ void logits_by_key(f32x16& s, const Args& a, int r, int h, int i0, int j, int hf) {
-    const bool key_ok = j < a.L && (!a.mask || a.mask[(size_t)r * a.L + j] != 0.f);
+    for (int n = 0; n < 4; ++n)
+        *reinterpret_cast<float4*>(tile + (8 * n + (lane >> 3)) * kTilePitch + c4) =
+            make_float4(rows[n].x * sqrt_d, rows[n].y * sqrt_d, rows[n].z * sqrt_d, rows[n].w * sqrt_d);
+    __builtin_amdgcn_wave_barrier();
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const int i = i0 + 8 * (v >> 2) + 4 * hf + (v & 3);
-        const bool ok = key_ok && i < a.L;
-        const float b = (a.bias && ok) ? a.bias[((size_t)h * a.L + i) * a.L + j] * kLog2e : 0.f;
-        s[v] = ok ? s[v] * a.qscale2 + b : -INFINITY;
-    }
+    for (int v = 0; v < 16; ++v) b[v] = tile[(8 * (v >> 2) + 4 * hf + (v & 3)) * kTilePitch + col] + kterm;
+    __builtin_amdgcn_wave_barrier();
+}
+// the same without a bias: only the keys' 0 / -inf, straight from the mask bits
+__device__ __forceinline__ void mask_tile(f32x16& b, uint32_t keys, int hf) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) b[v] = ((keys >> (8 * (v >> 2) + 4 * hf + (v & 3))) & 1u) ? 0.f : -INFINITY;
 }
 
 // ====================================================================================
@@ -243,7 +243,7 @@ struct TileSrc {
 };
 
 // 16-byte piece `id` of the tile at position n0: where it comes from (NULL: zeros) and where it goes in the stage
-template <int D>
+template <int D, bool FULL>
 __device__ __forceinline__ const uint4* stage_piece(const TileSrc& t, int n0, int id, int& dst) {
     constexpr int PR = D / 8, NR = 32 * PR, NC = 4 * D;
     if (id < 2 * NR) {
@@ -251,7 +251,7 @@ __device__ __forceinline__ const uint4* stage_piece(const TileSrc& t, int n0, in
         const int k = second ? id - NR : id, n = k / PR, pc = k - n * PR;
         dst = (second ? kStRowsY : kStRowsX) + n * kStPitch + pc * 16;
         const bf16_t* src = second ? t.y : t.x;
-        if (!src || n0 + n >= t.L) return nullptr;
+        if (!src || (!FULL && n0 + n >= t.L)) return nullptr;
         return reinterpret_cast<const uint4*>(src + (size_t)(n0 + n) * D + 8 * pc);
     }
     id -= 2 * NR;
@@ -274,40 +274,40 @@ __device__ __forceinline__ const uint4* stage_piece(const TileSrc& t, int n0, in
 template <int D> constexpr int stage_pieces() { return 2 * 32 * (D / 8) + 2 * 4 * D + 16; }
 
 // the (up to three) pieces of thread tid: requested from memory ...
-template <int D>
+template <int D, bool FULL>
 __device__ __forceinline__ void stage_fetch(const TileSrc& t, int n0, int tid, uint4& r0, uint4& r1, uint4& r2) {
     constexpr int N = stage_pieces<D>();
     int dst;
     r0 = r1 = r2 = make_uint4(0, 0, 0, 0);
     if (tid < N) {
-        const uint4* p = stage_piece<D>(t, n0, tid, dst);
+        const uint4* p = stage_piece<D, FULL>(t, n0, tid, dst);
         if (p) r0 = *p;
     }
     if (N > 256 && tid + 256 < N) {
-        const uint4* p = stage_piece<D>(t, n0, tid + 256, dst);
+        const uint4* p = stage_piece<D, FULL>(t, n0, tid + 256, dst);
         if (p) r1 = *p;
     }
     if (N > 512 && tid + 512 < N) {
-        const uint4* p = stage_piece<D>(t, n0, tid + 512, dst);
+        const uint4* p = stage_piece<D, FULL>(t, n0, tid + 512, dst);
         if (p) r2 = *p;
     }
 }
 // ... and put into the stage
-template <int D>
+template <int D, bool FULL>
 __device__ __forceinline__ void stage_store(const TileSrc& t, int n0, int tid, unsigned char* stage, const uint4& r0, const uint4& r1,
                                             const uint4& r2) {
     constexpr int N = stage_pieces<D>();
     int dst;
     if (tid < N) {
-        stage_piece<D>(t, n0, tid, dst);
+        stage_piece<D, FULL>(t, n0, tid, dst);
         *reinterpret_cast<uint4*>(stage + dst) = r0;
     }
     if (N > 256 && tid + 256 < N) {
-        stage_piece<D>(t, n0, tid + 256, dst);
+        stage_piece<D, FULL>(t, n0, tid + 256, dst);
         *reinterpret_cast<uint4*>(stage + dst) = r1;
     }
     if (N > 512 && tid + 512 < N) {
-        stage_piece<D>(t, n0, tid + 512, dst);
+        stage_piece<D, FULL>(t, n0, tid + 512, dst);
         *reinterpret_cast<uint4*>(stage + dst) = r2;
     }
 }
@@ -333,11 +333,59 @@ __device__ __forceinline__ void staged_cols(Frag (&f)[2], const unsigned char* c
     }
 }
 
+// Tile loop of the two kernels whose wavefronts keep a query tile and walk over the key tiles.  Memory is two
+// tiles ahead of the arithmetic: while tile t is worked on, tile t + 1 waits in registers (it was requested during
+// tile t - 1 and goes into the free LDS stage at the end of tile t) and tile t + 2 is being requested; one tile
+// ahead the block stalled on every tile for most of a memory latency.  Two named register sets (even tiles, odd
+// tiles), hence a loop body written for a literal parity P and used twice: tile tt + P, stage P, sets [P].
+//   rs[P]: staged pieces of the thread; brow[P]: the lane's bias rows; mk[P]: the lane's key-mask entry.
+// tiles between a request to memory and its use (1 or 2)
+constexpr int kAhead = 1;
+#define FF_BWD_Q_PROLOGUE                                                                                        \
+    uint4 rs[2][3];                                                                                              \
+    float4 brow[2][4];                                                                                           \
+    float mk[2] = {1.f, 1.f};                                                                                    \
+    const int i0a = active ? i0 : 0;                                                                             \
+    const float* mrow = a.mrow + (size_t)r * a.mstride;                                                          \
+    {                                                                                                            \
+        const int n1 = 32 < a.L ? 32 : 0;         /* (a single tile: fetched twice, the second copy unused) */   \
+        stage_fetch<D, FULL>(src, 0, tid, rs[0][0], rs[0][1], rs[0][2]);                                         \
+        if (kAhead == 2) stage_fetch<D, FULL>(src, n1, tid, rs[1][0], rs[1][1], rs[1][2]);                       \
+        if (BIAS) {                                                                                              \
+            bias_rows_fetch<FULL>(brow[0], a, h, i0a, 0, lane);                                                  \
+            if (kAhead == 2) bias_rows_fetch<FULL>(brow[1], a, h, i0a, n1, lane);                                \
+        }                                                                                                        \
+        if (FULL || col < a.L) mk[0] = mrow[col];                                                                \
+        if (kAhead == 2 && (FULL || n1 + col < a.L)) mk[1] = mrow[n1 + col];                                     \
+    }                                                                                                            \
+    stage_store<D, FULL>(src, 0, tid, s_stage, rs[0][0], rs[0][1], rs[0][2]);                                    \
+    __syncthreads();
+// (bt: what the accumulator of the logits starts from, see bias_rows_fetch.  Every load of the loop is issued on
+// every path - the last two tiles ask for themselves again - because a load under a condition makes the compiler
+// wait, at every later wait, also for the loads just issued.)
+#define FF_BWD_Q_HEAD(P)                                                                                         \
+    const int j0 = 32 * (tt + (P));                                                                              \
+    const unsigned char* stage = s_stage + (P) * kStBytes;                                                       \
+    constexpr int PF = kAhead == 2 ? (P) : 1 - (P);       /* the register set that receives what is requested now */ \
+    const int jn = j0 + 32 * kAhead < a.L ? j0 + 32 * kAhead : j0;                                               \
+    stage_fetch<D, FULL>(src, jn, tid, rs[PF][0], rs[PF][1], rs[PF][2]);                                         \
+    const uint32_t keys = (uint32_t)__ballot((FULL || j0 + col < a.L) && mk[P] != 0.f);                          \
+    f32x16 bt;                                                                                                   \
+    if (BIAS) bias_rows_to_tile(bt, brow[P], keys, a.sqrt_d, tile, lane, col, hf);                               \
+    else if (FULL && !a.mask) bt = zero16();                                                                     \
+    else mask_tile(bt, keys, hf);                                                                                \
+    if (BIAS) bias_rows_fetch<FULL>(brow[PF], a, h, i0a, jn, lane);                                              \
+    if (FULL || jn + col < a.L) mk[PF] = mrow[jn + col];
+#define FF_BWD_Q_TAIL(P)                                                                                         \
+    if (j0 + 32 < a.L)                                                                                           \
+        stage_store<D, FULL>(src, j0 + 32, tid, s_stage + (1 - (P)) * kStBytes, rs[1 - (P)][0], rs[1 - (P)][1], rs[1 - (P)][2]); \
+    __syncthreads();
+
 // ====================================================================================
 // Block = four consecutive query tiles of one (row, head); the key-side tiles (k rows, v position-contiguous) are
 // staged once per block and key tile; the bias rows and the key-mask entries of the next tile are requested
 // while this one is worked on.
-template <int D>
+template <int D, bool FULL, bool BIAS>
 __global__ __launch_bounds__(256) void k_bwd_stats(Args a) {
     constexpr int KS = (D + 15) / 16;
     __shared__ __attribute__((aligned(16))) unsigned char s_stage[2 * kStBytes];
@@ -354,65 +402,46 @@ __global__ __launch_bounds__(256) void k_bwd_stats(Args a) {
     src.x = a.k + base; src.y = nullptr; src.xT = nullptr; src.yT = a.vT + (size_t)rh * D * a.Lp;
     src.va = nullptr; src.vb = nullptr; src.L = a.L; src.Lp = a.Lp;
     Frag qf[KS];
-    load_rows<D>(qf, a.q + base, active ? i0 : 0, a.L, col, hf);
-    float4 brow[4];
-    bias_rows_fetch(brow, a, h, active ? i0 : 0, 0, lane);
-    float mk = 1.f;
-    if (a.mask && col < a.L) mk = a.mask[(size_t)r * a.L + col];
-    {
-        uint4 r0, r1, r2;
-        stage_fetch<D>(src, 0, tid, r0, r1, r2);
-        stage_store<D>(src, 0, tid, s_stage, r0, r1, r2);
-    }
-    __syncthreads();
+    load_rows<D, FULL>(qf, a.q + base, active ? i0 : 0, a.L, col, hf);
+    FF_BWD_Q_PROLOGUE
 
     float m = -INFINITY, l = 0.f;
     f32x16 ctx = zero16();          // ctx^T: lane = query, register v = channel 8(v/4) + 4hf + v%4
-    int st = 0;
-    for (int j0 = 0; j0 < a.L; j0 += 32, st ^= 1) {
-        const unsigned char* stage = s_stage + st * kStBytes;
-        const bool more = j0 + 32 < a.L;     // (uniform)
-        uint4 r0, r1, r2;
-        if (more) stage_fetch<D>(src, j0 + 32, tid, r0, r1, r2);
-        const uint32_t keys = (uint32_t)__ballot(j0 + col < a.L && mk != 0.f);
-        f32x16 bt = zero16();
-        if (a.bias) bias_rows_to_tile(bt, brow, tile, lane, col, hf);
-        if (more) {
-            if (a.bias) bias_rows_fetch(brow, a, h, active ? i0 : 0, j0 + 32, lane);
-            mk = 1.f;
-            if (a.mask && j0 + 32 + col < a.L) mk = a.mask[(size_t)r * a.L + j0 + 32 + col];
-        }
-        if (active) {
-            Frag kf[KS], vt[2], pf[2];
-            staged_rows<D>(kf, stage + kStRowsX, col, hf);
-            staged_cols<D>(vt, stage + kStColsY, col, hf);
-            f32x16 s = zero16();
-#pragma unroll
-            for (int t = 0; t < KS; ++t) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t].v, qf[t].v, s, 0, 0, 0);
-            logits_by_query(s, bt, keys, i < a.L, a.qscale2, hf);
-            float tmax = s[0];
-#pragma unroll
-            for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, s[v]);
-            tmax = fmaxf(tmax, other_half(tmax));
-            const float m_new = fmaxf(m, tmax);
-            // (nothing valid so far: every weight of the tile is zero and nothing is rescaled)
-            const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m - m_new);
-            float lt = 0.f;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                s[v] = m_new == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(s[v] - m_new);
-                lt += s[v];
-                ctx[v] *= alpha;
-            }
-            l = l * alpha + lt;
-            m = m_new;
-            pack_rows(pf, s);
-#pragma unroll
-            for (int t = 0; t < 2; ++t) ctx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt[t].v, pf[t].v, ctx, 0, 0, 0);
-        }
-        if (more) stage_store<D>(src, j0 + 32, tid, s_stage + (st ^ 1) * kStBytes, r0, r1, r2);
-        __syncthreads();
+#define FF_BWD_STATS_TILE(P)                                                                                     \
+    {                                                                                                            \
+        FF_BWD_Q_HEAD(P)                                                                                         \
+        if (active) {                                                                                            \
+            Frag kf[KS], vt[2], pf[2];                                                                           \
+            staged_rows<D>(kf, stage + kStRowsX, col, hf);                                                       \
+            staged_cols<D>(vt, stage + kStColsY, col, hf);                                                       \
+            f32x16 s = bt;                                                                                       \
+            _Pragma("unroll") for (int t = 0; t < KS; ++t)                                                       \
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t].v, qf[t].v, s, 0, 0, 0);                       \
+            float tmax = s[0];                                                                                   \
+            _Pragma("unroll") for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, s[v]);                             \
+            tmax = fmaxf(tmax, other_half(tmax)) * a.qscale2;       /* (qscale2 > 0) */                          \
+            const float m_new = fmaxf(m, tmax);                                                                  \
+            /* (nothing valid so far: every weight of the tile is zero and nothing is rescaled) */               \
+            const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m - m_new);                    \
+            float lt = 0.f;                                                                                      \
+            _Pragma("unroll") for (int v = 0; v < 16; ++v) {                                                     \
+                s[v] = m_new == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(s[v] * a.qscale2 - m_new);              \
+                lt += s[v];                                                                                      \
+                ctx[v] *= alpha;                                                                                 \
+            }                                                                                                    \
+            l = l * alpha + lt;                                                                                  \
+            m = m_new;                                                                                           \
+            pack_rows(pf, s);                                                                                    \
+            _Pragma("unroll") for (int t = 0; t < 2; ++t)                                                        \
+                ctx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt[t].v, pf[t].v, ctx, 0, 0, 0);                   \
+        }                                                                                                        \
+        FF_BWD_Q_TAIL(P)                                                                                         \
     }
+    for (int tt = 0; 32 * tt < a.L; tt += 2) {
+        FF_BWD_STATS_TILE(0)
+        if (32 * (tt + 1) < a.L) FF_BWD_STATS_TILE(1)
+    }
+#undef FF_BWD_STATS_TILE
     if (!active) return;             // (no barrier after this point)
     const float l_tot = l + other_half(l);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
@@ -463,8 +492,8 @@ __global__ __launch_bounds__(256) void k_bwd_stats(Args a) {
 
 // ====================================================================================
 // Block = four consecutive query tiles of one (row, head); staged per key tile: k rows, v rows, k position-contiguous.
-template <int D>
-__global__ __launch_bounds__(256) void k_bwd_dq(Args a) {
+template <int D, bool FULL, bool BIAS>
+__global__ __launch_bounds__(256, 3) void k_bwd_dq(Args a) {
     constexpr int KS = (D + 15) / 16;
     __shared__ __attribute__((aligned(16))) unsigned char s_stage[2 * kStBytes];
     __shared__ __attribute__((aligned(16))) float s_tile[4 * 32 * kTilePitch];
@@ -480,56 +509,41 @@ __global__ __launch_bounds__(256) void k_bwd_dq(Args a) {
     src.x = a.k + base; src.y = a.v + base; src.xT = a.kT + (size_t)rh * D * a.Lp; src.yT = nullptr;
     src.va = nullptr; src.vb = nullptr; src.L = a.L; src.Lp = a.Lp;
     Frag qf[KS], dcf[KS];
-    load_rows<D>(qf, a.q + base, active ? i0 : 0, a.L, col, hf);
-    load_rows<D>(dcf, a.dctx + base, active ? i0 : 0, a.L, col, hf);
+    load_rows<D, FULL>(qf, a.q + base, active ? i0 : 0, a.L, col, hf);
+    load_rows<D, FULL>(dcf, a.dctx + base, active ? i0 : 0, a.L, col, hf);
     const float lse = a.lse[(size_t)rh * a.Lp + (active ? i : col)], delta = a.delta[(size_t)rh * a.Lp + (active ? i : col)];
-    float4 brow[4];
-    bias_rows_fetch(brow, a, h, active ? i0 : 0, 0, lane);
-    float mk = 1.f;
-    if (a.mask && col < a.L) mk = a.mask[(size_t)r * a.L + col];
-    {
-        uint4 r0, r1, r2;
-        stage_fetch<D>(src, 0, tid, r0, r1, r2);
-        stage_store<D>(src, 0, tid, s_stage, r0, r1, r2);
-    }
-    __syncthreads();
+    FF_BWD_Q_PROLOGUE
 
     f32x16 dq = zero16();           // dq^T: lane = query, register = channel
-    int st = 0;
-    for (int j0 = 0; j0 < a.L; j0 += 32, st ^= 1) {
-        const unsigned char* stage = s_stage + st * kStBytes;
-        const bool more = j0 + 32 < a.L;     // (uniform)
-        uint4 r0, r1, r2;
-        if (more) stage_fetch<D>(src, j0 + 32, tid, r0, r1, r2);
-        const uint32_t keys = (uint32_t)__ballot(j0 + col < a.L && mk != 0.f);
-        f32x16 bt = zero16();
-        if (a.bias) bias_rows_to_tile(bt, brow, tile, lane, col, hf);
-        if (more) {
-            if (a.bias) bias_rows_fetch(brow, a, h, active ? i0 : 0, j0 + 32, lane);
-            mk = 1.f;
-            if (a.mask && j0 + 32 + col < a.L) mk = a.mask[(size_t)r * a.L + j0 + 32 + col];
-        }
-        if (active) {
-            Frag kf[KS], vf[KS], kt[2], dsf[2];
-            staged_rows<D>(kf, stage + kStRowsX, col, hf);
-            staged_rows<D>(vf, stage + kStRowsY, col, hf);
-            f32x16 s = zero16(), dp = zero16();
+    f32x16 ndelta;
 #pragma unroll
-            for (int t = 0; t < KS; ++t) {
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t].v, qf[t].v, s, 0, 0, 0);
-                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t].v, dcf[t].v, dp, 0, 0, 0);
-            }
-            staged_cols<D>(kt, stage + kStColsX, col, hf);
-            logits_by_query(s, bt, keys, i < a.L, a.qscale2, hf);
-#pragma unroll
-            for (int v = 0; v < 16; ++v) s[v] = __builtin_amdgcn_exp2f(s[v] - lse) * (dp[v] - delta);
-            pack_rows(dsf, s);
-#pragma unroll
-            for (int t = 0; t < 2; ++t) dq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt[t].v, dsf[t].v, dq, 0, 0, 0);
-        }
-        if (more) stage_store<D>(src, j0 + 32, tid, s_stage + (st ^ 1) * kStBytes, r0, r1, r2);
-        __syncthreads();
+    for (int v = 0; v < 16; ++v) ndelta[v] = -delta;
+#define FF_BWD_DQ_TILE(P)                                                                                        \
+    {                                                                                                            \
+        FF_BWD_Q_HEAD(P)                                                                                         \
+        if (active) {                                                                                            \
+            Frag kf[KS], vf[KS], kt[2], dsf[2];                                                                  \
+            staged_rows<D>(kf, stage + kStRowsX, col, hf);                                                       \
+            staged_rows<D>(vf, stage + kStRowsY, col, hf);                                                       \
+            f32x16 s = bt, dp = ndelta;      /* dP - delta: the accumulator starts from -delta */                \
+            _Pragma("unroll") for (int t = 0; t < KS; ++t) {                                                     \
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t].v, qf[t].v, s, 0, 0, 0);                       \
+                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t].v, dcf[t].v, dp, 0, 0, 0);                    \
+            }                                                                                                    \
+            staged_cols<D>(kt, stage + kStColsX, col, hf);                                                       \
+            _Pragma("unroll") for (int v = 0; v < 16; ++v)                                                       \
+                s[v] = __builtin_amdgcn_exp2f(s[v] * a.qscale2 - lse) * dp[v];                                   \
+            pack_rows(dsf, s);                                                                                   \
+            _Pragma("unroll") for (int t = 0; t < 2; ++t)                                                        \
+                dq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kt[t].v, dsf[t].v, dq, 0, 0, 0);                    \
+        }                                                                                                        \
+        FF_BWD_Q_TAIL(P)                                                                                         \
     }
+    for (int tt = 0; 32 * tt < a.L; tt += 2) {
+        FF_BWD_DQ_TILE(0)
+        if (32 * (tt + 1) < a.L) FF_BWD_DQ_TILE(1)
+    }
+#undef FF_BWD_DQ_TILE
     if (active && i < a.L) {
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
@@ -545,10 +559,11 @@ __global__ __launch_bounds__(256) void k_bwd_dq(Args a) {
 // ====================================================================================
 // Block = four consecutive key tiles of one (row, head); the query-side tiles (q, dctx, their position-contiguous
 // copies, logsumexp, delta) are staged once per block and query tile.
-template <int D>
+template <int D, bool FULL, bool BIAS>
 __global__ __launch_bounds__(256) void k_bwd_dkv(Args a) {
     constexpr int KS = (D + 15) / 16;
     __shared__ __attribute__((aligned(16))) unsigned char s_stage[2 * kStBytes];
+    __shared__ __attribute__((aligned(16))) float s_tile[4 * 32 * kTilePitch];
     const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nt = a.Lp >> 5, bpr = (nt + 3) >> 2;               // key tiles, blocks per (row, head)
@@ -563,80 +578,90 @@ __global__ __launch_bounds__(256) void k_bwd_dkv(Args a) {
     src.L = a.L; src.Lp = a.Lp;
 
     Frag kf[KS], vf[KS];
-    load_rows<D>(kf, a.k + base, active ? j0 : 0, a.L, col, hf);
-    load_rows<D>(vf, a.v + base, active ? j0 : 0, a.L, col, hf);
-    const bool key_ok = active && j < a.L && (!a.mask || a.mask[(size_t)r * a.L + j] != 0.f);
-    // the lane's bias column, times log2(e), for the queries of the coming tile: register v = query i0 + 8(v/4) + 4hf + v%4
-    const float* bcol = a.bias ? a.bias + (size_t)h * a.L * a.L + (j < a.L ? j : 0) : nullptr;
-    f32x16 bn = zero16();
-    if (bcol) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int i = 8 * (v >> 2) + 4 * hf + (v & 3);
-            if (i < a.L) bn[v] = bcol[(size_t)i * a.L];
+    load_rows<D, FULL>(kf, a.k + base, active ? j0 : 0, a.L, col, hf);
+    load_rows<D, FULL>(vf, a.v + base, active ? j0 : 0, a.L, col, hf);
+    const bool key_ok = active && (FULL || j < a.L) && a.mrow[(size_t)r * a.mstride + ((FULL || j < a.L) ? j : 0)] != 0.f;
+    // What the accumulator of the logits starts from (see bias_rows_fetch), here with lane = key and register v =
+    // query i0 + 8(v/4) + 4hf + v%4: the bias tile times sqrt(d), or -inf in every register if the lane's key is
+    // masked or beyond L.  Two sets of bias rows (even and odd query tiles), requested two tiles ahead like the
+    // staged tiles.
+    const float kterm = key_ok ? 0.f : -INFINITY;
+    const int j0a = active ? j0 : 0;
+    float* tile = s_tile + wave * 32 * kTilePitch;
+    float4 brow[2][4];
+    uint4 rs[2][3];
+    {
+        const int n1 = 32 < a.L ? 32 : 0;
+        stage_fetch<D, FULL>(src, 0, tid, rs[0][0], rs[0][1], rs[0][2]);
+        if (kAhead == 2) stage_fetch<D, FULL>(src, n1, tid, rs[1][0], rs[1][1], rs[1][2]);
+        if (BIAS) {
+            bias_rows_fetch<FULL>(brow[0], a, h, 0, j0a, lane);
+            if (kAhead == 2) bias_rows_fetch<FULL>(brow[1], a, h, n1, j0a, lane);
         }
     }
-    {
-        uint4 r0, r1, r2;
-        stage_fetch<D>(src, 0, tid, r0, r1, r2);
-        stage_store<D>(src, 0, tid, s_stage, r0, r1, r2);
-    }
+    stage_store<D, FULL>(src, 0, tid, s_stage, rs[0][0], rs[0][1], rs[0][2]);
     __syncthreads();
 
     f32x16 dk = zero16(), dv = zero16();     // dk^T, dv^T: lane = key, register = channel
-    int st = 0;
-    for (int i0 = 0; i0 < a.L; i0 += 32, st ^= 1) {
-        const unsigned char* stage = s_stage + st * kStBytes;
-        const bool more = i0 + 32 < a.L;     // (uniform)
-        uint4 r0, r1, r2;
-        if (more) stage_fetch<D>(src, i0 + 32, tid, r0, r1, r2);
-        f32x16 bt = bn;
-        if (bcol && more) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int i = i0 + 32 + 8 * (v >> 2) + 4 * hf + (v & 3);
-                bn[v] = 0.f;
-                if (i < a.L) bn[v] = bcol[(size_t)i * a.L];
-            }
-        }
-        if (active) {
-            Frag qf[KS], dcf[KS], qt[2], dct[2], pf[2], dsf[2];
-            staged_rows<D>(qf, stage + kStRowsX, col, hf);
-            staged_rows<D>(dcf, stage + kStRowsY, col, hf);
-            f32x16 s = zero16(), dp = zero16();      // lane = key, register v = query i0 + 8(v/4) + 4hf + v%4
-#pragma unroll
-            for (int t = 0; t < KS; ++t) {
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[t].v, kf[t].v, s, 0, 0, 0);
-                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dcf[t].v, vf[t].v, dp, 0, 0, 0);
-            }
-            staged_cols<D>(qt, stage + kStColsX, col, hf);
-            staged_cols<D>(dct, stage + kStColsY, col, hf);
-#pragma unroll
-            for (int gq = 0; gq < 4; ++gq) {
-                const float4 l4 = *reinterpret_cast<const float4*>(stage + kStVecA + (8 * gq + 4 * hf) * 4);
-                const float4 d4 = *reinterpret_cast<const float4*>(stage + kStVecB + (8 * gq + 4 * hf) * 4);
-                const float ls[4] = {l4.x, l4.y, l4.z, l4.w}, ds_[4] = {d4.x, d4.y, d4.z, d4.w};
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int v = 4 * gq + e;
-                    // (a query beyond L has logsumexp +inf: weight 0; a masked key or one beyond L: weight 0)
-                    const float p = key_ok ? __builtin_amdgcn_exp2f(s[v] * a.qscale2 + bt[v] * kLog2e - ls[e]) : 0.f;
-                    s[v] = p;
-                    dp[v] = p * (dp[v] - ds_[e]);
-                }
-            }
-            pack_rows(pf, s);
-            pack_rows(dsf, dp);
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                dv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dct[t].v, pf[t].v, dv, 0, 0, 0);
-                dk = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt[t].v, dsf[t].v, dk, 0, 0, 0);
-            }
-        }
-        if (more) stage_store<D>(src, i0 + 32, tid, s_stage + (st ^ 1) * kStBytes, r0, r1, r2);
-        __syncthreads();
+#define FF_BWD_DKV_TILE(P)                                                                                       \
+    {                                                                                                            \
+        const int i0 = 32 * (tt + (P));                                                                          \
+        const unsigned char* stage = s_stage + (P) * kStBytes;                                                   \
+        constexpr int PF = kAhead == 2 ? (P) : 1 - (P);                                                          \
+        const int in = i0 + 32 * kAhead < a.L ? i0 + 32 * kAhead : i0;    /* (the last tiles ask for themselves again) */ \
+        stage_fetch<D, FULL>(src, in, tid, rs[PF][0], rs[PF][1], rs[PF][2]);                                     \
+        f32x16 s;                                                                                                \
+        if (BIAS) {                                                                                              \
+            bias_rows_to_tile_by_key(s, brow[P], kterm, a.sqrt_d, tile, lane, col, hf);                          \
+            bias_rows_fetch<FULL>(brow[PF], a, h, in, j0a, lane);                                                \
+        } else {                                                                                                 \
+            _Pragma("unroll") for (int v = 0; v < 16; ++v) s[v] = kterm;                                         \
+        }                                                                                                        \
+        if (active) {                                                                                            \
+            Frag qf[KS], dcf[KS], qt[2], dct[2], pf[2], dsf[2];                                                  \
+            staged_rows<D>(qf, stage + kStRowsX, col, hf);                                                       \
+            staged_rows<D>(dcf, stage + kStRowsY, col, hf);                                                      \
+            f32x16 dp;        /* lane = key, register v = query i0 + 8(v/4) + 4hf + v%4; starts from -delta */   \
+            _Pragma("unroll") for (int gq = 0; gq < 4; ++gq) {                                                   \
+                const float4 d4 = *reinterpret_cast<const float4*>(stage + kStVecB + (8 * gq + 4 * hf) * 4);     \
+                dp[4 * gq] = -d4.x; dp[4 * gq + 1] = -d4.y; dp[4 * gq + 2] = -d4.z; dp[4 * gq + 3] = -d4.w;      \
+            }                                                                                                    \
+            _Pragma("unroll") for (int t = 0; t < KS; ++t) {                                                     \
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[t].v, kf[t].v, s, 0, 0, 0);                       \
+                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dcf[t].v, vf[t].v, dp, 0, 0, 0);                    \
+            }                                                                                                    \
+            staged_cols<D>(qt, stage + kStColsX, col, hf);                                                       \
+            staged_cols<D>(dct, stage + kStColsY, col, hf);                                                      \
+            _Pragma("unroll") for (int gq = 0; gq < 4; ++gq) {                                                   \
+                const float4 l4 = *reinterpret_cast<const float4*>(stage + kStVecA + (8 * gq + 4 * hf) * 4);     \
+                const float ls[4] = {l4.x, l4.y, l4.z, l4.w};                                                    \
+                _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                                  \
+                    const int v = 4 * gq + e;                                                                    \
+                    /* (a query beyond L or without keys has logsumexp +inf, a masked key a logit of -inf:        \
+                       weight 0 either way) */                                                                   \
+                    const float p = __builtin_amdgcn_exp2f(s[v] * a.qscale2 - ls[e]);                            \
+                    s[v] = p;                                                                                    \
+                    dp[v] = p * dp[v];                                                                           \
+                }                                                                                                \
+            }                                                                                                    \
+            pack_rows(pf, s);                                                                                    \
+            pack_rows(dsf, dp);                                                                                  \
+            _Pragma("unroll") for (int t = 0; t < 2; ++t) {                                                      \
+                dv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dct[t].v, pf[t].v, dv, 0, 0, 0);                    \
+                dk = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qt[t].v, dsf[t].v, dk, 0, 0, 0);                    \
+            }                                                                                                    \
+        }                                                                                                        \
+        if (i0 + 32 < a.L)                                                                                       \
+            stage_store<D, FULL>(src, i0 + 32, tid, s_stage + (1 - (P)) * kStBytes, rs[1 - (P)][0], rs[1 - (P)][1], \
+                                 rs[1 - (P)][2]);                                                                \
+        __syncthreads();                                                                                         \
     }
-    if (active && j < a.L) {
+    for (int tt = 0; 32 * tt < a.L; tt += 2) {
+        FF_BWD_DKV_TILE(0)
+        if (32 * (tt + 1) < a.L) FF_BWD_DKV_TILE(1)
+    }
+#undef FF_BWD_DKV_TILE
+    if (active && (FULL || j < a.L)) {
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
             const int e0 = 8 * gq + 4 * hf;
@@ -651,7 +676,7 @@ __global__ __launch_bounds__(256) void k_bwd_dkv(Args a) {
 }
 
 // ====================================================================================
-template <int D>
+template <int D, bool FULL, bool BIAS>
 __global__ __launch_bounds__(256) void k_bwd_dbias(Args a) {
     constexpr int KS = (D + 15) / 16;
     const int lane = threadIdx.x & 63, col = lane & 31, hf = lane >> 5;
@@ -665,8 +690,12 @@ __global__ __launch_bounds__(256) void k_bwd_dbias(Args a) {
     const int r_end = r_begin + a.rows_per_chunk < a.R ? r_begin + a.rows_per_chunk : a.R;
     const int i = i0 + col;
     __shared__ __attribute__((aligned(16))) float s_tile[4 * 32 * kTilePitch];
-    f32x16 bt;
-    bias_tile_by_query(bt, a, h, i0, j0, s_tile + wave * 32 * kTilePitch, lane, col, hf);
+    f32x16 bt;                      // bias tile times sqrt(d) (the tile is the same for every batch row; the key mask is not)
+    {
+        float4 rows[4];
+        bias_rows_fetch<FULL>(rows, a, h, i0, j0, lane);
+        bias_rows_to_tile(bt, rows, 0xffffffffu, a.sqrt_d, s_tile + wave * 32 * kTilePitch, lane, col, hf);
+    }
     f32x16 acc = zero16();          // lane = query i, register v = key j0 + 8(v/4) + 4hf + v%4
     // the operands of the next batch row are requested before this one is worked on (the last round asks for its
     // own again: a load under a condition would make every wait in the loop a wait for all loads)
@@ -675,40 +704,45 @@ __global__ __launch_bounds__(256) void k_bwd_dbias(Args a) {
     {
         const int rh = r_begin * a.H + h;
         const size_t base = (size_t)rh * a.L * D;
-        load_rows<D>(qn, a.q + base, i0, a.L, col, hf);
-        load_rows<D>(dcn, a.dctx + base, i0, a.L, col, hf);
-        load_rows<D>(kn, a.k + base, j0, a.L, col, hf);
-        load_rows<D>(vn, a.v + base, j0, a.L, col, hf);
+        load_rows<D, FULL>(qn, a.q + base, i0, a.L, col, hf);
+        load_rows<D, FULL>(dcn, a.dctx + base, i0, a.L, col, hf);
+        load_rows<D, FULL>(kn, a.k + base, j0, a.L, col, hf);
+        load_rows<D, FULL>(vn, a.v + base, j0, a.L, col, hf);
         lse_n = a.lse[(size_t)rh * a.Lp + i];
         delta_n = a.delta[(size_t)rh * a.Lp + i];
-        if (a.mask && j0 + col < a.L) mk_n = a.mask[(size_t)r_begin * a.L + j0 + col];
+        if (FULL || j0 + col < a.L) mk_n = a.mrow[(size_t)r_begin * a.mstride + j0 + col];
     }
     for (int r = r_begin; r < r_end; ++r) {
         Frag qf[KS], dcf[KS], kf[KS], vf[KS];
 #pragma unroll
         for (int t = 0; t < KS; ++t) { qf[t].u = qn[t].u; dcf[t].u = dcn[t].u; kf[t].u = kn[t].u; vf[t].u = vn[t].u; }
         const float lse = lse_n, delta = delta_n;
-        const uint32_t keys = (uint32_t)__ballot(j0 + col < a.L && mk_n != 0.f);
+        const uint32_t keys = (uint32_t)__ballot((FULL || j0 + col < a.L) && mk_n != 0.f);
         {
             const int rn = r + 1 < r_end ? r + 1 : r, rh = rn * a.H + h;
             const size_t base = (size_t)rh * a.L * D;
-            load_rows<D>(qn, a.q + base, i0, a.L, col, hf);
-            load_rows<D>(dcn, a.dctx + base, i0, a.L, col, hf);
-            load_rows<D>(kn, a.k + base, j0, a.L, col, hf);
-            load_rows<D>(vn, a.v + base, j0, a.L, col, hf);
+            load_rows<D, FULL>(qn, a.q + base, i0, a.L, col, hf);
+            load_rows<D, FULL>(dcn, a.dctx + base, i0, a.L, col, hf);
+            load_rows<D, FULL>(kn, a.k + base, j0, a.L, col, hf);
+            load_rows<D, FULL>(vn, a.v + base, j0, a.L, col, hf);
             lse_n = a.lse[(size_t)rh * a.Lp + i];
             delta_n = a.delta[(size_t)rh * a.Lp + i];
-            if (a.mask && j0 + col < a.L) mk_n = a.mask[(size_t)rn * a.L + j0 + col];
+            if (FULL || j0 + col < a.L) mk_n = a.mrow[(size_t)rn * a.mstride + j0 + col];
         }
-        f32x16 s = zero16(), dp = zero16();
+        f32x16 s = bt, dp;          // the accumulators start from the bias tile (-inf for this row's masked keys) and -delta
+        if (!FULL || a.mask) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) s[v] = ((keys >> (8 * (v >> 2) + 4 * hf + (v & 3))) & 1u) ? bt[v] : -INFINITY;
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) dp[v] = -delta;
 #pragma unroll
         for (int t = 0; t < KS; ++t) {
             s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t].v, qf[t].v, s, 0, 0, 0);
             dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t].v, dcf[t].v, dp, 0, 0, 0);
         }
-        logits_by_query(s, bt, keys, i < a.L, a.qscale2, hf);
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[v] += __builtin_amdgcn_exp2f(s[v] - lse) * (dp[v] - delta);
+        for (int v = 0; v < 16; ++v) acc[v] += __builtin_amdgcn_exp2f(s[v] * a.qscale2 - lse) * dp[v];
     }
     if (i < a.L) {
         float* out = a.row_chunks > 1 ? a.dbias_part + (size_t)chunk * a.H * a.L * a.L : a.dbias;
@@ -749,7 +783,7 @@ static int dbias_chunks(const ff_core_desc& d) {
 size_t core_backward_workspace(const ff_core_desc& d) {
     const size_t Lp = bwd::round_up(d.length, 32), rh = (size_t)d.rows * d.heads;
     const int chunks = dbias_chunks(d);
-    return 2 * bwd::align256(rh * Lp * 4) + bwd::align256(rh * d.length * d.head_dim * 2) +
+    return bwd::align256(Lp * 4) + 2 * bwd::align256(rh * Lp * 4) + bwd::align256(rh * d.length * d.head_dim * 2) +
            4 * bwd::align256(rh * d.head_dim * Lp * 2) +
            (chunks > 1 ? bwd::align256((size_t)chunks * d.heads * d.length * d.length * 4) : 0);
 }
@@ -764,6 +798,9 @@ ff_status core_backward_run(const ff_core_desc& d, const void* q, const void* k,
     a.R = d.rows; a.H = d.heads; a.L = d.length; a.Lp = round_up(d.length, 32);
     const size_t rh = (size_t)d.rows * d.heads;
     char* p = (char*)ws;
+    a.ones = (float*)p; p += align256((size_t)a.Lp * 4);
+    a.mrow = mask ? mask : a.ones;
+    a.mstride = mask ? d.length : 0;
     a.lse = (float*)p; p += align256(rh * a.Lp * 4);
     a.delta = (float*)p; p += align256(rh * a.Lp * 4);
     a.dctx = (bf16_t*)p; p += align256(rh * d.length * d.head_dim * 2);
@@ -777,17 +814,31 @@ ff_status core_backward_run(const ff_core_desc& d, const void* q, const void* k,
     a.dbias_part = a.row_chunks > 1 ? (float*)p : nullptr;
     a.qscale2 = kLog2e / sqrtf((float)d.head_dim);
     a.scale = 1.f / sqrtf((float)d.head_dim);
+    a.sqrt_d = sqrtf((float)d.head_dim);
     const int nt = a.Lp / 32;
     const dim3 g1((unsigned)((rh * nt + 3) / 4)), g2((unsigned)(((size_t)a.row_chunks * d.heads * nt * nt + 3) / 4));
+    const bool full = d.length % 32 == 0;        // nothing out of range: the kernels without bounds checks
+#define FF_BWD_D(KERNEL, GRID, DV)                                                                       \
+    do {                                                                                                 \
+        if (full && bias) hipLaunchKernelGGL((KERNEL<DV, true, true>), GRID, dim3(256), 0, st, a);       \
+        else if (full) hipLaunchKernelGGL((KERNEL<DV, true, false>), GRID, dim3(256), 0, st, a);         \
+        else if (bias) hipLaunchKernelGGL((KERNEL<DV, false, true>), GRID, dim3(256), 0, st, a);         \
+        else hipLaunchKernelGGL((KERNEL<DV, false, false>), GRID, dim3(256), 0, st, a);                  \
+    } while (0)
 #define FF_BWD(KERNEL, GRID, KIND)                                                                       \
     do {                                                                                                 \
         Timed t(KIND, st);                                                                               \
-        if (d.head_dim == 8) hipLaunchKernelGGL((KERNEL<8>), GRID, dim3(256), 0, st, a);                 \
-        else if (d.head_dim == 16) hipLaunchKernelGGL((KERNEL<16>), GRID, dim3(256), 0, st, a);          \
-        else hipLaunchKernelGGL((KERNEL<32>), GRID, dim3(256), 0, st, a);                                \
+        if (d.head_dim == 8) FF_BWD_D(KERNEL, GRID, 8);                                                  \
+        else if (d.head_dim == 16) FF_BWD_D(KERNEL, GRID, 16);                                           \
+        else FF_BWD_D(KERNEL, GRID, 32);                                                                 \
     } while (0)
     const dim3 gt(g1.x, 3);
-    FF_BWD(k_bwd_transpose, gt, KK_BWD_STATS);
+    {
+        Timed t(KK_BWD_STATS, st);
+        if (d.head_dim == 8) hipLaunchKernelGGL((k_bwd_transpose<8>), gt, dim3(256), 0, st, a);
+        else if (d.head_dim == 16) hipLaunchKernelGGL((k_bwd_transpose<16>), gt, dim3(256), 0, st, a);
+        else hipLaunchKernelGGL((k_bwd_transpose<32>), gt, dim3(256), 0, st, a);
+    }
     const dim3 g4((unsigned)(rh * ((nt + 3) / 4)));          // blocks of four tiles of one (row, head)
     FF_BWD(k_bwd_stats, g4, KK_BWD_STATS);
     FF_BWD(k_bwd_dq, g4, KK_BWD_DQ);
@@ -800,6 +851,7 @@ ff_status core_backward_run(const ff_core_desc& d, const void* q, const void* k,
         }
     }
 #undef FF_BWD
+#undef FF_BWD_D
     return check_launch("attention core backward");
 }
 
