@@ -366,23 +366,30 @@ __global__ __launch_bounds__(256, 2) void k_tm_mul(TmMulArgs p) {
 #undef stash
 
     // t leaves as [i][channel][j]: the channels of a row i lie close together, which is what the LayerNorm over
-    // the channels in k_tm_out reads (128 short segments inside half a megabyte instead of one per 8 MiB plane)
-    bf16_t* xc = p.x + (size_t)ch * p.Np;
-    const size_t xrow = (size_t)p.C * p.Np;
+    // the channels in k_tm_out reads (128 short segments inside half a megabyte instead of one per 8 MiB plane).
+    // A lane holds 8-byte pieces of 64 different rows i, rows that lie C Np elements apart: stored like that every
+    // instruction would touch 64 lines.  The wavefront's 64 x 64 tile is therefore gathered in LDS (free after the
+    // last barrier of the loop; each wavefront uses its own part, and a wavefront's LDS operations complete in
+    // order) and leaves as 128-byte row segments, 16 bytes per lane.
+    {
+        unsigned char* s_o = smem + wave * (64 * PITCH);
 #pragma unroll
-    for (int ti = 0; ti < 2; ++ti) {
-        const int i = i0 + wi * 64 + 32 * ti + col;
-        if (i >= p.N) continue;
+        for (int ti = 0; ti < 2; ++ti)
 #pragma unroll
-        for (int tj = 0; tj < 2; ++tj)
+            for (int tj = 0; tj < 2; ++tj)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int j = j0 + wj * 64 + 32 * tj + 8 * g + 4 * hf;
-                if (j < p.Np)
-                    *reinterpret_cast<uint2*>(xc + (size_t)i * xrow + j) =
-                        make_uint2(pack2(acc[tj][ti][4 * g], acc[tj][ti][4 * g + 1]),
-                                   pack2(acc[tj][ti][4 * g + 2], acc[tj][ti][4 * g + 3]));
-            }
+                for (int g = 0; g < 4; ++g)
+                    *reinterpret_cast<uint2*>(s_o + (32 * ti + col) * PITCH + (32 * tj + 8 * g + 4 * hf) * 2) =
+                        make_uint2(pack2(acc[tj][ti][4 * g], acc[tj][ti][4 * g + 1]), pack2(acc[tj][ti][4 * g + 2], acc[tj][ti][4 * g + 3]));
+        bf16_t* xc = p.x + (size_t)ch * p.Np;
+        const size_t xrow = (size_t)p.C * p.Np;
+        const int pcj = lane & 7, j = j0 + wj * 64 + pcj * 8;
+#pragma unroll
+        for (int n = 0; n < 8; ++n) {
+            const int row = 8 * n + (lane >> 3), i = i0 + wi * 64 + row;
+            const uint4 v = *reinterpret_cast<const uint4*>(s_o + row * PITCH + pcj * 16);
+            if (i < p.N && j < p.Np) *reinterpret_cast<uint4*>(xc + (size_t)i * xrow + j) = v;
+        }
     }
 }
 
