@@ -256,35 +256,51 @@ __global__ __launch_bounds__(512, 2) void k_tm_proj(TmProjArgs p) {
 struct TmMulArgs {
     const bf16_t *a, *b;     // [C][N][Np]
     bf16_t* x;               // [N][C][Np]
-    int N, Np, C, tiles;     // tiles per side
+    int N, Np, C, tiles_i, tiles_j;     // block tiles along i and along j
 };
 
 constexpr int kMulPitch = 144;                          // bytes per 64-element row in LDS (128 + 16 padding)
-constexpr int kMulStage = 128 * kMulPitch;
-constexpr size_t kMulSmem = 4 * (size_t)kMulStage;      // two operands, two buffers
 
-__global__ __launch_bounds__(256, 2) void k_tm_mul(TmMulArgs p) {
-    constexpr int PITCH = kMulPitch, STAGE = kMulStage;
+// Block tile (32 WI TI) x (32 WJ TJ) of one channel: WI x WJ wavefronts, each TI x TJ accumulator tiles of 32 x 32.
+// Per contraction step a wavefront reads TI + TJ operand fragments from LDS for TI TJ matrix instructions: the
+// LDS read rate is what bounds this kernel (1 KiB per instruction at 2 x 2), hence 4 x 2 tiles per wavefront (and a
+// 256 x 256 block tile, eight wavefronts, all of LDS) where the matrix is large enough to fill the chip with those.
+template <int WI, int WJ, int TI, int TJ>
+struct MulShape {
+    static constexpr int NT = 64 * WI * WJ, BI = 32 * WI * TI, BJ = 32 * WJ * TJ;
+    static constexpr int RSTEP = NT / 8;                 // rows between the pieces of one thread
+    static_assert(BI * 8 / NT == 4 && BJ * 8 / NT == 4, "four 16-byte pieces per thread, operand and chunk");
+    static constexpr int STAGE_A = BI * kMulPitch, STAGE_B = BJ * kMulPitch;
+    static constexpr size_t SMEM = 2 * (size_t)(STAGE_A + STAGE_B);      // two operands, two buffers
+    static_assert((size_t)WI * WJ * 32 * TI * kMulPitch <= SMEM, "the output tiles of all wavefronts fit in LDS");
+};
+
+template <int WI, int WJ, int TI, int TJ>
+__global__ __launch_bounds__(64 * WI * WJ, 2) void k_tm_mul(TmMulArgs p) {
+    using Sh = MulShape<WI, WJ, TI, TJ>;
+    constexpr int PITCH = kMulPitch, NT = Sh::NT, BI = Sh::BI, BJ = Sh::BJ, RSTEP = Sh::RSTEP;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    unsigned char* s_a = smem;                  // [2][STAGE]
-    unsigned char* s_b = smem + 2 * STAGE;      // [2][STAGE]
+    unsigned char* s_a = smem;                          // [2][STAGE_A]
+    unsigned char* s_b = smem + 2 * Sh::STAGE_A;        // [2][STAGE_B]
     const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wi = wave >> 1, wj = wave & 1;
-    const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3, t2 = p.tiles * p.tiles;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wi = wave / WJ, wj = wave % WJ;
+    const int xcd = blockIdx.x & 7, idx = blockIdx.x >> 3, t2 = p.tiles_i * p.tiles_j;
     const int ch = (idx / t2) * 8 + xcd, tile = idx % t2;
     if (ch >= p.C) return;                              // (whole block)
-    const int i0 = (tile / p.tiles) * 128, j0 = (tile % p.tiles) * 128;
+    const int i0 = (tile / p.tiles_j) * BI, j0 = (tile % p.tiles_j) * BJ;
     const size_t plane = (size_t)p.N * p.Np;
     const bf16_t* ac = p.a + (size_t)ch * plane;
     const bf16_t* bc = p.b + (size_t)ch * plane;
 
-    // this thread's four pieces of each operand chunk: rows tid/8 + 32n, piece tid%8 (16 bytes = 8 positions of k)
+    // this thread's four pieces of each operand chunk: rows tid/8 + RSTEP n, piece tid%8 (16 bytes = 8 positions of k)
     // (named registers and macros: arrays captured by a lambda end up in scratch memory)
     const int prow = tid >> 3, pc = tid & 7;
-    const bool a_ok0 = i0 + prow < p.N, a_ok1 = i0 + prow + 32 < p.N, a_ok2 = i0 + prow + 64 < p.N, a_ok3 = i0 + prow + 96 < p.N;
-    const bool b_ok0 = j0 + prow < p.N, b_ok1 = j0 + prow + 32 < p.N, b_ok2 = j0 + prow + 64 < p.N, b_ok3 = j0 + prow + 96 < p.N;
-    const size_t row32 = (size_t)32 * p.Np;
-    const bf16_t* ap = ac + (size_t)(a_ok0 ? i0 + prow : 0) * p.Np + pc * 8;     // rows + 32n: ap + n * row32 (guarded)
+    const bool a_ok0 = i0 + prow < p.N, a_ok1 = i0 + prow + RSTEP < p.N, a_ok2 = i0 + prow + 2 * RSTEP < p.N,
+               a_ok3 = i0 + prow + 3 * RSTEP < p.N;
+    const bool b_ok0 = j0 + prow < p.N, b_ok1 = j0 + prow + RSTEP < p.N, b_ok2 = j0 + prow + 2 * RSTEP < p.N,
+               b_ok3 = j0 + prow + 3 * RSTEP < p.N;
+    const size_t rstep = (size_t)RSTEP * p.Np;
+    const bf16_t* ap = ac + (size_t)(a_ok0 ? i0 + prow : 0) * p.Np + pc * 8;     // rows + RSTEP n: ap + n * rstep (guarded)
     const bf16_t* bp = bc + (size_t)(b_ok0 ? j0 + prow : 0) * p.Np + pc * 8;
     const int sdst = prow * PITCH + pc * 16;
     const uint4 zero4 = make_uint4(0, 0, 0, 0);
@@ -294,41 +310,41 @@ __global__ __launch_bounds__(256, 2) void k_tm_mul(TmMulArgs p) {
         const int k0_ = (KCH) * 64;                                                                    \
         const bool k_ok_ = k0_ + pc * 8 < p.Np;   /* Np is a multiple of 32: the last chunk may be half there */ \
         ra0 = zero4;                                                                                   \
-        if (a_ok0 && k_ok_) ra0 = *reinterpret_cast<const uint4*>(ap + k0_);   \
+        if (a_ok0 && k_ok_) ra0 = *reinterpret_cast<const uint4*>(ap + k0_);                           \
         ra1 = zero4;                                                                                   \
-        if (a_ok1 && k_ok_) ra1 = *reinterpret_cast<const uint4*>(ap + row32 + k0_);   \
+        if (a_ok1 && k_ok_) ra1 = *reinterpret_cast<const uint4*>(ap + rstep + k0_);                   \
         ra2 = zero4;                                                                                   \
-        if (a_ok2 && k_ok_) ra2 = *reinterpret_cast<const uint4*>(ap + 2 * row32 + k0_);   \
+        if (a_ok2 && k_ok_) ra2 = *reinterpret_cast<const uint4*>(ap + 2 * rstep + k0_);               \
         ra3 = zero4;                                                                                   \
-        if (a_ok3 && k_ok_) ra3 = *reinterpret_cast<const uint4*>(ap + 3 * row32 + k0_);   \
+        if (a_ok3 && k_ok_) ra3 = *reinterpret_cast<const uint4*>(ap + 3 * rstep + k0_);               \
         rb0 = zero4;                                                                                   \
-        if (b_ok0 && k_ok_) rb0 = *reinterpret_cast<const uint4*>(bp + k0_);   \
+        if (b_ok0 && k_ok_) rb0 = *reinterpret_cast<const uint4*>(bp + k0_);                           \
         rb1 = zero4;                                                                                   \
-        if (b_ok1 && k_ok_) rb1 = *reinterpret_cast<const uint4*>(bp + row32 + k0_);   \
+        if (b_ok1 && k_ok_) rb1 = *reinterpret_cast<const uint4*>(bp + rstep + k0_);                   \
         rb2 = zero4;                                                                                   \
-        if (b_ok2 && k_ok_) rb2 = *reinterpret_cast<const uint4*>(bp + 2 * row32 + k0_);   \
+        if (b_ok2 && k_ok_) rb2 = *reinterpret_cast<const uint4*>(bp + 2 * rstep + k0_);               \
         rb3 = zero4;                                                                                   \
-        if (b_ok3 && k_ok_) rb3 = *reinterpret_cast<const uint4*>(bp + 3 * row32 + k0_);   \
+        if (b_ok3 && k_ok_) rb3 = *reinterpret_cast<const uint4*>(bp + 3 * rstep + k0_);               \
     } while (0)
 #define stash(BUF)                                                                           \
     do {                                                                                     \
-        unsigned char* da_ = s_a + (BUF) * STAGE + sdst;                                     \
-        unsigned char* db_ = s_b + (BUF) * STAGE + sdst;                                     \
+        unsigned char* da_ = s_a + (BUF) * Sh::STAGE_A + sdst;                               \
+        unsigned char* db_ = s_b + (BUF) * Sh::STAGE_B + sdst;                               \
         *reinterpret_cast<uint4*>(da_) = ra0;                                                \
-        *reinterpret_cast<uint4*>(da_ + 32 * PITCH) = ra1;                                   \
-        *reinterpret_cast<uint4*>(da_ + 64 * PITCH) = ra2;                                   \
-        *reinterpret_cast<uint4*>(da_ + 96 * PITCH) = ra3;                                   \
+        *reinterpret_cast<uint4*>(da_ + RSTEP * PITCH) = ra1;                                \
+        *reinterpret_cast<uint4*>(da_ + 2 * RSTEP * PITCH) = ra2;                            \
+        *reinterpret_cast<uint4*>(da_ + 3 * RSTEP * PITCH) = ra3;                            \
         *reinterpret_cast<uint4*>(db_) = rb0;                                                \
-        *reinterpret_cast<uint4*>(db_ + 32 * PITCH) = rb1;                                   \
-        *reinterpret_cast<uint4*>(db_ + 64 * PITCH) = rb2;                                   \
-        *reinterpret_cast<uint4*>(db_ + 96 * PITCH) = rb3;                                   \
+        *reinterpret_cast<uint4*>(db_ + RSTEP * PITCH) = rb1;                                \
+        *reinterpret_cast<uint4*>(db_ + 2 * RSTEP * PITCH) = rb2;                            \
+        *reinterpret_cast<uint4*>(db_ + 3 * RSTEP * PITCH) = rb3;                            \
     } while (0)
 
-    f32x16 acc[2][2];     // [j tile][i tile]: lane = i, registers = j
+    f32x16 acc[TJ][TI];     // [j tile][i tile]: lane = i, registers = j
 #pragma unroll
-    for (int tj = 0; tj < 2; ++tj)
+    for (int tj = 0; tj < TJ; ++tj)
 #pragma unroll
-        for (int ti = 0; ti < 2; ++ti)
+        for (int ti = 0; ti < TI; ++ti)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[tj][ti][v] = 0.f;
 
@@ -345,19 +361,20 @@ __global__ __launch_bounds__(256, 2) void k_tm_mul(TmMulArgs p) {
     for (int kc = 0; kc < nk; ++kc) {
         const bool more = kc + 2 < nk;
         if (more) fetch(kc + 2);
-        const unsigned char* sa = s_a + (kc & 1) * STAGE + (wi * 64 + col) * PITCH + hf * 16;
-        const unsigned char* sb = s_b + (kc & 1) * STAGE + (wj * 64 + col) * PITCH + hf * 16;
+        const unsigned char* sa = s_a + (kc & 1) * Sh::STAGE_A + (wi * 32 * TI + col) * PITCH + hf * 16;
+        const unsigned char* sb = s_b + (kc & 1) * Sh::STAGE_B + (wj * 32 * TJ + col) * PITCH + hf * 16;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-            Frag af0, af1, bf0, bf1;
-            af0.u = *reinterpret_cast<const uint4*>(sa + kk * 32);
-            af1.u = *reinterpret_cast<const uint4*>(sa + 32 * PITCH + kk * 32);
-            bf0.u = *reinterpret_cast<const uint4*>(sb + kk * 32);
-            bf1.u = *reinterpret_cast<const uint4*>(sb + 32 * PITCH + kk * 32);
-            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf0.v, af0.v, acc[0][0], 0, 0, 0);
-            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf0.v, af1.v, acc[0][1], 0, 0, 0);
-            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf1.v, af0.v, acc[1][0], 0, 0, 0);
-            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf1.v, af1.v, acc[1][1], 0, 0, 0);
+            Frag af[TI], bf[TJ];
+#pragma unroll
+            for (int ti = 0; ti < TI; ++ti) af[ti].u = *reinterpret_cast<const uint4*>(sa + ti * 32 * PITCH + kk * 32);
+#pragma unroll
+            for (int tj = 0; tj < TJ; ++tj) bf[tj].u = *reinterpret_cast<const uint4*>(sb + tj * 32 * PITCH + kk * 32);
+#pragma unroll
+            for (int tj = 0; tj < TJ; ++tj)
+#pragma unroll
+                for (int ti = 0; ti < TI; ++ti)
+                    acc[tj][ti] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[tj].v, af[ti].v, acc[tj][ti], 0, 0, 0);
         }
         __syncthreads();
         if (more) stash(kc & 1);
@@ -367,26 +384,27 @@ __global__ __launch_bounds__(256, 2) void k_tm_mul(TmMulArgs p) {
 
     // t leaves as [i][channel][j]: the channels of a row i lie close together, which is what the LayerNorm over
     // the channels in k_tm_out reads (128 short segments inside half a megabyte instead of one per 8 MiB plane).
-    // A lane holds 8-byte pieces of 64 different rows i, rows that lie C Np elements apart: stored like that every
-    // instruction would touch 64 lines.  The wavefront's 64 x 64 tile is therefore gathered in LDS (free after the
+    // A lane holds 8-byte pieces of 32 TI different rows i, rows that lie C Np elements apart: stored like that every
+    // instruction would touch 64 lines.  The wavefront's tile is therefore gathered in LDS (free after the
     // last barrier of the loop; each wavefront uses its own part, and a wavefront's LDS operations complete in
-    // order) and leaves as 128-byte row segments, 16 bytes per lane.
+    // order) and leaves as row segments of 64 TJ bytes, 16 bytes per lane.
     {
-        unsigned char* s_o = smem + wave * (64 * PITCH);
+        static_assert(TJ == 2, "a row of the wavefront's tile is 64 elements: eight 16-byte pieces");
+        unsigned char* s_o = smem + wave * (32 * TI * PITCH);
 #pragma unroll
-        for (int ti = 0; ti < 2; ++ti)
+        for (int ti = 0; ti < TI; ++ti)
 #pragma unroll
-            for (int tj = 0; tj < 2; ++tj)
+            for (int tj = 0; tj < TJ; ++tj)
 #pragma unroll
                 for (int g = 0; g < 4; ++g)
                     *reinterpret_cast<uint2*>(s_o + (32 * ti + col) * PITCH + (32 * tj + 8 * g + 4 * hf) * 2) =
                         make_uint2(pack2(acc[tj][ti][4 * g], acc[tj][ti][4 * g + 1]), pack2(acc[tj][ti][4 * g + 2], acc[tj][ti][4 * g + 3]));
         bf16_t* xc = p.x + (size_t)ch * p.Np;
         const size_t xrow = (size_t)p.C * p.Np;
-        const int pcj = lane & 7, j = j0 + wj * 64 + pcj * 8;
+        const int pcj = lane & 7, j = j0 + wj * 32 * TJ + pcj * 8;
 #pragma unroll
-        for (int n = 0; n < 8; ++n) {
-            const int row = 8 * n + (lane >> 3), i = i0 + wi * 64 + row;
+        for (int n = 0; n < 4 * TI; ++n) {
+            const int row = 8 * n + (lane >> 3), i = i0 + wi * 32 * TI + row;
             const uint4 v = *reinterpret_cast<const uint4*>(s_o + row * PITCH + pcj * 16);
             if (i < p.N && j < p.Np) *reinterpret_cast<uint4*>(xc + (size_t)i * xrow + j) = v;
         }
@@ -608,13 +626,25 @@ ff_status trimul_run(const ff_trimul_desc& d, const ff_trimul_weights& w, const 
     }
     {
         TmMulArgs a{};
-        a.a = m.a; a.b = m.b; a.x = m.x; a.N = N; a.Np = Np; a.C = c; a.tiles = (N + 127) / 128;
-        const int blocks = 8 * ((c + 7) / 8) * a.tiles * a.tiles;
-        static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_tm_mul),
-                                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMulSmem);
-        if (attr != hipSuccess) return fail(FF_EHIP, "k_tm_mul: dynamic LDS limit: %s", hipGetErrorString(attr));
+        a.a = m.a; a.b = m.b; a.x = m.x; a.N = N; a.Np = Np; a.C = c;
+        hipError_t attr = hipSuccess;
         Timed t(KK_TM_MUL, st);
-        hipLaunchKernelGGL(k_tm_mul, dim3(blocks), dim3(256), kMulSmem, st, a);
+#define FF_TM_MUL(WI, WJ, TI, TJ)                                                                                \
+    do {                                                                                                         \
+        using Sh = tm::MulShape<WI, WJ, TI, TJ>;                                                                 \
+        static const hipError_t once = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_tm_mul<WI, WJ, TI, TJ>), \
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)Sh::SMEM); \
+        attr = once;                                                                                             \
+        a.tiles_i = (N + Sh::BI - 1) / Sh::BI;                                                                   \
+        a.tiles_j = (N + Sh::BJ - 1) / Sh::BJ;                                                                   \
+        const int blocks = 8 * ((c + 7) / 8) * a.tiles_i * a.tiles_j;                                            \
+        if (once == hipSuccess) hipLaunchKernelGGL((k_tm_mul<WI, WJ, TI, TJ>), dim3(blocks), dim3(Sh::NT), Sh::SMEM, st, a); \
+    } while (0)
+        // 256 x 256 block tiles once they fill the chip several times over (c channels x (N / 256)^2 blocks, one per CU)
+        if ((int64_t)c * ((N + 255) / 256) * ((N + 255) / 256) >= 4 * compute_units() && N % 256 == 0) FF_TM_MUL(2, 4, 4, 2);
+        else FF_TM_MUL(2, 2, 2, 2);
+#undef FF_TM_MUL
+        if (attr != hipSuccess) return fail(FF_EHIP, "k_tm_mul: dynamic LDS limit: %s", hipGetErrorString(attr));
     }
     {
         TmOutArgs a{};
