@@ -170,11 +170,14 @@ __global__ __launch_bounds__(512, 2) void k_tm_proj(TmProjArgs p) {
     float* s_S = reinterpret_cast<float*>(smem + (size_t)64 * p.ppb * PITCH);     // [64 ppb] row sums of the folded weights
     float* s_C = s_S + 64 * p.ppb;                                                // [64 ppb] offsets
     const int pr_first = blockIdx.y * p.ppb;
+    constexpr int OPITCH = 80;                          // bytes per channel row of a staged output half-tile [16][32]
 
     const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int tpr = p.Np >> 5;                          // token tiles per row
     const int tiles_m = p.N * tpr;
+    // the wavefront's own staging area (only it reads or writes there; its LDS operations complete in order)
+    unsigned char* s_o = reinterpret_cast<unsigned char*>(s_C + 64 * p.ppb) + wave * (16 * OPITCH);
 
     // The block's share of the folded weight matrix (all of it, at most 512 rows of 256 bytes, for large inputs;
     // a quarter for small ones, which need the blocks) stays in LDS for the life of the block, which works through
@@ -228,21 +231,31 @@ __global__ __launch_bounds__(512, 2) void k_tm_proj(TmProjArgs p) {
                 acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1.v, xa[s].v, acc1, 0, 0, 0);
             }
             const bool left = pr < p.G;
-            const int ch0 = 32 * (left ? pr : pr - p.G) + 4 * hf;
-            // a store instruction writes one channel row per half-wave: 32 consecutive positions, 64 contiguous bytes
-            bf16_t* dst = (left ? p.a : p.b) + (size_t)ch0 * plane + (size_t)r * p.Np + l;
+            const int ch0 = 32 * (left ? pr : pr - p.G);
+            // A lane holds ONE position of 16 channels, and the channel rows of a and b lie a whole plane apart:
+            // 16 channels at a time the results are turned in LDS into rows [channel][32 positions] and leave as
+            // 16-byte pieces, a store instruction writing 16 channel rows of 64 contiguous bytes (2-byte stores,
+            // one channel row per half-wave and instruction, took a quarter of the kernel's time).
+            bf16_t* dst = (left ? p.a : p.b) + (size_t)(ch0 + (lane >> 2)) * plane + (size_t)r * p.Np + l0 + 8 * (lane & 3);
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const float4 sp4 = *reinterpret_cast<const float4*>(s_S + 64 * pl + 8 * g + 4 * hf);
-                const float4 cp4 = *reinterpret_cast<const float4*>(s_C + 64 * pl + 8 * g + 4 * hf);
-                const float4 sg4 = *reinterpret_cast<const float4*>(s_S + 64 * pl + 32 + 8 * g + 4 * hf);
-                const float4 cg4 = *reinterpret_cast<const float4*>(s_C + 64 * pl + 32 + 8 * g + 4 * hf);
+            for (int hh = 0; hh < 2; ++hh) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float tp = rstd * (acc0[4 * g + e] - mean * pick(sp4, e)) + pick(cp4, e);
-                    const float tgv = rstd * (acc1[4 * g + e] - mean * pick(sg4, e)) + pick(cg4, e);
-                    dst[(size_t)(8 * g + e) * plane] = (bf16_t)(pack2(tp * sigmoid(tgv) * mval, 0.f) & 0xffffu);
+                for (int gg = 0; gg < 2; ++gg) {
+                    const int g = 2 * hh + gg;
+                    const float4 sp4 = *reinterpret_cast<const float4*>(s_S + 64 * pl + 8 * g + 4 * hf);
+                    const float4 cp4 = *reinterpret_cast<const float4*>(s_C + 64 * pl + 8 * g + 4 * hf);
+                    const float4 sg4 = *reinterpret_cast<const float4*>(s_S + 64 * pl + 32 + 8 * g + 4 * hf);
+                    const float4 cg4 = *reinterpret_cast<const float4*>(s_C + 64 * pl + 32 + 8 * g + 4 * hf);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float tp = rstd * (acc0[4 * g + e] - mean * pick(sp4, e)) + pick(cp4, e);
+                        const float tgv = rstd * (acc1[4 * g + e] - mean * pick(sg4, e)) + pick(cg4, e);
+                        *reinterpret_cast<bf16_t*>(s_o + (8 * gg + 4 * hf + e) * OPITCH + col * 2) =
+                            (bf16_t)(pack2(tp * sigmoid(tgv) * mval, 0.f) & 0xffffu);
+                    }
                 }
+                const uint4 v = *reinterpret_cast<const uint4*>(s_o + (lane >> 2) * OPITCH + (lane & 3) * 16);
+                *reinterpret_cast<uint4*>(dst + (size_t)(16 * hh) * plane) = v;
             }
         }
     }
@@ -608,7 +621,8 @@ ff_status trimul_run(const ff_trimul_desc& d, const ff_trimul_weights& w, const 
         const int per_cu = split;
         if (blocks > compute_units() * per_cu) blocks = compute_units() * per_cu;
         const dim3 grid(blocks, split);
-        auto smem = [&](int kc) { return (size_t)64 * a.ppb * (kc * 32 + 16) + (size_t)2 * 64 * a.ppb * 4; };
+        // weights, row sums and offsets, one staged output half-tile [16][32] per wavefront
+        auto smem = [&](int kc) { return (size_t)64 * a.ppb * (kc * 32 + 16) + (size_t)2 * 64 * a.ppb * 4 + (size_t)8 * 16 * 80; };
         hipError_t attr = hipSuccess;
         Timed t(KK_TM_PROJ, st);
 #define FF_TM_PROJ(KCV)                                                                                          \
