@@ -45,6 +45,13 @@ __device__ __forceinline__ uint32_t pack2(float a, float b) {   // a -> low half
     t[1] = (__bf16)b;
     return __builtin_bit_cast(uint32_t, t);
 }
+// After the call lanes of the lower half hold (a of lower lane, a of upper lane) and lanes of the upper half hold
+// (b of lower lane, b of upper lane)
+__device__ __forceinline__ void merge_halves(uint32_t& a, uint32_t& b) {
+    auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
+    a = r[0];
+    b = r[1];
+}
 __device__ __forceinline__ float lo_f32(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float hi_f32(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 __device__ __forceinline__ float sigmoid(float t) {
@@ -427,22 +434,25 @@ __global__ __launch_bounds__(64 * WI * WJ, 2) void k_tm_mul(TmMulArgs p) {
 // ====================================================================================
 // out[i][j][:] = g[i][j][:] * (LayerNorm_out(t[:, i, j]) W_o^T + b_o) (+ z[i][j][:]),
 // g[i][j][:] = sigmoid(LayerNorm_in(z[i][j][:]) W_g^T + b_g).
-// Block = 4 wavefronts, both folded weight matrices resident in LDS, each wavefront working through 32-token
+// Block = 8 wavefronts, both folded weight matrices resident in LDS, each wavefront working through 32-token
 // tiles (i, j0 .. j0 + 31); features x tokens on the matrix cores (the lane owns a token) for both GEMMs, so the
-// gate meets the projected value in the same lane and register.
+// gate meets the projected value in the same lane and register.  Results leave the accumulators as 8-byte pieces
+// of 32 different tokens; the output tile [32 tokens][cz], one contiguous block of out, is gathered in the
+// wavefront's own LDS area and stored 16 bytes per lane.
 struct TmOutArgs {
     const bf16_t* x;         // [N][C][Np]
     const bf16_t* z;         // [N*N][cz]
     bf16_t* out;             // [N*N][cz]; may be z itself when residual
     int residual;
     int N, Np, C, cz;
+    int wave_bytes;          // LDS area of a wavefront: 32 * (2 cz + 16)
     float eps;
     const bf16_t *wp, *wg;   // [cz][16 KC], [cz][16 KZ]
     const float *S, *Cn, *Sg, *Cg;
 };
 
 template <int KC, int KZ>
-__global__ __launch_bounds__(256) void k_tm_out(TmOutArgs p) {
+__global__ __launch_bounds__(512) void k_tm_out(TmOutArgs p) {
     constexpr int PC = KC * 32 + 16, PZ = KZ * 32 + 16;     // bytes per weight row in LDS (padded: conflict-free operand reads)
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     unsigned char* s_wo = smem;                             // [cz][PC]
@@ -450,37 +460,42 @@ __global__ __launch_bounds__(256) void k_tm_out(TmOutArgs p) {
     float* s_k = reinterpret_cast<float*>(s_wg + (size_t)p.cz * PZ);   // [4][cz]: S, Cn, Sg, Cg
     const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    for (int id = tid; id < p.cz; id += 256) {
+    // (only this wavefront reads or writes its area; a wavefront's LDS operations complete in order)
+    unsigned char* s_x = reinterpret_cast<unsigned char*>(s_k + 4 * p.cz) + (size_t)wave * p.wave_bytes;
+    const int tpr = p.Np >> 5, tiles_m = p.N * tpr, n_ft = p.cz >> 5, nwaves = gridDim.x * 8;
+    const int PO = 2 * p.cz + 16;                           // bytes per token row of the staged output tile
+    int t = blockIdx.x * 8 + wave;
+
+    for (int id = tid; id < p.cz; id += 512) {
         s_k[id] = p.S[id];
         s_k[p.cz + id] = p.Cn[id];
         s_k[2 * p.cz + id] = p.Sg[id];
         s_k[3 * p.cz + id] = p.Cg[id];
     }
-    for (int id = tid; id < p.cz * 2 * KC; id += 256) {
+    for (int id = tid; id < p.cz * 2 * KC; id += 512) {
         const int row = id / (2 * KC), pc = id - row * (2 * KC);
         *reinterpret_cast<uint4*>(s_wo + row * PC + pc * 16) = *reinterpret_cast<const uint4*>(p.wp + (size_t)row * (16 * KC) + pc * 8);
     }
-    for (int id = tid; id < p.cz * 2 * KZ; id += 256) {
+    for (int id = tid; id < p.cz * 2 * KZ; id += 512) {
         const int row = id / (2 * KZ), pc = id - row * (2 * KZ);
         *reinterpret_cast<uint4*>(s_wg + row * PZ + pc * 16) = *reinterpret_cast<const uint4*>(p.wg + (size_t)row * (16 * KZ) + pc * 8);
     }
-    __syncthreads();
+    __syncthreads();                                        // (the only barrier)
 
-    const int tpr = p.Np >> 5, tiles_m = p.N * tpr, n_ft = p.cz >> 5;
-    for (int t = blockIdx.x * 4 + wave; t < tiles_m; t += gridDim.x * 4) {
-        const int i = t / tpr, j0 = (t - i * tpr) * 32, j = j0 + col;       // j < Np
-        const bool valid = j < p.N;
-        const size_t tok = (size_t)i * p.N + (valid ? j : 0);
+    for (; t < tiles_m; t += nwaves) {
+        const int i = t / tpr, j0 = (t - i * tpr) * 32;
         Frag za[KZ], xa[KC];
         {
-            const bf16_t* zp = p.z + tok * p.cz;
+            const int j = j0 + col;
+            const bf16_t* zp = p.z + ((size_t)i * p.N + (j < p.N ? j : 0)) * p.cz;
 #pragma unroll
             for (int s = 0; s < KZ; ++s) {
                 za[s].u = make_uint4(0, 0, 0, 0);
                 if (16 * s + 8 * hf < p.cz) za[s].u = *reinterpret_cast<const uint4*>(zp + 16 * s + 8 * hf);
             }
             // t is [i][channel][j]: the eight channels of an operand fragment are eight 2-byte loads, each of
-            // them 64 contiguous bytes across the half-wave
+            // them 64 contiguous bytes across the half-wave (turning the tile in LDS instead, 16-byte loads and
+            // 2-byte LDS reads, measured the same)
             const bf16_t* xp = p.x + (size_t)i * p.C * p.Np + j;
 #pragma unroll
             for (int s = 0; s < KC; ++s) {
@@ -496,8 +511,15 @@ __global__ __launch_bounds__(256) void k_tm_out(TmOutArgs p) {
         float mean_z, rstd_z, mean, rstd;
         token_stats<KZ>(za, p.cz, hf, p.eps, mean_z, rstd_z);
         token_stats<KC>(xa, p.C, hf, p.eps, mean, rstd);
+        // (the row sums and offsets are the same for every tile; read through an offset the compiler cannot see
+        // through, or it keeps all 4 cz of them in registers across the tile loop)
+        int kofs = 0;
+        asm volatile("" : "+v"(kofs));
+        const float* s_kt = s_k + kofs;
 
-        for (int ft = 0; ft < n_ft; ++ft) {
+#pragma unroll
+        for (int ft = 0; ft < KZ / 2; ++ft) {               // (unrolled: the residual below picks registers by ft)
+            if (ft >= n_ft) break;
             f32x16 acc, accg;
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[v] = accg[v] = 0.f;
@@ -518,10 +540,10 @@ __global__ __launch_bounds__(256) void k_tm_out(TmOutArgs p) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int f0 = ft * 32 + 8 * g + 4 * hf;
-                const float4 s4 = *reinterpret_cast<const float4*>(s_k + f0);
-                const float4 c4 = *reinterpret_cast<const float4*>(s_k + p.cz + f0);
-                const float4 sg4 = *reinterpret_cast<const float4*>(s_k + 2 * p.cz + f0);
-                const float4 cg4 = *reinterpret_cast<const float4*>(s_k + 3 * p.cz + f0);
+                const float4 s4 = *reinterpret_cast<const float4*>(s_kt + f0);
+                const float4 c4 = *reinterpret_cast<const float4*>(s_kt + p.cz + f0);
+                const float4 sg4 = *reinterpret_cast<const float4*>(s_kt + 2 * p.cz + f0);
+                const float4 cg4 = *reinterpret_cast<const float4*>(s_kt + 3 * p.cz + f0);
                 float o[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -530,12 +552,31 @@ __global__ __launch_bounds__(256) void k_tm_out(TmOutArgs p) {
                     o[e] = lin * gate;
                 }
                 if (p.residual) {
-                    // (the token's row of z again, eight bytes that are in the cache; this lane alone stores these
-                    // elements, after every lane of the wavefront has read its fragments of the row, so out may be z itself)
-                    const uint2 rs = *reinterpret_cast<const uint2*>(p.z + tok * p.cz + f0);
-                    o[0] += lo_f32(rs.x); o[1] += hi_f32(rs.x); o[2] += lo_f32(rs.y); o[3] += hi_f32(rs.y);
+                    // z[token][f0 .. f0 + 3] is in the registers of the token's two lanes: channels 16 s + 8 h' + u of
+                    // fragment s belong to half h'; the lane wants words 2 hf, 2 hf + 1 of fragment 2 ft + g / 2 of half
+                    // g % 2, its own or the other half's (one exchange per fragment word serves both halves)
+                    const int sz = 2 * ft + (g >> 1);        // (a constant: the loop over ft is unrolled)
+                    uint32_t a0 = za[sz].w[0], b0 = za[sz].w[2], a1 = za[sz].w[1], b1 = za[sz].w[3];
+                    merge_halves(a0, b0);
+                    merge_halves(a1, b1);
+                    const uint32_t r0 = (g & 1) ? b0 : a0, r1 = (g & 1) ? b1 : a1;
+                    o[0] += lo_f32(r0); o[1] += hi_f32(r0); o[2] += lo_f32(r1); o[3] += hi_f32(r1);
                 }
-                if (valid) *reinterpret_cast<uint2*>(p.out + tok * p.cz + f0) = make_uint2(pack2(o[0], o[1]), pack2(o[2], o[3]));
+                *reinterpret_cast<uint2*>(s_x + col * PO + f0 * 2) = make_uint2(pack2(o[0], o[1]), pack2(o[2], o[3]));
+            }
+            __builtin_amdgcn_sched_barrier(0);              // (keeps the next feature tile's weight reads out of this one: registers)
+        }
+        // the tile is 32 cz contiguous elements of out (tokens j0 .. j0 + 31 of row i): 16 bytes per lane
+        {
+            const int ppr = p.cz >> 3;                      // 16-byte pieces per token
+            unsigned char* ob = reinterpret_cast<unsigned char*>(p.out + ((size_t)i * p.N + j0) * p.cz);
+#pragma unroll
+            for (int n = 0; n < KZ; ++n) {
+                const int id = lane + 64 * n, row = id / ppr, pc = id - row * ppr;
+                if (id < 32 * ppr) {
+                    const uint4 v = *reinterpret_cast<const uint4*>(s_x + row * PO + pc * 16);
+                    if (j0 + row < p.N) *reinterpret_cast<uint4*>(ob + (size_t)id * 16) = v;
+                }
             }
         }
     }
@@ -666,18 +707,19 @@ ff_status trimul_run(const ff_trimul_desc& d, const ff_trimul_weights& w, const 
         a.N = N; a.Np = Np; a.C = c; a.cz = cz; a.eps = d.ln_eps;
         a.wp = m.wp3; a.wg = m.wp4; a.S = m.S3; a.Cn = m.C3; a.Sg = m.S4; a.Cg = m.C4;
         const int tiles_m = N * (Np / 32);
-        int blocks = (tiles_m + 3) / 4;
-        if (blocks > 512) blocks = 512;                 // two blocks per compute unit, each working through its share of the tiles
+        int blocks = (tiles_m + 7) / 8;
+        if (blocks > compute_units()) blocks = compute_units();     // one block of eight wavefronts per compute unit
         const dim3 grid(blocks);
-        const size_t smem = (size_t)cz * (kc3 * 32 + 16) + (size_t)cz * (kc1 * 32 + 16) + (size_t)4 * cz * 4;
+        a.wave_bytes = 32 * (2 * cz + 16);
+        const size_t smem = (size_t)cz * (kc3 * 32 + 16) + (size_t)cz * (kc1 * 32 + 16) + (size_t)4 * cz * 4 + (size_t)8 * a.wave_bytes;
         hipError_t attr = hipSuccess;
         Timed t(KK_TM_OUT, st);
 #define FF_TM_OUT(KCV, KZV)                                                                                          \
     do {                                                                                                             \
         static const hipError_t once = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_tm_out<KCV, KZV>),      \
-                                                           hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);  \
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024); \
         attr = once;                                                                                                 \
-        if (once == hipSuccess) hipLaunchKernelGGL((k_tm_out<KCV, KZV>), grid, dim3(256), smem, st, a);             \
+        if (once == hipSuccess) hipLaunchKernelGGL((k_tm_out<KCV, KZV>), grid, dim3(512), smem, st, a);             \
     } while (0)
 #define FF_TM_OUT_Z(KCV)              \
     do {                              \
