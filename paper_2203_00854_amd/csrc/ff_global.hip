@@ -9,17 +9,19 @@
 // out bound it (HBM).  Four launches:
 //   k_gca_prep     folds the LayerNorm gain into the weights (W' = bf16(W * gamma), C = W beta (+ bias)) and
 //                  writes W_o in the operand order of the last contraction
-//   k_gca_kv       one wavefront per (column, up to 256 sequences): 32 sequences at a time it normalises the tokens
-//                  into bf16 operand fragments (masked ones as zeros) and contracts them with W_q' (tokens x
-//                  features, so that the sum over the tile's sequences - the query average - is a sum over the
-//                  lane's own registers) and with W_k' | W_v' (features x tokens: k, v of a token leave as
-//                  float32); partial query sums and counts go to the workspace
+//   k_gca_kv       one block per (32 residues, group of sequences), its four wavefronts each a range of consecutive
+//                  sequences: a tile = the 32 c contiguous elements of one sequence's residues, normalised into
+//                  bf16 operand fragments (masked tokens as zeros) and contracted with W_q' (tokens x features,
+//                  never cleared between sequences: the accumulator IS the sum over the sequences, the query
+//                  average's numerator) and with W_k' | W_v' (features x tokens: k, v of a token leave as bf16,
+//                  four sequences at a time through LDS so that kv[residue][sequence] is written in whole lines);
+//                  partial query sums and counts go to the workspace
 //   k_gca_softmax  one block per column, a thread per sequence with all heads in registers: q from the partial
 //                  sums, one sweep over k and v (running maximum per thread, exponentials, denominators,
 //                  weighted sums of v), o[i] normalised
-//   k_gca_out      one wavefront per (sequence, 32 residues): gate GEMM, sigmoid, times o[i] (the gated tile is
-//                  already the B operand of the output GEMM because W_o was stored in the matching order),
-//                  output GEMM, + b_o
+//   k_gca_out      a wavefront keeps one tile of 32 residues and walks over the sequences (o[i] read once): gate
+//                  GEMM, sigmoid, times o[i] (the gated tile is already the B operand of the output GEMM because
+//                  W_o was stored in the matching order), output GEMM, + b_o, the output tile through LDS
 // Operand layouts of v_mfma_f32_32x32x16_bf16 as in ff_trimul.hip.
 #include "ff_common.h"
 
@@ -51,14 +53,13 @@ __device__ __forceinline__ float pick(const float4& q, int e) { return e == 0 ? 
 
 static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-// Sequences per wavefront of k_gca_kv (a multiple of 32): 256, or fewer while that leaves fewer than four
-// wavefronts per SIMD (a wavefront walks its sequences one 32-tile after the other)
-static int chunk_for(int n_seq, int n_res) {
-    int chunk = 256;
-    while (chunk > 32 && (int64_t)n_res * ((n_seq + chunk - 1) / chunk) < 4096) chunk >>= 1;
-    return chunk;
+// Blocks per residue tile of k_gca_kv (four wavefronts each, every wavefront a range of consecutive sequences): also
+// the number of partial query sums per residue that k_gca_softmax adds up.  Enough blocks for three per compute
+// unit at the paper's shapes, at least four sequences per wavefront.
+static int kv_groups(int n_seq) {
+    int g = n_seq / 16;
+    return g < 1 ? 1 : (g > 64 ? 64 : g);
 }
-
 // Normalised operand fragments of the lane's token: xn = bf16((x - mean) * rstd) (the LayerNorm gain and
 // offset live in the folded weights), or zeros if !keep.  Two passes over the registers for the statistics.
 template <int KC>
@@ -153,49 +154,50 @@ __global__ __launch_bounds__(256) void k_gca_prep(PrepArgs a) {
 struct KvArgs {
     const bf16_t* m;         // [S][R][c]
     const float* mask;       // [S][R] or NULL
-    int S, R, c, Hd, d, nchunk, chunk;
+    int S, R, c, Hd, d, groups;
     float eps;
     const bf16_t *wq, *wkv;  // folded, pitch 16 KC
     const float* Ckv;
-    float* kv;               // [R][S][2d]: k then v of a token, float32
-    float* qpart;            // [R][nchunk][Hd]
-    float* cntpart;          // [R][nchunk]
+    bf16_t* kv;              // [R][S][2d]: k then v of a token
+    float* qpart;            // [R][groups][Hd]
+    float* cntpart;          // [R][groups]
 };
 
+// Block = one residue tile (32 residues) and one group of sequences; its four wavefronts walk over the sequences
+// s = 4 group + wave, + 4 groups, ...: a tile is 32 c contiguous elements of m (the tokens of the next sequence are
+// requested before this one is worked on), and k | v of its 32 tokens 32 x 2d contiguous elements of kv.  The query
+// sums need no arithmetic of their own: the accumulator of the tokens x features contraction with W_q' simply is
+// not cleared between sequences (lane = feature, register = residue).  At the end the block adds the four
+// wavefronts' sums in LDS and writes one partial sum per residue and feature.
 template <int KC, int D>
 __global__ __launch_bounds__(256) void k_gca_kv(KvArgs p) {
     constexpr int PITCH = KC * 32 + 16;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     unsigned char* s_wq = smem;                                  // [Hd][PITCH]
     unsigned char* s_wkv = smem + (size_t)p.Hd * PITCH;          // [32][PITCH]
+    float* s_red = reinterpret_cast<float*>(s_wkv + 32 * PITCH); // [4][32][Hd + 1]: the wavefronts' query sums and counts
     const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    for (int id = tid; id < (p.Hd + 32) * 2 * KC; id += 256) {
-        const int row = id / (2 * KC), pc = id - row * (2 * KC);
-        const bf16_t* src = row < p.Hd ? p.wq + (size_t)row * (16 * KC) : p.wkv + (size_t)(row - p.Hd) * (16 * KC);
-        *reinterpret_cast<uint4*>(smem + row * PITCH + pc * 16) = *reinterpret_cast<const uint4*>(src + pc * 8);
-    }
-    __syncthreads();
+    const int tpr = (p.R + 31) >> 5;
+    const int rt = blockIdx.x % tpr, grp = blockIdx.x / tpr;
+    const int per = (p.S + 4 * p.groups - 1) / (4 * p.groups);       // consecutive sequences per wavefront
+    const int s_lo = (4 * grp + wave) * per, s_hi = s_lo + per < p.S ? s_lo + per : p.S;
+    const int i_raw = rt * 32 + col;
+    const bool valid = i_raw < p.R;
+    const int i = valid ? i_raw : p.R - 1;
+    constexpr int REC = 4 * D, BP = 4 * REC + 16;  // bytes of a token's k | v; bytes per residue row of the batch in LDS
+    // k | v of four consecutive sequences are gathered per residue in the wavefront's own LDS area and leave as whole
+    // 128-byte (d = 8) runs of kv[residue][sequence]: stored straight from the accumulators they would be 8-byte
+    // pieces of 32 different lines per instruction (only this wavefront touches the area; its LDS operations
+    // complete in order)
+    unsigned char* s_b = smem + (size_t)(p.Hd + 32) * PITCH + (size_t)4 * 32 * (p.Hd + 1) * 4 + (size_t)wave * 32 * BP;
 
-    const int task = blockIdx.x * 4 + wave;
-    if (task >= p.R * p.nchunk) return;          // (no barrier after this point)
-    const int i = task / p.nchunk, ck = task - i * p.nchunk;
-    const int s_begin = ck * p.chunk;
-    int s_end = s_begin + p.chunk;
-    if (s_end > p.S) s_end = p.S;
-    const int n_qt = p.Hd >> 5;                  // 32-feature tiles of the query projection (at most 4)
-    float qacc0 = 0.f, qacc1 = 0.f, qacc2 = 0.f, qacc3 = 0.f;
-    float cnt = 0.f;
-    // offsets of the lane's key / value rows (read once: a load inside the loop would wait for the stores before it)
-    const float4 ckv0 = *reinterpret_cast<const float4*>(p.Ckv + 4 * hf), ckv1 = *reinterpret_cast<const float4*>(p.Ckv + 8 + 4 * hf);
-    const float4 ckv2 = *reinterpret_cast<const float4*>(p.Ckv + 16 + 4 * hf), ckv3 = *reinterpret_cast<const float4*>(p.Ckv + 24 + 4 * hf);
-
-    // the tokens and mask entries of the next 32 sequences are requested before this tile is worked on
+    // the first tokens are requested before the weights are copied: both are on their way together
     Frag xn[KC];
     float mkn = 1.f;
     {
-        const int s = s_begin + col;
-        const size_t tok = (size_t)(s < s_end ? s : s_begin) * p.R + i;
+        const int s0 = s_lo < p.S ? s_lo : 0;
+        const size_t tok = (size_t)s0 * p.R + i;
         const bf16_t* mp = p.m + tok * p.c;
 #pragma unroll
         for (int q = 0; q < KC; ++q) {
@@ -204,16 +206,32 @@ __global__ __launch_bounds__(256) void k_gca_kv(KvArgs p) {
         }
         if (p.mask) mkn = p.mask[tok];
     }
-    for (int s0 = s_begin; s0 < s_end; s0 += 32) {
-        const int s = s0 + col;
-        const bool valid = s < s_end;
+    for (int id = tid; id < (p.Hd + 32) * 2 * KC; id += 256) {
+        const int row = id / (2 * KC), pc = id - row * (2 * KC);
+        const bf16_t* src = row < p.Hd ? p.wq + (size_t)row * (16 * KC) : p.wkv + (size_t)(row - p.Hd) * (16 * KC);
+        *reinterpret_cast<uint4*>(smem + row * PITCH + pc * 16) = *reinterpret_cast<const uint4*>(src + pc * 8);
+    }
+    __syncthreads();
+
+    const int n_qt = p.Hd >> 5;                  // 32-feature tiles of the query projection (at most 4)
+    f32x16 qacc[4];                              // tokens x features, summed over the wavefront's sequences
+#pragma unroll
+    for (int T = 0; T < 4; ++T)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) qacc[T][v] = 0.f;
+    float cnt = 0.f;                             // unmasked sequences of the lane's residue
+    // offsets of the lane's key / value rows (read once)
+    const float4 ckv0 = *reinterpret_cast<const float4*>(p.Ckv + 4 * hf), ckv1 = *reinterpret_cast<const float4*>(p.Ckv + 8 + 4 * hf);
+    const float4 ckv2 = *reinterpret_cast<const float4*>(p.Ckv + 16 + 4 * hf), ckv3 = *reinterpret_cast<const float4*>(p.Ckv + 24 + 4 * hf);
+
+    for (int s = s_lo; s < s_hi; ++s) {
         Frag xa[KC];
 #pragma unroll
         for (int q = 0; q < KC; ++q) xa[q].u = xn[q].u;
         const bool keep = valid && mkn != 0.f;
         {
-            const int sn = s + 32;                         // (beyond the chunk: the chunk's first token again, unused)
-            const size_t tok = (size_t)(sn < s_end ? sn : s_begin) * p.R + i;
+            const int sn = s + 1 < s_hi ? s + 1 : s;               // (the last round asks for its own tokens again)
+            const size_t tok = (size_t)sn * p.R + i;
             const bf16_t* mp = p.m + tok * p.c;
 #pragma unroll
             for (int q = 0; q < KC; ++q)
@@ -221,28 +239,16 @@ __global__ __launch_bounds__(256) void k_gca_kv(KvArgs p) {
             if (p.mask) mkn = p.mask[tok];
         }
         normalise<KC>(xa, p.c, hf, p.eps, keep);
-        cnt += (float)__builtin_popcountll(__ballot(keep && hf == 0));
-
-        // query sums: tokens x features, the lane owns a feature and its 16 registers are 16 of the tile's sequences
+        cnt += keep ? 1.f : 0.f;
 #pragma unroll
         for (int T = 0; T < 4; ++T) {
             if (T < n_qt) {
-                f32x16 acc;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[v] = 0.f;
 #pragma unroll
                 for (int q = 0; q < KC; ++q) {
                     Frag wf;
                     wf.u = *reinterpret_cast<const uint4*>(s_wq + (32 * T + col) * PITCH + (2 * q + hf) * 16);
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[q].v, wf.v, acc, 0, 0, 0);
+                    qacc[T] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[q].v, wf.v, qacc[T], 0, 0, 0);
                 }
-                float t = 0.f;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) t += acc[v];
-                if (T == 0) qacc0 += t;
-                else if (T == 1) qacc1 += t;
-                else if (T == 2) qacc2 += t;
-                else qacc3 += t;
             }
         }
         // keys and values: features x tokens, the lane owns a token; rows 0 .. D-1 keys, 16 .. 16+D-1 values
@@ -256,7 +262,7 @@ __global__ __launch_bounds__(256) void k_gca_kv(KvArgs p) {
                 wf.u = *reinterpret_cast<const uint4*>(s_wkv + col * PITCH + (2 * q + hf) * 16);
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf.v, xa[q].v, acc, 0, 0, 0);
             }
-            float* dst = p.kv + ((size_t)i * p.S + (valid ? s : s_begin)) * (2 * D);
+            const int b = (s - s_lo) & 3;
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int row = 8 * g + 4 * hf;                  // rows row .. row + 3 of the tile
@@ -264,29 +270,47 @@ __global__ __launch_bounds__(256) void k_gca_kv(KvArgs p) {
                 const int e0 = is_v ? row - 16 : row;            // first key / value channel of the group
                 if (e0 < D) {
                     const float4 c4 = g == 0 ? ckv0 : (g == 1 ? ckv1 : (g == 2 ? ckv2 : ckv3));
-                    const float4 o = make_float4(acc[4 * g] + c4.x, acc[4 * g + 1] + c4.y, acc[4 * g + 2] + c4.z, acc[4 * g + 3] + c4.w);
-                    if (valid) *reinterpret_cast<float4*>(dst + (is_v ? D : 0) + e0) = o;
+                    *reinterpret_cast<uint2*>(s_b + col * BP + b * REC + ((is_v ? D : 0) + e0) * 2) =
+                        make_uint2(pack2(acc[4 * g] + c4.x, acc[4 * g + 1] + c4.y), pack2(acc[4 * g + 2] + c4.z, acc[4 * g + 3] + c4.w));
+                }
+            }
+            if (b == 3 || s + 1 == s_hi) {
+                // nb sequences s - b .. s of 32 residues: 16-byte pieces, a residue's nb records are contiguous in kv
+                const int ppr = (b + 1) * (REC / 16);            // pieces per residue
+                unsigned char* kvb = reinterpret_cast<unsigned char*>(p.kv) + ((size_t)(rt * 32) * p.S + (s - b)) * REC;
+                for (int id = lane; id < 32 * ppr; id += 64) {
+                    const int r = id / ppr, pc = id - r * ppr;
+                    const uint4 v = *reinterpret_cast<const uint4*>(s_b + r * BP + pc * 16);
+                    if (rt * 32 + r < p.R) *reinterpret_cast<uint4*>(kvb + (size_t)r * p.S * REC + pc * 16) = v;
                 }
             }
         }
     }
-    qacc0 += __shfl_xor(qacc0, 32, 64);
-    qacc1 += __shfl_xor(qacc1, 32, 64);
-    qacc2 += __shfl_xor(qacc2, 32, 64);
-    qacc3 += __shfl_xor(qacc3, 32, 64);
-    if (hf == 0) {
-        float* qp = p.qpart + (size_t)task * p.Hd + col;
-        qp[0] = qacc0;
-        if (n_qt > 1) qp[32] = qacc1;
-        if (n_qt > 2) qp[64] = qacc2;
-        if (n_qt > 3) qp[96] = qacc3;
+    // the block's partial sums: wavefront w leaves [residue][feature] (and the count in column Hd) in its part of LDS
+    const int RP = p.Hd + 1;
+    float* red = s_red + (size_t)wave * 32 * RP;
+#pragma unroll
+    for (int T = 0; T < 4; ++T)
+        if (T < n_qt) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) red[(8 * (v >> 2) + 4 * hf + (v & 3)) * RP + 32 * T + col] = qacc[T][v];
+        }
+    if (hf == 0) red[col * RP + p.Hd] = cnt;
+    __syncthreads();
+    for (int id = tid; id < 32 * RP; id += 256) {
+        const int r = id / RP, f = id - r * RP;
+        const float t = s_red[id] + s_red[32 * RP + id] + s_red[2 * 32 * RP + id] + s_red[3 * 32 * RP + id];
+        const int ir = rt * 32 + r;
+        if (ir < p.R) {
+            if (f < p.Hd) p.qpart[((size_t)ir * p.groups + grp) * p.Hd + f] = t;
+            else p.cntpart[(size_t)ir * p.groups + grp] = t;
+        }
     }
-    if (lane == 0) p.cntpart[task] = cnt;
 }
 
 // ====================================================================================
 struct SmArgs {
-    const float* kv;         // [R][S][2d]
+    const bf16_t* kv;        // [R][S][2d]
     const float* mask;       // [S][R] or NULL
     const float *qpart, *cntpart, *Cq;
     float* o;                // [R][Hd]
@@ -333,7 +357,8 @@ template <int H, int D, int NT>
 __global__ __launch_bounds__(NT) void k_gca_softmax(SmArgs p) {
     constexpr int HD = H * D, NW = NT / 64, PW = HD + 2 * H;
     __shared__ float s_q[HD];
-    __shared__ float s_red[NW * PW > NT ? NW * PW : NT];   // per wavefront: weighted sums, denominators, maxima (first: query partial sums)
+    __shared__ float s_red[NW * PW];              // per wavefront: weighted sums, denominators, maxima
+    __shared__ __attribute__((aligned(16))) float s_part[4 * NT];   // the threads' partial query sums
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, i = blockIdx.x;
     // partial counts and query sums of the column's chunks: spread over the lanes / the threads so that the loads
     // do not queue behind each other (a column of 5120 sequences has 20 chunks)
@@ -345,21 +370,35 @@ __global__ __launch_bounds__(NT) void k_gca_softmax(SmArgs p) {
         return;
     }
     {
-        constexpr int G = NT / HD;                 // threads per feature
-        const int f = tid % HD, g = tid / HD;
-        float q = 0.f;
-        for (int j = g; j < p.nchunk; j += G) q += p.qpart[((size_t)i * p.nchunk + j) * HD + f];
-        s_red[g * HD + f] = q;
+        // the column's partial query sums [groups][HD], contiguous: 16 bytes per thread and step, four steps'
+        // loads in flight together; a thread always meets the same four features, threads tid % (HD / 4) apart
+        // share them and are added up through LDS
+        constexpr int QP = HD / 4, G = NT / QP;    // 16-byte pieces per partial sum; threads per piece
+        const float4* qp = reinterpret_cast<const float4*>(p.qpart + (size_t)i * p.nchunk * HD);
+        const int n = p.nchunk * QP;
+        float4 q = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int id = tid; id < n; id += 4 * NT) {
+            float4 t0 = make_float4(0.f, 0.f, 0.f, 0.f), t1 = t0, t2 = t0, t3 = t0;
+            t0 = qp[id];
+            if (id + NT < n) t1 = qp[id + NT];
+            if (id + 2 * NT < n) t2 = qp[id + 2 * NT];
+            if (id + 3 * NT < n) t3 = qp[id + 3 * NT];
+            q.x += (t0.x + t1.x) + (t2.x + t3.x); q.y += (t0.y + t1.y) + (t2.y + t3.y);
+            q.z += (t0.z + t1.z) + (t2.z + t3.z); q.w += (t0.w + t1.w) + (t2.w + t3.w);
+        }
+        static_assert(NT % QP == 0, "whole groups of threads per piece");
+        float4* s_q4 = reinterpret_cast<float4*>(s_part);
+        s_q4[tid] = q;                              // [G][QP] pieces
         __syncthreads();
         if (tid < HD) {
             float t = 0.f;
 #pragma unroll
-            for (int gg = 0; gg < G; ++gg) t += s_red[gg * HD + tid];
+            for (int gg = 0; gg < G; ++gg) t += s_part[(gg * QP + (tid >> 2)) * 4 + (tid & 3)];
             s_q[tid] = (t / cnt + p.Cq[tid]) * p.qscale;
         }
     }
     __syncthreads();
-    const float* kvc = p.kv + (size_t)i * p.S * (2 * D);
+    const bf16_t* kvc = p.kv + (size_t)i * p.S * (2 * D);
 
     float mx[H], den[H], o[HD];
 #pragma unroll
@@ -369,19 +408,20 @@ __global__ __launch_bounds__(NT) void k_gca_softmax(SmArgs p) {
     // U sequences at a time: their loads (k, v and the mask entry, none of which depends on another) are all in
     // flight before the first is used; k and v of a masked sequence exist (finite) and are simply not used
     constexpr int U = 64 / (2 * D);
+    static_assert(D % 8 == 0, "k and v of a token are read in 16-byte pieces");
     for (int s0 = tid; s0 < p.S; s0 += U * NT) {
-        float4 kv4[U][2 * D / 4];
+        uint4 kv4[U][2 * D / 8];
         float mk[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int s = s0 + u * NT;
             mk[u] = 0.f;
 #pragma unroll
-            for (int e4 = 0; e4 < 2 * D / 4; ++e4) kv4[u][e4] = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int e8 = 0; e8 < 2 * D / 8; ++e8) kv4[u][e8] = make_uint4(0, 0, 0, 0);
             if (s < p.S) {
-                const float4* kp = reinterpret_cast<const float4*>(kvc + (size_t)s * (2 * D));
+                const uint4* kp = reinterpret_cast<const uint4*>(kvc + (size_t)s * (2 * D));
 #pragma unroll
-                for (int e4 = 0; e4 < 2 * D / 4; ++e4) kv4[u][e4] = kp[e4];
+                for (int e8 = 0; e8 < 2 * D / 8; ++e8) kv4[u][e8] = kp[e8];
                 mk[u] = 1.f;
                 if (p.mask) mk[u] = p.mask[(size_t)s * p.R + i];
             }
@@ -391,10 +431,14 @@ __global__ __launch_bounds__(NT) void k_gca_softmax(SmArgs p) {
             if (mk[u] == 0.f) continue;
             float k[D], v[D];
 #pragma unroll
-            for (int e4 = 0; e4 < D / 4; ++e4) {
-                const float4 k4 = kv4[u][e4], v4 = kv4[u][D / 4 + e4];
-                k[4 * e4] = k4.x; k[4 * e4 + 1] = k4.y; k[4 * e4 + 2] = k4.z; k[4 * e4 + 3] = k4.w;
-                v[4 * e4] = v4.x; v[4 * e4 + 1] = v4.y; v[4 * e4 + 2] = v4.z; v[4 * e4 + 3] = v4.w;
+            for (int e8 = 0; e8 < D / 8; ++e8) {
+                const uint4 k8 = kv4[u][e8], v8 = kv4[u][D / 8 + e8];
+                const uint32_t kw[4] = {k8.x, k8.y, k8.z, k8.w}, vw[4] = {v8.x, v8.y, v8.z, v8.w};
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    k[8 * e8 + 2 * w] = lo_f32(kw[w]); k[8 * e8 + 2 * w + 1] = hi_f32(kw[w]);
+                    v[8 * e8 + 2 * w] = lo_f32(vw[w]); v[8 * e8 + 2 * w + 1] = hi_f32(vw[w]);
+                }
             }
 #pragma unroll
             for (int h = 0; h < H; ++h) {
@@ -605,15 +649,15 @@ __global__ __launch_bounds__(256) void k_gca_out(OutArgs p) {
 
 // ====================================================================================
 struct Ws {
-    bf16_t *wq, *wkv, *wg, *wo;
-    float *Cq, *Ckv, *Cg, *Co, *kv, *qpart, *cntpart, *o;
+    bf16_t *wq, *wkv, *wg, *wo, *kv;
+    float *Cq, *Ckv, *Cg, *Co, *qpart, *cntpart, *o;
     size_t total;
 };
 
 static int kc_for(int K) { return K <= 32 ? 2 : (K <= 64 ? 4 : 8); }
 
 static Ws carve(const ff_global_desc& d, void* base) {
-    const int Hd = d.heads * d.head_dim, Kp = 16 * kc_for(d.c), chunk = chunk_for(d.n_seq, d.n_res), nchunk = (d.n_seq + chunk - 1) / chunk;
+    const int Hd = d.heads * d.head_dim, Kp = 16 * kc_for(d.c), groups = kv_groups(d.n_seq);
     char* b = (char*)base;
     size_t off = 0;
     auto take = [&](size_t bytes) {
@@ -630,9 +674,9 @@ static Ws carve(const ff_global_desc& d, void* base) {
     w.Ckv = (float*)take(32 * 4);
     w.Cg = (float*)take((size_t)Hd * 4);
     w.Co = (float*)take((size_t)d.c * 4);
-    w.kv = (float*)take((size_t)d.n_res * d.n_seq * 2 * d.head_dim * 4);
-    w.qpart = (float*)take((size_t)d.n_res * nchunk * Hd * 4);
-    w.cntpart = (float*)take((size_t)d.n_res * nchunk * 4);
+    w.kv = (bf16_t*)take((size_t)d.n_res * d.n_seq * 2 * d.head_dim * 2);
+    w.qpart = (float*)take((size_t)d.n_res * groups * Hd * 4);
+    w.cntpart = (float*)take((size_t)d.n_res * groups * 4);
     w.o = (float*)take((size_t)d.n_res * Hd * 4);
     w.total = off;
     return w;
@@ -651,7 +695,7 @@ size_t global_workspace(const ff_global_desc& d) { return gca::carve(d, nullptr)
 ff_status global_run(const ff_global_desc& d, const ff_global_weights& w, const void* m, const float* mask, void* out,
                      void* ws, hipStream_t st) {
     using namespace gca;
-    const int Hd = d.heads * d.head_dim, kc = kc_for(d.c), chunk = gca::chunk_for(d.n_seq, d.n_res), nchunk = (d.n_seq + chunk - 1) / chunk;
+    const int Hd = d.heads * d.head_dim, kc = kc_for(d.c), groups = kv_groups(d.n_seq);
     const Ws s = carve(d, ws);
     {
         PrepArgs a{};
@@ -667,25 +711,36 @@ ff_status global_run(const ff_global_desc& d, const ff_global_weights& w, const 
     {
         KvArgs a{};
         a.m = (const bf16_t*)m; a.mask = mask; a.S = d.n_seq; a.R = d.n_res; a.c = d.c; a.Hd = Hd; a.d = d.head_dim;
-        a.nchunk = nchunk; a.chunk = chunk; a.eps = d.ln_eps; a.wq = s.wq; a.wkv = s.wkv; a.Ckv = s.Ckv; a.kv = s.kv; a.qpart = s.qpart;
+        a.groups = groups; a.eps = d.ln_eps; a.wq = s.wq; a.wkv = s.wkv; a.Ckv = s.Ckv; a.kv = s.kv; a.qpart = s.qpart;
         a.cntpart = s.cntpart;
-        const dim3 grid((d.n_res * nchunk + 3) / 4);
-        const size_t smem = (size_t)(Hd + 32) * (kc * 32 + 16);
+        const dim3 grid(((d.n_res + 31) / 32) * groups);
+        // weights, the four wavefronts' partial sums [32 residues][Hd + 1], and their batches of k | v [32 residues][4 sequences]
+        const size_t smem = (size_t)(Hd + 32) * (kc * 32 + 16) + (size_t)4 * 32 * (Hd + 1) * 4 + (size_t)4 * 32 * (16 * d.head_dim + 16);
+        hipError_t attr = hipSuccess;
         Timed t(KK_GCA_KV, st);
+#define FF_GCA_KV_D(KCV, DV)                                                                                     \
+    do {                                                                                                         \
+        static const hipError_t once = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gca_kv<KCV, DV>),   \
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024); \
+        attr = once;                                                                                             \
+        if (once == hipSuccess) hipLaunchKernelGGL((k_gca_kv<KCV, DV>), grid, dim3(256), smem, st, a);           \
+    } while (0)
 #define FF_GCA_KV(KCV)                                                                        \
     do {                                                                                      \
-        if (d.head_dim == 8) hipLaunchKernelGGL((k_gca_kv<KCV, 8>), grid, dim3(256), smem, st, a);   \
-        else hipLaunchKernelGGL((k_gca_kv<KCV, 16>), grid, dim3(256), smem, st, a);                  \
+        if (d.head_dim == 8) FF_GCA_KV_D(KCV, 8);                                             \
+        else FF_GCA_KV_D(KCV, 16);                                                            \
     } while (0)
         if (kc == 2) FF_GCA_KV(2);
         else if (kc == 4) FF_GCA_KV(4);
         else FF_GCA_KV(8);
 #undef FF_GCA_KV
+#undef FF_GCA_KV_D
+        if (attr != hipSuccess) return fail(FF_EHIP, "k_gca_kv: dynamic LDS limit: %s", hipGetErrorString(attr));
     }
     {
         SmArgs a{};
         a.kv = s.kv; a.mask = mask; a.qpart = s.qpart; a.cntpart = s.cntpart; a.Cq = s.Cq; a.o = s.o;
-        a.S = d.n_seq; a.R = d.n_res; a.Hd = Hd; a.H = d.heads; a.nchunk = nchunk;
+        a.S = d.n_seq; a.R = d.n_res; a.Hd = Hd; a.H = d.heads; a.nchunk = groups;
         a.qscale = kLog2e / sqrtf((float)d.head_dim);
         Timed t(KK_GCA_SOFTMAX, st);
 #define FF_GCA_SM(HV, DV)                                                                                          \

@@ -298,7 +298,7 @@ struct MulShape {
 template <int WI, int WJ, int TI, int TJ>
 __global__ __launch_bounds__(64 * WI * WJ, 2) void k_tm_mul(TmMulArgs p) {
     using Sh = MulShape<WI, WJ, TI, TJ>;
-    constexpr int PITCH = kMulPitch, NT = Sh::NT, BI = Sh::BI, BJ = Sh::BJ, RSTEP = Sh::RSTEP;
+    constexpr int PITCH = kMulPitch, BI = Sh::BI, BJ = Sh::BJ, RSTEP = Sh::RSTEP;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     unsigned char* s_a = smem;                          // [2][STAGE_A]
     unsigned char* s_b = smem + 2 * Sh::STAGE_A;        // [2][STAGE_B]

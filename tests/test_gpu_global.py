@@ -42,10 +42,10 @@ def run(case):
     return out
 
 
-SHAPES = [   # n_seq, n_res, c, heads, head_dim, mask: ragged around the 32-sequence tiles and the 256-sequence chunks
+SHAPES = [   # n_seq, n_res, c, heads, head_dim, mask: ragged around the 32-residue tiles, the groups of 4 residues and of 16 sequences
     (1, 1, 32, 4, 8, "none"), (5, 3, 64, 8, 8, "random:0.7"), (33, 7, 64, 8, 8, "tail:4"), (70, 5, 96, 4, 16, "random:0.8"),
     (256, 4, 64, 8, 8, "tail:30"), (257, 3, 128, 16, 8, "random:0.9"), (600, 9, 32, 2, 16, "tail:90"),
-    (300, 40, 64, 4, 8, "random:0.5"), (129, 2, 128, 8, 16, "none"),
+    (300, 40, 64, 4, 8, "random:0.5"), (129, 2, 128, 8, 16, "none"), (50, 33, 64, 8, 8, "random:0.8"), (40, 70, 64, 8, 8, "tail:7"),
 ]
 
 
