@@ -446,8 +446,9 @@ def time_layernorm(steps):
     return res
 
 
-def cpu_baseline(case, runs=3):
-    """The float64 oracle as it stands, on the host cores, full module of the workload."""
+def cpu_baseline(case, budget_s=12.0):
+    """The float64 oracle as it stands, on the host cores, full module of the workload: repeated for about
+    budget_s seconds of CPU work (3 to 25 runs), the median run reported."""
     import numpy as np
     from oracle import evoformer_attention as O
     try:
@@ -461,15 +462,18 @@ def cpu_baseline(case, runs=3):
     w = {k: v.astype(np.float64) for k, v in case.widened_weights().items()}
     ts = []
     ref = None
-    for _ in range(runs):
+    runs = 3
+    while len(ts) < runs:
         t0 = time.perf_counter()
         ref = O.gated_attention(sp.mode, x, z, case.mask, w, sp.heads, sp.ln_eps)
         ts.append(time.perf_counter() - t0)
+        if len(ts) == 1:
+            runs = int(min(25, max(3, round(budget_s / max(ts[0], 1e-3)))))
     ts.sort()
     sec = ts[len(ts) // 2]
     return ref, {"value": counted_flop(sp)["total"] / sec / 1e12, "unit": "TFLOP/s", "cores": threads,
                  "kind": "oracle", "seconds_per_module": sec,
-                 "sample": f"full {sp.name} module (all {sp.batch_len[0]} batch rows), float64 numpy, median of {runs} runs"}
+                 "sample": f"full {sp.name} module (all {sp.batch_len[0]} batch rows), float64 numpy, median of {runs} runs ({sum(ts):.1f} s of CPU work)"}
 
 
 def main():
