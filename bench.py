@@ -489,6 +489,7 @@ def main():
     ap.add_argument("--backward-only", action="store_true", help="time only the attention-core backward pass")
     ap.add_argument("--global-only", action="store_true", help="time only the extra-MSA global column attention shapes")
     ap.add_argument("--trimul-only", action="store_true", help="time only the triangular multiplicative update shapes")
+    ap.add_argument("--shape", default=None, help="with --trimul-only / --global-only / --backward-only: this shape only")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy 5 times (reference for HBM traffic counters)")
     args = ap.parse_args()
@@ -517,17 +518,19 @@ def main():
     if args.layernorm_only:
         print(json.dumps({"calibration": measured, "layernorm": time_layernorm(args.steps)}))
         return
+    wanted = lambda name: args.shape is None or args.shape == name      # (--shape: one shape of a --*-only run)
     if args.backward_only:
-        print(json.dumps({name: time_backward(name, args.steps, 3, measured) for name in ("core_row_256", "core_tri_256")}))
+        print(json.dumps({name: time_backward(name, args.steps, 3, measured) for name in ("core_row_256", "core_tri_256")
+                          if wanted(name)}))
         return
     if args.global_only:
         print(json.dumps({name: time_global(name, st, 3, measured) for name, st in
-                          (("gca_bf16_1024x384", args.steps), ("gca_bf16_5120x384", max(args.steps // 5, 3)))}))
+                          (("gca_bf16_1024x384", args.steps), ("gca_bf16_5120x384", max(args.steps // 5, 3))) if wanted(name)}))
         return
     if args.trimul_only:
         print(json.dumps({name: time_trimul(name, st, 3, measured) for name, st in
                           (("tm_out_bf16_256", args.steps), ("tm_in_bf16_256", args.steps), ("tm_out_bf16_384", args.steps),
-                           ("tm_out_bf16_2048", 3))}))
+                           ("tm_out_bf16_2048", 3)) if wanted(name)}))
         return
     case, desc, out, ms, kernels = time_workload(args.workload, args.steps, args.warmup)
     path_taken = P.ff_attention_last_path()
