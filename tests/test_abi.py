@@ -148,3 +148,47 @@ def test_workspace_never_holds_the_score_tensor_of_section_3_2():
     assert need * 8 < per_layer
     # chunking bounds it: the whole-module workspace grows with the rows, the chunked one does not
     assert P.ff_attention_workspace_bytes(desc, 0) > need
+
+
+# ---- the entry points added after the attention module: layouts, workspace sizes, argument errors (no launches)
+def test_struct_layouts_of_the_widened_modules():
+    assert C.sizeof(B.TriMulDesc) == 6 * 4
+    assert C.sizeof(B.TriMulWeights) == len(B.TRIMUL_FIELDS) * C.sizeof(C.c_void_p)
+    assert C.sizeof(B.GlobalDesc) == 7 * 4
+    assert C.sizeof(B.GlobalWeights) == len(B.GLOBAL_FIELDS) * C.sizeof(C.c_void_p)
+    assert C.sizeof(B.CoreDesc) == 5 * 4
+    text = open(os.path.join(ROOT, "include", "ff.h")).read()
+    for name, fields in (("ff_trimul_weights", B.TRIMUL_FIELDS), ("ff_global_weights", B.GLOBAL_FIELDS)):
+        body = re.search(r"typedef struct\s*\{([^}]*)\}\s*" + name, text, flags=re.S).group(1)
+        body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+        declared = re.findall(r"\*\s*([a-z_0-9]+)", body)
+        assert tuple(declared) == tuple(fields), name        # same members, same order
+
+
+def test_workspace_sizes_of_the_widened_modules():
+    lib = P.lib()
+    tm = B.TriMulDesc(dtype=P.FF_BF16, incoming=0, n=256, c_z=128, c=128, ln_eps=1e-5)
+    ws = lib.ff_triangle_multiplication_workspace_bytes(C.byref(tm))
+    # a, b and t (three bf16 tensors of n^2 c) plus the prepared weights, and nothing of order n^3
+    assert 3 * 256 * 256 * 128 * 2 <= ws < 3 * 256 * 256 * 128 * 2 + (1 << 20)
+    gd = B.GlobalDesc(dtype=P.FF_BF16, n_seq=1024, n_res=384, c=64, heads=8, head_dim=8, ln_eps=1e-5)
+    ws = lib.ff_global_column_attention_workspace_bytes(C.byref(gd))
+    assert 1024 * 384 * 16 * 2 <= ws < 1024 * 384 * 64 * 2         # k | v per token and partial sums: below the input's size
+    cd = B.CoreDesc(dtype=P.FF_BF16, rows=128, heads=8, length=256, head_dim=32)
+    ws = lib.ff_attention_core_backward_workspace_bytes(C.byref(cd))
+    assert 0 < ws < 128 * 8 * 256 * 256 * 2                        # never a score-sized tensor
+    for bad in (B.TriMulDesc(dtype=P.FF_F32, incoming=0, n=64, c_z=128, c=128, ln_eps=1e-5),
+                B.TriMulDesc(dtype=P.FF_BF16, incoming=0, n=64, c_z=100, c=128, ln_eps=1e-5)):
+        assert lib.ff_triangle_multiplication_workspace_bytes(C.byref(bad)) == 0
+    assert lib.ff_global_column_attention_workspace_bytes(
+        C.byref(B.GlobalDesc(dtype=P.FF_BF16, n_seq=64, n_res=8, c=64, heads=8, head_dim=32, ln_eps=1e-5))) == 0
+    assert lib.ff_attention_core_backward_workspace_bytes(
+        C.byref(B.CoreDesc(dtype=P.FF_BF16, rows=4, heads=2, length=64, head_dim=64))) == 0
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=60)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr
