@@ -198,8 +198,8 @@ ff_status ff_triangle_multiplication(const ff_trimul_desc* desc, const ff_trimul
  *   P[i,h,:]   = softmax over s of q[i,h] . k[s,i]           masked sequences: weight exactly 0
  *   o[i,h,:]   = sum_s P[i,h,s] v[s,i,:]
  *   out[s,i,:] = w_o (sigmoid(w_g mn[s,i] + b_g) * concat_h o[i,h]) + b_o
- * A column without unmasked sequences gets zero context (out = b_o).  k, v, the softmax and o are
- * float32; the normalised tokens, the folded weights and the gated context are bfloat16 operands. */
+ * A column without unmasked sequences gets zero context (out = b_o).  The softmax and o are float32;
+ * the normalised tokens, the folded weights, k, v and the gated context are bfloat16. */
 typedef struct {
     int32_t dtype;      /* ff_dtype; FF_BF16 only (FF_F32 -> FF_EUNSUPPORTED) */
     int32_t n_seq;      /* m and out are [n_seq, n_res, c] */
@@ -218,7 +218,7 @@ typedef struct {
     const void *w_o, *b_o;        /* [c, heads*head_dim], [c]                    */
 } ff_global_weights;
 
-/* Bytes of device workspace (k and v of every token in float32, partial query sums, folded weights);
+/* Bytes of device workspace (k and v of every token in bfloat16, partial query sums, folded weights);
  * 0 if desc is invalid or unsupported (ff_last_error says why). */
 size_t ff_global_column_attention_workspace_bytes(const ff_global_desc* desc);
 
@@ -251,7 +251,9 @@ typedef struct {
     int32_t head_dim;   /* 8, 16 or 32 */
 } ff_core_desc;
 
-/* Bytes of device workspace (logsumexp and delta per query, dctx); 0 if desc is invalid or unsupported. */
+/* Bytes of device workspace (logsumexp and delta per query, dctx, position-contiguous copies of q, k, v and dctx,
+ * partial sums of dbias over groups of rows: about six times the size of q, never a score-sized tensor); 0 if desc
+ * is invalid or unsupported. */
 size_t ff_attention_core_backward_workspace_bytes(const ff_core_desc* desc);
 
 /* All tensor pointers are device pointers, 16-byte aligned; gradient tensors must not overlap the inputs or
