@@ -7,9 +7,10 @@
 //   dq[i] = scale sum_j dS[i,j] k[j];  dk[j] = scale sum_i dS[i,j] q[i];  dbias[h,i,j] = sum_r dS[r,h,i,j]
 //
 // The score matrix is never stored (Section 3.2): as in the forward pass it is recomputed tile by tile.
-// One wavefront per 32-query (or 32-key) tile:
+// One wavefront per 32-query (or 32-key) tile, four consecutive tiles of one (row, head) per block; the tiles of the
+// other side, which all four contract with, are copied into LDS once per block, a tile ahead of the arithmetic:
 //   k_bwd_transpose  position-contiguous copies [d][L] of q, k and v for the operands whose contraction runs over
-//                positions (k_bwd_stats adds the one of dctx)
+//                positions (k_bwd_stats adds the one of dctx); also the row of ones that stands in for no mask
 //   k_bwd_stats  forward recomputation with an online softmax: the logsumexp of every query (base 2), ctx,
 //                dg, dctx and delta
 //   k_bwd_dq     per query tile, over the key tiles: S^T = K Q^T and dP^T = V dctx^T (lane = query, so that
@@ -19,10 +20,11 @@
 //   k_bwd_dbias  per (head, query tile, key tile, chunk of batch rows): dS summed in registers over the rows of the
 //                chunk, the chunks' partial sums added in a fixed order by a small second kernel (deterministic,
 //                no atomics)
-// Operands whose contraction runs over the head dim are 16-byte row loads; operands whose contraction runs
-// over keys or queries ("transposed" fragments: lane = channel) are two 8-byte loads from the position-contiguous
+// Operands whose contraction runs over the head dim are 16-byte row reads; operands whose contraction runs
+// over keys or queries ("transposed" fragments: lane = channel) are two 8-byte reads of the position-contiguous
 // copies, taken in exactly the order in which the accumulator of the previous contraction leaves its values, so
-// nothing moves between two contractions.
+// nothing moves between two contractions.  What is added to q.k (bias, -inf of masked keys) and what is
+// subtracted from dP (delta) enter as the accumulators' starting values.
 // Operand layouts of v_mfma_f32_32x32x16_bf16: A (32 x 16): lane l holds row l%32, columns 8*(l/32)..+7;
 // B (16 x 32): lane l holds column l%32, rows 8*(l/32)..+7; D (32 x 32): lane l holds column l%32, register
 // v holds row 8*(v/4) + 4*(l/32) + v%4.

@@ -15,8 +15,8 @@
 //              projection value also holds its gate value; a and b leave channel-major, [c][N][Np], which makes every
 //              channel a dense N x N matrix for the next kernel.  The incoming form is the outgoing form
 //              on the transposed view of z (strides), so a[c][i][k] then holds a of pair (k, i).
-//   k_tm_mul   per channel t_c = A_c B_c^T: a batched N x N x N contraction, 128 x 128 tiles through LDS; t leaves
-//              as [i][channel][j]
+//   k_tm_mul   per channel t_c = A_c B_c^T: a batched N x N x N contraction, 128 x 128 or 256 x 256 tiles through
+//              LDS; t leaves as [i][channel][j]
 //   k_tm_out   LayerNorm over the channels of t (read as 2-byte loads straight into operand fragments), output
 //              projection; the output gate g is computed here, from z, in float32 (it never exists in
 //              memory), then the product and the optional residual
@@ -269,8 +269,9 @@ __global__ __launch_bounds__(512, 2) void k_tm_proj(TmProjArgs p) {
 }
 
 // ====================================================================================
-// t_c[i][j] = sum_k A_c[i][k] B_c[j][k] for every channel c: block = 4 wavefronts (2 x 2), block tile
-// 128 x 128, wavefront tile 64 x 64, the contraction in chunks of 64 through double-buffered LDS.
+// t_c[i][j] = sum_k A_c[i][k] B_c[j][k] for every channel c: block = WI x WJ wavefronts, each TI x TJ accumulator tiles
+// (block tile 128 x 128 with 2 x 2 wavefronts of 64 x 64, or 256 x 256 with 2 x 4 wavefronts of 128 x 64), the
+// contraction in chunks of 64 through double-buffered LDS.
 // Blocks are handed to the 8 XCDs round-robin; channel c goes to XCD c % 8 with all of its tiles, so a
 // channel's operands live in one L2.
 struct TmMulArgs {
