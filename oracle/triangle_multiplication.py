@@ -54,23 +54,44 @@ def _linear(x, w, b):
     return x @ np.asarray(w, _F).T + np.asarray(b, _F)
 
 
+def _side(zn, mask, w, side):
+    """Left (side "a") or right ("b") gated projection of the normalised pair representation."""
+    m = 1.0 if mask is None else np.asarray(mask, _F)[..., None]
+    return m * sigmoid(_linear(zn, w[f"w_{side}g"], w[f"b_{side}g"])) * _linear(zn, w[f"w_{side}p"], w[f"b_{side}p"])
+
+
 def projections(z, mask, w, eps):
     """(a, b, g) of the definition above."""
     zn = layer_norm(z, w["ln_g"], w["ln_b"], eps)
-    m = 1.0 if mask is None else np.asarray(mask, _F)[:, :, None]
-    a = m * sigmoid(_linear(zn, w["w_ag"], w["b_ag"])) * _linear(zn, w["w_ap"], w["b_ap"])
-    b = m * sigmoid(_linear(zn, w["w_bg"], w["b_bg"])) * _linear(zn, w["w_bp"], w["b_bp"])
+    a = _side(zn, mask, w, "a")
+    b = _side(zn, mask, w, "b")
     g = sigmoid(_linear(zn, w["w_g"], w["b_g"]))
     return a, b, g
 
 
-def triangle_multiplication(z, mask, w, incoming=False, eps=1e-5, residual=False):
-    """Triangular multiplicative update of the pair representation z [N, N, c_z] (float64 out)."""
+def triangle_multiplication(z, mask, w, incoming=False, eps=1e-5, residual=False, rows=None):
+    """Triangular multiplicative update of the pair representation z [N, N, c_z] (float64 out).
+    rows: evaluate only these rows i of the output and return [len(rows), N, c_z]: out[i] needs a of row i (outgoing)
+    or of column i (incoming), all of b, and the gate of row i; nothing else of the definition changes."""
     z = np.asarray(z, _F)
-    a, b, g = projections(z, mask, w, eps)
+    if rows is None:
+        a, b, g = projections(z, mask, w, eps)
+        if incoming:
+            t = np.einsum("kic,kjc->ijc", a, b)
+        else:
+            t = np.einsum("ikc,jkc->ijc", a, b)
+        out = g * _linear(layer_norm(t, w["lno_g"], w["lno_b"], eps), w["w_o"], w["b_o"])
+        return z + out if residual else out
+    sel = list(rows)
+    zn = layer_norm(z, w["ln_g"], w["ln_b"], eps)
+    mk = None if mask is None else np.asarray(mask, _F)
+    b = _side(zn, mk, w, "b")
     if incoming:
-        t = np.einsum("kic,kjc->ijc", a, b)
+        a = _side(zn[:, sel], None if mk is None else mk[:, sel], w, "a")       # a[k, i] for the wanted i
+        t = np.stack([np.einsum("kc,kjc->jc", a[:, n], b) for n in range(len(sel))])
     else:
-        t = np.einsum("ikc,jkc->ijc", a, b)
+        a = _side(zn[sel], None if mk is None else mk[sel], w, "a")             # a[i, k] for the wanted i
+        t = np.stack([np.einsum("kc,jkc->jc", a[n], b) for n in range(len(sel))])
+    g = sigmoid(_linear(zn[sel], w["w_g"], w["b_g"]))
     out = g * _linear(layer_norm(t, w["lno_g"], w["lno_b"], eps), w["w_o"], w["b_o"])
-    return z + out if residual else out
+    return z[sel] + out if residual else out

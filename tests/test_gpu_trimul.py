@@ -110,6 +110,20 @@ def test_long_sequence_1024_residues():
     check(got, oracle(case), "1024 residues")
 
 
+@pytest.mark.timeout(900)
+def test_long_sequence_2048_residues_sampled_rows():
+    """The long-sequence inference length (Section 6.2), the shape bench.py times, in the same launch configuration
+    (256 x 256 product tiles): the GPU computes everything, the oracle six whole rows i of the output (rows are
+    independent given a and b, which the oracle computes in full), spread over the block tiles and their edges."""
+    case = I.make_trimul_case("tm_out_bf16_2048")
+    rows = [0, 255, 256, 1031, 1789, 2047]
+    w = {k: v.astype(np.float64) for k, v in case.widened_weights().items()}
+    ref = T.triangle_multiplication(I.widen(case.z).astype(np.float64), case.mask, w, case.spec.incoming, case.spec.ln_eps,
+                                    rows=rows)
+    got = to_np(run(case)[rows])
+    check(got, ref, "2048 residues, six rows")
+
+
 def test_bad_arguments_are_status_codes():
     import ctypes as C
     from paper_2203_00854_amd import binding as B

@@ -210,3 +210,15 @@ def test_layer_norm_and_sigmoid_against_library():
     assert np.max(np.abs(T.layer_norm(x, g, b, 1e-3) - ref.numpy())) < 1e-13
     t = np.linspace(-30, 30, 13)
     assert np.max(np.abs(T.sigmoid(t) - torch.sigmoid(torch.from_numpy(t)).numpy())) < 1e-15
+
+
+@pytest.mark.parametrize("incoming", [False, True])
+def test_rows_option_against_scalar_brute_force(incoming):
+    """rows= (only some rows i of the output, what the full-size GPU comparison uses) against the scalar loops, which
+    know nothing of it; with and without the residual, and with the mask."""
+    z, mask, w = f64_case(6, 32, 32, incoming, "random:0.7", name=f"pin_tm_rows_{int(incoming)}")
+    ref = brute_force(z, mask, w, incoming, 1e-5)
+    rows = [4, 0, 5]
+    np.testing.assert_allclose(T.triangle_multiplication(z, mask, w, incoming, 1e-5, rows=rows), ref[rows], rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(T.triangle_multiplication(z, mask, w, incoming, 1e-5, residual=True, rows=rows),
+                               (z + ref)[rows], rtol=1e-11, atol=1e-12)
