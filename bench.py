@@ -319,7 +319,8 @@ def time_trimul(name, steps, warmup, measured):
 def time_global(name, steps, warmup, measured):
     """Extra-MSA global column attention (ff_global_column_attention).  The module is linear in the number of
     sequences and bound by HBM: the method reads m and writes out once each (algorithmic bytes); this
-    implementation reads m twice (key/value/query pass, gate/output pass) and moves k, v through HBM as float32."""
+    implementation reads m twice (key/value/query pass, gate/output pass) and moves k, v (bfloat16) and one mask
+    byte per token through HBM once each way."""
     import torch
     import paper_2203_00854_amd as P
     from paper_2203_00854_amd import inputs as I
@@ -351,8 +352,8 @@ def time_global(name, steps, warmup, measured):
     hd, tok = sp.heads * sp.head_dim, sp.n_seq * sp.n_res
     flop = 2.0 * tok * sp.c * (2 * hd + 2 * sp.head_dim) + 2.0 * tok * hd * sp.c + 2.0 * 2 * tok * hd
     n_bytes = tok * sp.c * 2
-    kv_bytes = tok * 2 * sp.head_dim * 4
-    per_kernel = {"k_gca_kv": n_bytes + kv_bytes, "k_gca_softmax": 2 * kv_bytes, "k_gca_out": 2 * n_bytes}
+    kv_bytes = tok * 2 * sp.head_dim * 2 + (tok if mask is not None else 0)
+    per_kernel = {"k_gca_kv": n_bytes + kv_bytes, "k_gca_softmax": kv_bytes, "k_gca_out": 2 * n_bytes}
     rows = []
     for kname, (kms, cnt) in kernels.items():
         r = {"kernel": kname, "avg_us": kms / cnt * 1e3}

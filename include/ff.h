@@ -199,7 +199,10 @@ ff_status ff_triangle_multiplication(const ff_trimul_desc* desc, const ff_trimul
  *   o[i,h,:]   = sum_s P[i,h,s] v[s,i,:]
  *   out[s,i,:] = w_o (sigmoid(w_g mn[s,i] + b_g) * concat_h o[i,h]) + b_o
  * A column without unmasked sequences gets zero context (out = b_o).  The softmax and o are float32;
- * the normalised tokens, the folded weights, k, v and the gated context are bfloat16. */
+ * the folded weights, the normalised tokens of the k, v and query projections, k, v and the gated context
+ * are bfloat16.  The gate projection takes the tokens as stored (LayerNorm's mean and scale are applied to
+ * its float32 result); the LayerNorm variance is E[x^2] - mean^2 in float32, its relative rounding error
+ * about 2^-22 (1 + mean^2 / variance). */
 typedef struct {
     int32_t dtype;      /* ff_dtype; FF_BF16 only (FF_F32 -> FF_EUNSUPPORTED) */
     int32_t n_seq;      /* m and out are [n_seq, n_res, c] */
@@ -218,7 +221,8 @@ typedef struct {
     const void *w_o, *b_o;        /* [c, heads*head_dim], [c]                    */
 } ff_global_weights;
 
-/* Bytes of device workspace (k and v of every token in bfloat16, partial query sums, folded weights);
+/* Bytes of device workspace (k and v of every token in bfloat16, one mask byte per token, partial query
+ * sums, folded weights);
  * 0 if desc is invalid or unsupported (ff_last_error says why). */
 size_t ff_global_column_attention_workspace_bytes(const ff_global_desc* desc);
 

@@ -7,21 +7,26 @@
 //
 // The module is linear in N_seq and moves far more bytes than it computes: two reads of m and one write of
 // out bound it (HBM).  Four launches:
-//   k_gca_prep     folds the LayerNorm gain into the weights (W' = bf16(W * gamma), C = W beta (+ bias)) and
-//                  writes W_o in the operand order of the last contraction
+//   k_gca_prep     folds the LayerNorm gain into the weights (W' = bf16(W * gamma), C = W beta (+ bias)), writes
+//                  W_o in the operand order of the last contraction and, for the gate rows, the row sums of W'
+//                  and the offsets C as bfloat16 pairs (one more contraction step of the gate GEMM)
 //   k_gca_kv       one block per (32 residues, group of sequences), its four wavefronts each a range of consecutive
-//                  sequences: a tile = the 32 c contiguous elements of one sequence's residues, normalised into
-//                  bf16 operand fragments (masked tokens as zeros) and contracted with W_q' (tokens x features,
-//                  never cleared between sequences: the accumulator IS the sum over the sequences, the query
-//                  average's numerator) and with W_k' | W_v' (features x tokens: k, v of a token leave as bf16,
-//                  four sequences at a time through LDS so that kv[residue][sequence] is written in whole lines);
-//                  partial query sums and counts go to the workspace
+//                  sequences: a tile = the 32 c contiguous elements of one sequence's residues, asked for as whole
+//                  lines and turned into operand fragments through LDS, normalised (masked tokens as zeros) and
+//                  contracted with W_q' (tokens x features, never cleared between sequences: the accumulator IS the
+//                  sum over the sequences, the query average's numerator) and with W_k' | W_v' (features x tokens:
+//                  k, v of a token leave as bf16, four sequences at a time through LDS so that
+//                  kv[residue][sequence] is written in whole lines; the mask goes along as one byte per token,
+//                  by column); partial query sums and counts go to the workspace
 //   k_gca_softmax  one block per column, a thread per sequence with all heads in registers: q from the partial
-//                  sums, one sweep over k and v (running maximum per thread, exponentials, denominators,
-//                  weighted sums of v), o[i] normalised
+//                  sums, one sweep over k and v (a reference per thread and head that follows the maximum lazily,
+//                  exponentials, denominators, weighted sums of v; the next sequences' k, v are on their way
+//                  meanwhile), o[i] normalised
 //   k_gca_out      a wavefront keeps one tile of 32 residues and walks over the sequences (o[i] read once): gate
-//                  GEMM, sigmoid, times o[i] (the gated tile is already the B operand of the output GEMM because
-//                  W_o was stored in the matching order), output GEMM, + b_o, the output tile through LDS
+//                  GEMM on the tokens as they are (LayerNorm's mean and scale enter through the extra contraction
+//                  step and the factor of the exponential), sigmoid, times o[i] (the gated tile is already the B
+//                  operand of the output GEMM because W_o was stored in the matching order), output GEMM with
+//                  b_o as one more step, the output tile through LDS
 // Operand layouts of v_mfma_f32_32x32x16_bf16 as in ff_trimul.hip.
 #include "ff_common.h"
 
@@ -54,51 +59,112 @@ __device__ __forceinline__ float pick(const float4& q, int e) { return e == 0 ? 
 static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 // Blocks per residue tile of k_gca_kv (four wavefronts each, every wavefront a range of consecutive sequences): also
-// the number of partial query sums per residue that k_gca_softmax adds up.  Enough blocks for three per compute
-// unit at 5120 sequences, at least eight sequences per wavefront (1024 sequences, 384 residues: 25 us with eight, 28 with four).
+// the number of partial query sums per residue that k_gca_softmax adds up.  Three blocks per compute unit at 5120
+// sequences x 384 residues (as many as its LDS lets be resident), at least eight sequences per wavefront (more
+// groups: 5120 sequences 79 -> 86 us with 80, 95 us with 128; 1024 sequences unchanged with 64).
 static int kv_groups(int n_seq) {
     int g = n_seq / 32;
     return g < 1 ? 1 : (g > 64 ? 64 : g);
 }
+// A tile (32 tokens of c channels, contiguous in m) is asked for as whole lines: lane l of request j asks for
+// the 16-byte piece 64 j + l of the tile (asked for in the operand layout - lane = token, 16 bytes of its 2 c -
+// every request would touch 32 lines for a quarter of each, which holds the reads of m near 3.7 TB/s).  The
+// pieces reach the operand layout through the wavefront's own LDS area [32 tokens][2 c + 16 bytes] (only this
+// wavefront touches it; its LDS operations complete in order).  Tokens past the end of the residues repeat the
+// last valid one.
+template <int KC>
+struct TileFetch {
+    int goff[KC];      // element offset of the lane's piece of request j within the tile
+    int woff[KC];      // byte offset of that piece in the LDS area, or -1: no such piece (c < 16 KC)
+    __device__ __forceinline__ void init(int c, int lane, int valid_tokens) {
+        const int ppt = c >> 3, pitch = 2 * c + 16;
+#pragma unroll
+        for (int j = 0; j < KC; ++j) {
+            const int P = 64 * j + lane;
+            const bool act = P < 32 * ppt;
+            const int t = act ? P / ppt : 0, w = act ? P - t * ppt : 0;
+            const int tt = t < valid_tokens ? t : valid_tokens - 1;
+            goff[j] = tt * c + 8 * w;
+            woff[j] = act ? t * pitch + 16 * w : -1;
+        }
+    }
+    __device__ __forceinline__ void fetch(Frag (&raw)[KC], const bf16_t* tile) const {
+#pragma unroll
+        for (int j = 0; j < KC; ++j) raw[j].u = *reinterpret_cast<const uint4*>(tile + goff[j]);
+    }
+    // raw pieces -> xa: eight channels 16 q + 8 hf .. of token col per step q (zeros beyond c)
+    __device__ __forceinline__ void to_operands(const Frag (&raw)[KC], Frag (&xa)[KC], unsigned char* area, int c, int col, int hf) const {
+        const int pitch = 2 * c + 16;
+#pragma unroll
+        for (int j = 0; j < KC; ++j) {
+            uint32_t a = raw[j].w[0], b = raw[j].w[1], cc = raw[j].w[2], d = raw[j].w[3];
+            asm volatile("" : "+v"(a), "+v"(b), "+v"(cc), "+v"(d));   // (keeps the pieces in registers from load to store)
+            if (woff[j] >= 0) *reinterpret_cast<uint4*>(area + woff[j]) = make_uint4(a, b, cc, d);
+        }
+#pragma unroll
+        for (int q = 0; q < KC; ++q) {
+            xa[q].u = make_uint4(0, 0, 0, 0);
+            if (16 * q + 8 * hf < c) xa[q].u = *reinterpret_cast<const uint4*>(area + col * pitch + (2 * q + hf) * 16);
+        }
+    }
+};
+
+// Statistics of the lane's token (which stays as it is): mean, 1 / sqrt(variance + eps) and sqrt(variance + eps).
+// Sum and sum of squares come from the packed pairs directly (a two-element dot product with float32
+// accumulation per pair: the squares of bfloat16 values are exact in float32), the variance as
+// E[x^2] - mean^2: its rounding error is about 2^-22 (1 + mean^2 / variance), far below what the bfloat16
+// tokens themselves carry.
+template <int KC>
+__device__ __forceinline__ void statistics(const Frag (&xa)[KC], int K, float eps, float& mean, float& rstd, float& istd) {
+    const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
+    float sum = 0.f, sq = 0.f;
+#pragma unroll
+    for (int s = 0; s < KC; ++s)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {                    // (channels beyond K are zero)
+            const bf16x2 w = __builtin_bit_cast(bf16x2, xa[s].w[i]);
+            sum = __builtin_amdgcn_fdot2_f32_bf16(w, ones, sum, false);
+            sq = __builtin_amdgcn_fdot2_f32_bf16(w, w, sq, false);
+        }
+    sum += __shfl_xor(sum, 32, 64);
+    sq += __shfl_xor(sq, 32, 64);
+    const float rk = 1.f / (float)K;
+    mean = sum * rk;
+    const float var = fmaxf(sq * rk - mean * mean, 0.f);
+    const float ve = var + eps;
+    rstd = rsqrtf(ve);
+    istd = ve * rstd;                                // sqrt(variance + eps)
+}
 // Normalised operand fragments of the lane's token: xn = bf16((x - mean) * rstd) (the LayerNorm gain and
-// offset live in the folded weights), or zeros if !keep.  Two passes over the registers for the statistics.
+// offset live in the folded weights), or zeros if !keep.
 template <int KC>
 __device__ __forceinline__ void normalise(Frag (&xa)[KC], int K, int hf, float eps, bool keep) {
-    float sum = 0.f;
-#pragma unroll
-    for (int s = 0; s < KC; ++s)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) sum += lo_f32(xa[s].w[i]) + hi_f32(xa[s].w[i]);   // (channels beyond K are zero)
-    sum += __shfl_xor(sum, 32, 64);
-    const float mean = sum / (float)K;
-    float sq = 0.f;
-#pragma unroll
-    for (int s = 0; s < KC; ++s)
-        if (16 * s + 8 * hf < K) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float d0 = lo_f32(xa[s].w[i]) - mean, d1 = hi_f32(xa[s].w[i]) - mean;
-                sq += d0 * d0 + d1 * d1;
-            }
-        }
-    sq += __shfl_xor(sq, 32, 64);
-    const float rstd = keep ? rsqrtf(sq / (float)K + eps) : 0.f;
+    float mean, rstd, istd;
+    statistics<KC>(xa, K, eps, mean, rstd, istd);
+    if (!keep) rstd = 0.f;
+    const float off = -mean * rstd;
 #pragma unroll
     for (int s = 0; s < KC; ++s) {
         const bool in = 16 * s + 8 * hf < K;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const float a = (lo_f32(xa[s].w[i]) - mean) * rstd, b = (hi_f32(xa[s].w[i]) - mean) * rstd;
+            const float a = lo_f32(xa[s].w[i]) * rstd + off, b = hi_f32(xa[s].w[i]) * rstd + off;
             xa[s].w[i] = in ? pack2(a, b) : 0u;
         }
     }
+}
+// v = hi + lo with hi, lo bfloat16 (hi the nearest, lo the nearest to the rest): 16 significant bits in two operand slots
+__device__ __forceinline__ void split2(float v, float& hi, float& lo) {
+    hi = __uint_as_float(pack2(0.f, v) & 0xffff0000u);
+    lo = v - hi;
 }
 
 // ====================================================================================
 struct PrepArgs {
     const bf16_t *w_q, *w_k, *w_v, *w_g, *b_g, *w_o, *b_o, *ln_g, *ln_b;
     bf16_t *wq, *wkv, *wg, *wo;       // [Hd][Kp], [32][Kp], [Hd][Kp], [c][Hd] (operand order)
-    float *Cq, *Ckv, *Cg, *Co;        // [Hd], [32], [Hd], [c]
+    float *Cq, *Ckv, *Co;             // [Hd], [32], [c]
+    bf16_t* gext;                     // [Hd][8]: the gate rows' extra contraction step (see k_gca_out)
     int c, Hd, d, Kp;
 };
 
@@ -111,7 +177,8 @@ __global__ __launch_bounds__(256) void k_gca_prep(PrepArgs a) {
         const bf16_t* wrow = nullptr;
         float bias = 0.f;
         bf16_t* dst;
-        float* Cd;
+        float* Cd = nullptr;
+        bf16_t* ext = nullptr;
         if (n < a.Hd) {
             wrow = a.w_q + (size_t)n * a.c; dst = a.wq + (size_t)n * a.Kp; Cd = a.Cq + n;
         } else if (n < a.Hd + 32) {
@@ -122,9 +189,9 @@ __global__ __launch_bounds__(256) void k_gca_prep(PrepArgs a) {
         } else {
             const int f = n - a.Hd - 32;
             wrow = a.w_g + (size_t)f * a.c; bias = bf16_to_f32(a.b_g[f]);
-            dst = a.wg + (size_t)f * a.Kp; Cd = a.Cg + f;
+            dst = a.wg + (size_t)f * a.Kp; ext = a.gext + (size_t)f * 8;
         }
-        float cst = 0.f;
+        float cst = 0.f, rowsum = 0.f;
         for (int k = lane; k < a.Kp; k += 64) {
             float r = 0.f;
             if (wrow && k < a.c) {
@@ -132,10 +199,24 @@ __global__ __launch_bounds__(256) void k_gca_prep(PrepArgs a) {
                 r = w * bf16_to_f32(a.ln_g[k]);
                 cst += w * bf16_to_f32(a.ln_b[k]);
             }
-            dst[k] = f32_to_bf16(r);
+            const bf16_t rb = f32_to_bf16(r);
+            dst[k] = rb;
+            rowsum += bf16_to_f32(rb);                // of the rounded entries: what the matrix unit multiplies with
         }
         cst = wave_sum(cst);
-        if (lane == 0) *Cd = cst + bias;
+        rowsum = wave_sum(rowsum);
+        if (lane == 0) {
+            if (Cd) *Cd = cst + bias;
+            if (ext) {
+                // slots of the extra step: S S_ S' C C_ C' 0 0 with S = hi(rowsum), S' = lo(rowsum), C likewise; the
+                // token side holds -mean and 1 / rstd split the same way (hi, lo, hi): the three largest of the four products
+                const float C = cst + bias;
+                const bf16_t s_hi = f32_to_bf16(rowsum), s_lo = f32_to_bf16(rowsum - bf16_to_f32(s_hi));
+                const bf16_t c_hi = f32_to_bf16(C), c_lo = f32_to_bf16(C - bf16_to_f32(c_hi));
+                ext[0] = s_hi; ext[1] = s_hi; ext[2] = s_lo; ext[3] = c_hi; ext[4] = c_hi; ext[5] = c_lo;
+                ext[6] = f32_to_bf16(0.f); ext[7] = f32_to_bf16(0.f);
+            }
+        }
         return;
     }
     const int co = n - rows_fold;
@@ -159,6 +240,7 @@ struct KvArgs {
     const bf16_t *wq, *wkv;  // folded, pitch 16 KC
     const float* Ckv;
     bf16_t* kv;              // [R][S][2d]: k then v of a token
+    unsigned char* keepT;    // [R][S]: 1 = the token takes part (the mask, by column); written only if mask != NULL
     float* qpart;            // [R][groups][Hd]
     float* cntpart;          // [R][groups]
 };
@@ -169,13 +251,13 @@ struct KvArgs {
 // sums need no arithmetic of their own: the accumulator of the tokens x features contraction with W_q' simply is
 // not cleared between sequences (lane = feature, register = residue).  At the end the block adds the four
 // wavefronts' sums in LDS and writes one partial sum per residue and feature.
-template <int KC, int D>
+template <int KC, int D, int NQT>      // NQT = H d / 32: 32-feature tiles of the query projection
 __global__ __launch_bounds__(256) void k_gca_kv(KvArgs p) {
     constexpr int PITCH = KC * 32 + 16;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     unsigned char* s_wq = smem;                                  // [Hd][PITCH]
     unsigned char* s_wkv = smem + (size_t)p.Hd * PITCH;          // [32][PITCH]
-    float* s_red = reinterpret_cast<float*>(s_wkv + 32 * PITCH); // [4][32][Hd + 1]: the wavefronts' query sums and counts
+    float* s_red = reinterpret_cast<float*>(smem);               // [4][32][Hd + 1]: the wavefronts' query sums and counts, after the loop
     const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int tpr = (p.R + 31) >> 5;
@@ -190,21 +272,21 @@ __global__ __launch_bounds__(256) void k_gca_kv(KvArgs p) {
     // 128-byte (d = 8) runs of kv[residue][sequence]: stored straight from the accumulators they would be 8-byte
     // pieces of 32 different lines per instruction (only this wavefront touches the area; its LDS operations
     // complete in order)
-    unsigned char* s_b = smem + (size_t)(p.Hd + 32) * PITCH + (size_t)4 * 32 * (p.Hd + 1) * 4 + (size_t)wave * 32 * BP;
+    unsigned char* s_b = smem + (size_t)(p.Hd + 32) * PITCH + (size_t)wave * 32 * BP;
+    // the wavefront's area for the incoming tile [32 tokens][2 c + 16]
+    unsigned char* s_in = smem + (size_t)(p.Hd + 32) * PITCH + (size_t)4 * 32 * BP + (size_t)wave * 32 * (2 * p.c + 16);
+    // ... and for the keep flags of the batch [32 residues][4 sequences]
+    unsigned char* s_keep = smem + (size_t)(p.Hd + 32) * PITCH + (size_t)4 * 32 * BP + (size_t)4 * 32 * (2 * p.c + 16) + wave * 128;
+    TileFetch<KC> tf;
+    tf.init(p.c, lane, p.R - rt * 32 < 32 ? p.R - rt * 32 : 32);
 
     // the first tokens are requested before the weights are copied: both are on their way together
     Frag xn[KC];
     float mkn = 1.f;
     {
         const int s0 = s_lo < p.S ? s_lo : 0;
-        const size_t tok = (size_t)s0 * p.R + i;
-        const bf16_t* mp = p.m + tok * p.c;
-#pragma unroll
-        for (int q = 0; q < KC; ++q) {
-            xn[q].u = make_uint4(0, 0, 0, 0);
-            if (16 * q + 8 * hf < p.c) xn[q].u = *reinterpret_cast<const uint4*>(mp + 16 * q + 8 * hf);
-        }
-        if (p.mask) mkn = p.mask[tok];
+        tf.fetch(xn, p.m + ((size_t)s0 * p.R + rt * 32) * p.c);
+        if (p.mask) mkn = p.mask[(size_t)s0 * p.R + i];
     }
     for (int id = tid; id < (p.Hd + 32) * 2 * KC; id += 256) {
         const int row = id / (2 * KC), pc = id - row * (2 * KC);
@@ -213,10 +295,9 @@ __global__ __launch_bounds__(256) void k_gca_kv(KvArgs p) {
     }
     __syncthreads();
 
-    const int n_qt = p.Hd >> 5;                  // 32-feature tiles of the query projection (at most 4)
-    f32x16 qacc[4];                              // tokens x features, summed over the wavefront's sequences
+    f32x16 qacc[NQT];                            // tokens x features, summed over the wavefront's sequences
 #pragma unroll
-    for (int T = 0; T < 4; ++T)
+    for (int T = 0; T < NQT; ++T)
 #pragma unroll
         for (int v = 0; v < 16; ++v) qacc[T][v] = 0.f;
     float cnt = 0.f;                             // unmasked sequences of the lane's residue
@@ -226,29 +307,22 @@ __global__ __launch_bounds__(256) void k_gca_kv(KvArgs p) {
 
     for (int s = s_lo; s < s_hi; ++s) {
         Frag xa[KC];
-#pragma unroll
-        for (int q = 0; q < KC; ++q) xa[q].u = xn[q].u;
+        tf.to_operands(xn, xa, s_in, p.c, col, hf);
         const bool keep = valid && mkn != 0.f;
         {
             const int sn = s + 1 < s_hi ? s + 1 : s;               // (the last round asks for its own tokens again)
-            const size_t tok = (size_t)sn * p.R + i;
-            const bf16_t* mp = p.m + tok * p.c;
-#pragma unroll
-            for (int q = 0; q < KC; ++q)
-                if (16 * q + 8 * hf < p.c) xn[q].u = *reinterpret_cast<const uint4*>(mp + 16 * q + 8 * hf);
-            if (p.mask) mkn = p.mask[tok];
+            tf.fetch(xn, p.m + ((size_t)sn * p.R + rt * 32) * p.c);
+            if (p.mask) mkn = p.mask[(size_t)sn * p.R + i];
         }
         normalise<KC>(xa, p.c, hf, p.eps, keep);
         cnt += keep ? 1.f : 0.f;
 #pragma unroll
-        for (int T = 0; T < 4; ++T) {
-            if (T < n_qt) {
+        for (int T = 0; T < NQT; ++T) {
 #pragma unroll
-                for (int q = 0; q < KC; ++q) {
-                    Frag wf;
-                    wf.u = *reinterpret_cast<const uint4*>(s_wq + (32 * T + col) * PITCH + (2 * q + hf) * 16);
-                    qacc[T] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[q].v, wf.v, qacc[T], 0, 0, 0);
-                }
+            for (int q = 0; q < KC; ++q) {
+                Frag wf;
+                wf.u = *reinterpret_cast<const uint4*>(s_wq + (32 * T + col) * PITCH + (2 * q + hf) * 16);
+                qacc[T] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[q].v, wf.v, qacc[T], 0, 0, 0);
             }
         }
         // keys and values: features x tokens, the lane owns a token; rows 0 .. D-1 keys, 16 .. 16+D-1 values
@@ -263,6 +337,7 @@ __global__ __launch_bounds__(256) void k_gca_kv(KvArgs p) {
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf.v, xa[q].v, acc, 0, 0, 0);
             }
             const int b = (s - s_lo) & 3;
+            const bool last = s + 1 == s_hi;
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int row = 8 * g + 4 * hf;                  // rows row .. row + 3 of the tile
@@ -274,7 +349,8 @@ __global__ __launch_bounds__(256) void k_gca_kv(KvArgs p) {
                         make_uint2(pack2(acc[4 * g] + c4.x, acc[4 * g + 1] + c4.y), pack2(acc[4 * g + 2] + c4.z, acc[4 * g + 3] + c4.w));
                 }
             }
-            if (b == 3 || s + 1 == s_hi) {
+            if (p.mask && hf == 0) s_keep[col * 4 + b] = keep ? 1 : 0;
+            if (b == 3 || last) {
                 // nb sequences s - b .. s of 32 residues: 16-byte pieces, a residue's nb records are contiguous in kv
                 const int ppr = (b + 1) * (REC / 16);            // pieces per residue
                 unsigned char* kvb = reinterpret_cast<unsigned char*>(p.kv) + ((size_t)(rt * 32) * p.S + (s - b)) * REC;
@@ -283,18 +359,25 @@ __global__ __launch_bounds__(256) void k_gca_kv(KvArgs p) {
                     const uint4 v = *reinterpret_cast<const uint4*>(s_b + r * BP + pc * 16);
                     if (rt * 32 + r < p.R) *reinterpret_cast<uint4*>(kvb + (size_t)r * p.S * REC + pc * 16) = v;
                 }
+                if (p.mask) {
+                    const int nb = b + 1;
+                    for (int id = lane; id < 32 * nb; id += 64) {
+                        const int r = id / nb, j = id - r * nb;
+                        if (rt * 32 + r < p.R) p.keepT[(size_t)(rt * 32 + r) * p.S + (s - b) + j] = s_keep[r * 4 + j];
+                    }
+                }
             }
         }
     }
     // the block's partial sums: wavefront w leaves [residue][feature] (and the count in column Hd) in its part of LDS
+    // (the sums take the place of the weights and the k | v batches, which every wavefront is done with by now)
+    __syncthreads();
     const int RP = p.Hd + 1;
     float* red = s_red + (size_t)wave * 32 * RP;
 #pragma unroll
-    for (int T = 0; T < 4; ++T)
-        if (T < n_qt) {
+    for (int T = 0; T < NQT; ++T)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) red[(8 * (v >> 2) + 4 * hf + (v & 3)) * RP + 32 * T + col] = qacc[T][v];
-        }
+        for (int v = 0; v < 16; ++v) red[(8 * (v >> 2) + 4 * hf + (v & 3)) * RP + 32 * T + col] = qacc[T][v];
     if (hf == 0) red[col * RP + p.Hd] = cnt;
     __syncthreads();
     for (int id = tid; id < 32 * RP; id += 256) {
@@ -311,7 +394,7 @@ __global__ __launch_bounds__(256) void k_gca_kv(KvArgs p) {
 // ====================================================================================
 struct SmArgs {
     const bf16_t* kv;        // [R][S][2d]
-    const float* mask;       // [S][R] or NULL
+    const unsigned char* keepT;   // [R][S] (1 = takes part) or NULL: every token takes part
     const float *qpart, *cntpart, *Cq;
     float* o;                // [R][Hd]
     int S, R, Hd, H, nchunk;
@@ -349,17 +432,40 @@ __device__ __forceinline__ void wave_reduce_scatter(float (&v)[N], int lane) {
 }
 
 // Block = one column, NT threads; a thread takes the sequences s = tid, tid + NT, ... and holds all H heads:
-// k and v of a sequence are read ONCE (one sweep: every thread keeps a running maximum per head and rescales
-// its own partial sums when that maximum rises, so no pass over the logits precedes the exponentials), the H
+// k and v of a sequence are read ONCE (one sweep: every thread keeps a reference per head - at most kSlack below
+// the largest logit it has met - and rescales its own partial sums when the reference moves, so no pass over the
+// logits precedes the exponentials), the H
 // denominators and H x D weighted sums live in registers (hence H and D as template parameters), and the
 // block combines the threads' partial results, each brought to the common maximum, through shuffles and LDS.
 template <int H, int D, int NT>
 __global__ __launch_bounds__(NT) void k_gca_softmax(SmArgs p) {
     constexpr int HD = H * D, NW = NT / 64, PW = HD + 2 * H;
+    constexpr float kSlack = 8.f;                 // (logits are in units of log 2)
     __shared__ float s_q[HD];
     __shared__ float s_red[NW * PW];              // per wavefront: weighted sums, denominators, maxima
     __shared__ __attribute__((aligned(16))) float s_part[4 * NT];   // the threads' partial query sums
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, i = blockIdx.x;
+    // U sequences at a time: their loads (k, v and the keep flag, none of which depends on another) are all in
+    // flight together; k and v of a masked sequence exist (finite) and are simply not used.  The first batch is
+    // asked for here, before the partial sums: the two round trips to memory overlap.
+    constexpr int U = 64 / (2 * D);
+    static_assert(D % 8 == 0, "k and v of a token are read in 16-byte pieces");
+    const bf16_t* kvc = p.kv + (size_t)i * p.S * (2 * D);
+    // (the next U sequences are asked for before this batch is worked on; sequences past the end ask for the last
+    // one again and count as masked; nothing is done with a loaded value before its batch's turn, so that no wait
+    // for it precedes the work on the batch before)
+    uint4 kvn[U][2 * D / 8];
+    unsigned char keepn[U];
+    const unsigned char* keepc = p.keepT ? p.keepT + (size_t)i * p.S : nullptr;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int s = tid + u * NT, sc = s < p.S ? s : p.S - 1;
+        const uint4* kp = reinterpret_cast<const uint4*>(kvc + (size_t)sc * (2 * D));
+#pragma unroll
+        for (int e8 = 0; e8 < 2 * D / 8; ++e8) kvn[u][e8] = kp[e8];
+        keepn[u] = 1;
+        if (keepc) keepn[u] = keepc[sc];
+    }
     // partial counts and query sums of the column's chunks: spread over the lanes / the threads so that the loads
     // do not queue behind each other (a column of 5120 sequences has 20 chunks)
     float cnt = 0.f;
@@ -398,33 +504,27 @@ __global__ __launch_bounds__(NT) void k_gca_softmax(SmArgs p) {
         }
     }
     __syncthreads();
-    const bf16_t* kvc = p.kv + (size_t)i * p.S * (2 * D);
-
     float mx[H], den[H], o[HD];
 #pragma unroll
     for (int h = 0; h < H; ++h) { mx[h] = -INFINITY; den[h] = 0.f; }
 #pragma unroll
     for (int f = 0; f < HD; ++f) o[f] = 0.f;
-    // U sequences at a time: their loads (k, v and the mask entry, none of which depends on another) are all in
-    // flight before the first is used; k and v of a masked sequence exist (finite) and are simply not used
-    constexpr int U = 64 / (2 * D);
-    static_assert(D % 8 == 0, "k and v of a token are read in 16-byte pieces");
     for (int s0 = tid; s0 < p.S; s0 += U * NT) {
         uint4 kv4[U][2 * D / 8];
         float mk[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            const int s = s0 + u * NT;
-            mk[u] = 0.f;
+            mk[u] = s0 + u * NT < p.S && keepn[u] ? 1.f : 0.f;
 #pragma unroll
-            for (int e8 = 0; e8 < 2 * D / 8; ++e8) kv4[u][e8] = make_uint4(0, 0, 0, 0);
-            if (s < p.S) {
-                const uint4* kp = reinterpret_cast<const uint4*>(kvc + (size_t)s * (2 * D));
+            for (int e8 = 0; e8 < 2 * D / 8; ++e8) kv4[u][e8] = kvn[u][e8];
+        }
 #pragma unroll
-                for (int e8 = 0; e8 < 2 * D / 8; ++e8) kv4[u][e8] = kp[e8];
-                mk[u] = 1.f;
-                if (p.mask) mk[u] = p.mask[(size_t)s * p.R + i];
-            }
+        for (int u = 0; u < U; ++u) {
+            const int s = s0 + (U + u) * NT, sc = s < p.S ? s : p.S - 1;
+            const uint4* kp = reinterpret_cast<const uint4*>(kvc + (size_t)sc * (2 * D));
+#pragma unroll
+            for (int e8 = 0; e8 < 2 * D / 8; ++e8) kvn[u][e8] = kp[e8];
+            if (keepc) keepn[u] = keepc[sc];
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -445,13 +545,20 @@ __global__ __launch_bounds__(NT) void k_gca_softmax(SmArgs p) {
                 float l = 0.f;
 #pragma unroll
                 for (int e = 0; e < D; ++e) l += s_q[h * D + e] * k[e];
-                const float m_new = fmaxf(mx[h], l);
-                const float a = __builtin_amdgcn_exp2f(mx[h] - m_new);      // 0 for the thread's first sequence
-                const float w = __builtin_amdgcn_exp2f(l - m_new);
-                mx[h] = m_new;
-                den[h] = den[h] * a + w;
+                // mx is the thread's reference for the exponentials, not the exact maximum: it moves (and the sums
+                // are rescaled) only when a logit exceeds it by more than kSlack, so that after a thread's first
+                // sequences almost no step pays for the rescaling; weights stay below 2^kSlack
+                if (l > mx[h] + kSlack) {
+                    const float a = __builtin_amdgcn_exp2f(mx[h] - l);      // 0 for the thread's first sequence
+                    mx[h] = l;
+                    den[h] *= a;
 #pragma unroll
-                for (int e = 0; e < D; ++e) o[h * D + e] = o[h * D + e] * a + w * v[e];
+                    for (int e = 0; e < D; ++e) o[h * D + e] *= a;
+                }
+                const float w = __builtin_amdgcn_exp2f(l - mx[h]);
+                den[h] += w;
+#pragma unroll
+                for (int e = 0; e < D; ++e) o[h * D + e] += w * v[e];
             }
         }
     }
@@ -512,7 +619,8 @@ struct OutArgs {
     int S, R, c, Hd;
     float eps;
     const bf16_t *wg, *wo;   // folded gate weights (pitch 16 KC); W_o in operand order [c][Hd]
-    const float *Cg, *Co;
+    const bf16_t* gext;      // [Hd][8]: row sums and offsets of the gate rows as one more contraction step
+    const float* Co;         // [c] output bias
 };
 
 template <int KC, int NGT>       // contraction steps of the gate GEMM (c / 16, rounded up to 2, 4, 8); gate tiles H d / 32
@@ -520,10 +628,10 @@ __global__ __launch_bounds__(256) void k_gca_out(OutArgs p) {
     constexpr int PITCH = KC * 32 + 16;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int po = p.Hd * 2 + 16;                                // bytes per row of W_o in LDS
+    // the 16 bytes that pad a row of either matrix hold one more contraction step: for a gate row its row sum S and
+    // offset C as S S S' C C C' 0 0 (hi, hi, lo), for a row of W_o its bias as b 0 ... 0
     unsigned char* s_wg = smem;                                  // [Hd][PITCH]
     unsigned char* s_wo = smem + (size_t)p.Hd * PITCH;           // [c][po]
-    float* s_cg = reinterpret_cast<float*>(s_wo + (size_t)p.c * po);   // [Hd] gate offsets
-    float* s_co = s_cg + p.Hd;                                   // [c]  output bias
     const int pt = p.c * 2 + 16;                                 // bytes per token row of the staged output tile
     const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -531,17 +639,18 @@ __global__ __launch_bounds__(256) void k_gca_out(OutArgs p) {
     // pieces of 32 different tokens; written to memory like that every store instruction would touch 32 lines, so
     // they are gathered here and leave as whole contiguous kilobytes (only this wavefront reads or writes the area;
     // a wavefront's LDS operations complete in order)
-    unsigned char* s_tile = reinterpret_cast<unsigned char*>(s_co + p.c) + (size_t)wave * 32 * pt;
-    for (int id = tid; id < p.Hd; id += 256) s_cg[id] = p.Cg[id];
-    for (int id = tid; id < p.c; id += 256) s_co[id] = p.Co[id];
-    for (int id = tid; id < p.Hd * 2 * KC; id += 256) {
-        const int row = id / (2 * KC), pc = id - row * (2 * KC);
-        *reinterpret_cast<uint4*>(s_wg + row * PITCH + pc * 16) = *reinterpret_cast<const uint4*>(p.wg + (size_t)row * (16 * KC) + pc * 8);
+    unsigned char* s_tile = s_wo + (size_t)p.c * po + (size_t)wave * 32 * pt;
+    for (int id = tid; id < p.Hd * (2 * KC + 1); id += 256) {
+        const int row = id / (2 * KC + 1), pc = id - row * (2 * KC + 1);
+        const bf16_t* src = pc < 2 * KC ? p.wg + (size_t)row * (16 * KC) + pc * 8 : p.gext + (size_t)row * 8;
+        *reinterpret_cast<uint4*>(s_wg + row * PITCH + pc * 16) = *reinterpret_cast<const uint4*>(src);
     }
     const int opr = p.Hd >> 3;                                   // 16-byte pieces per row of W_o
-    for (int id = tid; id < p.c * opr; id += 256) {
-        const int row = id / opr, pc = id - row * opr;
-        *reinterpret_cast<uint4*>(s_wo + row * po + pc * 16) = *reinterpret_cast<const uint4*>(p.wo + (size_t)row * p.Hd + pc * 8);
+    for (int id = tid; id < p.c * (opr + 1); id += 256) {
+        const int row = id / (opr + 1), pc = id - row * (opr + 1);
+        uint4 v = make_uint4(f32_to_bf16(p.Co[row]), 0, 0, 0);
+        if (pc < opr) v = *reinterpret_cast<const uint4*>(p.wo + (size_t)row * p.Hd + pc * 8);
+        *reinterpret_cast<uint4*>(s_wo + row * po + pc * 16) = v;
     }
     __syncthreads();
 
@@ -565,27 +674,37 @@ __global__ __launch_bounds__(256) void k_gca_out(OutArgs p) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) o4[T][g] = *reinterpret_cast<const float4*>(oi + 32 * T + 8 * g + 4 * hf);
     }
+    Frag one;                                    // token side of the bias step: a one in slot 0 of the first half
+    one.u = make_uint4(hf ? 0u : 0x3f80u, 0u, 0u, 0u);
+    TileFetch<KC> tf;
+    tf.init(p.c, lane, p.R - rt * 32 < 32 ? p.R - rt * 32 : 32);
     Frag xn[KC];
-    {
-        const bf16_t* mp = p.m + ((size_t)sg * p.R + i) * p.c;
-#pragma unroll
-        for (int q = 0; q < KC; ++q) {
-            xn[q].u = make_uint4(0, 0, 0, 0);
-            if (valid && 16 * q + 8 * hf < p.c) xn[q].u = *reinterpret_cast<const uint4*>(mp + 16 * q + 8 * hf);
-        }
-    }
+    tf.fetch(xn, p.m + ((size_t)sg * p.R + rt * 32) * p.c);
     for (int s = sg; s < p.S; s += ng) {
+        // (the incoming tile passes through the area that later stages the output tile)
         Frag xa[KC];
-#pragma unroll
-        for (int q = 0; q < KC; ++q) xa[q].u = xn[q].u;
+        tf.to_operands(xn, xa, s_tile, p.c, col, hf);
         {
             const int sn = s + ng < p.S ? s + ng : s;        // (the last round fetches its own tokens again)
-            const bf16_t* mp = p.m + ((size_t)sn * p.R + i) * p.c;
-#pragma unroll
-            for (int q = 0; q < KC; ++q)
-                if (valid && 16 * q + 8 * hf < p.c) xn[q].u = *reinterpret_cast<const uint4*>(mp + 16 * q + 8 * hf);
+            tf.fetch(xn, p.m + ((size_t)sn * p.R + rt * 32) * p.c);
         }
-        normalise<KC>(xa, p.c, hf, p.eps, valid);
+        // The tokens enter the gate GEMM as they are.  With W' the folded weights, S their row sums and C the
+        // offsets, LayerNorm followed by the projection is rstd (W' x - mean S + C / rstd): the two corrections are
+        // one more contraction step whose token side holds -mean and 1 / rstd (each as hi + lo bfloat16, slots
+        // hi lo hi against the row's hi hi lo), and rstd rides in the factor of the exponential.
+        float mean, rstd, istd;
+        statistics<KC>(xa, p.c, p.eps, mean, rstd, istd);
+        Frag xe;
+        {
+            float m_hi, m_lo, r_hi, r_lo;
+            split2(-mean, m_hi, m_lo);
+            split2(istd, r_hi, r_lo);
+            xe.w[0] = hf ? 0u : pack2(m_hi, m_lo);
+            xe.w[1] = hf ? 0u : pack2(m_hi, r_hi);
+            xe.w[2] = hf ? 0u : pack2(r_lo, r_hi);
+            xe.w[3] = 0u;
+        }
+        const float nrl = -kLog2e * rstd;            // sigmoid(rstd a) = 1 / (1 + exp2(nrl a))
 
         // gate: features x tokens; value of feature 32T + 8g + 4hf + e in register 4g + e, times o[i][feature];
         // registers 8j .. 8j+7 of tile T packed are the B operand of contraction step 2T + j of the output GEMM
@@ -601,13 +720,17 @@ __global__ __launch_bounds__(256) void k_gca_out(OutArgs p) {
                 wf.u = *reinterpret_cast<const uint4*>(s_wg + (32 * T + col) * PITCH + (2 * q + hf) * 16);
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf.v, xa[q].v, acc, 0, 0, 0);
             }
+            {
+                Frag wf;
+                wf.u = *reinterpret_cast<const uint4*>(s_wg + (32 * T + col) * PITCH + 2 * KC * 16);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf.v, xe.v, acc, 0, 0, 0);
+            }
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int f0 = 32 * T + 8 * g + 4 * hf;
-                const float4 c4 = *reinterpret_cast<const float4*>(s_cg + f0);
                 float t[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) t[e] = sigmoid(acc[4 * g + e] + pick(c4, e)) * pick(o4[T][g], e);
+                for (int e = 0; e < 4; ++e)
+                    t[e] = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(nrl * acc[4 * g + e])) * pick(o4[T][g], e);
                 gf[2 * T + (g >> 1)].w[2 * (g & 1)] = pack2(t[0], t[1]);
                 gf[2 * T + (g >> 1)].w[2 * (g & 1) + 1] = pack2(t[2], t[3]);
             }
@@ -625,12 +748,16 @@ __global__ __launch_bounds__(256) void k_gca_out(OutArgs p) {
                     wf.u = *reinterpret_cast<const uint4*>(s_wo + (32 * ct + col) * po + kk * 32 + hf * 16);
                     acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf.v, gf[kk].v, acc, 0, 0, 0);
                 }
+                {
+                    Frag wf;                                     // + b_o: the bias against a one
+                    wf.u = *reinterpret_cast<const uint4*>(s_wo + (32 * ct + col) * po + 2 * NGT * 32);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf.v, one.v, acc, 0, 0, 0);
+                }
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const int c0 = 32 * ct + 8 * g + 4 * hf;
-                    const float4 b4 = *reinterpret_cast<const float4*>(s_co + c0);
-                    *reinterpret_cast<uint2*>(s_tile + col * pt + c0 * 2) = make_uint2(pack2(acc[4 * g] + b4.x, acc[4 * g + 1] + b4.y),
-                                                                                       pack2(acc[4 * g + 2] + b4.z, acc[4 * g + 3] + b4.w));
+                    *reinterpret_cast<uint2*>(s_tile + col * pt + c0 * 2) =
+                        make_uint2(pack2(acc[4 * g], acc[4 * g + 1]), pack2(acc[4 * g + 2], acc[4 * g + 3]));
                 }
             }
         }
@@ -649,8 +776,9 @@ __global__ __launch_bounds__(256) void k_gca_out(OutArgs p) {
 
 // ====================================================================================
 struct Ws {
-    bf16_t *wq, *wkv, *wg, *wo, *kv;
-    float *Cq, *Ckv, *Cg, *Co, *qpart, *cntpart, *o;
+    bf16_t *wq, *wkv, *wg, *wo, *gext, *kv;
+    unsigned char* keepT;
+    float *Cq, *Ckv, *Co, *qpart, *cntpart, *o;
     size_t total;
 };
 
@@ -672,9 +800,10 @@ static Ws carve(const ff_global_desc& d, void* base) {
     w.wo = (bf16_t*)take((size_t)d.c * Hd * 2);
     w.Cq = (float*)take((size_t)Hd * 4);
     w.Ckv = (float*)take(32 * 4);
-    w.Cg = (float*)take((size_t)Hd * 4);
+    w.gext = (bf16_t*)take((size_t)Hd * 8 * 2);
     w.Co = (float*)take((size_t)d.c * 4);
     w.kv = (bf16_t*)take((size_t)d.n_res * d.n_seq * 2 * d.head_dim * 2);
+    w.keepT = (unsigned char*)take((size_t)d.n_res * d.n_seq);
     w.qpart = (float*)take((size_t)d.n_res * groups * Hd * 4);
     w.cntpart = (float*)take((size_t)d.n_res * groups * 4);
     w.o = (float*)take((size_t)d.n_res * Hd * 4);
@@ -702,7 +831,7 @@ ff_status global_run(const ff_global_desc& d, const ff_global_weights& w, const 
         a.w_q = (const bf16_t*)w.w_q; a.w_k = (const bf16_t*)w.w_k; a.w_v = (const bf16_t*)w.w_v; a.w_g = (const bf16_t*)w.w_g;
         a.b_g = (const bf16_t*)w.b_g; a.w_o = (const bf16_t*)w.w_o; a.b_o = (const bf16_t*)w.b_o;
         a.ln_g = (const bf16_t*)w.ln_g; a.ln_b = (const bf16_t*)w.ln_b;
-        a.wq = s.wq; a.wkv = s.wkv; a.wg = s.wg; a.wo = s.wo; a.Cq = s.Cq; a.Ckv = s.Ckv; a.Cg = s.Cg; a.Co = s.Co;
+        a.wq = s.wq; a.wkv = s.wkv; a.wg = s.wg; a.wo = s.wo; a.Cq = s.Cq; a.Ckv = s.Ckv; a.gext = s.gext; a.Co = s.Co;
         a.c = d.c; a.Hd = Hd; a.d = d.head_dim; a.Kp = 16 * kc;
         const int rows = 2 * Hd + 32 + d.c;
         Timed t(KK_GCA_PREP, st);
@@ -711,19 +840,29 @@ ff_status global_run(const ff_global_desc& d, const ff_global_weights& w, const 
     {
         KvArgs a{};
         a.m = (const bf16_t*)m; a.mask = mask; a.S = d.n_seq; a.R = d.n_res; a.c = d.c; a.Hd = Hd; a.d = d.head_dim;
-        a.groups = groups; a.eps = d.ln_eps; a.wq = s.wq; a.wkv = s.wkv; a.Ckv = s.Ckv; a.kv = s.kv; a.qpart = s.qpart;
+        a.groups = groups; a.eps = d.ln_eps; a.wq = s.wq; a.wkv = s.wkv; a.Ckv = s.Ckv; a.kv = s.kv; a.keepT = s.keepT; a.qpart = s.qpart;
         a.cntpart = s.cntpart;
         const dim3 grid(((d.n_res + 31) / 32) * groups);
-        // weights, the four wavefronts' partial sums [32 residues][Hd + 1], and their batches of k | v [32 residues][4 sequences]
-        const size_t smem = (size_t)(Hd + 32) * (kc * 32 + 16) + (size_t)4 * 32 * (Hd + 1) * 4 + (size_t)4 * 32 * (16 * d.head_dim + 16);
+        // weights, the wavefronts' batches of k | v [32 residues][4 sequences] and incoming tiles; afterwards the same bytes hold the
+        // four wavefronts' partial sums [32 residues][Hd + 1]
+        const size_t smem_loop = (size_t)(Hd + 32) * (kc * 32 + 16) + (size_t)4 * 32 * (16 * d.head_dim + 16) +
+                                 (size_t)4 * 32 * (2 * d.c + 16) + 4 * 128;
+        const size_t smem_red = (size_t)4 * 32 * (Hd + 1) * 4;
+        const size_t smem = smem_loop > smem_red ? smem_loop : smem_red;
         hipError_t attr = hipSuccess;
         Timed t(KK_GCA_KV, st);
-#define FF_GCA_KV_D(KCV, DV)                                                                                     \
+#define FF_GCA_KV_Q(KCV, DV, QV)                                                                                 \
     do {                                                                                                         \
-        static const hipError_t once = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gca_kv<KCV, DV>),   \
+        static const hipError_t once = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gca_kv<KCV, DV, QV>), \
                                                            hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024); \
         attr = once;                                                                                             \
-        if (once == hipSuccess) hipLaunchKernelGGL((k_gca_kv<KCV, DV>), grid, dim3(256), smem, st, a);           \
+        if (once == hipSuccess) hipLaunchKernelGGL((k_gca_kv<KCV, DV, QV>), grid, dim3(256), smem, st, a);       \
+    } while (0)
+#define FF_GCA_KV_D(KCV, DV)                                                                  \
+    do {                                                                                      \
+        if (Hd == 32) FF_GCA_KV_Q(KCV, DV, 1);                                                \
+        else if (Hd == 64) FF_GCA_KV_Q(KCV, DV, 2);                                           \
+        else FF_GCA_KV_Q(KCV, DV, 4);                                                         \
     } while (0)
 #define FF_GCA_KV(KCV)                                                                        \
     do {                                                                                      \
@@ -735,11 +874,12 @@ ff_status global_run(const ff_global_desc& d, const ff_global_weights& w, const 
         else FF_GCA_KV(8);
 #undef FF_GCA_KV
 #undef FF_GCA_KV_D
+#undef FF_GCA_KV_Q
         if (attr != hipSuccess) return fail(FF_EHIP, "k_gca_kv: dynamic LDS limit: %s", hipGetErrorString(attr));
     }
     {
         SmArgs a{};
-        a.kv = s.kv; a.mask = mask; a.qpart = s.qpart; a.cntpart = s.cntpart; a.Cq = s.Cq; a.o = s.o;
+        a.kv = s.kv; a.keepT = mask ? s.keepT : nullptr; a.qpart = s.qpart; a.cntpart = s.cntpart; a.Cq = s.Cq; a.o = s.o;
         a.S = d.n_seq; a.R = d.n_res; a.Hd = Hd; a.H = d.heads; a.nchunk = groups;
         a.qscale = kLog2e / sqrtf((float)d.head_dim);
         Timed t(KK_GCA_SOFTMAX, st);
@@ -762,13 +902,13 @@ ff_status global_run(const ff_global_desc& d, const ff_global_weights& w, const 
     {
         OutArgs a{};
         a.m = (const bf16_t*)m; a.out = (bf16_t*)out; a.o = s.o; a.S = d.n_seq; a.R = d.n_res; a.c = d.c; a.Hd = Hd;
-        a.eps = d.ln_eps; a.wg = s.wg; a.wo = s.wo; a.Cg = s.Cg; a.Co = s.Co;
+        a.eps = d.ln_eps; a.wg = s.wg; a.wo = s.wo; a.gext = s.gext; a.Co = s.Co;
         const int tasks = d.n_seq * ((d.n_res + 31) / 32);
-        int blocks = (tasks + 3) / 4;                                   // at least one wavefront per residue tile
-        if (blocks > 3 * compute_units()) blocks = 3 * compute_units();
-        if (blocks * 4 < (d.n_res + 31) / 32) blocks = ((d.n_res + 31) / 32 + 3) / 4;
-        const size_t smem = (size_t)Hd * (kc * 32 + 16) + (size_t)d.c * (Hd * 2 + 16) + (size_t)(Hd + d.c) * 4 +
-                            (size_t)4 * 32 * (d.c * 2 + 16);       // weights, offsets, one output tile per wavefront
+        // as many blocks as are resident together (registers and LDS of the instance decide; four per compute unit
+        // at most), at least one wavefront per residue tile
+        int blocks = 0;
+        const size_t smem = (size_t)Hd * (kc * 32 + 16) + (size_t)d.c * (Hd * 2 + 16) +
+                            (size_t)4 * 32 * (d.c * 2 + 16);       // weights (with their extra step), one output tile per wavefront
         hipError_t attr = hipSuccess;
         Timed t(KK_GCA_OUT, st);
 #define FF_GCA_OUT(KCV, NGTV)                                                                                    \
@@ -776,6 +916,13 @@ ff_status global_run(const ff_global_desc& d, const ff_global_weights& w, const 
         static const hipError_t once = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gca_out<KCV, NGTV>), \
                                                            hipFuncAttributeMaxDynamicSharedMemorySize, 112 * 1024); \
         attr = once;                                                                                             \
+        int per_cu = 0;                                                                                          \
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_gca_out<KCV, NGTV>, 256, smem) != hipSuccess || per_cu < 1) \
+            per_cu = 1;                                                                                          \
+        if (per_cu > 4) per_cu = 4;                                                                              \
+        blocks = (tasks + 3) / 4;                                                                                \
+        if (blocks > per_cu * compute_units()) blocks = per_cu * compute_units();                                \
+        if (blocks * 4 < (d.n_res + 31) / 32) blocks = ((d.n_res + 31) / 32 + 3) / 4;                            \
         if (once == hipSuccess) hipLaunchKernelGGL((k_gca_out<KCV, NGTV>), dim3(blocks), dim3(256), smem, st, a); \
     } while (0)
 #define FF_GCA_OUT_K(KCV)                                                                                        \

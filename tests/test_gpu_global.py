@@ -88,6 +88,17 @@ def test_columns_without_unmasked_sequences_and_masked_content():
     assert torch.equal(got[:70], b[:70])
 
 
+def test_tokens_with_a_mean_far_from_zero():
+    """The kernels take the LayerNorm variance as E[x^2] - mean^2 in float32: tokens whose mean is eight times
+    their spread (and a second set at sixty times) must still match the oracle."""
+    for shift, scale in ((4.0, 0.5), (30.0, 0.5)):
+        spec = I.GlobalSpec(f"t_gca_shifted_{shift}", "bf16", 150, 37, 64, 8, 8, "random:0.8")
+        case = I.make_global_case(spec)
+        m = I.widen(case.m).astype(np.float64) * scale + shift
+        case = I.GlobalCase(spec, I.to_storage(m, "bf16"), case.mask, case.weights)
+        check(to_np(run(case)), oracle(case), spec.name)
+
+
 def test_sequence_permutation_permutes_the_output():
     """Reordering the sequences reorders the output; the attended vectors are sums over the sequences in another
     order, so equality holds to rounding, not bit for bit."""
