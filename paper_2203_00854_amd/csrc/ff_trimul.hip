@@ -8,8 +8,9 @@
 //
 // Four launches per call:
 //   k_tm_prep  folds the LayerNorm gains into the weights: W' = bf16(W * gamma), S = rowsum(W'),
-//              Cn = W beta + bias, so that LN(x) W^T + bias = rstd * (x W'^T - mean * S) + Cn and the
-//              matrix cores read the raw activations
+//              Cn = W beta + bias, so that LN(x) W^T + bias = rstd * (x W'^T - mean * S + Cn / rstd): the
+//              matrix cores read the raw activations, and S, Cn of a row (as bfloat16 pairs) are one more
+//              contraction step against the token's -mean and 1 / rstd (token_side)
 //   k_tm_proj  one merged GEMM over the 4c features of the left and right side.  A projection tile is
 //              contracted together with its gate tile (features x tokens), so that the lane that holds a
 //              projection value also holds its gate value; a and b leave channel-major, [c][N][Np], which makes every
@@ -54,37 +55,56 @@ __device__ __forceinline__ void merge_halves(uint32_t& a, uint32_t& b) {
 }
 __device__ __forceinline__ float lo_f32(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float hi_f32(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
-__device__ __forceinline__ float sigmoid(float t) {
-    return __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-t * kLog2e));
-}
-__device__ __forceinline__ float pick(const float4& q, int e) { return e == 0 ? q.x : (e == 1 ? q.y : (e == 2 ? q.z : q.w)); }
 
 static inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 static inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
-// LayerNorm statistics of the token whose K channels lie in the fragments of the two lanes (col, hf = 0 | 1):
-// mean and 1 / sqrt(var + eps), float32, two passes over the registers.
+// LayerNorm statistics of the token whose K channels lie in the fragments of the two lanes (col, hf = 0 | 1),
+// channels beyond K being zero: mean, 1 / sqrt(var + eps) and sqrt(var + eps), float32.  Sum and sum of squares
+// come from the packed pairs directly (two-element dot products with float32 accumulation: the squares of
+// bfloat16 values are exact in float32), the variance as E[x^2] - mean^2: its rounding error is about
+// 2^-22 (1 + mean^2 / variance), far below what the bfloat16 tokens themselves carry.
 template <int KC>
-__device__ __forceinline__ void token_stats(const Frag (&xa)[KC], int K, int hf, float eps, float& mean, float& rstd) {
-    float sum = 0.f;
+__device__ __forceinline__ void token_stats(const Frag (&xa)[KC], int K, float eps, float& mean, float& rstd, float& istd) {
+    const bf16x2 ones = __builtin_bit_cast(bf16x2, 0x3f803f80u);
+    float sum = 0.f, sq = 0.f;
 #pragma unroll
     for (int s = 0; s < KC; ++s)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) sum += lo_f32(xa[s].w[i]) + hi_f32(xa[s].w[i]);   // (channels beyond K are zero)
-    sum += __shfl_xor(sum, 32, 64);
-    mean = sum / (float)K;
-    float sq = 0.f;
-#pragma unroll
-    for (int s = 0; s < KC; ++s)
-        if (16 * s + 8 * hf < K) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float d0 = lo_f32(xa[s].w[i]) - mean, d1 = hi_f32(xa[s].w[i]) - mean;
-                sq += d0 * d0 + d1 * d1;
-            }
+        for (int i = 0; i < 4; ++i) {
+            const bf16x2 w = __builtin_bit_cast(bf16x2, xa[s].w[i]);
+            sum = __builtin_amdgcn_fdot2_f32_bf16(w, ones, sum, false);
+            sq = __builtin_amdgcn_fdot2_f32_bf16(w, w, sq, false);
         }
+    sum += __shfl_xor(sum, 32, 64);
     sq += __shfl_xor(sq, 32, 64);
-    rstd = rsqrtf(sq / (float)K + eps);
+    const float rk = 1.f / (float)K;
+    mean = sum * rk;
+    const float ve = fmaxf(sq * rk - mean * mean, 0.f) + eps;
+    rstd = rsqrtf(ve);
+    istd = ve * rstd;
+}
+
+// LayerNorm followed by a projection with folded weights W' (row sums S, offsets C) is rstd (W' x - mean S + C / rstd):
+// the matrix cores take the tokens as stored, and the two corrections are ONE MORE contraction step.  Its weight
+// side (a row's eight slots, written by k_tm_prep) is S S S' C C C' 0 0 with S + S' = the row sum as a bfloat16 pair
+// (hi, lo) and C likewise; its token side, built here, holds -mean and 1 / rstd split the same way in the order
+// hi lo hi: the three largest of the four partial products, 16 significant bits.  The upper half of the
+// wavefront (slots 8 .. 15 of the step) holds zeros.
+__device__ __forceinline__ void split2(float v, float& hi, float& lo) {
+    hi = __uint_as_float(pack2(0.f, v) & 0xffff0000u);
+    lo = v - hi;
+}
+__device__ __forceinline__ Frag token_side(float mean, float istd, int hf) {
+    float m_hi, m_lo, r_hi, r_lo;
+    split2(-mean, m_hi, m_lo);
+    split2(istd, r_hi, r_lo);
+    Frag xe;
+    xe.w[0] = hf ? 0u : pack2(m_hi, m_lo);
+    xe.w[1] = hf ? 0u : pack2(m_hi, r_hi);
+    xe.w[2] = hf ? 0u : pack2(r_lo, r_hi);
+    xe.w[3] = 0u;
+    return xe;
 }
 
 // ====================================================================================
@@ -97,7 +117,7 @@ struct TmPrepArgs {
     const bf16_t *w_ap, *b_ap, *w_ag, *b_ag, *w_bp, *b_bp, *w_bg, *b_bg, *w_g, *b_g, *ln_g, *ln_b;
     const bf16_t *w_o, *b_o, *lno_g, *lno_b;
     bf16_t *wp1, *wp3, *wp4;       // [64 n_pairs][Kp1], [cz][Kp3], [cz][Kp1]
-    float *S1, *C1, *S3, *C3, *S4, *C4;
+    bf16_t *ext1, *ext3, *ext4;    // [rows][8]: the extra contraction step of every row (see token_side)
     int cz, c, G, n_pairs, Kp1, Kp3;
 };
 
@@ -109,12 +129,11 @@ __global__ __launch_bounds__(256) void k_tm_prep(TmPrepArgs a) {
     const bf16_t *wrow = nullptr, *gamma, *beta;
     float bias = 0.f;
     int K, Kp;
-    bf16_t* dst;
-    float *Sd, *Cd;
+    bf16_t *dst, *ext;
     if (n < rows1) {
         const int p = n >> 6, half = (n >> 5) & 1, j = n & 31;
         K = a.cz; Kp = a.Kp1; gamma = a.ln_g; beta = a.ln_b;
-        dst = a.wp1 + (size_t)n * Kp; Sd = a.S1 + n; Cd = a.C1 + n;
+        dst = a.wp1 + (size_t)n * Kp; ext = a.ext1 + (size_t)n * 8;
         const bool left = p < a.G;
         const int ch = 32 * (left ? p : p - a.G) + j;
         const bf16_t* w = left ? (half ? a.w_ag : a.w_ap) : (half ? a.w_bg : a.w_bp);
@@ -124,13 +143,13 @@ __global__ __launch_bounds__(256) void k_tm_prep(TmPrepArgs a) {
     } else if (n < rows1 + a.cz) {
         const int f = n - rows1;
         K = a.c; Kp = a.Kp3; gamma = a.lno_g; beta = a.lno_b;
-        dst = a.wp3 + (size_t)f * Kp; Sd = a.S3 + f; Cd = a.C3 + f;
+        dst = a.wp3 + (size_t)f * Kp; ext = a.ext3 + (size_t)f * 8;
         wrow = a.w_o + (size_t)f * K;
         bias = bf16_to_f32(a.b_o[f]);
     } else {
         const int f = n - rows1 - a.cz;
         K = a.cz; Kp = a.Kp1; gamma = a.ln_g; beta = a.ln_b;
-        dst = a.wp4 + (size_t)f * Kp; Sd = a.S4 + f; Cd = a.C4 + f;
+        dst = a.wp4 + (size_t)f * Kp; ext = a.ext4 + (size_t)f * 8;
         wrow = a.w_g + (size_t)f * K;
         bias = bf16_to_f32(a.b_g[f]);
     }
@@ -148,8 +167,11 @@ __global__ __launch_bounds__(256) void k_tm_prep(TmPrepArgs a) {
     sum = wave_sum(sum);
     cst = wave_sum(cst);
     if (lane == 0) {
-        *Sd = sum;
-        *Cd = cst + bias;
+        const float C = cst + bias;
+        const bf16_t s_hi = f32_to_bf16(sum), s_lo = f32_to_bf16(sum - bf16_to_f32(s_hi));
+        const bf16_t c_hi = f32_to_bf16(C), c_lo = f32_to_bf16(C - bf16_to_f32(c_hi));
+        ext[0] = s_hi; ext[1] = s_hi; ext[2] = s_lo; ext[3] = c_hi; ext[4] = c_hi; ext[5] = c_lo;
+        ext[6] = f32_to_bf16(0.f); ext[7] = f32_to_bf16(0.f);
     }
 }
 
@@ -165,7 +187,7 @@ struct TmProjArgs {
     int ppb;                 // pairs per block: blockIdx.y takes pairs [blockIdx.y * ppb, + ppb)
     float eps;
     const bf16_t* wp;        // [64 n_pairs][16 KC]
-    const float *S, *Cn;
+    const bf16_t* ext;       // [64 n_pairs][8]
     bf16_t *a, *b;           // [C][N][Np]
 };
 
@@ -173,9 +195,7 @@ template <int KC>
 __global__ __launch_bounds__(512, 2) void k_tm_proj(TmProjArgs p) {
     constexpr int PITCH = KC * 32 + 16;                 // bytes per weight row in LDS
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    unsigned char* s_w = smem;                                                    // [64 ppb][PITCH]: the block's share of the folded weights
-    float* s_S = reinterpret_cast<float*>(smem + (size_t)64 * p.ppb * PITCH);     // [64 ppb] row sums of the folded weights
-    float* s_C = s_S + 64 * p.ppb;                                                // [64 ppb] offsets
+    unsigned char* s_w = smem;       // [64 ppb][PITCH]: the block's share of the folded weights, a row's extra step in its last 16 bytes
     const int pr_first = blockIdx.y * p.ppb;
     constexpr int OPITCH = 80;                          // bytes per channel row of a staged output half-tile [16][32]
 
@@ -184,21 +204,18 @@ __global__ __launch_bounds__(512, 2) void k_tm_proj(TmProjArgs p) {
     const int tpr = p.Np >> 5;                          // token tiles per row
     const int tiles_m = p.N * tpr;
     // the wavefront's own staging area (only it reads or writes there; its LDS operations complete in order)
-    unsigned char* s_o = reinterpret_cast<unsigned char*>(s_C + 64 * p.ppb) + wave * (16 * OPITCH);
+    unsigned char* s_o = smem + (size_t)64 * p.ppb * PITCH + wave * (16 * OPITCH);
 
     // The block's share of the folded weight matrix (all of it, at most 512 rows of 256 bytes, for large inputs;
     // a quarter for small ones, which need the blocks) stays in LDS for the life of the block, which works through
     // token tiles blockIdx.x * 8 + wave, + 8 * gridDim.x, ...: after this one barrier the wavefronts run
     // independently, so that one wavefront's matrix instructions overlap another's epilogue arithmetic on the
     // same SIMD, and the weights are read from L2 once per block, not once per 256 tokens.
-    for (int id = tid; id < 64 * p.ppb * 2 * KC; id += 512) {
-        const int row = id / (2 * KC), pc = id - row * (2 * KC);
-        *reinterpret_cast<uint4*>(s_w + row * PITCH + pc * 16) =
-            *reinterpret_cast<const uint4*>(p.wp + (size_t)(64 * pr_first + row) * (16 * KC) + pc * 8);
-    }
-    for (int id = tid; id < 64 * p.ppb; id += 512) {
-        s_S[id] = p.S[64 * pr_first + id];
-        s_C[id] = p.Cn[64 * pr_first + id];
+    for (int id = tid; id < 64 * p.ppb * (2 * KC + 1); id += 512) {
+        const int row = id / (2 * KC + 1), pc = id - row * (2 * KC + 1);
+        const bf16_t* src = pc < 2 * KC ? p.wp + (size_t)(64 * pr_first + row) * (16 * KC) + pc * 8
+                                        : p.ext + (size_t)(64 * pr_first + row) * 8;
+        *reinterpret_cast<uint4*>(s_w + row * PITCH + pc * 16) = *reinterpret_cast<const uint4*>(src);
     }
     __syncthreads();                                    // (the only barrier)
 
@@ -218,8 +235,11 @@ __global__ __launch_bounds__(512, 2) void k_tm_proj(TmProjArgs p) {
             }
         }
         const float mval = valid ? (p.mask ? p.mask[tok] : 1.f) : 0.f;
-        float mean, rstd;
-        token_stats<KC>(xa, p.K, hf, p.eps, mean, rstd);
+        float mean, rstd, istd;
+        token_stats<KC>(xa, p.K, p.eps, mean, rstd, istd);
+        const Frag xe = token_side(mean, istd, hf);
+        const float nrl = -kLog2e * rstd;               // sigmoid(rstd t) = 1 / (1 + exp2(nrl t))
+        const float rm = rstd * mval;
 
         for (int pl = 0; pl < p.ppb; ++pl) {
             const int pr = pr_first + pl;
@@ -237,6 +257,13 @@ __global__ __launch_bounds__(512, 2) void k_tm_proj(TmProjArgs p) {
                 acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w0.v, xa[s].v, acc0, 0, 0, 0);
                 acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1.v, xa[s].v, acc1, 0, 0, 0);
             }
+            {
+                Frag w0, w1;                            // - mean S + C / rstd (the same 16 bytes for both halves: the token side's upper half is zero)
+                w0.u = *reinterpret_cast<const uint4*>(st + col * PITCH + 2 * KC * 16);
+                w1.u = *reinterpret_cast<const uint4*>(st + (32 + col) * PITCH + 2 * KC * 16);
+                acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w0.v, xe.v, acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w1.v, xe.v, acc1, 0, 0, 0);
+            }
             const bool left = pr < p.G;
             const int ch0 = 32 * (left ? pr : pr - p.G);
             // A lane holds ONE position of 16 channels, and the channel rows of a and b lie a whole plane apart:
@@ -249,16 +276,11 @@ __global__ __launch_bounds__(512, 2) void k_tm_proj(TmProjArgs p) {
 #pragma unroll
                 for (int gg = 0; gg < 2; ++gg) {
                     const int g = 2 * hh + gg;
-                    const float4 sp4 = *reinterpret_cast<const float4*>(s_S + 64 * pl + 8 * g + 4 * hf);
-                    const float4 cp4 = *reinterpret_cast<const float4*>(s_C + 64 * pl + 8 * g + 4 * hf);
-                    const float4 sg4 = *reinterpret_cast<const float4*>(s_S + 64 * pl + 32 + 8 * g + 4 * hf);
-                    const float4 cg4 = *reinterpret_cast<const float4*>(s_C + 64 * pl + 32 + 8 * g + 4 * hf);
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const float tp = rstd * (acc0[4 * g + e] - mean * pick(sp4, e)) + pick(cp4, e);
-                        const float tgv = rstd * (acc1[4 * g + e] - mean * pick(sg4, e)) + pick(cg4, e);
+                        const float gate = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(nrl * acc1[4 * g + e]));
                         *reinterpret_cast<bf16_t*>(s_o + (8 * gg + 4 * hf + e) * OPITCH + col * 2) =
-                            (bf16_t)(pack2(tp * sigmoid(tgv) * mval, 0.f) & 0xffffu);
+                            (bf16_t)(pack2(acc0[4 * g + e] * rm * gate, 0.f) & 0xffffu);
                     }
                 }
                 const uint4 v = *reinterpret_cast<const uint4*>(s_o + (lane >> 2) * OPITCH + (lane & 3) * 16);
@@ -449,7 +471,7 @@ struct TmOutArgs {
     int wave_bytes;          // LDS area of a wavefront: 32 * (2 cz + 16)
     float eps;
     const bf16_t *wp, *wg;   // [cz][16 KC], [cz][16 KZ]
-    const float *S, *Cn, *Sg, *Cg;
+    const bf16_t *ext, *extg;  // [cz][8] each: the rows' extra contraction step
 };
 
 template <int KC, int KZ>
@@ -458,28 +480,24 @@ __global__ __launch_bounds__(512) void k_tm_out(TmOutArgs p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     unsigned char* s_wo = smem;                             // [cz][PC]
     unsigned char* s_wg = smem + (size_t)p.cz * PC;         // [cz][PZ]
-    float* s_k = reinterpret_cast<float*>(s_wg + (size_t)p.cz * PZ);   // [4][cz]: S, Cn, Sg, Cg
     const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // (only this wavefront reads or writes its area; a wavefront's LDS operations complete in order)
-    unsigned char* s_x = reinterpret_cast<unsigned char*>(s_k + 4 * p.cz) + (size_t)wave * p.wave_bytes;
+    unsigned char* s_x = s_wg + (size_t)p.cz * PZ + (size_t)wave * p.wave_bytes;
     const int tpr = p.Np >> 5, tiles_m = p.N * tpr, n_ft = p.cz >> 5, nwaves = gridDim.x * 8;
     const int PO = 2 * p.cz + 16;                           // bytes per token row of the staged output tile
     int t = blockIdx.x * 8 + wave;
 
-    for (int id = tid; id < p.cz; id += 512) {
-        s_k[id] = p.S[id];
-        s_k[p.cz + id] = p.Cn[id];
-        s_k[2 * p.cz + id] = p.Sg[id];
-        s_k[3 * p.cz + id] = p.Cg[id];
+    // (a row's extra contraction step - see token_side - sits in the 16 bytes that pad it)
+    for (int id = tid; id < p.cz * (2 * KC + 1); id += 512) {
+        const int row = id / (2 * KC + 1), pc = id - row * (2 * KC + 1);
+        const bf16_t* src = pc < 2 * KC ? p.wp + (size_t)row * (16 * KC) + pc * 8 : p.ext + (size_t)row * 8;
+        *reinterpret_cast<uint4*>(s_wo + row * PC + pc * 16) = *reinterpret_cast<const uint4*>(src);
     }
-    for (int id = tid; id < p.cz * 2 * KC; id += 512) {
-        const int row = id / (2 * KC), pc = id - row * (2 * KC);
-        *reinterpret_cast<uint4*>(s_wo + row * PC + pc * 16) = *reinterpret_cast<const uint4*>(p.wp + (size_t)row * (16 * KC) + pc * 8);
-    }
-    for (int id = tid; id < p.cz * 2 * KZ; id += 512) {
-        const int row = id / (2 * KZ), pc = id - row * (2 * KZ);
-        *reinterpret_cast<uint4*>(s_wg + row * PZ + pc * 16) = *reinterpret_cast<const uint4*>(p.wg + (size_t)row * (16 * KZ) + pc * 8);
+    for (int id = tid; id < p.cz * (2 * KZ + 1); id += 512) {
+        const int row = id / (2 * KZ + 1), pc = id - row * (2 * KZ + 1);
+        const bf16_t* src = pc < 2 * KZ ? p.wg + (size_t)row * (16 * KZ) + pc * 8 : p.extg + (size_t)row * 8;
+        *reinterpret_cast<uint4*>(s_wg + row * PZ + pc * 16) = *reinterpret_cast<const uint4*>(src);
     }
     __syncthreads();                                        // (the only barrier)
 
@@ -509,14 +527,11 @@ __global__ __launch_bounds__(512) void k_tm_out(TmOutArgs p) {
                 }
             }
         }
-        float mean_z, rstd_z, mean, rstd;
-        token_stats<KZ>(za, p.cz, hf, p.eps, mean_z, rstd_z);
-        token_stats<KC>(xa, p.C, hf, p.eps, mean, rstd);
-        // (the row sums and offsets are the same for every tile; read through an offset the compiler cannot see
-        // through, or it keeps all 4 cz of them in registers across the tile loop)
-        int kofs = 0;
-        asm volatile("" : "+v"(kofs));
-        const float* s_kt = s_k + kofs;
+        float mean_z, rstd_z, istd_z, mean, rstd, istd;
+        token_stats<KZ>(za, p.cz, p.eps, mean_z, rstd_z, istd_z);
+        token_stats<KC>(xa, p.C, p.eps, mean, rstd, istd);
+        const Frag xe = token_side(mean, istd, hf), ze = token_side(mean_z, istd_z, hf);
+        const float nrl = -kLog2e * rstd_z;                 // sigmoid(rstd_z t) = 1 / (1 + exp2(nrl t))
 
 #pragma unroll
         for (int ft = 0; ft < KZ / 2; ++ft) {               // (unrolled: the residual below picks registers by ft)
@@ -538,20 +553,20 @@ __global__ __launch_bounds__(512) void k_tm_out(TmOutArgs p) {
                 gf.u = *reinterpret_cast<const uint4*>(grow + 32 * s);
                 accg = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf.v, za[s].v, accg, 0, 0, 0);
             }
+            {
+                Frag wf, gf;                                // - mean S + C / rstd of either projection
+                wf.u = *reinterpret_cast<const uint4*>(s_wo + (ft * 32 + col) * PC + 2 * KC * 16);
+                gf.u = *reinterpret_cast<const uint4*>(s_wg + (ft * 32 + col) * PZ + 2 * KZ * 16);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf.v, xe.v, acc, 0, 0, 0);
+                accg = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf.v, ze.v, accg, 0, 0, 0);
+            }
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int f0 = ft * 32 + 8 * g + 4 * hf;
-                const float4 s4 = *reinterpret_cast<const float4*>(s_kt + f0);
-                const float4 c4 = *reinterpret_cast<const float4*>(s_kt + p.cz + f0);
-                const float4 sg4 = *reinterpret_cast<const float4*>(s_kt + 2 * p.cz + f0);
-                const float4 cg4 = *reinterpret_cast<const float4*>(s_kt + 3 * p.cz + f0);
                 float o[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float lin = rstd * (acc[4 * g + e] - mean * pick(s4, e)) + pick(c4, e);
-                    const float gate = sigmoid(rstd_z * (accg[4 * g + e] - mean_z * pick(sg4, e)) + pick(cg4, e));
-                    o[e] = lin * gate;
-                }
+                for (int e = 0; e < 4; ++e)
+                    o[e] = acc[4 * g + e] * rstd * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(nrl * accg[4 * g + e]));
                 if (p.residual) {
                     // z[token][f0 .. f0 + 3] is in the registers of the token's two lanes: channels 16 s + 8 h' + u of
                     // fragment s belong to half h'; the lane wants words 2 hf, 2 hf + 1 of fragment 2 ft + g / 2 of half
@@ -585,8 +600,7 @@ __global__ __launch_bounds__(512) void k_tm_out(TmOutArgs p) {
 
 // ====================================================================================
 struct TmWs {
-    bf16_t *wp1, *wp3, *wp4, *a, *b, *x;
-    float *S1, *C1, *S3, *C3, *S4, *C4;
+    bf16_t *wp1, *wp3, *wp4, *ext1, *ext3, *ext4, *a, *b, *x;
     size_t total;
 };
 
@@ -606,12 +620,9 @@ static TmWs tm_carve(int N, int cz, int c, void* base) {
     w.wp1 = (bf16_t*)take((size_t)64 * n_pairs * Kp1 * 2);
     w.wp3 = (bf16_t*)take((size_t)cz * Kp3 * 2);
     w.wp4 = (bf16_t*)take((size_t)cz * Kp1 * 2);
-    w.S1 = (float*)take((size_t)64 * n_pairs * 4);
-    w.C1 = (float*)take((size_t)64 * n_pairs * 4);
-    w.S3 = (float*)take((size_t)cz * 4);
-    w.C3 = (float*)take((size_t)cz * 4);
-    w.S4 = (float*)take((size_t)cz * 4);
-    w.C4 = (float*)take((size_t)cz * 4);
+    w.ext1 = (bf16_t*)take((size_t)64 * n_pairs * 8 * 2);
+    w.ext3 = (bf16_t*)take((size_t)cz * 8 * 2);
+    w.ext4 = (bf16_t*)take((size_t)cz * 8 * 2);
     const size_t plane = (size_t)c * N * Np * 2;
     w.a = (bf16_t*)take(plane);
     w.b = (bf16_t*)take(plane);
@@ -640,7 +651,7 @@ ff_status trimul_run(const ff_trimul_desc& d, const ff_trimul_weights& w, const 
         a.w_bp = (const bf16_t*)w.w_bp; a.b_bp = (const bf16_t*)w.b_bp; a.w_bg = (const bf16_t*)w.w_bg; a.b_bg = (const bf16_t*)w.b_bg;
         a.w_g = (const bf16_t*)w.w_g; a.b_g = (const bf16_t*)w.b_g; a.ln_g = (const bf16_t*)w.ln_g; a.ln_b = (const bf16_t*)w.ln_b;
         a.w_o = (const bf16_t*)w.w_o; a.b_o = (const bf16_t*)w.b_o; a.lno_g = (const bf16_t*)w.lno_g; a.lno_b = (const bf16_t*)w.lno_b;
-        a.wp1 = m.wp1; a.wp3 = m.wp3; a.wp4 = m.wp4; a.S1 = m.S1; a.C1 = m.C1; a.S3 = m.S3; a.C3 = m.C3; a.S4 = m.S4; a.C4 = m.C4;
+        a.wp1 = m.wp1; a.wp3 = m.wp3; a.wp4 = m.wp4; a.ext1 = m.ext1; a.ext3 = m.ext3; a.ext4 = m.ext4;
         a.cz = cz; a.c = c; a.G = G; a.n_pairs = n_pairs; a.Kp1 = 16 * kc1; a.Kp3 = 16 * kc3;
         const int rows = 64 * n_pairs + 2 * cz;
         Timed t(KK_TM_PREP, st);
@@ -651,7 +662,7 @@ ff_status trimul_run(const ff_trimul_desc& d, const ff_trimul_weights& w, const 
         a.z = (const bf16_t*)z;
         a.sr = d.incoming ? 1 : N; a.sl = d.incoming ? N : 1;
         a.mask = mask; a.N = N; a.Np = Np; a.K = cz; a.C = c; a.cz = cz; a.G = G; a.n_pairs = n_pairs; a.eps = d.ln_eps;
-        a.wp = m.wp1; a.S = m.S1; a.Cn = m.C1; a.a = m.a; a.b = m.b;
+        a.wp = m.wp1; a.ext = m.ext1; a.a = m.a; a.b = m.b;
         const int tiles_m = N * (Np / 32);
         int blocks = (tiles_m + 7) / 8;
         // Large inputs: one persistent block per compute unit with all weights in its LDS.  Small ones (fewer than
@@ -663,8 +674,8 @@ ff_status trimul_run(const ff_trimul_desc& d, const ff_trimul_weights& w, const 
         const int per_cu = split;
         if (blocks > compute_units() * per_cu) blocks = compute_units() * per_cu;
         const dim3 grid(blocks, split);
-        // weights, row sums and offsets, one staged output half-tile [16][32] per wavefront
-        auto smem = [&](int kc) { return (size_t)64 * a.ppb * (kc * 32 + 16) + (size_t)2 * 64 * a.ppb * 4 + (size_t)8 * 16 * 80; };
+        // weights (with their extra step), one staged output half-tile [16][32] per wavefront
+        auto smem = [&](int kc) { return (size_t)64 * a.ppb * (kc * 32 + 16) + (size_t)8 * 16 * 80; };
         hipError_t attr = hipSuccess;
         Timed t(KK_TM_PROJ, st);
 #define FF_TM_PROJ(KCV)                                                                                          \
@@ -706,13 +717,13 @@ ff_status trimul_run(const ff_trimul_desc& d, const ff_trimul_weights& w, const 
         TmOutArgs a{};
         a.x = m.x; a.z = (const bf16_t*)z; a.out = (bf16_t*)out; a.residual = residual ? 1 : 0;
         a.N = N; a.Np = Np; a.C = c; a.cz = cz; a.eps = d.ln_eps;
-        a.wp = m.wp3; a.wg = m.wp4; a.S = m.S3; a.Cn = m.C3; a.Sg = m.S4; a.Cg = m.C4;
+        a.wp = m.wp3; a.wg = m.wp4; a.ext = m.ext3; a.extg = m.ext4;
         const int tiles_m = N * (Np / 32);
         int blocks = (tiles_m + 7) / 8;
         if (blocks > compute_units()) blocks = compute_units();     // one block of eight wavefronts per compute unit
         const dim3 grid(blocks);
         a.wave_bytes = 32 * (2 * cz + 16);
-        const size_t smem = (size_t)cz * (kc3 * 32 + 16) + (size_t)cz * (kc1 * 32 + 16) + (size_t)4 * cz * 4 + (size_t)8 * a.wave_bytes;
+        const size_t smem = (size_t)cz * (kc3 * 32 + 16) + (size_t)cz * (kc1 * 32 + 16) + (size_t)8 * a.wave_bytes;
         hipError_t attr = hipSuccess;
         Timed t(KK_TM_OUT, st);
 #define FF_TM_OUT(KCV, KZV)                                                                                          \
