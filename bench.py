@@ -29,6 +29,7 @@ PEAK_HBM_GBS = 8000.0
 # plain (unpacked) float32 vector instructions: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-operations per second
 # (the published 157.3 TFLOP/s is this rate x 2 for the packed forms, which this build switches off, x 2 for FMA)
 PEAK_VALU_GLANEOPS = 256 * 4 * 16 * 2.4
+VALU_SIMDS = 256 * 4
 
 # Peaks measured on an MI355X of this machine with the library's own probes (a bare loop of bf16
 # 32x32x16 matrix instructions; a plain 256 MiB copy): bench.py measures both again in every run
@@ -221,6 +222,9 @@ def kernel_rooflines(sp, kernels, steps, measured=None):
                 # (at head dims of 64 and more the matrix core would bind; the workloads here have d <= 32)
                 r.update(bound="alu", achieved=r["achieved_glaneops"], peak=PEAK_VALU_GLANEOPS, unit="Glane-op/s",
                          frac=r["frac_alu"])
+                if measured and measured.get("attention_elements_per_s_at_measured_rates"):
+                    # the same elements against what the vector-instruction probes sustain for this kernel's mix
+                    r["frac_of_measured_peak"] = (alu_per_step[name] / 3.0 / sec) / measured["attention_elements_per_s_at_measured_rates"]
             elif bound == "mfma":
                 r.update(bound="mfma", achieved=tf, peak=PEAK_MFMA_BF16_TFLOPS, unit="TFLOP/s", frac=tf / PEAK_MFMA_BF16_TFLOPS)
                 if measured and measured.get("mfma_tflops"):
@@ -257,8 +261,27 @@ def calibrate():
     P.ff_profile_enable(False)
     ms_m, n_m = k["probe: mfma loop"]
     ms_c, n_c = k["probe: copy"]
+    # loops of ONE vector instruction: nanoseconds a SIMD spends per wavefront-wide instruction (1024 SIMDs share the launch)
+    valu_ns = {}
+    for kind, name in enumerate(("fma_f32", "exp_f32", "cvt_pk_bf16_f32", "dot2_f32_bf16")):
+        P.ff_probe_valu(sink, kind, 256)
+        torch.cuda.synchronize()
+        P.ff_profile_enable(True)
+        for _ in range(3):
+            insts = P.ff_probe_valu(sink, kind, 4096)
+        torch.cuda.synchronize()
+        kk = P.ff_profile_collect()
+        P.ff_profile_enable(False)
+        ms_v, n_v = kk["probe: vector loop"]
+        valu_ns[name] = (ms_v / n_v * 1e6) / (insts / VALU_SIMDS)
+    # per score element of the attention kernel: one fused multiply-add (scale and reference), one exponential,
+    # half a pack and half a partial-denominator instruction, each per wavefront of 64 elements
+    attn_ns = valu_ns["fma_f32"] + valu_ns["exp_f32"] + 0.5 * valu_ns["cvt_pk_bf16_f32"] + 0.5 * valu_ns["dot2_f32_bf16"]
     return {"mfma_tflops": flop / (ms_m / n_m * 1e-3) / 1e12, "copy_gbs": 2.0 * (256 << 20) / (ms_c / n_c * 1e-3) / 1e9,
-            "note": "library probes, HIP-event timed: 32x32x16 bf16 matrix-instruction loop, 256 MiB copy (read + written)"}
+            "valu_ns_per_wave_instruction": valu_ns,
+            "attention_elements_per_s_at_measured_rates": 64.0 * VALU_SIMDS / (attn_ns * 1e-9),
+            "note": "library probes, HIP-event timed: 32x32x16 bf16 matrix-instruction loop, 256 MiB copy (read + written), "
+                    "loops of one vector instruction (16 independent registers, 8 wavefronts per SIMD)"}
 
 
 def trimul_flop(sp):

@@ -313,18 +313,24 @@ const char* ff_profile_name(int32_t kind);
 ff_status ff_profile_collect(double* total_ms, int64_t* launches);
 
 /* Calibration probes for the benchmark report (no part of the attention path): what this GPU
- * sustains on a bare loop of 32x32x16 bf16 matrix instructions and on a plain copy, so that
- * roofline fractions can be quoted against measured as well as published peaks.  Both only
- * enqueue one kernel on hip_stream; time them with the launch timer above (kinds
- * "probe: mfma loop", "probe: copy").
+ * sustains on a bare loop of 32x32x16 bf16 matrix instructions, on a plain copy and on loops of one
+ * vector instruction, so that roofline fractions can be quoted against measured as well as published
+ * peaks.  Each only enqueues one kernel on hip_stream; time them with the launch timer above (kinds
+ * "probe: mfma loop", "probe: copy", "probe: vector loop").
  *   ff_probe_mfma: sink = device buffer of ff_probe_sink_bytes() bytes (receives sums nobody reads);
  *                  iters >= 1 rounds of four matrix instructions per wavefront; *flop (host) receives
  *                  the floating-point operations the launch performs.
  *   ff_probe_copy: dst[i] = src[i] for `bytes` bytes (device pointers and size multiples of 16):
  *                  `bytes` read + `bytes` written.
+ *   ff_probe_valu: sink as for ff_probe_mfma; iters >= 1 rounds of 16 independent instructions per
+ *                  wavefront, eight wavefronts per SIMD of a 256-unit chip; kind 0: v_fma_f32, 1: v_exp_f32
+ *                  (the softmax's exponential), 2: v_cvt_pk_bf16_f32 (two floats to a bfloat16 pair),
+ *                  3: v_dot2c_f32_bf16 (the partial denominators); *wave_insts (host) receives the number
+ *                  of wavefront-wide instructions of that kind the launch issues.
  * FF_EINVAL for bad arguments, FF_EHIP if the launch fails. */
 size_t ff_probe_sink_bytes(void);
 ff_status ff_probe_mfma(void* sink, int32_t iters, double* flop, void* hip_stream);
+ff_status ff_probe_valu(void* sink, int32_t kind, int32_t iters, double* wave_insts, void* hip_stream);
 ff_status ff_probe_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
 
 /* Message for the last non-OK status returned on this thread ("" if none). */

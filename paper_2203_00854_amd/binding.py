@@ -124,6 +124,8 @@ def lib() -> C.CDLL:
         L.ff_probe_sink_bytes.argtypes = []
         L.ff_probe_mfma.restype = C.c_int
         L.ff_probe_mfma.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.c_void_p]
+        L.ff_probe_valu.restype = C.c_int
+        L.ff_probe_valu.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_double), C.c_void_p]
         L.ff_probe_copy.restype = C.c_int
         L.ff_probe_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.ff_last_error.restype = C.c_char_p
@@ -367,6 +369,14 @@ def ff_probe_mfma(sink, iters: int) -> float:
     assert sink.numel() * sink.element_size() >= lib().ff_probe_sink_bytes()
     _check(lib().ff_probe_mfma(_ptr(sink), iters, C.byref(flop), _stream()))
     return flop.value
+
+
+def ff_probe_valu(sink, kind: int, iters: int) -> float:
+    """Enqueue the vector-instruction probe of one kind; returns the wavefront-wide instructions of the launch."""
+    n = C.c_double(0.0)
+    assert sink.numel() * sink.element_size() >= lib().ff_probe_sink_bytes()
+    _check(lib().ff_probe_valu(_ptr(sink), kind, iters, C.byref(n), _stream()))
+    return n.value
 
 
 def ff_probe_copy(dst, src):

@@ -1,6 +1,6 @@
 // Calibration probes (diagnostics for the benchmark report, no part of the attention path):
-// what this GPU sustains on a bare bf16 matrix-instruction loop and on a plain copy, so that
-// roofline fractions can be quoted against measured as well as published peaks.
+// what this GPU sustains on a bare bf16 matrix-instruction loop, on a plain copy and on loops of single
+// vector instructions, so that roofline fractions can be quoted against measured as well as published peaks.
 #include "ff_common.h"
 
 namespace ff {
@@ -39,6 +39,34 @@ __global__ __launch_bounds__(256) void k_probe_copy(uint4* __restrict__ dst, con
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
+// Every wavefront issues `iters` rounds of 16 independent vector instructions of one kind (16 registers, so
+// that none waits for the one before it): what one SIMD spends per wavefront-wide instruction of that kind.
+//   0: v_fma_f32   1: v_exp_f32   2: v_cvt_pk_bf16_f32 (two floats -> a bfloat16 pair)   3: v_dot2c_f32_bf16
+template <int KIND>
+__global__ __launch_bounds__(256) void k_probe_valu(float* sink, int iters, float seed) {
+    typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf2;
+    float r[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) r[i] = seed + (float)i * 0.001f + (float)threadIdx.x * 1e-6f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            if (KIND == 0) r[i] = __builtin_fmaf(r[i], 0.999f, 0.001f);
+            else if (KIND == 1) r[i] = __builtin_amdgcn_exp2f(r[i]);
+            else if (KIND == 2) {
+                bf2 t;
+                t[0] = (__bf16)r[i];
+                t[1] = (__bf16)r[(i + 1) & 15];
+                r[i] = __builtin_bit_cast(float, t);
+            } else r[i] = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf2, r[(i + 1) & 15]), __builtin_bit_cast(bf2, 0x3f803f80u), r[i], false);
+        }
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += r[i];
+    sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
 constexpr int kProbeBlocks = 512, kProbeThreads = 512;     // two 8-wavefront blocks per compute unit of a 256-unit chip
 
 }  // namespace ff
@@ -58,6 +86,21 @@ ff_status ff_probe_mfma(void* sink, int32_t iters, double* flop, void* hip_strea
     }
     *flop = (double)kProbeBlocks * (kProbeThreads / 64) * (double)iters * 4.0 * (2.0 * 32 * 32 * 16);
     return check_launch("ff_probe_mfma");
+}
+
+ff_status ff_probe_valu(void* sink, int32_t kind, int32_t iters, double* wave_insts, void* hip_stream) {
+    if (!sink || kind < 0 || kind > 3 || iters < 1 || !wave_insts) return fail(FF_EINVAL, "ff_probe_valu: bad argument");
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int blocks = 1024;                                   // x 256 threads = the sink's size: eight wavefronts per SIMD of a 256-unit chip
+    {
+        Timed t(KK_PROBE_VALU, st);
+        if (kind == 0) hipLaunchKernelGGL(k_probe_valu<0>, dim3(blocks), dim3(256), 0, st, (float*)sink, iters, 0.5f);
+        else if (kind == 1) hipLaunchKernelGGL(k_probe_valu<1>, dim3(blocks), dim3(256), 0, st, (float*)sink, iters, 0.5f);
+        else if (kind == 2) hipLaunchKernelGGL(k_probe_valu<2>, dim3(blocks), dim3(256), 0, st, (float*)sink, iters, 0.5f);
+        else hipLaunchKernelGGL(k_probe_valu<3>, dim3(blocks), dim3(256), 0, st, (float*)sink, iters, 0.5f);
+    }
+    *wave_insts = (double)blocks * 4.0 * (double)iters * 16.0;
+    return check_launch("ff_probe_valu");
 }
 
 ff_status ff_probe_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {
