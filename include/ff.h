@@ -256,8 +256,8 @@ typedef struct {
 } ff_core_desc;
 
 /* Bytes of device workspace (logsumexp and delta per query, dctx, position-contiguous copies of q, k, v and dctx,
- * partial sums of dbias over groups of rows: about six times the size of q, never a score-sized tensor); 0 if desc
- * is invalid or unsupported. */
+ * two tiled copies of the bias, partial sums of dbias over groups of rows: about six times the size of q plus a
+ * few times that of the bias, never a score-sized tensor); 0 if desc is invalid or unsupported. */
 size_t ff_attention_core_backward_workspace_bytes(const ff_core_desc* desc);
 
 /* All tensor pointers are device pointers, 16-byte aligned; gradient tensors must not overlap the inputs or

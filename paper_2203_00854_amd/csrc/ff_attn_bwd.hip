@@ -10,7 +10,9 @@
 // One wavefront per 32-query (or 32-key) tile, four consecutive tiles of one (row, head) per block; the tiles of the
 // other side, which all four contract with, are copied into LDS once per block, a tile ahead of the arithmetic:
 //   k_bwd_transpose  position-contiguous copies [d][L] of q, k and v for the operands whose contraction runs over
-//                positions (k_bwd_stats adds the one of dctx); also the row of ones that stands in for no mask
+//                positions (k_bwd_stats adds the one of dctx); the row of ones that stands in for no mask; and the
+//                bias times sqrt(d), tile by tile in the order of the accumulator registers, once with lane = query
+//                and once with lane = key, so that a bias tile is four 16-byte loads per lane in every kernel
 //   k_bwd_stats  forward recomputation with an online softmax: the logsumexp of every query (base 2), ctx,
 //                dg, dctx and delta
 //   k_bwd_dq     per query tile, over the key tiles: S^T = K Q^T and dP^T = V dctx^T (lane = query, so that
@@ -23,8 +25,10 @@
 // Operands whose contraction runs over the head dim are 16-byte row reads; operands whose contraction runs
 // over keys or queries ("transposed" fragments: lane = channel) are two 8-byte reads of the position-contiguous
 // copies, taken in exactly the order in which the accumulator of the previous contraction leaves its values, so
-// nothing moves between two contractions.  What is added to q.k (bias, -inf of masked keys) and what is
-// subtracted from dP (delta) enter as the accumulators' starting values.
+// nothing moves between two contractions.  What is added to q.k and what is subtracted from dP enter through the
+// matrix core: the bias tile and -delta as the accumulators' starting values, the -inf of masked keys as one more
+// contraction step (key side 0 or -inf, query side 1).  A thread's share of the staging copies (which pieces,
+// from where, to where) is worked out once per block (StagePlan), not per tile.
 // Operand layouts of v_mfma_f32_32x32x16_bf16: A (32 x 16): lane l holds row l%32, columns 8*(l/32)..+7;
 // B (16 x 32): lane l holds column l%32, rows 8*(l/32)..+7; D (32 x 32): lane l holds column l%32, register
 // v holds row 8*(v/4) + 4*(l/32) + v%4.
@@ -70,6 +74,8 @@ struct Args {
     bf16_t* dctx;                            // workspace [R][H][L][D]
     bf16_t *qT, *kT, *vT, *dctxT;            // workspace [R][H][D][Lp]: position-contiguous copies for the transposed operands
     float *lse, *delta;                      // workspace [R*H][Lp]
+    float *biasA, *biasK;                    // workspace [H][Lp/32][Lp/32][4][64][4]: the bias, times sqrt(D), tile by tile in the
+                                             // order of the accumulator registers (biasA: lane = query, biasK: lane = key)
     int R, H, L, Lp;
     float qscale2;                           // log2(e) / sqrt(D)
     float scale;                             // 1 / sqrt(D)
@@ -113,13 +119,40 @@ __global__ __launch_bounds__(256) void k_bwd_transpose(Args a) {
     const int lane = threadIdx.x & 63, col = lane & 31, hf = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nt = a.Lp >> 5;
-    if (blockIdx.x == 0 && blockIdx.y == 0)
+    // blockIdx.y: with a bias 0 = the bias tiles (first, so that their chains of dependent loads run beside the
+    // copies), then q, k, v; without a bias q, k, v
+    const int which = a.bias ? (int)blockIdx.y - 1 : (int)blockIdx.y;
+    if (blockIdx.x == 0 && which == 0)
         for (int n = threadIdx.x; n < a.Lp; n += 256) a.ones[n] = 1.f;
     const int task = blockIdx.x * 4 + wave;
+    if (which < 0) {
+        // The bias tile (it, jt) of head h, times sqrt(D), as the accumulator of the logits holds it: float4 g of
+        // lane (col, hf) = entries 8 g + 4 hf .. + 3 along the register axis.  biasA: lane = query i0 + col, registers
+        // along the keys; biasK: lane = key j0 + col, registers along the queries.  Zeros outside [0, L)^2.
+        if (task >= a.H * nt * nt) return;
+        const int h = task / (nt * nt), rem = task - h * nt * nt, it = rem / nt, jt = rem - it * nt;
+        const float* bh = a.bias + (size_t)h * a.L * a.L;
+        float* ta = a.biasA + (size_t)task * 1024 + lane * 4;
+        float* tk = a.biasK + (size_t)task * 1024 + lane * 4;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            float va[4], vk[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int x = 8 * g + 4 * hf + e;
+                const int ia = it * 32 + col, ja = jt * 32 + x, ik = it * 32 + x, jk = jt * 32 + col;
+                va[e] = (ia < a.L && ja < a.L) ? bh[(size_t)ia * a.L + ja] * a.sqrt_d : 0.f;
+                vk[e] = (ik < a.L && jk < a.L) ? bh[(size_t)ik * a.L + jk] * a.sqrt_d : 0.f;
+            }
+            *reinterpret_cast<float4*>(ta + 256 * g) = make_float4(va[0], va[1], va[2], va[3]);
+            *reinterpret_cast<float4*>(tk + 256 * g) = make_float4(vk[0], vk[1], vk[2], vk[3]);
+        }
+        return;
+    }
     if (task >= a.R * a.H * nt) return;
     const int rh = task / nt, n0 = (task - rh * nt) * 32, n = n0 + col;
-    const bf16_t* src = blockIdx.y == 0 ? a.q : (blockIdx.y == 1 ? a.k : a.v);
-    bf16_t* dst = blockIdx.y == 0 ? a.qT : (blockIdx.y == 1 ? a.kT : a.vT);
+    const bf16_t* src = which == 0 ? a.q : (which == 1 ? a.k : a.v);
+    bf16_t* dst = which == 0 ? a.qT : (which == 1 ? a.kT : a.vT);
     // lane (n, hf) takes channels 8 hf + 16 s .. + 7 of position n
 #pragma unroll
     for (int s = 0; s < (D + 15) / 16; ++s) {
@@ -152,79 +185,33 @@ __device__ __forceinline__ f32x16 zero16() {
     return a;
 }
 
-constexpr int kTilePitch = 36;       // floats per row of a staged 32 x 32 bias tile (16-byte aligned rows, conflict-free reads)
-
 // The logits enter the matrix core's accumulator already holding what is added to q.k: S = (q.k + B) * scale with
 // B[i][j] = bias[h][i][j] * sqrt(d) for a key that may be attended to and -inf for one that is masked or beyond L
-// (exp2 of the base-2 logit then gives weight 0 without any select).  The tile B [i0 .. i0+31][j0 .. j0+31] in the
-// accumulator layout with lane = query: register v = key j0 + 8(v/4) + 4hf + v%4 of query i0 + col.  The bias is
-// read from memory in whole rows (a load instruction covers eight 128-byte rows; bias_rows_fetch, which can run
-// tiles ahead), scaled, given the keys' -inf and turned through the wavefront's own LDS tile (bias_rows_to_tile).
-// FULL: L is a multiple of 32, nothing is out of range.
-template <bool FULL>
-__device__ __forceinline__ void bias_rows_fetch(float4 (&rows)[4], const Args& a, int h, int i0, int j0, int lane) {
-    const int c4 = (lane & 7) * 4;
+// (exp2 of the base-2 logit then gives weight 0 without any select).  The bias part comes from the copies that
+// k_bwd_transpose leaves in the order of the accumulator registers (four 16-byte loads per lane and tile, a
+// contiguous KiB per instruction; bias_tile_fetch can run tiles ahead).  The -inf part is one more matrix
+// instruction: a contraction step whose key side holds 0 or -inf in its first slot and whose query side a one.
+__device__ __forceinline__ void bias_tile_fetch(float4 (&rows)[4], const float* tiles, int h, int nt, int it, int jt, int lane) {
+    const float* p = tiles + (((size_t)h * nt + it) * nt + jt) * 1024 + lane * 4;
 #pragma unroll
-    for (int n = 0; n < 4; ++n) {
-        const int row = 8 * n + (lane >> 3), i = i0 + row, j = j0 + c4;
-        const float* p = a.bias + ((size_t)h * a.L + i) * a.L + j;
-        if (FULL) {
-            rows[n] = *reinterpret_cast<const float4*>(p);
-        } else {
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (i < a.L) {
-                if ((a.L & 3) == 0 && j + 3 < a.L) v = *reinterpret_cast<const float4*>(p);
-                else {
-                    if (j < a.L) v.x = p[0];
-                    if (j + 1 < a.L) v.y = p[1];
-                    if (j + 2 < a.L) v.z = p[2];
-                    if (j + 3 < a.L) v.w = p[3];
-                }
-            }
-            rows[n] = v;
-        }
-    }
+    for (int g = 0; g < 4; ++g) rows[g] = *reinterpret_cast<const float4*>(p + 256 * g);
 }
-// keys: bit n set if key j0 + n may be attended to
-__device__ __forceinline__ void bias_rows_to_tile(f32x16& b, const float4 (&rows)[4], uint32_t keys, float sqrt_d, float* tile, int lane,
-                                                  int col, int hf) {
-    const int c4 = (lane & 7) * 4;
-    const uint32_t kb = keys >> c4;
-    const float m0 = (kb & 1u) ? 0.f : -INFINITY, m1 = (kb & 2u) ? 0.f : -INFINITY;
-    const float m2 = (kb & 4u) ? 0.f : -INFINITY, m3 = (kb & 8u) ? 0.f : -INFINITY;
-#pragma unroll
-    for (int n = 0; n < 4; ++n)
-        *reinterpret_cast<float4*>(tile + (8 * n + (lane >> 3)) * kTilePitch + c4) =
-            make_float4(rows[n].x * sqrt_d + m0, rows[n].y * sqrt_d + m1, rows[n].z * sqrt_d + m2, rows[n].w * sqrt_d + m3);
-    // (LDS operations of one wavefront are carried out in order and the compiler keeps a load behind a store that
-    // may alias it, so the lanes see each other's rows without any wait; a fence here would also wait for the
-    // loads in flight and serialise the tiles)
-    __builtin_amdgcn_wave_barrier();
+__device__ __forceinline__ void rows_to_acc(f32x16& b, const float4 (&rows)[4]) {
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
-        const float4 v = *reinterpret_cast<const float4*>(tile + col * kTilePitch + 8 * g + 4 * hf);
-        b[4 * g] = v.x; b[4 * g + 1] = v.y; b[4 * g + 2] = v.z; b[4 * g + 3] = v.w;
+        b[4 * g] = rows[g].x; b[4 * g + 1] = rows[g].y; b[4 * g + 2] = rows[g].z; b[4 * g + 3] = rows[g].w;
     }
-    __builtin_amdgcn_wave_barrier();
 }
-// the same tile with lane = key: register v = query i0 + 8(v/4) + 4hf + v%4 of key j0 + col; kterm is the lane's own
-// 0 / -inf
-__device__ __forceinline__ void bias_rows_to_tile_by_key(f32x16& b, const float4 (&rows)[4], float kterm, float sqrt_d, float* tile,
-                                                         int lane, int col, int hf) {
-    const int c4 = (lane & 7) * 4;
-#pragma unroll
-    for (int n = 0; n < 4; ++n)
-        *reinterpret_cast<float4*>(tile + (8 * n + (lane >> 3)) * kTilePitch + c4) =
-            make_float4(rows[n].x * sqrt_d, rows[n].y * sqrt_d, rows[n].z * sqrt_d, rows[n].w * sqrt_d);
-    __builtin_amdgcn_wave_barrier();
-#pragma unroll
-    for (int v = 0; v < 16; ++v) b[v] = tile[(8 * (v >> 2) + 4 * hf + (v & 3)) * kTilePitch + col] + kterm;
-    __builtin_amdgcn_wave_barrier();
+// operand fragments of that step: ok = the lane's key may be attended to
+__device__ __forceinline__ Frag key_side(bool ok, int hf) {
+    Frag f;
+    f.u = make_uint4((hf == 0 && !ok) ? 0xff80u : 0u, 0u, 0u, 0u);        // bfloat16 -inf
+    return f;
 }
-// the same without a bias: only the keys' 0 / -inf, straight from the mask bits
-__device__ __forceinline__ void mask_tile(f32x16& b, uint32_t keys, int hf) {
-#pragma unroll
-    for (int v = 0; v < 16; ++v) b[v] = ((keys >> (8 * (v >> 2) + 4 * hf + (v & 3))) & 1u) ? 0.f : -INFINITY;
+__device__ __forceinline__ Frag one_side(int hf) {
+    Frag f;
+    f.u = make_uint4(hf == 0 ? 0x3f80u : 0u, 0u, 0u, 0u);                 // bfloat16 1
+    return f;
 }
 
 // ====================================================================================
@@ -235,7 +222,7 @@ __device__ __forceinline__ void mask_tile(f32x16& b, uint32_t keys, int hf) {
 // from LDS just before the matrix instructions that use them.
 constexpr int kStPitch = 80;                          // bytes per staged row: 32 bf16 + 16 bytes, 16-byte aligned
 constexpr int kStRowsX = 0, kStRowsY = 32 * kStPitch, kStColsX = 64 * kStPitch, kStColsY = 96 * kStPitch;
-constexpr int kStVecA = 128 * kStPitch, kStVecB = kStVecA + 128, kStBytes = kStVecB + 128;
+constexpr int kStVecA = 128 * kStPitch, kStVecB = kStVecA + 128, kStSpare = kStVecB + 128, kStBytes = kStSpare + 16;
 
 struct TileSrc {
     const bf16_t *x, *y;         // [L][D] of the (row, head), or NULL (tile not needed: zeros)
@@ -244,75 +231,73 @@ struct TileSrc {
     int L, Lp;
 };
 
-// 16-byte piece `id` of the tile at position n0: where it comes from (NULL: zeros) and where it goes in the stage
+// A thread moves up to three 16-byte pieces of every tile.  Which pieces, where they come from and where they go in the
+// stage does not depend on the tile, so it is worked out once (StagePlan::init): per piece the address for tile
+// position 0, the bytes per position and the offset in the stage.  A piece nobody needs (its tensor is NULL, or the
+// thread has no third piece) asks for the start of x again and lands in a spare slot of the stage: every load and
+// every store of the loop is unconditional.
 template <int D, bool FULL>
-__device__ __forceinline__ const uint4* stage_piece(const TileSrc& t, int n0, int id, int& dst) {
-    constexpr int PR = D / 8, NR = 32 * PR, NC = 4 * D;
-    if (id < 2 * NR) {
-        const bool second = id >= NR;
-        const int k = second ? id - NR : id, n = k / PR, pc = k - n * PR;
-        dst = (second ? kStRowsY : kStRowsX) + n * kStPitch + pc * 16;
-        const bf16_t* src = second ? t.y : t.x;
-        if (!src || (!FULL && n0 + n >= t.L)) return nullptr;
-        return reinterpret_cast<const uint4*>(src + (size_t)(n0 + n) * D + 8 * pc);
-    }
-    id -= 2 * NR;
-    if (id < 2 * NC) {
-        const bool second = id >= NC;
-        const int k = second ? id - NC : id, e = k >> 2, pc = k & 3;
-        dst = (second ? kStColsY : kStColsX) + e * kStPitch + pc * 16;
-        const bf16_t* src = second ? t.yT : t.xT;
-        if (!src) return nullptr;
-        return reinterpret_cast<const uint4*>(src + (size_t)e * t.Lp + n0 + 8 * pc);
-    }
-    id -= 2 * NC;
-    const bool second = id >= 8;
-    const int pc = second ? id - 8 : id;
-    dst = (second ? kStVecB : kStVecA) + pc * 16;
-    const float* src = second ? t.vb : t.va;
-    if (!src) return nullptr;
-    return reinterpret_cast<const uint4*>(src + n0 + 4 * pc);
-}
-template <int D> constexpr int stage_pieces() { return 2 * 32 * (D / 8) + 2 * 4 * D + 16; }
+struct StagePlan {
+    const unsigned char *b0, *b1, *b2;     // piece address at tile position 0
+    int s0, s1, s2;                        // bytes per position
+    int d0, d1, d2;                        // offset in the stage
+    int n0_, n1_, n2_;                     // !FULL: position of a row piece within the tile (zeros beyond L), else a large negative number
 
-// the (up to three) pieces of thread tid: requested from memory ...
-template <int D, bool FULL>
-__device__ __forceinline__ void stage_fetch(const TileSrc& t, int n0, int tid, uint4& r0, uint4& r1, uint4& r2) {
-    constexpr int N = stage_pieces<D>();
-    int dst;
-    r0 = r1 = r2 = make_uint4(0, 0, 0, 0);
-    if (tid < N) {
-        const uint4* p = stage_piece<D, FULL>(t, n0, tid, dst);
-        if (p) r0 = *p;
+    static __device__ __forceinline__ void piece(const TileSrc& t, int id, const unsigned char*& base, int& stride, int& dst, int& row) {
+        constexpr int PR = D / 8, NR = 32 * PR, NC = 4 * D, N = 2 * NR + 2 * NC + 16;
+        base = reinterpret_cast<const unsigned char*>(t.x); stride = 0; dst = kStSpare; row = -(1 << 30);
+        if (id >= N) return;
+        if (id < 2 * NR) {
+            const bool second = id >= NR;
+            const int k = second ? id - NR : id, n = k / PR, pc = k - n * PR;
+            const bf16_t* src = second ? t.y : t.x;
+            if (!src) return;
+            base = reinterpret_cast<const unsigned char*>(src + (size_t)n * D + 8 * pc); stride = 2 * D;
+            dst = (second ? kStRowsY : kStRowsX) + n * kStPitch + pc * 16; row = n;
+            return;
+        }
+        id -= 2 * NR;
+        if (id < 2 * NC) {
+            const bool second = id >= NC;
+            const int k = second ? id - NC : id, e = k >> 2, pc = k & 3;
+            const bf16_t* src = second ? t.yT : t.xT;
+            if (!src) return;
+            base = reinterpret_cast<const unsigned char*>(src + (size_t)e * t.Lp + 8 * pc); stride = 2;
+            dst = (second ? kStColsY : kStColsX) + e * kStPitch + pc * 16;
+            return;
+        }
+        id -= 2 * NC;
+        const bool second = id >= 8;
+        const int pc = second ? id - 8 : id;
+        const float* src = second ? t.vb : t.va;
+        if (!src) return;
+        base = reinterpret_cast<const unsigned char*>(src + 4 * pc); stride = 4;
+        dst = (second ? kStVecB : kStVecA) + pc * 16;
     }
-    if (N > 256 && tid + 256 < N) {
-        const uint4* p = stage_piece<D, FULL>(t, n0, tid + 256, dst);
-        if (p) r1 = *p;
+    __device__ __forceinline__ void init(const TileSrc& t, int tid) {
+        piece(t, tid, b0, s0, d0, n0_);
+        piece(t, tid + 256, b1, s1, d1, n1_);
+        piece(t, tid + 512, b2, s2, d2, n2_);
     }
-    if (N > 512 && tid + 512 < N) {
-        const uint4* p = stage_piece<D, FULL>(t, n0, tid + 512, dst);
-        if (p) r2 = *p;
+    // the pieces of the tile at position n: requested from memory ...
+    __device__ __forceinline__ void fetch(int n, uint4& r0, uint4& r1, uint4& r2) const {
+        r0 = *reinterpret_cast<const uint4*>(b0 + (size_t)n * s0);
+        r1 = *reinterpret_cast<const uint4*>(b1 + (size_t)n * s1);
+        r2 = *reinterpret_cast<const uint4*>(b2 + (size_t)n * s2);
     }
-}
-// ... and put into the stage
-template <int D, bool FULL>
-__device__ __forceinline__ void stage_store(const TileSrc& t, int n0, int tid, unsigned char* stage, const uint4& r0, const uint4& r1,
-                                            const uint4& r2) {
-    constexpr int N = stage_pieces<D>();
-    int dst;
-    if (tid < N) {
-        stage_piece<D, FULL>(t, n0, tid, dst);
-        *reinterpret_cast<uint4*>(stage + dst) = r0;
+    // ... and put into the stage (L: rows at positions n + row >= L are zeros)
+    __device__ __forceinline__ void store(unsigned char* stage, int n, int L, uint4 r0, uint4 r1, uint4 r2) const {
+        const uint4 z = make_uint4(0, 0, 0, 0);
+        if (!FULL) {
+            if (n + n0_ >= L) r0 = z;
+            if (n + n1_ >= L) r1 = z;
+            if (n + n2_ >= L) r2 = z;
+        }
+        *reinterpret_cast<uint4*>(stage + d0) = r0;
+        *reinterpret_cast<uint4*>(stage + d1) = r1;
+        *reinterpret_cast<uint4*>(stage + d2) = r2;
     }
-    if (N > 256 && tid + 256 < N) {
-        stage_piece<D, FULL>(t, n0, tid + 256, dst);
-        *reinterpret_cast<uint4*>(stage + dst) = r1;
-    }
-    if (N > 512 && tid + 512 < N) {
-        stage_piece<D, FULL>(t, n0, tid + 512, dst);
-        *reinterpret_cast<uint4*>(stage + dst) = r2;
-    }
-}
+};
 // operand fragments out of a stage: rows of the lane's position (as load_rows), channels of the lane (as load_cols)
 template <int D>
 __device__ __forceinline__ void staged_rows(Frag (&f)[(D + 15) / 16], const unsigned char* rows, int col, int hf) {
@@ -351,18 +336,18 @@ constexpr int kAhead = 1;
     const float* mrow = a.mrow + (size_t)r * a.mstride;                                                          \
     {                                                                                                            \
         const int n1 = 32 < a.L ? 32 : 0;         /* (a single tile: fetched twice, the second copy unused) */   \
-        stage_fetch<D, FULL>(src, 0, tid, rs[0][0], rs[0][1], rs[0][2]);                                         \
-        if (kAhead == 2) stage_fetch<D, FULL>(src, n1, tid, rs[1][0], rs[1][1], rs[1][2]);                       \
+        plan.fetch(0, rs[0][0], rs[0][1], rs[0][2]);                                         \
+        if (kAhead == 2) plan.fetch(n1, rs[1][0], rs[1][1], rs[1][2]);                       \
         if (BIAS) {                                                                                              \
-            bias_rows_fetch<FULL>(brow[0], a, h, i0a, 0, lane);                                                  \
-            if (kAhead == 2) bias_rows_fetch<FULL>(brow[1], a, h, i0a, n1, lane);                                \
+            bias_tile_fetch(brow[0], a.biasA, h, nt, i0a >> 5, 0, lane);                                         \
+            if (kAhead == 2) bias_tile_fetch(brow[1], a.biasA, h, nt, i0a >> 5, n1 >> 5, lane);                  \
         }                                                                                                        \
         if (FULL || col < a.L) mk[0] = mrow[col];                                                                \
         if (kAhead == 2 && (FULL || n1 + col < a.L)) mk[1] = mrow[n1 + col];                                     \
     }                                                                                                            \
-    stage_store<D, FULL>(src, 0, tid, s_stage, rs[0][0], rs[0][1], rs[0][2]);                                    \
+    plan.store(s_stage, 0, a.L, rs[0][0], rs[0][1], rs[0][2]);                                    \
     __syncthreads();
-// (bt: what the accumulator of the logits starts from, see bias_rows_fetch.  Every load of the loop is issued on
+// (bt and kx: what the accumulator of the logits starts from, see bias_tile_fetch.  Every load of the loop is issued on
 // every path - the last two tiles ask for themselves again - because a load under a condition makes the compiler
 // wait, at every later wait, also for the loads just issued.)
 #define FF_BWD_Q_HEAD(P)                                                                                         \
@@ -370,17 +355,16 @@ constexpr int kAhead = 1;
     const unsigned char* stage = s_stage + (P) * kStBytes;                                                       \
     constexpr int PF = kAhead == 2 ? (P) : 1 - (P);       /* the register set that receives what is requested now */ \
     const int jn = j0 + 32 * kAhead < a.L ? j0 + 32 * kAhead : j0;                                               \
-    stage_fetch<D, FULL>(src, jn, tid, rs[PF][0], rs[PF][1], rs[PF][2]);                                         \
-    const uint32_t keys = (uint32_t)__ballot((FULL || j0 + col < a.L) && mk[P] != 0.f);                          \
+    plan.fetch(jn, rs[PF][0], rs[PF][1], rs[PF][2]);                                         \
+    const Frag kx = key_side((FULL || j0 + col < a.L) && mk[P] != 0.f, hf);                                      \
     f32x16 bt;                                                                                                   \
-    if (BIAS) bias_rows_to_tile(bt, brow[P], keys, a.sqrt_d, tile, lane, col, hf);                               \
-    else if (FULL && !a.mask) bt = zero16();                                                                     \
-    else mask_tile(bt, keys, hf);                                                                                \
-    if (BIAS) bias_rows_fetch<FULL>(brow[PF], a, h, i0a, jn, lane);                                              \
+    if (BIAS) rows_to_acc(bt, brow[P]);                                                                          \
+    else bt = zero16();                                                                                          \
+    if (BIAS) bias_tile_fetch(brow[PF], a.biasA, h, nt, i0a >> 5, jn >> 5, lane);                                \
     if (FULL || jn + col < a.L) mk[PF] = mrow[jn + col];
 #define FF_BWD_Q_TAIL(P)                                                                                         \
     if (j0 + 32 < a.L)                                                                                           \
-        stage_store<D, FULL>(src, j0 + 32, tid, s_stage + (1 - (P)) * kStBytes, rs[1 - (P)][0], rs[1 - (P)][1], rs[1 - (P)][2]); \
+        plan.store(s_stage + (1 - (P)) * kStBytes, j0 + 32, a.L, rs[1 - (P)][0], rs[1 - (P)][1], rs[1 - (P)][2]); \
     __syncthreads();
 
 // ====================================================================================
@@ -391,7 +375,6 @@ template <int D, bool FULL, bool BIAS>
 __global__ __launch_bounds__(256) void k_bwd_stats(Args a) {
     constexpr int KS = (D + 15) / 16;
     __shared__ __attribute__((aligned(16))) unsigned char s_stage[2 * kStBytes];
-    __shared__ __attribute__((aligned(16))) float s_tile[4 * 32 * kTilePitch];
     const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nt = a.Lp >> 5, bpr = (nt + 3) >> 2;
@@ -399,13 +382,15 @@ __global__ __launch_bounds__(256) void k_bwd_stats(Args a) {
     const int r = rh / a.H, h = rh - r * a.H, i0 = it * 32, i = i0 + col;
     const bool active = it < nt;
     const size_t base = (size_t)rh * a.L * D;
-    float* tile = s_tile + wave * 32 * kTilePitch;
     TileSrc src;
     src.x = a.k + base; src.y = nullptr; src.xT = nullptr; src.yT = a.vT + (size_t)rh * D * a.Lp;
     src.va = nullptr; src.vb = nullptr; src.L = a.L; src.Lp = a.Lp;
     Frag qf[KS];
     load_rows<D, FULL>(qf, a.q + base, active ? i0 : 0, a.L, col, hf);
+    StagePlan<D, FULL> plan;
+    plan.init(src, tid);
     FF_BWD_Q_PROLOGUE
+    const Frag one = one_side(hf);
 
     float m = -INFINITY, l = 0.f;
     f32x16 ctx = zero16();          // ctx^T: lane = query, register v = channel 8(v/4) + 4hf + v%4
@@ -416,7 +401,7 @@ __global__ __launch_bounds__(256) void k_bwd_stats(Args a) {
             Frag kf[KS], vt[2], pf[2];                                                                           \
             staged_rows<D>(kf, stage + kStRowsX, col, hf);                                                       \
             staged_cols<D>(vt, stage + kStColsY, col, hf);                                                       \
-            f32x16 s = bt;                                                                                       \
+            f32x16 s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kx.v, one.v, bt, 0, 0, 0);                        \
             _Pragma("unroll") for (int t = 0; t < KS; ++t)                                                       \
                 s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t].v, qf[t].v, s, 0, 0, 0);                       \
             float tmax = s[0];                                                                                   \
@@ -498,7 +483,6 @@ template <int D, bool FULL, bool BIAS>
 __global__ __launch_bounds__(256, 3) void k_bwd_dq(Args a) {
     constexpr int KS = (D + 15) / 16;
     __shared__ __attribute__((aligned(16))) unsigned char s_stage[2 * kStBytes];
-    __shared__ __attribute__((aligned(16))) float s_tile[4 * 32 * kTilePitch];
     const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nt = a.Lp >> 5, bpr = (nt + 3) >> 2;
@@ -506,7 +490,6 @@ __global__ __launch_bounds__(256, 3) void k_bwd_dq(Args a) {
     const int r = rh / a.H, h = rh - r * a.H, i0 = it * 32, i = i0 + col;
     const bool active = it < nt;
     const size_t base = (size_t)rh * a.L * D;
-    float* tile = s_tile + wave * 32 * kTilePitch;
     TileSrc src;
     src.x = a.k + base; src.y = a.v + base; src.xT = a.kT + (size_t)rh * D * a.Lp; src.yT = nullptr;
     src.va = nullptr; src.vb = nullptr; src.L = a.L; src.Lp = a.Lp;
@@ -514,7 +497,10 @@ __global__ __launch_bounds__(256, 3) void k_bwd_dq(Args a) {
     load_rows<D, FULL>(qf, a.q + base, active ? i0 : 0, a.L, col, hf);
     load_rows<D, FULL>(dcf, a.dctx + base, active ? i0 : 0, a.L, col, hf);
     const float lse = a.lse[(size_t)rh * a.Lp + (active ? i : col)], delta = a.delta[(size_t)rh * a.Lp + (active ? i : col)];
+    StagePlan<D, FULL> plan;
+    plan.init(src, tid);
     FF_BWD_Q_PROLOGUE
+    const Frag one = one_side(hf);
 
     f32x16 dq = zero16();           // dq^T: lane = query, register = channel
     f32x16 ndelta;
@@ -527,7 +513,8 @@ __global__ __launch_bounds__(256, 3) void k_bwd_dq(Args a) {
             Frag kf[KS], vf[KS], kt[2], dsf[2];                                                                  \
             staged_rows<D>(kf, stage + kStRowsX, col, hf);                                                       \
             staged_rows<D>(vf, stage + kStRowsY, col, hf);                                                       \
-            f32x16 s = bt, dp = ndelta;      /* dP - delta: the accumulator starts from -delta */                \
+            f32x16 s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kx.v, one.v, bt, 0, 0, 0);                        \
+            f32x16 dp = ndelta;              /* dP - delta: the accumulator starts from -delta */                \
             _Pragma("unroll") for (int t = 0; t < KS; ++t) {                                                     \
                 s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t].v, qf[t].v, s, 0, 0, 0);                       \
                 dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t].v, dcf[t].v, dp, 0, 0, 0);                    \
@@ -565,7 +552,6 @@ template <int D, bool FULL, bool BIAS>
 __global__ __launch_bounds__(256) void k_bwd_dkv(Args a) {
     constexpr int KS = (D + 15) / 16;
     __shared__ __attribute__((aligned(16))) unsigned char s_stage[2 * kStBytes];
-    __shared__ __attribute__((aligned(16))) float s_tile[4 * 32 * kTilePitch];
     const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nt = a.Lp >> 5, bpr = (nt + 3) >> 2;               // key tiles, blocks per (row, head)
@@ -583,25 +569,25 @@ __global__ __launch_bounds__(256) void k_bwd_dkv(Args a) {
     load_rows<D, FULL>(kf, a.k + base, active ? j0 : 0, a.L, col, hf);
     load_rows<D, FULL>(vf, a.v + base, active ? j0 : 0, a.L, col, hf);
     const bool key_ok = active && (FULL || j < a.L) && a.mrow[(size_t)r * a.mstride + ((FULL || j < a.L) ? j : 0)] != 0.f;
-    // What the accumulator of the logits starts from (see bias_rows_fetch), here with lane = key and register v =
-    // query i0 + 8(v/4) + 4hf + v%4: the bias tile times sqrt(d), or -inf in every register if the lane's key is
-    // masked or beyond L.  Two sets of bias rows (even and odd query tiles), requested two tiles ahead like the
-    // staged tiles.
-    const float kterm = key_ok ? 0.f : -INFINITY;
-    const int j0a = active ? j0 : 0;
-    float* tile = s_tile + wave * 32 * kTilePitch;
+    // What the accumulator of the logits starts from (see bias_tile_fetch), here with lane = key and register v =
+    // query i0 + 8(v/4) + 4hf + v%4: the bias tile times sqrt(d), and -inf in every register if the lane's key is
+    // masked or beyond L.  Two sets of bias tiles (even and odd query tiles), requested ahead like the staged tiles.
+    const Frag kx = key_side(key_ok, hf), one = one_side(hf);
+    const int jta = active ? jt : 0;
     float4 brow[2][4];
     uint4 rs[2][3];
+    StagePlan<D, FULL> plan;
+    plan.init(src, tid);
     {
         const int n1 = 32 < a.L ? 32 : 0;
-        stage_fetch<D, FULL>(src, 0, tid, rs[0][0], rs[0][1], rs[0][2]);
-        if (kAhead == 2) stage_fetch<D, FULL>(src, n1, tid, rs[1][0], rs[1][1], rs[1][2]);
+        plan.fetch(0, rs[0][0], rs[0][1], rs[0][2]);
+        if (kAhead == 2) plan.fetch(n1, rs[1][0], rs[1][1], rs[1][2]);
         if (BIAS) {
-            bias_rows_fetch<FULL>(brow[0], a, h, 0, j0a, lane);
-            if (kAhead == 2) bias_rows_fetch<FULL>(brow[1], a, h, n1, j0a, lane);
+            bias_tile_fetch(brow[0], a.biasK, h, nt, 0, jta, lane);
+            if (kAhead == 2) bias_tile_fetch(brow[1], a.biasK, h, nt, n1 >> 5, jta, lane);
         }
     }
-    stage_store<D, FULL>(src, 0, tid, s_stage, rs[0][0], rs[0][1], rs[0][2]);
+    plan.store(s_stage, 0, a.L, rs[0][0], rs[0][1], rs[0][2]);
     __syncthreads();
 
     f32x16 dk = zero16(), dv = zero16();     // dk^T, dv^T: lane = key, register = channel
@@ -611,13 +597,13 @@ __global__ __launch_bounds__(256) void k_bwd_dkv(Args a) {
         const unsigned char* stage = s_stage + (P) * kStBytes;                                                   \
         constexpr int PF = kAhead == 2 ? (P) : 1 - (P);                                                          \
         const int in = i0 + 32 * kAhead < a.L ? i0 + 32 * kAhead : i0;    /* (the last tiles ask for themselves again) */ \
-        stage_fetch<D, FULL>(src, in, tid, rs[PF][0], rs[PF][1], rs[PF][2]);                                     \
+        plan.fetch(in, rs[PF][0], rs[PF][1], rs[PF][2]);                                     \
         f32x16 s;                                                                                                \
         if (BIAS) {                                                                                              \
-            bias_rows_to_tile_by_key(s, brow[P], kterm, a.sqrt_d, tile, lane, col, hf);                          \
-            bias_rows_fetch<FULL>(brow[PF], a, h, in, j0a, lane);                                                \
+            rows_to_acc(s, brow[P]);                                                                             \
+            bias_tile_fetch(brow[PF], a.biasK, h, nt, in >> 5, jta, lane);                                       \
         } else {                                                                                                 \
-            _Pragma("unroll") for (int v = 0; v < 16; ++v) s[v] = kterm;                                         \
+            s = zero16();                                                                                        \
         }                                                                                                        \
         if (active) {                                                                                            \
             Frag qf[KS], dcf[KS], qt[2], dct[2], pf[2], dsf[2];                                                  \
@@ -628,6 +614,7 @@ __global__ __launch_bounds__(256) void k_bwd_dkv(Args a) {
                 const float4 d4 = *reinterpret_cast<const float4*>(stage + kStVecB + (8 * gq + 4 * hf) * 4);     \
                 dp[4 * gq] = -d4.x; dp[4 * gq + 1] = -d4.y; dp[4 * gq + 2] = -d4.z; dp[4 * gq + 3] = -d4.w;      \
             }                                                                                                    \
+            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(one.v, kx.v, s, 0, 0, 0);      /* -inf for a masked key */ \
             _Pragma("unroll") for (int t = 0; t < KS; ++t) {                                                     \
                 s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[t].v, kf[t].v, s, 0, 0, 0);                       \
                 dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(dcf[t].v, vf[t].v, dp, 0, 0, 0);                    \
@@ -654,8 +641,7 @@ __global__ __launch_bounds__(256) void k_bwd_dkv(Args a) {
             }                                                                                                    \
         }                                                                                                        \
         if (i0 + 32 < a.L)                                                                                       \
-            stage_store<D, FULL>(src, i0 + 32, tid, s_stage + (1 - (P)) * kStBytes, rs[1 - (P)][0], rs[1 - (P)][1], \
-                                 rs[1 - (P)][2]);                                                                \
+            plan.store(s_stage + (1 - (P)) * kStBytes, i0 + 32, a.L, rs[1 - (P)][0], rs[1 - (P)][1], rs[1 - (P)][2]); \
         __syncthreads();                                                                                         \
     }
     for (int tt = 0; 32 * tt < a.L; tt += 2) {
@@ -691,13 +677,13 @@ __global__ __launch_bounds__(256) void k_bwd_dbias(Args a) {
     const int r_begin = chunk * a.rows_per_chunk;
     const int r_end = r_begin + a.rows_per_chunk < a.R ? r_begin + a.rows_per_chunk : a.R;
     const int i = i0 + col;
-    __shared__ __attribute__((aligned(16))) float s_tile[4 * 32 * kTilePitch];
     f32x16 bt;                      // bias tile times sqrt(d) (the tile is the same for every batch row; the key mask is not)
     {
         float4 rows[4];
-        bias_rows_fetch<FULL>(rows, a, h, i0, j0, lane);
-        bias_rows_to_tile(bt, rows, 0xffffffffu, a.sqrt_d, s_tile + wave * 32 * kTilePitch, lane, col, hf);
+        bias_tile_fetch(rows, a.biasA, h, nt, i0 >> 5, j0 >> 5, lane);
+        rows_to_acc(bt, rows);
     }
+    const Frag one = one_side(hf);
     f32x16 acc = zero16();          // lane = query i, register v = key j0 + 8(v/4) + 4hf + v%4
     // the operands of the next batch row are requested before this one is worked on (the last round asks for its
     // own again: a load under a condition would make every wait in the loop a wait for all loads)
@@ -719,7 +705,7 @@ __global__ __launch_bounds__(256) void k_bwd_dbias(Args a) {
 #pragma unroll
         for (int t = 0; t < KS; ++t) { qf[t].u = qn[t].u; dcf[t].u = dcn[t].u; kf[t].u = kn[t].u; vf[t].u = vn[t].u; }
         const float lse = lse_n, delta = delta_n;
-        const uint32_t keys = (uint32_t)__ballot((FULL || j0 + col < a.L) && mk_n != 0.f);
+        const Frag kx = key_side((FULL || j0 + col < a.L) && mk_n != 0.f, hf);
         {
             const int rn = r + 1 < r_end ? r + 1 : r, rh = rn * a.H + h;
             const size_t base = (size_t)rh * a.L * D;
@@ -731,11 +717,8 @@ __global__ __launch_bounds__(256) void k_bwd_dbias(Args a) {
             delta_n = a.delta[(size_t)rh * a.Lp + i];
             if (FULL || j0 + col < a.L) mk_n = a.mrow[(size_t)rn * a.mstride + j0 + col];
         }
-        f32x16 s = bt, dp;          // the accumulators start from the bias tile (-inf for this row's masked keys) and -delta
-        if (!FULL || a.mask) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) s[v] = ((keys >> (8 * (v >> 2) + 4 * hf + (v & 3))) & 1u) ? bt[v] : -INFINITY;
-        }
+        // the accumulators start from the bias tile (and -inf for this row's masked keys) and -delta
+        f32x16 s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kx.v, one.v, bt, 0, 0, 0), dp;
 #pragma unroll
         for (int v = 0; v < 16; ++v) dp[v] = -delta;
 #pragma unroll
@@ -786,7 +769,7 @@ size_t core_backward_workspace(const ff_core_desc& d) {
     const size_t Lp = bwd::round_up(d.length, 32), rh = (size_t)d.rows * d.heads;
     const int chunks = dbias_chunks(d);
     return bwd::align256(Lp * 4) + 2 * bwd::align256(rh * Lp * 4) + bwd::align256(rh * d.length * d.head_dim * 2) +
-           4 * bwd::align256(rh * d.head_dim * Lp * 2) +
+           4 * bwd::align256(rh * d.head_dim * Lp * 2) + 2 * bwd::align256((size_t)d.heads * Lp * Lp * 4) +
            (chunks > 1 ? bwd::align256((size_t)chunks * d.heads * d.length * d.length * 4) : 0);
 }
 
@@ -811,6 +794,9 @@ ff_status core_backward_run(const ff_core_desc& d, const void* q, const void* k,
     a.kT = (bf16_t*)p; p += tbytes;
     a.vT = (bf16_t*)p; p += tbytes;
     a.dctxT = (bf16_t*)p; p += tbytes;
+    const size_t bbytes = align256((size_t)d.heads * a.Lp * a.Lp * 4);
+    a.biasA = (float*)p; p += bbytes;
+    a.biasK = (float*)p; p += bbytes;
     a.row_chunks = bias ? dbias_chunks(d) : 1;
     a.rows_per_chunk = (d.rows + a.row_chunks - 1) / a.row_chunks;
     a.dbias_part = a.row_chunks > 1 ? (float*)p : nullptr;
@@ -834,7 +820,8 @@ ff_status core_backward_run(const ff_core_desc& d, const void* q, const void* k,
         else if (d.head_dim == 16) FF_BWD_D(KERNEL, GRID, 16);                                           \
         else FF_BWD_D(KERNEL, GRID, 32);                                                                 \
     } while (0)
-    const dim3 gt(g1.x, 3);
+    const unsigned bias_blocks = (unsigned)(((size_t)d.heads * nt * nt + 3) / 4);
+    const dim3 gt(bias && bias_blocks > g1.x ? bias_blocks : g1.x, bias ? 4 : 3);      // q, k, v; the bias tiles
     {
         Timed t(KK_BWD_STATS, st);
         if (d.head_dim == 8) hipLaunchKernelGGL((k_bwd_transpose<8>), gt, dim3(256), 0, st, a);
