@@ -19,7 +19,7 @@
 //                logsumexp and delta are lane-local), dS^T, dq^T += K^T dS^T
 //   k_bwd_dkv    per key tile, over the query tiles: S = Q K^T and dP = dctx V^T (lane = key), P and dS,
 //                dv^T += dctx^T P, dk^T += Q^T dS
-//   k_bwd_dbias  per (head, query tile, key tile, chunk of batch rows): dS summed in registers over the rows of the
+//   k_bwd_dbias  per (head, patch of 4 x 4 tiles, chunk of batch rows), a wavefront per tile: dS summed in registers over the rows of the
 //                chunk, the chunks' partial sums added in a fixed order by a small second kernel (deterministic,
 //                no atomics)
 // Operands whose contraction runs over the head dim are 16-byte row reads; operands whose contraction runs
@@ -664,72 +664,150 @@ __global__ __launch_bounds__(256) void k_bwd_dkv(Args a) {
 }
 
 // ====================================================================================
-template <int D, bool FULL, bool BIAS>
-__global__ __launch_bounds__(256) void k_bwd_dbias(Args a) {
-    constexpr int KS = (D + 15) / 16;
-    const int lane = threadIdx.x & 63, col = lane & 31, hf = lane >> 5;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int nt = a.Lp >> 5;
-    const int task = blockIdx.x * 4 + wave;
-    if (task >= a.row_chunks * a.H * nt * nt) return;
-    const int chunk = task / (a.H * nt * nt), t2 = task - chunk * a.H * nt * nt;
-    const int h = t2 / (nt * nt), rem = t2 - h * nt * nt, i0 = (rem / nt) * 32, j0 = (rem - (rem / nt) * nt) * 32;
+// dbias: block = 16 wavefronts = a patch of 4 x 4 tiles of one head and one chunk of batch rows; wavefront (wi, wj)
+// sums dS of tile (it0 + wi, jt0 + wj) over the rows of the chunk in registers.  Per batch row the patch needs the
+// q and dctx rows of four query tiles and the k and v rows of four key tiles (16 operand tiles, 2 KiB per result
+// tile instead of the 8 KiB a wavefront on its own would fetch), logsumexp and delta of its 128 queries and the mask
+// entries of its 128 keys.  The block copies them global -> registers -> LDS (two stages, one barrier per row); a
+// thread's share is two 16-byte pieces and one float per row, so that a row is requested two iterations before it is
+// needed at the price of nine registers.
+constexpr int kDbOperand = 32 * kStPitch;                 // bytes of a staged operand tile [32][D]
+constexpr int kDbVec = 16 * kDbOperand;                   // then logsumexp [128], delta [128], key mask [128] (floats)
+constexpr int kDbStage = kDbVec + 3 * 128 * 4;
+
+template <int D, bool FULL>
+__global__ __launch_bounds__(1024) void k_bwd_dbias(Args a) {
+    constexpr int KS = (D + 15) / 16, PR = D / 8, NP = 16 * 32 * PR;      // 16-byte row pieces per batch row
+    extern __shared__ __attribute__((aligned(16))) unsigned char s_db[];
+    const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), wi = wave >> 2, wj = wave & 3;
+    const int nt = a.Lp >> 5, np = (nt + 3) >> 2;
+    const int chunk = blockIdx.x / (a.H * np * np), rem = blockIdx.x - chunk * a.H * np * np;
+    const int h = rem / (np * np), pp = rem - h * np * np, it0 = 4 * (pp / np), jt0 = 4 * (pp - (pp / np) * np);
+    const int it = it0 + wi, jt = jt0 + wj;
+    const bool active = it < nt && jt < nt;
     const int r_begin = chunk * a.rows_per_chunk;
     const int r_end = r_begin + a.rows_per_chunk < a.R ? r_begin + a.rows_per_chunk : a.R;
-    const int i = i0 + col;
-    f32x16 bt;                      // bias tile times sqrt(d) (the tile is the same for every batch row; the key mask is not)
+    const int i0 = it * 32, j0 = jt * 32, i = i0 + col;
+    if (r_begin >= r_end) return;                          // (whole block)
+
+    // ---- the thread's pieces: address for batch row 0, offset in a stage; rows beyond L are staged as zeros
+    const size_t row_stride = (size_t)a.H * a.L * D;       // elements from a batch row to the next
+    // (piece tid + 1024, which exists at D = 32 only, is the same row and piece of the operand eight further on)
+    constexpr bool TWO = NP > 1024;
+    static_assert(NP == 2048 || NP <= 1024, "one or two pieces for every thread");
+    const bf16_t *pb0, *pb1;
+    int pd0;
+    bool pz0, pz1;
     {
+        auto plan = [&](int p, const bf16_t*& base, int& dst, bool& zero) {
+            const bool has = p < NP;
+            const int pq = has ? p : 0;
+            const int o = pq / (32 * PR), n = (pq - o * 32 * PR) / PR, pc = pq - (pq / PR) * PR;
+            const bf16_t* t = o < 4 ? a.q : (o < 8 ? a.dctx : (o < 12 ? a.k : a.v));
+            const int pos = ((o & 3) + (o < 8 ? it0 : jt0)) * 32 + n;
+            const bool ok = pos < a.L;
+            base = t + ((size_t)h * a.L + (ok ? pos : 0)) * D + 8 * pc;
+            dst = has ? o * kDbOperand + n * kStPitch + pc * 16 : -1;
+            zero = !ok;
+        };
+        int unused;
+        plan(tid, pb0, pd0, pz0);
+        plan(TWO ? tid + 1024 : tid, pb1, unused, pz1);
+    }
+    // threads 0 .. 383: one float of logsumexp | delta | key mask per row
+    const float* vb = a.lse;
+    int vstride = 0;                                       // (floats from a batch row to the next: below 2^31)
+    int vd = -1;
+    bool vz = false;
+    if (tid < 384) {
+        const int kind = tid >> 7, x = tid & 127;
+        if (kind < 2) {
+            const int q = it0 * 32 + x;
+            vb = (kind == 0 ? a.lse : a.delta) + (size_t)h * a.Lp + (q < a.Lp ? q : 0);
+            vstride = a.H * a.Lp;
+        } else {
+            const int j = jt0 * 32 + x;
+            vz = j >= a.L;
+            vb = a.mrow + (vz ? 0 : j);
+            vstride = a.mstride;
+        }
+        vd = kDbVec + kind * 512 + x * 4;
+    }
+#define FF_DB_FETCH(R, ROW)                                                                         \
+    {                                                                                               \
+        const int rr_ = (ROW) < r_end ? (ROW) : r_end - 1;      /* (past the end: the last row again) */ \
+        R##a = *reinterpret_cast<const uint4*>(pb0 + (size_t)rr_ * row_stride);                     \
+        if (TWO) R##b = *reinterpret_cast<const uint4*>(pb1 + (size_t)rr_ * row_stride);            \
+        R##v = vb[rr_ * vstride];                                                                   \
+    }
+#define FF_DB_STORE(R, STAGE)                                                                       \
+    {                                                                                               \
+        /* (through opaque registers: pieces that go from a load straight to an LDS store end up in scratch memory otherwise) */ \
+        uint32_t a0_ = R##a.x, a1_ = R##a.y, a2_ = R##a.z, a3_ = R##a.w, b0_ = R##b.x, b1_ = R##b.y, b2_ = R##b.z, b3_ = R##b.w; \
+        asm volatile("" : "+v"(a0_), "+v"(a1_), "+v"(a2_), "+v"(a3_), "+v"(b0_), "+v"(b1_), "+v"(b2_), "+v"(b3_));      \
+        if (pz0) a0_ = a1_ = a2_ = a3_ = 0u;                                                        \
+        if (pz1) b0_ = b1_ = b2_ = b3_ = 0u;                                                        \
+        if (pd0 >= 0) *reinterpret_cast<uint4*>((STAGE) + pd0) = make_uint4(a0_, a1_, a2_, a3_);    \
+        if (TWO) *reinterpret_cast<uint4*>((STAGE) + pd0 + 8 * kDbOperand) = make_uint4(b0_, b1_, b2_, b3_); \
+        if (vd >= 0) *reinterpret_cast<float*>((STAGE) + vd) = vz ? 0.f : R##v;                     \
+    }
+    // two register sets, by name (a copy from one set to another would have to wait for the load that fills it; a
+    // third set spilled, and a spilled load result is waited for at once, which undoes the whole pipeline)
+    uint4 rAa, rAb = make_uint4(0, 0, 0, 0), rBa, rBb = make_uint4(0, 0, 0, 0);
+    float rAv, rBv;
+    FF_DB_FETCH(rA, r_begin)
+    FF_DB_FETCH(rB, r_begin + 1)
+
+    f32x16 bt = zero16();           // bias tile times sqrt(d) (the same for every batch row; the key mask is not)
+    if (active) {
         float4 rows[4];
-        bias_tile_fetch(rows, a.biasA, h, nt, i0 >> 5, j0 >> 5, lane);
+        bias_tile_fetch(rows, a.biasA, h, nt, it, jt, lane);
         rows_to_acc(bt, rows);
     }
     const Frag one = one_side(hf);
     f32x16 acc = zero16();          // lane = query i, register v = key j0 + 8(v/4) + 4hf + v%4
-    // the operands of the next batch row are requested before this one is worked on (the last round asks for its
-    // own again: a load under a condition would make every wait in the loop a wait for all loads)
-    Frag qn[KS], dcn[KS], kn[KS], vn[KS];
-    float lse_n, delta_n, mk_n = 1.f;
-    {
-        const int rh = r_begin * a.H + h;
-        const size_t base = (size_t)rh * a.L * D;
-        load_rows<D, FULL>(qn, a.q + base, i0, a.L, col, hf);
-        load_rows<D, FULL>(dcn, a.dctx + base, i0, a.L, col, hf);
-        load_rows<D, FULL>(kn, a.k + base, j0, a.L, col, hf);
-        load_rows<D, FULL>(vn, a.v + base, j0, a.L, col, hf);
-        lse_n = a.lse[(size_t)rh * a.Lp + i];
-        delta_n = a.delta[(size_t)rh * a.Lp + i];
-        if (FULL || j0 + col < a.L) mk_n = a.mrow[(size_t)r_begin * a.mstride + j0 + col];
+    FF_DB_STORE(rA, s_db)
+    __syncthreads();
+    // Row r: the set FREE (its row is in the stage) asks for row r + 2, the stage is worked on, the set NEXT (row r + 1,
+    // requested one row ago) goes into the other stage.
+#define FF_DB_ROW(FREE, NEXT)                                                                                    \
+    {                                                                                                            \
+        const unsigned char* stage = s_db + ((r - r_begin) & 1) * kDbStage;                                      \
+        FF_DB_FETCH(FREE, r + 2)                                                                                 \
+        if (active) {                                                                                            \
+            Frag qf[KS], dcf[KS], kf[KS], vf[KS];                                                                \
+            staged_rows<D>(qf, stage + wi * kDbOperand, col, hf);                                                \
+            staged_rows<D>(dcf, stage + (4 + wi) * kDbOperand, col, hf);                                         \
+            staged_rows<D>(kf, stage + (8 + wj) * kDbOperand, col, hf);                                          \
+            staged_rows<D>(vf, stage + (12 + wj) * kDbOperand, col, hf);                                         \
+            const float lse = *reinterpret_cast<const float*>(stage + kDbVec + (wi * 32 + col) * 4);             \
+            const float delta = *reinterpret_cast<const float*>(stage + kDbVec + 512 + (wi * 32 + col) * 4);     \
+            const float mk = *reinterpret_cast<const float*>(stage + kDbVec + 1024 + (wj * 32 + col) * 4);       \
+            const Frag kx = key_side(mk != 0.f, hf);                                                             \
+            /* the accumulators start from the bias tile (and -inf for this row's masked keys) and -delta */      \
+            f32x16 s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kx.v, one.v, bt, 0, 0, 0), dp;                    \
+            _Pragma("unroll") for (int v = 0; v < 16; ++v) dp[v] = -delta;                                       \
+            _Pragma("unroll") for (int t = 0; t < KS; ++t) {                                                     \
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t].v, qf[t].v, s, 0, 0, 0);                       \
+                dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t].v, dcf[t].v, dp, 0, 0, 0);                    \
+            }                                                                                                    \
+            _Pragma("unroll") for (int v = 0; v < 16; ++v)                                                       \
+                acc[v] += __builtin_amdgcn_exp2f(s[v] * a.qscale2 - lse) * dp[v];                                \
+        }                                                                                                        \
+        if (r + 1 < r_end) FF_DB_STORE(NEXT, s_db + ((r + 1 - r_begin) & 1) * kDbStage)                          \
+        __syncthreads();                                                                                         \
+        ++r;                                                                                                     \
     }
-    for (int r = r_begin; r < r_end; ++r) {
-        Frag qf[KS], dcf[KS], kf[KS], vf[KS];
-#pragma unroll
-        for (int t = 0; t < KS; ++t) { qf[t].u = qn[t].u; dcf[t].u = dcn[t].u; kf[t].u = kn[t].u; vf[t].u = vn[t].u; }
-        const float lse = lse_n, delta = delta_n;
-        const Frag kx = key_side((FULL || j0 + col < a.L) && mk_n != 0.f, hf);
-        {
-            const int rn = r + 1 < r_end ? r + 1 : r, rh = rn * a.H + h;
-            const size_t base = (size_t)rh * a.L * D;
-            load_rows<D, FULL>(qn, a.q + base, i0, a.L, col, hf);
-            load_rows<D, FULL>(dcn, a.dctx + base, i0, a.L, col, hf);
-            load_rows<D, FULL>(kn, a.k + base, j0, a.L, col, hf);
-            load_rows<D, FULL>(vn, a.v + base, j0, a.L, col, hf);
-            lse_n = a.lse[(size_t)rh * a.Lp + i];
-            delta_n = a.delta[(size_t)rh * a.Lp + i];
-            if (FULL || j0 + col < a.L) mk_n = a.mrow[(size_t)rn * a.mstride + j0 + col];
-        }
-        // the accumulators start from the bias tile (and -inf for this row's masked keys) and -delta
-        f32x16 s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kx.v, one.v, bt, 0, 0, 0), dp;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) dp[v] = -delta;
-#pragma unroll
-        for (int t = 0; t < KS; ++t) {
-            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t].v, qf[t].v, s, 0, 0, 0);
-            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t].v, dcf[t].v, dp, 0, 0, 0);
-        }
-#pragma unroll
-        for (int v = 0; v < 16; ++v) acc[v] += __builtin_amdgcn_exp2f(s[v] * a.qscale2 - lse) * dp[v];
+    for (int r = r_begin; r < r_end;) {
+        FF_DB_ROW(rA, rB)
+        if (r >= r_end) break;
+        FF_DB_ROW(rB, rA)
     }
-    if (i < a.L) {
+#undef FF_DB_ROW
+#undef FF_DB_FETCH
+#undef FF_DB_STORE
+    if (active && i < a.L) {
         float* out = a.row_chunks > 1 ? a.dbias_part + (size_t)chunk * a.H * a.L * a.L : a.dbias;
         float* drow = out + ((size_t)h * a.L + i) * a.L;
 #pragma unroll
@@ -756,11 +834,12 @@ bool core_backward_supported(const ff_core_desc& d) {
     return d.dtype == FF_BF16 && (d.head_dim == 8 || d.head_dim == 16 || d.head_dim == 32);
 }
 
-// Row chunks of the bias gradient: enough (head, tile, tile, chunk) wavefronts to fill the chip, at least 8 rows each.
+// Row chunks of the bias gradient: enough (head, patch of 4 x 4 tiles, chunk) blocks for one per compute unit, at
+// least 8 rows each.
 static int dbias_chunks(const ff_core_desc& d) {
-    const int nt = (d.length + 31) / 32;
-    const long tasks = (long)d.heads * nt * nt;
-    int chunks = (int)((4096 + tasks - 1) / tasks);
+    const int nt = (d.length + 31) / 32, np = (nt + 3) / 4;
+    const long patches = (long)d.heads * np * np;
+    int chunks = (int)((256 + patches - 1) / patches);
     if (chunks > d.rows / 8) chunks = d.rows / 8;
     return chunks < 1 ? 1 : chunks;
 }
@@ -804,7 +883,7 @@ ff_status core_backward_run(const ff_core_desc& d, const void* q, const void* k,
     a.scale = 1.f / sqrtf((float)d.head_dim);
     a.sqrt_d = sqrtf((float)d.head_dim);
     const int nt = a.Lp / 32;
-    const dim3 g1((unsigned)((rh * nt + 3) / 4)), g2((unsigned)(((size_t)a.row_chunks * d.heads * nt * nt + 3) / 4));
+    const dim3 g1((unsigned)((rh * nt + 3) / 4)), g2((unsigned)((size_t)a.row_chunks * d.heads * ((nt + 3) / 4) * ((nt + 3) / 4)));
     const bool full = d.length % 32 == 0;        // nothing out of range: the kernels without bounds checks
 #define FF_BWD_D(KERNEL, GRID, DV)                                                                       \
     do {                                                                                                 \
@@ -833,7 +912,22 @@ ff_status core_backward_run(const ff_core_desc& d, const void* q, const void* k,
     FF_BWD(k_bwd_dq, g4, KK_BWD_DQ);
     FF_BWD(k_bwd_dkv, g4, KK_BWD_DKV);
     if (bias) {
-        FF_BWD(k_bwd_dbias, g2, KK_BWD_DBIAS);
+        {
+            Timed t(KK_BWD_DBIAS, st);
+            hipError_t attr = hipSuccess;
+#define FF_BWD_DB(DV, FV)                                                                                        \
+    do {                                                                                                         \
+        static const hipError_t once = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_bwd_dbias<DV, FV>), \
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kDbStage); \
+        attr = once;                                                                                             \
+        if (once == hipSuccess) hipLaunchKernelGGL((k_bwd_dbias<DV, FV>), g2, dim3(1024), 2 * kDbStage, st, a);  \
+    } while (0)
+            if (d.head_dim == 8) { if (full) FF_BWD_DB(8, true); else FF_BWD_DB(8, false); }
+            else if (d.head_dim == 16) { if (full) FF_BWD_DB(16, true); else FF_BWD_DB(16, false); }
+            else { if (full) FF_BWD_DB(32, true); else FF_BWD_DB(32, false); }
+#undef FF_BWD_DB
+            if (attr != hipSuccess) return fail(FF_EHIP, "k_bwd_dbias: dynamic LDS limit: %s", hipGetErrorString(attr));
+        }
         if (a.row_chunks > 1) {
             Timed t(KK_BWD_DBIAS, st);
             hipLaunchKernelGGL(k_bwd_dbias_reduce, dim3(1024), dim3(256), 0, st, a);
