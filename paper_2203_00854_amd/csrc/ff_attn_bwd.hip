@@ -392,7 +392,9 @@ __global__ __launch_bounds__(256) void k_bwd_stats(Args a) {
     FF_BWD_Q_PROLOGUE
     const Frag one = one_side(hf);
 
-    float m = -INFINITY, l = 0.f;
+    // (the reference starts finite: exp2(-inf - m) is 0 for a masked key, not NaN, also before the first valid one)
+    constexpr float kSlack = 8.f;
+    float m = -1e30f, l = 0.f;
     f32x16 ctx = zero16();          // ctx^T: lane = query, register v = channel 8(v/4) + 4hf + v%4
 #define FF_BWD_STATS_TILE(P)                                                                                     \
     {                                                                                                            \
@@ -406,18 +408,24 @@ __global__ __launch_bounds__(256) void k_bwd_stats(Args a) {
                 s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t].v, qf[t].v, s, 0, 0, 0);                       \
             float tmax = s[0];                                                                                   \
             _Pragma("unroll") for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, s[v]);                             \
-            tmax = fmaxf(tmax, other_half(tmax)) * a.qscale2;       /* (qscale2 > 0) */                          \
-            const float m_new = fmaxf(m, tmax);                                                                  \
-            /* (nothing valid so far: every weight of the tile is zero and nothing is rescaled) */               \
-            const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m - m_new);                    \
+            tmax *= a.qscale2;                                      /* (qscale2 > 0) */                          \
+            /* m is the query's reference for the exponentials (the same in its two lanes), not its exact       \
+               maximum: it moves, and the sums are rescaled, only when a logit of the tile exceeds it by more    \
+               than kSlack - after a query's first tiles almost never, and then the tile pays neither for the    \
+               exchange between the halves nor for the rescaling; weights stay below 2^kSlack */                 \
+            if (__builtin_amdgcn_ballot_w64(tmax > m + kSlack) != 0) {                                           \
+                const float m_new = fmaxf(m, fmaxf(tmax, other_half(tmax)));                                     \
+                const float alpha = __builtin_amdgcn_exp2f(m - m_new);                                           \
+                _Pragma("unroll") for (int v = 0; v < 16; ++v) ctx[v] *= alpha;                                  \
+                l *= alpha;                                                                                      \
+                m = m_new;                                                                                       \
+            }                                                                                                    \
             float lt = 0.f;                                                                                      \
             _Pragma("unroll") for (int v = 0; v < 16; ++v) {                                                     \
-                s[v] = m_new == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(s[v] * a.qscale2 - m_new);              \
+                s[v] = __builtin_amdgcn_exp2f(s[v] * a.qscale2 - m);                                             \
                 lt += s[v];                                                                                      \
-                ctx[v] *= alpha;                                                                                 \
             }                                                                                                    \
-            l = l * alpha + lt;                                                                                  \
-            m = m_new;                                                                                           \
+            l += lt;                                                                                             \
             pack_rows(pf, s);                                                                                    \
             _Pragma("unroll") for (int t = 0; t < 2; ++t)                                                        \
                 ctx = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt[t].v, pf[t].v, ctx, 0, 0, 0);                   \
