@@ -274,11 +274,25 @@ def calibrate():
         P.ff_profile_enable(False)
         ms_v, n_v = kk["probe: vector loop"]
         valu_ns[name] = (ms_v / n_v * 1e6) / (insts / VALU_SIMDS)
+    # rounds of four matrix instructions with vector instructions between them: do the two overlap?
+    mix_ns = {}
+    for kind, name in ((4, "4_mfma"), (5, "4_mfma_16_fma"), (6, "4_mfma_32_fma"), (7, "4_mfma_16_exp")):
+        P.ff_probe_valu(sink, kind, 256)
+        torch.cuda.synchronize()
+        P.ff_profile_enable(True)
+        for _ in range(3):
+            rounds = P.ff_probe_valu(sink, kind, 2048)
+        torch.cuda.synchronize()
+        kk = P.ff_profile_collect()
+        P.ff_profile_enable(False)
+        ms_v, n_v = kk["probe: vector loop"]
+        mix_ns[name] = (ms_v / n_v * 1e6) / (rounds / VALU_SIMDS)
     # per score element of the attention kernel: one fused multiply-add (scale and reference), one exponential,
     # half a pack and half a partial-denominator instruction, each per wavefront of 64 elements
     attn_ns = valu_ns["fma_f32"] + valu_ns["exp_f32"] + 0.5 * valu_ns["cvt_pk_bf16_f32"] + 0.5 * valu_ns["dot2_f32_bf16"]
     return {"mfma_tflops": flop / (ms_m / n_m * 1e-3) / 1e12, "copy_gbs": 2.0 * (256 << 20) / (ms_c / n_c * 1e-3) / 1e9,
             "valu_ns_per_wave_instruction": valu_ns,
+            "ns_per_round_of_4_matrix_instructions_per_wavefront": mix_ns,
             "attention_elements_per_s_at_measured_rates": 64.0 * VALU_SIMDS / (attn_ns * 1e-9),
             "note": "library probes, HIP-event timed: 32x32x16 bf16 matrix-instruction loop, 256 MiB copy (read + written), "
                     "loops of one vector instruction (16 independent registers, 8 wavefronts per SIMD)"}

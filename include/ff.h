@@ -326,7 +326,10 @@ ff_status ff_profile_collect(double* total_ms, int64_t* launches);
  *                  wavefront, eight wavefronts per SIMD of a 256-unit chip; kind 0: v_fma_f32, 1: v_exp_f32
  *                  (the softmax's exponential), 2: v_cvt_pk_bf16_f32 (two floats to a bfloat16 pair),
  *                  3: v_dot2c_f32_bf16 (the partial denominators); *wave_insts (host) receives the number
- *                  of wavefront-wide instructions of that kind the launch issues.
+ *                  of wavefront-wide instructions of that kind the launch issues.  Kinds 4 .. 7 ask whether
+ *                  matrix and vector instructions overlap: rounds of four independent 32x32x16 bf16 matrix
+ *                  instructions with nothing (4), 16 multiply-adds (5), 32 multiply-adds (6) or 16
+ *                  exponentials (7) spread between them; *wave_insts then receives the number of rounds.
  * FF_EINVAL for bad arguments, FF_EHIP if the launch fails. */
 size_t ff_probe_sink_bytes(void);
 ff_status ff_probe_mfma(void* sink, int32_t iters, double* flop, void* hip_stream);

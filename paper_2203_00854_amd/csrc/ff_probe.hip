@@ -67,6 +67,46 @@ __global__ __launch_bounds__(256) void k_probe_valu(float* sink, int iters, floa
     sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
+// Do matrix and vector instructions of one SIMD overlap?  Every wavefront issues `iters` rounds of four independent
+// 32x32x16 bf16 matrix instructions with NV independent vector instructions (multiply-adds, or exponentials if EXP)
+// spread evenly between them.
+template <int NV, bool EXP>
+__global__ __launch_bounds__(256) void k_probe_mix(float* sink, int iters, float seed) {
+    probe_bf16x8 a, b;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        a[i] = (__bf16)(0.001f * (float)((threadIdx.x + i) & 7));
+        b[i] = (__bf16)(0.002f * (float)((threadIdx.x + 3 * i) & 7));
+    }
+    probe_f32x16 c[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) c[t][v] = 0.f;
+    float r[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) r[i] = seed + (float)i * 0.001f + (float)threadIdx.x * 1e-6f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            c[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c[t], 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < NV / 4; ++i) {
+                const int k = (t * (NV / 4) + i) & 15;
+                r[k] = EXP ? __builtin_amdgcn_exp2f(r[k]) : __builtin_fmaf(r[k], 0.999f, 0.001f);
+            }
+        }
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += r[i];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s += c[t][v];
+    sink[(size_t)blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
 constexpr int kProbeBlocks = 512, kProbeThreads = 512;     // two 8-wavefront blocks per compute unit of a 256-unit chip
 
 }  // namespace ff
@@ -89,7 +129,7 @@ ff_status ff_probe_mfma(void* sink, int32_t iters, double* flop, void* hip_strea
 }
 
 ff_status ff_probe_valu(void* sink, int32_t kind, int32_t iters, double* wave_insts, void* hip_stream) {
-    if (!sink || kind < 0 || kind > 3 || iters < 1 || !wave_insts) return fail(FF_EINVAL, "ff_probe_valu: bad argument");
+    if (!sink || kind < 0 || kind > 7 || iters < 1 || !wave_insts) return fail(FF_EINVAL, "ff_probe_valu: bad argument");
     hipStream_t st = (hipStream_t)hip_stream;
     const int blocks = 1024;                                   // x 256 threads = the sink's size: eight wavefronts per SIMD of a 256-unit chip
     {
@@ -97,9 +137,14 @@ ff_status ff_probe_valu(void* sink, int32_t kind, int32_t iters, double* wave_in
         if (kind == 0) hipLaunchKernelGGL(k_probe_valu<0>, dim3(blocks), dim3(256), 0, st, (float*)sink, iters, 0.5f);
         else if (kind == 1) hipLaunchKernelGGL(k_probe_valu<1>, dim3(blocks), dim3(256), 0, st, (float*)sink, iters, 0.5f);
         else if (kind == 2) hipLaunchKernelGGL(k_probe_valu<2>, dim3(blocks), dim3(256), 0, st, (float*)sink, iters, 0.5f);
-        else hipLaunchKernelGGL(k_probe_valu<3>, dim3(blocks), dim3(256), 0, st, (float*)sink, iters, 0.5f);
+        else if (kind == 3) hipLaunchKernelGGL(k_probe_valu<3>, dim3(blocks), dim3(256), 0, st, (float*)sink, iters, 0.5f);
+        else if (kind == 4) hipLaunchKernelGGL((k_probe_mix<0, false>), dim3(blocks), dim3(256), 0, st, (float*)sink, iters, 0.5f);
+        else if (kind == 5) hipLaunchKernelGGL((k_probe_mix<16, false>), dim3(blocks), dim3(256), 0, st, (float*)sink, iters, 0.5f);
+        else if (kind == 6) hipLaunchKernelGGL((k_probe_mix<32, false>), dim3(blocks), dim3(256), 0, st, (float*)sink, iters, 0.5f);
+        else hipLaunchKernelGGL((k_probe_mix<16, true>), dim3(blocks), dim3(256), 0, st, (float*)sink, iters, 0.5f);
     }
-    *wave_insts = (double)blocks * 4.0 * (double)iters * 16.0;
+    // kinds 0 .. 3: instructions of the kind; kinds 4 .. 7: rounds (of four matrix instructions each)
+    *wave_insts = (double)blocks * 4.0 * (double)iters * (kind < 4 ? 16.0 : 1.0);
     return check_launch("ff_probe_valu");
 }
 
