@@ -6,10 +6,12 @@
 //   o[i,h] = sum_s P[i,h,s] v[s,i];  out[s,i] = W_o (sigmoid(W_g mn[s,i] + b_g) * o[i]) + b_o
 //
 // The module is linear in N_seq and moves far more bytes than it computes: two reads of m and one write of
-// out bound it (HBM).  Four launches:
-//   k_gca_prep     folds the LayerNorm gain into the weights (W' = bf16(W * gamma), C = W beta (+ bias)), writes
-//                  W_o in the operand order of the last contraction and, for the gate rows, the row sums of W'
-//                  and the offsets C as bfloat16 pairs (one more contraction step of the gate GEMM)
+// out bound it (HBM).  Three launches:
+//   (prep_row)     the LayerNorm gain folded into the weights (W' = bf16(W * gamma), C = W beta (+ bias)), W_o in the
+//                  operand order of the last contraction and, for the gate rows, the row sums of W' and the
+//                  offsets C as bfloat16 pairs (one more contraction step of the gate GEMM): what the second and
+//                  third launch need of it is written by the last blocks of the first launch, one wavefront per
+//                  row; the key / value blocks fold their own [W_q | W_k | W_v] on their way into LDS
 //   k_gca_kv       one block per (32 residues, group of sequences), its four wavefronts each a range of consecutive
 //                  sequences: a tile = the 32 c contiguous elements of one sequence's residues, asked for as whole
 //                  lines and turned into operand fragments through LDS, normalised (masked tokens as zeros) and
@@ -168,10 +170,10 @@ struct PrepArgs {
     int c, Hd, d, Kp;
 };
 
-// one wavefront per row of the three folded matrices; the rows after them copy W_o and b_o
-__global__ __launch_bounds__(256) void k_gca_prep(PrepArgs a) {
-    const int lane = threadIdx.x & 63;
-    const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+// One wavefront per row n of the three folded matrices (rows [0, Hd): W_q', [Hd, Hd + 32): W_k' | W_v',
+// [Hd + 32, 2 Hd + 32): W_g'); the c rows after them copy W_o and b_o.  Run by the last blocks of the k_gca_kv launch
+// for what the later kernels need (C_q, W_g', W_o: the key / value blocks fold their own weights).
+__device__ __forceinline__ void prep_row(const PrepArgs& a, int n, int lane) {
     const int rows_fold = 2 * a.Hd + 32;
     if (n < rows_fold) {
         const bf16_t* wrow = nullptr;
@@ -237,8 +239,9 @@ struct KvArgs {
     const float* mask;       // [S][R] or NULL
     int S, R, c, Hd, d, groups;
     float eps;
-    const bf16_t *wq, *wkv;  // folded, pitch 16 KC
-    const float* Ckv;
+    const bf16_t *w_q, *w_k, *w_v, *ln_g, *ln_b;   // the caller's weights: [Hd][c], [d][c], [d][c], [c], [c]
+    PrepArgs prep;           // for the blocks behind the kv_blocks key / value blocks
+    int kv_blocks;
     bf16_t* kv;              // [R][S][2d]: k then v of a token
     unsigned char* keepT;    // [R][S]: 1 = the token takes part (the mask, by column); written only if mask != NULL
     float* qpart;            // [R][groups][Hd]
@@ -260,6 +263,13 @@ __global__ __launch_bounds__(256) void k_gca_kv(KvArgs p) {
     float* s_red = reinterpret_cast<float*>(smem);               // [4][32][Hd + 1]: the wavefronts' query sums and counts, after the loop
     const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    if ((int)blockIdx.x >= p.kv_blocks) {
+        // what the softmax and the output kernel need of the weights (rows of W_q' for C_q, W_g', W_o): it depends
+        // on nothing, so it rides in this launch instead of one of its own
+        const int n = ((int)blockIdx.x - p.kv_blocks) * 4 + wave;
+        prep_row(p.prep, n < p.Hd ? n : n + 32, lane);
+        return;
+    }
     const int tpr = (p.R + 31) >> 5;
     const int rt = blockIdx.x % tpr, grp = blockIdx.x / tpr;
     const int per = (p.S + 4 * p.groups - 1) / (4 * p.groups);       // consecutive sequences per wavefront
@@ -288,10 +298,39 @@ __global__ __launch_bounds__(256) void k_gca_kv(KvArgs p) {
         tf.fetch(xn, p.m + ((size_t)s0 * p.R + rt * 32) * p.c);
         if (p.mask) mkn = p.mask[(size_t)s0 * p.R + i];
     }
+    // The block folds the LayerNorm gain into its own copy of [W_q | W_k | W_v] (W' = bf16(W gamma), eight channels
+    // per thread and step; rows Hd .. Hd + 31: keys in 0 .. d - 1, values in 16 .. 16 + d - 1, the others zero) and
+    // forms the key / value offsets C = W beta from the pieces' partial sums in a fixed order.
+    float* s_part = reinterpret_cast<float*>(s_keep + (4 - wave) * 128);      // [32][2 KC] (behind the four wavefronts' flag areas)
+    float* s_ckv = s_part + 32 * 2 * KC;                                        // [32]
     for (int id = tid; id < (p.Hd + 32) * 2 * KC; id += 256) {
-        const int row = id / (2 * KC), pc = id - row * (2 * KC);
-        const bf16_t* src = row < p.Hd ? p.wq + (size_t)row * (16 * KC) : p.wkv + (size_t)(row - p.Hd) * (16 * KC);
-        *reinterpret_cast<uint4*>(smem + row * PITCH + pc * 16) = *reinterpret_cast<const uint4*>(src + pc * 8);
+        const int row = id / (2 * KC), pc = id - row * (2 * KC), r = row - p.Hd;
+        const bf16_t* src = row < p.Hd ? p.w_q + (size_t)row * p.c
+                                       : (r < p.d ? p.w_k + (size_t)r * p.c : ((r >= 16 && r < 16 + p.d) ? p.w_v + (size_t)(r - 16) * p.c : nullptr));
+        uint4 out = make_uint4(0, 0, 0, 0);
+        float cst = 0.f;
+        if (src && 8 * pc < p.c) {
+            const uint4 w8 = *reinterpret_cast<const uint4*>(src + 8 * pc);
+            const uint4 g8 = *reinterpret_cast<const uint4*>(p.ln_g + 8 * pc);
+            const uint4 b8 = *reinterpret_cast<const uint4*>(p.ln_b + 8 * pc);
+            const uint32_t ww[4] = {w8.x, w8.y, w8.z, w8.w}, gw[4] = {g8.x, g8.y, g8.z, g8.w}, bw[4] = {b8.x, b8.y, b8.z, b8.w};
+            uint32_t o[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                o[e] = pack2(lo_f32(ww[e]) * lo_f32(gw[e]), hi_f32(ww[e]) * hi_f32(gw[e]));
+                cst += lo_f32(ww[e]) * lo_f32(bw[e]) + hi_f32(ww[e]) * hi_f32(bw[e]);
+            }
+            out = make_uint4(o[0], o[1], o[2], o[3]);
+        }
+        *reinterpret_cast<uint4*>(smem + row * PITCH + pc * 16) = out;
+        if (r >= 0) s_part[r * 2 * KC + pc] = cst;
+    }
+    __syncthreads();
+    if (tid < 32) {
+        float t = 0.f;
+#pragma unroll
+        for (int pc = 0; pc < 2 * KC; ++pc) t += s_part[tid * 2 * KC + pc];
+        s_ckv[tid] = t;
     }
     __syncthreads();
 
@@ -302,8 +341,8 @@ __global__ __launch_bounds__(256) void k_gca_kv(KvArgs p) {
         for (int v = 0; v < 16; ++v) qacc[T][v] = 0.f;
     float cnt = 0.f;                             // unmasked sequences of the lane's residue
     // offsets of the lane's key / value rows (read once)
-    const float4 ckv0 = *reinterpret_cast<const float4*>(p.Ckv + 4 * hf), ckv1 = *reinterpret_cast<const float4*>(p.Ckv + 8 + 4 * hf);
-    const float4 ckv2 = *reinterpret_cast<const float4*>(p.Ckv + 16 + 4 * hf), ckv3 = *reinterpret_cast<const float4*>(p.Ckv + 24 + 4 * hf);
+    const float4 ckv0 = *reinterpret_cast<const float4*>(s_ckv + 4 * hf), ckv1 = *reinterpret_cast<const float4*>(s_ckv + 8 + 4 * hf);
+    const float4 ckv2 = *reinterpret_cast<const float4*>(s_ckv + 16 + 4 * hf), ckv3 = *reinterpret_cast<const float4*>(s_ckv + 24 + 4 * hf);
 
     for (int s = s_lo; s < s_hi; ++s) {
         Frag xa[KC];
@@ -827,26 +866,24 @@ ff_status global_run(const ff_global_desc& d, const ff_global_weights& w, const 
     const int Hd = d.heads * d.head_dim, kc = kc_for(d.c), groups = kv_groups(d.n_seq);
     const Ws s = carve(d, ws);
     {
-        PrepArgs a{};
-        a.w_q = (const bf16_t*)w.w_q; a.w_k = (const bf16_t*)w.w_k; a.w_v = (const bf16_t*)w.w_v; a.w_g = (const bf16_t*)w.w_g;
-        a.b_g = (const bf16_t*)w.b_g; a.w_o = (const bf16_t*)w.w_o; a.b_o = (const bf16_t*)w.b_o;
-        a.ln_g = (const bf16_t*)w.ln_g; a.ln_b = (const bf16_t*)w.ln_b;
-        a.wq = s.wq; a.wkv = s.wkv; a.wg = s.wg; a.wo = s.wo; a.Cq = s.Cq; a.Ckv = s.Ckv; a.gext = s.gext; a.Co = s.Co;
-        a.c = d.c; a.Hd = Hd; a.d = d.head_dim; a.Kp = 16 * kc;
-        const int rows = 2 * Hd + 32 + d.c;
-        Timed t(KK_GCA_PREP, st);
-        hipLaunchKernelGGL(k_gca_prep, dim3((rows + 3) / 4), dim3(256), 0, st, a);
-    }
-    {
         KvArgs a{};
+        PrepArgs& pa = a.prep;
+        pa.w_q = (const bf16_t*)w.w_q; pa.w_k = (const bf16_t*)w.w_k; pa.w_v = (const bf16_t*)w.w_v; pa.w_g = (const bf16_t*)w.w_g;
+        pa.b_g = (const bf16_t*)w.b_g; pa.w_o = (const bf16_t*)w.w_o; pa.b_o = (const bf16_t*)w.b_o;
+        pa.ln_g = (const bf16_t*)w.ln_g; pa.ln_b = (const bf16_t*)w.ln_b;
+        pa.wq = s.wq; pa.wkv = s.wkv; pa.wg = s.wg; pa.wo = s.wo; pa.Cq = s.Cq; pa.Ckv = s.Ckv; pa.gext = s.gext; pa.Co = s.Co;
+        pa.c = d.c; pa.Hd = Hd; pa.d = d.head_dim; pa.Kp = 16 * kc;
         a.m = (const bf16_t*)m; a.mask = mask; a.S = d.n_seq; a.R = d.n_res; a.c = d.c; a.Hd = Hd; a.d = d.head_dim;
-        a.groups = groups; a.eps = d.ln_eps; a.wq = s.wq; a.wkv = s.wkv; a.Ckv = s.Ckv; a.kv = s.kv; a.keepT = s.keepT; a.qpart = s.qpart;
+        a.groups = groups; a.eps = d.ln_eps; a.kv = s.kv; a.keepT = s.keepT; a.qpart = s.qpart;
+        a.w_q = pa.w_q; a.w_k = pa.w_k; a.w_v = pa.w_v; a.ln_g = pa.ln_g; a.ln_b = pa.ln_b;
         a.cntpart = s.cntpart;
-        const dim3 grid(((d.n_res + 31) / 32) * groups);
+        a.kv_blocks = ((d.n_res + 31) / 32) * groups;
+        // behind the key / value blocks: one wavefront per row of W_q' (for C_q), W_g' and W_o
+        const dim3 grid(a.kv_blocks + (2 * Hd + d.c + 3) / 4);
         // weights, the wavefronts' batches of k | v [32 residues][4 sequences] and incoming tiles; afterwards the same bytes hold the
         // four wavefronts' partial sums [32 residues][Hd + 1]
         const size_t smem_loop = (size_t)(Hd + 32) * (kc * 32 + 16) + (size_t)4 * 32 * (16 * d.head_dim + 16) +
-                                 (size_t)4 * 32 * (2 * d.c + 16) + 4 * 128;
+                                 (size_t)4 * 32 * (2 * d.c + 16) + 4 * 128 + (size_t)32 * 2 * kc * 4 + 128;
         const size_t smem_red = (size_t)4 * 32 * (Hd + 1) * 4;
         const size_t smem = smem_loop > smem_red ? smem_loop : smem_red;
         hipError_t attr = hipSuccess;
