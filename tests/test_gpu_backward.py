@@ -66,6 +66,7 @@ SHAPES = [   # rows, heads, length, head_dim, bias, mask: ragged around the 32-w
     (1, 1, 1, 8, True, "none"), (2, 3, 31, 16, True, "random:0.7"), (3, 2, 33, 32, True, "tail:5"),
     (2, 2, 64, 32, False, "random:0.8"), (5, 4, 97, 8, True, "random:0.9"), (2, 8, 130, 32, True, "tail:20"),
     (3, 1, 200, 16, False, "none"), (9, 2, 70, 32, True, "random:0.5"),
+    (26, 2, 64, 16, True, "random:0.8"),       # three uneven row chunks of the bias gradient (9, 9, 8 rows)
 ]
 
 
