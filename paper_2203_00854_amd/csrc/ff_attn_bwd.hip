@@ -556,8 +556,11 @@ __global__ __launch_bounds__(256, 3) void k_bwd_dq(Args a) {
 // ====================================================================================
 // Block = four consecutive key tiles of one (row, head); the query-side tiles (q, dctx, their position-contiguous
 // copies, logsumexp, delta) are staged once per block and query tile.
+// (three wavefronts per SIMD where the lengths are whole tiles: at d = 32 with a bias that costs four spilled
+// registers, all outside the tile loop; in the variant with bounds checks one of them would land inside it, and a
+// reload inside the loop is waited for together with every load in flight)
 template <int D, bool FULL, bool BIAS>
-__global__ __launch_bounds__(256) void k_bwd_dkv(Args a) {
+__global__ __launch_bounds__(256, FULL ? 3 : 1) void k_bwd_dkv(Args a) {
     constexpr int KS = (D + 15) / 16;
     __shared__ __attribute__((aligned(16))) unsigned char s_stage[2 * kStBytes];
     const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
