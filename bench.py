@@ -189,6 +189,10 @@ def kernel_rooflines(sp, kernels, steps, measured=None):
                          tok * (sp.c + 4 * hd) * 2 + w_main + (bias_out if tri_fused else 0), "mfma"),
         "k_attn": (fl["attn"], None,
                    tok * 5 * hd * 2 + (bias_out * (R // rows_per_launch) if sp.mode != 1 else 0), "alu"),
+        # sequences of at most 256 positions at head dim 32: projections and attention in one kernel, which
+        # reads x, the weights and the bias and writes the gated context only
+        "k_proj_attn": (fl["proj"] + fl["attn"], tok * sp.c * 2 + w_main + (bias_out if sp.mode != 1 else 0),
+                        tok * (sp.c + hd) * 2 + w_main + (bias_out * (R // rows_per_launch) if sp.mode != 1 else 0), "mfma"),
         "k_gemm<OUT>": (fl["out"], tok * sp.c * 2 + hd * sp.c * 2, tok * (hd + sp.c) * 2 + hd * sp.c * 2, "mfma"),
         # row mode: k_prep_bias (z once, the float32 bias, and the weight preparation in the same
         # launch); chunked triangle modes: the pair-bias pass over all of x

@@ -21,7 +21,8 @@ static const char* kKindNames[KK_COUNT] = {"k_prep", "pair bias pass", "k_gemm<P
                                            "k_gemm<OUT>", "k_layernorm", "generic family", "probe: mfma loop",
                                            "probe: copy", "k_tm_prep", "k_tm_proj", "k_tm_mul", "k_tm_out",
                                            "k_gca_kv", "k_gca_softmax", "k_gca_out",
-                                           "k_bwd_stats", "k_bwd_dq", "k_bwd_dkv", "k_bwd_dbias", "probe: vector loop"};
+                                           "k_bwd_stats", "k_bwd_dq", "k_bwd_dkv", "k_bwd_dbias", "probe: vector loop",
+                                           "k_proj_attn"};
 
 static hipEvent_t prof_event() {
     if (!g_prof_pool.empty()) {

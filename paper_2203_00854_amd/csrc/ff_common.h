@@ -70,7 +70,7 @@ struct Workspace {
 // kernel kinds for the launch timer (ff_profile_* in the C ABI)
 enum KernelKind { KK_PREP = 0, KK_BIAS, KK_PROJ, KK_ATTN, KK_OUT, KK_LAYERNORM, KK_GENERIC, KK_PROBE_MFMA, KK_PROBE_COPY,
                   KK_TM_PREP, KK_TM_PROJ, KK_TM_MUL, KK_TM_OUT, KK_GCA_KV, KK_GCA_SOFTMAX, KK_GCA_OUT,
-                  KK_BWD_STATS, KK_BWD_DQ, KK_BWD_DKV, KK_BWD_DBIAS, KK_PROBE_VALU, KK_COUNT };
+                  KK_BWD_STATS, KK_BWD_DQ, KK_BWD_DKV, KK_BWD_DBIAS, KK_PROBE_VALU, KK_PROJ_ATTN, KK_COUNT };
 void prof_begin(int kind, hipStream_t st);
 void prof_end(int kind, hipStream_t st);
 // brackets the launches issued in its scope with HIP events when the timer is on

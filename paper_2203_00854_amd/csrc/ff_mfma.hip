@@ -283,8 +283,21 @@ __global__ __launch_bounds__(256) void k_prep(PrepArgs a) {
 // the first chunk) and the weight preparation in ONE launch (they do not depend on each other).  Blocks below bias_blocks take
 // 256 pairs each (one 32-pair tile per wavefront, the folded 32 x K weight tile built by the block
 // itself in LDS, same algebra as k_gemm's pair-bias tile); the blocks above them run prep_row.
+// Element (h, q, k) of the pair bias.  Plain: [H][Lq][Lp].  Tiled (for k_proj_attn): 32 x 32 tiles in
+// the register order of an S^T accumulator, [H][Lq/32][Lp/32][4][64 lanes][4]: lane = (q % 32) + 32 hf
+// holds the keys 16c + 8hf + 4i + e of the tile in element e of group 2c + i, so that a wavefront
+// fetches a tile with four loads of 1 KiB each.
+__device__ __forceinline__ size_t bias_index(bool tiled, int h, int q, int k, int Lq, int Lp) {
+    if (!tiled) return ((size_t)h * Lq + q) * Lp + k;
+    const int kk = k & 31;
+    const int grp = 2 * (kk >> 4) + ((kk >> 2) & 1), hf = (kk >> 3) & 1;
+    const size_t tile = ((size_t)h * (Lq >> 5) + (q >> 5)) * (Lp >> 5) + (k >> 5);
+    return ((tile * 4 + grp) * 64 + (q & 31) + 32 * hf) * 4 + (kk & 3);
+}
+
 struct PrepBiasArgs {
     PrepArgs prep;
+    int tiled;                   // layout of the output (bias_index)
     int bias_blocks;
     const bf16_t* z;             // pair (i, j) at z + (i*sr + j*sl)*K
     int64_t sr, sl;
@@ -361,7 +374,7 @@ __global__ __launch_bounds__(512) void k_prep_bias(PrepBiasArgs a) {
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa.v, xaug.v, acc, 0, 0, 0);
     }
     // lane = pair (qi, kj), register v = head 8*(v/4) + 4*hf + v%4
-    float* bp = a.bias + (size_t)qi * a.Lp + kj;
+    float* bp = a.bias + bias_index(a.tiled != 0, 0, qi, kj, a.Lq, a.Lp);
     const size_t plane = (size_t)a.Lq * a.Lp;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
@@ -373,12 +386,13 @@ __global__ __launch_bounds__(512) void k_prep_bias(PrepBiasArgs a) {
 // Rows q in [L, Lq) of the bias tensor [H][Lq][Lp] belong to pad queries: no kernel computes them, but
 // the attention kernel stages whole 64-query tiles.  Zeros there keep its lanes for pad queries (never
 // stored) on the common path whatever the caller's workspace held before.
-__global__ __launch_bounds__(256) void k_zero_bias_pad(float* bias, int L, int Lq, int Lp, int H) {
+__global__ __launch_bounds__(256) void k_zero_bias_pad(float* bias, int L, int Lq, int Lp, int H, int tiled) {
     const int per_head = (Lq - L) * Lp;
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= per_head * H) return;
     const int h = i / per_head, r = i - h * per_head;
-    bias[((size_t)h * Lq + L) * Lp + r] = 0.f;
+    const int q = L + r / Lp, k = r - (q - L) * Lp;
+    bias[bias_index(tiled != 0, h, q, k, Lq, Lp)] = 0.f;
 }
 
 // ====================================================================================
@@ -1386,6 +1400,453 @@ __global__ __launch_bounds__(RB * 64, (RB == 4 && !HAS_BIAS && D < 32) ? 3 : 2) 
 }
 
 // ====================================================================================
+// Projection and attention in one kernel, for sequences of at most 256 positions with head
+// dimension 32 (the row-wise and triangle attentions of the training crop, Section 5.2's merged
+// projections feeding its fused softmax): a block takes two batch rows and one head, projects
+// that head's q, k, v and gate for all tokens of the two rows straight from the raw input (the
+// LayerNorm folded into the weights as in k_gemm) and attends at once.  q and the gate never
+// leave the registers, k and v^T live in LDS, so that of the five tensors k_gemm<PROJ> hands to
+// k_attn through HBM only the gated context is ever written.
+//
+// Wavefront w owns tokens 32w .. 32w+31 of both rows: as projection tokens first, as queries
+// afterwards.  A projection tile leaves the matrix core with the lane = token, register =
+// feature 8*(v/4) + 4*hf + v%4 layout; packed in register order it is a valid B operand of
+// S^T = K Q^T as long as the key side uses the same order of the contraction, which is how the k
+// tile is written to LDS (one 16-byte piece per step and half-wave).  The gate has the layout
+// of O^T already.  v is computed with the operands swapped (lane = feature), which is the
+// layout of a row of v^T.  The bias tile of a key tile is loaded once and used as accumulator
+// input for both rows.
+//
+// LDS: the head's four folded 32 x K weight tiles (row pitch 2K + 16 bytes), their extra pieces,
+// k [2][256][80 bytes] (four pieces of the contraction and the piece with 1 and the mask term),
+// v^T [2][32][528 bytes], 1/std of the tokens, and one flag per (row, key tile) that tells
+// whether the tile holds a valid key.
+struct FusedArgs {
+    const bf16_t* x;       // raw input, token (r, l) at (r*sr + l*sl)*K
+    int64_t sr, sl;        // token strides of x and of the mask
+    int r0, rows, L, Lp, Lq;
+    float eps;
+    const bf16_t* wp;      // prepared weights [(4*Hd + 32)][K]
+    const uint4* aug;      // their extra pieces
+    int H, Hd;
+    const float* bias;     // [H][Lq][Lp] or NULL
+    const float* mask;     // caller's mask or NULL
+    bf16_t* o;             // gated context [rows][H][Lp][32]
+#ifdef FF_FU_DBG
+    unsigned long long* dbg;
+#endif
+};
+#ifdef FF_FU_DBG
+#define FU_STAMP(k) do { if (tid == DBGT) a.dbg[(blockIdx.x * 4 + dbg_item) * 8 + (k)] = wall_clock64(); } while (0)
+#else
+#define FU_STAMP(k) do { } while (0)
+#endif
+
+constexpr int kFuKPitch = 80;       // bytes of a key row in LDS
+constexpr int kFuVPitch = 528;      // bytes of a v^T row in LDS: 256 keys and a pad
+constexpr int kFuWaves = 8;
+
+static size_t fused_smem_bytes(int kc) {
+    return (size_t)4 * 32 * (32 * kc + 16) + 128 * 16 + 2 * 256 * kFuKPitch + 2 * 32 * kFuVPitch + kFuWaves * 2 * 32 * 4 + 64 +
+           kFuWaves * 2048;
+}
+
+template <int KC, bool HAS_BIAS>
+__global__ __launch_bounds__(kFuWaves * 64) void k_proj_attn(FusedArgs a) {
+    constexpr int K = 16 * KC, WP = 32 * KC + 16;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    unsigned char* s_w = smem;                                                  // [4][32][WP]
+    uint4* s_aug = reinterpret_cast<uint4*>(s_w + 4 * 32 * WP);                 // [4][32]
+    unsigned char* s_k = reinterpret_cast<unsigned char*>(s_aug + 128);         // [2][256][kFuKPitch]
+    unsigned char* s_vt = s_k + 2 * 256 * kFuKPitch;                            // [2][32][kFuVPitch]
+    float* s_stat = reinterpret_cast<float*>(s_vt + 2 * 32 * kFuVPitch);        // [wave][2][32]
+    int* s_live = reinterpret_cast<int*>(s_stat + kFuWaves * 2 * 32);           // [2][8]
+    unsigned char* s_st = reinterpret_cast<unsigned char*>(s_live + 16) + (threadIdx.x >> 6) * 2048;   // [wave][16][128]
+
+    const int tid = threadIdx.x, lane = tid & 63, col = lane & 31, hf = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nt = a.Lp >> 5;                               // 32-token tiles of a row: even, at most 8
+    const bool active = wave < nt;                          // (wave-uniform)
+    // Work-groups go to the 8 XCDs round-robin and each XCD has its own L2: the heads of a row
+    // pair run on one XCD at about the same time, so the rows of x come from HBM once.  Item
+    // jj*H + h of an XCD is row pair xcd + 8 jj, head h; a block takes the items slot, slot +
+    // slots, ...: with the slots a multiple of H its head never changes and the weights are
+    // loaded once.
+    const int n_rp = (a.rows + 1) >> 1;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, slots = gridDim.x >> 3;
+    const int n_local = xcd < n_rp ? ((n_rp - xcd + 7) >> 3) * a.H : 0;
+    int h_loaded = -1;
+    // permuted key of S^T row m = col (see k_attn): the lane's registers 8c .. 8c+7 then hold the
+    // keys 16c + 8hf .. + 7 of the tile
+    const int kperm = 16 * (col >> 4) + 8 * ((col >> 2) & 1) + 4 * ((col >> 3) & 1) + (col & 3);
+    const int l_tok = 32 * wave + col;
+    const bool tok_in = active && l_tok < a.L;
+    const bool has_mask = a.mask != nullptr;
+
+#ifdef FF_FU_DBG
+    int dbg_item = -1;
+    constexpr int DBGT = 64 * 3;
+#endif
+    for (int it = slot; it < n_local; it += slots) {
+        const int jj = it / a.H, h = it - jj * a.H;
+        const int rp = xcd + 8 * jj;
+#ifdef FF_FU_DBG
+        ++dbg_item;
+#endif
+        FU_STAMP(0);
+        if (it != slot) __syncthreads();            // every wavefront has left the item before: k and v^T may be overwritten
+        FU_STAMP(1);
+
+        // ---- raw tokens (row 0 issued first; row 1 follows line by line as the registers fall free),
+        // the mask entries.  Eight lanes fetch one 128-byte line of a token (a load with lane =
+        // token, the operand layout, touches 64 lines for 1 KiB and the cache looks up one line per
+        // cycle); raw[m][hh][i] holds line m of the tokens 16hh + 8i + lane/8 of the wavefront's
+        // tile, piece lane%8.
+        constexpr int NG = KC / 4;              // 128-byte lines per token
+        uint4 raw[NG][2][2];
+        float mval[2];
+        bool row_ok[2];
+        int rlv[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int rl = 2 * rp + j;
+            row_ok[j] = rl < a.rows;
+            rlv[j] = row_ok[j] ? rl : a.rows - 1;
+            mval[j] = 1.f;
+            if (has_mask && tok_in) mval[j] = a.mask[(int64_t)(a.r0 + rlv[j]) * a.sr + (int64_t)l_tok * a.sl];
+        }
+        auto fetch_line = [&](int j, int m) __attribute__((always_inline)) {
+            const int64_t row_tok = (int64_t)(a.r0 + rlv[j]) * a.sr;
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const int l = 32 * wave + 16 * hh + 8 * i + (lane >> 3);
+                    const bool in = active && l < a.L;
+                    raw[m][hh][i] = make_uint4(0, 0, 0, 0);
+                    if (in) raw[m][hh][i] = ldg16(a.x + (row_tok + (int64_t)l * a.sl) * K + (lane & 7) * 8 + 64 * m);
+                }
+        };
+#pragma unroll
+        for (int m = 0; m < NG; ++m) fetch_line(0, m);
+
+        // ---- the head's weight tiles
+        if (h != h_loaded) {
+            // (128 rows of 2 KC pieces, KC / 2 pieces per thread, up to four loads in flight)
+            constexpr int WB = KC / 2 < 4 ? KC / 2 : 4;          // loads in flight per thread
+#pragma unroll
+            for (int n0 = 0; n0 < KC / 2; n0 += WB) {
+                uint4 wv[WB];
+#pragma unroll
+                for (int n = 0; n < WB; ++n) {
+                    const int p = tid + (n0 + n) * kFuWaves * 64;
+                    const int row = p / (2 * KC), pp = p - row * (2 * KC);
+                    wv[n] = ldg16(a.wp + ((size_t)((row >> 5) * a.Hd + h * 32 + (row & 31)) * K + pp * 8));
+                }
+#pragma unroll
+                for (int n = 0; n < WB; ++n) {
+                    const int p = tid + (n0 + n) * kFuWaves * 64;
+                    const int row = p / (2 * KC), pp = p - row * (2 * KC);
+                    *reinterpret_cast<uint4*>(s_w + row * WP + pp * 16) = wv[n];
+                }
+            }
+            if (tid < 128) s_aug[tid] = a.aug[(tid >> 5) * a.Hd + h * 32 + (tid & 31)];
+            h_loaded = h;
+            __syncthreads();
+        }
+
+        FU_STAMP(2);
+        // ---- projections: q and gate stay in registers, k and v^T go to LDS
+        Frag qf[2][3];
+        uint32_t gpk[2][8];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+#pragma unroll
+            for (int s = 0; s < 3; ++s) qf[j][s].u = make_uint4(0, 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) gpk[j][i] = 0u;
+        }
+        if (active) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                // The lines pass through the wavefront's staging area (16 tokens x 128 bytes, the eight
+                // pieces of a token rotated by its index: conflict-free) and come back in the operand
+                // layout, lane = token, pieces 2s' + hf of line m = contraction steps 4m + s'.  The
+                // area is private to the wavefront, whose LDS operations complete in order.
+                f32x16 aq, ak, av, ag;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) aq[v] = ak[v] = av[v] = ag[v] = 0.f;
+                const unsigned char* wrow = s_w + col * WP + hf * 16;
+                float sum = 0.f, sq = 0.f;
+#pragma unroll
+                for (int m = 0; m < NG; ++m) {
+                    Frag xg[4];
+#pragma unroll
+                    for (int hh = 0; hh < 2; ++hh) {
+#pragma unroll
+                        for (int i = 0; i < 2; ++i) {
+                            const int tl = 8 * i + (lane >> 3);
+                            *reinterpret_cast<uint4*>(s_st + tl * 128 + (((lane & 7) ^ (tl & 7)) * 16)) = raw[m][hh][i];
+                        }
+                        __builtin_amdgcn_wave_barrier();
+                        if ((col >> 4) == hh) {
+                            const int tl = col & 15;
+#pragma unroll
+                            for (int sp = 0; sp < 4; ++sp)
+                                xg[sp].u = *reinterpret_cast<const uint4*>(s_st + tl * 128 + (((2 * sp + hf) ^ (tl & 7)) * 16));
+                        }
+                        __builtin_amdgcn_wave_barrier();
+                    }
+                    if (j == 0) fetch_line(1, m);         // (the line's registers are free again)
+                    // LayerNorm statistics as in token_stats, one line at a time
+#pragma unroll
+                    for (int sp = 0; sp < 4; ++sp)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            sum = add_pair(xg[sp].w[i], sum);
+                            sq = add_pair_sq(xg[sp].w[i], sq);
+                        }
+#pragma unroll
+                    for (int sp = 0; sp < 4; ++sp) {
+                        const int st = 4 * m + sp;
+                        Frag wq, wk, wv, wg;
+                        wq.u = *reinterpret_cast<const uint4*>(wrow + 0 * 32 * WP + 32 * st);
+                        wk.u = *reinterpret_cast<const uint4*>(wrow + 1 * 32 * WP + 32 * st);
+                        wv.u = *reinterpret_cast<const uint4*>(wrow + 2 * 32 * WP + 32 * st);
+                        wg.u = *reinterpret_cast<const uint4*>(wrow + 3 * 32 * WP + 32 * st);
+                        aq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wq.v, xg[sp].v, aq, 0, 0, 0);
+                        ak = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wk.v, xg[sp].v, ak, 0, 0, 0);
+                        av = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xg[sp].v, wv.v, av, 0, 0, 0);
+                        ag = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wg.v, xg[sp].v, ag, 0, 0, 0);
+                    }
+                }
+                sum += other_half(sum);
+                sq += other_half(sq);
+                const float mu = sum * (1.f / (float)K);
+                const float var = fmaxf(sq * (1.f / (float)K) - mu * mu, 0.f) + a.eps;
+                const float rstd = tok_in ? rsqrtf(var) : 0.f;
+                const float mneg = tok_in ? -mu : 0.f, r = var * rstd;
+                const float m_hi = bf16_round(mneg), m_lo = bf16_round(mneg - m_hi);
+                const float r_hi = bf16_round(r), r_lo = bf16_round(r - r_hi);
+                Frag xaug;
+                xaug.u = make_uint4(0, 0, 0, 0);
+                if (hf == 0) {
+                    xaug.u = make_uint4(pack2(m_hi, m_hi), pack2(m_lo, r_hi), pack2(r_hi, r_lo), 0u);
+                    s_stat[(wave * 2 + j) * 32 + col] = rstd;
+                }
+                const bool key_valid = tok_in && mval[j] != 0.f;
+                const bool any_valid = __any(key_valid);
+                if (lane == 0) s_live[j * 8 + wave] = any_valid ? 1 : 0;
+                {
+                    Frag wq, wk, wv, wg;
+                    wq.u = s_aug[col];
+                    wk.u = s_aug[32 + col];
+                    wv.u = s_aug[64 + col];
+                    wg.u = s_aug[96 + col];
+                    aq = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wq.v, xaug.v, aq, 0, 0, 0);
+                    ak = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wk.v, xaug.v, ak, 0, 0, 0);
+                    av = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xaug.v, wv.v, av, 0, 0, 0);
+                    ag = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wg.v, xaug.v, ag, 0, 0, 0);
+                }
+                // q: B operand of S^T, step s = registers 8s .. 8s+7; step 2 carries (-m_ref, 1)
+                // k: the same pieces into the token's LDS row, then (1, mask term)
+                unsigned char* krow = s_k + (j * 256 + l_tok) * kFuKPitch;
+#pragma unroll
+                for (int s = 0; s < 2; ++s) {
+                    uint32_t kw[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        qf[j][s].w[i] = pack2(aq[8 * s + 2 * i] * rstd, aq[8 * s + 2 * i + 1] * rstd);
+                        kw[i] = pack2(ak[8 * s + 2 * i] * rstd, ak[8 * s + 2 * i + 1] * rstd);
+                    }
+                    *reinterpret_cast<uint4*>(krow + (2 * s + hf) * 16) = make_uint4(kw[0], kw[1], kw[2], kw[3]);
+                }
+                if (hf == 0) {
+                    qf[j][2].w[0] = 0x3f800000u;            // (-m_ref = 0, 1.0)
+                    *reinterpret_cast<uint4*>(krow + 64) = make_uint4(key_valid ? 0x00003f80u : 0xff803f80u, 0u, 0u, 0u);   // (1.0, mask term)
+                }
+                // gate: the layout of O^T
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const float g0 = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-(ag[2 * i] * rstd) * kLog2e));
+                    const float g1 = __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-(ag[2 * i + 1] * rstd) * kLog2e));
+                    gpk[j][i] = pack2(g0, g1);
+                }
+                // v: lane = feature col, register v = token 8*(v/4) + 4*hf + v%4 of the wavefront's tile
+                // (1/std of those tokens comes back from LDS: written above by this wavefront, whose LDS
+                // operations complete in order)
+                __builtin_amdgcn_wave_barrier();
+                unsigned char* vrow = s_vt + (j * 32 + col) * kFuVPitch + (32 * wave + 4 * hf) * 2;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const float4 rs = *reinterpret_cast<const float4*>(s_stat + (wave * 2 + j) * 32 + 8 * g + 4 * hf);
+                    *reinterpret_cast<uint2*>(vrow + 16 * g) =
+                        make_uint2(pack2(av[4 * g] * rs.x, av[4 * g + 1] * rs.y), pack2(av[4 * g + 2] * rs.z, av[4 * g + 3] * rs.w));
+                }
+            }
+        }
+        FU_STAMP(3);
+        __syncthreads();
+        FU_STAMP(4);
+
+        // ---- attention of the wavefront's 32 queries of both rows over the nt key tiles
+        if (active) {
+            // (the lane's indices anew, opaque to the optimiser: the addresses of this phase would
+            // otherwise be computed before the projections and held in registers through them)
+            int lane_a = lane;
+            asm volatile("" : "+v"(lane_a));
+            const int col_a = lane_a & 31, hf_a = lane_a >> 5;
+            const int kperm_a = 16 * (col_a >> 4) + 8 * ((col_a >> 2) & 1) + 4 * ((col_a >> 3) & 1) + (col_a & 3);
+            int lv[2];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                int bits = 0;
+                for (int t = 0; t < nt; ++t) bits |= s_live[j * 8 + t] << t;
+                lv[j] = __builtin_amdgcn_readfirstlane(bits);
+            }
+            f32x16 o_acc[2];
+            float m_ref[2], l_run[2];
+            bool first[2];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                m_ref[j] = 0.f;
+                l_run[j] = 0.f;
+                first[j] = true;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o_acc[j][v] = 0.f;
+            }
+            // (tiled bias, see bias_index: the tiles of the wavefront's 32 queries follow each other)
+            const float* bh = HAS_BIAS ? a.bias + ((size_t)h * (a.Lq >> 5) + wave) * nt * 1024 : nullptr;
+            const uint32_t b_lane = (uint32_t)lane_a * 16;
+            auto load_bias = [&](int kt, f32x16& bt) __attribute__((always_inline)) {
+                if constexpr (HAS_BIAS) {
+                    const char* bp = reinterpret_cast<const char*>(bh + 1024 * kt) + b_lane;
+#pragma unroll
+                    for (int c = 0; c < 2; ++c)
+#pragma unroll
+                        for (int i = 0; i < 2; ++i) {
+                            const float4 x4 = *reinterpret_cast<const float4*>(bp + (2 * c + i) * 1024);
+                            bt[8 * c + 4 * i] = x4.x; bt[8 * c + 4 * i + 1] = x4.y;
+                            bt[8 * c + 4 * i + 2] = x4.z; bt[8 * c + 4 * i + 3] = x4.w;
+                        }
+                } else {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) bt[v] = 0.f;
+                }
+            };
+            auto tile = [&](int kt, const f32x16& bt) __attribute__((always_inline)) {
+                f32x16 sa[2];
+                Frag vf[2][2];
+                bool live[2];
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    live[j] = (lv[j] >> kt) & 1;
+                    if (live[j]) {
+                        const unsigned char* krow = s_k + (j * 256 + 32 * kt + kperm_a) * kFuKPitch;
+                        Frag kf[3];
+                        kf[0].u = *reinterpret_cast<const uint4*>(krow + hf_a * 16);
+                        kf[1].u = *reinterpret_cast<const uint4*>(krow + 32 + hf_a * 16);
+                        kf[2].u = make_uint4(0, 0, 0, 0);
+                        if (hf_a == 0) kf[2].u = *reinterpret_cast<const uint4*>(krow + 64);
+                        const unsigned char* vrow = s_vt + (j * 32 + col_a) * kFuVPitch + (32 * kt + 8 * hf_a) * 2;
+                        vf[j][0].u = *reinterpret_cast<const uint4*>(vrow);
+                        vf[j][1].u = *reinterpret_cast<const uint4*>(vrow + 32);
+                        sa[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0].v, qf[j][0].v, bt, 0, 0, 0);
+                        sa[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1].v, qf[j][1].v, sa[j], 0, 0, 0);
+                        sa[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[2].v, qf[j][2].v, sa[j], 0, 0, 0);
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    if (!live[j]) continue;
+                    // sa holds s - m_ref (masked keys: -inf).  The first live tile sets the reference to
+                    // its maximum; later tiles are exponentiated as they are, and a partial denominator
+                    // beyond kOver sends the tile through raise_ref (see k_attn)
+                    auto tile_max = [&]() __attribute__((always_inline)) -> float {
+                        float mx = sa[j][0];
+#pragma unroll
+                        for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sa[j][v]);
+                        return fmaxf(mx, other_half(mx));
+                    };
+                    auto raise_ref = [&](float tmax, bool always) __attribute__((always_inline)) {
+                        const bool raise = always || tmax > kRaise;
+                        const float new_ref = raise ? bf16_round(m_ref[j] + tmax) : m_ref[j];
+                        const float delta = new_ref - m_ref[j];
+                        m_ref[j] = new_ref;
+                        const float sc = first[j] ? 1.f : __builtin_amdgcn_exp2f(-delta);
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) {
+                            o_acc[j][v] *= sc;
+                            sa[j][v] -= delta;
+                        }
+                        l_run[j] *= sc;
+                        if (hf_a == 0) qf[j][2].w[0] = pack2(-new_ref, 1.f);
+                    };
+                    if (first[j]) {
+                        raise_ref(tile_max(), true);
+                        first[j] = false;
+                    }
+                    Frag pf[2];
+                    float lt;
+                    auto exponentiate = [&]() __attribute__((always_inline)) {
+                        lt = 0.f;
+#pragma unroll
+                        for (int c = 0; c < 2; ++c)
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                const float p0 = __builtin_amdgcn_exp2f(sa[j][8 * c + 2 * i]);
+                                const float p1 = __builtin_amdgcn_exp2f(sa[j][8 * c + 2 * i + 1]);
+                                pf[c].w[i] = pack2(p0, p1);
+                                lt = add_pair(pf[c].w[i], lt);
+                            }
+                    };
+                    exponentiate();
+                    if (__any(!(lt <= kOver))) {
+                        raise_ref(tile_max(), false);
+                        exponentiate();
+                    }
+                    l_run[j] += lt;
+#pragma unroll
+                    for (int c = 0; c < 2; ++c)
+                        o_acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[j][c].v, pf[c].v, o_acc[j], 0, 0, 0);
+                }
+            };
+            f32x16 bA, bB;
+            load_bias(0, bA);
+            for (int kt = 0; kt < nt; kt += 2) {
+                load_bias(kt + 1, bB);
+                tile(kt, bA);
+                load_bias(kt + 2 < nt ? kt + 2 : nt - 1, bA);        // (past the end: a harmless repeat)
+                tile(kt + 1, bB);
+            }
+
+            FU_STAMP(5);
+            // ---- normalise, gate, store: o_acc[j]: lane = query, register v = e = 8*(v/4) + 4*hf + v%4
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const float l_tot = l_run[j] + other_half(l_run[j]);
+                const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+                uint32_t pk[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    pk[i] = pack2(o_acc[j][2 * i] * inv * lo_f32(gpk[j][i]), o_acc[j][2 * i + 1] * inv * hi_f32(gpk[j][i]));
+                merge_halves(pk[0], pk[2]);      // lower half-wave: e 0..7, upper: e 8..15
+                merge_halves(pk[1], pk[3]);
+                merge_halves(pk[4], pk[6]);      // lower: e 16..23, upper: e 24..31
+                merge_halves(pk[5], pk[7]);
+                bf16_t* op = a.o + ((size_t)(rlv[j] * a.H + h) * a.Lp + 32 * wave) * 32;        // (uniform)
+                const uint32_t o_lane = (uint32_t)(col * 32 + 8 * hf) * 2;
+                if (row_ok[j] && l_tok < a.L) {
+                    stg16(op, o_lane, make_uint4(pk[0], pk[1], pk[2], pk[3]));
+                    stg16(op + 16, o_lane, make_uint4(pk[4], pk[5], pk[6], pk[7]));
+                }
+            }
+        }
+        FU_STAMP(6);
+    }
+}
+
+// ====================================================================================
 // host side
 // token tiles per wavefront: two halve the LDS traffic per MFMA, one keeps the register count at
 // two wavefronts per SIMD when the contraction is long
@@ -1502,6 +1963,8 @@ static ff_status launch_attn(int n_items, size_t smem, hipStream_t st, const Att
     return FF_OK;
 }
 
+static bool fused_proj_attn(const Problem& p, int chunk);
+
 static GemmArgs proj_args(const Problem& p, const MfmaWs& m, const Workspace& ws) {
     const int Lp = round_up(p.L, 64), Lq = round_up(p.L, 64);
     GemmArgs g{};
@@ -1533,12 +1996,13 @@ ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x
         seg(4, tri ? w.w_b : nullptr, nullptr, tri ? p.H : 0, 32, 4 * Hd, kLog2e);
         a.nseg = 5;
         const int rows = 4 * Hd + 32;
-        const bool chunked_tri = tri && ws.chunk < p.R;
+        const bool chunked_tri = tri && (ws.chunk < p.R || (p.has_bias && fused_proj_attn(p, ws.chunk)));
         if (p.mode == FF_MSA_ROW || chunked_tri) {
             // the pair-bias pass shares the launch: row mode projects z (own LayerNorm); chunked
             // triangle attention needs the bias of all rows before the first chunk
             PrepBiasArgs b{};
             b.prep = a;
+            b.tiled = fused_proj_attn(p, ws.chunk) ? 1 : 0;
             b.bias_blocks = (p.L * (Lp / 32) + 7) / 8;
             b.w_b = (const bf16_t*)w.w_b;
             if (chunked_tri) {
@@ -1564,9 +2028,60 @@ ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x
     if (p.has_bias && Lq > p.L) {
         const int n = (Lq - p.L) * Lp * p.H;
         Timed t(KK_PREP, st);
-        hipLaunchKernelGGL(k_zero_bias_pad, dim3((n + 255) / 256), dim3(256), 0, st, ws.bias, p.L, Lq, Lp, p.H);
+        hipLaunchKernelGGL(k_zero_bias_pad, dim3((n + 255) / 256), dim3(256), 0, st, ws.bias, p.L, Lq, Lp, p.H,
+                           fused_proj_attn(p, ws.chunk) ? 1 : 0);
     }
     return check_launch("prepare (mfma)");
+}
+
+// Shapes that k_proj_attn takes: head dimension 32, between 129 and 256 positions (fewer would leave
+// most of its eight wavefronts without tokens), 64, 128 or 256 channels, and a pair bias that
+// does not ride along with the projections (row mode, chunked triangle modes, or none)
+static bool fused_proj_attn(const Problem& p, int chunk) {
+    static const bool off = getenv("FF_NO_FUSED") != nullptr;
+    if (off) return false;
+    const bool tri = p.mode == FF_TRI_START || p.mode == FF_TRI_END;
+    if (p.d != 32 || p.L <= 128 || p.L > 256) return false;
+    if (p.c != 64 && p.c != 128 && p.c != 256) return false;
+    static const bool no_tri = getenv("FF_NO_FUSED_TRI") != nullptr;
+    if (no_tri && p.has_bias && tri && chunk >= p.R) return false;
+    return true;
+}
+
+template <int KC, bool HAS_BIAS>
+static ff_status launch_fused(const FusedArgs& a, hipStream_t st) {
+    static const hipError_t attr = allow_large_lds(&k_proj_attn<KC, HAS_BIAS>);
+    if (attr != hipSuccess) return fail(FF_EHIP, "k_proj_attn: dynamic LDS limit: %s", hipGetErrorString(attr));
+    // one block per compute unit (LDS); per XCD at most as many blocks as it has items
+    const int n_rp = (a.rows + 1) / 2;
+    int slots = compute_units() / 8;
+    const int items_xcd = ((n_rp + 7) / 8) * a.H;
+    if (slots > items_xcd) slots = items_xcd;
+    if (slots < 1) slots = 1;
+#ifdef FF_FU_DBG
+    static unsigned long long* dbg = nullptr;
+    static int calls = 0;
+    if (!dbg) { (void)hipMalloc(&dbg, 256 * 4 * 8 * 8); }
+    FusedArgs b = a; b.dbg = dbg;
+    (void)hipMemsetAsync(dbg, 0, 256 * 4 * 8 * 8, st);
+    hipLaunchKernelGGL((k_proj_attn<KC, HAS_BIAS>), dim3(8 * slots), dim3(kFuWaves * 64), fused_smem_bytes(KC), st, b);
+    if (++calls == 20) {
+        (void)hipStreamSynchronize(st);
+        static unsigned long long hb[256 * 4 * 8];
+        (void)hipMemcpy(hb, dbg, sizeof(hb), hipMemcpyDeviceToHost);
+        unsigned long long t0 = ~0ull;
+        for (int b2 = 0; b2 < 8 * slots; ++b2) if (hb[b2 * 32] && hb[b2 * 32] < t0) t0 = hb[b2 * 32];
+        for (int b2 = 0; b2 < 8 * slots; b2 += 37)
+            for (int i = 0; i < 2; ++i) {
+                fprintf(stderr, "blk %3d item %d:", b2, i);
+                for (int k = 0; k < 7; ++k) fprintf(stderr, " %7.2f", (double)(hb[(b2 * 4 + i) * 8 + k] - t0) * 0.01);
+                fprintf(stderr, "\n");
+            }
+    }
+    return FF_OK;
+#endif
+    hipLaunchKernelGGL((k_proj_attn<KC, HAS_BIAS>), dim3(8 * slots), dim3(kFuWaves * 64), fused_smem_bytes(KC), st, a);
+    return FF_OK;
 }
 
 ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, const float* mask, const void* res,
@@ -1576,7 +2091,24 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
     const bool tri = p.mode == FF_TRI_START || p.mode == FF_TRI_END;
     const int tiles_m = rows * (Lp / 32);
     const int blocks_m = gemm_blocks_m(true, tiles_m, p.c);
-    {
+    const bool fused = fused_proj_attn(p, ws.chunk);
+    if (fused) {
+        FusedArgs f{};
+        f.x = (const bf16_t*)x; f.sr = p.sr; f.sl = p.sl; f.r0 = r0; f.rows = rows; f.L = p.L; f.Lp = Lp; f.Lq = Lq;
+        f.eps = p.eps; f.wp = m.wp; f.aug = m.aug; f.H = p.H; f.Hd = p.Hd; f.bias = ws.bias; f.mask = mask; f.o = m.o;
+        Timed t(KK_PROJ_ATTN, st);
+        ff_status ls = FF_OK;
+#define FF_FUSED(KCV)                                              \
+    do {                                                           \
+        if (p.has_bias) ls = launch_fused<KCV, true>(f, st);       \
+        else ls = launch_fused<KCV, false>(f, st);                 \
+    } while (0)
+        if (p.c == 64) FF_FUSED(4);
+        else if (p.c == 128) FF_FUSED(8);
+        else FF_FUSED(16);
+#undef FF_FUSED
+        if (ls != FF_OK) return ls;
+    } else {
         GemmArgs g = proj_args(p, m, ws);
         g.src = (const bf16_t*)x; g.r0 = r0; g.rows = rows;
         // one chunk covering every row: the pair-bias tile rides along with the projections
@@ -1593,7 +2125,7 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
     a.q = m.q; a.k = m.k; a.g = m.g; a.vt = m.vt; a.o = m.o; a.bias = ws.bias; a.mask = mask;
     a.sr = p.sr; a.sl = p.sl; a.r0 = r0; a.rows = rows; a.L = p.L; a.Lp = Lp; a.Lq = Lq; a.H = p.H; a.Hd = p.Hd;
     a.inv_nq = 1.f / (float)(Lp / 64); a.inv_nqh = 1.f / (float)((Lp / 64) * p.H);
-    {
+    if (!fused) {
         Timed t(KK_ATTN, st);
         ff_status ls = FF_OK;
         const int rb = attn_rows_per_block(p, rows);
