@@ -17,6 +17,8 @@
 //               (the paper's fused scale + mask + bias softmax, Section 5.2, without ever
 //               materialising the score tensor of Section 3.2); O^T = V^T P^T; gate product
 //   k_gemm<OUT> output projection + b_o, scattered to the caller's layout
+//   k_proj_attn sequences of 129..256 positions at head dimension 32: k_gemm<PROJ> and k_attn in one
+//               kernel (a block = two batch rows x one head), q, k, v and gate never leave the chip
 //
 // Matrix-core operand layouts (wave64, 32x32x16, bf16 in, f32 out):
 //   A (32 x 16): lane l holds row l%32, columns 8*(l/32) .. +7
@@ -29,7 +31,7 @@
 // fetched, so nothing moves between the two contractions.
 //
 // Workspace layout of this family (Lp = Lq = L rounded up to 64, token p = rl*Lp + l):
-//   bias [H][Lq][Lp] float32 (times log2 e)
+//   bias [H][Lq][Lp] float32 (times log2 e); for k_proj_attn the same elements in 32 x 32 tiles (bias_index)
 //   q, k, g, o [rows][H][Lp][D] bf16;  vt [rows][H][Lp/32][D][32] bf16
 //   prepared weights [(4*Hd + 32)][c] (+ [32][c_z] in row mode) bf16, their sums and offsets
 // Pad tokens (l in [L, Lp)) hold finite values everywhere; they are masked as keys.
@@ -1419,8 +1421,16 @@ __global__ __launch_bounds__(RB * 64, (RB == 4 && !HAS_BIAS && D < 32) ? 3 : 2) 
 //
 // LDS: the head's four folded 32 x K weight tiles (row pitch 2K + 16 bytes), their extra pieces,
 // k [2][256][80 bytes] (four pieces of the contraction and the piece with 1 and the mask term),
-// v^T [2][32][528 bytes], 1/std of the tokens, and one flag per (row, key tile) that tells
-// whether the tile holds a valid key.
+// v^T [2][32][528 bytes], 1/std of the tokens, one flag per (row, key tile) that tells whether
+// the tile holds a valid key, and 2 KiB per wavefront through which the raw tokens, fetched as
+// whole 128-byte lines, are turned into matrix-core operands.  With 256 channels that is 159 KiB
+// of the compute unit's 160: one block of eight wavefronts per compute unit.
+//
+// Measured on the training crop of the row-wise attention (128 x 256 tokens, 8 heads): 50 us
+// against 34 + 31 us for k_gemm<PROJ> and k_attn.  The projections of a block are bound by LDS
+// traffic (every matrix instruction takes a fresh weight operand from LDS), the attention by the
+// vector unit; of the two wavefronts of a SIMD the older one is served first and finishes each
+// phase about a quarter earlier, and the block waits for the younger one at both barriers.
 struct FusedArgs {
     const bf16_t* x;       // raw input, token (r, l) at (r*sr + l*sl)*K
     int64_t sr, sl;        // token strides of x and of the mask
@@ -1429,18 +1439,10 @@ struct FusedArgs {
     const bf16_t* wp;      // prepared weights [(4*Hd + 32)][K]
     const uint4* aug;      // their extra pieces
     int H, Hd;
-    const float* bias;     // [H][Lq][Lp] or NULL
+    const float* bias;     // tiled (bias_index) or NULL
     const float* mask;     // caller's mask or NULL
     bf16_t* o;             // gated context [rows][H][Lp][32]
-#ifdef FF_FU_DBG
-    unsigned long long* dbg;
-#endif
 };
-#ifdef FF_FU_DBG
-#define FU_STAMP(k) do { if (tid == DBGT) a.dbg[(blockIdx.x * 4 + dbg_item) * 8 + (k)] = wall_clock64(); } while (0)
-#else
-#define FU_STAMP(k) do { } while (0)
-#endif
 
 constexpr int kFuKPitch = 80;       // bytes of a key row in LDS
 constexpr int kFuVPitch = 528;      // bytes of a v^T row in LDS: 256 keys and a pad
@@ -1476,32 +1478,19 @@ __global__ __launch_bounds__(kFuWaves * 64) void k_proj_attn(FusedArgs a) {
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, slots = gridDim.x >> 3;
     const int n_local = xcd < n_rp ? ((n_rp - xcd + 7) >> 3) * a.H : 0;
     int h_loaded = -1;
-    // permuted key of S^T row m = col (see k_attn): the lane's registers 8c .. 8c+7 then hold the
-    // keys 16c + 8hf .. + 7 of the tile
-    const int kperm = 16 * (col >> 4) + 8 * ((col >> 2) & 1) + 4 * ((col >> 3) & 1) + (col & 3);
     const int l_tok = 32 * wave + col;
     const bool tok_in = active && l_tok < a.L;
     const bool has_mask = a.mask != nullptr;
 
-#ifdef FF_FU_DBG
-    int dbg_item = -1;
-    constexpr int DBGT = 64 * 3;
-#endif
     for (int it = slot; it < n_local; it += slots) {
         const int jj = it / a.H, h = it - jj * a.H;
         const int rp = xcd + 8 * jj;
-#ifdef FF_FU_DBG
-        ++dbg_item;
-#endif
-        FU_STAMP(0);
-        if (it != slot) __syncthreads();            // every wavefront has left the item before: k and v^T may be overwritten
-        FU_STAMP(1);
-
         // ---- raw tokens (row 0 issued first; row 1 follows line by line as the registers fall free),
         // the mask entries.  Eight lanes fetch one 128-byte line of a token (a load with lane =
         // token, the operand layout, touches 64 lines for 1 KiB and the cache looks up one line per
-        // cycle); raw[m][hh][i] holds line m of the tokens 16hh + 8i + lane/8 of the wavefront's
-        // tile, piece lane%8.
+        // cycle: 5 us per item instead of 1.2); raw[m][hh][i] holds line m of the tokens 16hh + 8i +
+        // lane/8 of the wavefront's tile, piece lane%8.  Issued before the barrier: the loads are on
+        // their way while the block waits for its last wavefront.
         constexpr int NG = KC / 4;              // 128-byte lines per token
         uint4 raw[NG][2][2];
         float mval[2];
@@ -1530,6 +1519,8 @@ __global__ __launch_bounds__(kFuWaves * 64) void k_proj_attn(FusedArgs a) {
 #pragma unroll
         for (int m = 0; m < NG; ++m) fetch_line(0, m);
 
+        if (it != slot) __syncthreads();            // every wavefront has left the item before: k and v^T may be overwritten
+
         // ---- the head's weight tiles
         if (h != h_loaded) {
             // (128 rows of 2 KC pieces, KC / 2 pieces per thread, up to four loads in flight)
@@ -1555,17 +1546,9 @@ __global__ __launch_bounds__(kFuWaves * 64) void k_proj_attn(FusedArgs a) {
             __syncthreads();
         }
 
-        FU_STAMP(2);
         // ---- projections: q and gate stay in registers, k and v^T go to LDS
-        Frag qf[2][3];
+        Frag qf[2][3];          // (set and used by wavefronts with tokens only)
         uint32_t gpk[2][8];
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-#pragma unroll
-            for (int s = 0; s < 3; ++s) qf[j][s].u = make_uint4(0, 0, 0, 0);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) gpk[j][i] = 0u;
-        }
         if (active) {
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
@@ -1661,8 +1644,8 @@ __global__ __launch_bounds__(kFuWaves * 64) void k_proj_attn(FusedArgs a) {
                     }
                     *reinterpret_cast<uint4*>(krow + (2 * s + hf) * 16) = make_uint4(kw[0], kw[1], kw[2], kw[3]);
                 }
+                qf[j][2].u = make_uint4(hf == 0 ? 0x3f800000u : 0u, 0u, 0u, 0u);            // (-m_ref = 0, 1.0)
                 if (hf == 0) {
-                    qf[j][2].w[0] = 0x3f800000u;            // (-m_ref = 0, 1.0)
                     *reinterpret_cast<uint4*>(krow + 64) = make_uint4(key_valid ? 0x00003f80u : 0xff803f80u, 0u, 0u, 0u);   // (1.0, mask term)
                 }
                 // gate: the layout of O^T
@@ -1685,9 +1668,7 @@ __global__ __launch_bounds__(kFuWaves * 64) void k_proj_attn(FusedArgs a) {
                 }
             }
         }
-        FU_STAMP(3);
         __syncthreads();
-        FU_STAMP(4);
 
         // ---- attention of the wavefront's 32 queries of both rows over the nt key tiles
         if (active) {
@@ -1696,6 +1677,8 @@ __global__ __launch_bounds__(kFuWaves * 64) void k_proj_attn(FusedArgs a) {
             int lane_a = lane;
             asm volatile("" : "+v"(lane_a));
             const int col_a = lane_a & 31, hf_a = lane_a >> 5;
+            // permuted key of S^T row m = col (see k_attn): the lane's registers 8c .. 8c+7 then hold
+            // the keys 16c + 8hf .. + 7 of the tile
             const int kperm_a = 16 * (col_a >> 4) + 8 * ((col_a >> 2) & 1) + 4 * ((col_a >> 3) & 1) + (col_a & 3);
             int lv[2];
 #pragma unroll
@@ -1820,7 +1803,6 @@ __global__ __launch_bounds__(kFuWaves * 64) void k_proj_attn(FusedArgs a) {
                 tile(kt + 1, bB);
             }
 
-            FU_STAMP(5);
             // ---- normalise, gate, store: o_acc[j]: lane = query, register v = e = 8*(v/4) + 4*hf + v%4
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
@@ -1842,7 +1824,6 @@ __global__ __launch_bounds__(kFuWaves * 64) void k_proj_attn(FusedArgs a) {
                 }
             }
         }
-        FU_STAMP(6);
     }
 }
 
@@ -1963,7 +1944,7 @@ static ff_status launch_attn(int n_items, size_t smem, hipStream_t st, const Att
     return FF_OK;
 }
 
-static bool fused_proj_attn(const Problem& p, int chunk);
+static bool fused_proj_attn(const Problem& p);
 
 static GemmArgs proj_args(const Problem& p, const MfmaWs& m, const Workspace& ws) {
     const int Lp = round_up(p.L, 64), Lq = round_up(p.L, 64);
@@ -1996,13 +1977,13 @@ ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x
         seg(4, tri ? w.w_b : nullptr, nullptr, tri ? p.H : 0, 32, 4 * Hd, kLog2e);
         a.nseg = 5;
         const int rows = 4 * Hd + 32;
-        const bool chunked_tri = tri && (ws.chunk < p.R || (p.has_bias && fused_proj_attn(p, ws.chunk)));
+        const bool chunked_tri = tri && (ws.chunk < p.R || (p.has_bias && fused_proj_attn(p)));
         if (p.mode == FF_MSA_ROW || chunked_tri) {
             // the pair-bias pass shares the launch: row mode projects z (own LayerNorm); chunked
             // triangle attention needs the bias of all rows before the first chunk
             PrepBiasArgs b{};
             b.prep = a;
-            b.tiled = fused_proj_attn(p, ws.chunk) ? 1 : 0;
+            b.tiled = fused_proj_attn(p) ? 1 : 0;
             b.bias_blocks = (p.L * (Lp / 32) + 7) / 8;
             b.w_b = (const bf16_t*)w.w_b;
             if (chunked_tri) {
@@ -2029,23 +2010,18 @@ ff_status mfma_prepare(const Problem& p, const ff_attn_weights& w, const void* x
         const int n = (Lq - p.L) * Lp * p.H;
         Timed t(KK_PREP, st);
         hipLaunchKernelGGL(k_zero_bias_pad, dim3((n + 255) / 256), dim3(256), 0, st, ws.bias, p.L, Lq, Lp, p.H,
-                           fused_proj_attn(p, ws.chunk) ? 1 : 0);
+                           fused_proj_attn(p) ? 1 : 0);
     }
     return check_launch("prepare (mfma)");
 }
 
 // Shapes that k_proj_attn takes: head dimension 32, between 129 and 256 positions (fewer would leave
-// most of its eight wavefronts without tokens), 64, 128 or 256 channels, and a pair bias that
-// does not ride along with the projections (row mode, chunked triangle modes, or none)
-static bool fused_proj_attn(const Problem& p, int chunk) {
-    static const bool off = getenv("FF_NO_FUSED") != nullptr;
-    if (off) return false;
-    const bool tri = p.mode == FF_TRI_START || p.mode == FF_TRI_END;
+// most of its eight wavefronts without tokens), 64, 128 or 256 channels.  The pair bias then comes
+// from k_prep_bias in every mode (the triangle modes too: it cannot ride along with projections
+// that never leave the attention kernel), in the tiled layout of bias_index.
+static bool fused_proj_attn(const Problem& p) {
     if (p.d != 32 || p.L <= 128 || p.L > 256) return false;
-    if (p.c != 64 && p.c != 128 && p.c != 256) return false;
-    static const bool no_tri = getenv("FF_NO_FUSED_TRI") != nullptr;
-    if (no_tri && p.has_bias && tri && chunk >= p.R) return false;
-    return true;
+    return p.c == 64 || p.c == 128 || p.c == 256;
 }
 
 template <int KC, bool HAS_BIAS>
@@ -2058,28 +2034,6 @@ static ff_status launch_fused(const FusedArgs& a, hipStream_t st) {
     const int items_xcd = ((n_rp + 7) / 8) * a.H;
     if (slots > items_xcd) slots = items_xcd;
     if (slots < 1) slots = 1;
-#ifdef FF_FU_DBG
-    static unsigned long long* dbg = nullptr;
-    static int calls = 0;
-    if (!dbg) { (void)hipMalloc(&dbg, 256 * 4 * 8 * 8); }
-    FusedArgs b = a; b.dbg = dbg;
-    (void)hipMemsetAsync(dbg, 0, 256 * 4 * 8 * 8, st);
-    hipLaunchKernelGGL((k_proj_attn<KC, HAS_BIAS>), dim3(8 * slots), dim3(kFuWaves * 64), fused_smem_bytes(KC), st, b);
-    if (++calls == 20) {
-        (void)hipStreamSynchronize(st);
-        static unsigned long long hb[256 * 4 * 8];
-        (void)hipMemcpy(hb, dbg, sizeof(hb), hipMemcpyDeviceToHost);
-        unsigned long long t0 = ~0ull;
-        for (int b2 = 0; b2 < 8 * slots; ++b2) if (hb[b2 * 32] && hb[b2 * 32] < t0) t0 = hb[b2 * 32];
-        for (int b2 = 0; b2 < 8 * slots; b2 += 37)
-            for (int i = 0; i < 2; ++i) {
-                fprintf(stderr, "blk %3d item %d:", b2, i);
-                for (int k = 0; k < 7; ++k) fprintf(stderr, " %7.2f", (double)(hb[(b2 * 4 + i) * 8 + k] - t0) * 0.01);
-                fprintf(stderr, "\n");
-            }
-    }
-    return FF_OK;
-#endif
     hipLaunchKernelGGL((k_proj_attn<KC, HAS_BIAS>), dim3(8 * slots), dim3(kFuWaves * 64), fused_smem_bytes(KC), st, a);
     return FF_OK;
 }
@@ -2091,7 +2045,7 @@ ff_status mfma_chunk(const Problem& p, const ff_attn_weights& w, const void* x, 
     const bool tri = p.mode == FF_TRI_START || p.mode == FF_TRI_END;
     const int tiles_m = rows * (Lp / 32);
     const int blocks_m = gemm_blocks_m(true, tiles_m, p.c);
-    const bool fused = fused_proj_attn(p, ws.chunk);
+    const bool fused = fused_proj_attn(p);
     if (fused) {
         FusedArgs f{};
         f.x = (const bf16_t*)x; f.sr = p.sr; f.sl = p.sl; f.r0 = r0; f.rows = rows; f.L = p.L; f.Lp = Lp; f.Lq = Lq;
