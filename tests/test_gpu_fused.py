@@ -78,3 +78,60 @@ def test_fused_chunked_is_bit_identical_to_unchunked():
     a = run_case(case)
     b = run_case(case, chunk_rows=3)
     assert torch.equal(a, b)
+
+
+def test_fused_fully_masked_rows_give_output_bias():
+    """A batch row without a valid key: every key tile is skipped, the context is zero and the module
+    returns the output projection's bias for that row."""
+    case = I.make_case(small_spec(COL, 200, 9, 64, 2, 32, dtype="bf16", mask="tail:3"))
+    case.mask[:, 4] = 0.0
+    got = to_np(run_case(case))
+    bo = I.widen(case.weights["b_o"]).astype(np.float64)
+    assert max_abs(got[:, 4], np.broadcast_to(bo, got[:, 4].shape)) == 0.0
+    check(got, oracle_case(case), "fully masked batch row")
+
+
+def test_fused_masked_key_content_is_irrelevant():
+    case = I.make_case(small_spec(ROW, 4, 180, 128, 4, 32, c_z=16, dtype="bf16", mask="tail:50"))
+    desc, w, x, z, mask = P.to_device(case, DEV)
+    a = P.ff_gated_attention(desc, w, x, z, mask)
+    x2 = x.clone()
+    x2[:, 130:, :] = torch.randn_like(x2[:, 130:, :]) * 3
+    b = P.ff_gated_attention(desc, w, x2, z, mask)
+    torch.cuda.synchronize()
+    assert torch.equal(a[:, :130], b[:, :130])
+
+
+@pytest.mark.parametrize("mode,n_a,n_b,c,H,d,c_z,chunk", [(ROW, 9, 200, 128, 4, 32, 32, 0), (TS, 140, 140, 64, 2, 32, 0, 48)])
+def test_fused_calls_can_be_captured_in_a_hip_graph(mode, n_a, n_b, c, H, d, c_z, chunk):
+    """The kernel keeps nothing in the workspace from call to call (the pad rows and columns of the
+    tiled bias are rewritten by every call): replays over a workspace filled with random bytes
+    reproduce the eager bits."""
+    case = I.make_case(small_spec(mode, n_a, n_b, c, H, d, c_z=c_z, dtype="bf16", mask="tail:5"))
+    desc, w, x, z, mask = P.to_device(case, DEV)
+    ws = torch.empty(P.ff_attention_workspace_bytes(desc, chunk), dtype=torch.uint8, device=DEV)
+
+    def call(out):
+        if chunk:
+            P.ff_attention_chunked(desc, w, x, z, mask, chunk_rows=chunk, out=out, ws=ws)
+        else:
+            P.ff_gated_attention(desc, w, x, z, mask, out=out, ws=ws)
+
+    eager = torch.empty_like(x)
+    call(eager)                                    # (also the one-time kernel attribute set-up)
+    torch.cuda.synchronize()
+    out = torch.zeros_like(x)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            call(out)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        out.fill_(float("nan"))
+        ws.random_(0, 255)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), rep
