@@ -222,15 +222,23 @@ template <typename Store>
 __device__ __forceinline__ uint4 fold_row(const bf16_t* wrow, const bf16_t* gamma, const bf16_t* beta, int K, float scale,
                                           bool real, float extra, int lane, Store&& store) {
     float sum = 0.f, cst = 0.f;
-    // K <= 256: at most four elements per lane, all loads issued before the first use
+    // K <= 256: at most four elements per lane.  The loads carry no condition (an element beyond K
+    // reads element K - 1 and is dropped below, a pad row reads the row the caller passes for it): a
+    // conditional load is a branch and a wait of its own, twelve memory round trips one after the other
+    // instead of one.
     bf16_t wv[4], gv[4], bv[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int k = lane + 64 * i;
-        const bool in = real && k < K;
-        wv[i] = in ? wrow[k] : (bf16_t)0;
-        gv[i] = in ? gamma[k] : (bf16_t)0;
-        bv[i] = in ? beta[k] : (bf16_t)0;
+        const int kc = k < K ? k : K - 1;
+        wv[i] = wrow[kc];
+        gv[i] = gamma[kc];
+        bv[i] = beta[kc];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const bool in = real && lane + 64 * i < K;
+        if (!in) wv[i] = gv[i] = bv[i] = (bf16_t)0;
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -252,7 +260,8 @@ __device__ __forceinline__ uint4 fold_row(const bf16_t* wrow, const bf16_t* gamm
 }
 
 // row n of the concatenated segments, by one wavefront
-__device__ __forceinline__ void prep_row(const PrepArgs& a, int n, int lane) {
+__device__ __forceinline__ void prep_row(const PrepArgs& a, int n_in, int lane) {
+    const int n = __builtin_amdgcn_readfirstlane(n_in);      // (a wavefront's row: the segment is then read with scalar loads)
     int base = 0, sg = -1, local = 0;
     for (int i = 0; i < a.nseg; ++i) {
         if (sg < 0 && n < base + a.seg[i].rows_pad) {
@@ -268,9 +277,13 @@ __device__ __forceinline__ void prep_row(const PrepArgs& a, int n, int lane) {
         if (i == sg) sgm = a.seg[i];
     const bool real = local < sgm.rows;
     const int K = sgm.K;
-    const float extra = (real && sgm.extra) ? bf16_to_f32(sgm.extra[local]) : 0.f;
+    // (no condition on the load, see fold_row: without an offset vector the row reads gamma[0] and drops it)
+    const bool has_extra = real && sgm.extra != nullptr;
+    const float extra_raw = bf16_to_f32(*(has_extra ? sgm.extra + local : sgm.gamma));
+    const float extra = has_extra ? extra_raw : 0.f;
     bf16_t* wp = sgm.wp + (size_t)local * K;
-    const uint4 piece = fold_row(sgm.w + (size_t)local * K, sgm.gamma, sgm.beta, K, sgm.scale, real, extra, lane,
+    // (a pad row has no weights, its segment possibly no matrix at all: it reads gamma, K valid elements, instead)
+    const uint4 piece = fold_row(real ? sgm.w + (size_t)local * K : sgm.gamma, sgm.gamma, sgm.beta, K, sgm.scale, real, extra, lane,
                                  [&](int k, bf16_t v) { wp[k] = v; });
     if (lane == 0) sgm.aug[local] = piece;
 }
@@ -329,13 +342,27 @@ __global__ __launch_bounds__(512) void k_prep_bias(PrepBiasArgs a) {
     const int pr = tg * 32 + col;
     const int qi = pr / a.Lp, kj = pr - qi * a.Lp;
     const bool valid = kj < a.L;
-    Frag xa[KC];
-    const bf16_t* zp = a.z + ((int64_t)qi * a.sr + (int64_t)kj * a.sl) * K;
+    // Eight lanes fetch one 128-byte line of a pair (64 channels); the lines pass through 4 KiB of LDS
+    // per wavefront and come back in the operand layout (lane = pair, pieces 2s' + hf of line m =
+    // contraction steps 4m + s').  A load with lane = pair touches 64 cache lines for 1 KiB, and the
+    // cache looks up one line per cycle: the fetch alone took 2.5 us of the block's 6.
+    constexpr int NG = (KC + 3) / 4;
+    __shared__ __attribute__((aligned(16))) unsigned char s_stage[8][4096];
+    unsigned char* s_st = s_stage[wave];
+    uint4 raw[NG][4];
+    {
+        const int q0 = (tg * 32) / a.Lp, k0 = tg * 32 - q0 * a.Lp;       // (uniform: a tile lies inside one query row)
+        const int pieces = K >> 3;
 #pragma unroll
-    for (int s = 0; s < KC; ++s) {
-        xa[s].u = make_uint4(0, 0, 0, 0);
-        const int f = 16 * s + 8 * hf;
-        if (valid && f < K) xa[s].u = ldg16(zp + f);
+        for (int i = 0; i < 4; ++i) {
+            const int kk = k0 + 8 * i + (lane >> 3);
+            const bf16_t* zq = a.z + ((int64_t)q0 * a.sr + (int64_t)(kk < a.L ? kk : 0) * a.sl) * K + (lane & 7) * 8;
+#pragma unroll
+            for (int m = 0; m < NG; ++m) {
+                raw[m][i] = make_uint4(0, 0, 0, 0);
+                if (kk < a.L && 8 * m + (lane & 7) < pieces) raw[m][i] = ldg16(zq + 64 * m);
+            }
+        }
     }
 
     // ---- the folded weight tile: zeros, then one wavefront per head row (fold_row)
@@ -347,6 +374,23 @@ __global__ __launch_bounds__(512) void k_prep_bias(PrepBiasArgs a) {
         const uint4 piece = fold_row(a.w_b + (size_t)row * K, a.gamma, a.beta, K, kLog2e, true, 0.f, lane,
                                      [&](int k, bf16_t v) { dst[k] = v; });
         if (lane == 0) s_aug[row] = piece;
+    }
+
+    // ---- the pairs as operands (the staging area is the wavefront's own, its LDS operations complete in order)
+    Frag xa[KC];
+#pragma unroll
+    for (int m = 0; m < NG; ++m) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int tl = 8 * i + (lane >> 3);
+            *reinterpret_cast<uint4*>(s_st + tl * 128 + (((lane & 7) ^ (tl & 7)) * 16)) = raw[m][i];
+        }
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int sp = 0; sp < 4; ++sp)
+            if (4 * m + sp < KC)
+                xa[4 * m + sp].u = *reinterpret_cast<const uint4*>(s_st + col * 128 + (((2 * sp + hf) ^ (col & 7)) * 16));
+        __builtin_amdgcn_wave_barrier();
     }
 
     // ---- LayerNorm statistics of the wavefront's pairs
