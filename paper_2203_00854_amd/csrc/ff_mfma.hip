@@ -1471,10 +1471,12 @@ __global__ __launch_bounds__(RB * 64, (RB == 4 && !HAS_BIAS && D < 32) ? 3 : 2) 
 // of the compute unit's 160: one block of eight wavefronts per compute unit.
 //
 // Measured on the training crop of the row-wise attention (128 x 256 tokens, 8 heads): 50 us
-// against 34 + 31 us for k_gemm<PROJ> and k_attn.  The projections of a block are bound by LDS
-// traffic (every matrix instruction takes a fresh weight operand from LDS), the attention by the
-// vector unit; of the two wavefronts of a SIMD the older one is served first and finishes each
-// phase about a quarter earlier, and the block waits for the younger one at both barriers.
+// against 34 + 31 us for k_gemm<PROJ> and k_attn.  No unit is saturated (LDS busy 22 %, matrix
+// pipe 25 %, vector unit 39 % of the kernel): in the projections every matrix instruction waits
+// for a fresh weight operand from LDS, the attention is paced by the exponentials, and two
+// wavefronts per SIMD with one dependent chain each leave a third of the issue slots empty.  Of
+// the two wavefronts of a SIMD the older one is served first and finishes each phase about a
+// quarter earlier; the block waits for the younger one at both barriers.
 struct FusedArgs {
     const bf16_t* x;       // raw input, token (r, l) at (r*sr + l*sl)*K
     int64_t sr, sl;        // token strides of x and of the mask
